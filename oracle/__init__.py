@@ -1,0 +1,223 @@
+"""CPU oracle for the Jigsaw linear-layer forward pass.  TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper around ``jigsaw_oracle.c`` (plain C, IEEE double) plus the
+layout definitions (which slice of X / W / b / Y a rank owns) written out as
+numpy slicing.  Nothing here is shared with, or imported by, the HIP library or
+its Python binding; only ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py`` may import this package.
+
+Partitioning (all matrices row-major; X is M x K, W is N x K, Y is M x N):
+
+* 2-way (Sec. 4.1): X_r = X[:, r-th half of K], W_r = W[:, r-th half of K]
+  (rank r holds all N rows of its W column-half and splits them internally into
+  W_{r,0}, W_{r,1}); Y_r = Y[:, r-th half of N].
+* 4-way (Sec. 4.2): X_r, W_r, Y_r are the 2 x 2 blocks numbered row-major
+  (r = 2*row_half + col_half), as in Eq. (3).
+* Bias: b_r is the slice of b matching Y_r's columns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "jigsaw_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (host only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared",
+                               "-pthread", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        f32p = ctypes.POINTER(ctypes.c_float)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        i64 = ctypes.c_int64
+        lib.oracle_linear.argtypes = [f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int]
+        lib.oracle_linear_rows.argtypes = [f32p, f32p, f32p, i64, i64, i64, i64, i64, f64p, ctypes.c_int]
+        lib.oracle_magnitude.argtypes = [f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int]
+        lib.oracle_entries.argtypes = [f32p, f32p, f32p, i64, i64p, i64p, i64, f64p, f64p]
+        lib.oracle_jigsaw.argtypes = [ctypes.c_int, f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int]
+        for fn in (lib.oracle_linear, lib.oracle_linear_rows, lib.oracle_magnitude,
+                   lib.oracle_entries, lib.oracle_jigsaw):
+            fn.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _opt_f32(a):
+    if a is None:
+        return None, None
+    return _f32(a)
+
+
+def _f64_out(shape):
+    a = np.empty(shape, dtype=np.float64)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"oracle: {what} failed with code {rc}")
+
+
+def host_threads() -> int:
+    try:
+        return max(1, len(os.sched_getaffinity(0)))
+    except AttributeError:  # pragma: no cover
+        return max(1, os.cpu_count() or 1)
+
+
+def linear(X, W, b=None, nthreads: int | None = None) -> np.ndarray:
+    """Y64 = X W^T + b by the definition, in double."""
+    X, xp = _f32(X)
+    W, wp = _f32(W)
+    b, bp = _opt_f32(b)
+    M, K = X.shape
+    N, K2 = W.shape
+    assert K == K2 and (b is None or b.shape == (N,))
+    Y, yp = _f64_out((M, N))
+    _check(_load().oracle_linear(xp, wp, bp, M, K, N, yp, nthreads or host_threads()), "linear")
+    return Y
+
+
+def linear_rows(X, W, b, row_begin: int, row_end: int, nthreads: int | None = None) -> np.ndarray:
+    """Rows [row_begin, row_end) of Y64 (returned as a (row_end-row_begin) x N array)."""
+    X, xp = _f32(X)
+    W, wp = _f32(W)
+    b, bp = _opt_f32(b)
+    M, K = X.shape
+    N = W.shape[0]
+    Y, yp = _f64_out((row_end - row_begin, N))
+    _check(_load().oracle_linear_rows(xp, wp, bp, M, K, N, row_begin, row_end, yp,
+                                      nthreads or host_threads()), "linear_rows")
+    return Y
+
+
+def magnitude(X, W, b=None, nthreads: int | None = None) -> np.ndarray:
+    """S = |b| + |X| |W|^T in double: the scale of the floating-point tolerance."""
+    X, xp = _f32(X)
+    W, wp = _f32(W)
+    b, bp = _opt_f32(b)
+    M, K = X.shape
+    N = W.shape[0]
+    S, sp = _f64_out((M, N))
+    _check(_load().oracle_magnitude(xp, wp, bp, M, K, N, sp, nthreads or host_threads()), "magnitude")
+    return S
+
+
+def entries(Xrows, Wrows, ix, jw, bias_per_entry=None):
+    """(value, magnitude) of entries e: <Xrows[ix[e]], Wrows[jw[e]]> + bias_per_entry[e]."""
+    Xr, xp = _f32(Xrows)
+    Wr, wp = _f32(Wrows)
+    bj, bp = _opt_f32(bias_per_entry)
+    K = Xr.shape[1]
+    assert Wr.shape[1] == K
+    ix = np.ascontiguousarray(ix, dtype=np.int64)
+    jw = np.ascontiguousarray(jw, dtype=np.int64)
+    n = ix.shape[0]
+    assert jw.shape[0] == n
+    assert n == 0 or (ix.min() >= 0 and ix.max() < Xr.shape[0] and jw.min() >= 0 and jw.max() < Wr.shape[0])
+    out, op = _f64_out((n,))
+    mag, mp = _f64_out((n,))
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    _check(_load().oracle_entries(xp, wp, bp, K, ix.ctypes.data_as(i64p), jw.ctypes.data_as(i64p),
+                                  n, op, mp), "entries")
+    return out, mag
+
+
+def jigsaw(ways: int, X, W, b=None, nthreads: int | None = None) -> np.ndarray:
+    """Y64 obtained by the method's own steps (shard, block products, exchange, add, gather)."""
+    X, xp = _f32(X)
+    W, wp = _f32(W)
+    b, bp = _opt_f32(b)
+    M, K = X.shape
+    N = W.shape[0]
+    Y, yp = _f64_out((M, N))
+    _check(_load().oracle_jigsaw(ways, xp, wp, bp, M, K, N, yp, nthreads or host_threads()), "jigsaw")
+    return Y
+
+
+# ----------------------------------------------------------------------------
+# layout definitions (pure indexing; bit-exact)
+# ----------------------------------------------------------------------------
+def _check_ways(ways, M, K, N):
+    if ways not in (1, 2, 4):
+        raise ValueError("ways must be 1, 2 or 4")
+    if ways >= 2 and (K % 2 or N % 2):
+        raise ValueError("K and N must be even")
+    if ways == 4 and M % 2:
+        raise ValueError("M must be even")
+
+
+def shard_x(X: np.ndarray, ways: int):
+    M, K = X.shape
+    _check_ways(ways, M, K, 0)
+    if ways == 1:
+        return [np.ascontiguousarray(X)]
+    if ways == 2:
+        return [np.ascontiguousarray(X[:, r * (K // 2):(r + 1) * (K // 2)]) for r in range(2)]
+    return [np.ascontiguousarray(X[(r // 2) * (M // 2):(r // 2 + 1) * (M // 2),
+                                   (r % 2) * (K // 2):(r % 2 + 1) * (K // 2)]) for r in range(4)]
+
+
+def shard_w(W: np.ndarray, ways: int):
+    N, K = W.shape
+    _check_ways(ways, 0, K, N)
+    if ways == 1:
+        return [np.ascontiguousarray(W)]
+    if ways == 2:
+        return [np.ascontiguousarray(W[:, r * (K // 2):(r + 1) * (K // 2)]) for r in range(2)]
+    return [np.ascontiguousarray(W[(r // 2) * (N // 2):(r // 2 + 1) * (N // 2),
+                                   (r % 2) * (K // 2):(r % 2 + 1) * (K // 2)]) for r in range(4)]
+
+
+def shard_b(b: np.ndarray, ways: int):
+    (N,) = b.shape
+    _check_ways(ways, 0, 0, N)
+    if ways == 1:
+        return [np.ascontiguousarray(b)]
+    if ways == 2:
+        return [np.ascontiguousarray(b[r * (N // 2):(r + 1) * (N // 2)]) for r in range(2)]
+    return [np.ascontiguousarray(b[(r % 2) * (N // 2):(r % 2 + 1) * (N // 2)]) for r in range(4)]
+
+
+def shard_y(Y: np.ndarray, ways: int):
+    """Y is partitioned like X: column halves (2-way) or 2 x 2 blocks (4-way)."""
+    M, N = Y.shape
+    _check_ways(ways, M, 0, N)
+    if ways == 1:
+        return [np.ascontiguousarray(Y)]
+    if ways == 2:
+        return [np.ascontiguousarray(Y[:, r * (N // 2):(r + 1) * (N // 2)]) for r in range(2)]
+    return [np.ascontiguousarray(Y[(r // 2) * (M // 2):(r // 2 + 1) * (M // 2),
+                                   (r % 2) * (N // 2):(r % 2 + 1) * (N // 2)]) for r in range(4)]
+
+
+def gather_y(shards, ways: int) -> np.ndarray:
+    if ways == 1:
+        return np.ascontiguousarray(shards[0])
+    if ways == 2:
+        return np.concatenate(shards, axis=1)
+    return np.concatenate([np.concatenate(shards[0:2], axis=1),
+                           np.concatenate(shards[2:4], axis=1)], axis=0)

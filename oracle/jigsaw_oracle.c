@@ -1,0 +1,321 @@
+/*
+ * CPU oracle for the forward pass of a Jigsaw-partitioned linear layer.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, obviously-correct C in IEEE double.
+ * It shares no code with the HIP library and must never be called from the
+ * product path; only the tests, the smoke check and the benchmark's
+ * "cpu_baseline" leg use it.
+ *
+ * What it computes
+ * ----------------
+ *  oracle_linear      : the definition the method must reach (Sec. 4, first
+ *                       paragraph: a linear layer is the product X W^T):
+ *                         Y[i][j] = b[j] + sum_{k=0}^{K-1} X[i][k] * W[j][k]
+ *                       every product and sum in double, k ascending.
+ *  oracle_magnitude   : S[i][j] = |b[j]| + sum_k |X[i][k]| * |W[j][k]|, the
+ *                       scale the floating-point tolerance is relative to.
+ *  oracle_entries     : the same definition for a list of (row of X, row of W)
+ *                       pairs, for sizes where the full product is too slow.
+ *  oracle_jigsaw      : the same product obtained the way the method obtains
+ *                       it: shard X and W, form the block products each rank
+ *                       owns, hand partial products (and, 4-way, weight blocks)
+ *                       to the peer by index, add, gather.
+ *                       2-way: Sec. 4.1, Eqs. (1)-(2).  4-way: Sec. 4.2,
+ *                       Eqs. (3)-(4).  ways = 1 is the unpartitioned layer.
+ *
+ * Pins (see tests/test_oracle_pins.py): closed forms for identity /
+ * permutation / all-ones / single-nonzero operands, exact integer brute force
+ * on tiny shapes, a library matmul in double, the block identities of
+ * Eqs. (2) and (4), linearity, and zero-padding invariance.
+ *
+ * Layout: every matrix is dense row-major; X is M x K, W is N x K, Y is M x N.
+ */
+#include <math.h>
+#include <pthread.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_OK 0
+#define ORACLE_E_ARG (-1)
+#define ORACLE_E_MEM (-2)
+
+/* ------------------------------------------------------------------ */
+/* row-parallel driver (plain pthreads; each thread owns whole rows)    */
+/* ------------------------------------------------------------------ */
+typedef void (*row_fn)(int64_t row, void* env);
+
+typedef struct {
+    row_fn fn;
+    void* env;
+    int64_t begin, end;
+} row_job;
+
+static void* row_worker(void* p)
+{
+    row_job* j = (row_job*)p;
+    for (int64_t r = j->begin; r < j->end; ++r) j->fn(r, j->env);
+    return NULL;
+}
+
+static int for_rows(int64_t begin, int64_t end, int nthreads, row_fn fn, void* env)
+{
+    int64_t n = end - begin;
+    if (n <= 0) return ORACLE_OK;
+    if (nthreads < 1) nthreads = 1;
+    if ((int64_t)nthreads > n) nthreads = (int)n;
+    if (nthreads == 1) {
+        row_job j = {fn, env, begin, end};
+        row_worker(&j);
+        return ORACLE_OK;
+    }
+    pthread_t* th = (pthread_t*)malloc(sizeof(pthread_t) * (size_t)nthreads);
+    row_job* jobs = (row_job*)malloc(sizeof(row_job) * (size_t)nthreads);
+    char* started = (char*)calloc((size_t)nthreads, 1);
+    if (!th || !jobs || !started) { free(th); free(jobs); free(started); return ORACLE_E_MEM; }
+    for (int t = 0; t < nthreads; ++t) {
+        jobs[t].fn = fn;
+        jobs[t].env = env;
+        jobs[t].begin = begin + n * t / nthreads;
+        jobs[t].end = begin + n * (t + 1) / nthreads;
+        if (pthread_create(&th[t], NULL, row_worker, &jobs[t]) == 0) started[t] = 1;
+        else row_worker(&jobs[t]); /* run inline if a thread cannot start */
+    }
+    for (int t = 0; t < nthreads; ++t)
+        if (started[t]) pthread_join(th[t], NULL);
+    free(th);
+    free(jobs);
+    free(started);
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* the definition                                                       */
+/* ------------------------------------------------------------------ */
+typedef struct {
+    const float *X, *W, *b;
+    int64_t K, N;
+    int64_t ldx, ldw, ldy;
+    double* Y;
+    int absolute; /* 0: value, 1: magnitude */
+} lin_env;
+
+static void linear_row(int64_t i, void* p)
+{
+    const lin_env* e = (const lin_env*)p;
+    const float* x = e->X + i * e->ldx;
+    double* y = e->Y + i * e->ldy;
+    for (int64_t j = 0; j < e->N; ++j) {
+        const float* w = e->W + j * e->ldw;
+        double acc;
+        if (e->b) acc = e->absolute ? fabs((double)e->b[j]) : (double)e->b[j];
+        else acc = 0.0;
+        if (e->absolute) {
+            for (int64_t k = 0; k < e->K; ++k) acc += fabs((double)x[k]) * fabs((double)w[k]);
+        } else {
+            for (int64_t k = 0; k < e->K; ++k) acc += (double)x[k] * (double)w[k];
+        }
+        y[j] = acc;
+    }
+}
+
+/* Rows [row_begin, row_end) of the result, written to Y[(row_end-row_begin) x N]. */
+int oracle_linear_rows(const float* X, const float* W, const float* b, int64_t M, int64_t K,
+                       int64_t N, int64_t row_begin, int64_t row_end, double* Y, int nthreads)
+{
+    if (!X || !W || !Y || M < 0 || K < 0 || N < 0) return ORACLE_E_ARG;
+    if (row_begin < 0 || row_end > M || row_begin > row_end) return ORACLE_E_ARG;
+    lin_env e = {X + row_begin * K, W, b, K, N, K, K, N, Y, 0};
+    return for_rows(0, row_end - row_begin, nthreads, linear_row, &e);
+}
+
+int oracle_linear(const float* X, const float* W, const float* b, int64_t M, int64_t K, int64_t N,
+                  double* Y, int nthreads)
+{
+    return oracle_linear_rows(X, W, b, M, K, N, 0, M, Y, nthreads);
+}
+
+int oracle_magnitude(const float* X, const float* W, const float* b, int64_t M, int64_t K,
+                     int64_t N, double* S, int nthreads)
+{
+    if (!X || !W || !S || M < 0 || K < 0 || N < 0) return ORACLE_E_ARG;
+    lin_env e = {X, W, b, K, N, K, K, N, S, 1};
+    return for_rows(0, M, nthreads, linear_row, &e);
+}
+
+/* n entries: out[e] = bj[e] + <Xr[ix[e]], Wr[jw[e]]>, mag[e] likewise with
+ * absolute values.  Xr / Wr are packed row sets with K columns each; bj (may
+ * be NULL) holds the bias value of each entry. */
+int oracle_entries(const float* Xr, const float* Wr, const float* bj, int64_t K, const int64_t* ix,
+                   const int64_t* jw, int64_t n, double* out, double* mag)
+{
+    if (!Xr || !Wr || !ix || !jw || !out || K < 0 || n < 0) return ORACLE_E_ARG;
+    for (int64_t e = 0; e < n; ++e) {
+        const float* x = Xr + ix[e] * K;
+        const float* w = Wr + jw[e] * K;
+        double acc = bj ? (double)bj[e] : 0.0;
+        double s = bj ? fabs((double)bj[e]) : 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            double p = (double)x[k] * (double)w[k];
+            acc += p;
+            s += fabs(p);
+        }
+        out[e] = acc;
+        if (mag) mag[e] = s;
+    }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* the method, step by step                                             */
+/* ------------------------------------------------------------------ */
+
+/* contiguous copy of the block [r0, r0+nr) x [c0, c0+nc) of a row-major matrix */
+static float* take_block(const float* A, int64_t ld, int64_t r0, int64_t nr, int64_t c0, int64_t nc)
+{
+    float* B = (float*)malloc(sizeof(float) * (size_t)(nr * nc > 0 ? nr * nc : 1));
+    if (!B) return NULL;
+    for (int64_t r = 0; r < nr; ++r)
+        memcpy(B + r * nc, A + (r0 + r) * ld + c0, sizeof(float) * (size_t)nc);
+    return B;
+}
+
+/* P = A * Bt^T for contiguous A [m x k] and Bt [n x k], in double */
+static int block_product(const float* A, const float* Bt, int64_t m, int64_t k, int64_t n,
+                         double* P, int nthreads)
+{
+    lin_env e = {A, Bt, NULL, k, n, k, k, n, P, 0};
+    return for_rows(0, m, nthreads, linear_row, &e);
+}
+
+static double* new_partial(int64_t m, int64_t n)
+{
+    return (double*)calloc((size_t)(m * n > 0 ? m * n : 1), sizeof(double));
+}
+
+static int jigsaw2(const float* X, const float* W, const float* b, int64_t M, int64_t K, int64_t N,
+                   double* Y, int nthreads)
+{
+    /* Sec. 4.1: X = [X_0, X_1] and W = [W_0, W_1] are split on the last
+     * (channel) dimension; each rank further splits its W_r on the
+     * second-to-last dimension into W_{r,0}, W_{r,1}.  Rank r keeps
+     * X_r W_{r,r}^T, ships X_r W_{r,1-r}^T to the other rank, and output
+     * column-half c ends up on rank c (Eq. 2). */
+    const int64_t Kh = K / 2, Nh = N / 2;
+    float *Xs[2] = {0, 0}, *Ws[2][2] = {{0, 0}, {0, 0}};
+    double *kept[2] = {0, 0}, *sent[2] = {0, 0}, *recv[2] = {0, 0};
+    int rc = ORACLE_E_MEM;
+    for (int r = 0; r < 2; ++r) {
+        Xs[r] = take_block(X, K, 0, M, r * Kh, Kh);
+        if (!Xs[r]) goto done;
+        for (int c = 0; c < 2; ++c) {
+            Ws[r][c] = take_block(W, K, c * Nh, Nh, r * Kh, Kh);
+            if (!Ws[r][c]) goto done;
+        }
+        kept[r] = new_partial(M, Nh);
+        sent[r] = new_partial(M, Nh);
+        if (!kept[r] || !sent[r]) goto done;
+    }
+    for (int r = 0; r < 2; ++r) {
+        rc = block_product(Xs[r], Ws[r][1 - r], M, Kh, Nh, sent[r], nthreads);
+        if (rc) goto done;
+        rc = block_product(Xs[r], Ws[r][r], M, Kh, Nh, kept[r], nthreads);
+        if (rc) goto done;
+    }
+    /* exchange: what rank r sent is what rank 1-r receives */
+    recv[0] = sent[1];
+    recv[1] = sent[0];
+    /* combine on the owner and gather: Y[:, c-th half] lives on rank c */
+    for (int c = 0; c < 2; ++c)
+        for (int64_t i = 0; i < M; ++i)
+            for (int64_t j = 0; j < Nh; ++j) {
+                double v = kept[c][i * Nh + j] + recv[c][i * Nh + j];
+                if (b) v += (double)b[c * Nh + j];
+                Y[i * N + c * Nh + j] = v;
+            }
+    rc = ORACLE_OK;
+done:
+    for (int r = 0; r < 2; ++r) {
+        free(Xs[r]); free(Ws[r][0]); free(Ws[r][1]); free(kept[r]); free(sent[r]);
+    }
+    return rc;
+}
+
+static int jigsaw4(const float* X, const float* W, const float* b, int64_t M, int64_t K, int64_t N,
+                   double* Y, int nthreads)
+{
+    /* Sec. 4.2: X = [[X_0, X_1], [X_2, X_3]] and W = [[W_0, W_1], [W_2, W_3]]
+     * are split 2 x 2 on the last two dimensions.  Eq. (4):
+     *   Y_0 = X_0 W_0^T + X_1 W_1^T     Y_1 = X_0 W_2^T + X_1 W_3^T
+     *   Y_2 = X_2 W_0^T + X_3 W_1^T     Y_3 = X_2 W_2^T + X_3 W_3^T
+     * and Y_r sits where X_r sat (rank r).  A term printed bold as a whole is
+     * computed on the rank holding its X block and shipped; a term in which
+     * only W^T is bold is computed where its X block lives, after that weight
+     * block has been shipped there.  Each rank therefore forms two products:
+     *   rank 0: X_0 W_0^T (keep)            X_0 W_2^T (W_2 from rank 2; to rank 1)
+     *   rank 1: X_1 W_1^T (to rank 0)       X_1 W_3^T (W_3 from rank 3; keep)
+     *   rank 2: X_2 W_2^T (to rank 3)       X_2 W_0^T (W_0 from rank 0; keep)
+     *   rank 3: X_3 W_3^T (keep)            X_3 W_1^T (W_1 from rank 1; to rank 2)
+     */
+    const int64_t Mh = M / 2, Kh = K / 2, Nh = N / 2;
+    static const int w_from[4] = {2, 3, 0, 1};      /* rank whose weight block rank r receives */
+    static const int own_is_kept[4] = {1, 0, 0, 1}; /* is X_r W_r^T the kept term on rank r?   */
+    static const int peer[4] = {1, 0, 3, 2};        /* partial-product exchange partner        */
+    float *Xs[4] = {0}, *Ws[4] = {0}, *Wrecv[4] = {0};
+    double *kept[4] = {0}, *sent[4] = {0}, *recv[4] = {0};
+    int rc = ORACLE_E_MEM;
+    for (int r = 0; r < 4; ++r) {
+        Xs[r] = take_block(X, K, (r / 2) * Mh, Mh, (r % 2) * Kh, Kh);
+        Ws[r] = take_block(W, K, (r / 2) * Nh, Nh, (r % 2) * Kh, Kh);
+        kept[r] = new_partial(Mh, Nh);
+        sent[r] = new_partial(Mh, Nh);
+        if (!Xs[r] || !Ws[r] || !kept[r] || !sent[r]) goto done;
+    }
+    /* weight-block exchange (a copy, as a transfer would deliver it) */
+    for (int r = 0; r < 4; ++r) {
+        Wrecv[r] = take_block(Ws[w_from[r]], Kh, 0, Nh, 0, Kh);
+        if (!Wrecv[r]) goto done;
+    }
+    for (int r = 0; r < 4; ++r) {
+        double* own = own_is_kept[r] ? kept[r] : sent[r];
+        double* cross = own_is_kept[r] ? sent[r] : kept[r];
+        rc = block_product(Xs[r], Ws[r], Mh, Kh, Nh, own, nthreads);
+        if (rc) goto done;
+        rc = block_product(Xs[r], Wrecv[r], Mh, Kh, Nh, cross, nthreads);
+        if (rc) goto done;
+    }
+    for (int r = 0; r < 4; ++r) recv[r] = sent[peer[r]];
+    for (int r = 0; r < 4; ++r) {
+        const int64_t i0 = (r / 2) * Mh, j0 = (r % 2) * Nh;
+        for (int64_t i = 0; i < Mh; ++i)
+            for (int64_t j = 0; j < Nh; ++j) {
+                double v = kept[r][i * Nh + j] + recv[r][i * Nh + j];
+                if (b) v += (double)b[j0 + j];
+                Y[(i0 + i) * N + j0 + j] = v;
+            }
+    }
+    rc = ORACLE_OK;
+done:
+    for (int r = 0; r < 4; ++r) {
+        free(Xs[r]); free(Ws[r]); free(Wrecv[r]); free(kept[r]); free(sent[r]);
+    }
+    return rc;
+}
+
+int oracle_jigsaw(int ways, const float* X, const float* W, const float* b, int64_t M, int64_t K,
+                  int64_t N, double* Y, int nthreads)
+{
+    if (!X || !W || !Y || M < 0 || K < 0 || N < 0) return ORACLE_E_ARG;
+    switch (ways) {
+    case 1:
+        return oracle_linear(X, W, b, M, K, N, Y, nthreads);
+    case 2:
+        if ((K % 2) || (N % 2)) return ORACLE_E_ARG;
+        return jigsaw2(X, W, b, M, K, N, Y, nthreads);
+    case 4:
+        if ((M % 2) || (K % 2) || (N % 2)) return ORACLE_E_ARG;
+        return jigsaw4(X, W, b, M, K, N, Y, nthreads);
+    default:
+        return ORACLE_E_ARG;
+    }
+}
