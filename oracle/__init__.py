@@ -51,7 +51,7 @@ def _load():
         lib.oracle_linear.argtypes = [f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int]
         lib.oracle_linear_rows.argtypes = [f32p, f32p, f32p, i64, i64, i64, i64, i64, f64p, ctypes.c_int]
         lib.oracle_magnitude.argtypes = [f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int]
-        lib.oracle_entries.argtypes = [f32p, f32p, f32p, i64, i64p, i64p, i64, f64p, f64p]
+        lib.oracle_entries.argtypes = [f32p, f32p, f32p, i64, i64p, i64p, i64, f64p, f64p, ctypes.c_int]
         lib.oracle_jigsaw.argtypes = [ctypes.c_int, f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int]
         for fn in (lib.oracle_linear, lib.oracle_linear_rows, lib.oracle_magnitude,
                    lib.oracle_entries, lib.oracle_jigsaw):
@@ -126,7 +126,7 @@ def magnitude(X, W, b=None, nthreads: int | None = None) -> np.ndarray:
     return S
 
 
-def entries(Xrows, Wrows, ix, jw, bias_per_entry=None):
+def entries(Xrows, Wrows, ix, jw, bias_per_entry=None, nthreads: int | None = None):
     """(value, magnitude) of entries e: <Xrows[ix[e]], Wrows[jw[e]]> + bias_per_entry[e]."""
     Xr, xp = _f32(Xrows)
     Wr, wp = _f32(Wrows)
@@ -142,7 +142,7 @@ def entries(Xrows, Wrows, ix, jw, bias_per_entry=None):
     mag, mp = _f64_out((n,))
     i64p = ctypes.POINTER(ctypes.c_int64)
     _check(_load().oracle_entries(xp, wp, bp, K, ix.ctypes.data_as(i64p), jw.ctypes.data_as(i64p),
-                                  n, op, mp), "entries")
+                                  n, op, mp, nthreads or host_threads()), "entries")
     return out, mag
 
 
@@ -221,3 +221,28 @@ def gather_y(shards, ways: int) -> np.ndarray:
         return np.concatenate(shards, axis=1)
     return np.concatenate([np.concatenate(shards[0:2], axis=1),
                            np.concatenate(shards[2:4], axis=1)], axis=0)
+
+
+# ----------------------------------------------------------------------------
+# Freivalds' check: the exact product applied to a vector, at O(MK + NK) cost
+# ----------------------------------------------------------------------------
+def freivalds_reference(X, W, b, v, chunk_rows: int = 4096):
+    """(Y64 @ v, S @ 1-ish bound) without forming Y: X (W^T v) + <b, v> in double.
+
+    Returns ``(yv, bound)`` with ``bound[i] = sum_j S[i][j] * |v[j]|`` (the scale
+    of the tolerance for row i of the projected result).
+    """
+    W64 = np.asarray(W, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    u = W64.T @ v
+    ua = np.abs(W64).T @ np.abs(v)
+    bv = 0.0 if b is None else float(np.asarray(b, dtype=np.float64) @ v)
+    ba = 0.0 if b is None else float(np.abs(np.asarray(b, dtype=np.float64)) @ np.abs(v))
+    M = X.shape[0]
+    yv = np.empty(M, dtype=np.float64)
+    bound = np.empty(M, dtype=np.float64)
+    for r0 in range(0, M, chunk_rows):
+        xc = np.asarray(X[r0:r0 + chunk_rows], dtype=np.float64)
+        yv[r0:r0 + chunk_rows] = xc @ u + bv
+        bound[r0:r0 + chunk_rows] = np.abs(xc) @ ua + ba
+    return yv, bound

@@ -146,24 +146,35 @@ int oracle_magnitude(const float* X, const float* W, const float* b, int64_t M, 
 /* n entries: out[e] = bj[e] + <Xr[ix[e]], Wr[jw[e]]>, mag[e] likewise with
  * absolute values.  Xr / Wr are packed row sets with K columns each; bj (may
  * be NULL) holds the bias value of each entry. */
+typedef struct {
+    const float *Xr, *Wr, *bj;
+    int64_t K;
+    const int64_t *ix, *jw;
+    double *out, *mag;
+} ent_env;
+
+static void entry_one(int64_t e, void* p)
+{
+    const ent_env* v = (const ent_env*)p;
+    const float* x = v->Xr + v->ix[e] * v->K;
+    const float* w = v->Wr + v->jw[e] * v->K;
+    double acc = v->bj ? (double)v->bj[e] : 0.0;
+    double s = v->bj ? fabs((double)v->bj[e]) : 0.0;
+    for (int64_t k = 0; k < v->K; ++k) {
+        double pr = (double)x[k] * (double)w[k];
+        acc += pr;
+        s += fabs(pr);
+    }
+    v->out[e] = acc;
+    if (v->mag) v->mag[e] = s;
+}
+
 int oracle_entries(const float* Xr, const float* Wr, const float* bj, int64_t K, const int64_t* ix,
-                   const int64_t* jw, int64_t n, double* out, double* mag)
+                   const int64_t* jw, int64_t n, double* out, double* mag, int nthreads)
 {
     if (!Xr || !Wr || !ix || !jw || !out || K < 0 || n < 0) return ORACLE_E_ARG;
-    for (int64_t e = 0; e < n; ++e) {
-        const float* x = Xr + ix[e] * K;
-        const float* w = Wr + jw[e] * K;
-        double acc = bj ? (double)bj[e] : 0.0;
-        double s = bj ? fabs((double)bj[e]) : 0.0;
-        for (int64_t k = 0; k < K; ++k) {
-            double p = (double)x[k] * (double)w[k];
-            acc += p;
-            s += fabs(p);
-        }
-        out[e] = acc;
-        if (mag) mag[e] = s;
-    }
-    return ORACLE_OK;
+    ent_env v = {Xr, Wr, bj, K, ix, jw, out, mag};
+    return for_rows(0, n, nthreads, entry_one, &v);
 }
 
 /* ------------------------------------------------------------------ */

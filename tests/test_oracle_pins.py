@@ -266,3 +266,14 @@ def test_shards_tile_the_matrices_without_redundancy(ways):
         assert bs[r].shape[0] == ys[r].shape[1]
         j0 = 0 if ways == 1 else (r % 2) * (N // 2)
         assert bs[r][0] == b[j0]
+
+
+def test_freivalds_reference_is_the_projected_product():
+    M, K, N = 40, 33, 21
+    X, W, b = inputs.layer_inputs(81, M, K, N, "R", bias=True)
+    v = np.where(inputs.keys(82, np.arange(N, dtype=np.uint64)) >> np.uint64(63), 1.0, -1.0)
+    yv, bound = oracle.freivalds_reference(X, W, b, v, chunk_rows=7)
+    Y = oracle.linear(X, W, b)
+    S = oracle.magnitude(X, W, b)
+    assert np.all(np.abs(yv - Y @ v) <= 1e-13 * bound)
+    assert np.allclose(bound, S @ np.abs(v), rtol=1e-13, atol=0)
