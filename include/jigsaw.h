@@ -1,0 +1,183 @@
+/*
+ * libjigsaw - forward pass of a Jigsaw-partitioned linear layer on one AMD MI355X (gfx950).
+ *
+ * The operation (Sec. 4 of the Jigsaw paper): a linear layer is the product
+ *     Y = X W^T (+ b),   X: M x K activations,  W: N x K weights,  Y: M x N,
+ * and in an n-way parallel model every rank holds 1/n of X, of W and of Y, with no
+ * all-gather or broadcast of parameters (Sec. 4, "zero memory redundancy").
+ *
+ *   ways = 1   the unpartitioned layer (the paper's 1-way baseline, Sec. 6.2.1).
+ *   ways = 2   Sec. 4.1, Eqs. (1)-(2): X and W are split on the last (channel)
+ *              dimension, X = [X_0, X_1], W = [W_0, W_1]; rank r splits its W_r by
+ *              rows into W_{r,0}, W_{r,1}, keeps X_r W_{r,r}^T, ships X_r W_{r,1-r}^T
+ *              to the other rank, and ends with Y_r = Y[:, r-th half of N].
+ *   ways = 4   Sec. 4.2, Eqs. (3)-(4): X, W (and Y) are split 2 x 2 on the last two
+ *              dimensions, blocks numbered row-major.  Rank r forms two block
+ *              products; one partial product and one weight block are handed to a
+ *              peer, and Y_r sits where X_r sat.
+ *
+ * All n ranks of one layer are "virtual ranks" resident on the one GPU: each has its
+ * own shard buffers, and a hand-off to a peer is a store into the peer's buffer.
+ *
+ * Conventions
+ *  - Every function returns JG_OK (0) or a negative jg_status.  Nothing throws,
+ *    aborts or prints.
+ *  - All matrices are dense row-major FP32.  "device" pointers are HIP device
+ *    addresses owned by the caller (e.g. PyTorch tensors); "host" pointers are
+ *    ordinary host memory.  The library allocates no device memory.
+ *  - Shard arguments are HOST arrays of `ways` DEVICE pointers, indexed by rank.
+ *    A rank's shard is contiguous (leading dimension = its column count).
+ *  - All GPU work is enqueued on the stream given to jg_init and is asynchronous;
+ *    the library synchronises only in jg_profile_read.
+ *  - Inputs are never written.  Outputs and workspace must not overlap inputs.
+ *  - Handles are host-heap objects freed only by the matching call; NULL is a no-op
+ *    for the two release functions.  One jg_ctx per host thread.  A plan is
+ *    immutable and reusable; concurrent forwards that share a workspace race.
+ */
+#ifndef JIGSAW_H
+#define JIGSAW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct jg_ctx jg_ctx;
+typedef struct jg_plan jg_plan;
+
+typedef enum jg_status {
+    JG_OK = 0,
+    JG_E_NULL = -1,      /* a required pointer (handle, array, array element) is NULL   */
+    JG_E_SHAPE = -2,     /* M, K, N <= 0, too large, or not divisible as `ways` needs   */
+    JG_E_WAYS = -3,      /* ways not in {1, 2, 4}, or rank out of range                 */
+    JG_E_DTYPE = -4,     /* unsupported dtype / op / option value                       */
+    JG_E_WORKSPACE = -5, /* workspace NULL or smaller than JG_Q_WORKSPACE_BYTES         */
+    JG_E_ALIGN = -6,     /* a device pointer is not 4-byte aligned, workspace not 256-B */
+    JG_E_HIP = -7,       /* a HIP runtime call failed                                   */
+    JG_E_ARCH = -8       /* the device is not gfx950                                    */
+} jg_status;
+
+enum { JG_OP_XWT = 0 };                                  /* Y = X W^T (Sec. 4)          */
+enum { JG_F32 = 0 };                                     /* the paper's uniform single precision (Sec. 6.1) */
+enum { JG_COMBINE_FUSED = 0, JG_COMBINE_SEPARATE = 1 };  /* where the "+" of Eq. (2)/(4) runs */
+enum { JG_WEIGHTS_COPY = 0, JG_WEIGHTS_DIRECT = 1 };     /* 4-way weight-block hand-off */
+enum { JG_T_X = 0, JG_T_W = 1, JG_T_B = 2 };             /* tensor selector of jg_shard */
+
+typedef struct jg_linear_desc {
+    int64_t M, K, N;     /* global sizes: X is M x K, W is N x K, Y is M x N            */
+    int32_t ways;        /* 1, 2 or 4                                                   */
+    int32_t op;          /* JG_OP_XWT                                                   */
+    int32_t dtype;       /* JG_F32                                                      */
+    int32_t has_bias;    /* 0 / 1: b_r (the slice of b matching Y_r's columns) is added
+                            once, by the rank that owns the output block                */
+    int32_t combine;     /* JG_COMBINE_FUSED: the local-product GEMM reads the received
+                            partial in its epilogue.  JG_COMBINE_SEPARATE: the local
+                            product is written out and a streaming kernel adds the two
+                            partials (for measurement).                                 */
+    int32_t weights;     /* 4-way only.  JG_WEIGHTS_COPY: the weight block a rank needs
+                            from its peer (the terms of Eq. (4) in which only W^T is
+                            bold) is copied into the workspace first, as a transfer
+                            would deliver it.  JG_WEIGHTS_DIRECT: the peer's buffer is
+                            read in place.                                              */
+} jg_linear_desc;
+
+typedef enum jg_query {
+    JG_Q_WORKSPACE_BYTES = 0,    /* device bytes jg_linear_forward needs (rank ignored)        */
+    JG_Q_FLOPS_TOTAL = 1,        /* 2 M K N: matmul dimensions only (Sec. 6.3 work model)      */
+    JG_Q_FLOPS_RANK = 2,         /* one rank's two block products                              */
+    JG_Q_HBM_BYTES_ALGO = 3,     /* 4(MK + NK + MN), plus 8 MN for ways >= 2 (each partial
+                                    product is written once and read once)                     */
+    JG_Q_EXCHANGE_BYTES_RANK = 4,/* bytes a rank hands to its peers per forward                */
+    JG_Q_X_ROWS = 5, JG_Q_X_COLS = 6,   /* shape of rank's X shard                             */
+    JG_Q_W_ROWS = 7, JG_Q_W_COLS = 8,   /* shape of rank's W shard                             */
+    JG_Q_Y_ROWS = 9, JG_Q_Y_COLS = 10,  /* shape of rank's Y shard                             */
+    JG_Q_B_LEN = 11,                    /* length of rank's bias slice (= Y_COLS)              */
+    JG_Q_RESIDENT_BYTES_RANK = 12,      /* bytes of X_r + W_r + Y_r (bias and workspace apart) */
+    JG_Q_GEMM_LAUNCHES = 13      /* GEMM kernel launches per forward (rank ignored)            */
+} jg_query;
+
+typedef enum jg_kernel {         /* kernel classes for jg_profile_read */
+    JG_KERNEL_GEMM = 0,          /* block-product GEMM (with or without fused combine)  */
+    JG_KERNEL_WEIGHT_COPY = 1,   /* 4-way weight-block hand-off                         */
+    JG_KERNEL_COMBINE = 2,       /* separate partial-sum combine                        */
+    JG_KERNEL_SHARD = 3,
+    JG_KERNEL_GATHER = 4,
+    JG_KERNEL_COUNT = 5
+} jg_kernel;
+
+/* init.  Creates a context bound to HIP device `device` and to `hip_stream`
+ * (a hipStream_t passed as void*; NULL = the device's default stream).  The stream
+ * stays owned by the caller and must outlive the context.
+ * Errors: JG_E_NULL (out), JG_E_HIP (bad device), JG_E_ARCH (not gfx950). */
+int jg_init(jg_ctx** out, int device, void* hip_stream);
+
+/* free.  Releases the context (not its plans, not the stream). */
+void jg_free(jg_ctx* ctx);
+
+/* build.  Validates `desc` and fixes the block decomposition of Sec. 4.1 / 4.2 for
+ * these sizes.  2-way needs even K and N; 4-way needs even M, K and N (the paper's
+ * loader zero-pads to make partitions equal, Sec. 5 "Data loading": padding is the
+ * caller's job).  Host-only; launches nothing.  `ctx` may be NULL: the plan then
+ * serves jg_plan_query only and the data calls return JG_E_NULL.
+ * Errors: JG_E_NULL, JG_E_WAYS, JG_E_DTYPE, JG_E_SHAPE (checked in this order). */
+int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out);
+void jg_plan_destroy(jg_plan* plan);
+
+/* query.  Host-only accounting of the plan; `rank` in [0, ways) where it matters.
+ * Errors: JG_E_NULL, JG_E_WAYS (rank), JG_E_DTYPE (unknown `what`). */
+int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out);
+
+/* build (data).  Splits a global tensor into the per-rank shards of Sec. 4.1 / 4.2.
+ *   which = JG_T_X: global is M x K with leading dimension ld >= K;
+ *           2-way: X_r = X[:, r-th half of K];  4-way: X_r = block (r/2, r%2).
+ *   which = JG_T_W: global is N x K, ld >= K; split exactly like X
+ *           (2-way: rank r holds all N rows of its column half).
+ *   which = JG_T_B: global is the length-N bias (ld ignored); b_r = the half of b
+ *           matching Y_r's columns (4-way: replicated on the two ranks of a column).
+ * `global` is a device pointer; `shards` is a host array of `ways` device pointers,
+ * each with room for the rank's shard.  Pure data movement: bit-exact.
+ * Errors: JG_E_NULL, JG_E_SHAPE (ld), JG_E_ALIGN, JG_E_DTYPE (which), JG_E_HIP. */
+int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, float* const* shards);
+
+/* run.  One forward pass of the layer over all `ways` virtual ranks:
+ *   (ways = 4, JG_WEIGHTS_COPY) copy each rank's incoming weight block;
+ *   launch 1: every rank's product that is handed to a peer, stored into the
+ *             peer-visible partial buffer in the workspace;
+ *   launch 2: every rank's kept product, whose epilogue adds the received partial
+ *             and the bias and writes Y_r (JG_COMBINE_FUSED), or the kept product
+ *             followed by a separate combine kernel (JG_COMBINE_SEPARATE).
+ * ways = 1 is a single GEMM with the bias in its epilogue and needs no workspace.
+ * x_sh, w_sh, y_sh: host arrays of `ways` device pointers (shapes: JG_Q_*_ROWS/COLS);
+ * b_sh: the same for the bias slices, required iff has_bias.  `workspace` is a
+ * 256-byte-aligned device buffer of at least JG_Q_WORKSPACE_BYTES bytes (may be NULL
+ * when that is 0); its contents on entry are irrelevant and are overwritten.
+ * FP32 storage, FP32 matrix-core multiply-accumulate.
+ * Errors: JG_E_NULL, JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
+int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                      const float* const* b_sh, float* const* y_sh, void* workspace,
+                      size_t workspace_bytes);
+
+/* query (data).  Inverse of jg_shard for Y: writes the M x N global result (device,
+ * leading dimension ld >= N) from the per-rank Y shards.  Bit-exact.
+ * Errors: JG_E_NULL, JG_E_SHAPE, JG_E_ALIGN, JG_E_HIP. */
+int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, int64_t ld);
+
+/* Per-kernel timing with HIP events on the context's stream.
+ * jg_profile(ctx, 1) starts bracketing every subsequent kernel launch of this
+ * context with an event pair (a bounded pool; launches beyond it go untimed);
+ * jg_profile(ctx, 0) stops.  jg_profile_read synchronises the stream, returns the
+ * summed duration (milliseconds) and the number of timed launches of one kernel
+ * class since the last read of that class, and clears them.
+ * Errors: JG_E_NULL, JG_E_DTYPE (kernel class), JG_E_HIP. */
+int jg_profile(jg_ctx* ctx, int enable);
+int jg_profile_read(jg_ctx* ctx, int kernel, double* total_ms, int64_t* launches);
+
+/* Static description of a status code (never NULL). */
+const char* jg_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JIGSAW_H */

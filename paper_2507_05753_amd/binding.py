@@ -1,0 +1,151 @@
+"""ctypes binding of ``libjigsaw.so`` (declared in ``include/jigsaw.h``).
+
+Argument marshalling only: every step of the layer runs in the library's HIP
+kernels.  The functions carry the C names.  Device pointers are plain integers
+(e.g. ``torch.Tensor.data_ptr()``); shard arguments are sequences of ``ways``
+such integers.  A negative status raises :class:`JigsawError`.
+
+There is no CPU fallback: importing this module fails if the library has not
+been built (``python -m paper_2507_05753_amd.build`` or ``__graft_entry__.build()``).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libjigsaw.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build the HIP library first "
+        "(python paper_2507_05753_amd/build.py); there is no CPU fallback")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+# ---- constants (mirror include/jigsaw.h) ------------------------------------
+JG_OK = 0
+JG_E_NULL, JG_E_SHAPE, JG_E_WAYS, JG_E_DTYPE = -1, -2, -3, -4
+JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP, JG_E_ARCH = -5, -6, -7, -8
+JG_OP_XWT = 0
+JG_F32 = 0
+JG_COMBINE_FUSED, JG_COMBINE_SEPARATE = 0, 1
+JG_WEIGHTS_COPY, JG_WEIGHTS_DIRECT = 0, 1
+JG_T_X, JG_T_W, JG_T_B = 0, 1, 2
+(JG_Q_WORKSPACE_BYTES, JG_Q_FLOPS_TOTAL, JG_Q_FLOPS_RANK, JG_Q_HBM_BYTES_ALGO,
+ JG_Q_EXCHANGE_BYTES_RANK, JG_Q_X_ROWS, JG_Q_X_COLS, JG_Q_W_ROWS, JG_Q_W_COLS,
+ JG_Q_Y_ROWS, JG_Q_Y_COLS, JG_Q_B_LEN, JG_Q_RESIDENT_BYTES_RANK, JG_Q_GEMM_LAUNCHES) = range(14)
+(JG_KERNEL_GEMM, JG_KERNEL_WEIGHT_COPY, JG_KERNEL_COMBINE, JG_KERNEL_SHARD,
+ JG_KERNEL_GATHER, JG_KERNEL_COUNT) = range(6)
+
+EXPORTS = ("jg_init", "jg_free", "jg_plan_create", "jg_plan_destroy", "jg_plan_query", "jg_shard",
+           "jg_linear_forward", "jg_gather", "jg_profile", "jg_profile_read", "jg_strerror")
+
+
+class jg_linear_desc(ctypes.Structure):
+    _fields_ = [("M", ctypes.c_int64), ("K", ctypes.c_int64), ("N", ctypes.c_int64),
+                ("ways", ctypes.c_int32), ("op", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("has_bias", ctypes.c_int32), ("combine", ctypes.c_int32), ("weights", ctypes.c_int32)]
+
+
+class JigsawError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {_lib.jg_strerror(status).decode()} ({status})")
+
+
+_vp = ctypes.c_void_p
+_vpp = ctypes.POINTER(ctypes.c_void_p)
+_lib.jg_strerror.argtypes = [ctypes.c_int]
+_lib.jg_strerror.restype = ctypes.c_char_p
+_lib.jg_init.argtypes = [_vpp, ctypes.c_int, _vp]
+_lib.jg_free.argtypes = [_vp]
+_lib.jg_free.restype = None
+_lib.jg_plan_create.argtypes = [_vp, ctypes.POINTER(jg_linear_desc), _vpp]
+_lib.jg_plan_destroy.argtypes = [_vp]
+_lib.jg_plan_destroy.restype = None
+_lib.jg_plan_query.argtypes = [_vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]
+_lib.jg_shard.argtypes = [_vp, ctypes.c_int, _vp, ctypes.c_int64, _vpp]
+_lib.jg_linear_forward.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
+_lib.jg_gather.argtypes = [_vp, _vpp, _vp, ctypes.c_int64]
+_lib.jg_profile.argtypes = [_vp, ctypes.c_int]
+_lib.jg_profile_read.argtypes = [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
+                                 ctypes.POINTER(ctypes.c_int64)]
+for _n in ("jg_init", "jg_plan_create", "jg_plan_query", "jg_shard", "jg_linear_forward",
+           "jg_gather", "jg_profile", "jg_profile_read"):
+    getattr(_lib, _n).restype = ctypes.c_int
+
+
+def _ptr_array(ptrs):
+    if ptrs is None:
+        return None
+    arr = (ctypes.c_void_p * len(ptrs))(*[int(p) if p else None for p in ptrs])
+    return ctypes.cast(arr, _vpp)
+
+
+def _raise(status: int, where: str):
+    if status != JG_OK:
+        raise JigsawError(status, where)
+
+
+def jg_strerror(status: int) -> str:
+    return _lib.jg_strerror(status).decode()
+
+
+def jg_init(device: int = 0, hip_stream: int | None = None) -> int:
+    out = ctypes.c_void_p()
+    _raise(_lib.jg_init(ctypes.byref(out), device, hip_stream or None), "jg_init")
+    return out.value
+
+
+def jg_free(ctx) -> None:
+    _lib.jg_free(ctx)
+
+
+def jg_plan_create(ctx, M: int, K: int, N: int, ways: int, has_bias: bool = False,
+                   combine: int = JG_COMBINE_FUSED, weights: int = JG_WEIGHTS_COPY,
+                   op: int = JG_OP_XWT, dtype: int = JG_F32) -> int:
+    d = jg_linear_desc(M, K, N, ways, op, dtype, int(has_bias), combine, weights)
+    out = ctypes.c_void_p()
+    _raise(_lib.jg_plan_create(ctx, ctypes.byref(d), ctypes.byref(out)), "jg_plan_create")
+    return out.value
+
+
+def jg_plan_destroy(plan) -> None:
+    _lib.jg_plan_destroy(plan)
+
+
+def jg_plan_query(plan, what: int, rank: int = 0) -> int:
+    out = ctypes.c_int64()
+    _raise(_lib.jg_plan_query(plan, what, rank, ctypes.byref(out)), "jg_plan_query")
+    return out.value
+
+
+def jg_shard(plan, which: int, global_ptr: int, ld: int, shard_ptrs) -> None:
+    _raise(_lib.jg_shard(plan, which, global_ptr, ld, _ptr_array(shard_ptrs)), "jg_shard")
+
+
+def jg_linear_forward(plan, x_ptrs, w_ptrs, b_ptrs, y_ptrs, workspace_ptr, workspace_bytes: int) -> None:
+    _raise(_lib.jg_linear_forward(plan, _ptr_array(x_ptrs), _ptr_array(w_ptrs), _ptr_array(b_ptrs),
+                                  _ptr_array(y_ptrs), workspace_ptr or None, workspace_bytes),
+           "jg_linear_forward")
+
+
+def jg_gather(plan, y_ptrs, global_y_ptr: int, ld: int) -> None:
+    _raise(_lib.jg_gather(plan, _ptr_array(y_ptrs), global_y_ptr, ld), "jg_gather")
+
+
+def jg_profile(ctx, enable: bool) -> None:
+    _raise(_lib.jg_profile(ctx, int(enable)), "jg_profile")
+
+
+def jg_profile_read(ctx, kernel: int):
+    ms = ctypes.c_double()
+    n = ctypes.c_int64()
+    _raise(_lib.jg_profile_read(ctx, kernel, ctypes.byref(ms), ctypes.byref(n)), "jg_profile_read")
+    return ms.value, n.value
+
+
+def raw():
+    """The loaded ``ctypes.CDLL`` (for tests that drive the C ABI with hand-made arguments)."""
+    return _lib

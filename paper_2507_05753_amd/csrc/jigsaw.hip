@@ -1,0 +1,462 @@
+// C-ABI layer of libjigsaw (see include/jigsaw.h): argument checking, the block
+// decomposition of Sec. 4.1 / 4.2, workspace layout, and kernel launches.
+// No device memory is allocated here and nothing synchronises except jg_profile_read.
+#include "../../include/jigsaw.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "gemm_nt.hpp"
+#include "stream_kernels.hpp"
+
+namespace {
+
+constexpr int kProfileMaxLaunches = 8192;
+constexpr int64_t kMaxDim = 0x7fffffff - 1024;   // every dimension fits an int with tile slack
+constexpr size_t kWsAlign = 256;
+
+struct TimedLaunch {
+    hipEvent_t start, stop;
+    int kernel;
+};
+
+}  // namespace
+
+struct jg_ctx {
+    int device;
+    hipStream_t stream;
+    bool profiling;
+    std::vector<hipEvent_t> pool;        // created on first jg_profile(ctx, 1)
+    size_t pool_used;
+    std::vector<TimedLaunch> timed;
+};
+
+struct jg_plan {
+    jg_ctx* ctx;
+    jg_linear_desc d;
+    // per-rank shard shapes
+    int64_t xr, xc, wr, wc, yr, yc;
+    // workspace layout (byte offsets); sizes are per rank
+    size_t part_bytes;     // one rank's partial product  (yr x yc floats, padded)
+    size_t wblk_bytes;     // one rank's received weight block (4-way, copy mode)
+    size_t off_send;       // ways x part_bytes: partial products handed to the peer
+    size_t off_kept;       // ways x part_bytes: kept products (separate combine only)
+    size_t off_wrecv;      // ways x wblk_bytes
+    size_t ws_bytes;
+};
+
+namespace {
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// 4-way roles (Sec. 4.2, Eq. (4)).  A term printed bold as a whole product is formed
+// on the rank that holds its X block and shipped; where only W^T is bold the weight
+// block is shipped to the rank holding the X block.
+//   rank 0: X0 W0^T keep            X0 W2^T (W2 from rank 2) -> rank 1
+//   rank 1: X1 W1^T -> rank 0       X1 W3^T (W3 from rank 3) keep
+//   rank 2: X2 W2^T -> rank 3       X2 W0^T (W0 from rank 0) keep
+//   rank 3: X3 W3^T keep            X3 W1^T (W1 from rank 1) -> rank 2
+constexpr int kWeightFrom4[4] = {2, 3, 0, 1};
+constexpr int kOwnIsKept4[4] = {1, 0, 0, 1};
+constexpr int kPeer4[4] = {1, 0, 3, 2};
+
+struct ScopedTimer {
+    jg_ctx* c;
+    int kernel;
+    hipEvent_t stop;
+    bool on;
+    ScopedTimer(jg_ctx* ctx, int k) : c(ctx), kernel(k), stop(nullptr), on(false)
+    {
+        if (c->profiling && c->pool_used + 2 <= c->pool.size()) {
+            hipEvent_t start = c->pool[c->pool_used++];
+            stop = c->pool[c->pool_used++];
+            if (hipEventRecord(start, c->stream) == hipSuccess) {
+                c->timed.push_back({start, stop, kernel});
+                on = true;
+            }
+        }
+    }
+    ~ScopedTimer()
+    {
+        if (on) (void)hipEventRecord(stop, c->stream);
+    }
+};
+
+inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+int check_ptr_array(const float* const* arr, int n)
+{
+    if (!arr) return JG_E_NULL;
+    for (int i = 0; i < n; ++i) {
+        if (!arr[i]) return JG_E_NULL;
+        if (!aligned(arr[i], 4)) return JG_E_ALIGN;
+    }
+    return JG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* jg_strerror(int status)
+{
+    switch (status) {
+    case JG_OK: return "ok";
+    case JG_E_NULL: return "required pointer is NULL";
+    case JG_E_SHAPE: return "bad shape: non-positive, too large, or not divisible as `ways` requires";
+    case JG_E_WAYS: return "ways must be 1, 2 or 4 and rank must be in [0, ways)";
+    case JG_E_DTYPE: return "unsupported dtype, op or option value";
+    case JG_E_WORKSPACE: return "workspace missing or too small";
+    case JG_E_ALIGN: return "misaligned device pointer";
+    case JG_E_HIP: return "HIP runtime call failed";
+    case JG_E_ARCH: return "device is not gfx950";
+    default: return "unknown status";
+    }
+}
+
+int jg_init(jg_ctx** out, int device, void* hip_stream)
+{
+    if (!out) return JG_E_NULL;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return JG_E_HIP;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return JG_E_HIP;
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return JG_E_ARCH;
+    if (hipSetDevice(device) != hipSuccess) return JG_E_HIP;
+    if (jg::prepare_gemm() != hipSuccess) return JG_E_HIP;
+    jg_ctx* c = new (std::nothrow) jg_ctx();
+    if (!c) return JG_E_HIP;
+    c->device = device;
+    c->stream = (hipStream_t)hip_stream;
+    c->profiling = false;
+    c->pool_used = 0;
+    *out = c;
+    return JG_OK;
+}
+
+void jg_free(jg_ctx* ctx)
+{
+    if (!ctx) return;
+    (void)hipSetDevice(ctx->device);
+    for (hipEvent_t e : ctx->pool) (void)hipEventDestroy(e);
+    delete ctx;
+}
+
+int jg_profile(jg_ctx* ctx, int enable)
+{
+    if (!ctx) return JG_E_NULL;
+    if (hipSetDevice(ctx->device) != hipSuccess) return JG_E_HIP;
+    if (enable && ctx->pool.empty()) {
+        ctx->pool.reserve(2 * kProfileMaxLaunches);
+        ctx->timed.reserve(kProfileMaxLaunches);
+        for (int i = 0; i < 2 * kProfileMaxLaunches; ++i) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return JG_E_HIP;
+            ctx->pool.push_back(e);
+        }
+    }
+    ctx->profiling = enable != 0;
+    return JG_OK;
+}
+
+int jg_profile_read(jg_ctx* ctx, int kernel, double* total_ms, int64_t* launches)
+{
+    if (!ctx || !total_ms || !launches) return JG_E_NULL;
+    if (kernel < 0 || kernel >= JG_KERNEL_COUNT) return JG_E_DTYPE;
+    if (hipSetDevice(ctx->device) != hipSuccess) return JG_E_HIP;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return JG_E_HIP;
+    double sum = 0.0;
+    int64_t n = 0;
+    std::vector<TimedLaunch> rest;
+    rest.reserve(ctx->timed.size());
+    for (const TimedLaunch& t : ctx->timed) {
+        if (t.kernel != kernel) {
+            rest.push_back(t);
+            continue;
+        }
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, t.start, t.stop) != hipSuccess) return JG_E_HIP;
+        sum += ms;
+        ++n;
+    }
+    ctx->timed.swap(rest);
+    if (ctx->timed.empty()) ctx->pool_used = 0;   // every pair has been read: reuse the pool
+    *total_ms = sum;
+    *launches = n;
+    return JG_OK;
+}
+
+int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
+{
+    if (!out) return JG_E_NULL;
+    *out = nullptr;
+    if (!desc) return JG_E_NULL;
+    const jg_linear_desc& d = *desc;
+    if (d.ways != 1 && d.ways != 2 && d.ways != 4) return JG_E_WAYS;
+    if (d.op != JG_OP_XWT || d.dtype != JG_F32) return JG_E_DTYPE;
+    if (d.combine != JG_COMBINE_FUSED && d.combine != JG_COMBINE_SEPARATE) return JG_E_DTYPE;
+    if (d.weights != JG_WEIGHTS_COPY && d.weights != JG_WEIGHTS_DIRECT) return JG_E_DTYPE;
+    if (d.has_bias != 0 && d.has_bias != 1) return JG_E_DTYPE;
+    if (d.M <= 0 || d.K <= 0 || d.N <= 0) return JG_E_SHAPE;
+    if (d.M > kMaxDim || d.K > kMaxDim || d.N > kMaxDim) return JG_E_SHAPE;
+    if (d.ways >= 2 && ((d.K & 1) || (d.N & 1))) return JG_E_SHAPE;
+    if (d.ways == 4 && (d.M & 1)) return JG_E_SHAPE;
+
+    jg_plan* p = new (std::nothrow) jg_plan();
+    if (!p) return JG_E_HIP;
+    p->ctx = ctx;
+    p->d = d;
+    switch (d.ways) {
+    case 1:
+        p->xr = d.M; p->xc = d.K; p->wr = d.N; p->wc = d.K; p->yr = d.M; p->yc = d.N;
+        break;
+    case 2:   // Sec. 4.1: channel (last) dimension halved; W_r keeps all N rows
+        p->xr = d.M; p->xc = d.K / 2; p->wr = d.N; p->wc = d.K / 2; p->yr = d.M; p->yc = d.N / 2;
+        break;
+    default:  // Sec. 4.2: 2 x 2 blocks
+        p->xr = d.M / 2; p->xc = d.K / 2; p->wr = d.N / 2; p->wc = d.K / 2;
+        p->yr = d.M / 2; p->yc = d.N / 2;
+        break;
+    }
+    p->part_bytes = p->wblk_bytes = 0;
+    p->off_send = p->off_kept = p->off_wrecv = 0;
+    size_t off = 0;
+    if (d.ways >= 2) {
+        p->part_bytes = round_up((size_t)p->yr * (size_t)p->yc * sizeof(float), kWsAlign);
+        p->off_send = off;
+        off += p->part_bytes * d.ways;
+        if (d.combine == JG_COMBINE_SEPARATE) {
+            p->off_kept = off;
+            off += p->part_bytes * d.ways;
+        }
+        if (d.ways == 4 && d.weights == JG_WEIGHTS_COPY) {
+            p->wblk_bytes = round_up((size_t)p->wr * (size_t)p->wc * sizeof(float), kWsAlign);
+            p->off_wrecv = off;
+            off += p->wblk_bytes * d.ways;
+        }
+    }
+    p->ws_bytes = off;
+    *out = p;
+    return JG_OK;
+}
+
+void jg_plan_destroy(jg_plan* plan) { delete plan; }
+
+int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
+{
+    if (!plan || !out) return JG_E_NULL;
+    const jg_linear_desc& d = plan->d;
+    const bool per_rank = what == JG_Q_FLOPS_RANK || what == JG_Q_EXCHANGE_BYTES_RANK ||
+                          (what >= JG_Q_X_ROWS && what <= JG_Q_RESIDENT_BYTES_RANK);
+    if (per_rank && (rank < 0 || rank >= d.ways)) return JG_E_WAYS;
+    const int64_t M = d.M, K = d.K, N = d.N;
+    switch (what) {
+    case JG_Q_WORKSPACE_BYTES: *out = (int64_t)plan->ws_bytes; break;
+    case JG_Q_FLOPS_TOTAL: *out = 2 * M * K * N; break;
+    case JG_Q_FLOPS_RANK: *out = 2 * M * K * N / d.ways; break;
+    case JG_Q_HBM_BYTES_ALGO:
+        *out = 4 * (M * K + N * K + M * N) + (d.ways >= 2 ? 8 * M * N : 0);
+        break;
+    case JG_Q_EXCHANGE_BYTES_RANK:
+        // 2-way: one M x N/2 partial.  4-way: one M/2 x N/2 partial and one N/2 x K/2 weight block.
+        *out = d.ways == 1 ? 0
+             : d.ways == 2 ? 4 * M * (N / 2)
+                           : 4 * ((M / 2) * (N / 2) + (N / 2) * (K / 2));
+        break;
+    case JG_Q_X_ROWS: *out = plan->xr; break;
+    case JG_Q_X_COLS: *out = plan->xc; break;
+    case JG_Q_W_ROWS: *out = plan->wr; break;
+    case JG_Q_W_COLS: *out = plan->wc; break;
+    case JG_Q_Y_ROWS: *out = plan->yr; break;
+    case JG_Q_Y_COLS: *out = plan->yc; break;
+    case JG_Q_B_LEN: *out = plan->yc; break;
+    case JG_Q_RESIDENT_BYTES_RANK:
+        *out = 4 * (plan->xr * plan->xc + plan->wr * plan->wc + plan->yr * plan->yc);
+        break;
+    case JG_Q_GEMM_LAUNCHES: *out = d.ways == 1 ? 1 : 2; break;
+    default: return JG_E_DTYPE;
+    }
+    return JG_OK;
+}
+
+int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, float* const* shards)
+{
+    if (!plan || !global) return JG_E_NULL;
+    const jg_linear_desc& d = plan->d;
+    if (int rc = check_ptr_array(shards, d.ways)) return rc;
+    if (!aligned(global, 4)) return JG_E_ALIGN;
+    if (which != JG_T_X && which != JG_T_W && which != JG_T_B) return JG_E_DTYPE;
+    jg_ctx* c = plan->ctx;
+    if (!c) return JG_E_NULL;
+    if (hipSetDevice(c->device) != hipSuccess) return JG_E_HIP;
+
+    jg::CopyGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.nblocks = d.ways;
+    if (which == JG_T_B) {
+        g.rows = 1;
+        g.cols = (int)plan->yc;
+        for (int r = 0; r < d.ways; ++r) {
+            const int64_t col_half = d.ways == 1 ? 0 : (r % 2);
+            g.b[r] = {global + col_half * plan->yc, shards[r], plan->yc, plan->yc};
+        }
+    } else {
+        const int64_t rows = which == JG_T_X ? plan->xr : plan->wr;
+        const int64_t cols = plan->xc;   // X and W shards have the same column count
+        if (ld < d.K) return JG_E_SHAPE;
+        g.rows = (int)rows;
+        g.cols = (int)cols;
+        for (int r = 0; r < d.ways; ++r) {
+            int64_t rb = 0, cb = 0;   // block coordinates of rank r
+            if (d.ways == 2) cb = r;
+            if (d.ways == 4) { rb = r / 2; cb = r % 2; }
+            g.b[r] = {global + rb * rows * ld + cb * cols, shards[r], ld, cols};
+        }
+    }
+    ScopedTimer t(c, JG_KERNEL_SHARD);
+    return jg::launch_copy_group(g, c->stream) == hipSuccess ? JG_OK : JG_E_HIP;
+}
+
+int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, int64_t ld)
+{
+    if (!plan || !global_y) return JG_E_NULL;
+    const jg_linear_desc& d = plan->d;
+    if (int rc = check_ptr_array(y_sh, d.ways)) return rc;
+    if (!aligned(global_y, 4)) return JG_E_ALIGN;
+    if (ld < d.N) return JG_E_SHAPE;
+    jg_ctx* c = plan->ctx;
+    if (!c) return JG_E_NULL;
+    if (hipSetDevice(c->device) != hipSuccess) return JG_E_HIP;
+
+    jg::CopyGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.nblocks = d.ways;
+    g.rows = (int)plan->yr;
+    g.cols = (int)plan->yc;
+    for (int r = 0; r < d.ways; ++r) {
+        int64_t rb = 0, cb = 0;
+        if (d.ways == 2) cb = r;
+        if (d.ways == 4) { rb = r / 2; cb = r % 2; }
+        g.b[r] = {y_sh[r], global_y + rb * plan->yr * ld + cb * plan->yc, plan->yc, ld};
+    }
+    ScopedTimer t(c, JG_KERNEL_GATHER);
+    return jg::launch_copy_group(g, c->stream) == hipSuccess ? JG_OK : JG_E_HIP;
+}
+
+int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                      const float* const* b_sh, float* const* y_sh, void* workspace,
+                      size_t workspace_bytes)
+{
+    if (!plan || !plan->ctx) return JG_E_NULL;
+    const jg_linear_desc& d = plan->d;
+    const int ways = d.ways;
+    if (int rc = check_ptr_array(x_sh, ways)) return rc;
+    if (int rc = check_ptr_array(w_sh, ways)) return rc;
+    if (int rc = check_ptr_array(y_sh, ways)) return rc;
+    if (d.has_bias) {
+        if (int rc = check_ptr_array(b_sh, ways)) return rc;
+    }
+    if (plan->ws_bytes > 0) {
+        if (!workspace || workspace_bytes < plan->ws_bytes) return JG_E_WORKSPACE;
+        if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
+    }
+    jg_ctx* c = plan->ctx;
+    if (hipSetDevice(c->device) != hipSuccess) return JG_E_HIP;
+    char* ws = static_cast<char*>(workspace);
+    auto bias_of = [&](int r) -> const float* { return d.has_bias ? b_sh[r] : nullptr; };
+
+    jg::GemmGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.M = (int)plan->yr;
+    g.N = (int)plan->yc;
+    g.K = (int)plan->xc;
+    const int ldk = (int)plan->xc;   // leading dimension of every X / W shard
+    const int ldn = (int)plan->yc;   // leading dimension of every Y shard / partial
+
+    if (ways == 1) {
+        g.nprob = 1;
+        g.p[0] = {x_sh[0], w_sh[0], y_sh[0], nullptr, bias_of(0), ldk, ldk, ldn, 0};
+        ScopedTimer t(c, JG_KERNEL_GEMM);
+        return jg::launch_gemm_group(g, c->stream) == hipSuccess ? JG_OK : JG_E_HIP;
+    }
+
+    auto send_buf = [&](int r) { return reinterpret_cast<float*>(ws + plan->off_send + r * plan->part_bytes); };
+    auto kept_buf = [&](int r) { return reinterpret_cast<float*>(ws + plan->off_kept + r * plan->part_bytes); };
+
+    // For every rank: the weight block of the product it ships, of the product it keeps,
+    // and the rank whose shipped partial it receives.
+    const float* w_send[4];
+    const float* w_keep[4];
+    int recv_from[4];
+    if (ways == 2) {
+        // Sec. 4.1: W_r = [W_{r,0}; W_{r,1}] by rows; rank r keeps X_r W_{r,r}^T and ships
+        // X_r W_{r,1-r}^T to the other rank.
+        const int64_t half = plan->yc * plan->xc;   // floats in one N/2 x K/2 block
+        for (int r = 0; r < 2; ++r) {
+            w_keep[r] = w_sh[r] + r * half;
+            w_send[r] = w_sh[r] + (1 - r) * half;
+            recv_from[r] = 1 - r;
+        }
+    } else {
+        const float* w_in[4];   // the weight block rank r receives from kWeightFrom4[r]
+        if (d.weights == JG_WEIGHTS_COPY) {
+            jg::CopyGroup cg;
+            std::memset(&cg, 0, sizeof(cg));
+            cg.nblocks = 4;
+            cg.rows = (int)plan->wr;
+            cg.cols = (int)plan->wc;
+            for (int r = 0; r < 4; ++r) {
+                float* dst = reinterpret_cast<float*>(ws + plan->off_wrecv + r * plan->wblk_bytes);
+                cg.b[r] = {w_sh[kWeightFrom4[r]], dst, plan->wc, plan->wc};
+                w_in[r] = dst;
+            }
+            ScopedTimer t(c, JG_KERNEL_WEIGHT_COPY);
+            if (jg::launch_copy_group(cg, c->stream) != hipSuccess) return JG_E_HIP;
+        } else {
+            for (int r = 0; r < 4; ++r) w_in[r] = w_sh[kWeightFrom4[r]];
+        }
+        for (int r = 0; r < 4; ++r) {
+            w_keep[r] = kOwnIsKept4[r] ? w_sh[r] : w_in[r];
+            w_send[r] = kOwnIsKept4[r] ? w_in[r] : w_sh[r];
+            recv_from[r] = kPeer4[r];
+        }
+    }
+
+    // launch 1: the products handed to a peer, stored where the peer will read them
+    g.nprob = ways;
+    for (int r = 0; r < ways; ++r)
+        g.p[r] = {x_sh[r], w_send[r], send_buf(r), nullptr, nullptr, ldk, ldk, ldn, 0};
+    {
+        ScopedTimer t(c, JG_KERNEL_GEMM);
+        if (jg::launch_gemm_group(g, c->stream) != hipSuccess) return JG_E_HIP;
+    }
+
+    // launch 2: the kept products
+    if (d.combine == JG_COMBINE_FUSED) {
+        for (int r = 0; r < ways; ++r)
+            g.p[r] = {x_sh[r], w_keep[r], y_sh[r], send_buf(recv_from[r]), bias_of(r), ldk, ldk, ldn, ldn};
+        ScopedTimer t(c, JG_KERNEL_GEMM);
+        return jg::launch_gemm_group(g, c->stream) == hipSuccess ? JG_OK : JG_E_HIP;
+    }
+    for (int r = 0; r < ways; ++r)
+        g.p[r] = {x_sh[r], w_keep[r], kept_buf(r), nullptr, nullptr, ldk, ldk, ldn, 0};
+    {
+        ScopedTimer t(c, JG_KERNEL_GEMM);
+        if (jg::launch_gemm_group(g, c->stream) != hipSuccess) return JG_E_HIP;
+    }
+    jg::CombineGroup cb;
+    std::memset(&cb, 0, sizeof(cb));
+    cb.nblocks = ways;
+    cb.rows = (int)plan->yr;
+    cb.cols = (int)plan->yc;
+    for (int r = 0; r < ways; ++r)
+        cb.b[r] = {kept_buf(r), send_buf(recv_from[r]), bias_of(r), y_sh[r]};
+    ScopedTimer t(c, JG_KERNEL_COMBINE);
+    return jg::launch_combine_group(cb, c->stream) == hipSuccess ? JG_OK : JG_E_HIP;
+}
+
+}  // extern "C"

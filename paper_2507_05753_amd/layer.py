@@ -1,0 +1,76 @@
+"""Convenience holder for one Jigsaw linear layer's device buffers.
+
+PyTorch is used for device memory and the stream only; every computation (shard,
+forward, gather) is a call into ``libjigsaw`` through :mod:`binding`.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as jg
+
+
+class JigsawLinear:
+    """Plan + per-rank shard tensors (X_r, W_r, b_r, Y_r) + workspace on one GPU."""
+
+    def __init__(self, M: int, K: int, N: int, ways: int, bias: bool = False,
+                 combine: int = jg.JG_COMBINE_FUSED, weights: int = jg.JG_WEIGHTS_COPY,
+                 device: int = 0, ctx=None):
+        if not torch.cuda.is_available():
+            raise RuntimeError("JigsawLinear needs a GPU: the HIP library has no CPU fallback")
+        self.M, self.K, self.N, self.ways, self.bias = M, K, N, ways, bias
+        self.dev = torch.device("cuda", device)
+        self._own_ctx = ctx is None
+        self.stream = torch.cuda.current_stream(self.dev)
+        self.ctx = ctx if ctx is not None else jg.jg_init(device, self.stream.cuda_stream)
+        self.plan = jg.jg_plan_create(self.ctx, M, K, N, ways, bias, combine, weights)
+        q = lambda what, r=0: jg.jg_plan_query(self.plan, what, r)
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        self.x = [torch.empty((q(jg.JG_Q_X_ROWS, r), q(jg.JG_Q_X_COLS, r)), **f32) for r in range(ways)]
+        self.w = [torch.empty((q(jg.JG_Q_W_ROWS, r), q(jg.JG_Q_W_COLS, r)), **f32) for r in range(ways)]
+        self.y = [torch.empty((q(jg.JG_Q_Y_ROWS, r), q(jg.JG_Q_Y_COLS, r)), **f32) for r in range(ways)]
+        self.b = [torch.empty((q(jg.JG_Q_B_LEN, r),), **f32) for r in range(ways)] if bias else None
+        self.ws_bytes = q(jg.JG_Q_WORKSPACE_BYTES)
+        self.ws = torch.empty((max(self.ws_bytes, 1),), dtype=torch.uint8, device=self.dev)
+
+    # -- data movement ---------------------------------------------------------
+    def shard(self, X=None, W=None, b=None):
+        """Split global device tensors into the per-rank shards (jg_shard)."""
+        if X is not None:
+            assert X.is_cuda and X.dtype == torch.float32 and X.shape == (self.M, self.K) and X.stride(1) == 1
+            jg.jg_shard(self.plan, jg.JG_T_X, X.data_ptr(), X.stride(0), [t.data_ptr() for t in self.x])
+        if W is not None:
+            assert W.is_cuda and W.dtype == torch.float32 and W.shape == (self.N, self.K) and W.stride(1) == 1
+            jg.jg_shard(self.plan, jg.JG_T_W, W.data_ptr(), W.stride(0), [t.data_ptr() for t in self.w])
+        if b is not None:
+            assert self.bias and b.is_cuda and b.dtype == torch.float32 and b.shape == (self.N,)
+            jg.jg_shard(self.plan, jg.JG_T_B, b.data_ptr(), self.N, [t.data_ptr() for t in self.b])
+
+    def forward(self):
+        jg.jg_linear_forward(self.plan, [t.data_ptr() for t in self.x], [t.data_ptr() for t in self.w],
+                             [t.data_ptr() for t in self.b] if self.bias else None,
+                             [t.data_ptr() for t in self.y],
+                             self.ws.data_ptr() if self.ws_bytes else None, self.ws_bytes)
+
+    def gather(self, out=None):
+        if out is None:
+            out = torch.empty((self.M, self.N), dtype=torch.float32, device=self.dev)
+        jg.jg_gather(self.plan, [t.data_ptr() for t in self.y], out.data_ptr(), out.stride(0))
+        return out
+
+    def query(self, what: int, rank: int = 0) -> int:
+        return jg.jg_plan_query(self.plan, what, rank)
+
+    def close(self):
+        if self.plan:
+            jg.jg_plan_destroy(self.plan)
+            self.plan = None
+        if self._own_ctx and self.ctx:
+            jg.jg_free(self.ctx)
+            self.ctx = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()

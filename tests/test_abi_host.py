@@ -1,0 +1,139 @@
+"""Host-side checks of the C-ABI library: it loads, exports what the header declares,
+validates descriptors and does its accounting.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2507_05753_amd import binding as jg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "jigsaw.h")).read()
+    declared = set(re.findall(r"^\s*(?:const\s+char\s*\*|int|void)\s+(jg_\w+)\s*\(", header, re.M))
+    assert declared == set(jg.EXPORTS)
+    lib = ctypes.CDLL(jg.LIB_PATH)
+    for name in sorted(declared):
+        assert getattr(lib, name) is not None, name
+
+
+def test_strerror_is_total():
+    for s in range(-12, 2):
+        assert isinstance(jg.jg_strerror(s), str) and jg.jg_strerror(s)
+    assert jg.jg_strerror(jg.JG_OK) == "ok"
+    assert "gfx950" in jg.jg_strerror(jg.JG_E_ARCH)
+
+
+def status_of(**kw):
+    base = dict(M=8, K=8, N=8, ways=2)
+    base.update(kw)
+    try:
+        p = jg.jg_plan_create(None, **base)
+    except jg.JigsawError as e:
+        return e.status
+    jg.jg_plan_destroy(p)
+    return jg.JG_OK
+
+
+def test_plan_validation():
+    assert status_of() == jg.JG_OK
+    assert status_of(ways=3) == jg.JG_E_WAYS
+    assert status_of(ways=0) == jg.JG_E_WAYS
+    assert status_of(ways=8) == jg.JG_E_WAYS
+    assert status_of(M=0) == jg.JG_E_SHAPE
+    assert status_of(K=-2) == jg.JG_E_SHAPE
+    assert status_of(N=2 ** 31) == jg.JG_E_SHAPE
+    assert status_of(K=7) == jg.JG_E_SHAPE            # 2-way needs even K
+    assert status_of(N=7) == jg.JG_E_SHAPE            # ... and even N
+    assert status_of(M=7) == jg.JG_OK                 # ... but any M
+    assert status_of(M=7, ways=4) == jg.JG_E_SHAPE    # 4-way needs even M too
+    assert status_of(M=7, K=7, N=7, ways=1) == jg.JG_OK
+    assert status_of(dtype=1) == jg.JG_E_DTYPE
+    assert status_of(op=1) == jg.JG_E_DTYPE
+    assert status_of(combine=2) == jg.JG_E_DTYPE
+    assert status_of(weights=5) == jg.JG_E_DTYPE
+    lib = jg.raw()
+    out = ctypes.c_void_p()
+    assert lib.jg_plan_create(None, None, ctypes.byref(out)) == jg.JG_E_NULL
+    d = jg.jg_linear_desc(8, 8, 8, 2, 0, 0, 0, 0, 0)
+    assert lib.jg_plan_create(None, ctypes.byref(d), None) == jg.JG_E_NULL
+    jg.jg_plan_destroy(None)
+    jg.jg_free(None)
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,K,N", [(100, 100, 100), (25000, 4000, 4000), (200000, 10000, 10000), (6, 4, 2)])
+def test_accounting(ways, M, K, N):
+    p = jg.jg_plan_create(None, M, K, N, ways)
+    q = lambda what, r=0: jg.jg_plan_query(p, what, r)
+    try:
+        assert q(jg.JG_Q_FLOPS_TOTAL) == 2 * M * K * N
+        assert sum(q(jg.JG_Q_FLOPS_RANK, r) for r in range(ways)) == 2 * M * K * N
+        # zero memory redundancy (Sec. 4): the shards tile X, W and Y exactly
+        assert sum(q(jg.JG_Q_RESIDENT_BYTES_RANK, r) for r in range(ways)) == 4 * (M * K + N * K + M * N)
+        assert sum(q(jg.JG_Q_X_ROWS, r) * q(jg.JG_Q_X_COLS, r) for r in range(ways)) == M * K
+        assert sum(q(jg.JG_Q_W_ROWS, r) * q(jg.JG_Q_W_COLS, r) for r in range(ways)) == N * K
+        assert sum(q(jg.JG_Q_Y_ROWS, r) * q(jg.JG_Q_Y_COLS, r) for r in range(ways)) == M * N
+        for r in range(ways):
+            assert q(jg.JG_Q_B_LEN, r) == q(jg.JG_Q_Y_COLS, r)
+            # Y is partitioned like X (Sec. 4.1: the scheme is maintained after the product)
+            assert q(jg.JG_Q_Y_ROWS, r) == q(jg.JG_Q_X_ROWS, r)
+        if ways == 1:
+            assert q(jg.JG_Q_WORKSPACE_BYTES) == 0 and q(jg.JG_Q_EXCHANGE_BYTES_RANK) == 0
+            assert q(jg.JG_Q_HBM_BYTES_ALGO) == 4 * (M * K + N * K + M * N)
+            assert q(jg.JG_Q_GEMM_LAUNCHES) == 1
+        else:
+            assert q(jg.JG_Q_HBM_BYTES_ALGO) == 4 * (M * K + N * K + M * N) + 8 * M * N
+            assert q(jg.JG_Q_GEMM_LAUNCHES) == 2
+            # one partial per output element, plus (4-way, copy mode) one weight block per rank
+            ws = q(jg.JG_Q_WORKSPACE_BYTES)
+            need = 4 * M * N + (4 * N * K if ways == 4 else 0)
+            assert need <= ws <= need + 2 * ways * 256
+            if ways == 2:
+                assert q(jg.JG_Q_EXCHANGE_BYTES_RANK, 1) == 4 * M * N // 2
+            else:
+                assert q(jg.JG_Q_EXCHANGE_BYTES_RANK, 3) == 4 * (M * N // 4 + N * K // 4)
+        with pytest.raises(jg.JigsawError) as e:
+            q(jg.JG_Q_X_ROWS, ways)
+        assert e.value.status == jg.JG_E_WAYS
+        with pytest.raises(jg.JigsawError) as e:
+            q(99)
+        assert e.value.status == jg.JG_E_DTYPE
+    finally:
+        jg.jg_plan_destroy(p)
+
+
+def test_workspace_grows_with_options():
+    M, K, N = 64, 32, 48
+    base = jg.jg_plan_create(None, M, K, N, 4)
+    sep = jg.jg_plan_create(None, M, K, N, 4, combine=jg.JG_COMBINE_SEPARATE)
+    direct = jg.jg_plan_create(None, M, K, N, 4, weights=jg.JG_WEIGHTS_DIRECT)
+    ws = lambda p: jg.jg_plan_query(p, jg.JG_Q_WORKSPACE_BYTES)
+    assert ws(sep) == ws(base) + 4 * M * N
+    assert ws(direct) == ws(base) - 4 * N * K
+    for p in (base, sep, direct):
+        jg.jg_plan_destroy(p)
+
+
+def test_data_calls_refuse_a_plan_without_context():
+    p = jg.jg_plan_create(None, 8, 8, 8, 2)
+    lib = jg.raw()
+    arr = (ctypes.c_void_p * 2)(256, 512)
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    assert lib.jg_linear_forward(p, pp, pp, None, pp, 256, 1 << 20) == jg.JG_E_NULL
+    assert lib.jg_shard(p, jg.JG_T_X, 256, 8, pp) == jg.JG_E_NULL
+    assert lib.jg_gather(p, pp, 256, 8) == jg.JG_E_NULL
+    assert lib.jg_linear_forward(None, pp, pp, None, pp, 256, 1 << 20) == jg.JG_E_NULL
+    jg.jg_plan_destroy(p)
+
+
+def test_init_without_a_gpu_fails_cleanly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(jg.JigsawError) as e:
+        jg.jg_init(0, None)
+    assert e.value.status == jg.JG_E_HIP
