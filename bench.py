@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the Jigsaw linear-layer forward pass on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--ways 4]
+
+A *step* is one ``jg_linear_forward``: every virtual rank's two block products, the
+hand-off of partial products (and, 4-way, weight blocks) and the combine, with all
+shards already resident in HBM.  ``value`` = items/s = (M*K elements of X) / step time.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X dense FP32 matrix peak
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--ways", type=int, default=4, choices=[1, 2, 4])
+    ap.add_argument("--combine", choices=["fused", "separate"], default="fused")
+    ap.add_argument("--weights", choices=["copy", "direct"], default="copy")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+                    help="target CPU time of the oracle baseline sample (0 disables it)")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="skip the other `ways` and the streaming-kernel measurements")
+    return ap.parse_args()
+
+
+def make_inputs(cfg, dev):
+    """Global X [M,K] and W [N,K] on the device (seeded, synthetic)."""
+    import torch
+    from paper_2507_05753_amd import inputs
+    M, K, N, seed = cfg["M"], cfg["K"], cfg["N"], cfg["seed"]
+    if cfg["x_mode"] == "Z":   # Zipf ranks are drawn on the host in float64
+        X = torch.from_numpy(inputs.matrix(seed, M, K, "Z")).to(dev)
+    else:
+        X = inputs.matrix_torch(seed, M, K, "R", 0, device=dev)
+    W = inputs.matrix_torch(seed + inputs.W_STREAM, N, K, "R", inputs.W_SCALE_EXP, device=dev)
+    return X, W
+
+
+def time_forward(L, jg, steps, warmup):
+    """(seconds per step by wall clock, GEMM ms total, GEMM launches, other kernel ms per step)."""
+    import torch
+    for _ in range(warmup):
+        L.forward()
+    torch.cuda.synchronize()
+    for k in (jg.JG_KERNEL_GEMM, jg.JG_KERNEL_WEIGHT_COPY, jg.JG_KERNEL_COMBINE):
+        jg.jg_profile_read(L.ctx, k)
+    jg.jg_profile(L.ctx, True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        L.forward()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    jg.jg_profile(L.ctx, False)
+    gemm_ms, gemm_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_GEMM)
+    wc_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_WEIGHT_COPY)
+    cb_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_COMBINE)
+    return (t1 - t0) / steps, gemm_ms, gemm_n, (wc_ms + cb_ms) / steps
+
+
+def measure(cfg, ways, args, X, W, streaming=False):
+    import torch
+    from paper_2507_05753_amd import binding as jg
+    from paper_2507_05753_amd.layer import JigsawLinear
+    M, K, N = cfg["M"], cfg["K"], cfg["N"]
+    combine = jg.JG_COMBINE_FUSED if args.combine == "fused" else jg.JG_COMBINE_SEPARATE
+    weights = jg.JG_WEIGHTS_COPY if args.weights == "copy" else jg.JG_WEIGHTS_DIRECT
+    out = {}
+    with JigsawLinear(M, K, N, ways, combine=combine, weights=weights) as L:
+        L.shard(X, W)
+        sec, gemm_ms, gemm_n, other_ms = time_forward(L, jg, args.steps, args.warmup)
+        flops = L.query(jg.JG_Q_FLOPS_TOTAL)
+        launches = L.query(jg.JG_Q_GEMM_LAUNCHES)
+        algo_bytes = L.query(jg.JG_Q_HBM_BYTES_ALGO)
+        avg_launch_ms = gemm_ms / max(gemm_n, 1)
+        out = dict(
+            ms_per_step=sec * 1e3, items_per_s=M * K / sec, tflops=flops / sec / 1e12,
+            gemm_avg_launch_ms=avg_launch_ms, gemm_launches_timed=gemm_n,
+            gemm_tflops=(flops / launches) / (avg_launch_ms * 1e-3) / 1e12 if gemm_n else None,
+            other_kernels_ms_per_step=other_ms,
+            hbm_algo_gbps=algo_bytes / sec / 1e9, hbm_algo_frac=algo_bytes / sec / 1e9 / HBM_PEAK_GBPS,
+            workspace_bytes=L.ws_bytes)
+        if streaming:
+            # the HBM-bound steps around the forward: shard (X), gather (Y); bytes = read + write
+            stream = {}
+            jg.jg_profile(L.ctx, True)
+            reps = 5
+            for _ in range(reps):
+                L.shard(X=X)
+            Yg = L.gather()
+            for _ in range(reps - 1):
+                L.gather(Yg)
+            jg.jg_profile(L.ctx, False)
+            sh_ms, sh_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_SHARD)
+            ga_ms, ga_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_GATHER)
+            stream["shard_x_gbps"] = 8.0 * M * K / (sh_ms / sh_n * 1e-3) / 1e9
+            stream["gather_y_gbps"] = 8.0 * M * N / (ga_ms / ga_n * 1e-3) / 1e9
+            stream["shard_x_frac"] = stream["shard_x_gbps"] / HBM_PEAK_GBPS
+            stream["gather_y_frac"] = stream["gather_y_gbps"] / HBM_PEAK_GBPS
+            out["streaming"] = stream
+            del Yg
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline(cfg, seconds):
+    """The oracle as it stands, timed on a bounded sample of rows of the same workload."""
+    import numpy as np
+    import oracle
+    from paper_2507_05753_amd import inputs
+    M, K, N, seed = cfg["M"], cfg["K"], cfg["N"], cfg["seed"]
+    cores = min(oracle.host_threads(), 16)
+    W = inputs.matrix(seed + inputs.W_STREAM, N, K, "R", inputs.W_SCALE_EXP)
+    probe = min(M, 2 * cores)
+    Xp = inputs.matrix(seed, M, K, cfg["x_mode"], row_begin=0, row_end=probe)
+    t0 = time.perf_counter()
+    oracle.linear_rows(Xp, W, None, 0, probe, nthreads=cores)
+    rate = probe / max(time.perf_counter() - t0, 1e-9)          # rows per second
+    rows = int(min(M, max(probe, rate * seconds)))
+    rows = max(cores, rows // cores * cores)
+    rows = min(rows, M)
+    Xs = inputs.matrix(seed, M, K, cfg["x_mode"], row_begin=0, row_end=rows)
+    t0 = time.perf_counter()
+    Y = oracle.linear_rows(Xs, W, None, 0, rows, nthreads=cores)
+    dt = time.perf_counter() - t0
+    assert np.isfinite(Y).all()
+    return dict(value=rows * K / dt, unit="items/s", cores=cores, kind="oracle",
+                sample=f"rows 0..{rows - 1} of X ({rows} x {K}) against all of W ({N} x {K}), "
+                       f"{dt:.1f} s, fp64 triple loop")
+
+
+def load_traffic(workload_key):
+    """HBM bytes per GEMM launch from the committed rocprofv3 --pmc summaries, if any."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload_key)
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (all n ranks of the layer are virtual ranks on it); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    from paper_2507_05753_amd import inputs
+
+    cfg = inputs.CONFIGS[args.config]
+    M, K, N = cfg["M"], cfg["K"], cfg["N"]
+    dev = torch.device("cuda", 0)
+    X, W = make_inputs(cfg, dev)
+
+    head = measure(cfg, args.ways, args, X, W, streaming=not args.only_headline)
+    by_ways = {}
+    if not args.only_headline:
+        for w in (1, 2, 4):
+            if w != args.ways:
+                r = measure(cfg, w, args, X, W)
+                by_ways[str(w)] = {k: r[k] for k in ("ms_per_step", "items_per_s", "tflops", "gemm_tflops")}
+    del X, W
+    torch.cuda.empty_cache()
+
+    workload = f"config {args.config}: Y = X W^T, M={M} K={K} N={N}, {args.ways}-way Jigsaw, fp32"
+    achieved = head["gemm_tflops"]
+    line = {
+        "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
+        "value": head["items_per_s"],
+        "unit": "items/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": workload, "n_items": M * K, "ways": args.ways, "M": M, "K": K, "N": N,
+                   "seed": cfg["seed"], "x_values": cfg["x_mode"], "combine": args.combine,
+                   "weights": args.weights},
+        "tflops": head["tflops"],
+        "hbm_algo_gbps": head["hbm_algo_gbps"],
+        "hbm_algo_frac_of_8TBps": head["hbm_algo_frac"],
+        "roofline": {
+            "bound": "mfma", "kernel": "gemm_nt_f32",
+            "achieved": achieved, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": achieved / FP32_MFMA_PEAK_TFLOPS if achieved else None,
+            "avg_launch_ms": head["gemm_avg_launch_ms"], "launches": head["gemm_launches_timed"],
+            "traffic": load_traffic(f"config{args.config}_ways{args.ways}"),
+        },
+        "other_kernels_ms_per_step": head["other_kernels_ms_per_step"],
+    }
+    if "streaming" in head:
+        line["streaming"] = head["streaming"]
+    if by_ways:
+        line["by_ways"] = by_ways
+    if args.cpu_seconds > 0:
+        line["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

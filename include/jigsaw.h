@@ -177,6 +177,10 @@ int jg_profile_read(jg_ctx* ctx, int kernel, double* total_ms, int64_t* launches
 /* Static description of a status code (never NULL). */
 const char* jg_strerror(int status);
 
+/* Which HIP call last failed on the calling host thread, and the runtime's message
+ * for it (a thread-local string, never NULL; valid until the next failure). */
+const char* jg_last_hip_error(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -13,6 +13,8 @@ from __future__ import annotations
 import ctypes
 import os
 
+import torch  # noqa: F401  imported first so that the library binds to the HIP runtime torch loaded
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libjigsaw.so")
 
@@ -39,7 +41,8 @@ JG_T_X, JG_T_W, JG_T_B = 0, 1, 2
  JG_KERNEL_GATHER, JG_KERNEL_COUNT) = range(6)
 
 EXPORTS = ("jg_init", "jg_free", "jg_plan_create", "jg_plan_destroy", "jg_plan_query", "jg_shard",
-           "jg_linear_forward", "jg_gather", "jg_profile", "jg_profile_read", "jg_strerror")
+           "jg_linear_forward", "jg_gather", "jg_profile", "jg_profile_read", "jg_strerror",
+           "jg_last_hip_error")
 
 
 class jg_linear_desc(ctypes.Structure):
@@ -51,13 +54,18 @@ class jg_linear_desc(ctypes.Structure):
 class JigsawError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {_lib.jg_strerror(status).decode()} ({status})")
+        msg = f"{where}: {_lib.jg_strerror(status).decode()} ({status})"
+        if status == JG_E_HIP:
+            msg += f" [{_lib.jg_last_hip_error().decode()}]"
+        super().__init__(msg)
 
 
 _vp = ctypes.c_void_p
 _vpp = ctypes.POINTER(ctypes.c_void_p)
 _lib.jg_strerror.argtypes = [ctypes.c_int]
 _lib.jg_strerror.restype = ctypes.c_char_p
+_lib.jg_last_hip_error.argtypes = []
+_lib.jg_last_hip_error.restype = ctypes.c_char_p
 _lib.jg_init.argtypes = [_vpp, ctypes.c_int, _vp]
 _lib.jg_free.argtypes = [_vp]
 _lib.jg_free.restype = None
@@ -90,6 +98,10 @@ def _raise(status: int, where: str):
 
 def jg_strerror(status: int) -> str:
     return _lib.jg_strerror(status).decode()
+
+
+def jg_last_hip_error() -> str:
+    return _lib.jg_last_hip_error().decode()
 
 
 def jg_init(device: int = 0, hip_stream: int | None = None) -> int:

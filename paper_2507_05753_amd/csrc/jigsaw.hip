@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -13,6 +14,18 @@
 #include "stream_kernels.hpp"
 
 namespace {
+
+// Last failing HIP call of this host thread, for jg_last_hip_error().
+thread_local char g_hip_detail[160] = "no HIP error recorded";
+
+bool hip_ok(hipError_t e, const char* what)
+{
+    if (e == hipSuccess) return true;
+    std::snprintf(g_hip_detail, sizeof(g_hip_detail), "%s: %s (%d)", what, hipGetErrorString(e), (int)e);
+    (void)hipGetLastError();   // clear the sticky per-thread error
+    return false;
+}
+#define HIP_OK(call) hip_ok((call), #call)
 
 constexpr int kProfileMaxLaunches = 8192;
 constexpr int64_t kMaxDim = 0x7fffffff - 1024;   // every dimension fits an int with tile slack
@@ -101,6 +114,8 @@ int check_ptr_array(const float* const* arr, int n)
 
 extern "C" {
 
+const char* jg_last_hip_error(void) { return g_hip_detail; }
+
 const char* jg_strerror(int status)
 {
     switch (status) {
@@ -122,12 +137,16 @@ int jg_init(jg_ctx** out, int device, void* hip_stream)
     if (!out) return JG_E_NULL;
     *out = nullptr;
     int count = 0;
-    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return JG_E_HIP;
+    if (!HIP_OK(hipGetDeviceCount(&count))) return JG_E_HIP;
+    if (device < 0 || device >= count) {
+        std::snprintf(g_hip_detail, sizeof(g_hip_detail), "device %d out of range (%d visible)", device, count);
+        return JG_E_HIP;
+    }
     hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return JG_E_HIP;
+    if (!HIP_OK(hipGetDeviceProperties(&prop, device))) return JG_E_HIP;
     if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return JG_E_ARCH;
-    if (hipSetDevice(device) != hipSuccess) return JG_E_HIP;
-    if (jg::prepare_gemm() != hipSuccess) return JG_E_HIP;
+    if (!HIP_OK(hipSetDevice(device))) return JG_E_HIP;
+    if (!HIP_OK(jg::prepare_gemm())) return JG_E_HIP;
     jg_ctx* c = new (std::nothrow) jg_ctx();
     if (!c) return JG_E_HIP;
     c->device = device;
@@ -149,13 +168,13 @@ void jg_free(jg_ctx* ctx)
 int jg_profile(jg_ctx* ctx, int enable)
 {
     if (!ctx) return JG_E_NULL;
-    if (hipSetDevice(ctx->device) != hipSuccess) return JG_E_HIP;
+    if (!HIP_OK(hipSetDevice(ctx->device))) return JG_E_HIP;
     if (enable && ctx->pool.empty()) {
         ctx->pool.reserve(2 * kProfileMaxLaunches);
         ctx->timed.reserve(kProfileMaxLaunches);
         for (int i = 0; i < 2 * kProfileMaxLaunches; ++i) {
             hipEvent_t e;
-            if (hipEventCreate(&e) != hipSuccess) return JG_E_HIP;
+            if (!HIP_OK(hipEventCreate(&e))) return JG_E_HIP;
             ctx->pool.push_back(e);
         }
     }
@@ -167,8 +186,8 @@ int jg_profile_read(jg_ctx* ctx, int kernel, double* total_ms, int64_t* launches
 {
     if (!ctx || !total_ms || !launches) return JG_E_NULL;
     if (kernel < 0 || kernel >= JG_KERNEL_COUNT) return JG_E_DTYPE;
-    if (hipSetDevice(ctx->device) != hipSuccess) return JG_E_HIP;
-    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return JG_E_HIP;
+    if (!HIP_OK(hipSetDevice(ctx->device))) return JG_E_HIP;
+    if (!HIP_OK(hipStreamSynchronize(ctx->stream))) return JG_E_HIP;
     double sum = 0.0;
     int64_t n = 0;
     std::vector<TimedLaunch> rest;
@@ -179,7 +198,7 @@ int jg_profile_read(jg_ctx* ctx, int kernel, double* total_ms, int64_t* launches
             continue;
         }
         float ms = 0.f;
-        if (hipEventElapsedTime(&ms, t.start, t.stop) != hipSuccess) return JG_E_HIP;
+        if (!HIP_OK(hipEventElapsedTime(&ms, t.start, t.stop))) return JG_E_HIP;
         sum += ms;
         ++n;
     }
@@ -292,7 +311,7 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
     if (which != JG_T_X && which != JG_T_W && which != JG_T_B) return JG_E_DTYPE;
     jg_ctx* c = plan->ctx;
     if (!c) return JG_E_NULL;
-    if (hipSetDevice(c->device) != hipSuccess) return JG_E_HIP;
+    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
 
     jg::CopyGroup g;
     std::memset(&g, 0, sizeof(g));
@@ -318,7 +337,7 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
         }
     }
     ScopedTimer t(c, JG_KERNEL_SHARD);
-    return jg::launch_copy_group(g, c->stream) == hipSuccess ? JG_OK : JG_E_HIP;
+    return HIP_OK(jg::launch_copy_group(g, c->stream)) ? JG_OK : JG_E_HIP;
 }
 
 int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, int64_t ld)
@@ -330,7 +349,7 @@ int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, in
     if (ld < d.N) return JG_E_SHAPE;
     jg_ctx* c = plan->ctx;
     if (!c) return JG_E_NULL;
-    if (hipSetDevice(c->device) != hipSuccess) return JG_E_HIP;
+    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
 
     jg::CopyGroup g;
     std::memset(&g, 0, sizeof(g));
@@ -344,7 +363,7 @@ int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, in
         g.b[r] = {y_sh[r], global_y + rb * plan->yr * ld + cb * plan->yc, plan->yc, ld};
     }
     ScopedTimer t(c, JG_KERNEL_GATHER);
-    return jg::launch_copy_group(g, c->stream) == hipSuccess ? JG_OK : JG_E_HIP;
+    return HIP_OK(jg::launch_copy_group(g, c->stream)) ? JG_OK : JG_E_HIP;
 }
 
 int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
@@ -365,7 +384,7 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
         if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
     }
     jg_ctx* c = plan->ctx;
-    if (hipSetDevice(c->device) != hipSuccess) return JG_E_HIP;
+    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
     char* ws = static_cast<char*>(workspace);
     auto bias_of = [&](int r) -> const float* { return d.has_bias ? b_sh[r] : nullptr; };
 
@@ -381,7 +400,7 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
         g.nprob = 1;
         g.p[0] = {x_sh[0], w_sh[0], y_sh[0], nullptr, bias_of(0), ldk, ldk, ldn, 0};
         ScopedTimer t(c, JG_KERNEL_GEMM);
-        return jg::launch_gemm_group(g, c->stream) == hipSuccess ? JG_OK : JG_E_HIP;
+        return HIP_OK(jg::launch_gemm_group(g, c->stream)) ? JG_OK : JG_E_HIP;
     }
 
     auto send_buf = [&](int r) { return reinterpret_cast<float*>(ws + plan->off_send + r * plan->part_bytes); };
@@ -415,7 +434,7 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
                 w_in[r] = dst;
             }
             ScopedTimer t(c, JG_KERNEL_WEIGHT_COPY);
-            if (jg::launch_copy_group(cg, c->stream) != hipSuccess) return JG_E_HIP;
+            if (!HIP_OK(jg::launch_copy_group(cg, c->stream))) return JG_E_HIP;
         } else {
             for (int r = 0; r < 4; ++r) w_in[r] = w_sh[kWeightFrom4[r]];
         }
@@ -432,7 +451,7 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
         g.p[r] = {x_sh[r], w_send[r], send_buf(r), nullptr, nullptr, ldk, ldk, ldn, 0};
     {
         ScopedTimer t(c, JG_KERNEL_GEMM);
-        if (jg::launch_gemm_group(g, c->stream) != hipSuccess) return JG_E_HIP;
+        if (!HIP_OK(jg::launch_gemm_group(g, c->stream))) return JG_E_HIP;
     }
 
     // launch 2: the kept products
@@ -440,13 +459,13 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
         for (int r = 0; r < ways; ++r)
             g.p[r] = {x_sh[r], w_keep[r], y_sh[r], send_buf(recv_from[r]), bias_of(r), ldk, ldk, ldn, ldn};
         ScopedTimer t(c, JG_KERNEL_GEMM);
-        return jg::launch_gemm_group(g, c->stream) == hipSuccess ? JG_OK : JG_E_HIP;
+        return HIP_OK(jg::launch_gemm_group(g, c->stream)) ? JG_OK : JG_E_HIP;
     }
     for (int r = 0; r < ways; ++r)
         g.p[r] = {x_sh[r], w_keep[r], kept_buf(r), nullptr, nullptr, ldk, ldk, ldn, 0};
     {
         ScopedTimer t(c, JG_KERNEL_GEMM);
-        if (jg::launch_gemm_group(g, c->stream) != hipSuccess) return JG_E_HIP;
+        if (!HIP_OK(jg::launch_gemm_group(g, c->stream))) return JG_E_HIP;
     }
     jg::CombineGroup cb;
     std::memset(&cb, 0, sizeof(cb));
@@ -456,7 +475,7 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
     for (int r = 0; r < ways; ++r)
         cb.b[r] = {kept_buf(r), send_buf(recv_from[r]), bias_of(r), y_sh[r]};
     ScopedTimer t(c, JG_KERNEL_COMBINE);
-    return jg::launch_combine_group(cb, c->stream) == hipSuccess ? JG_OK : JG_E_HIP;
+    return HIP_OK(jg::launch_combine_group(cb, c->stream)) ? JG_OK : JG_E_HIP;
 }
 
 }  // extern "C"
