@@ -35,8 +35,10 @@ def parse():
     ap.add_argument("--weights", choices=["copy", "direct"], default="copy")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="target CPU time of the oracle baseline sample (0 disables it)")
+    ap.add_argument("--all-ways", action="store_true",
+                    help="also time the other values of `ways` (reported under by_ways)")
     ap.add_argument("--only-headline", action="store_true",
-                    help="skip the other `ways` and the streaming-kernel measurements")
+                    help="skip the streaming-kernel measurements")
     return ap.parse_args()
 
 
@@ -175,7 +177,7 @@ def main():
 
     head = measure(cfg, args.ways, args, X, W, streaming=not args.only_headline)
     by_ways = {}
-    if not args.only_headline:
+    if args.all_ways:
         for w in (1, 2, 4):
             if w != args.ways:
                 r = measure(cfg, w, args, X, W)

@@ -227,22 +227,29 @@ def gather_y(shards, ways: int) -> np.ndarray:
 # Freivalds' check: the exact product applied to a vector, at O(MK + NK) cost
 # ----------------------------------------------------------------------------
 def freivalds_reference(X, W, b, v, chunk_rows: int = 4096):
-    """(Y64 @ v, S @ 1-ish bound) without forming Y: X (W^T v) + <b, v> in double.
+    """(Y64 @ v, bound) without forming Y: X (W^T v) + <b, v> in double.
 
-    Returns ``(yv, bound)`` with ``bound[i] = sum_j S[i][j] * |v[j]|`` (the scale
-    of the tolerance for row i of the projected result).
+    ``v`` is a length-N vector or an N x nv matrix of vectors (one pass over X serves all
+    of them).  ``bound = S @ |v|`` is the scale of the tolerance for each projected row.
     """
     W64 = np.asarray(W, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
-    u = W64.T @ v
-    ua = np.abs(W64).T @ np.abs(v)
-    bv = 0.0 if b is None else float(np.asarray(b, dtype=np.float64) @ v)
-    ba = 0.0 if b is None else float(np.abs(np.asarray(b, dtype=np.float64)) @ np.abs(v))
+    single = v.ndim == 1
+    V = v.reshape(v.shape[0], -1)
+    U = W64.T @ V
+    Ua = np.abs(W64).T @ np.abs(V)
+    if b is None:
+        bv = ba = np.zeros(V.shape[1])
+    else:
+        b64 = np.asarray(b, dtype=np.float64)
+        bv, ba = b64 @ V, np.abs(b64) @ np.abs(V)
     M = X.shape[0]
-    yv = np.empty(M, dtype=np.float64)
-    bound = np.empty(M, dtype=np.float64)
+    yv = np.empty((M, V.shape[1]), dtype=np.float64)
+    bound = np.empty((M, V.shape[1]), dtype=np.float64)
     for r0 in range(0, M, chunk_rows):
         xc = np.asarray(X[r0:r0 + chunk_rows], dtype=np.float64)
-        yv[r0:r0 + chunk_rows] = xc @ u + bv
-        bound[r0:r0 + chunk_rows] = np.abs(xc) @ ua + ba
+        yv[r0:r0 + chunk_rows] = xc @ U + bv
+        bound[r0:r0 + chunk_rows] = np.abs(xc) @ Ua + ba
+    if single:
+        return yv[:, 0], bound[:, 0]
     return yv, bound

@@ -2,8 +2,11 @@
 // (shard, gather, 4-way weight-block hand-off) and the separate partial-sum combine
 // (the "+" of Eqs. (2) and (4) when it is not fused into the GEMM epilogue).
 //
-// Every kernel moves each element exactly once (one read per source, one write)
-// with 128-bit accesses when shapes and pointers allow it, 32-bit otherwise.
+// Every kernel moves each element exactly once (one read per source, one write).
+// One thread moves one 16-byte vector (or one float when shapes or pointers rule out
+// 128-bit accesses); consecutive threads walk consecutive vectors of a row, so a
+// wavefront reads and writes 1 KiB runs.  Loads and stores are non-temporal: nothing
+// copied here is read again before it has left the caches.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -13,11 +16,13 @@ namespace jg {
 
 constexpr int kMaxBlocks = 4;        // blocks (ranks) per grouped launch
 constexpr int COPY_THREADS = 256;
-constexpr int COPY_ROWS = 8;         // rows per workgroup
+constexpr int64_t kMaxUnitsPerLaunch = (int64_t)1 << 31;   // 32-bit unit index inside a launch
+
+typedef float vf4 __attribute__((ext_vector_type(4)));
 
 struct CopyBlock {
-    const float* src;   // rows x cols, leading dimension lds_
-    float* dst;         // rows x cols, leading dimension ldd
+    const float* src;   // rows x cols, leading dimension ld_src
+    float* dst;         // rows x cols, leading dimension ld_dst
     int64_t ld_src, ld_dst;
 };
 
@@ -26,38 +31,27 @@ struct CopyGroup {
     int nblocks;
     int rows, cols;     // common shape
     int vec_ok;         // cols, both leading dimensions multiples of 4 and all pointers 16-B aligned
-    int col_chunks;     // ceil(cols / (4 * COPY_THREADS))
+    uint32_t units_per_row;   // cols / 4 (vector path) or cols (scalar path)
+    uint32_t units;           // rows * units_per_row
 };
 
-// grid: x = row chunk * col_chunks + column chunk, y = block
+// grid: x = unit index / COPY_THREADS, y = block
 __global__ __launch_bounds__(COPY_THREADS) void copy2d_f32(const CopyGroup g)
 {
     const CopyBlock& B = g.b[blockIdx.y];
-    const int cchunk = blockIdx.x % g.col_chunks;
-    const int row0 = (blockIdx.x / g.col_chunks) * COPY_ROWS;
-    const int row1 = min(row0 + COPY_ROWS, g.rows);
+    const uint32_t i = blockIdx.x * (uint32_t)COPY_THREADS + threadIdx.x;
+    if (i >= g.units) return;
+    const uint32_t row = i / g.units_per_row;
+    const uint32_t c = i - row * g.units_per_row;
     if (g.vec_ok) {
-        const int c4 = cchunk * COPY_THREADS + threadIdx.x;
-        if (c4 * 4 >= g.cols) return;
-        float4 v[COPY_ROWS];
-#pragma unroll
-        for (int r = 0; r < COPY_ROWS; ++r)
-            if (row0 + r < row1)
-                v[r] = *reinterpret_cast<const float4*>(B.src + (int64_t)(row0 + r) * B.ld_src + c4 * 4);
-#pragma unroll
-        for (int r = 0; r < COPY_ROWS; ++r)
-            if (row0 + r < row1)
-                *reinterpret_cast<float4*>(B.dst + (int64_t)(row0 + r) * B.ld_dst + c4 * 4) = v[r];
+        const vf4 v = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(B.src + (int64_t)row * B.ld_src) + c);
+        __builtin_nontemporal_store(v, reinterpret_cast<vf4*>(B.dst + (int64_t)row * B.ld_dst) + c);
     } else {
-        // scalar path: the x extent of the grid was sized for 4 columns per thread
-        const int c0 = (cchunk * COPY_THREADS + threadIdx.x) * 4;
-        for (int r = row0; r < row1; ++r)
-            for (int c = c0; c < min(c0 + 4, g.cols); ++c)
-                B.dst[(int64_t)r * B.ld_dst + c] = B.src[(int64_t)r * B.ld_src + c];
+        B.dst[(int64_t)row * B.ld_dst + c] = B.src[(int64_t)row * B.ld_src + c];
     }
 }
 
-inline hipError_t launch_copy_group(CopyGroup& g, hipStream_t stream)
+inline hipError_t launch_copy_group(CopyGroup g, hipStream_t stream)
 {
     if (g.rows <= 0 || g.cols <= 0 || g.nblocks <= 0) return hipSuccess;
     int vec = (g.cols & 3) == 0;
@@ -67,16 +61,27 @@ inline hipError_t launch_copy_group(CopyGroup& g, hipStream_t stream)
             vec = 0;
     }
     g.vec_ok = vec;
-    const int per_block_cols = COPY_THREADS * 4;
-    g.col_chunks = (g.cols + per_block_cols - 1) / per_block_cols;
-    const int64_t nx = (int64_t)g.col_chunks * ((g.rows + COPY_ROWS - 1) / COPY_ROWS);
-    if (nx > 0x7fffffff) return hipErrorInvalidValue;
-    dim3 grid((unsigned)nx, g.nblocks, 1);
-    hipLaunchKernelGGL(copy2d_f32, grid, dim3(COPY_THREADS), 0, stream, g);
-    return hipGetLastError();
+    g.units_per_row = (uint32_t)(vec ? g.cols / 4 : g.cols);
+    // a launch indexes its units with 32 bits: very tall blocks go in several row ranges
+    const int64_t max_rows = kMaxUnitsPerLaunch / g.units_per_row;
+    const int total_rows = g.rows;
+    for (int64_t r0 = 0; r0 < total_rows; r0 += max_rows) {
+        CopyGroup part = g;
+        part.rows = (int)((total_rows - r0 < max_rows) ? total_rows - r0 : max_rows);
+        for (int i = 0; i < g.nblocks; ++i) {
+            part.b[i].src = g.b[i].src + r0 * g.b[i].ld_src;
+            part.b[i].dst = g.b[i].dst + r0 * g.b[i].ld_dst;
+        }
+        part.units = (uint32_t)((int64_t)part.rows * part.units_per_row);
+        dim3 grid((part.units + COPY_THREADS - 1) / COPY_THREADS, g.nblocks, 1);
+        hipLaunchKernelGGL(copy2d_f32, grid, dim3(COPY_THREADS), 0, stream, part);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
-// ---- separate combine: y = kept + received (+ bias), dense n_rows x n_cols each ----
+// ---- separate combine: y = kept + received (+ bias), dense rows x cols each ----
 struct CombineBlock {
     const float* kept;
     const float* recv;
@@ -87,52 +92,32 @@ struct CombineBlock {
 struct CombineGroup {
     CombineBlock b[kMaxBlocks];
     int nblocks;
-    int rows, cols;      // all four arrays dense (leading dimension = cols)
+    int rows, cols;      // all arrays dense (leading dimension = cols)
     int vec_ok;
-    int col_chunks;
+    uint32_t units_per_row;
+    uint32_t units;
 };
 
 __global__ __launch_bounds__(COPY_THREADS) void combine_f32(const CombineGroup g)
 {
     const CombineBlock& B = g.b[blockIdx.y];
-    const int cchunk = blockIdx.x % g.col_chunks;
-    const int row0 = (blockIdx.x / g.col_chunks) * COPY_ROWS;
-    const int row1 = min(row0 + COPY_ROWS, g.rows);
+    const uint32_t i = blockIdx.x * (uint32_t)COPY_THREADS + threadIdx.x;
+    if (i >= g.units) return;
+    const uint32_t c = i % g.units_per_row;
     if (g.vec_ok) {
-        const int c4 = cchunk * COPY_THREADS + threadIdx.x;
-        if (c4 * 4 >= g.cols) return;
-        float4 bj = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (B.bias) bj = *reinterpret_cast<const float4*>(B.bias + c4 * 4);
-        float4 a[COPY_ROWS], b[COPY_ROWS];
-#pragma unroll
-        for (int r = 0; r < COPY_ROWS; ++r)
-            if (row0 + r < row1) {
-                const int64_t o = (int64_t)(row0 + r) * g.cols + c4 * 4;
-                a[r] = *reinterpret_cast<const float4*>(B.kept + o);
-                b[r] = *reinterpret_cast<const float4*>(B.recv + o);
-            }
-#pragma unroll
-        for (int r = 0; r < COPY_ROWS; ++r)
-            if (row0 + r < row1) {
-                const int64_t o = (int64_t)(row0 + r) * g.cols + c4 * 4;
-                float4 y;
-                y.x = a[r].x + b[r].x + bj.x;
-                y.y = a[r].y + b[r].y + bj.y;
-                y.z = a[r].z + b[r].z + bj.z;
-                y.w = a[r].w + b[r].w + bj.w;
-                *reinterpret_cast<float4*>(B.y + o) = y;
-            }
+        const vf4 a = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(B.kept) + i);
+        const vf4 r = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(B.recv) + i);
+        vf4 y = a + r;   // same order as the fused epilogue: (kept + received) + bias
+        if (B.bias) y += reinterpret_cast<const vf4*>(B.bias)[c];
+        __builtin_nontemporal_store(y, reinterpret_cast<vf4*>(B.y) + i);
     } else {
-        const int c0 = (cchunk * COPY_THREADS + threadIdx.x) * 4;
-        for (int r = row0; r < row1; ++r)
-            for (int c = c0; c < min(c0 + 4, g.cols); ++c) {
-                const int64_t o = (int64_t)r * g.cols + c;
-                B.y[o] = B.kept[o] + B.recv[o] + (B.bias ? B.bias[c] : 0.f);
-            }
+        float y = B.kept[i] + B.recv[i];
+        if (B.bias) y += B.bias[c];
+        B.y[i] = y;
     }
 }
 
-inline hipError_t launch_combine_group(CombineGroup& g, hipStream_t stream)
+inline hipError_t launch_combine_group(CombineGroup g, hipStream_t stream)
 {
     if (g.rows <= 0 || g.cols <= 0 || g.nblocks <= 0) return hipSuccess;
     int vec = (g.cols & 3) == 0;
@@ -142,13 +127,26 @@ inline hipError_t launch_combine_group(CombineGroup& g, hipStream_t stream)
             vec = 0;
     }
     g.vec_ok = vec;
-    const int per_block_cols = COPY_THREADS * 4;
-    g.col_chunks = (g.cols + per_block_cols - 1) / per_block_cols;
-    const int64_t nx = (int64_t)g.col_chunks * ((g.rows + COPY_ROWS - 1) / COPY_ROWS);
-    if (nx > 0x7fffffff) return hipErrorInvalidValue;
-    dim3 grid((unsigned)nx, g.nblocks, 1);
-    hipLaunchKernelGGL(combine_f32, grid, dim3(COPY_THREADS), 0, stream, g);
-    return hipGetLastError();
+    g.units_per_row = (uint32_t)(vec ? g.cols / 4 : g.cols);
+    const int unit_floats = vec ? 4 : 1;
+    const int64_t max_rows = kMaxUnitsPerLaunch / g.units_per_row;
+    const int total_rows = g.rows;
+    for (int64_t r0 = 0; r0 < total_rows; r0 += max_rows) {
+        CombineGroup part = g;
+        part.rows = (int)((total_rows - r0 < max_rows) ? total_rows - r0 : max_rows);
+        const int64_t off = r0 * g.units_per_row * unit_floats;
+        for (int i = 0; i < g.nblocks; ++i) {
+            part.b[i].kept = g.b[i].kept + off;
+            part.b[i].recv = g.b[i].recv + off;
+            part.b[i].y = g.b[i].y + off;
+        }
+        part.units = (uint32_t)((int64_t)part.rows * part.units_per_row);
+        dim3 grid((part.units + COPY_THREADS - 1) / COPY_THREADS, g.nblocks, 1);
+        hipLaunchKernelGGL(combine_f32, grid, dim3(COPY_THREADS), 0, stream, part);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace jg

@@ -1,0 +1,137 @@
+"""GPU parity at the full benchmark sizes (configs 3, 4, 5), in the launch configuration
+``bench.py`` times.  The full double-precision product is too slow there, so the GPU result
+is checked by
+
+* Freivalds' projection: for seeded +-1 vectors v, (Y_gpu v) against X (W^T v) computed in
+  double, row by row, within 1e-6 * (S |v|) - every output element takes part;
+* sampled entries the oracle computes one by one: a seeded random sample plus every entry of
+  the first / last / block-boundary rows and columns, each within 1e-6 * S.
+
+Configs 1 and 2 are compared in full in test_gpu_parity.py.
+"""
+import os
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2507_05753_amd import inputs
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-6
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def note(capsys, msg):
+    """Progress line that reaches the terminal (and a log file) even under output capture."""
+    line = f"[{time.strftime('%H:%M:%S')}] {msg}"
+    with capsys.disabled():
+        print(line, flush=True)
+    try:
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "test_progress.log"), "a") as f:
+            f.write(line + "\n")
+    except OSError:
+        pass
+
+
+def pm1(seed, n, cols):
+    bits = inputs.keys(seed, np.arange(n * cols, dtype=np.uint64)) >> np.uint64(63)
+    return np.where(bits.reshape(n, cols) == 1, 1.0, -1.0)
+
+
+def project(Y, V, chunk=8192):
+    out = np.empty((Y.shape[0], V.shape[1]))
+    for r0 in range(0, Y.shape[0], chunk):
+        out[r0:r0 + chunk] = Y[r0:r0 + chunk].astype(np.float64) @ V
+    return out
+
+
+def check_entries(Y, X, W, ii, jj, what):
+    v, s = oracle.entries(X, W, ii, jj)
+    err = np.abs(Y[ii, jj].astype(np.float64) - v)
+    bad = err > TOL * s
+    assert not bad.any(), f"{what}: {bad.sum()} entries off, worst err/S = {(err / s).max():.3e}"
+    return float((err / s).max())
+
+
+def boundary_and_sample(M, N, seed, n_rows, n_cols_per_row):
+    """Index lists: a random sample plus all entries of the edge / block-boundary rows and columns."""
+    k = inputs.keys(seed, np.arange(n_rows + n_rows * n_cols_per_row, dtype=np.uint64))
+    rows = (k[:n_rows] % np.uint64(M)).astype(np.int64)
+    cols = (k[n_rows:] % np.uint64(N)).astype(np.int64).reshape(n_rows, n_cols_per_row)
+    ii = [np.repeat(rows, n_cols_per_row)]
+    jj = [cols.reshape(-1)]
+    for r in (0, M // 2 - 1, M // 2, M - 1):
+        ii.append(np.full(N, r, np.int64)); jj.append(np.arange(N, dtype=np.int64))
+    for c in (0, N // 2 - 1, N // 2, N - 1):
+        ii.append(np.arange(M, dtype=np.int64)); jj.append(np.full(M, c, np.int64))
+    return np.concatenate(ii), np.concatenate(jj)
+
+
+def run_config(capsys, cfg_id, X_host, X_dev, W_host, n_rows, n_cols_per_row):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    cfg = inputs.CONFIGS[cfg_id]
+    M, K, N = cfg["M"], cfg["K"], cfg["N"]
+    W_dev = torch.from_numpy(W_host).cuda()
+    V = pm1(1000 + cfg_id, N, 3)
+    t0 = time.time()
+    yv, bound = oracle.freivalds_reference(X_host, W_host, None, V)
+    note(capsys, f"config {cfg_id}: Freivalds reference done in {time.time() - t0:.1f} s")
+    ii, jj = boundary_and_sample(M, N, 2000 + cfg_id, n_rows, n_cols_per_row)
+    for ways in (1, 2, 4):
+        with JigsawLinear(M, K, N, ways) as L:
+            L.ws.fill_(0xFF)   # NaN pattern: stale workspace contents must not matter
+            L.shard(X_dev, W_dev)
+            L.forward()
+            Yd = L.gather()
+            torch.cuda.synchronize()
+            Y = Yd.cpu().numpy()
+            del Yd
+        torch.cuda.empty_cache()
+        assert np.isfinite(Y).all()
+        got = project(Y, V)
+        err = np.abs(got - yv)
+        assert np.all(err <= TOL * bound), f"ways={ways}: Freivalds worst err/bound = {(err / bound).max():.3e}"
+        worst = check_entries(Y, X_host, W_host, ii, jj, f"config {cfg_id} ways={ways}")
+        note(capsys, f"config {cfg_id} ways={ways}: Freivalds max err/bound {(err / bound).max():.2e}, "
+                     f"{ii.size} entries max err/S {worst:.2e}")
+        del Y
+
+
+@pytest.mark.timeout(300)
+def test_config_3_uniform_keys(capsys):
+    cfg = inputs.CONFIGS[3]
+    X = inputs.matrix(cfg["seed"], cfg["M"], cfg["K"], "R")
+    W = inputs.matrix(cfg["seed"] + inputs.W_STREAM, cfg["N"], cfg["K"], "R", inputs.W_SCALE_EXP)
+    # the bench generates X on the device: same bits
+    Xd = inputs.matrix_torch(cfg["seed"], cfg["M"], cfg["K"], "R", device="cuda")
+    assert torch.equal(Xd[::997].cpu(), torch.from_numpy(X[::997]))
+    run_config(capsys, 3, X, Xd, W, n_rows=4000, n_cols_per_row=250)
+
+
+@pytest.mark.timeout(300)
+def test_config_4_zipf_values(capsys):
+    cfg = inputs.CONFIGS[4]
+    X = inputs.matrix(cfg["seed"], cfg["M"], cfg["K"], "Z")
+    W = inputs.matrix(cfg["seed"] + inputs.W_STREAM, cfg["N"], cfg["K"], "R", inputs.W_SCALE_EXP)
+    _, counts = np.unique(X[:200], return_counts=True)
+    assert counts.max() / X[:200].size > 0.05          # heavy duplicates are really there
+    run_config(capsys, 4, X, torch.from_numpy(X).cuda(), W, n_rows=4000, n_cols_per_row=250)
+
+
+@pytest.mark.timeout(900)
+def test_config_5_largest_instance(capsys):
+    cfg = inputs.CONFIGS[5]
+    M, K, N, seed = cfg["M"], cfg["K"], cfg["N"], cfg["seed"]
+    t0 = time.time()
+    Xd = inputs.matrix_torch(seed, M, K, "R", device="cuda")
+    torch.cuda.synchronize()
+    X = Xd.cpu().numpy()
+    note(capsys, f"config 5: X generated on the device and copied back in {time.time() - t0:.1f} s")
+    rows = [0, 1, M // 2, M - 1, 123457]
+    assert np.array_equal(X[rows], inputs.matrix_rows(seed, K, rows, "R"))   # host generator agrees
+    W = inputs.matrix(seed + inputs.W_STREAM, N, K, "R", inputs.W_SCALE_EXP)
+    run_config(capsys, 5, X, Xd, W, n_rows=2000, n_cols_per_row=250)

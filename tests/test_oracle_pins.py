@@ -277,3 +277,7 @@ def test_freivalds_reference_is_the_projected_product():
     S = oracle.magnitude(X, W, b)
     assert np.all(np.abs(yv - Y @ v) <= 1e-13 * bound)
     assert np.allclose(bound, S @ np.abs(v), rtol=1e-13, atol=0)
+    V = np.stack([v, -v, np.ones(N)], axis=1)
+    yV, bV = oracle.freivalds_reference(X, W, b, V)
+    assert yV.shape == (M, 3) and np.all(np.abs(yV - Y @ V) <= 1e-13 * bV)
+    assert np.array_equal(yV[:, 0], yv) and np.array_equal(bV[:, 0], bound)
