@@ -280,4 +280,4 @@ def test_freivalds_reference_is_the_projected_product():
     V = np.stack([v, -v, np.ones(N)], axis=1)
     yV, bV = oracle.freivalds_reference(X, W, b, V)
     assert yV.shape == (M, 3) and np.all(np.abs(yV - Y @ V) <= 1e-13 * bV)
-    assert np.array_equal(yV[:, 0], yv) and np.array_equal(bV[:, 0], bound)
+    assert np.allclose(yV[:, 0], yv, rtol=0, atol=1e-13) and np.allclose(bV[:, 0], bound, rtol=1e-13, atol=0)
