@@ -19,8 +19,9 @@
 // each wave-level load writes 1 KiB of LDS = 8 rows x 128 B, lane l filling 16-byte
 // slot l.  Rows are not padded; instead the lane chooses WHICH 16-byte chunk of its
 // row it fetches, chunk = slot ^ ((row >> 1) & 7), so that the later 128-bit LDS
-// reads of 16 consecutive rows at one k-chunk fall into 16 different slots.  A
-// ragged last slab (K % 32 != 0), and every slab of the GUARDED variant (unaligned
+// reads of 16 consecutive rows at one k-chunk fall into 16 different slots.  Chunks
+// past column K are fetched from outside the buffer and arrive as zeros.  A last slab
+// whose K is not a multiple of 4, and every slab of the GUARDED variant (unaligned
 // rows), goes through registers with per-element bounds checks and is written to
 // the same swizzled positions.
 //
@@ -32,6 +33,8 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 namespace jg {
 
@@ -65,7 +68,8 @@ struct GemmGroup {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void lds_void;
 constexpr int kBufferRsrcFlags = 0x00020000;   // raw 32-bit-element buffer descriptor, gfx9 family
-constexpr int kMaxDirectLd = 1 << 21;          // keeps 128 rows * ld * 4 B inside a 32-bit offset
+constexpr int kMaxDirectLd = 1 << 21;          // keeps a tile's 128 rows * ld * 4 B below 2^30
+constexpr int kOutOfBuffer = 0x7FFFFFF0;       // byte offset beyond any such tile: reads as zero
 
 // s_waitcnt that waits only for the vector-memory counter to drop to n (n < 64)
 #define JG_WAIT_VMCNT(n) \
@@ -144,19 +148,32 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_f32(const GemmGroup g)
     const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float*>(P.B + (int64_t)n0 * P.ldb), 0, (int)b_bytes, kBufferRsrcFlags);
 
-    auto load_direct = [&](int kt, float* sA) {   // full slab, aligned rows; asynchronous
+    // Asynchronous slab load (aligned rows).  A 16-byte chunk that starts at or beyond column K
+    // is redirected to an offset outside the buffer, which the hardware answers with zeros:
+    // the ragged last slab of a K that is a multiple of 4 needs no special path.
+    auto load_direct_impl = [&](int kt, float* sA, auto ragged) {
         float* sB = sA + BM * ROW_FLOATS;
         const int soff = kt * BK * 4;
+        const int k_left = K - kt * BK;                 // valid columns of this slab
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int woff = (p * 32 + wave * 8) * ROW_FLOATS;   // wave-uniform LDS offset
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_void*)(sA + woff), 16, a_voff[p], soff, 0, 0);
+            const bool in = !decltype(ragged)::value || src_chunk[p] * 4 < k_left;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_void*)(sA + woff), 16,
+                                                     in ? a_voff[p] : kOutOfBuffer, soff, 0, 0);
         }
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int woff = (p * 32 + wave * 8) * ROW_FLOATS;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_void*)(sB + woff), 16, b_voff[p], soff, 0, 0);
+            const bool in = !decltype(ragged)::value || src_chunk[p] * 4 < k_left;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_void*)(sB + woff), 16,
+                                                     in ? b_voff[p] : kOutOfBuffer, soff, 0, 0);
         }
+    };
+    const int kt_ragged = (K % BK) ? K / BK : -1;       // the slab that needs the zero fill, if any
+    auto load_direct = [&](int kt, float* sA) {
+        if (kt == kt_ragged) load_direct_impl(kt, sA, std::true_type{});
+        else load_direct_impl(kt, sA, std::false_type{});
     };
     auto load_guarded_slab = [&](int kt, float* sA) {   // any slab, any alignment; synchronous
         float* sB = sA + BM * ROW_FLOATS;
@@ -173,7 +190,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_f32(const GemmGroup g)
             *reinterpret_cast<float4*>(sB + (p * 32 + lrow) * ROW_FLOATS + slot * 4) = rb[p];
     };
 
-    const int nfull = DIRECT ? K / BK : 0;        // slabs that take the direct path
+    // slabs that take the direct path: all of them when K is a multiple of 4, else the full ones
+    const int nfull = !DIRECT ? 0 : (K % 4 == 0) ? (K + BK - 1) / BK : K / BK;
     const int nkt = (K + BK - 1) / BK;
 
     // ---- MFMA operand addressing -------------------------------------------
@@ -274,22 +292,62 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_f32(const GemmGroup g)
     }
 
     // ---- epilogue: C = acc (+ addend) (+ bias) -----------------------------
-    // accumulator register v of lane (lr, lk) holds row 8 (v / 4) + 4 lk + v % 4, column lr
+    // accumulator register v of lane (lr, lk) holds row 8 (v / 4) + 4 lk + v % 4, column lr of
+    // its 32 x 32 block: one store instruction writes two 128-byte row segments.
+    const float* __restrict__ addend = P.addend;
+    const float* __restrict__ bias = P.bias;
+    float* __restrict__ C = P.C;
+    const int ldc = P.ldc, ldadd = P.ldadd;
+    const int row_base = m0 + wm * 64 + 4 * lk;     // + i * 32 + 8 (v / 4) + v % 4
+    const int col_base = n0 + wn * 64 + lr;         // + j * 32
+    if (m0 + BM <= M && n0 + BN <= N) {
+        // interior tile: no bounds checks; all loads of the received partial are issued
+        // before the first of them is needed
+        float* c_lane = C + (int64_t)row_base * ldc + col_base;
+        if (addend) {
+            const float* a_lane = addend + (int64_t)row_base * ldadd + col_base;
+            float r[2][2][16];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        r[i][j][v] = a_lane[(int64_t)(i * 32 + 8 * (v >> 2) + (v & 3)) * ldadd + j * 32];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[i][j][v] += r[i][j][v];
+        }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const int col = n0 + wn * 64 + j * 32 + lr;
-            if (col >= N) continue;
-            const float bj = P.bias ? P.bias[col] : 0.f;
+            const float bj = bias ? bias[col_base + j * 32] : 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-                if (row < M) {
-                    float y = acc[i][j][v];
-                    if (P.addend) y += P.addend[(int64_t)row * P.ldadd + col];
-                    y += bj;
-                    P.C[(int64_t)row * P.ldc + col] = y;
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    c_lane[(int64_t)(i * 32 + 8 * (v >> 2) + (v & 3)) * ldc + j * 32] = acc[i][j][v] + bj;
+        }
+    } else {
+        // edge tile: every element checked against M and N
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int col = col_base + j * 32;
+                if (col >= N) continue;
+                const float bj = bias ? bias[col] : 0.f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = row_base + i * 32 + 8 * (v >> 2) + (v & 3);
+                    if (row < M) {
+                        float y = acc[i][j][v];
+                        if (addend) y += addend[(int64_t)row * ldadd + col];
+                        y += bj;
+                        C[(int64_t)row * ldc + col] = y;
+                    }
                 }
             }
         }
