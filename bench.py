@@ -56,7 +56,7 @@ def make_inputs(cfg, dev):
 
 
 def time_forward(L, jg, steps, warmup):
-    """(seconds per step by wall clock, GEMM ms total, GEMM launches, other kernel ms per step)."""
+    """(seconds per step by wall clock, GEMM ms total, GEMM launches, weight-copy and combine ms per step)."""
     import torch
     for _ in range(warmup):
         L.forward()
@@ -74,7 +74,7 @@ def time_forward(L, jg, steps, warmup):
     gemm_ms, gemm_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_GEMM)
     wc_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_WEIGHT_COPY)
     cb_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_COMBINE)
-    return (t1 - t0) / steps, gemm_ms, gemm_n, (wc_ms + cb_ms) / steps
+    return (t1 - t0) / steps, gemm_ms, gemm_n, wc_ms / steps, cb_ms / steps
 
 
 def measure(cfg, ways, args, X, W, streaming=False):
@@ -87,7 +87,8 @@ def measure(cfg, ways, args, X, W, streaming=False):
     out = {}
     with JigsawLinear(M, K, N, ways, combine=combine, weights=weights) as L:
         L.shard(X, W)
-        sec, gemm_ms, gemm_n, other_ms = time_forward(L, jg, args.steps, args.warmup)
+        sec, gemm_ms, gemm_n, wcopy_ms, comb_ms = time_forward(L, jg, args.steps, args.warmup)
+        other_ms = wcopy_ms + comb_ms
         flops = L.query(jg.JG_Q_FLOPS_TOTAL)
         launches = L.query(jg.JG_Q_GEMM_LAUNCHES)
         algo_bytes = L.query(jg.JG_Q_HBM_BYTES_ALGO)
@@ -99,6 +100,8 @@ def measure(cfg, ways, args, X, W, streaming=False):
             other_kernels_ms_per_step=other_ms,
             hbm_algo_gbps=algo_bytes / sec / 1e9, hbm_algo_frac=algo_bytes / sec / 1e9 / HBM_PEAK_GBPS,
             workspace_bytes=L.ws_bytes)
+        if comb_ms > 0:   # separate combine: two reads and one write per output element
+            out["combine_gbps"] = 12.0 * M * N / (comb_ms * 1e-3) / 1e9
         if streaming:
             # the HBM-bound steps around the forward: shard (X), gather (Y); bytes = read + write
             stream = {}
@@ -118,6 +121,23 @@ def measure(cfg, ways, args, X, W, streaming=False):
             stream["gather_y_frac"] = stream["gather_y_gbps"] / HBM_PEAK_GBPS
             out["streaming"] = stream
             del Yg
+    if streaming and ways > 1:
+        # One rank's share at its real shape: its two block products, alone on the GPU
+        # (what one GPU of an n-GPU node would run per layer, exchange excluded).
+        Mr, Kr, Nr = (M, K // 2, N // 2) if ways == 2 else (M // 2, K // 2, N // 2)
+        with JigsawLinear(Mr, Kr, Nr, 1) as R:
+            R.shard(X[:Mr, :Kr], W[:Nr, :Kr])
+            for _ in range(2 * args.warmup):
+                R.forward()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                R.forward()
+                R.forward()
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / args.steps
+            out["one_rank_share"] = dict(ms=dt * 1e3, tflops=2 * R.query(jg.JG_Q_FLOPS_TOTAL) / dt / 1e12,
+                                         shape=f"2 x ([{Mr} x {Kr}] . [{Nr} x {Kr}]^T)")
     torch.cuda.empty_cache()
     return out
 
@@ -207,7 +227,7 @@ def main():
         "hbm_algo_gbps": head["hbm_algo_gbps"],
         "hbm_algo_frac_of_8TBps": head["hbm_algo_frac"],
         "roofline": {
-            "bound": "mfma", "kernel": "gemm_nt_f32",
+            "bound": "mfma", "kernel": "jg::gemm_nt_f32<2, true>",
             "achieved": achieved, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": achieved / FP32_MFMA_PEAK_TFLOPS if achieved else None,
             "avg_launch_ms": head["gemm_avg_launch_ms"], "launches": head["gemm_launches_timed"],
@@ -217,6 +237,11 @@ def main():
     }
     if "streaming" in head:
         line["streaming"] = head["streaming"]
+    if "one_rank_share" in head:
+        line["one_rank_share"] = head["one_rank_share"]
+    if "combine_gbps" in head:
+        line.setdefault("streaming", {})["combine_gbps"] = head["combine_gbps"]
+        line["streaming"]["combine_frac"] = head["combine_gbps"] / HBM_PEAK_GBPS
     if by_ways:
         line["by_ways"] = by_ways
     if args.cpu_seconds > 0:

@@ -316,6 +316,7 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
     jg::CopyGroup g;
     std::memset(&g, 0, sizeof(g));
     g.nblocks = d.ways;
+    g.nontemporal = which == JG_T_X;   // activations are streamed once; weights and bias are re-read soon
     if (which == JG_T_B) {
         g.rows = 1;
         g.cols = (int)plan->yc;
@@ -354,6 +355,7 @@ int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, in
     jg::CopyGroup g;
     std::memset(&g, 0, sizeof(g));
     g.nblocks = d.ways;
+    g.nontemporal = 1;
     g.rows = (int)plan->yr;
     g.cols = (int)plan->yc;
     for (int r = 0; r < d.ways; ++r) {

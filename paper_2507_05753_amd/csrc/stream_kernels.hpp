@@ -5,8 +5,10 @@
 // Every kernel moves each element exactly once (one read per source, one write).
 // One thread moves one 16-byte vector (or one float when shapes or pointers rule out
 // 128-bit accesses); consecutive threads walk consecutive vectors of a row, so a
-// wavefront reads and writes 1 KiB runs.  Loads and stores are non-temporal: nothing
-// copied here is read again before it has left the caches.
+// wavefront reads and writes 1 KiB runs.  Large single-use tensors (activations,
+// outputs, partial products) move with non-temporal loads and stores so that they do
+// not displace what the GEMM re-reads; small tensors the GEMM is about to read
+// (weight blocks, bias) use ordinary cached accesses.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -31,11 +33,13 @@ struct CopyGroup {
     int nblocks;
     int rows, cols;     // common shape
     int vec_ok;         // cols, both leading dimensions multiples of 4 and all pointers 16-B aligned
+    int nontemporal;    // 1: single-use data, bypass-style accesses; 0: cached accesses
     uint32_t units_per_row;   // cols / 4 (vector path) or cols (scalar path)
     uint32_t units;           // rows * units_per_row
 };
 
 // grid: x = unit index / COPY_THREADS, y = block
+template <bool VEC, bool NT>
 __global__ __launch_bounds__(COPY_THREADS) void copy2d_f32(const CopyGroup g)
 {
     const CopyBlock& B = g.b[blockIdx.y];
@@ -43,9 +47,11 @@ __global__ __launch_bounds__(COPY_THREADS) void copy2d_f32(const CopyGroup g)
     if (i >= g.units) return;
     const uint32_t row = i / g.units_per_row;
     const uint32_t c = i - row * g.units_per_row;
-    if (g.vec_ok) {
-        const vf4 v = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(B.src + (int64_t)row * B.ld_src) + c);
-        __builtin_nontemporal_store(v, reinterpret_cast<vf4*>(B.dst + (int64_t)row * B.ld_dst) + c);
+    if (VEC) {
+        const vf4* src = reinterpret_cast<const vf4*>(B.src + (int64_t)row * B.ld_src) + c;
+        vf4* dst = reinterpret_cast<vf4*>(B.dst + (int64_t)row * B.ld_dst) + c;
+        if (NT) __builtin_nontemporal_store(__builtin_nontemporal_load(src), dst);
+        else *dst = *src;
     } else {
         B.dst[(int64_t)row * B.ld_dst + c] = B.src[(int64_t)row * B.ld_src + c];
     }
@@ -74,7 +80,12 @@ inline hipError_t launch_copy_group(CopyGroup g, hipStream_t stream)
         }
         part.units = (uint32_t)((int64_t)part.rows * part.units_per_row);
         dim3 grid((part.units + COPY_THREADS - 1) / COPY_THREADS, g.nblocks, 1);
-        hipLaunchKernelGGL(copy2d_f32, grid, dim3(COPY_THREADS), 0, stream, part);
+        if (vec && g.nontemporal)
+            hipLaunchKernelGGL((copy2d_f32<true, true>), grid, dim3(COPY_THREADS), 0, stream, part);
+        else if (vec)
+            hipLaunchKernelGGL((copy2d_f32<true, false>), grid, dim3(COPY_THREADS), 0, stream, part);
+        else
+            hipLaunchKernelGGL((copy2d_f32<false, false>), grid, dim3(COPY_THREADS), 0, stream, part);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
