@@ -72,8 +72,8 @@ typedef struct jg_linear_desc {
     int32_t dtype;       /* JG_F32                                                      */
     int32_t has_bias;    /* 0 / 1: b_r (the slice of b matching Y_r's columns) is added
                             once, by the rank that owns the output block                */
-    int32_t combine;     /* JG_COMBINE_FUSED: the local-product GEMM reads the received
-                            partial in its epilogue.  JG_COMBINE_SEPARATE: the local
+    int32_t combine;     /* JG_COMBINE_FUSED: the kept-product GEMM starts its accumulators
+                            from the received partial.  JG_COMBINE_SEPARATE: the kept
                             product is written out and a streaming kernel adds the two
                             partials (for measurement).                                 */
     int32_t weights;     /* 4-way only.  JG_WEIGHTS_COPY: the weight block a rank needs
@@ -145,8 +145,8 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
  *   (ways = 4, JG_WEIGHTS_COPY) copy each rank's incoming weight block;
  *   launch 1: every rank's product that is handed to a peer, stored into the
  *             peer-visible partial buffer in the workspace;
- *   launch 2: every rank's kept product, whose epilogue adds the received partial
- *             and the bias and writes Y_r (JG_COMBINE_FUSED), or the kept product
+ *   launch 2: every rank's kept product, accumulated on top of the received partial,
+ *             plus the bias, written to Y_r (JG_COMBINE_FUSED); or the kept product
  *             followed by a separate combine kernel (JG_COMBINE_SEPARATE).
  * ways = 1 is a single GEMM with the bias in its epilogue and needs no workspace.
  * x_sh, w_sh, y_sh: host arrays of `ways` device pointers (shapes: JG_Q_*_ROWS/COLS);

@@ -146,7 +146,6 @@ int jg_init(jg_ctx** out, int device, void* hip_stream)
     if (!HIP_OK(hipGetDeviceProperties(&prop, device))) return JG_E_HIP;
     if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return JG_E_ARCH;
     if (!HIP_OK(hipSetDevice(device))) return JG_E_HIP;
-    if (!HIP_OK(jg::prepare_gemm())) return JG_E_HIP;
     jg_ctx* c = new (std::nothrow) jg_ctx();
     if (!c) return JG_E_HIP;
     c->device = device;
