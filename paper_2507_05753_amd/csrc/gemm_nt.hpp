@@ -50,6 +50,7 @@ constexpr int STAGE_FLOATS = (BM + BN) * ROW_FLOATS;    // one K slab of A and B
 constexpr int GEMM_THREADS = 256;
 constexpr int kNumXcd = 8;
 constexpr int kBandRows = 8;                            // row-tiles per band
+constexpr int kFlushSlabs = 32;                         // K extent of one first-level accumulation = 1024
 
 struct GemmProblem {
     const float* A;       // M x K, leading dimension lda
@@ -145,6 +146,23 @@ __device__ __forceinline__ void mfma_group(floatx16 (&acc)[2][2], const float4 (
 #pragma unroll
             for (int j = 0; j < 2; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][tt], bv[j][tt], acc[i][j], 0, 0, 0);
+}
+
+// Two-level accumulation.  The MFMAs add into `acc`; every kFlushSlabs slabs `acc` is folded
+// into `sum` and cleared.  A single FP32 running sum over K same-sign products drifts by about
+// sqrt(K / 6) roundings of the whole sum (over 1e-6 of it from K of a few thousand); with
+// chunks of 1024 the drift stays near 1e-7 of the magnitude for any K this library accepts.
+__device__ __forceinline__ void fold_acc(floatx16 (&sum)[2][2], floatx16 (&acc)[2][2])
+{
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                sum[i][j][v] += acc[i][j][v];
+                acc[i][j][v] = 0.f;
+            }
 }
 
 // Accumulator register v of lane (lr, lk) holds row 8 (v / 4) + 4 lk + v % 4, column lr of
@@ -300,7 +318,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_nt_f32_stream(const Gemm
         else request_slab_impl(kt, sA, std::false_type{});
     };
 
-    floatx16 acc[2][2];
+    floatx16 acc[2][2], sum[2][2];
     float4 fa[2][2], fb[2][2];   // two register sets of MFMA operands (even / odd k-group)
 
     // One slab: inside it the operands of k-group kk + 1 are requested before the 16 MFMAs of
@@ -326,7 +344,13 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_nt_f32_stream(const Gemm
     };
 
     request_slab(0, ring0);
-    init_acc(P, M, N, m0, n0, L, acc);   // its loads fly together with slab 0
+    init_acc(P, M, N, m0, n0, L, sum);   // its loads fly together with slab 0
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     JG_WAIT_VMCNT(0);
     __syncthreads();
     if (1 < nkt) request_slab(1, ring1);
@@ -336,10 +360,12 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_nt_f32_stream(const Gemm
     for (; kt + 1 < nkt; kt += 2) {
         step(kt, ring0, ring1);
         step(kt + 1, ring1, ring0);
+        if ((kt & (kFlushSlabs - 1)) == kFlushSlabs - 2) fold_acc(sum, acc);
     }
     if (kt < nkt) step(kt, ring0, ring1);
+    fold_acc(sum, acc);
 
-    store_tile(P, M, N, m0, n0, L, acc);
+    store_tile(P, M, N, m0, n0, L, sum);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -380,11 +406,18 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_f32_guarded(const GemmGr
         src_chunk[p] = slot ^ ((r >> 1) & 7);
     }
 
-    floatx16 acc[2][2];
-    init_acc(P, M, N, tc.m0, tc.n0, L, acc);
+    floatx16 acc[2][2], sum[2][2];
+    init_acc(P, M, N, tc.m0, tc.n0, L, sum);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     float4 fa[2][2], fb[2][2];
     const int nkt = (K + BK - 1) / BK;
     for (int kt = 0; kt < nkt; ++kt) {
+        if (kt && (kt & (kFlushSlabs - 1)) == 0) fold_acc(sum, acc);
         float4 ra[4], rb[4];
 #pragma unroll
         for (int p = 0; p < 4; ++p) ra[p] = load_guarded(a_src[p], kt * BK + src_chunk[p] * 4, K);
@@ -405,7 +438,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_f32_guarded(const GemmGr
             mfma_group(acc, fa[kk & 1], fb[kk & 1]);
         }
     }
-    store_tile(P, M, N, tc.m0, tc.n0, L, acc);
+    fold_acc(sum, acc);
+    store_tile(P, M, N, tc.m0, tc.n0, L, sum);
 }
 
 // Host side: fills the derived fields of `g` and enqueues the launch.

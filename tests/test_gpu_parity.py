@@ -130,6 +130,21 @@ def test_options_agree(jg, ctx, ways):
     assert np.array_equal(fusedL.astype(np.float64), oracle.linear(XL, WL, bL))
 
 
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,K,N", [(256, 4096, 256), (128, 16384, 128)])
+def test_same_sign_data_stays_within_tolerance(jg, ctx, ways, M, K, N):
+    """All products positive: nothing cancels, S = |Y|, and a single FP32 running sum over K
+    would drift past 1e-6 of it; the kernel's two-level accumulation must not."""
+    X, W, b = inputs.layer_inputs(29, M, K, N, "R", bias=True)
+    X, W, b = np.abs(X) + np.float32(2.0 ** -10), np.abs(W) + np.float32(2.0 ** -16), np.abs(b)
+    Y, _ = run_layer(ctx, X, W, b, ways)
+    Y64 = oracle.linear(X, W, b)
+    S = oracle.magnitude(X, W, b)
+    assert np.array_equal(S, Y64)
+    err = np.abs(Y.astype(np.float64) - Y64) / S
+    assert err.max() <= TOL, f"max err/S = {err.max():.3e}"
+
+
 def test_config_2_full_comparison(jg, ctx):
     cfg = inputs.CONFIGS[2]
     X, W, _ = inputs.layer_inputs(cfg["seed"], cfg["M"], cfg["K"], cfg["N"], "R")
