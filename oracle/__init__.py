@@ -53,8 +53,11 @@ def _load():
         lib.oracle_magnitude.argtypes = [f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int]
         lib.oracle_entries.argtypes = [f32p, f32p, f32p, i64, i64p, i64p, i64, f64p, f64p, ctypes.c_int]
         lib.oracle_jigsaw.argtypes = [ctypes.c_int, f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int]
+        lib.oracle_backward.argtypes = [f32p, f32p, f32p, i64, i64, i64, f64p, f64p, ctypes.c_int, ctypes.c_int]
+        lib.oracle_jigsaw_backward.argtypes = [ctypes.c_int, f32p, f32p, f32p, i64, i64, i64, f64p, f64p,
+                                               ctypes.c_int]
         for fn in (lib.oracle_linear, lib.oracle_linear_rows, lib.oracle_magnitude,
-                   lib.oracle_entries, lib.oracle_jigsaw):
+                   lib.oracle_entries, lib.oracle_jigsaw, lib.oracle_backward, lib.oracle_jigsaw_backward):
             fn.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -158,6 +161,40 @@ def jigsaw(ways: int, X, W, b=None, nthreads: int | None = None) -> np.ndarray:
     return Y
 
 
+def backward(X, W, dY, nthreads: int | None = None, absolute: bool = False):
+    """(dX64, dW64) = (dY W, dY^T X) by the definition, in double (magnitudes if ``absolute``)."""
+    X, xp = _f32(X)
+    W, wp = _f32(W)
+    G, gp = _f32(dY)
+    M, K = X.shape
+    N = W.shape[0]
+    assert W.shape[1] == K and G.shape == (M, N)
+    dX, dxp = _f64_out((M, K))
+    dW, dwp = _f64_out((N, K))
+    _check(_load().oracle_backward(xp, wp, gp, M, K, N, dxp, dwp, int(absolute),
+                                   nthreads or host_threads()), "backward")
+    return dX, dW
+
+
+def backward_magnitude(X, W, dY, nthreads: int | None = None):
+    """(|dY| |W|, |dY|^T |X|): the scales of the backward tolerances."""
+    return backward(X, W, dY, nthreads, absolute=True)
+
+
+def jigsaw_backward(ways: int, X, W, dY, nthreads: int | None = None):
+    """(dX64, dW64) obtained block by block with dX partitioned like X and dW like W."""
+    X, xp = _f32(X)
+    W, wp = _f32(W)
+    G, gp = _f32(dY)
+    M, K = X.shape
+    N = W.shape[0]
+    dX, dxp = _f64_out((M, K))
+    dW, dwp = _f64_out((N, K))
+    _check(_load().oracle_jigsaw_backward(ways, xp, wp, gp, M, K, N, dxp, dwp,
+                                          nthreads or host_threads()), "jigsaw_backward")
+    return dX, dW
+
+
 # ----------------------------------------------------------------------------
 # layout definitions (pure indexing; bit-exact)
 # ----------------------------------------------------------------------------
@@ -253,3 +290,25 @@ def freivalds_reference(X, W, b, v, chunk_rows: int = 4096):
     if single:
         return yv[:, 0], bound[:, 0]
     return yv, bound
+
+
+def freivalds_backward(X, W, dY, v, chunk_rows: int = 4096):
+    """Projections of the gradients on vectors ``v`` (K x nv): dX v = dY (W v), dW v = dY^T (X v).
+
+    Returns ``(dXv, bound_dX, dWv, bound_dW)``; the bounds are the magnitudes projected on |v|.
+    """
+    V = np.asarray(v, dtype=np.float64)
+    V = V.reshape(V.shape[0], -1)
+    W64 = np.asarray(W, dtype=np.float64)
+    Wv, Wa = W64 @ V, np.abs(W64) @ np.abs(V)                  # N x nv
+    M, N = dY.shape
+    dXv = np.empty((M, V.shape[1])); bX = np.empty((M, V.shape[1]))
+    dWv = np.zeros((N, V.shape[1])); bW = np.zeros((N, V.shape[1]))
+    for r0 in range(0, M, chunk_rows):
+        g = np.asarray(dY[r0:r0 + chunk_rows], dtype=np.float64)
+        x = np.asarray(X[r0:r0 + chunk_rows], dtype=np.float64)
+        dXv[r0:r0 + chunk_rows] = g @ Wv
+        bX[r0:r0 + chunk_rows] = np.abs(g) @ Wa
+        dWv += g.T @ (x @ V)
+        bW += np.abs(g).T @ (np.abs(x) @ np.abs(V))
+    return dXv, bX, dWv, bW

@@ -22,6 +22,16 @@
  *                       to the peer by index, add, gather.
  *                       2-way: Sec. 4.1, Eqs. (1)-(2).  4-way: Sec. 4.2,
  *                       Eqs. (3)-(4).  ways = 1 is the unpartitioned layer.
+ *  oracle_backward    : the backward pass of the same layer (Sec. 4.1, last
+ *                       sentence: the transposed multiplications with the
+ *                       incoming gradient), by its definition:
+ *                         dX[i][k] = sum_j dY[i][j] * W[j][k]
+ *                         dW[j][k] = sum_i dY[i][j] * X[i][k]
+ *                       (and, optionally, the same sums of absolute values).
+ *  oracle_jigsaw_backward : the same gradients obtained block by block with
+ *                       dX partitioned like X and dW like W: every output
+ *                       block is the sum of two block products, one of them
+ *                       formed from a peer's block.
  *
  * Pins (see tests/test_oracle_pins.py): closed forms for identity /
  * permutation / all-ones / single-nonzero operands, exact integer brute force
@@ -329,4 +339,173 @@ int oracle_jigsaw(int ways, const float* X, const float* W, const float* b, int6
     default:
         return ORACLE_E_ARG;
     }
+}
+
+/* ------------------------------------------------------------------ */
+/* backward pass: the definition                                        */
+/* ------------------------------------------------------------------ */
+typedef struct {
+    const float *X, *W, *dY;
+    int64_t M, K, N;
+    double *dX, *dW;
+    int absolute;
+} bwd_env;
+
+/* row i of dX: for every k, sum over j ascending */
+static void dx_row(int64_t i, void* p)
+{
+    const bwd_env* e = (const bwd_env*)p;
+    double* out = e->dX + i * e->K;
+    for (int64_t k = 0; k < e->K; ++k) out[k] = 0.0;
+    for (int64_t j = 0; j < e->N; ++j) {
+        double g = (double)e->dY[i * e->N + j];
+        const float* w = e->W + j * e->K;
+        if (e->absolute) { g = fabs(g); for (int64_t k = 0; k < e->K; ++k) out[k] += g * fabs((double)w[k]); }
+        else { for (int64_t k = 0; k < e->K; ++k) out[k] += g * (double)w[k]; }
+    }
+}
+
+/* row j of dW: for every k, sum over i ascending */
+static void dw_row(int64_t j, void* p)
+{
+    const bwd_env* e = (const bwd_env*)p;
+    double* out = e->dW + j * e->K;
+    for (int64_t k = 0; k < e->K; ++k) out[k] = 0.0;
+    for (int64_t i = 0; i < e->M; ++i) {
+        double g = (double)e->dY[i * e->N + j];
+        const float* x = e->X + i * e->K;
+        if (e->absolute) { g = fabs(g); for (int64_t k = 0; k < e->K; ++k) out[k] += g * fabs((double)x[k]); }
+        else { for (int64_t k = 0; k < e->K; ++k) out[k] += g * (double)x[k]; }
+    }
+}
+
+/* dX [M x K] and dW [N x K] (either may be NULL); absolute != 0 gives the magnitudes */
+int oracle_backward(const float* X, const float* W, const float* dY, int64_t M, int64_t K, int64_t N,
+                    double* dX, double* dW, int absolute, int nthreads)
+{
+    if (!dY || M < 0 || K < 0 || N < 0) return ORACLE_E_ARG;
+    if ((dX && !W) || (dW && !X)) return ORACLE_E_ARG;
+    bwd_env e = {X, W, dY, M, K, N, dX, dW, absolute};
+    int rc = ORACLE_OK;
+    if (dX) rc = for_rows(0, M, nthreads, dx_row, &e);
+    if (rc == ORACLE_OK && dW) rc = for_rows(0, N, nthreads, dw_row, &e);
+    return rc;
+}
+
+/* ------------------------------------------------------------------ */
+/* backward pass, block by block                                        */
+/* ------------------------------------------------------------------ */
+
+/* C += A * B for contiguous A [m x n] and B [n x k] (contraction over A's columns / B's rows) */
+typedef struct { const float *A, *B; int64_t n, k; double* C; } nn_env;
+static void nn_row(int64_t i, void* p)
+{
+    const nn_env* e = (const nn_env*)p;
+    double* out = e->C + i * e->k;
+    for (int64_t j = 0; j < e->n; ++j) {
+        const double a = (double)e->A[i * e->n + j];
+        const float* b = e->B + j * e->k;
+        for (int64_t c = 0; c < e->k; ++c) out[c] += a * (double)b[c];
+    }
+}
+static int add_nn(const float* A, const float* B, int64_t m, int64_t n, int64_t k, double* C, int nthreads)
+{
+    nn_env e = {A, B, n, k, C};
+    return for_rows(0, m, nthreads, nn_row, &e);
+}
+
+/* C += A^T * B for contiguous A [m x n] and B [m x k] (contraction over the rows of both) */
+typedef struct { const float *A, *B; int64_t m, n, k; double* C; } tn_env;
+static void tn_row(int64_t j, void* p)
+{
+    const tn_env* e = (const tn_env*)p;
+    double* out = e->C + j * e->k;
+    for (int64_t i = 0; i < e->m; ++i) {
+        const double a = (double)e->A[i * e->n + j];
+        const float* b = e->B + i * e->k;
+        for (int64_t c = 0; c < e->k; ++c) out[c] += a * (double)b[c];
+    }
+}
+static int add_tn(const float* A, const float* B, int64_t m, int64_t n, int64_t k, double* C, int nthreads)
+{
+    tn_env e = {A, B, m, n, k, C};
+    return for_rows(0, n, nthreads, tn_row, &e);
+}
+
+static void put_block(double* G, int64_t ld, int64_t r0, int64_t nr, int64_t c0, int64_t nc, const double* B)
+{
+    for (int64_t r = 0; r < nr; ++r)
+        memcpy(G + (r0 + r) * ld + c0, B + r * nc, sizeof(double) * (size_t)nc);
+}
+
+/* Partitioning as in the forward pass: dY like Y, dX like X, dW like W.
+ * 2-way (Sec. 4.1): rank r holds X_r = X[:, r], W_r = [W_{r,0}; W_{r,1}] = W[:, r], dY_r = dY[:, r]
+ * (column halves).  dX_r = dY_0 W_{r,0} + dY_1 W_{r,1} and dW_{r,c} = dY_c^T X_r: the rank needs the
+ * peer's dY half; with it, both products of every output block are local.
+ * 4-way (Sec. 4.2): blocks (i, j) = rank 2 i + j.  dX_(i,j) = dY_(i,0) W_(0,j) + dY_(i,1) W_(1,j)
+ * (the row neighbour's dY block and the column neighbour's W block come from peers);
+ * dW_(c,j) = dY_(0,c)^T X_(0,j) + dY_(1,c)^T X_(1,j): the term with i != c is formed on the column
+ * neighbour (which holds X_(i,j)) and handed over as a partial product. */
+int oracle_jigsaw_backward(int ways, const float* X, const float* W, const float* dY, int64_t M,
+                           int64_t K, int64_t N, double* dX, double* dW, int nthreads)
+{
+    if (!X || !W || !dY || !dX || !dW || M < 0 || K < 0 || N < 0) return ORACLE_E_ARG;
+    if (ways == 1) return oracle_backward(X, W, dY, M, K, N, dX, dW, 0, nthreads);
+    if (ways != 2 && ways != 4) return ORACLE_E_ARG;
+    if ((K % 2) || (N % 2) || (ways == 4 && (M % 2))) return ORACLE_E_ARG;
+    const int rh = ways == 4 ? 2 : 1;                 /* row halves of X / dY */
+    const int64_t Mb = M / rh, Kh = K / 2, Nh = N / 2;
+    int rc = ORACLE_E_MEM;
+    /* blocks: Xb[i][j] (Mb x Kh), Gb[i][c] (Mb x Nh) = dY blocks, Wb[c][j] (Nh x Kh) */
+    float *Xb[2][2] = {{0}}, *Gb[2][2] = {{0}}, *Wb[2][2] = {{0}};
+    for (int i = 0; i < rh; ++i)
+        for (int j = 0; j < 2; ++j) {
+            Xb[i][j] = take_block(X, K, i * Mb, Mb, j * Kh, Kh);
+            Gb[i][j] = take_block(dY, N, i * Mb, Mb, j * Nh, Nh);
+            if (!Xb[i][j] || !Gb[i][j]) goto done;
+        }
+    for (int c = 0; c < 2; ++c)
+        for (int j = 0; j < 2; ++j) {
+            Wb[c][j] = take_block(W, K, c * Nh, Nh, j * Kh, Kh);
+            if (!Wb[c][j]) goto done;
+        }
+    /* dX blocks: owner (i, j) adds its own-dY term, then the term with the received dY block */
+    for (int i = 0; i < rh; ++i)
+        for (int j = 0; j < 2; ++j) {
+            double* acc = new_partial(Mb, Kh);
+            if (!acc) goto done;
+            const int own_c = j;                      /* the dY block this rank holds: column half j */
+            rc = add_nn(Gb[i][own_c], Wb[own_c][j], Mb, Nh, Kh, acc, nthreads);
+            if (!rc) rc = add_nn(Gb[i][1 - own_c], Wb[1 - own_c][j], Mb, Nh, Kh, acc, nthreads);
+            if (!rc) put_block(dX, K, i * Mb, Mb, j * Kh, Kh, acc);
+            free(acc);
+            if (rc) goto done;
+            rc = ORACLE_E_MEM;
+        }
+    /* dW blocks (c, j): one term per row half i; 4-way: the i != c term arrives as a partial */
+    for (int c = 0; c < 2; ++c)
+        for (int j = 0; j < 2; ++j) {
+            double* kept = new_partial(Nh, Kh);
+            double* recv = new_partial(Nh, Kh);
+            if (!kept || !recv) { free(kept); free(recv); goto done; }
+            rc = ORACLE_OK;
+            if (ways == 2) {
+                rc = add_tn(Gb[0][c], Xb[0][j], Mb, Nh, Kh, kept, nthreads);
+            } else {
+                rc = add_tn(Gb[c][c], Xb[c][j], Mb, Nh, Kh, kept, nthreads);
+                if (!rc) rc = add_tn(Gb[1 - c][c], Xb[1 - c][j], Mb, Nh, Kh, recv, nthreads);
+            }
+            if (!rc) {
+                for (int64_t t = 0; t < Nh * Kh; ++t) kept[t] += recv[t];
+                put_block(dW, K, c * Nh, Nh, j * Kh, Kh, kept);
+            }
+            free(kept); free(recv);
+            if (rc) goto done;
+            rc = ORACLE_E_MEM;
+        }
+    rc = ORACLE_OK;
+done:
+    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j) { free(Xb[i][j]); free(Gb[i][j]); free(Wb[i][j]); }
+    return rc;
 }
