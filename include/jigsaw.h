@@ -63,7 +63,7 @@ enum { JG_OP_XWT = 0 };                                  /* Y = X W^T (Sec. 4)  
 enum { JG_F32 = 0 };                                     /* the paper's uniform single precision (Sec. 6.1) */
 enum { JG_COMBINE_FUSED = 0, JG_COMBINE_SEPARATE = 1 };  /* where the "+" of Eq. (2)/(4) runs */
 enum { JG_WEIGHTS_COPY = 0, JG_WEIGHTS_DIRECT = 1 };     /* 4-way weight-block hand-off */
-enum { JG_T_X = 0, JG_T_W = 1, JG_T_B = 2 };             /* tensor selector of jg_shard */
+enum { JG_T_X = 0, JG_T_W = 1, JG_T_B = 2, JG_T_Y = 3 }; /* tensor selector of jg_shard / jg_gather_as */
 
 typedef struct jg_linear_desc {
     int64_t M, K, N;     /* global sizes: X is M x K, W is N x K, Y is M x N            */
@@ -95,16 +95,21 @@ typedef enum jg_query {
     JG_Q_Y_ROWS = 9, JG_Q_Y_COLS = 10,  /* shape of rank's Y shard                             */
     JG_Q_B_LEN = 11,                    /* length of rank's bias slice (= Y_COLS)              */
     JG_Q_RESIDENT_BYTES_RANK = 12,      /* bytes of X_r + W_r + Y_r (bias and workspace apart) */
-    JG_Q_GEMM_LAUNCHES = 13      /* GEMM kernel launches per forward (rank ignored)            */
+    JG_Q_GEMM_LAUNCHES = 13,     /* GEMM kernel launches per forward (rank ignored)            */
+    JG_Q_BACKWARD_WORKSPACE_BYTES = 14, /* device bytes jg_linear_backward needs (rank ignored)  */
+    JG_Q_BACKWARD_FLOPS_TOTAL = 15,     /* 4 M K N: twice the forward (Sec. 6.3 work model)      */
+    JG_Q_BACKWARD_GEMM_LAUNCHES = 16    /* GEMM kernel launches per backward (rank ignored)      */
 } jg_query;
 
 typedef enum jg_kernel {         /* kernel classes for jg_profile_read */
-    JG_KERNEL_GEMM = 0,          /* block-product GEMM (with or without fused combine)  */
+    JG_KERNEL_GEMM = 0,          /* forward block-product GEMM (X W^T form)             */
     JG_KERNEL_WEIGHT_COPY = 1,   /* 4-way weight-block hand-off                         */
     JG_KERNEL_COMBINE = 2,       /* separate partial-sum combine                        */
     JG_KERNEL_SHARD = 3,
     JG_KERNEL_GATHER = 4,
-    JG_KERNEL_COUNT = 5
+    JG_KERNEL_GEMM_DX = 5,       /* backward dX = dY W products                          */
+    JG_KERNEL_GEMM_DW = 6,       /* backward dW = dY^T X products                        */
+    JG_KERNEL_COUNT = 7
 } jg_kernel;
 
 /* init.  Creates a context bound to HIP device `device` and to `hip_stream`
@@ -136,6 +141,8 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out);
  *           (2-way: rank r holds all N rows of its column half).
  *   which = JG_T_B: global is the length-N bias (ld ignored); b_r = the half of b
  *           matching Y_r's columns (4-way: replicated on the two ranks of a column).
+ *   which = JG_T_Y: global is M x N, ld >= N (an incoming gradient dY): partitioned like Y,
+ *           2-way: column halves of N; 4-way: block (r/2, r%2).
  * `global` is a device pointer; `shards` is a host array of `ways` device pointers,
  * each with room for the rank's shard.  Pure data movement: bit-exact.
  * Errors: JG_E_NULL, JG_E_SHAPE (ld), JG_E_ALIGN, JG_E_DTYPE (which), JG_E_HIP. */
@@ -159,10 +166,37 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
                       const float* const* b_sh, float* const* y_sh, void* workspace,
                       size_t workspace_bytes);
 
+/* run (backward).  Gradients of the same layer for an incoming gradient dY (partitioned like Y):
+ *     dX = dY W      (M x K, partitioned like X)       dW = dY^T X    (N x K, partitioned like W)
+ * the transposed multiplications of Sec. 4.1 (last sentence); Sec. 6.3 counts them as twice the
+ * forward work.  No operand is transposed in memory.  Every output block is the sum of two block
+ * products over the two halves of the contracted dimension; one of the two is formed from blocks
+ * that live on peers (read in place from the peers' shard buffers), stored as a partial in the
+ * workspace, and the second product is accumulated on top of it:
+ *   ways = 1   one launch for dX, one for dW, no workspace;
+ *   ways = 2   dX_r = dY_r W_{r,r} + dY_{1-r} W_{r,1-r} (the rank needs the peer's dY half);
+ *              dW_{r,c} = dY_c^T X_r is a single product per block;
+ *   ways = 4   dX_(i,j) = sum_c dY_(i,c) W_(c,j)   and   dW_(c,j) = sum_i dY_(i,c)^T X_(i,j),
+ *              blocks (row half, column half) = rank 2 * row + column.
+ * x_sh, w_sh, dy_sh: host arrays of `ways` device pointers to the X, W and dY shards (shapes of
+ * X_r, W_r, Y_r); dx_sh, dw_sh: the same for the outputs (shapes of X_r, W_r).  `workspace`:
+ * 256-byte-aligned device buffer of at least JG_Q_BACKWARD_WORKSPACE_BYTES bytes (may be NULL when
+ * that is 0).  The bias gradient is not computed.  The plan's combine / weights options do not apply.
+ * Errors: JG_E_NULL, JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
+int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                       const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh,
+                       void* workspace, size_t workspace_bytes);
+
 /* query (data).  Inverse of jg_shard for Y: writes the M x N global result (device,
  * leading dimension ld >= N) from the per-rank Y shards.  Bit-exact.
  * Errors: JG_E_NULL, JG_E_SHAPE, JG_E_ALIGN, JG_E_HIP. */
 int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, int64_t ld);
+
+/* query (data).  Inverse of jg_shard for a tensor partitioned like X (JG_T_X: e.g. dX), like W
+ * (JG_T_W: e.g. dW) or like Y (JG_T_Y): writes the global matrix from the per-rank shards.
+ * jg_gather(plan, ...) is jg_gather_as(plan, JG_T_Y, ...).  Bit-exact.
+ * Errors: JG_E_NULL, JG_E_DTYPE (which), JG_E_SHAPE (ld), JG_E_ALIGN, JG_E_HIP. */
+int jg_gather_as(const jg_plan* plan, int which, const float* const* shards, float* global, int64_t ld);
 
 /* Per-kernel timing with HIP events on the context's stream.
  * jg_profile(ctx, 1) starts bracketing every subsequent kernel launch of this

@@ -33,15 +33,16 @@ JG_OP_XWT = 0
 JG_F32 = 0
 JG_COMBINE_FUSED, JG_COMBINE_SEPARATE = 0, 1
 JG_WEIGHTS_COPY, JG_WEIGHTS_DIRECT = 0, 1
-JG_T_X, JG_T_W, JG_T_B = 0, 1, 2
+JG_T_X, JG_T_W, JG_T_B, JG_T_Y = 0, 1, 2, 3
 (JG_Q_WORKSPACE_BYTES, JG_Q_FLOPS_TOTAL, JG_Q_FLOPS_RANK, JG_Q_HBM_BYTES_ALGO,
  JG_Q_EXCHANGE_BYTES_RANK, JG_Q_X_ROWS, JG_Q_X_COLS, JG_Q_W_ROWS, JG_Q_W_COLS,
- JG_Q_Y_ROWS, JG_Q_Y_COLS, JG_Q_B_LEN, JG_Q_RESIDENT_BYTES_RANK, JG_Q_GEMM_LAUNCHES) = range(14)
+ JG_Q_Y_ROWS, JG_Q_Y_COLS, JG_Q_B_LEN, JG_Q_RESIDENT_BYTES_RANK, JG_Q_GEMM_LAUNCHES,
+ JG_Q_BACKWARD_WORKSPACE_BYTES, JG_Q_BACKWARD_FLOPS_TOTAL, JG_Q_BACKWARD_GEMM_LAUNCHES) = range(17)
 (JG_KERNEL_GEMM, JG_KERNEL_WEIGHT_COPY, JG_KERNEL_COMBINE, JG_KERNEL_SHARD,
- JG_KERNEL_GATHER, JG_KERNEL_COUNT) = range(6)
+ JG_KERNEL_GATHER, JG_KERNEL_GEMM_DX, JG_KERNEL_GEMM_DW, JG_KERNEL_COUNT) = range(8)
 
 EXPORTS = ("jg_init", "jg_free", "jg_plan_create", "jg_plan_destroy", "jg_plan_query", "jg_shard",
-           "jg_linear_forward", "jg_gather", "jg_profile", "jg_profile_read", "jg_strerror",
+           "jg_linear_forward", "jg_linear_backward", "jg_gather", "jg_gather_as", "jg_profile", "jg_profile_read", "jg_strerror",
            "jg_last_hip_error")
 
 
@@ -75,12 +76,14 @@ _lib.jg_plan_destroy.restype = None
 _lib.jg_plan_query.argtypes = [_vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]
 _lib.jg_shard.argtypes = [_vp, ctypes.c_int, _vp, ctypes.c_int64, _vpp]
 _lib.jg_linear_forward.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
+_lib.jg_linear_backward.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
 _lib.jg_gather.argtypes = [_vp, _vpp, _vp, ctypes.c_int64]
+_lib.jg_gather_as.argtypes = [_vp, ctypes.c_int, _vpp, _vp, ctypes.c_int64]
 _lib.jg_profile.argtypes = [_vp, ctypes.c_int]
 _lib.jg_profile_read.argtypes = [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                  ctypes.POINTER(ctypes.c_int64)]
-for _n in ("jg_init", "jg_plan_create", "jg_plan_query", "jg_shard", "jg_linear_forward",
-           "jg_gather", "jg_profile", "jg_profile_read"):
+for _n in ("jg_init", "jg_plan_create", "jg_plan_query", "jg_shard", "jg_linear_forward", "jg_linear_backward",
+           "jg_gather", "jg_gather_as", "jg_profile", "jg_profile_read"):
     getattr(_lib, _n).restype = ctypes.c_int
 
 
@@ -143,8 +146,18 @@ def jg_linear_forward(plan, x_ptrs, w_ptrs, b_ptrs, y_ptrs, workspace_ptr, works
            "jg_linear_forward")
 
 
+def jg_linear_backward(plan, x_ptrs, w_ptrs, dy_ptrs, dx_ptrs, dw_ptrs, workspace_ptr, workspace_bytes: int) -> None:
+    _raise(_lib.jg_linear_backward(plan, _ptr_array(x_ptrs), _ptr_array(w_ptrs), _ptr_array(dy_ptrs),
+                                   _ptr_array(dx_ptrs), _ptr_array(dw_ptrs), workspace_ptr or None,
+                                   workspace_bytes), "jg_linear_backward")
+
+
 def jg_gather(plan, y_ptrs, global_y_ptr: int, ld: int) -> None:
     _raise(_lib.jg_gather(plan, _ptr_array(y_ptrs), global_y_ptr, ld), "jg_gather")
+
+
+def jg_gather_as(plan, which: int, shard_ptrs, global_ptr: int, ld: int) -> None:
+    _raise(_lib.jg_gather_as(plan, which, _ptr_array(shard_ptrs), global_ptr, ld), "jg_gather_as")
 
 
 def jg_profile(ctx, enable: bool) -> None:

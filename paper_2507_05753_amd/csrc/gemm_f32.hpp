@@ -1,0 +1,593 @@
+// FP32 matrix-core block GEMM for gfx950:  C[M x N] = op(A) * op(B) (+ addend) (+ bias)
+//
+// The contraction index k may be the contiguous index of an operand ("K-contiguous", KC) or
+// its row index ("K-strided", KS):
+//   A KC : A is M x K row-major          A KS : A is K x M row-major
+//   B KC : B is N x K row-major          B KS : B is K x N row-major
+// Forward  Y  = X W^T    : A = X  (KC), B = W (KC)     - the "X W^T" form of Sec. 4
+// Backward dX = dY W     : A = dY (KC), B = W (KS)     - contraction over the out-features
+//          dW = dY^T X   : A = dY (KS), B = X (KS)     - contraction over the rows (tokens);
+// the paper calls these the transposed multiplications of the backward pass (Sec. 4.1) and
+// needs the K-strided form for its transposed MLP as well (Sec. 5).  No operand is ever
+// transposed in memory.
+//
+// One launch runs a *group* of up to four equally-shaped problems (the block products of
+// all virtual ranks that belong to the same step of a pass: the products handed to a peer,
+// or the kept products accumulated on top of the received partial, Eqs. (2) and (4)).
+//
+// Work decomposition
+//   workgroup : 256 threads = 4 wavefronts (2 x 2), one 128 x 128 tile of C
+//   wavefront : 64 x 64 sub-tile = 2 x 2 MFMA blocks of 32 x 32 (v_mfma_f32_32x32x2_f32)
+//   K loop    : slabs of 32, two slab buffers in LDS used alternately
+//
+// gemm_f32_stream<A_KS, B_KS> (operand rows 16-byte aligned, contiguous extents in whole
+// 16-byte chunks): slabs go global -> LDS without passing through registers
+// (buffer_load_dwordx4 ... lds), one slab ahead of the math.  A wave-level load fills 1 KiB
+// of LDS, lane l writing 16-byte slot l; rows are not padded, instead the lane chooses WHICH
+// 16-byte chunk of global memory it fetches so that the later LDS reads are conflict-free:
+//   KC operand slab: 128 rows x 32 k (128-B rows), chunk = slot ^ ((row >> 1) & 7); the MFMA
+//      side reads 4 consecutive k of one row with one 128-bit read;
+//   KS operand slab: 32 k x 128 rows-of-C (512-B rows), chunk = slot ^ (8 * ((k >> 2) & 1));
+//      the MFMA side reads the same 4 k with four 32-bit reads 512 B apart.
+// Either way a lane ends up with the same four operand values, so the MFMA code, the
+// accumulator layout and the epilogue do not depend on the operand layouts.  Chunks outside
+// the operand (past K, or past the last row / column) are fetched from outside the buffer
+// descriptor and arrive as zeros, or are clamped to valid rows whose results are discarded.
+// The received partial product (the addend) is loaded straight into the accumulators while
+// the first slab is in flight, so the epilogue only stores.
+//
+// gemm_f32_guarded<A_KS, B_KS> (anything else): register loads with per-element bounds
+// checks written to the same LDS positions.
+//
+// Tile order: consecutive workgroup ids land on different XCDs (round-robin dispatch), so
+// the id is first folded into a per-XCD contiguous range, then walked column-major inside
+// bands of 8 row-tiles.  The 64 workgroups an XCD has in flight (2 per CU) therefore form an
+// 8 x 8 block of tiles that shares 8 A panels and 8 B panels in that XCD's L2.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+namespace jg {
+
+constexpr int kMaxGroup = 4;
+constexpr int BM = 128;
+constexpr int BN = 128;
+constexpr int BK = 32;
+constexpr int OPERAND_FLOATS = BM * BK;                  // one K slab of one operand = 16 KiB (BM == BN)
+constexpr int STAGE_FLOATS = 2 * OPERAND_FLOATS;        // one K slab of A and B = 32 KiB
+constexpr int GEMM_THREADS = 256;
+constexpr int kNumXcd = 8;
+constexpr int kBandRows = 8;                            // row-tiles per band
+constexpr int kFlushSlabs = 32;                         // K extent of one first-level accumulation = 1024
+
+struct GemmProblem {
+    const float* A;       // M x K (KC) or K x M (KS), leading dimension lda
+    const float* B;       // N x K (KC) or K x N (KS), leading dimension ldb
+    float* C;             // M x N, leading dimension ldc
+    const float* addend;  // M x N (ldadd) added in the epilogue, or nullptr
+    const float* bias;    // length N added in the epilogue, or nullptr
+    int lda, ldb, ldc, ldadd;
+};
+
+struct GemmGroup {
+    GemmProblem p[kMaxGroup];
+    int nprob;
+    int M, N, K;          // common shape of every problem in the group
+    int tiles_m, tiles_n; // ceil(M / BM), ceil(N / BN)
+    int per_xcd;          // ceil(nprob * tiles_m * tiles_n / kNumXcd)
+};
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void lds_void;
+constexpr int kBufferRsrcFlags = 0x00020000;   // raw 32-bit-element buffer descriptor, gfx9 family
+constexpr int kMaxDirectLd = 1 << 21;          // keeps a tile's 128 rows * ld * 4 B below 2^30
+constexpr int kOutOfBuffer = 0x7FFFFFF0;       // byte offset beyond any such tile: reads as zero
+
+// s_waitcnt that waits only for the vector-memory counter to drop to n (n < 64)
+#define JG_WAIT_VMCNT(n) \
+    __builtin_amdgcn_s_waitcnt(((n) & 0xF) | ((((n) >> 4) & 0x3) << 14) | (0x7 << 4) | (0xF << 8))
+
+struct TileCoord {
+    int prob, m0, n0;
+};
+
+__device__ __forceinline__ TileCoord decode_tile(const GemmGroup& g, int lid)
+{
+    const int tiles_per_prob = g.tiles_m * g.tiles_n;
+    const int prob = lid / tiles_per_prob;
+    const int t = lid - prob * tiles_per_prob;
+    const int band = t / (kBandRows * g.tiles_n);
+    const int in_band = t - band * (kBandRows * g.tiles_n);
+    const int band_first = band * kBandRows;
+    const int band_rows = min(kBandRows, g.tiles_m - band_first);
+    TileCoord c;
+    c.prob = prob;
+    c.m0 = (band_first + in_band % band_rows) * BM;
+    c.n0 = (in_band / band_rows) * BN;
+    return c;
+}
+
+// Lane coordinates inside the workgroup's tile.
+struct LaneMap {
+    int wave, lane, wm, wn, lr, lk;
+    __device__ __forceinline__ void init(int tid)
+    {
+        wave = tid >> 6;
+        lane = tid & 63;
+        wm = wave >> 1;      // the wave's 64-row half of the tile
+        wn = wave & 1;       // ... and 64-column half
+        lr = lane & 31;      // row (A) / column (B) of the 32-wide MFMA block this lane feeds
+        lk = lane >> 5;      // which of the instruction's two k slots
+    }
+};
+
+// How a lane fetches its MFMA operand values of one operand from a slab in LDS.  For k-group
+// g (8 consecutive k) lanes with lk = 0 take k = 8 g .. 8 g + 3 and lanes with lk = 1 the next
+// four; the t-th MFMA of the group contracts the k slots {8 g + t, 8 g + 4 + t}.  A and B use
+// the same assignment, so the products pair up whatever the two layouts are.
+template <bool KS>
+struct FragReader {
+    int off[2];   // float offset of the lane's data for blocks 0 / 1 (operand base included)
+    int sw[2];    // KC only: the row's chunk swizzle
+    // half = the wave's 64-wide half of the tile along this operand's C dimension
+    __device__ __forceinline__ void init(int operand_base, int half, int lr, int lk)
+    {
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int r = half * 64 + b * 32 + lr;
+            if (KS) {
+                off[b] = operand_base + (4 * lk) * BM + (r ^ (32 * lk));
+                sw[b] = 0;
+            } else {
+                off[b] = operand_base + r * BK;
+                sw[b] = (r >> 1) & 7;
+            }
+        }
+    }
+    __device__ __forceinline__ float4 read(const float* s, int g, int b, int lk) const
+    {
+        if (KS) {
+            const float* p = s + off[b] + g * 8 * BM;
+            return make_float4(p[0], p[BM], p[2 * BM], p[3 * BM]);
+        } else {
+            return *reinterpret_cast<const float4*>(s + off[b] + (((g * 2 + lk) ^ sw[b]) << 2));
+        }
+    }
+};
+
+__device__ __forceinline__ void mfma_group(floatx16 (&acc)[2][2], const float4 (&fa)[2], const float4 (&fb)[2])
+{
+    const float av[2][4] = {{fa[0].x, fa[0].y, fa[0].z, fa[0].w}, {fa[1].x, fa[1].y, fa[1].z, fa[1].w}};
+    const float bv[2][4] = {{fb[0].x, fb[0].y, fb[0].z, fb[0].w}, {fb[1].x, fb[1].y, fb[1].z, fb[1].w}};
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][tt], bv[j][tt], acc[i][j], 0, 0, 0);
+}
+
+// Two-level accumulation.  The MFMAs add into `acc`; every kFlushSlabs slabs `acc` is folded
+// into `sum` and cleared.  A single FP32 running sum over K same-sign products drifts by about
+// sqrt(K / 6) roundings of the whole sum (over 1e-6 of it from K of a few thousand); with
+// chunks of 1024 the drift stays near 1e-7 of the magnitude for any K this library accepts.
+__device__ __forceinline__ void fold_acc(floatx16 (&sum)[2][2], floatx16 (&acc)[2][2])
+{
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                sum[i][j][v] += acc[i][j][v];
+                acc[i][j][v] = 0.f;
+            }
+}
+
+// Accumulator register v of lane (lr, lk) holds row 8 (v / 4) + 4 lk + v % 4, column lr of
+// its 32 x 32 block, so one load / store instruction touches two 128-byte row segments.
+
+// acc = addend tile (the partial product received from the peer), or zero.
+__device__ __forceinline__ void init_acc(const GemmProblem& P, int M, int N, int m0, int n0,
+                                         const LaneMap& L, floatx16 (&acc)[2][2])
+{
+    const float* __restrict__ addend = P.addend;
+    if (!addend) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        return;
+    }
+    const int ldadd = P.ldadd;
+    const int row_base = m0 + L.wm * 64 + 4 * L.lk;
+    const int col_base = n0 + L.wn * 64 + L.lr;
+    if (m0 + BM <= M && n0 + BN <= N) {
+        const float* a_lane = addend + (int64_t)row_base * ldadd + col_base;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    acc[i][j][v] = a_lane[(int64_t)(i * 32 + 8 * (v >> 2) + (v & 3)) * ldadd + j * 32];
+    } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int col = col_base + j * 32;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = row_base + i * 32 + 8 * (v >> 2) + (v & 3);
+                    acc[i][j][v] = (row < M && col < N) ? addend[(int64_t)row * ldadd + col] : 0.f;
+                }
+            }
+    }
+}
+
+// C = acc (+ bias) for the tile at (m0, n0).
+__device__ __forceinline__ void store_tile(const GemmProblem& P, int M, int N, int m0, int n0,
+                                           const LaneMap& L, const floatx16 (&acc)[2][2])
+{
+    const float* __restrict__ bias = P.bias;
+    float* __restrict__ C = P.C;
+    const int ldc = P.ldc;
+    const int row_base = m0 + L.wm * 64 + 4 * L.lk;     // + i * 32 + 8 (v / 4) + v % 4
+    const int col_base = n0 + L.wn * 64 + L.lr;         // + j * 32
+    if (m0 + BM <= M && n0 + BN <= N) {   // interior tile: no bounds checks
+        float* c_lane = C + (int64_t)row_base * ldc + col_base;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const float bj = bias ? bias[col_base + j * 32] : 0.f;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    c_lane[(int64_t)(i * 32 + 8 * (v >> 2) + (v & 3)) * ldc + j * 32] = acc[i][j][v] + bj;
+        }
+    } else {                              // edge tile: every element checked against M and N
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int col = col_base + j * 32;
+                if (col >= N) continue;
+                const float bj = bias ? bias[col] : 0.f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = row_base + i * 32 + 8 * (v >> 2) + (v & 3);
+                    if (row < M) C[(int64_t)row * ldc + col] = acc[i][j][v] + bj;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Slab loaders.  A loader is set up once per tile for one operand and then asked for slab kt.
+// LDS positions: a wave-level transfer fills 1 KiB; unit u = p * 4 + wave (p = 0..3) is the
+// u-th KiB of the operand's 16 KiB slab, lane l its l-th 16-byte slot.
+//   KC: unit u = rows 8 u .. 8 u + 7 of the tile, 8 slots per row.
+//   KS: unit u = k rows 2 u, 2 u + 1 of the slab, 32 slots per row.
+// ------------------------------------------------------------------------------------------
+struct OperandView {
+    const float* base;   // element (row-of-C 0, k 0) of the whole operand
+    int ld;              // leading dimension
+    int extent;          // M (for A) or N (for B): number of rows-of-C the operand spans
+    int origin;          // m0 or n0 of this tile
+};
+
+template <bool KS>
+struct StreamLoader {
+    int voff[4];                        // byte offsets of this lane's four chunks
+    int chunk_k[4];                     // KC: first k (within a slab) of each chunk, for the ragged slab
+    __amdgpu_buffer_rsrc_t rsrc;        // KC: the tile's rows; KS: rebuilt for every slab
+    const float* tile_base;             // KS: element (origin, k = 0)
+    int ld, K, valid;                   // valid = rows-of-C of this tile inside the operand
+
+    __device__ __forceinline__ void init(const OperandView& v, int K_, int wave, int lane)
+    {
+        ld = v.ld;
+        K = K_;
+        valid = min(BM, v.extent - v.origin);
+        if (KS) {
+            tile_base = v.base + v.origin;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int k = (p * 4 + wave) * 2 + (lane >> 5);
+                const int chunk = (lane & 31) ^ (8 * ((k >> 2) & 1));
+                voff[p] = (k * ld + chunk * 4) * 4;
+                chunk_k[p] = 0;
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int r = (p * 4 + wave) * 8 + (lane >> 3);
+                const int chunk = (lane & 7) ^ ((r >> 1) & 7);
+                // rows past the edge are clamped to the last valid row: read but never stored
+                voff[p] = (min(r, valid - 1) * ld + chunk * 4) * 4;
+                chunk_k[p] = chunk * 4;
+            }
+            // base = first row of the tile, extent = up to the end of its last valid row: an
+            // out-of-range offset reads zero instead of faulting
+            const int64_t bytes = ((int64_t)(valid - 1) * ld + K) * 4;
+            rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(v.base + (int64_t)v.origin * ld), 0,
+                                                     (int)bytes, kBufferRsrcFlags);
+        }
+    }
+    // asynchronous: the data is in LDS once this thread's vmcnt has drained and a barrier passed
+    __device__ __forceinline__ void request(int kt, float* operand_slab, int wave)
+    {
+        if (KS) {
+            // buffer over the k rows of this slab that exist; rows past K and columns past the
+            // operand's edge fall outside it and arrive as zeros
+            const int rows = min(BK, K - kt * BK);
+            const int64_t bytes = ((int64_t)(rows - 1) * ld + valid) * 4;
+            rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(tile_base + (int64_t)kt * BK * ld), 0,
+                                                     (int)bytes, kBufferRsrcFlags);
+#pragma unroll
+            for (int p = 0; p < 4; ++p)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(operand_slab + (p * 4 + wave) * 256),
+                                                         16, voff[p], 0, 0, 0);
+        } else {
+            const int soff = kt * BK * 4;
+            if (kt * BK + BK > K) {      // ragged last slab: chunks at or past column K read as zero
+                const int k_left = K - kt * BK;
+#pragma unroll
+                for (int p = 0; p < 4; ++p)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        rsrc, (lds_void*)(operand_slab + (p * 4 + wave) * 256), 16,
+                        chunk_k[p] < k_left ? voff[p] : kOutOfBuffer, soff, 0, 0);
+            } else {
+#pragma unroll
+                for (int p = 0; p < 4; ++p)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        rsrc, (lds_void*)(operand_slab + (p * 4 + wave) * 256), 16, voff[p], soff, 0, 0);
+            }
+        }
+    }
+};
+
+// Synchronous loader for operands that rule out 16-byte transfers: four guarded 4-element
+// reads per slab, written to the positions the stream loader would have filled.
+template <bool KS>
+struct GuardedLoader {
+    const float* base;
+    int ld, K, extent, origin;
+    __device__ __forceinline__ void init(const OperandView& v, int K_)
+    {
+        base = v.base; ld = v.ld; K = K_; extent = v.extent; origin = v.origin;
+    }
+    // element (row-of-C r, k), zero outside the operand
+    __device__ __forceinline__ float at(int r, int k) const
+    {
+        if (r >= extent || k >= K) return 0.f;
+        return KS ? base[(int64_t)k * ld + r] : base[(int64_t)r * ld + k];
+    }
+    __device__ __forceinline__ void fetch(int kt, int wave, int lane, float4 (&reg)[4]) const
+    {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            if (KS) {
+                const int k = (p * 4 + wave) * 2 + (lane >> 5);
+                const int chunk = (lane & 31) ^ (8 * ((k >> 2) & 1));
+                const int r = origin + chunk * 4, kk = kt * BK + k;
+                reg[p] = make_float4(at(r, kk), at(r + 1, kk), at(r + 2, kk), at(r + 3, kk));
+            } else {
+                const int rr = (p * 4 + wave) * 8 + (lane >> 3);
+                const int chunk = (lane & 7) ^ ((rr >> 1) & 7);
+                const int r = origin + rr, kk = kt * BK + chunk * 4;
+                reg[p] = make_float4(at(r, kk), at(r, kk + 1), at(r, kk + 2), at(r, kk + 3));
+            }
+        }
+    }
+    __device__ __forceinline__ static void put(float* operand_slab, int wave, int lane, const float4 (&reg)[4])
+    {
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            *reinterpret_cast<float4*>(operand_slab + (p * 4 + wave) * 256 + lane * 4) = reg[p];
+    }
+};
+
+// ------------------------------------------------------------------------------------------
+// asynchronous-load kernel: one tile per workgroup, two workgroups per CU
+// ------------------------------------------------------------------------------------------
+template <bool A_KS, bool B_KS>
+__global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGroup g)
+{
+    // One array per slab buffer: distinct LDS objects let the compiler prove that the
+    // asynchronous fill of one does not alias the reads of the other, so it does not make
+    // every LDS read wait for the loads still in flight.
+    __shared__ __align__(16) float ring0[STAGE_FLOATS];
+    __shared__ __align__(16) float ring1[STAGE_FLOATS];
+
+    const int lid = (blockIdx.x % kNumXcd) * g.per_xcd + blockIdx.x / kNumXcd;
+    if (lid >= g.nprob * g.tiles_m * g.tiles_n) return;   // whole workgroup leaves before any barrier
+    const TileCoord tc = decode_tile(g, lid);
+    const GemmProblem& P = g.p[tc.prob];
+    const int M = g.M, N = g.N, K = g.K;
+    const int m0 = tc.m0, n0 = tc.n0;
+    const int nkt = (K + BK - 1) / BK;
+
+    LaneMap L;
+    L.init(threadIdx.x);
+    StreamLoader<A_KS> load_a;
+    StreamLoader<B_KS> load_b;
+    load_a.init(OperandView{P.A, P.lda, M, m0}, K, L.wave, L.lane);
+    load_b.init(OperandView{P.B, P.ldb, N, n0}, K, L.wave, L.lane);
+    FragReader<A_KS> frag_a;
+    FragReader<B_KS> frag_b;
+    frag_a.init(0, L.wm, L.lr, L.lk);
+    frag_b.init(OPERAND_FLOATS, L.wn, L.lr, L.lk);
+
+    auto request_slab = [&](int kt, float* slab) {
+        load_a.request(kt, slab, L.wave);
+        load_b.request(kt, slab + OPERAND_FLOATS, L.wave);
+    };
+    auto read_frags = [&](const float* slab, int kk, float4 (&fa)[2], float4 (&fb)[2]) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            fa[b] = frag_a.read(slab, kk, b, L.lk);
+            fb[b] = frag_b.read(slab, kk, b, L.lk);
+        }
+    };
+
+    floatx16 acc[2][2], sum[2][2];
+    float4 fa[2][2], fb[2][2];   // two register sets of MFMA operands (even / odd k-group)
+
+    // One slab: inside it the operands of k-group kk + 1 are requested before the 16 MFMAs of
+    // group kk are issued, so LDS latency hides behind about a thousand matrix-pipe cycles.
+    // The slab boundary (wait for the next slab, barrier, request the slab after next, first
+    // operand read of the next slab) sits before the LAST group's MFMAs for the same reason.
+    // The scheduling fences keep the compiler from undoing this order.
+    auto step = [&](int kt, float* cur, const float* nxt) {
+#pragma unroll
+        for (int kk = 0; kk < 3; ++kk) {
+            read_frags(cur, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_group(acc, fa[kk & 1], fb[kk & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        JG_WAIT_VMCNT(0);   // this thread's part of slab kt + 1 has landed
+        __syncthreads();    // ... and everyone's; all waves hold their last operands of slab kt
+        if (kt + 2 < nkt) request_slab(kt + 2, cur);
+        if (kt + 1 < nkt) read_frags(nxt, 0, fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_group(acc, fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    request_slab(0, ring0);
+    init_acc(P, M, N, m0, n0, L, sum);   // its loads fly together with slab 0
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    JG_WAIT_VMCNT(0);
+    __syncthreads();
+    if (1 < nkt) request_slab(1, ring1);
+    read_frags(ring0, 0, fa[0], fb[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    int kt = 0;
+    for (; kt + 1 < nkt; kt += 2) {
+        step(kt, ring0, ring1);
+        step(kt + 1, ring1, ring0);
+        if ((kt & (kFlushSlabs - 1)) == kFlushSlabs - 2) fold_acc(sum, acc);
+    }
+    if (kt < nkt) step(kt, ring0, ring1);
+    fold_acc(sum, acc);
+
+    store_tile(P, M, N, m0, n0, L, sum);
+}
+
+// ------------------------------------------------------------------------------------------
+// guarded kernel: any alignment, any sizes; synchronous slab loads through registers
+// ------------------------------------------------------------------------------------------
+template <bool A_KS, bool B_KS>
+__global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_guarded(const GemmGroup g)
+{
+    __shared__ __align__(16) float slab[STAGE_FLOATS];
+
+    const int lid = (blockIdx.x % kNumXcd) * g.per_xcd + blockIdx.x / kNumXcd;
+    if (lid >= g.nprob * g.tiles_m * g.tiles_n) return;
+    const TileCoord tc = decode_tile(g, lid);
+    const GemmProblem& P = g.p[tc.prob];
+    const int M = g.M, N = g.N, K = g.K;
+
+    LaneMap L;
+    L.init(threadIdx.x);
+    GuardedLoader<A_KS> load_a;
+    GuardedLoader<B_KS> load_b;
+    load_a.init(OperandView{P.A, P.lda, M, tc.m0}, K);
+    load_b.init(OperandView{P.B, P.ldb, N, tc.n0}, K);
+    FragReader<A_KS> frag_a;
+    FragReader<B_KS> frag_b;
+    frag_a.init(0, L.wm, L.lr, L.lk);
+    frag_b.init(OPERAND_FLOATS, L.wn, L.lr, L.lk);
+
+    floatx16 acc[2][2], sum[2][2];
+    init_acc(P, M, N, tc.m0, tc.n0, L, sum);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    float4 fa[2][2], fb[2][2];
+    const int nkt = (K + BK - 1) / BK;
+    for (int kt = 0; kt < nkt; ++kt) {
+        if (kt && (kt & (kFlushSlabs - 1)) == 0) fold_acc(sum, acc);
+        float4 ra[4], rb[4];
+        load_a.fetch(kt, L.wave, L.lane, ra);
+        load_b.fetch(kt, L.wave, L.lane, rb);
+        __syncthreads();        // everyone is done reading the previous slab
+        GuardedLoader<A_KS>::put(slab, L.wave, L.lane, ra);
+        GuardedLoader<B_KS>::put(slab + OPERAND_FLOATS, L.wave, L.lane, rb);
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK / 8; ++kk) {
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                fa[kk & 1][b] = frag_a.read(slab, kk, b, L.lk);
+                fb[kk & 1][b] = frag_b.read(slab, kk, b, L.lk);
+            }
+            mfma_group(acc, fa[kk & 1], fb[kk & 1]);
+        }
+    }
+    fold_acc(sum, acc);
+    store_tile(P, M, N, tc.m0, tc.n0, L, sum);
+}
+
+enum GemmLayout { kGemmNT = 0 /* A KC, B KC */, kGemmNN = 1 /* A KC, B KS */, kGemmTN = 2 /* A KS, B KS */ };
+
+// Can this operand take the asynchronous 16-byte path?
+inline bool operand_streams(const float* p, int ld, bool ks, int extent, int K)
+{
+    if (((uintptr_t)p & 15) || (ld & 3) || ld > kMaxDirectLd) return false;
+    return ks ? (extent % 4) == 0 : (K % 4) == 0;   // the contiguous extent comes in whole chunks
+}
+
+template <bool A_KS, bool B_KS>
+inline void launch_gemm_layout(const GemmGroup& g, bool stream_ok, hipStream_t stream)
+{
+    const unsigned grid = (unsigned)(kNumXcd * g.per_xcd);
+    if (stream_ok)
+        hipLaunchKernelGGL((gemm_f32_stream<A_KS, B_KS>), dim3(grid), dim3(GEMM_THREADS), 0, stream, g);
+    else
+        hipLaunchKernelGGL((gemm_f32_guarded<A_KS, B_KS>), dim3(grid), dim3(GEMM_THREADS), 0, stream, g);
+}
+
+// Host side: fills the derived fields of `g` and enqueues the launch.
+// Preconditions (checked by the C-ABI layer): 1 <= nprob <= 4; M, N, K >= 1; all pointers valid
+// for their shapes; leading dimensions at least the contiguous extent of their operand.
+inline hipError_t launch_gemm_group(GemmGroup& g, int layout, hipStream_t stream)
+{
+    g.tiles_m = (g.M + BM - 1) / BM;
+    g.tiles_n = (g.N + BN - 1) / BN;
+    const int64_t total = (int64_t)g.nprob * g.tiles_m * g.tiles_n;
+    g.per_xcd = (int)((total + kNumXcd - 1) / kNumXcd);
+    const bool a_ks = layout == kGemmTN, b_ks = layout != kGemmNT;
+    bool stream_ok = true;
+    for (int i = 0; i < g.nprob; ++i) {
+        stream_ok = stream_ok && operand_streams(g.p[i].A, g.p[i].lda, a_ks, g.M, g.K) &&
+                    operand_streams(g.p[i].B, g.p[i].ldb, b_ks, g.N, g.K);
+    }
+    switch (layout) {
+    case kGemmNT: launch_gemm_layout<false, false>(g, stream_ok, stream); break;
+    case kGemmNN: launch_gemm_layout<false, true>(g, stream_ok, stream); break;
+    case kGemmTN: launch_gemm_layout<true, true>(g, stream_ok, stream); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace jg

@@ -10,7 +10,7 @@
 #include <new>
 #include <vector>
 
-#include "gemm_nt.hpp"
+#include "gemm_f32.hpp"
 #include "stream_kernels.hpp"
 
 namespace {
@@ -59,6 +59,8 @@ struct jg_plan {
     size_t off_kept;       // ways x part_bytes: kept products (separate combine only)
     size_t off_wrecv;      // ways x wblk_bytes
     size_t ws_bytes;
+    // backward workspace: ways partials of dX blocks, then (4-way) ways partials of dW blocks
+    size_t bw_dx_bytes, bw_dw_bytes, bw_off_dw, bw_ws_bytes;
 };
 
 namespace {
@@ -258,6 +260,16 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
         }
     }
     p->ws_bytes = off;
+    p->bw_dx_bytes = p->bw_dw_bytes = p->bw_off_dw = p->bw_ws_bytes = 0;
+    if (d.ways >= 2) {
+        p->bw_dx_bytes = round_up((size_t)p->xr * (size_t)p->xc * sizeof(float), kWsAlign);
+        p->bw_off_dw = p->bw_dx_bytes * d.ways;
+        p->bw_ws_bytes = p->bw_off_dw;
+        if (d.ways == 4) {
+            p->bw_dw_bytes = round_up((size_t)p->wr * (size_t)p->wc * sizeof(float), kWsAlign);
+            p->bw_ws_bytes += p->bw_dw_bytes * d.ways;
+        }
+    }
     *out = p;
     return JG_OK;
 }
@@ -296,9 +308,36 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
         *out = 4 * (plan->xr * plan->xc + plan->wr * plan->wc + plan->yr * plan->yc);
         break;
     case JG_Q_GEMM_LAUNCHES: *out = d.ways == 1 ? 1 : 2; break;
+    case JG_Q_BACKWARD_WORKSPACE_BYTES: *out = (int64_t)plan->bw_ws_bytes; break;
+    case JG_Q_BACKWARD_FLOPS_TOTAL: *out = 4 * M * K * N; break;
+    case JG_Q_BACKWARD_GEMM_LAUNCHES: *out = d.ways == 1 ? 2 : d.ways == 2 ? 3 : 4; break;
     default: return JG_E_DTYPE;
     }
     return JG_OK;
+}
+
+// Geometry of one tensor's partition: every rank's block is rows x cols, rank r's block sits at
+// block coordinates (rb, cb) of the global matrix, whose width is `width`.
+struct Partition {
+    int64_t rows, cols, width;
+};
+
+static int partition_of(const jg_plan* plan, int which, Partition* out)
+{
+    switch (which) {
+    case JG_T_X: *out = {plan->xr, plan->xc, plan->d.K}; return JG_OK;
+    case JG_T_W: *out = {plan->wr, plan->xc, plan->d.K}; return JG_OK;
+    case JG_T_Y: *out = {plan->yr, plan->yc, plan->d.N}; return JG_OK;
+    default: return JG_E_DTYPE;
+    }
+}
+
+static void block_coords(int ways, int r, int64_t* rb, int64_t* cb)
+{
+    *rb = 0;
+    *cb = 0;
+    if (ways == 2) *cb = r;
+    if (ways == 4) { *rb = r / 2; *cb = r % 2; }
 }
 
 int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, float* const* shards)
@@ -307,7 +346,7 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
     const jg_linear_desc& d = plan->d;
     if (int rc = check_ptr_array(shards, d.ways)) return rc;
     if (!aligned(global, 4)) return JG_E_ALIGN;
-    if (which != JG_T_X && which != JG_T_W && which != JG_T_B) return JG_E_DTYPE;
+    if (which != JG_T_X && which != JG_T_W && which != JG_T_B && which != JG_T_Y) return JG_E_DTYPE;
     jg_ctx* c = plan->ctx;
     if (!c) return JG_E_NULL;
     if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
@@ -315,7 +354,8 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
     jg::CopyGroup g;
     std::memset(&g, 0, sizeof(g));
     g.nblocks = d.ways;
-    g.nontemporal = which == JG_T_X;   // activations are streamed once; weights and bias are re-read soon
+    // activations and gradients are streamed once; weights and bias are re-read soon
+    g.nontemporal = which == JG_T_X || which == JG_T_Y;
     if (which == JG_T_B) {
         g.rows = 1;
         g.cols = (int)plan->yc;
@@ -324,29 +364,30 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
             g.b[r] = {global + col_half * plan->yc, shards[r], plan->yc, plan->yc};
         }
     } else {
-        const int64_t rows = which == JG_T_X ? plan->xr : plan->wr;
-        const int64_t cols = plan->xc;   // X and W shards have the same column count
-        if (ld < d.K) return JG_E_SHAPE;
-        g.rows = (int)rows;
-        g.cols = (int)cols;
+        Partition pt;
+        (void)partition_of(plan, which, &pt);
+        if (ld < pt.width) return JG_E_SHAPE;
+        g.rows = (int)pt.rows;
+        g.cols = (int)pt.cols;
         for (int r = 0; r < d.ways; ++r) {
-            int64_t rb = 0, cb = 0;   // block coordinates of rank r
-            if (d.ways == 2) cb = r;
-            if (d.ways == 4) { rb = r / 2; cb = r % 2; }
-            g.b[r] = {global + rb * rows * ld + cb * cols, shards[r], ld, cols};
+            int64_t rb, cb;
+            block_coords(d.ways, r, &rb, &cb);
+            g.b[r] = {global + rb * pt.rows * ld + cb * pt.cols, shards[r], ld, pt.cols};
         }
     }
     ScopedTimer t(c, JG_KERNEL_SHARD);
     return HIP_OK(jg::launch_copy_group(g, c->stream)) ? JG_OK : JG_E_HIP;
 }
 
-int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, int64_t ld)
+int jg_gather_as(const jg_plan* plan, int which, const float* const* shards, float* global, int64_t ld)
 {
-    if (!plan || !global_y) return JG_E_NULL;
+    if (!plan || !global) return JG_E_NULL;
     const jg_linear_desc& d = plan->d;
-    if (int rc = check_ptr_array(y_sh, d.ways)) return rc;
-    if (!aligned(global_y, 4)) return JG_E_ALIGN;
-    if (ld < d.N) return JG_E_SHAPE;
+    if (int rc = check_ptr_array(shards, d.ways)) return rc;
+    if (!aligned(global, 4)) return JG_E_ALIGN;
+    Partition pt;
+    if (int rc = partition_of(plan, which, &pt)) return rc;
+    if (ld < pt.width) return JG_E_SHAPE;
     jg_ctx* c = plan->ctx;
     if (!c) return JG_E_NULL;
     if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
@@ -355,16 +396,20 @@ int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, in
     std::memset(&g, 0, sizeof(g));
     g.nblocks = d.ways;
     g.nontemporal = 1;
-    g.rows = (int)plan->yr;
-    g.cols = (int)plan->yc;
+    g.rows = (int)pt.rows;
+    g.cols = (int)pt.cols;
     for (int r = 0; r < d.ways; ++r) {
-        int64_t rb = 0, cb = 0;
-        if (d.ways == 2) cb = r;
-        if (d.ways == 4) { rb = r / 2; cb = r % 2; }
-        g.b[r] = {y_sh[r], global_y + rb * plan->yr * ld + cb * plan->yc, plan->yc, ld};
+        int64_t rb, cb;
+        block_coords(d.ways, r, &rb, &cb);
+        g.b[r] = {shards[r], global + rb * pt.rows * ld + cb * pt.cols, pt.cols, ld};
     }
     ScopedTimer t(c, JG_KERNEL_GATHER);
     return HIP_OK(jg::launch_copy_group(g, c->stream)) ? JG_OK : JG_E_HIP;
+}
+
+int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, int64_t ld)
+{
+    return jg_gather_as(plan, JG_T_Y, y_sh, global_y, ld);
 }
 
 int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
@@ -401,7 +446,7 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
         g.nprob = 1;
         g.p[0] = {x_sh[0], w_sh[0], y_sh[0], nullptr, bias_of(0), ldk, ldk, ldn, 0};
         ScopedTimer t(c, JG_KERNEL_GEMM);
-        return HIP_OK(jg::launch_gemm_group(g, c->stream)) ? JG_OK : JG_E_HIP;
+        return HIP_OK(jg::launch_gemm_group(g, jg::kGemmNT, c->stream)) ? JG_OK : JG_E_HIP;
     }
 
     auto send_buf = [&](int r) { return reinterpret_cast<float*>(ws + plan->off_send + r * plan->part_bytes); };
@@ -452,7 +497,7 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
         g.p[r] = {x_sh[r], w_send[r], send_buf(r), nullptr, nullptr, ldk, ldk, ldn, 0};
     {
         ScopedTimer t(c, JG_KERNEL_GEMM);
-        if (!HIP_OK(jg::launch_gemm_group(g, c->stream))) return JG_E_HIP;
+        if (!HIP_OK(jg::launch_gemm_group(g, jg::kGemmNT, c->stream))) return JG_E_HIP;
     }
 
     // launch 2: the kept products
@@ -460,13 +505,13 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
         for (int r = 0; r < ways; ++r)
             g.p[r] = {x_sh[r], w_keep[r], y_sh[r], send_buf(recv_from[r]), bias_of(r), ldk, ldk, ldn, ldn};
         ScopedTimer t(c, JG_KERNEL_GEMM);
-        return HIP_OK(jg::launch_gemm_group(g, c->stream)) ? JG_OK : JG_E_HIP;
+        return HIP_OK(jg::launch_gemm_group(g, jg::kGemmNT, c->stream)) ? JG_OK : JG_E_HIP;
     }
     for (int r = 0; r < ways; ++r)
         g.p[r] = {x_sh[r], w_keep[r], kept_buf(r), nullptr, nullptr, ldk, ldk, ldn, 0};
     {
         ScopedTimer t(c, JG_KERNEL_GEMM);
-        if (!HIP_OK(jg::launch_gemm_group(g, c->stream))) return JG_E_HIP;
+        if (!HIP_OK(jg::launch_gemm_group(g, jg::kGemmNT, c->stream))) return JG_E_HIP;
     }
     jg::CombineGroup cb;
     std::memset(&cb, 0, sizeof(cb));
@@ -477,6 +522,101 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
         cb.b[r] = {kept_buf(r), send_buf(recv_from[r]), bias_of(r), y_sh[r]};
     ScopedTimer t(c, JG_KERNEL_COMBINE);
     return HIP_OK(jg::launch_combine_group(cb, c->stream)) ? JG_OK : JG_E_HIP;
+}
+
+int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                       const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh,
+                       void* workspace, size_t workspace_bytes)
+{
+    if (!plan || !plan->ctx) return JG_E_NULL;
+    const jg_linear_desc& d = plan->d;
+    const int ways = d.ways;
+    if (int rc = check_ptr_array(x_sh, ways)) return rc;
+    if (int rc = check_ptr_array(w_sh, ways)) return rc;
+    if (int rc = check_ptr_array(dy_sh, ways)) return rc;
+    if (int rc = check_ptr_array(dx_sh, ways)) return rc;
+    if (int rc = check_ptr_array(dw_sh, ways)) return rc;
+    if (plan->bw_ws_bytes > 0) {
+        if (!workspace || workspace_bytes < plan->bw_ws_bytes) return JG_E_WORKSPACE;
+        if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
+    }
+    jg_ctx* c = plan->ctx;
+    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    char* ws = static_cast<char*>(workspace);
+
+    // shard shapes: X_r is mr x kh, W_r is (wr) x kh, dY_r is mr x nh
+    const int mr = (int)plan->xr, kh = (int)plan->xc, nh = (int)plan->yc;
+    const int64_t wblock = (int64_t)nh * kh;   // floats in one nh x kh weight block
+
+    jg::GemmGroup g;
+    std::memset(&g, 0, sizeof(g));
+
+    auto launch = [&](int layout, int kernel_class) -> bool {
+        ScopedTimer t(c, kernel_class);
+        return HIP_OK(jg::launch_gemm_group(g, layout, c->stream));
+    };
+
+    if (ways == 1) {
+        // dX [M x K] = dY [M x N] . W [N x K]: contraction over N, W read K-strided
+        g.nprob = 1; g.M = mr; g.N = kh; g.K = nh;
+        g.p[0] = {dy_sh[0], w_sh[0], dx_sh[0], nullptr, nullptr, nh, kh, kh, 0};
+        if (!launch(jg::kGemmNN, JG_KERNEL_GEMM_DX)) return JG_E_HIP;
+        // dW [N x K] = dY^T . X: contraction over M, both operands read K-strided
+        g.M = nh; g.N = kh; g.K = mr;
+        g.p[0] = {dy_sh[0], x_sh[0], dw_sh[0], nullptr, nullptr, nh, kh, kh, 0};
+        return launch(jg::kGemmTN, JG_KERNEL_GEMM_DW) ? JG_OK : JG_E_HIP;
+    }
+
+    auto dx_part = [&](int r) { return reinterpret_cast<float*>(ws + r * plan->bw_dx_bytes); };
+    auto dw_part = [&](int r) { return reinterpret_cast<float*>(ws + plan->bw_off_dw + r * plan->bw_dw_bytes); };
+
+    if (ways == 2) {
+        // W_r = [W_{r,0}; W_{r,1}] by rows.  dX_r = dY_r W_{r,r} + dY_{1-r} W_{r,1-r}.
+        g.nprob = 2; g.M = mr; g.N = kh; g.K = nh;
+        for (int r = 0; r < 2; ++r)     // the product with the peer's dY half -> partial
+            g.p[r] = {dy_sh[1 - r], w_sh[r] + (1 - r) * wblock, dx_part(r), nullptr, nullptr, nh, kh, kh, 0};
+        if (!launch(jg::kGemmNN, JG_KERNEL_GEMM_DX)) return JG_E_HIP;
+        for (int r = 0; r < 2; ++r)     // the product with the rank's own dY half, on top of it
+            g.p[r] = {dy_sh[r], w_sh[r] + r * wblock, dx_sh[r], dx_part(r), nullptr, nh, kh, kh, kh};
+        if (!launch(jg::kGemmNN, JG_KERNEL_GEMM_DX)) return JG_E_HIP;
+        // dW_{r,c} = dY_c^T X_r: one product per block, four blocks in one launch
+        g.nprob = 4; g.M = nh; g.N = kh; g.K = mr;
+        for (int r = 0; r < 2; ++r)
+            for (int cc = 0; cc < 2; ++cc)
+                g.p[2 * r + cc] = {dy_sh[cc], x_sh[r], dw_sh[r] + cc * wblock, nullptr, nullptr, nh, kh, kh, 0};
+        return launch(jg::kGemmTN, JG_KERNEL_GEMM_DW) ? JG_OK : JG_E_HIP;
+    }
+
+    // 4-way: block (row half i, column half j) lives on rank 2 i + j, for X, W, dY, dX and dW alike.
+    auto rk = [](int a, int b) { return 2 * a + b; };
+    // dX_(i,j) = dY_(i,0) W_(0,j) + dY_(i,1) W_(1,j); the rank's own dY block is dY_(i,j)
+    g.nprob = 4; g.M = mr; g.N = kh; g.K = nh;
+    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j) {   // the term with the row neighbour's dY block -> partial
+            const int r = rk(i, j), cc = 1 - j;
+            g.p[r] = {dy_sh[rk(i, cc)], w_sh[rk(cc, j)], dx_part(r), nullptr, nullptr, nh, kh, kh, 0};
+        }
+    if (!launch(jg::kGemmNN, JG_KERNEL_GEMM_DX)) return JG_E_HIP;
+    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j) {   // the term with the rank's own dY block, on top of it
+            const int r = rk(i, j), cc = j;
+            g.p[r] = {dy_sh[rk(i, cc)], w_sh[rk(cc, j)], dx_sh[r], dx_part(r), nullptr, nh, kh, kh, kh};
+        }
+    if (!launch(jg::kGemmNN, JG_KERNEL_GEMM_DX)) return JG_E_HIP;
+    // dW_(c,j) = dY_(0,c)^T X_(0,j) + dY_(1,c)^T X_(1,j); rank (c,j) holds X_(c,j)
+    g.M = nh; g.N = kh; g.K = mr;
+    for (int cc = 0; cc < 2; ++cc)
+        for (int j = 0; j < 2; ++j) {   // the term formed on the column neighbour (row half 1 - c) -> partial
+            const int r = rk(cc, j), i = 1 - cc;
+            g.p[r] = {dy_sh[rk(i, cc)], x_sh[rk(i, j)], dw_part(r), nullptr, nullptr, nh, kh, kh, 0};
+        }
+    if (!launch(jg::kGemmTN, JG_KERNEL_GEMM_DW)) return JG_E_HIP;
+    for (int cc = 0; cc < 2; ++cc)
+        for (int j = 0; j < 2; ++j) {   // the term with the rank's own X block, on top of it
+            const int r = rk(cc, j), i = cc;
+            g.p[r] = {dy_sh[rk(i, cc)], x_sh[rk(i, j)], dw_sh[r], dw_part(r), nullptr, nh, kh, kh, kh};
+        }
+    return launch(jg::kGemmTN, JG_KERNEL_GEMM_DW) ? JG_OK : JG_E_HIP;
 }
 
 }  // extern "C"

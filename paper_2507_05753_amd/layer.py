@@ -58,6 +58,38 @@ class JigsawLinear:
         jg.jg_gather(self.plan, [t.data_ptr() for t in self.y], out.data_ptr(), out.stride(0))
         return out
 
+    # -- backward ---------------------------------------------------------------
+    def alloc_backward(self):
+        """Shard tensors for dY (like Y), dX (like X), dW (like W) and the backward workspace."""
+        if getattr(self, "dy", None) is None:
+            self.dy = [torch.empty_like(t) for t in self.y]
+            self.dx = [torch.empty_like(t) for t in self.x]
+            self.dw = [torch.empty_like(t) for t in self.w]
+            self.bw_ws_bytes = self.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES)
+            self.bw_ws = torch.empty((max(self.bw_ws_bytes, 1),), dtype=torch.uint8, device=self.dev)
+
+    def shard_dy(self, dY):
+        assert dY.is_cuda and dY.dtype == torch.float32 and dY.shape == (self.M, self.N) and dY.stride(1) == 1
+        self.alloc_backward()
+        jg.jg_shard(self.plan, jg.JG_T_Y, dY.data_ptr(), dY.stride(0), [t.data_ptr() for t in self.dy])
+
+    def backward(self):
+        self.alloc_backward()
+        jg.jg_linear_backward(self.plan, [t.data_ptr() for t in self.x], [t.data_ptr() for t in self.w],
+                              [t.data_ptr() for t in self.dy], [t.data_ptr() for t in self.dx],
+                              [t.data_ptr() for t in self.dw],
+                              self.bw_ws.data_ptr() if self.bw_ws_bytes else None, self.bw_ws_bytes)
+
+    def gather_dx(self):
+        out = torch.empty((self.M, self.K), dtype=torch.float32, device=self.dev)
+        jg.jg_gather_as(self.plan, jg.JG_T_X, [t.data_ptr() for t in self.dx], out.data_ptr(), out.stride(0))
+        return out
+
+    def gather_dw(self):
+        out = torch.empty((self.N, self.K), dtype=torch.float32, device=self.dev)
+        jg.jg_gather_as(self.plan, jg.JG_T_W, [t.data_ptr() for t in self.dw], out.data_ptr(), out.stride(0))
+        return out
+
     def query(self, what: int, rank: int = 0) -> int:
         return jg.jg_plan_query(self.plan, what, rank)
 

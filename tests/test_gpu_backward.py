@@ -1,0 +1,139 @@
+"""GPU parity of the backward pass (dX = dY W, dW = dY^T X) against the CPU oracle, element by
+element, through the C ABI.  Same bars as the forward: 1e-6 of the magnitude of what is summed
+(|dY| |W| and |dY|^T |X|), bit-exact on lattice inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2507_05753_amd import inputs
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def jg():
+    from paper_2507_05753_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ctx(jg):
+    c = jg.jg_init(0, torch.cuda.current_stream().cuda_stream)
+    yield c
+    torch.cuda.synchronize()
+    jg.jg_free(c)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def triple(seed, M, K, N, mode="R"):
+    X, W, _ = inputs.layer_inputs(seed, M, K, N, mode)
+    dY = inputs.matrix(seed + 3000, M, N, "L" if mode == "L" else "R")
+    return X, W, dY
+
+
+def run_backward(ctx, X, W, dY, ways):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    M, K = X.shape
+    N = W.shape[0]
+    with JigsawLinear(M, K, N, ways, ctx=ctx) as L:
+        L.alloc_backward()
+        if L.bw_ws_bytes:
+            L.bw_ws.fill_(0xFF)                 # NaN pattern: stale workspace contents must not matter
+        for t in L.dx + L.dw:
+            t.fill_(float("nan"))
+        L.shard(dev(X), dev(W))
+        L.shard_dy(dev(dY))
+        L.backward()
+        dX, dW = L.gather_dx(), L.gather_dw()
+        torch.cuda.synchronize()
+        dy_shards = [t.cpu().numpy() for t in L.dy]
+        return dX.cpu().numpy(), dW.cpu().numpy(), dy_shards
+
+
+SHAPES = [
+    (100, 100, 100),     # config 1: halves of 50 are not multiples of 4 (guarded kernels)
+    (2, 2, 2),
+    (130, 72, 258),      # ragged tiles in every dimension
+    (258, 200, 136),
+    (64, 520, 640),
+    (300, 1032, 260),    # long contraction for dX (N) ... and below for dW (M)
+    (2200, 136, 72),
+    (1000, 1000, 1000),  # config 2
+]
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,K,N", SHAPES)
+def test_backward_matches_oracle_within_tolerance(jg, ctx, ways, M, K, N):
+    X, W, dY = triple(41, M, K, N)
+    dX, dW, dy_sh = run_backward(ctx, X, W, dY, ways)
+    for got, want in zip(dy_sh, oracle.shard_y(dY, ways)):     # dY is partitioned like Y
+        assert np.array_equal(got, want)
+    dX64, dW64 = oracle.backward(X, W, dY)
+    SX, SW = oracle.backward_magnitude(X, W, dY)
+    ex, ew = np.abs(dX - dX64), np.abs(dW - dW64)
+    assert np.all(ex <= TOL * SX), f"dX max err/S = {(ex / SX).max():.3e}"
+    assert np.all(ew <= TOL * SW), f"dW max err/S = {(ew / SW).max():.3e}"
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,K,N", SHAPES)
+def test_backward_lattice_inputs_are_bit_exact(jg, ctx, ways, M, K, N):
+    X, W, dY = triple(43, M, K, N, "L")
+    dX, dW, _ = run_backward(ctx, X, W, dY, ways)
+    dX64, dW64 = oracle.backward(X, W, dY)
+    assert np.array_equal(dX.astype(np.float64), dX64)
+    assert np.array_equal(dW.astype(np.float64), dW64)
+    gX, gW = oracle.jigsaw_backward(ways, X, W, dY)              # the block-wise route reaches the same bits
+    assert np.array_equal(dX.astype(np.float64), gX) and np.array_equal(dW.astype(np.float64), gW)
+
+
+def test_backward_is_the_adjoint_of_the_gpu_forward(jg, ctx):
+    """<dY, forward(X', W)> = <dX, X'> with both sides from the GPU path (lattice inputs: exact)."""
+    from paper_2507_05753_amd.layer import JigsawLinear
+    M, K, N = 258, 200, 136
+    X, W, dY = triple(47, M, K, N, "L")
+    Xp = inputs.matrix(48, M, K, "L")
+    for ways in (1, 2, 4):
+        dX, dW, _ = run_backward(ctx, X, W, dY, ways)
+        with JigsawLinear(M, K, N, ways, ctx=ctx) as L:
+            L.shard(dev(Xp), dev(W))
+            L.forward()
+            Yp = L.gather().cpu().numpy()
+        assert np.sum(dY.astype(np.float64) * Yp) == np.sum(dX.astype(np.float64) * Xp)
+
+
+def test_backward_error_paths(jg, ctx):
+    import ctypes
+    lib = jg.raw()
+    plan = jg.jg_plan_create(ctx, 64, 64, 64, 4)
+    t = torch.zeros(64 * 64, dtype=torch.float32, device="cuda")
+    good = [t.data_ptr()] * 4
+    need = jg.jg_plan_query(plan, jg.JG_Q_BACKWARD_WORKSPACE_BYTES)
+    assert need >= 4 * (64 * 64 + 64 * 64)     # one partial per dX and per dW element
+    ws = torch.zeros(need + 256, dtype=torch.uint8, device="cuda")
+    base = (ws.data_ptr() + 255) // 256 * 256
+
+    def arr(ptrs):
+        a = (ctypes.c_void_p * len(ptrs))(*ptrs)
+        return ctypes.cast(a, ctypes.POINTER(ctypes.c_void_p))
+
+    bwd = lib.jg_linear_backward
+    assert bwd(plan, arr(good), arr(good), None, arr(good), arr(good), base, need) == jg.JG_E_NULL
+    assert bwd(plan, arr(good), arr(good), arr(good), arr(good), arr(good), None, need) == jg.JG_E_WORKSPACE
+    assert bwd(plan, arr(good), arr(good), arr(good), arr(good), arr(good), base, need - 1) == jg.JG_E_WORKSPACE
+    assert bwd(plan, arr(good), arr(good), arr(good), arr(good), arr(good), base + 4, need) == jg.JG_E_ALIGN
+    assert bwd(None, arr(good), arr(good), arr(good), arr(good), arr(good), base, need) == jg.JG_E_NULL
+    assert lib.jg_gather_as(plan, 9, arr(good), t.data_ptr(), 64) == jg.JG_E_DTYPE
+    assert lib.jg_gather_as(plan, jg.JG_T_X, arr(good), t.data_ptr(), 63) == jg.JG_E_SHAPE
+    jg.jg_plan_destroy(plan)
+    one = jg.jg_plan_create(ctx, 64, 64, 64, 1)
+    assert jg.jg_plan_query(one, jg.JG_Q_BACKWARD_WORKSPACE_BYTES) == 0
+    assert jg.jg_plan_query(one, jg.JG_Q_BACKWARD_FLOPS_TOTAL) == 4 * 64 ** 3
+    jg.jg_plan_destroy(one)
+    torch.cuda.synchronize()
