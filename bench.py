@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--ways", type=int, default=4, choices=[1, 2, 4])
+    ap.add_argument("--op", choices=["forward", "backward"], default="forward",
+                    help="forward: Y = X W^T (the headline); backward: dX = dY W and dW = dY^T X")
     ap.add_argument("--combine", choices=["fused", "separate"], default="fused")
     ap.add_argument("--weights", choices=["copy", "direct"], default="copy")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
@@ -143,6 +145,71 @@ def measure(cfg, ways, args, X, W, streaming=False):
     return out
 
 
+def measure_backward(cfg, ways, args, X, W):
+    """One step = one jg_linear_backward (dX and dW of all ranks), shards resident in HBM."""
+    import torch
+    from paper_2507_05753_amd import binding as jg
+    from paper_2507_05753_amd import inputs
+    from paper_2507_05753_amd.layer import JigsawLinear
+    M, K, N = cfg["M"], cfg["K"], cfg["N"]
+    dY = inputs.matrix_torch(cfg["seed"] + 3000, M, N, "R", 0, device=X.device)
+    with JigsawLinear(M, K, N, ways) as L:
+        L.shard(X, W)
+        L.shard_dy(dY)
+        del dY
+        for _ in range(args.warmup):
+            L.backward()
+        torch.cuda.synchronize()
+        for k in (jg.JG_KERNEL_GEMM_DX, jg.JG_KERNEL_GEMM_DW):
+            jg.jg_profile_read(L.ctx, k)
+        jg.jg_profile(L.ctx, True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            L.backward()
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / args.steps
+        jg.jg_profile(L.ctx, False)
+        dx_ms, dx_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_GEMM_DX)
+        dw_ms, dw_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_GEMM_DW)
+        flops = L.query(jg.JG_Q_BACKWARD_FLOPS_TOTAL)
+        half = flops / 2   # dX and dW cost the same
+        kernels = {
+            "dx": dict(kernel="jg::gemm_f32_stream<false, true>", avg_launch_ms=dx_ms / max(dx_n, 1), launches=dx_n,
+                       tflops=half * args.steps / (dx_ms * 1e-3) / 1e12),
+            "dw": dict(kernel="jg::gemm_f32_stream<true, true>", avg_launch_ms=dw_ms / max(dw_n, 1), launches=dw_n,
+                       tflops=half * args.steps / (dw_ms * 1e-3) / 1e12),
+        }
+        ws = L.bw_ws_bytes
+    torch.cuda.empty_cache()
+    return dict(ms_per_step=sec * 1e3, items_per_s=M * K / sec, tflops=flops / sec / 1e12, kernels=kernels,
+                workspace_bytes=ws)
+
+
+def cpu_baseline_backward(cfg, seconds):
+    """The backward oracle timed on a bounded row sample (dX rows and the matching share of dW)."""
+    import oracle
+    from paper_2507_05753_amd import inputs
+    M, K, N, seed = cfg["M"], cfg["K"], cfg["N"], cfg["seed"]
+    cores = min(oracle.host_threads(), 16)
+    W = inputs.matrix(seed + inputs.W_STREAM, N, K, "R", inputs.W_SCALE_EXP)
+
+    def run(rows):
+        X = inputs.matrix(seed, M, K, cfg["x_mode"], row_begin=0, row_end=rows)
+        dY = inputs.matrix(seed + 3000, M, N, "R", row_begin=0, row_end=rows)
+        t0 = time.perf_counter()
+        oracle.backward(X, W, dY, nthreads=cores)
+        return time.perf_counter() - t0
+
+    probe = min(M, 4 * cores)
+    rate = probe / max(run(probe), 1e-9)
+    rows = int(min(M, max(probe, rate * seconds)))
+    dt = run(rows)
+    return dict(value=rows * K / dt, unit="items/s", cores=cores, kind="oracle",
+                sample=f"dX and dW from rows 0..{rows - 1} of X and dY ({rows} x {K}, {rows} x {N}) and all of W, "
+                       f"{dt:.1f} s, fp64 loops")
+
+
 def cpu_baseline(cfg, seconds):
     """The oracle as it stands, timed on a bounded sample of rows of the same workload."""
     import numpy as np
@@ -194,6 +261,32 @@ def main():
     M, K, N = cfg["M"], cfg["K"], cfg["N"]
     dev = torch.device("cuda", 0)
     X, W = make_inputs(cfg, dev)
+
+    if args.op == "backward":
+        bw = measure_backward(cfg, args.ways, args, X, W)
+        del X, W
+        torch.cuda.empty_cache()
+        dom = max(bw["kernels"].values(), key=lambda k: k["avg_launch_ms"] * k["launches"])
+        line = {
+            "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
+            "value": bw["items_per_s"], "unit": "items/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": bw["ms_per_step"], "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"config {args.config}: dX = dY W and dW = dY^T X, M={M} K={K} N={N}, "
+                                   f"{args.ways}-way Jigsaw backward, fp32",
+                       "n_items": M * K, "ways": args.ways, "M": M, "K": K, "N": N, "seed": cfg["seed"],
+                       "x_values": cfg["x_mode"], "op": "backward"},
+            "tflops": bw["tflops"],
+            "roofline": {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["tflops"],
+                         "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": dom["tflops"] / FP32_MFMA_PEAK_TFLOPS, "avg_launch_ms": dom["avg_launch_ms"],
+                         "launches": dom["launches"], "traffic": None},
+            "kernels": bw["kernels"],
+        }
+        if args.cpu_seconds > 0:
+            line["cpu_baseline"] = cpu_baseline_backward(cfg, args.cpu_seconds)
+        print(json.dumps(line), flush=True)
+        return
 
     head = measure(cfg, args.ways, args, X, W, streaming=not args.only_headline)
     by_ways = {}

@@ -291,12 +291,14 @@ struct StreamLoader {
     __amdgpu_buffer_rsrc_t rsrc;        // KC: the tile's rows; KS: rebuilt for every slab
     const float* tile_base;             // KS: element (origin, k = 0)
     int ld, K, valid;                   // valid = rows-of-C of this tile inside the operand
+    int kt_ragged;                      // KC: the slab that needs the zero fill, or -1
 
     __device__ __forceinline__ void init(const OperandView& v, int K_, int wave, int lane)
     {
         ld = v.ld;
         K = K_;
         valid = min(BM, v.extent - v.origin);
+        kt_ragged = (K % BK) ? K / BK : -1;
         if (KS) {
             tile_base = v.base + v.origin;
 #pragma unroll
@@ -338,7 +340,7 @@ struct StreamLoader {
                                                          16, voff[p], 0, 0, 0);
         } else {
             const int soff = kt * BK * 4;
-            if (kt * BK + BK > K) {      // ragged last slab: chunks at or past column K read as zero
+            if (kt == kt_ragged) {       // ragged last slab: chunks at or past column K read as zero
                 const int k_left = K - kt * BK;
 #pragma unroll
                 for (int p = 0; p < 4; ++p)
