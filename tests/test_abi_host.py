@@ -96,6 +96,12 @@ def test_accounting(ways, M, K, N):
                 assert q(jg.JG_Q_EXCHANGE_BYTES_RANK, 1) == 4 * M * N // 2
             else:
                 assert q(jg.JG_Q_EXCHANGE_BYTES_RANK, 3) == 4 * (M * N // 4 + N * K // 4)
+        # backward: twice the forward work (Sec. 6.3); one partial per dX element, and per dW element in 4-way
+        assert q(jg.JG_Q_BACKWARD_FLOPS_TOTAL) == 4 * M * K * N
+        assert q(jg.JG_Q_BACKWARD_GEMM_LAUNCHES) == {1: 2, 2: 3, 4: 4}[ways]
+        bw = q(jg.JG_Q_BACKWARD_WORKSPACE_BYTES)
+        need = 0 if ways == 1 else 4 * M * K + (4 * N * K if ways == 4 else 0)
+        assert need <= bw <= need + 2 * ways * 256
         with pytest.raises(jg.JigsawError) as e:
             q(jg.JG_Q_X_ROWS, ways)
         assert e.value.status == jg.JG_E_WAYS
@@ -126,6 +132,8 @@ def test_data_calls_refuse_a_plan_without_context():
     assert lib.jg_linear_forward(p, pp, pp, None, pp, 256, 1 << 20) == jg.JG_E_NULL
     assert lib.jg_shard(p, jg.JG_T_X, 256, 8, pp) == jg.JG_E_NULL
     assert lib.jg_gather(p, pp, 256, 8) == jg.JG_E_NULL
+    assert lib.jg_gather_as(p, jg.JG_T_W, pp, 256, 8) == jg.JG_E_NULL
+    assert lib.jg_linear_backward(p, pp, pp, pp, pp, pp, 256, 1 << 20) == jg.JG_E_NULL
     assert lib.jg_linear_forward(None, pp, pp, None, pp, 256, 1 << 20) == jg.JG_E_NULL
     jg.jg_plan_destroy(p)
 

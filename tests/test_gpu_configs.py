@@ -135,3 +135,78 @@ def test_config_5_largest_instance(capsys):
     assert np.array_equal(X[rows], inputs.matrix_rows(seed, K, rows, "R"))   # host generator agrees
     W = inputs.matrix(seed + inputs.W_STREAM, N, K, "R", inputs.W_SCALE_EXP)
     run_config(capsys, 5, X, Xd, W, n_rows=2000, n_cols_per_row=250)
+
+
+# --------------------------------------------------------------------------------------------
+# backward pass at full size
+# --------------------------------------------------------------------------------------------
+def index_set(seed, n, extent):
+    """n seeded indices in [0, extent) plus the edges and the block boundary."""
+    k = inputs.keys(seed, np.arange(n, dtype=np.uint64))
+    fixed = [0, extent // 2 - 1, extent // 2, extent - 1]
+    return np.unique(np.concatenate([(k % np.uint64(extent)).astype(np.int64), np.array(fixed, np.int64)]))
+
+
+def run_backward_config(capsys, cfg_id, X_host, X_dev, W_host, dY_host, dY_dev, n_idx):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    cfg = inputs.CONFIGS[cfg_id]
+    M, K, N = cfg["M"], cfg["K"], cfg["N"]
+    W_dev = torch.from_numpy(W_host).cuda()
+    V = pm1(3000 + cfg_id, K, 3)
+    t0 = time.time()
+    dXv, bX, dWv, bW = oracle.freivalds_backward(X_host, W_host, dY_host, V)
+    note(capsys, f"config {cfg_id} backward: Freivalds reference done in {time.time() - t0:.1f} s")
+    I, J, Ks = index_set(4000 + cfg_id, n_idx, M), index_set(4100 + cfg_id, n_idx, N), index_set(4200 + cfg_id, n_idx, K)
+    # dX[i, k] = <dY[i, :], W[:, k]>,   dW[j, k] = <dY[:, j], X[:, k]>
+    gi, gk = np.meshgrid(np.arange(I.size), np.arange(Ks.size), indexing="ij")
+    dx_want, dx_mag = oracle.entries(dY_host[I], np.ascontiguousarray(W_host[:, Ks].T), gi.ravel(), gk.ravel())
+    gj, gk2 = np.meshgrid(np.arange(J.size), np.arange(Ks.size), indexing="ij")
+    dw_want, dw_mag = oracle.entries(np.ascontiguousarray(dY_host[:, J].T), np.ascontiguousarray(X_host[:, Ks].T),
+                                     gj.ravel(), gk2.ravel())
+    for ways in (1, 2, 4):
+        with JigsawLinear(M, K, N, ways) as L:
+            L.alloc_backward()
+            if L.bw_ws_bytes:
+                L.bw_ws.fill_(0xFF)
+            L.shard(X_dev, W_dev)
+            L.shard_dy(dY_dev)
+            L.backward()
+            dXd, dWd = L.gather_dx(), L.gather_dw()
+            torch.cuda.synchronize()
+            dX, dW = dXd.cpu().numpy(), dWd.cpu().numpy()
+            del dXd, dWd
+        torch.cuda.empty_cache()
+        assert np.isfinite(dX).all() and np.isfinite(dW).all()
+        ex, ew = np.abs(project(dX, V) - dXv), np.abs(project(dW, V) - dWv)
+        assert np.all(ex <= TOL * bX), f"ways={ways}: dX Freivalds worst {(ex / bX).max():.3e}"
+        assert np.all(ew <= TOL * bW), f"ways={ways}: dW Freivalds worst {(ew / bW).max():.3e}"
+        e1 = np.abs(dX[np.ix_(I, Ks)].ravel() - dx_want) / dx_mag
+        e2 = np.abs(dW[np.ix_(J, Ks)].ravel() - dw_want) / dw_mag
+        assert e1.max() <= TOL and e2.max() <= TOL, (ways, e1.max(), e2.max())
+        note(capsys, f"config {cfg_id} backward ways={ways}: Freivalds dX {(ex / bX).max():.2e} dW {(ew / bW).max():.2e}; "
+                     f"{e1.size}+{e2.size} entries max err/S {max(e1.max(), e2.max()):.2e}")
+        del dX, dW
+
+
+@pytest.mark.timeout(300)
+def test_config_3_backward(capsys):
+    cfg = inputs.CONFIGS[3]
+    M, K, N, seed = cfg["M"], cfg["K"], cfg["N"], cfg["seed"]
+    X = inputs.matrix(seed, M, K, "R")
+    W = inputs.matrix(seed + inputs.W_STREAM, N, K, "R", inputs.W_SCALE_EXP)
+    dYd = inputs.matrix_torch(seed + 3000, M, N, "R", device="cuda")
+    dY = dYd.cpu().numpy()
+    run_backward_config(capsys, 3, X, torch.from_numpy(X).cuda(), W, dY, dYd, n_idx=300)
+
+
+@pytest.mark.timeout(900)
+def test_config_5_backward(capsys):
+    cfg = inputs.CONFIGS[5]
+    M, K, N, seed = cfg["M"], cfg["K"], cfg["N"], cfg["seed"]
+    Xd = inputs.matrix_torch(seed, M, K, "R", device="cuda")
+    dYd = inputs.matrix_torch(seed + 3000, M, N, "R", device="cuda")
+    torch.cuda.synchronize()
+    X, dY = Xd.cpu().numpy(), dYd.cpu().numpy()
+    W = inputs.matrix(seed + inputs.W_STREAM, N, K, "R", inputs.W_SCALE_EXP)
+    note(capsys, "config 5 backward: inputs ready")
+    run_backward_config(capsys, 5, X, Xd, W, dY, dYd, n_idx=120)
