@@ -320,7 +320,7 @@ def main():
         "hbm_algo_gbps": head["hbm_algo_gbps"],
         "hbm_algo_frac_of_8TBps": head["hbm_algo_frac"],
         "roofline": {
-            "bound": "mfma", "kernel": "jg::gemm_nt_f32_stream",
+            "bound": "mfma", "kernel": "jg::gemm_f32_stream<false, false>",
             "achieved": achieved, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": achieved / FP32_MFMA_PEAK_TFLOPS if achieved else None,
             "avg_launch_ms": head["gemm_avg_launch_ms"], "launches": head["gemm_launches_timed"],

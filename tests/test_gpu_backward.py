@@ -137,3 +137,30 @@ def test_backward_error_paths(jg, ctx):
     assert jg.jg_plan_query(one, jg.JG_Q_BACKWARD_FLOPS_TOTAL) == 4 * 64 ** 3
     jg.jg_plan_destroy(one)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("M,K,N,ways", [(1, 1, 1, 1), (1, 2, 2, 2), (2, 2, 2, 4), (2, 4096, 2, 2), (4098, 2, 4, 4),
+                                         (3, 5, 7, 1), (129, 4, 132, 1), (128, 128, 128, 1), (256, 256, 256, 4)])
+def test_backward_degenerate_and_exact_tile_shapes(jg, ctx, M, K, N, ways):
+    X, W, dY = triple(53, M, K, N, "L")
+    dX, dW, _ = run_backward(ctx, X, W, dY, ways)
+    dX64, dW64 = oracle.backward(X, W, dY)
+    assert np.array_equal(dX.astype(np.float64), dX64) and np.array_equal(dW.astype(np.float64), dW64)
+
+
+def test_backward_leaves_its_inputs_alone_and_is_repeatable(jg, ctx):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    M, K, N = 258, 200, 136
+    X, W, dY = triple(55, M, K, N)
+    with JigsawLinear(M, K, N, 4, ctx=ctx) as L:
+        L.shard(dev(X), dev(W))
+        L.shard_dy(dev(dY))
+        before = [t.clone() for t in L.x + L.w + L.dy]
+        L.backward()
+        a = (L.gather_dx().clone(), L.gather_dw().clone())
+        L.backward()
+        L.backward()
+        c = (L.gather_dx(), L.gather_dw())
+        torch.cuda.synchronize()
+        assert all(torch.equal(p, q) for p, q in zip(before, L.x + L.w + L.dy))
+        assert torch.equal(a[0], c[0]) and torch.equal(a[1], c[1])

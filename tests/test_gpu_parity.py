@@ -244,3 +244,34 @@ def test_profile_counts_launches(jg, ctx):
         assert jg.jg_profile_read(ctx, jg.JG_KERNEL_WEIGHT_COPY)[1] == 3
         assert jg.jg_profile_read(ctx, jg.JG_KERNEL_COMBINE)[1] == 3
         assert jg.jg_profile_read(ctx, jg.JG_KERNEL_GEMM)[1] == 0
+
+
+@pytest.mark.parametrize("M,K,N,ways", [(1, 1, 1, 1), (1, 2, 2, 2), (2, 2, 2, 4), (1, 4096, 2, 2), (4098, 2, 2, 4),
+                                         (3, 5, 7, 1), (129, 4, 129, 1), (128, 32, 128, 1), (256, 64, 128, 4)])
+def test_degenerate_and_exact_tile_shapes(jg, ctx, M, K, N, ways):
+    X, W, b = inputs.layer_inputs(31, M, K, N, "L", bias=True)
+    Y, _ = run_layer(ctx, X, W, b, ways)
+    assert np.array_equal(Y.astype(np.float64), oracle.linear(X, W, b))
+
+
+def test_strided_global_views_and_untouched_inputs(jg, ctx):
+    """jg_shard / jg_gather take a leading dimension: shard from and gather into views of wider
+    matrices; inputs are never written, bytes outside the gathered region are left alone."""
+    from paper_2507_05753_amd.layer import JigsawLinear
+    M, K, N, pad = 130, 72, 136, 12
+    X, W, b = inputs.layer_inputs(33, M, K, N, "L", bias=True)
+    Xw = torch.full((M, K + pad), 7.0, device="cuda"); Xw[:, :K] = dev(X)
+    Ww = torch.full((N, K + pad), 7.0, device="cuda"); Ww[:, :K] = dev(W)
+    Yw = torch.full((M, N + pad), -5.0, device="cuda")
+    for ways in (1, 2, 4):
+        with JigsawLinear(M, K, N, ways, bias=True, ctx=ctx) as L:
+            L.shard(Xw[:, :K], Ww[:, :K], dev(b))
+            x_before = [t.clone() for t in L.x]
+            w_before = [t.clone() for t in L.w]
+            L.forward()
+            L.gather(Yw[:, :N])
+            torch.cuda.synchronize()
+            assert all(torch.equal(a, c) for a, c in zip(x_before, L.x))
+            assert all(torch.equal(a, c) for a, c in zip(w_before, L.w))
+        assert np.array_equal(Yw[:, :N].cpu().numpy().astype(np.float64), oracle.linear(X, W, b))
+        assert torch.all(Yw[:, N:] == -5.0) and torch.all(Xw[:, K:] == 7.0)
