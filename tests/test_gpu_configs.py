@@ -9,7 +9,6 @@ is checked by
 
 Configs 1 and 2 are compared in full in test_gpu_parity.py.
 """
-import os
 import time
 
 import numpy as np
@@ -21,20 +20,12 @@ from paper_2507_05753_amd import inputs
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-6
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def note(capsys, msg):
-    """Progress line that reaches the terminal (and a log file) even under output capture."""
-    line = f"[{time.strftime('%H:%M:%S')}] {msg}"
+    """Progress line that reaches the terminal even under output capture."""
     with capsys.disabled():
-        print(line, flush=True)
-    try:
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "test_progress.log"), "a") as f:
-            f.write(line + "\n")
-    except OSError:
-        pass
+        print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
 
 
 def pm1(seed, n, cols):
