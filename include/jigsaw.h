@@ -124,7 +124,9 @@ void jg_free(jg_ctx* ctx);
 /* build.  Validates `desc` and fixes the block decomposition of Sec. 4.1 / 4.2 for
  * these sizes.  2-way needs even K and N; 4-way needs even M, K and N (the paper's
  * loader zero-pads to make partitions equal, Sec. 5 "Data loading": padding is the
- * caller's job).  Host-only; launches nothing.  `ctx` may be NULL: the plan then
+ * caller's job).  Size limits: each of M, K, N below 2^31 - 1024, and for each pair
+ * of them ceil(a/128) * ceil(b/128) at most (2^31 - 65) / 4 (the tile index of a launch
+ * is 32 bits wide); beyond that JG_E_SHAPE.  Host-only; launches nothing.  `ctx` may be NULL: the plan then
  * serves jg_plan_query only and the data calls return JG_E_NULL.
  * Errors: JG_E_NULL, JG_E_WAYS, JG_E_DTYPE, JG_E_SHAPE (checked in this order). */
 int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out);

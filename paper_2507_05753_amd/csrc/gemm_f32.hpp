@@ -576,6 +576,9 @@ inline hipError_t launch_gemm_group(GemmGroup& g, int layout, hipStream_t stream
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
     const int64_t total = (int64_t)g.nprob * g.tiles_m * g.tiles_n;
+    // The tile index is a 32-bit block id (and the grid is one-dimensional): refuse a product
+    // with more tiles than that instead of wrapping around.
+    if (total + kNumXcd > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     g.per_xcd = (int)((total + kNumXcd - 1) / kNumXcd);
     const bool a_ks = layout == kGemmTN, b_ks = layout != kGemmNT;
     bool stream_ok = true;

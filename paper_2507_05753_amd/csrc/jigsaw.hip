@@ -225,6 +225,13 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     if (d.M > kMaxDim || d.K > kMaxDim || d.N > kMaxDim) return JG_E_SHAPE;
     if (d.ways >= 2 && ((d.K & 1) || (d.N & 1))) return JG_E_SHAPE;
     if (d.ways == 4 && (d.M & 1)) return JG_E_SHAPE;
+    {   // every product of the plan (forward M x N, backward M x K and N x K, up to four
+        // problems a launch) must have a tile count that fits the 32-bit block index
+        const int64_t tm = (d.M + jg::BM - 1) / jg::BM, tn = (d.N + jg::BM - 1) / jg::BM,
+                      tk = (d.K + jg::BM - 1) / jg::BM;
+        const int64_t limit = (0x7fffffffLL - 64) / 4;
+        if (tm * tn > limit || tm * tk > limit || tn * tk > limit) return JG_E_SHAPE;
+    }
 
     jg_plan* p = new (std::nothrow) jg_plan();
     if (!p) return JG_E_HIP;

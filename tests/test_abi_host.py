@@ -46,6 +46,10 @@ def test_plan_validation():
     assert status_of(M=0) == jg.JG_E_SHAPE
     assert status_of(K=-2) == jg.JG_E_SHAPE
     assert status_of(N=2 ** 31) == jg.JG_E_SHAPE
+    # tile counts beyond the 32-bit block index are refused, just below the limit is accepted
+    assert status_of(M=128 * 23171, N=128 * 23171, K=128) == jg.JG_E_SHAPE      # 23171^2 * 4 > 2^31
+    assert status_of(M=128 * 23169, N=128 * 23169, K=128) == jg.JG_OK
+    assert status_of(M=128, N=128 * 23171, K=128 * 23171) == jg.JG_E_SHAPE      # backward dW tiles
     assert status_of(K=7) == jg.JG_E_SHAPE            # 2-way needs even K
     assert status_of(N=7) == jg.JG_E_SHAPE            # ... and even N
     assert status_of(M=7) == jg.JG_OK                 # ... but any M
