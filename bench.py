@@ -238,10 +238,10 @@ def cpu_baseline(cfg, seconds):
 
 # HBM-side bytes per GEMM launch, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by
 # what the same counters read for the plain copy kernel of known size; the runs, the raw readings and
-# the factors are in profiles/gemm_nt_f32_stream_config3_ways4_hbm_counters.md.  Counters cannot be read
+# the factors are in profiles/gemm_f32_stream_forward_config3_ways4_hbm_counters.md.  Counters cannot be read
 # from inside this script, so the figure is quoted, keyed by workload, and is null for the others.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
-    ("config3", 4): 3.84e9,   # reads 3.42 GB (FETCH_SIZE / 0.5065) + writes 0.427 GB (WRITE_SIZE / 1.0018)
+    ("config3", 4): 3.97e9,   # reads 3.54 GB (FETCH_SIZE / 0.5065) + writes 0.429 GB (WRITE_SIZE / 1.0018)
 }
 
 

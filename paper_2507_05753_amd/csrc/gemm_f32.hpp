@@ -115,7 +115,7 @@ struct LaneMap {
     int wave, lane, wm, wn, lr, lk;
     __device__ __forceinline__ void init(int tid)
     {
-        wave = tid >> 6;
+        wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps LDS slot addresses in scalar registers
         lane = tid & 63;
         wm = wave >> 1;      // the wave's 64-row half of the tile
         wn = wave & 1;       // ... and 64-column half
@@ -287,7 +287,7 @@ struct OperandView {
 template <bool KS>
 struct StreamLoader {
     int voff[4];                        // byte offsets of this lane's four chunks
-    int chunk_k[4];                     // KC: first k (within a slab) of each chunk, for the ragged slab
+    int oob[4];                         // KC: kOutOfBuffer for chunks that lie at or past column K in the ragged last slab, else 0
     __amdgpu_buffer_rsrc_t rsrc;        // KC: the tile's rows; KS: rebuilt for every slab
     const float* tile_base;             // KS: element (origin, k = 0)
     int ld, K, valid;                   // valid = rows-of-C of this tile inside the operand
@@ -306,7 +306,7 @@ struct StreamLoader {
                 const int k = (p * 4 + wave) * 2 + (lane >> 5);
                 const int chunk = (lane & 31) ^ (8 * ((k >> 2) & 1));
                 voff[p] = (k * ld + chunk * 4) * 4;
-                chunk_k[p] = 0;
+                oob[p] = 0;
             }
         } else {
 #pragma unroll
@@ -315,7 +315,7 @@ struct StreamLoader {
                 const int chunk = (lane & 7) ^ ((r >> 1) & 7);
                 // rows past the edge are clamped to the last valid row: read but never stored
                 voff[p] = (min(r, valid - 1) * ld + chunk * 4) * 4;
-                chunk_k[p] = chunk * 4;
+                oob[p] = chunk * 4 < K % BK ? 0 : kOutOfBuffer;
             }
             // base = first row of the tile, extent = up to the end of its last valid row: an
             // out-of-range offset reads zero instead of faulting
@@ -324,8 +324,13 @@ struct StreamLoader {
                                                      (int)bytes, kBufferRsrcFlags);
         }
     }
-    // asynchronous: the data is in LDS once this thread's vmcnt has drained and a barrier passed
-    __device__ __forceinline__ void request(int kt, float* operand_slab, int wave)
+    // Requests are asynchronous: the data is in LDS once this thread's vmcnt has drained and a
+    // barrier has passed.  begin(kt) fixes the slab; issue(p) then enqueues the p-th of this
+    // lane's four 16-byte transfers.  They are separate calls because the kernel spreads the
+    // transfers between its MFMAs: issued back to back they hold up the matrix pipe.
+    int soff;                           // KC: byte offset of the slab inside a row
+    int ragged_mask;                    // KC: all ones while the ragged last slab is being requested, else 0
+    __device__ __forceinline__ void begin(int kt)
     {
         if (KS) {
             // buffer over the k rows of this slab that exist; rows past K and columns past the
@@ -334,26 +339,25 @@ struct StreamLoader {
             const int64_t bytes = ((int64_t)(rows - 1) * ld + valid) * 4;
             rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(tile_base + (int64_t)kt * BK * ld), 0,
                                                      (int)bytes, kBufferRsrcFlags);
-#pragma unroll
-            for (int p = 0; p < 4; ++p)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(operand_slab + (p * 4 + wave) * 256),
-                                                         16, voff[p], 0, 0, 0);
+            soff = 0;
+            ragged_mask = 0;
         } else {
-            const int soff = kt * BK * 4;
-            if (kt == kt_ragged) {       // ragged last slab: chunks at or past column K read as zero
-                const int k_left = K - kt * BK;
-#pragma unroll
-                for (int p = 0; p < 4; ++p)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                        rsrc, (lds_void*)(operand_slab + (p * 4 + wave) * 256), 16,
-                        chunk_k[p] < k_left ? voff[p] : kOutOfBuffer, soff, 0, 0);
-            } else {
-#pragma unroll
-                for (int p = 0; p < 4; ++p)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                        rsrc, (lds_void*)(operand_slab + (p * 4 + wave) * 256), 16, voff[p], soff, 0, 0);
-            }
+            soff = kt * BK * 4;
+            ragged_mask = kt == kt_ragged ? -1 : 0;
         }
+    }
+    __device__ __forceinline__ void issue(int p, float* operand_slab, int wave) const
+    {
+        // in the ragged slab the chunks past column K get an offset beyond the buffer and read as zero
+        const int off = KS ? voff[p] : (voff[p] | (oob[p] & ragged_mask));
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(operand_slab + (p * 4 + wave) * 256), 16, off, soff,
+                                                 0, 0);
+    }
+    __device__ __forceinline__ void request(int kt, float* operand_slab, int wave)
+    {
+        begin(kt);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) issue(p, operand_slab, wave);
     }
 };
 
@@ -444,11 +448,39 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGro
     floatx16 acc[2][2], sum[2][2];
     float4 fa[2][2], fb[2][2];   // two register sets of MFMA operands (even / odd k-group)
 
+    // The 16 MFMAs of one k-group; when `requesting`, this lane's eight transfers of slab
+    // `kt_req` into `slab` go out between them, one after every second MFMA.  Issued in a
+    // burst, the transfers keep the matrix pipe waiting measurably longer.
+    auto mfma_group_requesting = [&](const float4 (&a)[2], const float4 (&b)[2], bool requesting, int kt_req,
+                                     float* slab) {
+        const float av[2][4] = {{a[0].x, a[0].y, a[0].z, a[0].w}, {a[1].x, a[1].y, a[1].z, a[1].w}};
+        const float bv[2][4] = {{b[0].x, b[0].y, b[0].z, b[0].w}, {b[1].x, b[1].y, b[1].z, b[1].w}};
+        if (requesting) {
+            load_a.begin(kt_req);
+            load_b.begin(kt_req);
+        }
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][tt], bv[j][tt], acc[i][j], 0, 0, 0);
+                    const int idx = tt * 4 + i * 2 + j;
+                    if ((idx & 1) == 0 && requesting) {
+                        if (idx < 8) load_a.issue(idx >> 1, slab, L.wave);
+                        else load_b.issue((idx >> 1) & 3, slab + OPERAND_FLOATS, L.wave);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+    };
+
     // One slab: inside it the operands of k-group kk + 1 are requested before the 16 MFMAs of
     // group kk are issued, so LDS latency hides behind about a thousand matrix-pipe cycles.
-    // The slab boundary (wait for the next slab, barrier, request the slab after next, first
-    // operand read of the next slab) sits before the LAST group's MFMAs for the same reason.
-    // The scheduling fences keep the compiler from undoing this order.
+    // The slab boundary (wait for the next slab, barrier, first operand read of the next slab)
+    // sits before the LAST group's MFMAs for the same reason, and the requests for the slab
+    // after next go out between those MFMAs.  The scheduling fences keep the compiler from
+    // undoing this order.
     auto step = [&](int kt, float* cur, const float* nxt) {
 #pragma unroll
         for (int kk = 0; kk < 3; ++kk) {
@@ -459,10 +491,9 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGro
         }
         JG_WAIT_VMCNT(0);   // this thread's part of slab kt + 1 has landed
         __syncthreads();    // ... and everyone's; all waves hold their last operands of slab kt
-        if (kt + 2 < nkt) request_slab(kt + 2, cur);
         if (kt + 1 < nkt) read_frags(nxt, 0, fa[0], fb[0]);
         __builtin_amdgcn_sched_barrier(0);
-        mfma_group(acc, fa[1], fb[1]);
+        mfma_group_requesting(fa[1], fb[1], kt + 2 < nkt, kt + 2, cur);
         __builtin_amdgcn_sched_barrier(0);
     };
 
