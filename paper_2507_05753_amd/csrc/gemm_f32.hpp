@@ -327,9 +327,10 @@ struct StreamLoader {
     // Requests are asynchronous: the data is in LDS once this thread's vmcnt has drained and a
     // barrier has passed.  begin(kt) fixes the slab; issue(p) then enqueues the p-th of this
     // lane's four 16-byte transfers.  They are separate calls because the kernel spreads the
-    // transfers between its MFMAs: issued back to back they hold up the matrix pipe.
+    // transfers between its MFMAs: issued back to back they hold up the matrix pipe, and so
+    // does any vector ALU work between the MFMAs, which is why issue() does none.  A KC
+    // operand's ragged last slab needs per-lane masking and goes through request() instead.
     int soff;                           // KC: byte offset of the slab inside a row
-    int ragged_mask;                    // KC: all ones while the ragged last slab is being requested, else 0
     __device__ __forceinline__ void begin(int kt)
     {
         if (KS) {
@@ -340,24 +341,25 @@ struct StreamLoader {
             rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(tile_base + (int64_t)kt * BK * ld), 0,
                                                      (int)bytes, kBufferRsrcFlags);
             soff = 0;
-            ragged_mask = 0;
         } else {
             soff = kt * BK * 4;
-            ragged_mask = kt == kt_ragged ? -1 : 0;
         }
     }
     __device__ __forceinline__ void issue(int p, float* operand_slab, int wave) const
     {
-        // in the ragged slab the chunks past column K get an offset beyond the buffer and read as zero
-        const int off = KS ? voff[p] : (voff[p] | (oob[p] & ragged_mask));
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(operand_slab + (p * 4 + wave) * 256), 16, off, soff,
-                                                 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(operand_slab + (p * 4 + wave) * 256), 16, voff[p],
+                                                 soff, 0, 0);
     }
+    // all four transfers of any slab at once
     __device__ __forceinline__ void request(int kt, float* operand_slab, int wave)
     {
         begin(kt);
+        // in the ragged slab the chunks at or past column K get an offset beyond the buffer and read as zero
+        const int mask = (!KS && kt == kt_ragged) ? -1 : 0;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) issue(p, operand_slab, wave);
+        for (int p = 0; p < 4; ++p)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(operand_slab + (p * 4 + wave) * 256), 16,
+                                                     voff[p] | (oob[p] & mask), soff, 0, 0);
     }
 };
 
@@ -421,6 +423,11 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGro
     const int M = g.M, N = g.N, K = g.K;
     const int m0 = tc.m0, n0 = tc.n0;
     const int nkt = (K + BK - 1) / BK;
+    // slabs 2 .. nkt_spread - 1 are requested in the spread form; a ragged last slab is not, if an
+    // operand is K-contiguous
+    const bool ragged_burst = (!A_KS || !B_KS) && (K % BK) != 0;
+    const int nkt_spread = ragged_burst ? nkt - 1 : nkt;
+    const int kt_burst = ragged_burst ? nkt - 1 : -1;
 
     LaneMap L;
     L.init(threadIdx.x);
@@ -448,14 +455,14 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGro
     floatx16 acc[2][2], sum[2][2];
     float4 fa[2][2], fb[2][2];   // two register sets of MFMA operands (even / odd k-group)
 
-    // The 16 MFMAs of one k-group; when `requesting`, this lane's eight transfers of slab
+    // The 16 MFMAs of one k-group; when `spread` > 0, this lane's eight transfers of slab
     // `kt_req` into `slab` go out between them, one after every second MFMA.  Issued in a
     // burst, the transfers keep the matrix pipe waiting measurably longer.
-    auto mfma_group_requesting = [&](const float4 (&a)[2], const float4 (&b)[2], bool requesting, int kt_req,
+    auto mfma_group_requesting = [&](const float4 (&a)[2], const float4 (&b)[2], int spread, int kt_req,
                                      float* slab) {
         const float av[2][4] = {{a[0].x, a[0].y, a[0].z, a[0].w}, {a[1].x, a[1].y, a[1].z, a[1].w}};
         const float bv[2][4] = {{b[0].x, b[0].y, b[0].z, b[0].w}, {b[1].x, b[1].y, b[1].z, b[1].w}};
-        if (requesting) {
+        if (spread > 0) {
             load_a.begin(kt_req);
             load_b.begin(kt_req);
         }
@@ -467,7 +474,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGro
                 for (int j = 0; j < 2; ++j) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][tt], bv[j][tt], acc[i][j], 0, 0, 0);
                     const int idx = tt * 4 + i * 2 + j;
-                    if ((idx & 1) == 0 && requesting) {
+                    if ((idx & 1) == 0 && spread > 0) {
                         if (idx < 8) load_a.issue(idx >> 1, slab, L.wave);
                         else load_b.issue((idx >> 1) & 3, slab + OPERAND_FLOATS, L.wave);
                     }
@@ -491,9 +498,13 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGro
         }
         JG_WAIT_VMCNT(0);   // this thread's part of slab kt + 1 has landed
         __syncthreads();    // ... and everyone's; all waves hold their last operands of slab kt
+        // the slab after next: spread between the MFMAs below, or (ragged last slab of a
+        // K-contiguous operand, once per tile) all at once here
+        const int spread = nkt_spread - (kt + 2);   // > 0: request slab kt + 2 between the MFMAs
+        if (kt + 2 == kt_burst) request_slab(kt + 2, cur);
         if (kt + 1 < nkt) read_frags(nxt, 0, fa[0], fb[0]);
         __builtin_amdgcn_sched_barrier(0);
-        mfma_group_requesting(fa[1], fb[1], kt + 2 < nkt, kt + 2, cur);
+        mfma_group_requesting(fa[1], fb[1], spread, kt + 2, cur);
         __builtin_amdgcn_sched_barrier(0);
     };
 
