@@ -208,15 +208,23 @@ __device__ __forceinline__ void init_acc(const GemmProblem& P, int M, int N, int
     const int ldadd = P.ldadd;
     const int row_base = m0 + L.wm * 64 + 4 * L.lk;
     const int col_base = n0 + L.wn * 64 + L.lr;
-    if (m0 + BM <= M && n0 + BN <= N) {
-        const float* a_lane = addend + (int64_t)row_base * ldadd + col_base;
+    if (m0 + BM <= M && n0 + BN <= N && ldadd <= kMaxDirectLd) {
+        // interior tile: the lane's position goes into one vector offset per column block and the
+        // row of each access into a scalar offset, so the 64 loads need no vector ALU work (a
+        // workgroup that starts up shares its SIMDs with one that is saturating the matrix pipe,
+        // and every vector ALU instruction there waits for a gap between MFMAs)
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(addend + (int64_t)m0 * ldadd + n0), 0, ((BM - 1) * ldadd + BN) * 4, kBufferRsrcFlags);
+        const int lane_off = ((L.wm * 64 + 4 * L.lk) * ldadd + L.wn * 64 + L.lr) * 4;
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
-                    acc[i][j][v] = a_lane[(int64_t)(i * 32 + 8 * (v >> 2) + (v & 3)) * ldadd + j * 32];
+                    acc[i][j][v] = __builtin_bit_cast(
+                        float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, lane_off + j * 128,
+                                                                    (i * 32 + 8 * (v >> 2) + (v & 3)) * ldadd * 4, 0));
     } else {
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -241,16 +249,36 @@ __device__ __forceinline__ void store_tile(const GemmProblem& P, int M, int N, i
     const int ldc = P.ldc;
     const int row_base = m0 + L.wm * 64 + 4 * L.lk;     // + i * 32 + 8 (v / 4) + v % 4
     const int col_base = n0 + L.wn * 64 + L.lr;         // + j * 32
-    if (m0 + BM <= M && n0 + BN <= N) {   // interior tile: no bounds checks
-        float* c_lane = C + (int64_t)row_base * ldc + col_base;
+    if (m0 + BM <= M && n0 + BN <= N && ldc <= kMaxDirectLd) {
+        // interior tile: no bounds checks, and no vector ALU work for addresses (lane position in
+        // one vector offset per column block, the row of each store in a scalar offset)
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            C + (int64_t)m0 * ldc + n0, 0, ((BM - 1) * ldc + BN) * 4, kBufferRsrcFlags);
+        const int lane_off = ((L.wm * 64 + 4 * L.lk) * ldc + L.wn * 64 + L.lr) * 4;
+        if (bias) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const float bj = bias ? bias[col_base + j * 32] : 0.f;
+            for (int j = 0; j < 2; ++j) {
+                const float bj = bias[col_base + j * 32];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    c_lane[(int64_t)(i * 32 + 8 * (v >> 2) + (v & 3)) * ldc + j * 32] = acc[i][j][v] + bj;
+                    for (int v = 0; v < 16; ++v)
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, acc[i][j][v] + bj), rsrc,
+                                                              lane_off + j * 128,
+                                                              (i * 32 + 8 * (v >> 2) + (v & 3)) * ldc * 4, 0);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float value = acc[i][j][v];   // a copy: bit-casting the vector element in place reads element 0
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, value), rsrc,
+                                                              lane_off + j * 128,
+                                                              (i * 32 + 8 * (v >> 2) + (v & 3)) * ldc * 4, 0);
+                    }
         }
     } else {                              // edge tile: every element checked against M and N
 #pragma unroll
