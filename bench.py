@@ -241,7 +241,7 @@ def cpu_baseline(cfg, seconds):
 # the factors are in profiles/gemm_f32_stream_forward_config3_ways4_hbm_counters.md.  Counters cannot be read
 # from inside this script, so the figure is quoted, keyed by workload, and is null for the others.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
-    ("config3", 4): 3.97e9,   # reads 3.54 GB (FETCH_SIZE / 0.5065) + writes 0.429 GB (WRITE_SIZE / 1.0018)
+    ("config3", 4): 3.46e9,   # reads 3.05 GB (FETCH_SIZE / 0.5065) + writes 0.406 GB (WRITE_SIZE / 1.0018)
 }
 
 
