@@ -56,8 +56,11 @@ def _load():
         lib.oracle_backward.argtypes = [f32p, f32p, f32p, i64, i64, i64, f64p, f64p, ctypes.c_int, ctypes.c_int]
         lib.oracle_jigsaw_backward.argtypes = [ctypes.c_int, f32p, f32p, f32p, i64, i64, i64, f64p, f64p,
                                                ctypes.c_int]
+        lib.oracle_linear_xtw.argtypes = [f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int, ctypes.c_int]
+        lib.oracle_jigsaw_xtw.argtypes = [ctypes.c_int, f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int]
         for fn in (lib.oracle_linear, lib.oracle_linear_rows, lib.oracle_magnitude,
-                   lib.oracle_entries, lib.oracle_jigsaw, lib.oracle_backward, lib.oracle_jigsaw_backward):
+                   lib.oracle_entries, lib.oracle_jigsaw, lib.oracle_backward, lib.oracle_jigsaw_backward,
+                   lib.oracle_linear_xtw, lib.oracle_jigsaw_xtw):
             fn.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -195,6 +198,38 @@ def jigsaw_backward(ways: int, X, W, dY, nthreads: int | None = None):
     return dX, dW
 
 
+def linear_xtw(X, W, b=None, nthreads: int | None = None, absolute: bool = False) -> np.ndarray:
+    """Y64 = X^T W + b by the definition (X [T x C], W [T x D], Y [C x D]), in double; the
+    magnitude |b| + |X|^T |W| if ``absolute``."""
+    X, xp = _f32(X)
+    W, wp = _f32(W)
+    b, bp = _opt_f32(b)
+    T, C = X.shape
+    T2, D = W.shape
+    assert T == T2 and (b is None or b.shape == (D,))
+    Y, yp = _f64_out((C, D))
+    _check(_load().oracle_linear_xtw(xp, wp, bp, T, C, D, yp, int(absolute), nthreads or host_threads()),
+           "linear_xtw")
+    return Y
+
+
+def magnitude_xtw(X, W, b=None, nthreads: int | None = None) -> np.ndarray:
+    return linear_xtw(X, W, b, nthreads, absolute=True)
+
+
+def jigsaw_xtw(ways: int, X, W, b=None, nthreads: int | None = None) -> np.ndarray:
+    """Y64 = X^T W + b obtained block by block (the decomposition is stated in the C source)."""
+    X, xp = _f32(X)
+    W, wp = _f32(W)
+    b, bp = _opt_f32(b)
+    T, C = X.shape
+    D = W.shape[1]
+    assert W.shape[0] == T
+    Y, yp = _f64_out((C, D))
+    _check(_load().oracle_jigsaw_xtw(ways, xp, wp, bp, T, C, D, yp, nthreads or host_threads()), "jigsaw_xtw")
+    return Y
+
+
 # ----------------------------------------------------------------------------
 # layout definitions (pure indexing; bit-exact)
 # ----------------------------------------------------------------------------
@@ -227,6 +262,24 @@ def shard_w(W: np.ndarray, ways: int):
         return [np.ascontiguousarray(W[:, r * (K // 2):(r + 1) * (K // 2)]) for r in range(2)]
     return [np.ascontiguousarray(W[(r // 2) * (N // 2):(r // 2 + 1) * (N // 2),
                                    (r % 2) * (K // 2):(r % 2 + 1) * (K // 2)]) for r in range(4)]
+
+
+def shard_blocks(A: np.ndarray, ways: int):
+    """The partition every matrix of the method uses: whole (1-way), column halves (2-way),
+    2 x 2 blocks with block (i, j) at position 2 i + j (4-way)."""
+    R, Cc = A.shape
+    if ways not in (1, 2, 4):
+        raise ValueError("ways must be 1, 2 or 4")
+    if ways >= 2 and Cc % 2:
+        raise ValueError("the number of columns must be even")
+    if ways == 4 and R % 2:
+        raise ValueError("the number of rows must be even")
+    if ways == 1:
+        return [np.ascontiguousarray(A)]
+    if ways == 2:
+        return [np.ascontiguousarray(A[:, r * (Cc // 2):(r + 1) * (Cc // 2)]) for r in range(2)]
+    return [np.ascontiguousarray(A[(r // 2) * (R // 2):(r // 2 + 1) * (R // 2),
+                                   (r % 2) * (Cc // 2):(r % 2 + 1) * (Cc // 2)]) for r in range(4)]
 
 
 def shard_b(b: np.ndarray, ways: int):

@@ -32,13 +32,31 @@
  *                       dX partitioned like X and dW like W: every output
  *                       block is the sum of two block products, one of them
  *                       formed from a peer's block.
+ *  oracle_linear_xtw  : the transposed linear layer of the token-mixing MLP (Sec. 5:
+ *                       a forward pass defined by X^T W, so that the [tokens, channels]
+ *                       tensor of Sec. 3 is never transposed in memory), by definition:
+ *                         Y[c][d] = b[d] + sum_{t=0}^{T-1} X[t][c] * W[t][d]
+ *                       with X [T x C], W [T x D], Y [C x D]; t ascending, in double
+ *                       (optionally the same sum of absolute values).
+ *  oracle_jigsaw_xtw  : the same product obtained block by block.  The paper names the
+ *                       permutation but prints no equations for it; the decomposition
+ *                       used here keeps Sec. 4's rules (tensors split along the last
+ *                       dimension, 4-way in 2 x 2 blocks on rank 2 i + j, weights are
+ *                       never duplicated, two block products per rank, one partial
+ *                       product handed to one peer) and is stated above the function.
  *
  * Pins (see tests/test_oracle_pins.py): closed forms for identity /
  * permutation / all-ones / single-nonzero operands, exact integer brute force
  * on tiny shapes, a library matmul in double, the block identities of
  * Eqs. (2) and (4), linearity, and zero-padding invariance.
  *
- * Layout: every matrix is dense row-major; X is M x K, W is N x K, Y is M x N.
+ * Pins of the transposed layer (tests/test_oracle_xtw_pins.py): equality with
+ * oracle_linear applied to explicitly transposed operands, closed forms, integer
+ * brute force, exact equality of the block-wise result with the definition on
+ * lattice inputs.
+ *
+ * Layout: every matrix is dense row-major; X is M x K, W is N x K, Y is M x N
+ * (transposed layer: X is T x C, W is T x D, Y is C x D).
  */
 #include <math.h>
 #include <pthread.h>
@@ -507,5 +525,93 @@ int oracle_jigsaw_backward(int ways, const float* X, const float* W, const float
 done:
     for (int i = 0; i < 2; ++i)
         for (int j = 0; j < 2; ++j) { free(Xb[i][j]); free(Gb[i][j]); free(Wb[i][j]); }
+    return rc;
+}
+
+/* ------------------------------------------------------------------ */
+/* transposed linear layer  Y = X^T W + b                               */
+/* ------------------------------------------------------------------ */
+typedef struct { const float *X, *W, *b; int64_t T, C, D; double* Y; int absolute; } xtw_env;
+static void xtw_row(int64_t c, void* p)
+{
+    const xtw_env* e = (const xtw_env*)p;
+    double* out = e->Y + c * e->D;
+    for (int64_t d = 0; d < e->D; ++d) {
+        const double bd = e->b ? (double)e->b[d] : 0.0;
+        out[d] = e->absolute ? fabs(bd) : bd;
+    }
+    for (int64_t t = 0; t < e->T; ++t) {
+        const double x = (double)e->X[t * e->C + c];
+        const float* w = e->W + t * e->D;
+        if (e->absolute)
+            for (int64_t d = 0; d < e->D; ++d) out[d] += fabs(x) * fabs((double)w[d]);
+        else
+            for (int64_t d = 0; d < e->D; ++d) out[d] += x * (double)w[d];
+    }
+}
+
+int oracle_linear_xtw(const float* X, const float* W, const float* b, int64_t T, int64_t C, int64_t D,
+                      double* Y, int absolute, int nthreads)
+{
+    if (!X || !W || !Y || T < 0 || C < 0 || D < 0) return ORACLE_E_ARG;
+    xtw_env e = {X, W, b, T, C, D, Y, absolute};
+    return for_rows(0, C, nthreads, xtw_row, &e);
+}
+
+/* Block decomposition of Y = X^T W (X [T x C], W [T x D], Y [C x D]).
+ * 2-way: column halves, X_r = X[:, r], W_r = W[:, r], and Y_r = Y[:, r] = [X_0^T W_r ; X_1^T W_r].
+ * The contraction (over tokens) is not split, so nothing is summed across ranks: rank r forms
+ * the row half it can from its own X_r and the other one from the peer's activation block.
+ * 4-way: blocks (i, j) on rank 2 i + j, i the token half of X and W, j the channel half of X
+ * (column half of W); Y block (a, c) on rank 2 a + c:
+ *     Y_(a,c) = X_(0,a)^T W_(0,c) + X_(1,a)^T W_(1,c).
+ * Rank (i, j) multiplies its own W_(i,j) with its own X_(i,j) (a term of Y_(j,j)) and with
+ * X_(i,1-j), received from its row neighbour (a term of Y_(1-j,j)); the term whose block it
+ * owns (a = i) it keeps, the other goes to its column neighbour (1 - i, j), which owns that
+ * block and adds it to its own kept term.  Bias: b[c-th half] on the owner. */
+int oracle_jigsaw_xtw(int ways, const float* X, const float* W, const float* b, int64_t T, int64_t C,
+                      int64_t D, double* Y, int nthreads)
+{
+    if (!X || !W || !Y || T < 0 || C < 0 || D < 0) return ORACLE_E_ARG;
+    if (ways == 1) return oracle_linear_xtw(X, W, b, T, C, D, Y, 0, nthreads);
+    if (ways != 2 && ways != 4) return ORACLE_E_ARG;
+    if ((C % 2) || (D % 2) || (ways == 4 && (T % 2))) return ORACLE_E_ARG;
+    const int th = ways == 4 ? 2 : 1;                 /* token halves */
+    const int64_t Tb = T / th, Ch = C / 2, Dh = D / 2;
+    int rc = ORACLE_E_MEM;
+    float *Xb[2][2] = {{0}}, *Wb[2][2] = {{0}};
+    for (int i = 0; i < th; ++i)
+        for (int j = 0; j < 2; ++j) {
+            Xb[i][j] = take_block(X, C, i * Tb, Tb, j * Ch, Ch);
+            Wb[i][j] = take_block(W, D, i * Tb, Tb, j * Dh, Dh);
+            if (!Xb[i][j] || !Wb[i][j]) goto done;
+        }
+    for (int a = 0; a < 2; ++a)          /* channel half = row half of Y */
+        for (int c = 0; c < 2; ++c) {    /* column half of Y */
+            double* kept = new_partial(Ch, Dh);
+            double* recv = new_partial(Ch, Dh);
+            if (!kept || !recv) { free(kept); free(recv); goto done; }
+            if (ways == 2) {
+                /* owner: rank c; a == c uses its own X block, a != c the received one */
+                rc = add_tn(Xb[0][a], Wb[0][c], Tb, Ch, Dh, kept, nthreads);
+            } else {
+                /* owner: rank (a, c); its kept term has token half a, the received one 1 - a */
+                rc = add_tn(Xb[a][a], Wb[a][c], Tb, Ch, Dh, kept, nthreads);
+                if (!rc) rc = add_tn(Xb[1 - a][a], Wb[1 - a][c], Tb, Ch, Dh, recv, nthreads);
+            }
+            if (!rc) {
+                for (int64_t r = 0; r < Ch; ++r)
+                    for (int64_t q = 0; q < Dh; ++q)
+                        kept[r * Dh + q] += recv[r * Dh + q] + (b ? (double)b[c * Dh + q] : 0.0);
+                put_block(Y, D, a * Ch, Ch, c * Dh, Dh, kept);
+            }
+            free(kept); free(recv);
+            if (rc) goto done;
+            rc = ORACLE_E_MEM;
+        }
+    rc = ORACLE_OK;
+done:
+    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j) { free(Xb[i][j]); free(Wb[i][j]); }
     return rc;
 }
