@@ -31,8 +31,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--ways", type=int, default=4, choices=[1, 2, 4])
-    ap.add_argument("--op", choices=["forward", "backward"], default="forward",
-                    help="forward: Y = X W^T (the headline); backward: dX = dY W and dW = dY^T X")
+    ap.add_argument("--op", choices=["forward", "backward", "xtw"], default="forward",
+                    help="forward: Y = X W^T (the headline); backward: dX = dY W and dW = dY^T X; "
+                         "xtw: the transposed layer Y = X^T W at the token-mixing size (ignores --config)")
     ap.add_argument("--combine", choices=["fused", "separate"], default="fused")
     ap.add_argument("--weights", choices=["copy", "direct"], default="copy")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
@@ -186,6 +187,59 @@ def measure_backward(cfg, ways, args, X, W):
                 workspace_bytes=ws)
 
 
+def measure_xtw(cfg, ways, args):
+    """One step = one forward of the transposed layer Y = X^T W (all ranks), shards resident in HBM."""
+    import torch
+    from paper_2507_05753_amd import binding as jg
+    from paper_2507_05753_amd import inputs
+    from paper_2507_05753_amd.layer import JigsawLinear
+    K, M, N, seed = cfg["K"], cfg["M"], cfg["N"], cfg["seed"]
+    dev = torch.device("cuda", 0)
+    X = inputs.matrix_torch(seed, K, M, "R", 0, device=dev)
+    W = inputs.matrix_torch(seed + inputs.W_STREAM, K, N, "R", inputs.W_SCALE_EXP, device=dev)
+    combine = jg.JG_COMBINE_FUSED if args.combine == "fused" else jg.JG_COMBINE_SEPARATE
+    weights = jg.JG_WEIGHTS_COPY if args.weights == "copy" else jg.JG_WEIGHTS_DIRECT
+    with JigsawLinear(M, K, N, ways, combine=combine, weights=weights, op=jg.JG_OP_XTW) as L:
+        L.shard(X, W)
+        del X, W
+        sec, gemm_ms, gemm_n, copy_ms, comb_ms = time_forward(L, jg, args.steps, args.warmup)
+        flops = L.query(jg.JG_Q_FLOPS_TOTAL)
+        launches = L.query(jg.JG_Q_GEMM_LAUNCHES)
+        avg = gemm_ms / max(gemm_n, 1)
+        out = dict(ms_per_step=sec * 1e3, items_per_s=M * K / sec, tflops=flops / sec / 1e12,
+                   gemm_avg_launch_ms=avg, gemm_launches_timed=gemm_n,
+                   gemm_tflops=(flops / launches) / (avg * 1e-3) / 1e12 if gemm_n else None,
+                   other_kernels_ms_per_step=copy_ms + comb_ms,
+                   hbm_algo_gbps=L.query(jg.JG_Q_HBM_BYTES_ALGO) / sec / 1e9, workspace_bytes=L.ws_bytes)
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline_xtw(cfg, seconds):
+    """The transposed-layer oracle timed on a bounded sample of channels (columns of X = rows of Y)."""
+    import numpy as np
+    import oracle
+    from paper_2507_05753_amd import inputs
+    K, M, N, seed = cfg["K"], cfg["M"], cfg["N"], cfg["seed"]
+    cores = min(oracle.host_threads(), 16)
+    X = inputs.matrix(seed, K, M, "R")
+    W = inputs.matrix(seed + inputs.W_STREAM, K, N, "R", inputs.W_SCALE_EXP)
+
+    def run(ch):
+        Xs = np.ascontiguousarray(X[:, :ch])
+        t0 = time.perf_counter()
+        oracle.linear_xtw(Xs, W, None, nthreads=cores)
+        return time.perf_counter() - t0
+
+    probe = min(M, cores)
+    rate = probe / max(run(probe), 1e-9)            # channels per second
+    ch = int(min(M, max(probe, rate * seconds)))
+    ch = min(M, max(cores, ch // cores * cores))
+    dt = run(ch)
+    return dict(value=ch * K / dt, unit="items/s", cores=cores, kind="oracle",
+                sample=f"channels 0..{ch - 1} of X ({K} x {ch}) against all of W ({K} x {N}), {dt:.1f} s, fp64 loops")
+
+
 def cpu_baseline_backward(cfg, seconds):
     """The backward oracle timed on a bounded row sample (dX rows and the matching share of dW)."""
     import oracle
@@ -256,6 +310,32 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     from paper_2507_05753_amd import inputs
+
+    if args.op == "xtw":
+        xc = inputs.XTW_CONFIGS["token_mixing_1b"]
+        r = measure_xtw(xc, args.ways, args)
+        K, M, N = xc["K"], xc["M"], xc["N"]
+        line = {
+            "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
+            "value": r["items_per_s"], "unit": "items/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"token mixing of the 1B model: Y = X^T W, X {K} x {M} [tokens, channels], "
+                                   f"W {K} x {N}, {args.ways}-way Jigsaw, fp32",
+                       "n_items": M * K, "ways": args.ways, "M": M, "K": K, "N": N, "seed": xc["seed"],
+                       "x_values": "R", "op": "xtw", "combine": args.combine, "weights": args.weights},
+            "tflops": r["tflops"], "hbm_algo_gbps": r["hbm_algo_gbps"],
+            "roofline": {"bound": "mfma", "kernel": "jg::gemm_f32_stream<true, true>", "achieved": r["gemm_tflops"],
+                         "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": r["gemm_tflops"] / FP32_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None,
+                         "avg_launch_ms": r["gemm_avg_launch_ms"], "launches": r["gemm_launches_timed"],
+                         "traffic": None},
+            "other_kernels_ms_per_step": r["other_kernels_ms_per_step"],
+        }
+        if args.cpu_seconds > 0:
+            line["cpu_baseline"] = cpu_baseline_xtw(xc, args.cpu_seconds)
+        print(json.dumps(line), flush=True)
+        return
 
     cfg = inputs.CONFIGS[args.config]
     M, K, N = cfg["M"], cfg["K"], cfg["N"]

@@ -16,6 +16,21 @@
  *              products; one partial product and one weight block are handed to a
  *              peer, and Y_r sits where X_r sat.
  *
+ * The transposed layer (Sec. 5: a forward pass defined by X^T W, which removes the
+ * transpose of the [tokens, channels] tensor before the token-mixing MLP of Sec. 3):
+ *     Y = X^T W (+ b),   X: K x M ([tokens, channels]),  W: K x N,  Y: M x N,
+ * selected by op = JG_OP_XTW.  The paper names this permutation and says that it has
+ * its own exchange pattern, but prints no equations; this library keeps the rules of
+ * Sec. 4 (split on the last dimension, 2 x 2 blocks row-major, nothing duplicated,
+ * two block products per rank, one partial handed to one peer):
+ *   ways = 2   X_r = X[:, r], W_r = W[:, r], Y_r = Y[:, r] = [X_0^T W_r ; X_1^T W_r].  The
+ *              contraction is not split, so nothing is summed across ranks: rank r
+ *              gets the peer's activation block and fills both row halves of Y_r.
+ *   ways = 4   block (i, j) on rank 2 i + j.  Rank (i, j) multiplies its W_(i,j) with its
+ *              own X_(i,j) (a term of Y block (j, j)) and with X_(i,1-j) received from
+ *              rank (i, 1-j) (a term of Y block (1-j, j)); it keeps the term of the
+ *              block it owns (row half i) and hands the other to rank (1-i, j).
+ *
  * All n ranks of one layer are "virtual ranks" resident on the one GPU: each has its
  * own shard buffers, and a hand-off to a peer is a store into the peer's buffer.
  *
@@ -59,16 +74,18 @@ typedef enum jg_status {
     JG_E_ARCH = -8       /* the device is not gfx950                                    */
 } jg_status;
 
-enum { JG_OP_XWT = 0 };                                  /* Y = X W^T (Sec. 4)          */
+enum { JG_OP_XWT = 0,                                    /* Y = X W^T (Sec. 4)          */
+       JG_OP_XTW = 1 };                                  /* Y = X^T W (Sec. 5), forward only */
 enum { JG_F32 = 0 };                                     /* the paper's uniform single precision (Sec. 6.1) */
 enum { JG_COMBINE_FUSED = 0, JG_COMBINE_SEPARATE = 1 };  /* where the "+" of Eq. (2)/(4) runs */
 enum { JG_WEIGHTS_COPY = 0, JG_WEIGHTS_DIRECT = 1 };     /* 4-way weight-block hand-off */
 enum { JG_T_X = 0, JG_T_W = 1, JG_T_B = 2, JG_T_Y = 3 }; /* tensor selector of jg_shard / jg_gather_as */
 
 typedef struct jg_linear_desc {
-    int64_t M, K, N;     /* global sizes: X is M x K, W is N x K, Y is M x N            */
+    int64_t M, K, N;     /* global sizes: Y is M x N and K is contracted.  JG_OP_XWT: X is
+                            M x K, W is N x K.  JG_OP_XTW: X is K x M, W is K x N.      */
     int32_t ways;        /* 1, 2 or 4                                                   */
-    int32_t op;          /* JG_OP_XWT                                                   */
+    int32_t op;          /* JG_OP_XWT or JG_OP_XTW                                      */
     int32_t dtype;       /* JG_F32                                                      */
     int32_t has_bias;    /* 0 / 1: b_r (the slice of b matching Y_r's columns) is added
                             once, by the rank that owns the output block                */
@@ -76,7 +93,9 @@ typedef struct jg_linear_desc {
                             from the received partial.  JG_COMBINE_SEPARATE: the kept
                             product is written out and a streaming kernel adds the two
                             partials (for measurement).                                 */
-    int32_t weights;     /* 4-way only.  JG_WEIGHTS_COPY: the weight block a rank needs
+    int32_t weights;     /* The operand block a rank needs from a peer (JG_OP_XWT: 4-way, a
+                            weight block; JG_OP_XTW: 2- and 4-way, an activation block).
+                            JG_WEIGHTS_COPY: the weight block a rank needs
                             from its peer (the terms of Eq. (4) in which only W^T is
                             bold) is copied into the workspace first, as a transfer
                             would deliver it.  JG_WEIGHTS_DIRECT: the peer's buffer is
@@ -87,8 +106,9 @@ typedef enum jg_query {
     JG_Q_WORKSPACE_BYTES = 0,    /* device bytes jg_linear_forward needs (rank ignored)        */
     JG_Q_FLOPS_TOTAL = 1,        /* 2 M K N: matmul dimensions only (Sec. 6.3 work model)      */
     JG_Q_FLOPS_RANK = 2,         /* one rank's two block products                              */
-    JG_Q_HBM_BYTES_ALGO = 3,     /* 4(MK + NK + MN), plus 8 MN for ways >= 2 (each partial
-                                    product is written once and read once)                     */
+    JG_Q_HBM_BYTES_ALGO = 3,     /* 4(MK + NK + MN), plus 8 MN where partial products are handed
+                                    over (each written once and read once): ways >= 2, for
+                                    JG_OP_XTW ways = 4 only                                    */
     JG_Q_EXCHANGE_BYTES_RANK = 4,/* bytes a rank hands to its peers per forward                */
     JG_Q_X_ROWS = 5, JG_Q_X_COLS = 6,   /* shape of rank's X shard                             */
     JG_Q_W_ROWS = 7, JG_Q_W_COLS = 8,   /* shape of rank's W shard                             */
@@ -122,7 +142,8 @@ int jg_init(jg_ctx** out, int device, void* hip_stream);
 void jg_free(jg_ctx* ctx);
 
 /* build.  Validates `desc` and fixes the block decomposition of Sec. 4.1 / 4.2 for
- * these sizes.  2-way needs even K and N; 4-way needs even M, K and N (the paper's
+ * these sizes.  JG_OP_XWT: 2-way needs even K and N; JG_OP_XTW: 2-way needs even M and N
+ * (the dimensions that are split); 4-way needs even M, K and N for both (the paper's
  * loader zero-pads to make partitions equal, Sec. 5 "Data loading": padding is the
  * caller's job).  Size limits: each of M, K, N below 2^31 - 1024, and for each pair
  * of them ceil(a/128) * ceil(b/128) at most (2^31 - 65) / 4 (the tile index of a launch
@@ -145,6 +166,9 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out);
  *           matching Y_r's columns (4-way: replicated on the two ranks of a column).
  *   which = JG_T_Y: global is M x N, ld >= N (an incoming gradient dY): partitioned like Y,
  *           2-way: column halves of N; 4-way: block (r/2, r%2).
+ * For a JG_OP_XTW plan the global X is K x M (ld >= M), W is K x N (ld >= N) and Y is
+ * M x N; all three are partitioned the same way (2-way: column halves; 4-way: block
+ * (r/2, r%2)) and b as above.
  * `global` is a device pointer; `shards` is a host array of `ways` device pointers,
  * each with room for the rank's shard.  Pure data movement: bit-exact.
  * Errors: JG_E_NULL, JG_E_SHAPE (ld), JG_E_ALIGN, JG_E_DTYPE (which), JG_E_HIP. */
@@ -158,6 +182,10 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
  *             plus the bias, written to Y_r (JG_COMBINE_FUSED); or the kept product
  *             followed by a separate combine kernel (JG_COMBINE_SEPARATE).
  * ways = 1 is a single GEMM with the bias in its epilogue and needs no workspace.
+ * JG_OP_XTW plans: (JG_WEIGHTS_COPY) copy each rank's incoming activation block; 2-way: one
+ * launch of the four block products, each written with the bias straight into its row half
+ * of Y_r; 4-way: launch 1 / launch 2 as above, the partial going to rank (1-i, j).  Both
+ * operands are read along their rows' stride (no transpose in memory).
  * x_sh, w_sh, y_sh: host arrays of `ways` device pointers (shapes: JG_Q_*_ROWS/COLS);
  * b_sh: the same for the bias slices, required iff has_bias.  `workspace` is a
  * 256-byte-aligned device buffer of at least JG_Q_WORKSPACE_BYTES bytes (may be NULL
@@ -184,7 +212,8 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
  * X_r, W_r, Y_r); dx_sh, dw_sh: the same for the outputs (shapes of X_r, W_r).  `workspace`:
  * 256-byte-aligned device buffer of at least JG_Q_BACKWARD_WORKSPACE_BYTES bytes (may be NULL when
  * that is 0).  The bias gradient is not computed.  The plan's combine / weights options do not apply.
- * Errors: JG_E_NULL, JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
+ * JG_OP_XWT plans only: a JG_OP_XTW plan returns JG_E_DTYPE.
+ * Errors: JG_E_NULL, JG_E_DTYPE (op), JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
 int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
                        const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh,
                        void* workspace, size_t workspace_bytes);

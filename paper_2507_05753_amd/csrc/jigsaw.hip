@@ -217,14 +217,16 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     if (!desc) return JG_E_NULL;
     const jg_linear_desc& d = *desc;
     if (d.ways != 1 && d.ways != 2 && d.ways != 4) return JG_E_WAYS;
-    if (d.op != JG_OP_XWT || d.dtype != JG_F32) return JG_E_DTYPE;
+    if ((d.op != JG_OP_XWT && d.op != JG_OP_XTW) || d.dtype != JG_F32) return JG_E_DTYPE;
     if (d.combine != JG_COMBINE_FUSED && d.combine != JG_COMBINE_SEPARATE) return JG_E_DTYPE;
     if (d.weights != JG_WEIGHTS_COPY && d.weights != JG_WEIGHTS_DIRECT) return JG_E_DTYPE;
     if (d.has_bias != 0 && d.has_bias != 1) return JG_E_DTYPE;
     if (d.M <= 0 || d.K <= 0 || d.N <= 0) return JG_E_SHAPE;
     if (d.M > kMaxDim || d.K > kMaxDim || d.N > kMaxDim) return JG_E_SHAPE;
-    if (d.ways >= 2 && ((d.K & 1) || (d.N & 1))) return JG_E_SHAPE;
-    if (d.ways == 4 && (d.M & 1)) return JG_E_SHAPE;
+    // the dimensions that are halved: X W^T splits K (2-way) and M, K (4-way); X^T W splits M and K, M
+    const bool xtw = d.op == JG_OP_XTW;
+    if (d.ways >= 2 && ((xtw ? d.M & 1 : d.K & 1) || (d.N & 1))) return JG_E_SHAPE;
+    if (d.ways == 4 && ((d.M & 1) || (d.K & 1))) return JG_E_SHAPE;
     {   // every product of the plan (forward M x N, backward M x K and N x K, up to four
         // problems a launch) must have a tile count that fits the 32-bit block index
         const int64_t tm = (d.M + jg::BM - 1) / jg::BM, tn = (d.N + jg::BM - 1) / jg::BM,
@@ -237,22 +239,35 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     if (!p) return JG_E_HIP;
     p->ctx = ctx;
     p->d = d;
-    switch (d.ways) {
-    case 1:
-        p->xr = d.M; p->xc = d.K; p->wr = d.N; p->wc = d.K; p->yr = d.M; p->yc = d.N;
-        break;
-    case 2:   // Sec. 4.1: channel (last) dimension halved; W_r keeps all N rows
-        p->xr = d.M; p->xc = d.K / 2; p->wr = d.N; p->wc = d.K / 2; p->yr = d.M; p->yc = d.N / 2;
-        break;
-    default:  // Sec. 4.2: 2 x 2 blocks
-        p->xr = d.M / 2; p->xc = d.K / 2; p->wr = d.N / 2; p->wc = d.K / 2;
-        p->yr = d.M / 2; p->yc = d.N / 2;
-        break;
+    if (xtw) {
+        // X is K x M, W is K x N, Y is M x N; all split on the last dimension (2-way) or 2 x 2
+        const int64_t rows = d.ways == 4 ? 2 : 1, cols = d.ways >= 2 ? 2 : 1;
+        p->xr = d.K / rows; p->xc = d.M / cols;
+        p->wr = d.K / rows; p->wc = d.N / cols;
+        p->yr = d.M / rows; p->yc = d.N / cols;
+    } else {
+        switch (d.ways) {
+        case 1:
+            p->xr = d.M; p->xc = d.K; p->wr = d.N; p->wc = d.K; p->yr = d.M; p->yc = d.N;
+            break;
+        case 2:   // Sec. 4.1: channel (last) dimension halved; W_r keeps all N rows
+            p->xr = d.M; p->xc = d.K / 2; p->wr = d.N; p->wc = d.K / 2; p->yr = d.M; p->yc = d.N / 2;
+            break;
+        default:  // Sec. 4.2: 2 x 2 blocks
+            p->xr = d.M / 2; p->xc = d.K / 2; p->wr = d.N / 2; p->wc = d.K / 2;
+            p->yr = d.M / 2; p->yc = d.N / 2;
+            break;
+        }
     }
     p->part_bytes = p->wblk_bytes = 0;
     p->off_send = p->off_kept = p->off_wrecv = 0;
     size_t off = 0;
-    if (d.ways >= 2) {
+    // partial products are handed over wherever the contraction is split across ranks; an operand
+    // block comes from a peer in the 4-way X W^T layer (a weight block) and in the 2- and 4-way
+    // X^T W layer (an activation block)
+    const bool partials = xtw ? d.ways == 4 : d.ways >= 2;
+    const bool operand_blocks = (xtw ? d.ways >= 2 : d.ways == 4) && d.weights == JG_WEIGHTS_COPY;
+    if (partials) {
         p->part_bytes = round_up((size_t)p->yr * (size_t)p->yc * sizeof(float), kWsAlign);
         p->off_send = off;
         off += p->part_bytes * d.ways;
@@ -260,15 +275,16 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
             p->off_kept = off;
             off += p->part_bytes * d.ways;
         }
-        if (d.ways == 4 && d.weights == JG_WEIGHTS_COPY) {
-            p->wblk_bytes = round_up((size_t)p->wr * (size_t)p->wc * sizeof(float), kWsAlign);
-            p->off_wrecv = off;
-            off += p->wblk_bytes * d.ways;
-        }
+    }
+    if (operand_blocks) {
+        const size_t elems = xtw ? (size_t)p->xr * (size_t)p->xc : (size_t)p->wr * (size_t)p->wc;
+        p->wblk_bytes = round_up(elems * sizeof(float), kWsAlign);
+        p->off_wrecv = off;
+        off += p->wblk_bytes * d.ways;
     }
     p->ws_bytes = off;
     p->bw_dx_bytes = p->bw_dw_bytes = p->bw_off_dw = p->bw_ws_bytes = 0;
-    if (d.ways >= 2) {
+    if (d.ways >= 2 && !xtw) {
         p->bw_dx_bytes = round_up((size_t)p->xr * (size_t)p->xc * sizeof(float), kWsAlign);
         p->bw_off_dw = p->bw_dx_bytes * d.ways;
         p->bw_ws_bytes = p->bw_off_dw;
@@ -291,14 +307,26 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
                           (what >= JG_Q_X_ROWS && what <= JG_Q_RESIDENT_BYTES_RANK);
     if (per_rank && (rank < 0 || rank >= d.ways)) return JG_E_WAYS;
     const int64_t M = d.M, K = d.K, N = d.N;
+    const bool xtw = d.op == JG_OP_XTW;
+    if (xtw && (what == JG_Q_BACKWARD_WORKSPACE_BYTES || what == JG_Q_BACKWARD_FLOPS_TOTAL ||
+                what == JG_Q_BACKWARD_GEMM_LAUNCHES))
+        return JG_E_DTYPE;   // no backward for this op
     switch (what) {
     case JG_Q_WORKSPACE_BYTES: *out = (int64_t)plan->ws_bytes; break;
     case JG_Q_FLOPS_TOTAL: *out = 2 * M * K * N; break;
     case JG_Q_FLOPS_RANK: *out = 2 * M * K * N / d.ways; break;
     case JG_Q_HBM_BYTES_ALGO:
-        *out = 4 * (M * K + N * K + M * N) + (d.ways >= 2 ? 8 * M * N : 0);
+        *out = 4 * (M * K + N * K + M * N) + ((xtw ? d.ways == 4 : d.ways >= 2) ? 8 * M * N : 0);
         break;
     case JG_Q_EXCHANGE_BYTES_RANK:
+        if (xtw) {
+            // 2-way: one K x M/2 activation block.  4-way: one M/2 x N/2 partial and one K/2 x M/2
+            // activation block.
+            *out = d.ways == 1 ? 0
+                 : d.ways == 2 ? 4 * K * (M / 2)
+                               : 4 * ((M / 2) * (N / 2) + (K / 2) * (M / 2));
+            break;
+        }
         // 2-way: one M x N/2 partial.  4-way: one M/2 x N/2 partial and one N/2 x K/2 weight block.
         *out = d.ways == 1 ? 0
              : d.ways == 2 ? 4 * M * (N / 2)
@@ -314,7 +342,7 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     case JG_Q_RESIDENT_BYTES_RANK:
         *out = 4 * (plan->xr * plan->xc + plan->wr * plan->wc + plan->yr * plan->yc);
         break;
-    case JG_Q_GEMM_LAUNCHES: *out = d.ways == 1 ? 1 : 2; break;
+    case JG_Q_GEMM_LAUNCHES: *out = (d.ways == 1 || (xtw && d.ways == 2)) ? 1 : 2; break;
     case JG_Q_BACKWARD_WORKSPACE_BYTES: *out = (int64_t)plan->bw_ws_bytes; break;
     case JG_Q_BACKWARD_FLOPS_TOTAL: *out = 4 * M * K * N; break;
     case JG_Q_BACKWARD_GEMM_LAUNCHES: *out = d.ways == 1 ? 2 : d.ways == 2 ? 3 : 4; break;
@@ -332,8 +360,8 @@ struct Partition {
 static int partition_of(const jg_plan* plan, int which, Partition* out)
 {
     switch (which) {
-    case JG_T_X: *out = {plan->xr, plan->xc, plan->d.K}; return JG_OK;
-    case JG_T_W: *out = {plan->wr, plan->xc, plan->d.K}; return JG_OK;
+    case JG_T_X: *out = {plan->xr, plan->xc, plan->d.op == JG_OP_XTW ? plan->d.M : plan->d.K}; return JG_OK;
+    case JG_T_W: *out = {plan->wr, plan->wc, plan->d.op == JG_OP_XTW ? plan->d.N : plan->d.K}; return JG_OK;
     case JG_T_Y: *out = {plan->yr, plan->yc, plan->d.N}; return JG_OK;
     default: return JG_E_DTYPE;
     }
@@ -419,6 +447,105 @@ int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, in
     return jg_gather_as(plan, JG_T_Y, y_sh, global_y, ld);
 }
 
+// Forward pass of the transposed layer Y = X^T W (+ b); arguments already checked.  Every block
+// product is a GEMM whose two operands are read along their row stride (A = an X block, K x M;
+// B = a W block, K x N).
+static int forward_xtw(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                       const float* const* b_sh, float* const* y_sh, char* ws)
+{
+    const jg_linear_desc& d = plan->d;
+    const int ways = d.ways;
+    jg_ctx* c = plan->ctx;
+    auto bias_of = [&](int r) -> const float* { return d.has_bias ? b_sh[r] : nullptr; };
+    const int ldx = (int)plan->xc, ldw = (int)plan->wc, ldy = (int)plan->yc;
+
+    jg::GemmGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.M = (int)plan->xc;   // channels of one X block = rows of one Y block
+    g.N = (int)plan->wc;
+    g.K = (int)plan->xr;   // tokens of one block
+
+    if (ways == 1) {
+        g.nprob = 1;
+        g.p[0] = {x_sh[0], w_sh[0], y_sh[0], nullptr, bias_of(0), ldx, ldw, ldy, 0};
+        ScopedTimer t(c, JG_KERNEL_GEMM);
+        return HIP_OK(jg::launch_gemm_group(g, jg::kGemmTN, c->stream)) ? JG_OK : JG_E_HIP;
+    }
+
+    // the activation block every rank gets from its row neighbour (rank r ^ 1)
+    const float* x_in[4];
+    if (d.weights == JG_WEIGHTS_COPY) {
+        jg::CopyGroup cg;
+        std::memset(&cg, 0, sizeof(cg));
+        cg.nblocks = ways;
+        cg.nontemporal = 0;
+        cg.rows = (int)plan->xr;
+        cg.cols = (int)plan->xc;
+        for (int r = 0; r < ways; ++r) {
+            float* dst = reinterpret_cast<float*>(ws + plan->off_wrecv + r * plan->wblk_bytes);
+            cg.b[r] = {x_sh[r ^ 1], dst, plan->xc, plan->xc};
+            x_in[r] = dst;
+        }
+        ScopedTimer t(c, JG_KERNEL_WEIGHT_COPY);
+        if (!HIP_OK(jg::launch_copy_group(cg, c->stream))) return JG_E_HIP;
+    } else {
+        for (int r = 0; r < ways; ++r) x_in[r] = x_sh[r ^ 1];
+    }
+
+    if (ways == 2) {
+        // Y_r = [X_0^T W_r ; X_1^T W_r]: row half r from the rank's own block, the other from the
+        // received one; nothing is summed across ranks, so both products carry the bias
+        const int64_t half = (int64_t)plan->xc * plan->yc;   // floats in one M/2 x N/2 block of Y_r
+        g.nprob = 4;
+        for (int r = 0; r < 2; ++r) {
+            g.p[2 * r] = {x_sh[r], w_sh[r], y_sh[r] + r * half, nullptr, bias_of(r), ldx, ldw, ldy, 0};
+            g.p[2 * r + 1] = {x_in[r], w_sh[r], y_sh[r] + (1 - r) * half, nullptr, bias_of(r), ldx, ldw, ldy, 0};
+        }
+        ScopedTimer t(c, JG_KERNEL_GEMM);
+        return HIP_OK(jg::launch_gemm_group(g, jg::kGemmTN, c->stream)) ? JG_OK : JG_E_HIP;
+    }
+
+    // 4-way.  Rank (i, j) = 2 i + j: own X block -> a term of Y block (j, j), received X block -> a
+    // term of Y block (1 - j, j).  It owns block (i, j), so it keeps the first if i == j and the
+    // second otherwise, and hands the other one to rank (1 - i, j) = r ^ 2.
+    auto send_buf = [&](int r) { return reinterpret_cast<float*>(ws + plan->off_send + r * plan->part_bytes); };
+    auto kept_buf = [&](int r) { return reinterpret_cast<float*>(ws + plan->off_kept + r * plan->part_bytes); };
+    const float* x_keep[4];
+    const float* x_send[4];
+    for (int r = 0; r < 4; ++r) {
+        const bool own_is_kept = (r / 2) == (r % 2);
+        x_keep[r] = own_is_kept ? x_sh[r] : x_in[r];
+        x_send[r] = own_is_kept ? x_in[r] : x_sh[r];
+    }
+    g.nprob = 4;
+    for (int r = 0; r < 4; ++r)
+        g.p[r] = {x_send[r], w_sh[r], send_buf(r), nullptr, nullptr, ldx, ldw, ldy, 0};
+    {
+        ScopedTimer t(c, JG_KERNEL_GEMM);
+        if (!HIP_OK(jg::launch_gemm_group(g, jg::kGemmTN, c->stream))) return JG_E_HIP;
+    }
+    if (d.combine == JG_COMBINE_FUSED) {
+        for (int r = 0; r < 4; ++r)
+            g.p[r] = {x_keep[r], w_sh[r], y_sh[r], send_buf(r ^ 2), bias_of(r), ldx, ldw, ldy, ldy};
+        ScopedTimer t(c, JG_KERNEL_GEMM);
+        return HIP_OK(jg::launch_gemm_group(g, jg::kGemmTN, c->stream)) ? JG_OK : JG_E_HIP;
+    }
+    for (int r = 0; r < 4; ++r)
+        g.p[r] = {x_keep[r], w_sh[r], kept_buf(r), nullptr, nullptr, ldx, ldw, ldy, 0};
+    {
+        ScopedTimer t(c, JG_KERNEL_GEMM);
+        if (!HIP_OK(jg::launch_gemm_group(g, jg::kGemmTN, c->stream))) return JG_E_HIP;
+    }
+    jg::CombineGroup cb;
+    std::memset(&cb, 0, sizeof(cb));
+    cb.nblocks = 4;
+    cb.rows = (int)plan->yr;
+    cb.cols = (int)plan->yc;
+    for (int r = 0; r < 4; ++r) cb.b[r] = {kept_buf(r), send_buf(r ^ 2), bias_of(r), y_sh[r]};
+    ScopedTimer t(c, JG_KERNEL_COMBINE);
+    return HIP_OK(jg::launch_combine_group(cb, c->stream)) ? JG_OK : JG_E_HIP;
+}
+
 int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
                       const float* const* b_sh, float* const* y_sh, void* workspace,
                       size_t workspace_bytes)
@@ -440,6 +567,8 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
     if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
     char* ws = static_cast<char*>(workspace);
     auto bias_of = [&](int r) -> const float* { return d.has_bias ? b_sh[r] : nullptr; };
+
+    if (d.op == JG_OP_XTW) return forward_xtw(plan, x_sh, w_sh, b_sh, y_sh, ws);
 
     jg::GemmGroup g;
     std::memset(&g, 0, sizeof(g));
@@ -537,6 +666,7 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
 {
     if (!plan || !plan->ctx) return JG_E_NULL;
     const jg_linear_desc& d = plan->d;
+    if (d.op != JG_OP_XWT) return JG_E_DTYPE;
     const int ways = d.ways;
     if (int rc = check_ptr_array(x_sh, ways)) return rc;
     if (int rc = check_ptr_array(w_sh, ways)) return rc;

@@ -190,3 +190,12 @@ CONFIGS = {
     4: dict(M=25000, K=4000, N=4000, seed=4, x_mode="Z"),
     5: dict(M=200000, K=10000, N=10000, seed=5, x_mode="R"),
 }
+
+# Workloads of the transposed layer Y = X^T W (X is [tokens, channels] = K x M, W is K x N).
+# "token_mixing_1b": first token-mixing linear of the paper's 1-billion-parameter model
+# (Sec. 6.2.1: embedding dimension 4320, token-mixing hidden dimension 8640); 16200 tokens are the
+# 721 x 1440 grid of Sec. 3 in 8 x 8 patches.
+XTW_CONFIGS = {
+    "small": dict(K=200, M=264, N=136, seed=21),
+    "token_mixing_1b": dict(K=16200, M=4320, N=8640, seed=22),
+}

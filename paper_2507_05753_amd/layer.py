@@ -11,19 +11,25 @@ from . import binding as jg
 
 
 class JigsawLinear:
-    """Plan + per-rank shard tensors (X_r, W_r, b_r, Y_r) + workspace on one GPU."""
+    """Plan + per-rank shard tensors (X_r, W_r, b_r, Y_r) + workspace on one GPU.
+
+    ``op = JG_OP_XWT``: Y = X W^T with X (M, K) and W (N, K).  ``op = JG_OP_XTW``: the transposed
+    layer Y = X^T W with X (K, M) and W (K, N), forward only.
+    """
 
     def __init__(self, M: int, K: int, N: int, ways: int, bias: bool = False,
                  combine: int = jg.JG_COMBINE_FUSED, weights: int = jg.JG_WEIGHTS_COPY,
-                 device: int = 0, ctx=None):
+                 device: int = 0, ctx=None, op: int = jg.JG_OP_XWT):
         if not torch.cuda.is_available():
             raise RuntimeError("JigsawLinear needs a GPU: the HIP library has no CPU fallback")
-        self.M, self.K, self.N, self.ways, self.bias = M, K, N, ways, bias
+        self.M, self.K, self.N, self.ways, self.bias, self.op = M, K, N, ways, bias, op
+        self.x_shape = (K, M) if op == jg.JG_OP_XTW else (M, K)
+        self.w_shape = (K, N) if op == jg.JG_OP_XTW else (N, K)
         self.dev = torch.device("cuda", device)
         self._own_ctx = ctx is None
         self.stream = torch.cuda.current_stream(self.dev)
         self.ctx = ctx if ctx is not None else jg.jg_init(device, self.stream.cuda_stream)
-        self.plan = jg.jg_plan_create(self.ctx, M, K, N, ways, bias, combine, weights)
+        self.plan = jg.jg_plan_create(self.ctx, M, K, N, ways, bias, combine, weights, op)
         q = lambda what, r=0: jg.jg_plan_query(self.plan, what, r)
         f32 = dict(dtype=torch.float32, device=self.dev)
         self.x = [torch.empty((q(jg.JG_Q_X_ROWS, r), q(jg.JG_Q_X_COLS, r)), **f32) for r in range(ways)]
@@ -37,10 +43,10 @@ class JigsawLinear:
     def shard(self, X=None, W=None, b=None):
         """Split global device tensors into the per-rank shards (jg_shard)."""
         if X is not None:
-            assert X.is_cuda and X.dtype == torch.float32 and X.shape == (self.M, self.K) and X.stride(1) == 1
+            assert X.is_cuda and X.dtype == torch.float32 and X.shape == self.x_shape and X.stride(1) == 1
             jg.jg_shard(self.plan, jg.JG_T_X, X.data_ptr(), X.stride(0), [t.data_ptr() for t in self.x])
         if W is not None:
-            assert W.is_cuda and W.dtype == torch.float32 and W.shape == (self.N, self.K) and W.stride(1) == 1
+            assert W.is_cuda and W.dtype == torch.float32 and W.shape == self.w_shape and W.stride(1) == 1
             jg.jg_shard(self.plan, jg.JG_T_W, W.data_ptr(), W.stride(0), [t.data_ptr() for t in self.w])
         if b is not None:
             assert self.bias and b.is_cuda and b.dtype == torch.float32 and b.shape == (self.N,)

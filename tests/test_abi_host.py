@@ -56,7 +56,14 @@ def test_plan_validation():
     assert status_of(M=7, ways=4) == jg.JG_E_SHAPE    # 4-way needs even M too
     assert status_of(M=7, K=7, N=7, ways=1) == jg.JG_OK
     assert status_of(dtype=1) == jg.JG_E_DTYPE
-    assert status_of(op=1) == jg.JG_E_DTYPE
+    assert status_of(op=2) == jg.JG_E_DTYPE
+    # the transposed layer splits M and N (2-way), and K as well (4-way)
+    assert status_of(op=jg.JG_OP_XTW) == jg.JG_OK
+    assert status_of(op=jg.JG_OP_XTW, K=7) == jg.JG_OK
+    assert status_of(op=jg.JG_OP_XTW, M=7) == jg.JG_E_SHAPE
+    assert status_of(op=jg.JG_OP_XTW, N=7) == jg.JG_E_SHAPE
+    assert status_of(op=jg.JG_OP_XTW, K=7, ways=4) == jg.JG_E_SHAPE
+    assert status_of(op=jg.JG_OP_XTW, M=7, K=7, N=7, ways=1) == jg.JG_OK
     assert status_of(combine=2) == jg.JG_E_DTYPE
     assert status_of(weights=5) == jg.JG_E_DTYPE
     lib = jg.raw()
@@ -114,6 +121,55 @@ def test_accounting(ways, M, K, N):
         assert e.value.status == jg.JG_E_DTYPE
     finally:
         jg.jg_plan_destroy(p)
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,K,N", [(100, 100, 100), (4320, 16200, 8640), (6, 4, 2), (130, 72, 258)])
+def test_accounting_of_the_transposed_layer(ways, M, K, N):
+    p = jg.jg_plan_create(None, M, K, N, ways, op=jg.JG_OP_XTW)
+    q = lambda what, r=0: jg.jg_plan_query(p, what, r)
+    try:
+        assert q(jg.JG_Q_FLOPS_TOTAL) == 2 * M * K * N
+        assert sum(q(jg.JG_Q_FLOPS_RANK, r) for r in range(ways)) == 2 * M * K * N
+        # nothing is duplicated: the shards tile X (K x M), W (K x N) and Y (M x N) exactly
+        assert sum(q(jg.JG_Q_RESIDENT_BYTES_RANK, r) for r in range(ways)) == 4 * (M * K + N * K + M * N)
+        assert sum(q(jg.JG_Q_X_ROWS, r) * q(jg.JG_Q_X_COLS, r) for r in range(ways)) == M * K
+        assert sum(q(jg.JG_Q_W_ROWS, r) * q(jg.JG_Q_W_COLS, r) for r in range(ways)) == N * K
+        assert sum(q(jg.JG_Q_Y_ROWS, r) * q(jg.JG_Q_Y_COLS, r) for r in range(ways)) == M * N
+        rows, cols = (2 if ways == 4 else 1), (2 if ways >= 2 else 1)
+        for r in range(ways):
+            assert (q(jg.JG_Q_X_ROWS, r), q(jg.JG_Q_X_COLS, r)) == (K // rows, M // cols)
+            assert (q(jg.JG_Q_W_ROWS, r), q(jg.JG_Q_W_COLS, r)) == (K // rows, N // cols)
+            assert (q(jg.JG_Q_Y_ROWS, r), q(jg.JG_Q_Y_COLS, r)) == (M // rows, N // cols)
+            assert q(jg.JG_Q_B_LEN, r) == N // cols
+        ws = q(jg.JG_Q_WORKSPACE_BYTES)
+        if ways == 1:
+            assert ws == 0 and q(jg.JG_Q_EXCHANGE_BYTES_RANK) == 0 and q(jg.JG_Q_GEMM_LAUNCHES) == 1
+            assert q(jg.JG_Q_HBM_BYTES_ALGO) == 4 * (M * K + N * K + M * N)
+        elif ways == 2:
+            # only an activation block changes hands; no partial products
+            assert q(jg.JG_Q_EXCHANGE_BYTES_RANK, 1) == 4 * K * M // 2 and q(jg.JG_Q_GEMM_LAUNCHES) == 1
+            assert q(jg.JG_Q_HBM_BYTES_ALGO) == 4 * (M * K + N * K + M * N)
+            assert 4 * K * M <= ws <= 4 * K * M + 2 * ways * 256
+        else:
+            assert q(jg.JG_Q_EXCHANGE_BYTES_RANK, 3) == 4 * (M * N // 4 + K * M // 4) and q(jg.JG_Q_GEMM_LAUNCHES) == 2
+            assert q(jg.JG_Q_HBM_BYTES_ALGO) == 4 * (M * K + N * K + M * N) + 8 * M * N
+            assert 4 * (M * N + K * M) <= ws <= 4 * (M * N + K * M) + 2 * ways * 256
+        for what in (jg.JG_Q_BACKWARD_WORKSPACE_BYTES, jg.JG_Q_BACKWARD_FLOPS_TOTAL, jg.JG_Q_BACKWARD_GEMM_LAUNCHES):
+            with pytest.raises(jg.JigsawError) as e:     # forward only
+                q(what)
+            assert e.value.status == jg.JG_E_DTYPE
+    finally:
+        jg.jg_plan_destroy(p)
+
+
+def test_backward_refuses_a_transposed_plan():
+    p = jg.jg_plan_create(None, 8, 8, 8, 2, op=jg.JG_OP_XTW)
+    lib = jg.raw()
+    arr = (ctypes.c_void_p * 2)(256, 512)
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    assert lib.jg_linear_backward(p, pp, pp, pp, pp, pp, 256, 1 << 20) == jg.JG_E_NULL   # no context comes first
+    jg.jg_plan_destroy(p)
 
 
 def test_workspace_grows_with_options():
