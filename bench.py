@@ -176,9 +176,9 @@ def measure_backward(cfg, ways, args, X, W):
         flops = L.query(jg.JG_Q_BACKWARD_FLOPS_TOTAL)
         half = flops / 2   # dX and dW cost the same
         kernels = {
-            "dx": dict(kernel="jg::gemm_f32_stream<false, true>", avg_launch_ms=dx_ms / max(dx_n, 1), launches=dx_n,
+            "dx": dict(kernel="jg::gemm_f32_stream<false, true, false>", avg_launch_ms=dx_ms / max(dx_n, 1), launches=dx_n,
                        tflops=half * args.steps / (dx_ms * 1e-3) / 1e12),
-            "dw": dict(kernel="jg::gemm_f32_stream<true, true>", avg_launch_ms=dw_ms / max(dw_n, 1), launches=dw_n,
+            "dw": dict(kernel="jg::gemm_f32_stream<true, true, false>", avg_launch_ms=dw_ms / max(dw_n, 1), launches=dw_n,
                        tflops=half * args.steps / (dw_ms * 1e-3) / 1e12),
         }
         ws = L.bw_ws_bytes
@@ -325,7 +325,7 @@ def main():
                        "n_items": M * K, "ways": args.ways, "M": M, "K": K, "N": N, "seed": xc["seed"],
                        "x_values": "R", "op": "xtw", "combine": args.combine, "weights": args.weights},
             "tflops": r["tflops"], "hbm_algo_gbps": r["hbm_algo_gbps"],
-            "roofline": {"bound": "mfma", "kernel": "jg::gemm_f32_stream<true, true>", "achieved": r["gemm_tflops"],
+            "roofline": {"bound": "mfma", "kernel": "jg::gemm_f32_stream<true, true, false>", "achieved": r["gemm_tflops"],
                          "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": r["gemm_tflops"] / FP32_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None,
                          "avg_launch_ms": r["gemm_avg_launch_ms"], "launches": r["gemm_launches_timed"],
@@ -400,7 +400,7 @@ def main():
         "hbm_algo_gbps": head["hbm_algo_gbps"],
         "hbm_algo_frac_of_8TBps": head["hbm_algo_frac"],
         "roofline": {
-            "bound": "mfma", "kernel": "jg::gemm_f32_stream<false, false>",
+            "bound": "mfma", "kernel": "jg::gemm_f32_stream<false, false, false>",
             "achieved": achieved, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": achieved / FP32_MFMA_PEAK_TFLOPS if achieved else None,
             "avg_launch_ms": head["gemm_avg_launch_ms"], "launches": head["gemm_launches_timed"],

@@ -79,6 +79,7 @@ enum { JG_OP_XWT = 0,                                    /* Y = X W^T (Sec. 4)  
 enum { JG_F32 = 0 };                                     /* the paper's uniform single precision (Sec. 6.1) */
 enum { JG_COMBINE_FUSED = 0, JG_COMBINE_SEPARATE = 1 };  /* where the "+" of Eq. (2)/(4) runs */
 enum { JG_WEIGHTS_COPY = 0, JG_WEIGHTS_DIRECT = 1 };     /* 4-way weight-block hand-off */
+enum { JG_TAIL_SPLIT = 0, JG_TAIL_WHOLE = 1 };           /* last partial round of a GEMM launch */
 enum { JG_T_X = 0, JG_T_W = 1, JG_T_B = 2, JG_T_Y = 3 }; /* tensor selector of jg_shard / jg_gather_as */
 
 typedef struct jg_linear_desc {
@@ -100,6 +101,13 @@ typedef struct jg_linear_desc {
                             bold) is copied into the workspace first, as a transfer
                             would deliver it.  JG_WEIGHTS_DIRECT: the peer's buffer is
                             read in place.                                              */
+    int32_t tail;        /* JG_TAIL_SPLIT: when the tiles of a GEMM launch do not fill a whole
+                            number of rounds of the chip's workgroup slots, the K loops of
+                            the tiles of the last partial round are cut into equal runs, one
+                            per slot, and a second small kernel adds each tile's runs in
+                            ascending k order (no atomics: results do not vary from run to
+                            run).  Needs JG_Q_TAIL_SCRATCH_BYTES more workspace.
+                            JG_TAIL_WHOLE: one workgroup per tile throughout.           */
 } jg_linear_desc;
 
 typedef enum jg_query {
@@ -118,7 +126,9 @@ typedef enum jg_query {
     JG_Q_GEMM_LAUNCHES = 13,     /* GEMM kernel launches per forward (rank ignored)            */
     JG_Q_BACKWARD_WORKSPACE_BYTES = 14, /* device bytes jg_linear_backward needs (rank ignored)  */
     JG_Q_BACKWARD_FLOPS_TOTAL = 15,     /* 4 M K N: twice the forward (Sec. 6.3 work model)      */
-    JG_Q_BACKWARD_GEMM_LAUNCHES = 16    /* GEMM kernel launches per backward (rank ignored)      */
+    JG_Q_BACKWARD_GEMM_LAUNCHES = 16,   /* GEMM kernel launches per backward (rank ignored)      */
+    JG_Q_TAIL_SCRATCH_BYTES = 17,       /* part of JG_Q_WORKSPACE_BYTES that JG_TAIL_SPLIT adds   */
+    JG_Q_BACKWARD_TAIL_SCRATCH_BYTES = 18 /* the same for JG_Q_BACKWARD_WORKSPACE_BYTES           */
 } jg_query;
 
 typedef enum jg_kernel {         /* kernel classes for jg_profile_read */
@@ -129,7 +139,8 @@ typedef enum jg_kernel {         /* kernel classes for jg_profile_read */
     JG_KERNEL_GATHER = 4,
     JG_KERNEL_GEMM_DX = 5,       /* backward dX = dY W products                          */
     JG_KERNEL_GEMM_DW = 6,       /* backward dW = dY^T X products                        */
-    JG_KERNEL_COUNT = 7
+    JG_KERNEL_JOIN = 7,          /* adds the runs of split tail tiles (JG_TAIL_SPLIT)    */
+    JG_KERNEL_COUNT = 8
 } jg_kernel;
 
 /* init.  Creates a context bound to HIP device `device` and to `hip_stream`
@@ -181,7 +192,8 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
  *   launch 2: every rank's kept product, accumulated on top of the received partial,
  *             plus the bias, written to Y_r (JG_COMBINE_FUSED); or the kept product
  *             followed by a separate combine kernel (JG_COMBINE_SEPARATE).
- * ways = 1 is a single GEMM with the bias in its epilogue and needs no workspace.
+ * ways = 1 is a single GEMM with the bias in its epilogue; it needs no workspace beyond
+ * the tail scratch of JG_TAIL_SPLIT.
  * JG_OP_XTW plans: (JG_WEIGHTS_COPY) copy each rank's incoming activation block; 2-way: one
  * launch of the four block products, each written with the bias straight into its row half
  * of Y_r; 4-way: launch 1 / launch 2 as above, the partial going to rank (1-i, j).  Both

@@ -33,13 +33,15 @@ JG_OP_XWT, JG_OP_XTW = 0, 1
 JG_F32 = 0
 JG_COMBINE_FUSED, JG_COMBINE_SEPARATE = 0, 1
 JG_WEIGHTS_COPY, JG_WEIGHTS_DIRECT = 0, 1
+JG_TAIL_SPLIT, JG_TAIL_WHOLE = 0, 1
 JG_T_X, JG_T_W, JG_T_B, JG_T_Y = 0, 1, 2, 3
 (JG_Q_WORKSPACE_BYTES, JG_Q_FLOPS_TOTAL, JG_Q_FLOPS_RANK, JG_Q_HBM_BYTES_ALGO,
  JG_Q_EXCHANGE_BYTES_RANK, JG_Q_X_ROWS, JG_Q_X_COLS, JG_Q_W_ROWS, JG_Q_W_COLS,
  JG_Q_Y_ROWS, JG_Q_Y_COLS, JG_Q_B_LEN, JG_Q_RESIDENT_BYTES_RANK, JG_Q_GEMM_LAUNCHES,
- JG_Q_BACKWARD_WORKSPACE_BYTES, JG_Q_BACKWARD_FLOPS_TOTAL, JG_Q_BACKWARD_GEMM_LAUNCHES) = range(17)
+ JG_Q_BACKWARD_WORKSPACE_BYTES, JG_Q_BACKWARD_FLOPS_TOTAL, JG_Q_BACKWARD_GEMM_LAUNCHES,
+ JG_Q_TAIL_SCRATCH_BYTES, JG_Q_BACKWARD_TAIL_SCRATCH_BYTES) = range(19)
 (JG_KERNEL_GEMM, JG_KERNEL_WEIGHT_COPY, JG_KERNEL_COMBINE, JG_KERNEL_SHARD,
- JG_KERNEL_GATHER, JG_KERNEL_GEMM_DX, JG_KERNEL_GEMM_DW, JG_KERNEL_COUNT) = range(8)
+ JG_KERNEL_GATHER, JG_KERNEL_GEMM_DX, JG_KERNEL_GEMM_DW, JG_KERNEL_JOIN, JG_KERNEL_COUNT) = range(9)
 
 EXPORTS = ("jg_init", "jg_free", "jg_plan_create", "jg_plan_destroy", "jg_plan_query", "jg_shard",
            "jg_linear_forward", "jg_linear_backward", "jg_gather", "jg_gather_as", "jg_profile", "jg_profile_read", "jg_strerror",
@@ -49,7 +51,8 @@ EXPORTS = ("jg_init", "jg_free", "jg_plan_create", "jg_plan_destroy", "jg_plan_q
 class jg_linear_desc(ctypes.Structure):
     _fields_ = [("M", ctypes.c_int64), ("K", ctypes.c_int64), ("N", ctypes.c_int64),
                 ("ways", ctypes.c_int32), ("op", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("has_bias", ctypes.c_int32), ("combine", ctypes.c_int32), ("weights", ctypes.c_int32)]
+                ("has_bias", ctypes.c_int32), ("combine", ctypes.c_int32), ("weights", ctypes.c_int32),
+                ("tail", ctypes.c_int32)]
 
 
 class JigsawError(RuntimeError):
@@ -119,8 +122,8 @@ def jg_free(ctx) -> None:
 
 def jg_plan_create(ctx, M: int, K: int, N: int, ways: int, has_bias: bool = False,
                    combine: int = JG_COMBINE_FUSED, weights: int = JG_WEIGHTS_COPY,
-                   op: int = JG_OP_XWT, dtype: int = JG_F32) -> int:
-    d = jg_linear_desc(M, K, N, ways, op, dtype, int(has_bias), combine, weights)
+                   op: int = JG_OP_XWT, dtype: int = JG_F32, tail: int = JG_TAIL_SPLIT) -> int:
+    d = jg_linear_desc(M, K, N, ways, op, dtype, int(has_bias), combine, weights, tail)
     out = ctypes.c_void_p()
     _raise(_lib.jg_plan_create(ctx, ctypes.byref(d), ctypes.byref(out)), "jg_plan_create")
     return out.value

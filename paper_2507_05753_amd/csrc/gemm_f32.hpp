@@ -43,6 +43,15 @@
 // the id is first folded into a per-XCD contiguous range, then walked column-major inside
 // bands of 8 row-tiles.  The 64 workgroups an XCD has in flight (2 per CU) therefore form an
 // 8 x 8 block of tiles that shares 8 A panels and 8 B panels in that XCD's L2.
+//
+// Tail: tiles are equal, so a launch whose tile count is not a multiple of the number of
+// workgroups the chip holds (2 per CU) ends with a partial round in which part of the chip
+// idles - 10 % of the time for 2312 long tiles on 512 slots.  The launcher therefore runs only
+// whole rounds one tile per workgroup; the K loops of the remaining tiles are cut into equal
+// runs of slabs, one run per extra workgroup (a run covers the end of one tile and the start of
+// the next).  Each run writes its raw accumulators to a scratch tile, and a second small kernel
+// (`gemm_f32_join`) adds a tile's runs in ascending k order, then the addend and the bias, and
+// stores C: no atomics, no flags, the same result on every run.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -77,8 +86,25 @@ struct GemmGroup {
     int nprob;
     int M, N, K;          // common shape of every problem in the group
     int tiles_m, tiles_n; // ceil(M / BM), ceil(N / BN)
-    int per_xcd;          // ceil(nprob * tiles_m * tiles_n / kNumXcd)
+    int per_xcd;          // whole tiles handled by each XCD's workgroups (see launch_gemm_group)
+    // split tail (all zero when it is not used): tiles [whole_tiles, total) are cut into runs
+    int whole_tiles;      // tiles that get a workgroup of their own = kNumXcd * per_xcd when the tail is split
+    int run_wgs;          // workgroups that share the remaining tiles' K loops
+    int run_len, run_extra;   // run w covers run_len slabs, one more for w < run_extra
+    float* run_tiles;     // scratch: two BM x BN tiles per run workgroup
 };
+
+// First slab-iteration (tile-major, then slab) of run w; the runs partition [0, tail tiles * slabs).
+__host__ __device__ inline int64_t run_begin(const GemmGroup& g, int w)
+{
+    return (int64_t)w * g.run_len + (w < g.run_extra ? w : g.run_extra);
+}
+// The run that contains slab-iteration `it`.
+__host__ __device__ inline int run_of(const GemmGroup& g, int64_t it)
+{
+    const int64_t long_part = (int64_t)g.run_extra * (g.run_len + 1);
+    return it < long_part ? (int)(it / (g.run_len + 1)) : g.run_extra + (int)((it - long_part) / g.run_len);
+}
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void lds_void;
@@ -433,9 +459,12 @@ struct GuardedLoader {
 };
 
 // ------------------------------------------------------------------------------------------
-// asynchronous-load kernel: one tile per workgroup, two workgroups per CU
+// asynchronous-load kernel, two workgroups per CU.  RUNS = false: one whole tile per workgroup
+// (tiles [0, whole_tiles)).  RUNS = true: one run of slabs of the split tail per workgroup; it is
+// a separate instance, launched after the first on the same stream, so that the whole-tile code
+// carries none of the run bookkeeping.
 // ------------------------------------------------------------------------------------------
-template <bool A_KS, bool B_KS>
+template <bool A_KS, bool B_KS, bool RUNS>
 __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGroup g)
 {
     // One array per slab buffer: distinct LDS objects let the compiler prove that the
@@ -444,21 +473,54 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGro
     __shared__ __align__(16) float ring0[STAGE_FLOATS];
     __shared__ __align__(16) float ring1[STAGE_FLOATS];
 
-    const int lid = (blockIdx.x % kNumXcd) * g.per_xcd + blockIdx.x / kNumXcd;
-    if (lid >= g.nprob * g.tiles_m * g.tiles_n) return;   // whole workgroup leaves before any barrier
+    const int M = g.M, N = g.N, K = g.K;
+    const int nkt_all = (K + BK - 1) / BK;
+    LaneMap L;
+    L.init(threadIdx.x);
+
+    // What this workgroup does: one whole tile, or one run of slab-iterations [it, it_end) of the
+    // tail tiles, which touches one or two tiles.
+    constexpr bool is_run = RUNS;
+    int lid = 0;
+    int64_t it = 0, it_end = 0;
+    if (is_run) {
+        it = run_begin(g, (int)blockIdx.x);
+        it_end = run_begin(g, (int)blockIdx.x + 1);
+    } else {
+        lid = (blockIdx.x % kNumXcd) * g.per_xcd + blockIdx.x / kNumXcd;
+        if (lid >= g.whole_tiles) return;   // whole workgroup leaves before any barrier
+    }
+
+    for (int pass = 0;; ++pass) {   // one pass per tile touched: 1 for a whole tile, 1 or 2 for a run
+    int k0 = 0, k1 = nkt_all;       // slabs of this pass
+    if (is_run) {
+        if (it >= it_end) break;
+        const int t = (int)(it / nkt_all);
+        k0 = (int)(it - (int64_t)t * nkt_all);
+        k1 = (int)min((int64_t)nkt_all, k0 + (it_end - it));
+        lid = g.whole_tiles + t;
+    }
     const TileCoord tc = decode_tile(g, lid);
     const GemmProblem& P = g.p[tc.prob];
-    const int M = g.M, N = g.N, K = g.K;
     const int m0 = tc.m0, n0 = tc.n0;
-    const int nkt = (K + BK - 1) / BK;
-    // slabs 2 .. nkt_spread - 1 are requested in the spread form; a ragged last slab is not, if an
+    // where the accumulators start from and go to: the problem's addend / C / bias, or (a run)
+    // zero and a scratch tile of its own
+    GemmProblem out = P;
+    int out_m = M, out_n = N, out_m0 = m0, out_n0 = n0;
+    if (is_run) {
+        out.C = g.run_tiles + ((int64_t)2 * (int)blockIdx.x + pass) * (BM * BN);
+        out.ldc = BN;
+        out.addend = nullptr;
+        out.bias = nullptr;
+        out_m = BM; out_n = BN; out_m0 = 0; out_n0 = 0;
+    }
+    const int nkt = k1;             // the pass ends before this slab
+    // slabs up to nkt_spread - 1 are requested in the spread form; a ragged last slab is not, if an
     // operand is K-contiguous
-    const bool ragged_burst = (!A_KS || !B_KS) && (K % BK) != 0;
+    const bool ragged_burst = (!A_KS || !B_KS) && (K % BK) != 0 && k1 == nkt_all;
     const int nkt_spread = ragged_burst ? nkt - 1 : nkt;
     const int kt_burst = ragged_burst ? nkt - 1 : -1;
 
-    LaneMap L;
-    L.init(threadIdx.x);
     StreamLoader<A_KS> load_a;
     StreamLoader<B_KS> load_b;
     load_a.init(OperandView{P.A, P.lda, M, m0}, K, L.wave, L.lane);
@@ -536,8 +598,8 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGro
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    request_slab(0, ring0);
-    init_acc(P, M, N, m0, n0, L, sum);   // its loads fly together with slab 0
+    request_slab(k0, ring0);
+    init_acc(out, out_m, out_n, out_m0, out_n0, L, sum);   // its loads fly together with the first slab
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -546,19 +608,60 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGro
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     JG_WAIT_VMCNT(0);
     __syncthreads();
-    if (1 < nkt) request_slab(1, ring1);
+    if (k0 + 1 < nkt) request_slab(k0 + 1, ring1);
     read_frags(ring0, 0, fa[0], fb[0]);
     __builtin_amdgcn_sched_barrier(0);
-    int kt = 0;
-    for (; kt + 1 < nkt; kt += 2) {
+    int kt = k0;
+    for (int pair = 0; kt + 1 < nkt; kt += 2, ++pair) {
         step(kt, ring0, ring1);
         step(kt + 1, ring1, ring0);
-        if ((kt & (kFlushSlabs - 1)) == kFlushSlabs - 2) fold_acc(sum, acc);
+        if ((pair & (kFlushSlabs / 2 - 1)) == kFlushSlabs / 2 - 1) fold_acc(sum, acc);
     }
     if (kt < nkt) step(kt, ring0, ring1);
     fold_acc(sum, acc);
 
-    store_tile(P, M, N, m0, n0, L, sum);
+    store_tile(out, out_m, out_n, out_m0, out_n0, L, sum);
+    if (!is_run) break;
+    it += k1 - k0;
+    __syncthreads();   // every wave is done with the slab buffers before the next pass refills them
+    }
+}
+
+// Second kernel of a launch whose tail was split: workgroup t adds the runs of tail tile t in
+// ascending k order, then the addend and the bias, and stores the tile of C.
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_f32_join(const GemmGroup g)
+{
+    const int t = blockIdx.x;
+    const int nkt = (g.K + BK - 1) / BK;
+    const TileCoord tc = decode_tile(g, g.whole_tiles + t);
+    const GemmProblem& P = g.p[tc.prob];
+    const int64_t it0 = (int64_t)t * nkt;
+    const int w_first = run_of(g, it0), w_last = run_of(g, it0 + nkt - 1);
+    const float* __restrict__ addend = P.addend;
+    const float* __restrict__ bias = P.bias;
+#pragma unroll 1
+    for (int u = 0; u < BM * BN / 4 / GEMM_THREADS; ++u) {
+        const int idx = threadIdx.x + GEMM_THREADS * u;   // one 4-element piece of a tile row
+        const int r = idx / (BN / 4), c = (idx % (BN / 4)) * 4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int w = w_first; w <= w_last; ++w) {
+            const int first_tile = (int)(run_begin(g, w) / nkt);   // the tile of the run's pass 0
+            const float* src = g.run_tiles + ((int64_t)2 * w + (t - first_tile)) * (BM * BN);
+            const float4 p = *reinterpret_cast<const float4*>(src + r * BN + c);
+            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+        }
+        const int row = tc.m0 + r, col = tc.n0 + c;
+        if (row >= g.M) continue;
+        const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (col + q >= g.N) break;
+            float y = e[q];
+            if (addend) y += addend[(int64_t)row * P.ldadd + col + q];
+            if (bias) y += bias[col + q];
+            P.C[(int64_t)row * P.ldc + col + q] = y;
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -570,7 +673,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_guarded(const GemmGr
     __shared__ __align__(16) float slab[STAGE_FLOATS];
 
     const int lid = (blockIdx.x % kNumXcd) * g.per_xcd + blockIdx.x / kNumXcd;
-    if (lid >= g.nprob * g.tiles_m * g.tiles_n) return;
+    if (lid >= g.whole_tiles) return;   // the guarded kernel never splits: whole_tiles = all tiles
     const TileCoord tc = decode_tile(g, lid);
     const GemmProblem& P = g.p[tc.prob];
     const int M = g.M, N = g.N, K = g.K;
@@ -631,37 +734,104 @@ inline bool operand_streams(const float* p, int ld, bool ks, int extent, int K)
 template <bool A_KS, bool B_KS>
 inline void launch_gemm_layout(const GemmGroup& g, bool stream_ok, hipStream_t stream)
 {
-    const unsigned grid = (unsigned)(kNumXcd * g.per_xcd);
-    if (stream_ok)
-        hipLaunchKernelGGL((gemm_f32_stream<A_KS, B_KS>), dim3(grid), dim3(GEMM_THREADS), 0, stream, g);
-    else
+    const unsigned grid = (unsigned)(kNumXcd * g.per_xcd);   // whole tiles
+    if (stream_ok) {
+        if (grid)
+            hipLaunchKernelGGL((gemm_f32_stream<A_KS, B_KS, false>), dim3(grid), dim3(GEMM_THREADS), 0, stream, g);
+        if (g.run_wgs)
+            hipLaunchKernelGGL((gemm_f32_stream<A_KS, B_KS, true>), dim3((unsigned)g.run_wgs), dim3(GEMM_THREADS), 0,
+                               stream, g);
+    } else
         hipLaunchKernelGGL((gemm_f32_guarded<A_KS, B_KS>), dim3(grid), dim3(GEMM_THREADS), 0, stream, g);
 }
 
-// Host side: fills the derived fields of `g` and enqueues the launch.
+// ------------------------------------------------------------------------------------------
+// Host side
+// ------------------------------------------------------------------------------------------
+constexpr int kMinRunSlabs = 32;   // a run shorter than this is not worth its start-up and its scratch tile
+constexpr int kRunOverheadSlabs = 6;   // start-up, scratch store and join of a run, in slab times
+
+// How a launch of `total` tiles with `nkt` slabs each is divided on a chip that holds `slots`
+// workgroups: `whole` tiles one per workgroup, the rest (if that pays) in `runs` equal runs.
+struct TailSplit {
+    int whole, runs, run_len, run_extra;
+};
+inline TailSplit plan_tail(int64_t total, int nkt, int slots)
+{
+    TailSplit t = {(int)total, 0, 0, 0};
+    if (slots < kNumXcd) return t;
+    slots -= slots % kNumXcd;                         // whole rounds must fill every XCD's range evenly
+    const int64_t rest = total % slots;
+    if (rest == 0) return t;
+    const int64_t iters = rest * nkt;
+    const int64_t runs = iters / kMinRunSlabs < slots ? iters / kMinRunSlabs : slots;
+    if (runs <= rest) return t;                       // no finer than whole tiles: nothing gained
+    // Estimated time of the last round either way, in slab times at the two-workgroups-per-CU rate
+    // (a workgroup alone on its CU runs about 1.8 times as fast); split only for a saving of at least
+    // 3 % of the launch.
+    auto round_time = [slots](int64_t wgs, int64_t slabs) { return (double)slabs * (2 * wgs <= slots ? 0.55 : 1.0); };
+    const double saving = round_time(rest, nkt) - (round_time(runs, (iters + runs - 1) / runs) + kRunOverheadSlabs);
+    if (saving < 0.03 * ((double)total / slots) * nkt) return t;
+    t.whole = (int)(total - rest);
+    t.runs = (int)runs;
+    t.run_len = (int)(iters / runs);
+    t.run_extra = (int)(iters % runs);
+    return t;
+}
+// Scratch bytes launch_gemm_group may use for a launch of `total` tiles (0: the tail is not split).
+inline size_t tail_scratch_bytes(int64_t total, int K, int slots)
+{
+    const TailSplit t = plan_tail(total, (K + BK - 1) / BK, slots);
+    return (size_t)t.runs * 2 * BM * BN * sizeof(float);
+}
+
+// Fills the derived fields of `g` and enqueues the GEMM kernel.  `scratch` (device, 16-byte
+// aligned, may be null) enables the split tail when it holds tail_scratch_bytes(...) bytes;
+// `*needs_join` then tells the caller to enqueue launch_gemm_join(g) next on the same stream.
 // Preconditions (checked by the C-ABI layer): 1 <= nprob <= 4; M, N, K >= 1; all pointers valid
 // for their shapes; leading dimensions at least the contiguous extent of their operand.
-inline hipError_t launch_gemm_group(GemmGroup& g, int layout, hipStream_t stream)
+inline hipError_t launch_gemm_group(GemmGroup& g, int layout, hipStream_t stream, float* scratch,
+                                    size_t scratch_bytes, int slots, bool* needs_join)
 {
+    *needs_join = false;
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
     const int64_t total = (int64_t)g.nprob * g.tiles_m * g.tiles_n;
     // The tile index is a 32-bit block id (and the grid is one-dimensional): refuse a product
     // with more tiles than that instead of wrapping around.
-    if (total + kNumXcd > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    g.per_xcd = (int)((total + kNumXcd - 1) / kNumXcd);
+    if (total + kNumXcd + slots > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     const bool a_ks = layout == kGemmTN, b_ks = layout != kGemmNT;
     bool stream_ok = true;
     for (int i = 0; i < g.nprob; ++i) {
         stream_ok = stream_ok && operand_streams(g.p[i].A, g.p[i].lda, a_ks, g.M, g.K) &&
                     operand_streams(g.p[i].B, g.p[i].ldb, b_ks, g.N, g.K);
     }
+    TailSplit t = {(int)total, 0, 0, 0};
+    if (stream_ok && scratch) {
+        t = plan_tail(total, (g.K + BK - 1) / BK, slots);
+        if ((size_t)t.runs * 2 * BM * BN * sizeof(float) > scratch_bytes) t = {(int)total, 0, 0, 0};
+    }
+    g.whole_tiles = t.whole;
+    g.run_wgs = t.runs;
+    g.run_len = t.run_len;
+    g.run_extra = t.run_extra;
+    g.run_tiles = t.runs ? scratch : nullptr;
+    g.per_xcd = (t.whole + kNumXcd - 1) / kNumXcd;   // exact when the tail is split (whole is a multiple of 8)
     switch (layout) {
     case kGemmNT: launch_gemm_layout<false, false>(g, stream_ok, stream); break;
     case kGemmNN: launch_gemm_layout<false, true>(g, stream_ok, stream); break;
     case kGemmTN: launch_gemm_layout<true, true>(g, stream_ok, stream); break;
     default: return hipErrorInvalidValue;
     }
+    *needs_join = t.runs > 0;
+    return hipGetLastError();
+}
+
+// The second kernel of a launch whose tail was split (see launch_gemm_group).
+inline hipError_t launch_gemm_join(const GemmGroup& g, hipStream_t stream)
+{
+    const int tail_tiles = g.nprob * g.tiles_m * g.tiles_n - g.whole_tiles;
+    hipLaunchKernelGGL(gemm_f32_join, dim3((unsigned)tail_tiles), dim3(GEMM_THREADS), 0, stream, g);
     return hipGetLastError();
 }
 

@@ -29,6 +29,7 @@ bool hip_ok(hipError_t e, const char* what)
 
 constexpr int kProfileMaxLaunches = 8192;
 constexpr int64_t kMaxDim = 0x7fffffff - 1024;   // every dimension fits an int with tile slack
+constexpr int kDefaultSlots = 512;               // MI355X: 256 CUs x 2 resident GEMM workgroups (plans made without a context)
 constexpr size_t kWsAlign = 256;
 
 struct TimedLaunch {
@@ -40,6 +41,7 @@ struct TimedLaunch {
 
 struct jg_ctx {
     int device;
+    int slots;                           // workgroups of the GEMM kernel the device holds at once (2 per CU)
     hipStream_t stream;
     bool profiling;
     std::vector<hipEvent_t> pool;        // created on first jg_profile(ctx, 1)
@@ -61,6 +63,9 @@ struct jg_plan {
     size_t ws_bytes;
     // backward workspace: ways partials of dX blocks, then (4-way) ways partials of dW blocks
     size_t bw_dx_bytes, bw_dw_bytes, bw_off_dw, bw_ws_bytes;
+    // scratch tiles of the split tail (largest need over the pass's launches), at the end of each workspace
+    int slots;
+    size_t tail_bytes, off_tail, bw_tail_bytes, bw_off_tail;
 };
 
 namespace {
@@ -151,6 +156,7 @@ int jg_init(jg_ctx** out, int device, void* hip_stream)
     jg_ctx* c = new (std::nothrow) jg_ctx();
     if (!c) return JG_E_HIP;
     c->device = device;
+    c->slots = 2 * prop.multiProcessorCount;
     c->stream = (hipStream_t)hip_stream;
     c->profiling = false;
     c->pool_used = 0;
@@ -221,6 +227,7 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     if (d.combine != JG_COMBINE_FUSED && d.combine != JG_COMBINE_SEPARATE) return JG_E_DTYPE;
     if (d.weights != JG_WEIGHTS_COPY && d.weights != JG_WEIGHTS_DIRECT) return JG_E_DTYPE;
     if (d.has_bias != 0 && d.has_bias != 1) return JG_E_DTYPE;
+    if (d.tail != JG_TAIL_SPLIT && d.tail != JG_TAIL_WHOLE) return JG_E_DTYPE;
     if (d.M <= 0 || d.K <= 0 || d.N <= 0) return JG_E_SHAPE;
     if (d.M > kMaxDim || d.K > kMaxDim || d.N > kMaxDim) return JG_E_SHAPE;
     // the dimensions that are halved: X W^T splits K (2-way) and M, K (4-way); X^T W splits M and K, M
@@ -293,6 +300,27 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
             p->bw_ws_bytes += p->bw_dw_bytes * d.ways;
         }
     }
+    // scratch for the split tail: the largest need over the launches of each pass
+    p->slots = ctx ? ctx->slots : kDefaultSlots;
+    p->tail_bytes = p->bw_tail_bytes = 0;
+    if (d.tail == JG_TAIL_SPLIT) {
+        auto need = [&](int nprob, int64_t m, int64_t n, int64_t k) {
+            const int64_t tiles = nprob * ((m + jg::BM - 1) / jg::BM) * ((n + jg::BN - 1) / jg::BN);
+            return jg::tail_scratch_bytes(tiles, (int)k, p->slots);
+        };
+        if (xtw) {
+            p->tail_bytes = need(d.ways == 1 ? 1 : 4, p->xc, p->wc, p->xr);
+        } else {
+            p->tail_bytes = need(d.ways, p->yr, p->yc, p->xc);
+            const size_t dx = need(d.ways, p->xr, p->xc, p->yc);
+            const size_t dw = need(d.ways == 1 ? 1 : 4, p->yc, p->xc, p->xr);
+            p->bw_tail_bytes = dx > dw ? dx : dw;
+        }
+    }
+    p->off_tail = p->ws_bytes;
+    p->ws_bytes += p->tail_bytes;
+    p->bw_off_tail = p->bw_ws_bytes;
+    p->bw_ws_bytes += p->bw_tail_bytes;
     *out = p;
     return JG_OK;
 }
@@ -309,7 +337,7 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     const int64_t M = d.M, K = d.K, N = d.N;
     const bool xtw = d.op == JG_OP_XTW;
     if (xtw && (what == JG_Q_BACKWARD_WORKSPACE_BYTES || what == JG_Q_BACKWARD_FLOPS_TOTAL ||
-                what == JG_Q_BACKWARD_GEMM_LAUNCHES))
+                what == JG_Q_BACKWARD_GEMM_LAUNCHES || what == JG_Q_BACKWARD_TAIL_SCRATCH_BYTES))
         return JG_E_DTYPE;   // no backward for this op
     switch (what) {
     case JG_Q_WORKSPACE_BYTES: *out = (int64_t)plan->ws_bytes; break;
@@ -346,6 +374,8 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     case JG_Q_BACKWARD_WORKSPACE_BYTES: *out = (int64_t)plan->bw_ws_bytes; break;
     case JG_Q_BACKWARD_FLOPS_TOTAL: *out = 4 * M * K * N; break;
     case JG_Q_BACKWARD_GEMM_LAUNCHES: *out = d.ways == 1 ? 2 : d.ways == 2 ? 3 : 4; break;
+    case JG_Q_TAIL_SCRATCH_BYTES: *out = (int64_t)plan->tail_bytes; break;
+    case JG_Q_BACKWARD_TAIL_SCRATCH_BYTES: *out = (int64_t)plan->bw_tail_bytes; break;
     default: return JG_E_DTYPE;
     }
     return JG_OK;
@@ -447,6 +477,26 @@ int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, in
     return jg_gather_as(plan, JG_T_Y, y_sh, global_y, ld);
 }
 
+// One GEMM launch of a pass (timed as `kernel_class`), followed by the join kernel when the
+// launcher split the tail; `scratch` is the pass's tail region of the caller's workspace.
+static bool run_gemm(const jg_plan* plan, jg::GemmGroup& g, int layout, int kernel_class, char* scratch,
+                     size_t scratch_bytes)
+{
+    jg_ctx* c = plan->ctx;
+    bool join = false;
+    {
+        ScopedTimer t(c, kernel_class);
+        if (!HIP_OK(jg::launch_gemm_group(g, layout, c->stream, reinterpret_cast<float*>(scratch), scratch_bytes,
+                                          plan->slots, &join)))
+            return false;
+    }
+    if (join) {
+        ScopedTimer t(c, JG_KERNEL_JOIN);
+        if (!HIP_OK(jg::launch_gemm_join(g, c->stream))) return false;
+    }
+    return true;
+}
+
 // Forward pass of the transposed layer Y = X^T W (+ b); arguments already checked.  Every block
 // product is a GEMM whose two operands are read along their row stride (A = an X block, K x M;
 // B = a W block, K x N).
@@ -458,6 +508,7 @@ static int forward_xtw(const jg_plan* plan, const float* const* x_sh, const floa
     jg_ctx* c = plan->ctx;
     auto bias_of = [&](int r) -> const float* { return d.has_bias ? b_sh[r] : nullptr; };
     const int ldx = (int)plan->xc, ldw = (int)plan->wc, ldy = (int)plan->yc;
+    char* tail = plan->tail_bytes ? ws + plan->off_tail : nullptr;
 
     jg::GemmGroup g;
     std::memset(&g, 0, sizeof(g));
@@ -468,8 +519,7 @@ static int forward_xtw(const jg_plan* plan, const float* const* x_sh, const floa
     if (ways == 1) {
         g.nprob = 1;
         g.p[0] = {x_sh[0], w_sh[0], y_sh[0], nullptr, bias_of(0), ldx, ldw, ldy, 0};
-        ScopedTimer t(c, JG_KERNEL_GEMM);
-        return HIP_OK(jg::launch_gemm_group(g, jg::kGemmTN, c->stream)) ? JG_OK : JG_E_HIP;
+        return run_gemm(plan, g, jg::kGemmTN, JG_KERNEL_GEMM, tail, plan->tail_bytes) ? JG_OK : JG_E_HIP;
     }
 
     // the activation block every rank gets from its row neighbour (rank r ^ 1)
@@ -501,8 +551,7 @@ static int forward_xtw(const jg_plan* plan, const float* const* x_sh, const floa
             g.p[2 * r] = {x_sh[r], w_sh[r], y_sh[r] + r * half, nullptr, bias_of(r), ldx, ldw, ldy, 0};
             g.p[2 * r + 1] = {x_in[r], w_sh[r], y_sh[r] + (1 - r) * half, nullptr, bias_of(r), ldx, ldw, ldy, 0};
         }
-        ScopedTimer t(c, JG_KERNEL_GEMM);
-        return HIP_OK(jg::launch_gemm_group(g, jg::kGemmTN, c->stream)) ? JG_OK : JG_E_HIP;
+        return run_gemm(plan, g, jg::kGemmTN, JG_KERNEL_GEMM, tail, plan->tail_bytes) ? JG_OK : JG_E_HIP;
     }
 
     // 4-way.  Rank (i, j) = 2 i + j: own X block -> a term of Y block (j, j), received X block -> a
@@ -520,22 +569,15 @@ static int forward_xtw(const jg_plan* plan, const float* const* x_sh, const floa
     g.nprob = 4;
     for (int r = 0; r < 4; ++r)
         g.p[r] = {x_send[r], w_sh[r], send_buf(r), nullptr, nullptr, ldx, ldw, ldy, 0};
-    {
-        ScopedTimer t(c, JG_KERNEL_GEMM);
-        if (!HIP_OK(jg::launch_gemm_group(g, jg::kGemmTN, c->stream))) return JG_E_HIP;
-    }
+    if (!run_gemm(plan, g, jg::kGemmTN, JG_KERNEL_GEMM, tail, plan->tail_bytes)) return JG_E_HIP;
     if (d.combine == JG_COMBINE_FUSED) {
         for (int r = 0; r < 4; ++r)
             g.p[r] = {x_keep[r], w_sh[r], y_sh[r], send_buf(r ^ 2), bias_of(r), ldx, ldw, ldy, ldy};
-        ScopedTimer t(c, JG_KERNEL_GEMM);
-        return HIP_OK(jg::launch_gemm_group(g, jg::kGemmTN, c->stream)) ? JG_OK : JG_E_HIP;
+        return run_gemm(plan, g, jg::kGemmTN, JG_KERNEL_GEMM, tail, plan->tail_bytes) ? JG_OK : JG_E_HIP;
     }
     for (int r = 0; r < 4; ++r)
         g.p[r] = {x_keep[r], w_sh[r], kept_buf(r), nullptr, nullptr, ldx, ldw, ldy, 0};
-    {
-        ScopedTimer t(c, JG_KERNEL_GEMM);
-        if (!HIP_OK(jg::launch_gemm_group(g, jg::kGemmTN, c->stream))) return JG_E_HIP;
-    }
+    if (!run_gemm(plan, g, jg::kGemmTN, JG_KERNEL_GEMM, tail, plan->tail_bytes)) return JG_E_HIP;
     jg::CombineGroup cb;
     std::memset(&cb, 0, sizeof(cb));
     cb.nblocks = 4;
@@ -569,6 +611,7 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
     auto bias_of = [&](int r) -> const float* { return d.has_bias ? b_sh[r] : nullptr; };
 
     if (d.op == JG_OP_XTW) return forward_xtw(plan, x_sh, w_sh, b_sh, y_sh, ws);
+    char* tail = plan->tail_bytes ? ws + plan->off_tail : nullptr;
 
     jg::GemmGroup g;
     std::memset(&g, 0, sizeof(g));
@@ -581,8 +624,7 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
     if (ways == 1) {
         g.nprob = 1;
         g.p[0] = {x_sh[0], w_sh[0], y_sh[0], nullptr, bias_of(0), ldk, ldk, ldn, 0};
-        ScopedTimer t(c, JG_KERNEL_GEMM);
-        return HIP_OK(jg::launch_gemm_group(g, jg::kGemmNT, c->stream)) ? JG_OK : JG_E_HIP;
+        return run_gemm(plan, g, jg::kGemmNT, JG_KERNEL_GEMM, tail, plan->tail_bytes) ? JG_OK : JG_E_HIP;
     }
 
     auto send_buf = [&](int r) { return reinterpret_cast<float*>(ws + plan->off_send + r * plan->part_bytes); };
@@ -631,24 +673,17 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
     g.nprob = ways;
     for (int r = 0; r < ways; ++r)
         g.p[r] = {x_sh[r], w_send[r], send_buf(r), nullptr, nullptr, ldk, ldk, ldn, 0};
-    {
-        ScopedTimer t(c, JG_KERNEL_GEMM);
-        if (!HIP_OK(jg::launch_gemm_group(g, jg::kGemmNT, c->stream))) return JG_E_HIP;
-    }
+    if (!run_gemm(plan, g, jg::kGemmNT, JG_KERNEL_GEMM, tail, plan->tail_bytes)) return JG_E_HIP;
 
     // launch 2: the kept products
     if (d.combine == JG_COMBINE_FUSED) {
         for (int r = 0; r < ways; ++r)
             g.p[r] = {x_sh[r], w_keep[r], y_sh[r], send_buf(recv_from[r]), bias_of(r), ldk, ldk, ldn, ldn};
-        ScopedTimer t(c, JG_KERNEL_GEMM);
-        return HIP_OK(jg::launch_gemm_group(g, jg::kGemmNT, c->stream)) ? JG_OK : JG_E_HIP;
+        return run_gemm(plan, g, jg::kGemmNT, JG_KERNEL_GEMM, tail, plan->tail_bytes) ? JG_OK : JG_E_HIP;
     }
     for (int r = 0; r < ways; ++r)
         g.p[r] = {x_sh[r], w_keep[r], kept_buf(r), nullptr, nullptr, ldk, ldk, ldn, 0};
-    {
-        ScopedTimer t(c, JG_KERNEL_GEMM);
-        if (!HIP_OK(jg::launch_gemm_group(g, jg::kGemmNT, c->stream))) return JG_E_HIP;
-    }
+    if (!run_gemm(plan, g, jg::kGemmNT, JG_KERNEL_GEMM, tail, plan->tail_bytes)) return JG_E_HIP;
     jg::CombineGroup cb;
     std::memset(&cb, 0, sizeof(cb));
     cb.nblocks = ways;
@@ -688,9 +723,9 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
     jg::GemmGroup g;
     std::memset(&g, 0, sizeof(g));
 
+    char* tail = plan->bw_tail_bytes ? ws + plan->bw_off_tail : nullptr;
     auto launch = [&](int layout, int kernel_class) -> bool {
-        ScopedTimer t(c, kernel_class);
-        return HIP_OK(jg::launch_gemm_group(g, layout, c->stream));
+        return run_gemm(plan, g, layout, kernel_class, tail, plan->bw_tail_bytes);
     };
 
     if (ways == 1) {

@@ -19,7 +19,7 @@ class JigsawLinear:
 
     def __init__(self, M: int, K: int, N: int, ways: int, bias: bool = False,
                  combine: int = jg.JG_COMBINE_FUSED, weights: int = jg.JG_WEIGHTS_COPY,
-                 device: int = 0, ctx=None, op: int = jg.JG_OP_XWT):
+                 device: int = 0, ctx=None, op: int = jg.JG_OP_XWT, tail: int = jg.JG_TAIL_SPLIT):
         if not torch.cuda.is_available():
             raise RuntimeError("JigsawLinear needs a GPU: the HIP library has no CPU fallback")
         self.M, self.K, self.N, self.ways, self.bias, self.op = M, K, N, ways, bias, op
@@ -29,7 +29,7 @@ class JigsawLinear:
         self._own_ctx = ctx is None
         self.stream = torch.cuda.current_stream(self.dev)
         self.ctx = ctx if ctx is not None else jg.jg_init(device, self.stream.cuda_stream)
-        self.plan = jg.jg_plan_create(self.ctx, M, K, N, ways, bias, combine, weights, op)
+        self.plan = jg.jg_plan_create(self.ctx, M, K, N, ways, bias, combine, weights, op, tail=tail)
         q = lambda what, r=0: jg.jg_plan_query(self.plan, what, r)
         f32 = dict(dtype=torch.float32, device=self.dev)
         self.x = [torch.empty((q(jg.JG_Q_X_ROWS, r), q(jg.JG_Q_X_COLS, r)), **f32) for r in range(ways)]

@@ -92,15 +92,18 @@ def test_accounting(ways, M, K, N):
             assert q(jg.JG_Q_B_LEN, r) == q(jg.JG_Q_Y_COLS, r)
             # Y is partitioned like X (Sec. 4.1: the scheme is maintained after the product)
             assert q(jg.JG_Q_Y_ROWS, r) == q(jg.JG_Q_X_ROWS, r)
+        # the scratch of the split tail comes on top of what the method itself needs
+        tail = q(jg.JG_Q_TAIL_SCRATCH_BYTES)
+        assert 0 <= tail <= 512 * 2 * 128 * 128 * 4 and tail % (128 * 128 * 4) == 0
         if ways == 1:
-            assert q(jg.JG_Q_WORKSPACE_BYTES) == 0 and q(jg.JG_Q_EXCHANGE_BYTES_RANK) == 0
+            assert q(jg.JG_Q_WORKSPACE_BYTES) == tail and q(jg.JG_Q_EXCHANGE_BYTES_RANK) == 0
             assert q(jg.JG_Q_HBM_BYTES_ALGO) == 4 * (M * K + N * K + M * N)
             assert q(jg.JG_Q_GEMM_LAUNCHES) == 1
         else:
             assert q(jg.JG_Q_HBM_BYTES_ALGO) == 4 * (M * K + N * K + M * N) + 8 * M * N
             assert q(jg.JG_Q_GEMM_LAUNCHES) == 2
             # one partial per output element, plus (4-way, copy mode) one weight block per rank
-            ws = q(jg.JG_Q_WORKSPACE_BYTES)
+            ws = q(jg.JG_Q_WORKSPACE_BYTES) - tail
             need = 4 * M * N + (4 * N * K if ways == 4 else 0)
             assert need <= ws <= need + 2 * ways * 256
             if ways == 2:
@@ -110,7 +113,7 @@ def test_accounting(ways, M, K, N):
         # backward: twice the forward work (Sec. 6.3); one partial per dX element, and per dW element in 4-way
         assert q(jg.JG_Q_BACKWARD_FLOPS_TOTAL) == 4 * M * K * N
         assert q(jg.JG_Q_BACKWARD_GEMM_LAUNCHES) == {1: 2, 2: 3, 4: 4}[ways]
-        bw = q(jg.JG_Q_BACKWARD_WORKSPACE_BYTES)
+        bw = q(jg.JG_Q_BACKWARD_WORKSPACE_BYTES) - q(jg.JG_Q_BACKWARD_TAIL_SCRATCH_BYTES)
         need = 0 if ways == 1 else 4 * M * K + (4 * N * K if ways == 4 else 0)
         assert need <= bw <= need + 2 * ways * 256
         with pytest.raises(jg.JigsawError) as e:
@@ -142,7 +145,7 @@ def test_accounting_of_the_transposed_layer(ways, M, K, N):
             assert (q(jg.JG_Q_W_ROWS, r), q(jg.JG_Q_W_COLS, r)) == (K // rows, N // cols)
             assert (q(jg.JG_Q_Y_ROWS, r), q(jg.JG_Q_Y_COLS, r)) == (M // rows, N // cols)
             assert q(jg.JG_Q_B_LEN, r) == N // cols
-        ws = q(jg.JG_Q_WORKSPACE_BYTES)
+        ws = q(jg.JG_Q_WORKSPACE_BYTES) - q(jg.JG_Q_TAIL_SCRATCH_BYTES)
         if ways == 1:
             assert ws == 0 and q(jg.JG_Q_EXCHANGE_BYTES_RANK) == 0 and q(jg.JG_Q_GEMM_LAUNCHES) == 1
             assert q(jg.JG_Q_HBM_BYTES_ALGO) == 4 * (M * K + N * K + M * N)
@@ -155,7 +158,8 @@ def test_accounting_of_the_transposed_layer(ways, M, K, N):
             assert q(jg.JG_Q_EXCHANGE_BYTES_RANK, 3) == 4 * (M * N // 4 + K * M // 4) and q(jg.JG_Q_GEMM_LAUNCHES) == 2
             assert q(jg.JG_Q_HBM_BYTES_ALGO) == 4 * (M * K + N * K + M * N) + 8 * M * N
             assert 4 * (M * N + K * M) <= ws <= 4 * (M * N + K * M) + 2 * ways * 256
-        for what in (jg.JG_Q_BACKWARD_WORKSPACE_BYTES, jg.JG_Q_BACKWARD_FLOPS_TOTAL, jg.JG_Q_BACKWARD_GEMM_LAUNCHES):
+        for what in (jg.JG_Q_BACKWARD_WORKSPACE_BYTES, jg.JG_Q_BACKWARD_FLOPS_TOTAL, jg.JG_Q_BACKWARD_GEMM_LAUNCHES,
+                     jg.JG_Q_BACKWARD_TAIL_SCRATCH_BYTES):
             with pytest.raises(jg.JigsawError) as e:     # forward only
                 q(what)
             assert e.value.status == jg.JG_E_DTYPE
@@ -172,12 +176,47 @@ def test_backward_refuses_a_transposed_plan():
     jg.jg_plan_destroy(p)
 
 
+def test_tail_split_accounting():
+    q = lambda p, what: jg.jg_plan_query(p, what)
+    tile = 128 * 128 * 4
+    # token-mixing size of the transposed layer: 34 x 68 = 2312 tiles = 4 rounds of 512 slots + 264
+    # tiles of 507 slabs: the tail goes to 512 runs (two scratch tiles each)
+    p = jg.jg_plan_create(None, 4320, 16200, 8640, 1, op=jg.JG_OP_XTW)
+    assert q(p, jg.JG_Q_TAIL_SCRATCH_BYTES) == 512 * 2 * tile
+    assert q(p, jg.JG_Q_WORKSPACE_BYTES) == 512 * 2 * tile
+    jg.jg_plan_destroy(p)
+    p = jg.jg_plan_create(None, 4320, 16200, 8640, 1, op=jg.JG_OP_XTW, tail=jg.JG_TAIL_WHOLE)
+    assert q(p, jg.JG_Q_TAIL_SCRATCH_BYTES) == 0 and q(p, jg.JG_Q_WORKSPACE_BYTES) == 0
+    jg.jg_plan_destroy(p)
+    # config 3: 12 whole rounds and a quarter: the estimated saving is below the threshold
+    p = jg.jg_plan_create(None, 25000, 4000, 4000, 4)
+    assert q(p, jg.JG_Q_TAIL_SCRATCH_BYTES) == 0 and q(p, jg.JG_Q_BACKWARD_TAIL_SCRATCH_BYTES) == 0
+    jg.jg_plan_destroy(p)
+    # a whole number of rounds: nothing to split (64 x 64 tiles = 8 rounds)
+    p = jg.jg_plan_create(None, 8192, 4096, 8192, 1)
+    assert q(p, jg.JG_Q_TAIL_SCRATCH_BYTES) == 0
+    jg.jg_plan_destroy(p)
+    # a single short tile: runs would be shorter than the minimum, stays whole
+    p = jg.jg_plan_create(None, 100, 100, 100, 1)
+    assert q(p, jg.JG_Q_TAIL_SCRATCH_BYTES) == 0
+    jg.jg_plan_destroy(p)
+    # few long tiles: 3 x 3 tiles of 65 slabs -> 585 / 32 = 18 runs
+    p = jg.jg_plan_create(None, 300, 2080, 260, 1)
+    assert q(p, jg.JG_Q_TAIL_SCRATCH_BYTES) == 18 * 2 * tile
+    # ... and in the backward pass: dX 3 x 17 tiles of 9 slabs (whole), dW 3 x 17 tiles of 10 slabs (whole)
+    assert q(p, jg.JG_Q_BACKWARD_TAIL_SCRATCH_BYTES) == 0
+    jg.jg_plan_destroy(p)
+    with pytest.raises(jg.JigsawError) as e:
+        jg.jg_plan_create(None, 8, 8, 8, 2, tail=2)
+    assert e.value.status == jg.JG_E_DTYPE
+
+
 def test_workspace_grows_with_options():
     M, K, N = 64, 32, 48
     base = jg.jg_plan_create(None, M, K, N, 4)
     sep = jg.jg_plan_create(None, M, K, N, 4, combine=jg.JG_COMBINE_SEPARATE)
     direct = jg.jg_plan_create(None, M, K, N, 4, weights=jg.JG_WEIGHTS_DIRECT)
-    ws = lambda p: jg.jg_plan_query(p, jg.JG_Q_WORKSPACE_BYTES)
+    ws = lambda p: jg.jg_plan_query(p, jg.JG_Q_WORKSPACE_BYTES) - jg.jg_plan_query(p, jg.JG_Q_TAIL_SCRATCH_BYTES)
     assert ws(sep) == ws(base) + 4 * M * N
     assert ws(direct) == ws(base) - 4 * N * K
     for p in (base, sep, direct):
