@@ -36,6 +36,8 @@ def parse():
                          "xtw: the transposed layer Y = X^T W at the token-mixing size (ignores --config)")
     ap.add_argument("--combine", choices=["fused", "separate"], default="fused")
     ap.add_argument("--weights", choices=["copy", "direct"], default="copy")
+    ap.add_argument("--tail", choices=["split", "whole"], default="split",
+                    help="last partial round of a GEMM launch: cut into runs when that pays (default), or whole tiles")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="target CPU time of the oracle baseline sample (0 disables it)")
     ap.add_argument("--extras", action="store_true",
@@ -44,6 +46,11 @@ def parse():
     ap.add_argument("--only-headline", action="store_true",
                     help="skip the streaming-kernel measurements")
     return ap.parse_args()
+
+
+def tail_of(args):
+    from paper_2507_05753_amd import binding as jg
+    return jg.JG_TAIL_SPLIT if args.tail == "split" else jg.JG_TAIL_WHOLE
 
 
 def make_inputs(cfg, dev):
@@ -65,7 +72,7 @@ def time_forward(L, jg, steps, warmup):
     for _ in range(warmup):
         L.forward()
     torch.cuda.synchronize()
-    for k in (jg.JG_KERNEL_GEMM, jg.JG_KERNEL_WEIGHT_COPY, jg.JG_KERNEL_COMBINE):
+    for k in (jg.JG_KERNEL_GEMM, jg.JG_KERNEL_WEIGHT_COPY, jg.JG_KERNEL_COMBINE, jg.JG_KERNEL_JOIN):
         jg.jg_profile_read(L.ctx, k)
     jg.jg_profile(L.ctx, True)
     torch.cuda.synchronize()
@@ -78,7 +85,8 @@ def time_forward(L, jg, steps, warmup):
     gemm_ms, gemm_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_GEMM)
     wc_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_WEIGHT_COPY)
     cb_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_COMBINE)
-    return (t1 - t0) / steps, gemm_ms, gemm_n, wc_ms / steps, cb_ms / steps
+    join_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_JOIN)   # tail join of split launches, counted with the hand-off copy
+    return (t1 - t0) / steps, gemm_ms, gemm_n, (wc_ms + join_ms) / steps, cb_ms / steps
 
 
 def measure(cfg, ways, args, X, W, streaming=False):
@@ -89,7 +97,7 @@ def measure(cfg, ways, args, X, W, streaming=False):
     combine = jg.JG_COMBINE_FUSED if args.combine == "fused" else jg.JG_COMBINE_SEPARATE
     weights = jg.JG_WEIGHTS_COPY if args.weights == "copy" else jg.JG_WEIGHTS_DIRECT
     out = {}
-    with JigsawLinear(M, K, N, ways, combine=combine, weights=weights) as L:
+    with JigsawLinear(M, K, N, ways, combine=combine, weights=weights, tail=tail_of(args)) as L:
         L.shard(X, W)
         sec, gemm_ms, gemm_n, wcopy_ms, comb_ms = time_forward(L, jg, args.steps, args.warmup)
         other_ms = wcopy_ms + comb_ms
@@ -154,7 +162,7 @@ def measure_backward(cfg, ways, args, X, W):
     from paper_2507_05753_amd.layer import JigsawLinear
     M, K, N = cfg["M"], cfg["K"], cfg["N"]
     dY = inputs.matrix_torch(cfg["seed"] + 3000, M, N, "R", 0, device=X.device)
-    with JigsawLinear(M, K, N, ways) as L:
+    with JigsawLinear(M, K, N, ways, tail=tail_of(args)) as L:
         L.shard(X, W)
         L.shard_dy(dY)
         del dY
@@ -199,7 +207,7 @@ def measure_xtw(cfg, ways, args):
     W = inputs.matrix_torch(seed + inputs.W_STREAM, K, N, "R", inputs.W_SCALE_EXP, device=dev)
     combine = jg.JG_COMBINE_FUSED if args.combine == "fused" else jg.JG_COMBINE_SEPARATE
     weights = jg.JG_WEIGHTS_COPY if args.weights == "copy" else jg.JG_WEIGHTS_DIRECT
-    with JigsawLinear(M, K, N, ways, combine=combine, weights=weights, op=jg.JG_OP_XTW) as L:
+    with JigsawLinear(M, K, N, ways, combine=combine, weights=weights, op=jg.JG_OP_XTW, tail=tail_of(args)) as L:
         L.shard(X, W)
         del X, W
         sec, gemm_ms, gemm_n, copy_ms, comb_ms = time_forward(L, jg, args.steps, args.warmup)
@@ -323,7 +331,7 @@ def main():
             "config": {"workload": f"token mixing of the 1B model: Y = X^T W, X {K} x {M} [tokens, channels], "
                                    f"W {K} x {N}, {args.ways}-way Jigsaw, fp32",
                        "n_items": M * K, "ways": args.ways, "M": M, "K": K, "N": N, "seed": xc["seed"],
-                       "x_values": "R", "op": "xtw", "combine": args.combine, "weights": args.weights},
+                       "x_values": "R", "op": "xtw", "combine": args.combine, "weights": args.weights, "tail": args.tail},
             "tflops": r["tflops"], "hbm_algo_gbps": r["hbm_algo_gbps"],
             "roofline": {"bound": "mfma", "kernel": "jg::gemm_f32_stream<true, true, false>", "achieved": r["gemm_tflops"],
                          "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -395,7 +403,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": workload, "n_items": M * K, "ways": args.ways, "M": M, "K": K, "N": N,
                    "seed": cfg["seed"], "x_values": cfg["x_mode"], "combine": args.combine,
-                   "weights": args.weights},
+                   "weights": args.weights, "tail": args.tail},
         "tflops": head["tflops"],
         "hbm_algo_gbps": head["hbm_algo_gbps"],
         "hbm_algo_frac_of_8TBps": head["hbm_algo_frac"],
