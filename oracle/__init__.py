@@ -58,9 +58,12 @@ def _load():
                                                ctypes.c_int]
         lib.oracle_linear_xtw.argtypes = [f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int, ctypes.c_int]
         lib.oracle_jigsaw_xtw.argtypes = [ctypes.c_int, f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int]
+        lib.oracle_gelu.argtypes = [f64p, i64, f64p]
+        lib.oracle_mlp.argtypes = [f32p, f32p, f32p, f32p, f32p, i64, i64, i64, ctypes.c_int,
+                                   f64p, f64p, f64p, f64p, f64p, ctypes.c_int]
         for fn in (lib.oracle_linear, lib.oracle_linear_rows, lib.oracle_magnitude,
                    lib.oracle_entries, lib.oracle_jigsaw, lib.oracle_backward, lib.oracle_jigsaw_backward,
-                   lib.oracle_linear_xtw, lib.oracle_jigsaw_xtw):
+                   lib.oracle_linear_xtw, lib.oracle_jigsaw_xtw, lib.oracle_gelu, lib.oracle_mlp):
             fn.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -228,6 +231,46 @@ def jigsaw_xtw(ways: int, X, W, b=None, nthreads: int | None = None) -> np.ndarr
     Y, yp = _f64_out((C, D))
     _check(_load().oracle_jigsaw_xtw(ways, xp, wp, bp, T, C, D, yp, nthreads or host_threads()), "jigsaw_xtw")
     return Y
+
+
+def gelu(a) -> np.ndarray:
+    """x * Phi(x), element by element, in double."""
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    out = np.empty_like(a)
+    _check(_load().oracle_gelu(a.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), a.size,
+                               out.ctypes.data_as(ctypes.POINTER(ctypes.c_double))), "gelu")
+    return out
+
+
+def mlp(X, W1, b1, W2, b2, residual: bool = True, nthreads: int | None = None):
+    """One mixing MLP: H = gelu(X W1^T + b1), Y = (X +) H W2^T + b2, in double.
+
+    Returns a dict with H, Y and the magnitudes S1 (pre-activation), SY (second layer's own sums) and
+    PY = S1 |W2|^T (how an S1-relative error in H carries into Y)."""
+    X, xp = _f32(X)
+    W1, w1p = _f32(W1)
+    b1, b1p = _opt_f32(b1)
+    W2, w2p = _f32(W2)
+    b2, b2p = _opt_f32(b2)
+    M, C = X.shape
+    Hd = W1.shape[0]
+    assert W1.shape == (Hd, C) and W2.shape == (C, Hd)
+    H, hp = _f64_out((M, Hd))
+    Y, yp = _f64_out((M, C))
+    S1, s1p = _f64_out((M, Hd))
+    SY, syp = _f64_out((M, C))
+    PY, pyp = _f64_out((M, C))
+    _check(_load().oracle_mlp(xp, w1p, b1p, w2p, b2p, M, C, Hd, int(residual), hp, yp, s1p, syp, pyp,
+                              nthreads or host_threads()), "mlp")
+    return dict(H=H, Y=Y, S1=S1, SY=SY, PY=PY)
+
+
+def jigsaw_mlp(ways: int, X, W1, b1, W2, b2, residual: bool = True):
+    """The same MLP with both layers obtained block by block (jigsaw), H handed on in FP32 as the
+    method stores it, the residual added to the gathered result."""
+    H = gelu(jigsaw(ways, X, W1, b1)).astype(np.float32)
+    Y = jigsaw(ways, H, W2, b2)
+    return Y + np.asarray(X, dtype=np.float64) if residual else Y
 
 
 # ----------------------------------------------------------------------------

@@ -45,6 +45,17 @@
  *                       never duplicated, two block products per rank, one partial
  *                       product handed to one peer) and is stated above the function.
  *
+ *  oracle_gelu        : the activation between the two linear layers of a mixing MLP
+ *                       (Sec. 3; Sec. 5 "Activation functions": point-wise, no
+ *                       synchronisation).  The paper names GELU without a formula; this is
+ *                       its defining form x * Phi(x) = x/2 * (1 + erf(x / sqrt 2)), not the
+ *                       tanh approximation.
+ *  oracle_mlp         : one mixing MLP with its skip connection (Sec. 3: two linear layers,
+ *                       GELU between them, a residual connection around the MLP):
+ *                         H = gelu(X W1^T + b1),   Y = X + H W2^T + b2,
+ *                       row by row with H kept in double; also returns the magnitudes the
+ *                       tolerances of the two outputs are relative to.
+ *
  * Pins (see tests/test_oracle_pins.py): closed forms for identity /
  * permutation / all-ones / single-nonzero operands, exact integer brute force
  * on tiny shapes, a library matmul in double, the block identities of
@@ -55,8 +66,15 @@
  * brute force, exact equality of the block-wise result with the definition on
  * lattice inputs.
  *
+ * Pins of the MLP (tests/test_oracle_mlp_pins.py): tabulated values of the normal
+ * distribution function, the identity gelu(x) - gelu(-x) = x, limits, a library erf;
+ * the MLP against the pinned forward oracle applied twice, closed forms (zero first
+ * layer, identity weights), and brute force in exact rationals where gelu is not
+ * involved.
+ *
  * Layout: every matrix is dense row-major; X is M x K, W is N x K, Y is M x N
- * (transposed layer: X is T x C, W is T x D, Y is C x D).
+ * (transposed layer: X is T x C, W is T x D, Y is C x D; MLP: X and Y are M x C,
+ * W1 is Hd x C, W2 is C x Hd).
  */
 #include <math.h>
 #include <pthread.h>
@@ -614,4 +632,71 @@ done:
     for (int i = 0; i < 2; ++i)
         for (int j = 0; j < 2; ++j) { free(Xb[i][j]); free(Wb[i][j]); }
     return rc;
+}
+
+/* ------------------------------------------------------------------ */
+/* mixing MLP: H = gelu(X W1^T + b1), Y = X + H W2^T + b2               */
+/* ------------------------------------------------------------------ */
+static double gelu1(double x) { return 0.5 * x * (1.0 + erf(x * 0.70710678118654752440)); }
+
+int oracle_gelu(const double* in, int64_t n, double* out)
+{
+    if (!in || !out || n < 0) return ORACLE_E_ARG;
+    for (int64_t i = 0; i < n; ++i) out[i] = gelu1(in[i]);
+    return ORACLE_OK;
+}
+
+typedef struct {
+    const float *X, *W1, *b1, *W2, *b2;
+    int64_t C, Hd;
+    int residual;
+    double *H, *Y, *S1, *SY, *PY;
+} mlp_env;
+
+/* One row of X.  S1 = |b1| + |x| |W1|^T (scale of the pre-activation's rounding), SY = |b2| + |x| + |h| |W2|^T
+ * (scale of the second layer's own rounding), PY = S1 |W2|^T (how a unit of S1-relative error in H shows in Y;
+ * |gelu'| <= 1.13 is left to the caller). */
+static void mlp_row(int64_t i, void* p)
+{
+    const mlp_env* e = (const mlp_env*)p;
+    const float* x = e->X + i * e->C;
+    double* h = e->H + i * e->Hd;
+    double* s1 = e->S1 + i * e->Hd;
+    for (int64_t q = 0; q < e->Hd; ++q) {
+        const float* w = e->W1 + q * e->C;
+        double acc = e->b1 ? (double)e->b1[q] : 0.0, mag = fabs(acc);
+        for (int64_t k = 0; k < e->C; ++k) {
+            const double t = (double)x[k] * (double)w[k];
+            acc += t;
+            mag += fabs(t);
+        }
+        h[q] = gelu1(acc);
+        s1[q] = mag;
+    }
+    for (int64_t j = 0; j < e->C; ++j) {
+        const float* w = e->W2 + j * e->Hd;
+        double acc = e->b2 ? (double)e->b2[j] : 0.0, mag = fabs(acc), prop = 0.0;
+        for (int64_t q = 0; q < e->Hd; ++q) {
+            const double t = h[q] * (double)w[q];
+            acc += t;
+            mag += fabs(t);
+            prop += s1[q] * fabs((double)w[q]);
+        }
+        if (e->residual) {
+            acc += (double)x[j];
+            mag += fabs((double)x[j]);
+        }
+        e->Y[i * e->C + j] = acc;
+        e->SY[i * e->C + j] = mag;
+        e->PY[i * e->C + j] = prop;
+    }
+}
+
+int oracle_mlp(const float* X, const float* W1, const float* b1, const float* W2, const float* b2, int64_t M,
+               int64_t C, int64_t Hd, int residual, double* H, double* Y, double* S1, double* SY, double* PY,
+               int nthreads)
+{
+    if (!X || !W1 || !W2 || !H || !Y || !S1 || !SY || !PY || M < 0 || C < 0 || Hd < 0) return ORACLE_E_ARG;
+    mlp_env e = {X, W1, b1, W2, b2, C, Hd, residual, H, Y, S1, SY, PY};
+    return for_rows(0, M, nthreads, mlp_row, &e);
 }
