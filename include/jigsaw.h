@@ -80,6 +80,7 @@ enum { JG_F32 = 0 };                                     /* the paper's uniform 
 enum { JG_COMBINE_FUSED = 0, JG_COMBINE_SEPARATE = 1 };  /* where the "+" of Eq. (2)/(4) runs */
 enum { JG_WEIGHTS_COPY = 0, JG_WEIGHTS_DIRECT = 1 };     /* 4-way weight-block hand-off */
 enum { JG_TAIL_SPLIT = 0, JG_TAIL_WHOLE = 1 };           /* last partial round of a GEMM launch */
+enum { JG_ACT_NONE = 0, JG_ACT_GELU = 1 };               /* epilogue activation of jg_linear_forward_ex */
 enum { JG_T_X = 0, JG_T_W = 1, JG_T_B = 2, JG_T_Y = 3 }; /* tensor selector of jg_shard / jg_gather_as */
 
 typedef struct jg_linear_desc {
@@ -207,6 +208,36 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
 int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
                       const float* const* b_sh, float* const* y_sh, void* workspace,
                       size_t workspace_bytes);
+
+/* run (with epilogue).  jg_linear_forward with what a mixing MLP puts around its linear layers
+ * (Sec. 3: a GELU between the two layers, a residual connection around them; Sec. 5 "Activation
+ * functions": GELU is point-wise and needs no exchange), fused into the step that completes an
+ * output block:
+ *     Y_r = act(X W^T + b)_r + R_r
+ * activation: JG_ACT_NONE or JG_ACT_GELU, the defining form x * Phi(x) = x/2 (1 + erf(x / sqrt 2))
+ * evaluated in FP32.  r_sh: host array of `ways` device pointers to residual shards shaped and
+ * partitioned like Y_r (read only; may alias nothing that is written), or NULL for no residual.
+ * Everything else as in jg_linear_forward, which is this call with r_sh = NULL and JG_ACT_NONE.
+ * Errors: JG_E_NULL, JG_E_DTYPE (activation), JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
+int jg_linear_forward_ex(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                         const float* const* b_sh, const float* const* r_sh, int activation, float* const* y_sh,
+                         void* workspace, size_t workspace_bytes);
+
+/* run (MLP).  One mixing MLP with its skip connection (Sec. 3) on Jigsaw shards:
+ *     H = gelu(X W1^T + b1),    Y = X + H W2^T + b2,
+ * X and Y are M x C, W1 is Hd x C, W2 is C x Hd.  `first` is a JG_OP_XWT plan of sizes (M, K = C,
+ * N = Hd), `second` one of (M, K = Hd, N = C), same `ways`, same context.  Because a layer leaves
+ * its output partitioned like its input (Sec. 4.1), H_r is consumed where it was produced: no
+ * re-sharding between the layers.  h_sh: `ways` device buffers shaped like the first plan's Y_r
+ * (H is kept: a backward pass would need it).  The workspace is used by both layers in turn and
+ * must satisfy both plans' JG_Q_WORKSPACE_BYTES.  x_sh is read by both layers and must not
+ * overlap h_sh or y_sh.
+ * Errors: JG_E_NULL, JG_E_DTYPE (op), JG_E_WAYS, JG_E_SHAPE (plans do not chain), and those of
+ * jg_linear_forward_ex. */
+int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh,
+                   const float* const* w1_sh, const float* const* b1_sh, const float* const* w2_sh,
+                   const float* const* b2_sh, float* const* h_sh, float* const* y_sh, void* workspace,
+                   size_t workspace_bytes);
 
 /* run (backward).  Gradients of the same layer for an incoming gradient dY (partitioned like Y):
  *     dX = dY W      (M x K, partitioned like X)       dW = dY^T X    (N x K, partitioned like W)

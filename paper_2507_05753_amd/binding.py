@@ -34,6 +34,7 @@ JG_F32 = 0
 JG_COMBINE_FUSED, JG_COMBINE_SEPARATE = 0, 1
 JG_WEIGHTS_COPY, JG_WEIGHTS_DIRECT = 0, 1
 JG_TAIL_SPLIT, JG_TAIL_WHOLE = 0, 1
+JG_ACT_NONE, JG_ACT_GELU = 0, 1
 JG_T_X, JG_T_W, JG_T_B, JG_T_Y = 0, 1, 2, 3
 (JG_Q_WORKSPACE_BYTES, JG_Q_FLOPS_TOTAL, JG_Q_FLOPS_RANK, JG_Q_HBM_BYTES_ALGO,
  JG_Q_EXCHANGE_BYTES_RANK, JG_Q_X_ROWS, JG_Q_X_COLS, JG_Q_W_ROWS, JG_Q_W_COLS,
@@ -44,7 +45,7 @@ JG_T_X, JG_T_W, JG_T_B, JG_T_Y = 0, 1, 2, 3
  JG_KERNEL_GATHER, JG_KERNEL_GEMM_DX, JG_KERNEL_GEMM_DW, JG_KERNEL_JOIN, JG_KERNEL_COUNT) = range(9)
 
 EXPORTS = ("jg_init", "jg_free", "jg_plan_create", "jg_plan_destroy", "jg_plan_query", "jg_shard",
-           "jg_linear_forward", "jg_linear_backward", "jg_gather", "jg_gather_as", "jg_profile", "jg_profile_read", "jg_strerror",
+           "jg_linear_forward", "jg_linear_forward_ex", "jg_mlp_forward", "jg_linear_backward", "jg_gather", "jg_gather_as", "jg_profile", "jg_profile_read", "jg_strerror",
            "jg_last_hip_error")
 
 
@@ -79,13 +80,16 @@ _lib.jg_plan_destroy.restype = None
 _lib.jg_plan_query.argtypes = [_vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]
 _lib.jg_shard.argtypes = [_vp, ctypes.c_int, _vp, ctypes.c_int64, _vpp]
 _lib.jg_linear_forward.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
+_lib.jg_linear_forward_ex.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, ctypes.c_int, _vpp, _vp, ctypes.c_size_t]
+_lib.jg_mlp_forward.argtypes = [_vp, _vp, _vpp, _vpp, _vpp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
 _lib.jg_linear_backward.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
 _lib.jg_gather.argtypes = [_vp, _vpp, _vp, ctypes.c_int64]
 _lib.jg_gather_as.argtypes = [_vp, ctypes.c_int, _vpp, _vp, ctypes.c_int64]
 _lib.jg_profile.argtypes = [_vp, ctypes.c_int]
 _lib.jg_profile_read.argtypes = [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                  ctypes.POINTER(ctypes.c_int64)]
-for _n in ("jg_init", "jg_plan_create", "jg_plan_query", "jg_shard", "jg_linear_forward", "jg_linear_backward",
+for _n in ("jg_init", "jg_plan_create", "jg_plan_query", "jg_shard", "jg_linear_forward", "jg_linear_forward_ex",
+           "jg_mlp_forward", "jg_linear_backward",
            "jg_gather", "jg_gather_as", "jg_profile", "jg_profile_read"):
     getattr(_lib, _n).restype = ctypes.c_int
 
@@ -147,6 +151,20 @@ def jg_linear_forward(plan, x_ptrs, w_ptrs, b_ptrs, y_ptrs, workspace_ptr, works
     _raise(_lib.jg_linear_forward(plan, _ptr_array(x_ptrs), _ptr_array(w_ptrs), _ptr_array(b_ptrs),
                                   _ptr_array(y_ptrs), workspace_ptr or None, workspace_bytes),
            "jg_linear_forward")
+
+
+def jg_linear_forward_ex(plan, x_ptrs, w_ptrs, b_ptrs, r_ptrs, activation: int, y_ptrs, workspace_ptr,
+                         workspace_bytes: int) -> None:
+    _raise(_lib.jg_linear_forward_ex(plan, _ptr_array(x_ptrs), _ptr_array(w_ptrs), _ptr_array(b_ptrs),
+                                     _ptr_array(r_ptrs), activation, _ptr_array(y_ptrs), workspace_ptr or None,
+                                     workspace_bytes), "jg_linear_forward_ex")
+
+
+def jg_mlp_forward(first, second, x_ptrs, w1_ptrs, b1_ptrs, w2_ptrs, b2_ptrs, h_ptrs, y_ptrs, workspace_ptr,
+                   workspace_bytes: int) -> None:
+    _raise(_lib.jg_mlp_forward(first, second, _ptr_array(x_ptrs), _ptr_array(w1_ptrs), _ptr_array(b1_ptrs),
+                               _ptr_array(w2_ptrs), _ptr_array(b2_ptrs), _ptr_array(h_ptrs), _ptr_array(y_ptrs),
+                               workspace_ptr or None, workspace_bytes), "jg_mlp_forward")
 
 
 def jg_linear_backward(plan, x_ptrs, w_ptrs, dy_ptrs, dx_ptrs, dw_ptrs, workspace_ptr, workspace_bytes: int) -> None:

@@ -59,6 +59,8 @@
 
 #include <type_traits>
 
+#include "epilogue.hpp"
+
 namespace jg {
 
 constexpr int kMaxGroup = 4;
@@ -79,6 +81,8 @@ struct GemmProblem {
     const float* addend;  // M x N (ldadd) added in the epilogue, or nullptr
     const float* bias;    // length N added in the epilogue, or nullptr
     int lda, ldb, ldc, ldadd;
+    const float* residual;   // M x N (ldres) added after the activation, or nullptr
+    int ldres;
 };
 
 struct GemmGroup {
@@ -92,6 +96,7 @@ struct GemmGroup {
     int run_wgs;          // workgroups that share the remaining tiles' K loops
     int run_len, run_extra;   // run w covers run_len slabs, one more for w < run_extra
     float* run_tiles;     // scratch: two BM x BN tiles per run workgroup
+    int act;              // kActNone / kActGelu, applied to (sum + bias) of every finished element
 };
 
 // First slab-iteration (tile-major, then slab) of run w; the runs partition [0, tail tiles * slabs).
@@ -266,34 +271,23 @@ __device__ __forceinline__ void init_acc(const GemmProblem& P, int M, int N, int
     }
 }
 
-// C = acc (+ bias) for the tile at (m0, n0).
+// C = act(acc + bias) + residual for the tile at (m0, n0).
 __device__ __forceinline__ void store_tile(const GemmProblem& P, int M, int N, int m0, int n0,
-                                           const LaneMap& L, const floatx16 (&acc)[2][2])
+                                           const LaneMap& L, const floatx16 (&acc)[2][2], int act)
 {
     const float* __restrict__ bias = P.bias;
+    const float* __restrict__ residual = P.residual;
     float* __restrict__ C = P.C;
     const int ldc = P.ldc;
     const int row_base = m0 + L.wm * 64 + 4 * L.lk;     // + i * 32 + 8 (v / 4) + v % 4
     const int col_base = n0 + L.wn * 64 + L.lr;         // + j * 32
-    if (m0 + BM <= M && n0 + BN <= N && ldc <= kMaxDirectLd) {
+    if (m0 + BM <= M && n0 + BN <= N && ldc <= kMaxDirectLd && (!residual || P.ldres <= kMaxDirectLd)) {
         // interior tile: no bounds checks, and no vector ALU work for addresses (lane position in
         // one vector offset per column block, the row of each store in a scalar offset)
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             C + (int64_t)m0 * ldc + n0, 0, ((BM - 1) * ldc + BN) * 4, kBufferRsrcFlags);
         const int lane_off = ((L.wm * 64 + 4 * L.lk) * ldc + L.wn * 64 + L.lr) * 4;
-        if (bias) {
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const float bj = bias[col_base + j * 32];
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, acc[i][j][v] + bj), rsrc,
-                                                              lane_off + j * 128,
-                                                              (i * 32 + 8 * (v >> 2) + (v & 3)) * ldc * 4, 0);
-            }
-        } else {
+        if (!bias && !act && !residual) {
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -305,6 +299,34 @@ __device__ __forceinline__ void store_tile(const GemmProblem& P, int M, int N, i
                                                               lane_off + j * 128,
                                                               (i * 32 + 8 * (v >> 2) + (v & 3)) * ldc * 4, 0);
                     }
+        } else {
+            const int ldres = P.ldres;
+            const __amdgpu_buffer_rsrc_t res_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<float*>(residual ? residual + (int64_t)m0 * ldres + n0 : C), 0,
+                residual ? ((BM - 1) * ldres + BN) * 4 : 0, kBufferRsrcFlags);
+            const int res_off = ((L.wm * 64 + 4 * L.lk) * ldres + L.wn * 64 + L.lr) * 4;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float bj = bias ? bias[col_base + j * 32] : 0.f;
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    float res[16];
+                    if (residual) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v)
+                            res[v] = __builtin_bit_cast(
+                                float, __builtin_amdgcn_raw_buffer_load_b32(
+                                           res_rsrc, res_off + j * 128, (i * 32 + 8 * (v >> 2) + (v & 3)) * ldres * 4, 0));
+                    }
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        float y = activate(acc[i][j][v] + bj, act);
+                        if (residual) y += res[v];
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rsrc, lane_off + j * 128,
+                                                              (i * 32 + 8 * (v >> 2) + (v & 3)) * ldc * 4, 0);
+                    }
+                }
+            }
         }
     } else {                              // edge tile: every element checked against M and N
 #pragma unroll
@@ -317,7 +339,11 @@ __device__ __forceinline__ void store_tile(const GemmProblem& P, int M, int N, i
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = row_base + i * 32 + 8 * (v >> 2) + (v & 3);
-                    if (row < M) C[(int64_t)row * ldc + col] = acc[i][j][v] + bj;
+                    if (row < M) {
+                        float y = activate(acc[i][j][v] + bj, act);
+                        if (residual) y += residual[(int64_t)row * P.ldres + col];
+                        C[(int64_t)row * ldc + col] = y;
+                    }
                 }
             }
         }
@@ -512,6 +538,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGro
         out.ldc = BN;
         out.addend = nullptr;
         out.bias = nullptr;
+        out.residual = nullptr;
         out_m = BM; out_n = BN; out_m0 = 0; out_n0 = 0;
     }
     const int nkt = k1;             // the pass ends before this slab
@@ -620,7 +647,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGro
     if (kt < nkt) step(kt, ring0, ring1);
     fold_acc(sum, acc);
 
-    store_tile(out, out_m, out_n, out_m0, out_n0, L, sum);
+    store_tile(out, out_m, out_n, out_m0, out_n0, L, sum, is_run ? (int)kActNone : g.act);
     if (!is_run) break;
     it += k1 - k0;
     __syncthreads();   // every wave is done with the slab buffers before the next pass refills them
@@ -628,7 +655,8 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGro
 }
 
 // Second kernel of a launch whose tail was split: workgroup t adds the runs of tail tile t in
-// ascending k order, then the addend and the bias, and stores the tile of C.
+// ascending k order, then the addend and the bias, applies the activation, adds the residual and
+// stores the tile of C.
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_f32_join(const GemmGroup g)
 {
     const int t = blockIdx.x;
@@ -659,6 +687,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_f32_join(const GemmGroup g)
             float y = e[q];
             if (addend) y += addend[(int64_t)row * P.ldadd + col + q];
             if (bias) y += bias[col + q];
+            y = activate(y, g.act);
+            if (P.residual) y += P.residual[(int64_t)row * P.ldres + col + q];
             P.C[(int64_t)row * P.ldc + col + q] = y;
         }
     }
@@ -719,7 +749,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_guarded(const GemmGr
         }
     }
     fold_acc(sum, acc);
-    store_tile(P, M, N, tc.m0, tc.n0, L, sum);
+    store_tile(P, M, N, tc.m0, tc.n0, L, sum, g.act);
 }
 
 enum GemmLayout { kGemmNT = 0 /* A KC, B KC */, kGemmNN = 1 /* A KC, B KS */, kGemmTN = 2 /* A KS, B KS */ };

@@ -501,12 +501,13 @@ static bool run_gemm(const jg_plan* plan, jg::GemmGroup& g, int layout, int kern
 // product is a GEMM whose two operands are read along their row stride (A = an X block, K x M;
 // B = a W block, K x N).
 static int forward_xtw(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
-                       const float* const* b_sh, float* const* y_sh, char* ws)
+                       const float* const* b_sh, const float* const* r_sh, int act, float* const* y_sh, char* ws)
 {
     const jg_linear_desc& d = plan->d;
     const int ways = d.ways;
     jg_ctx* c = plan->ctx;
     auto bias_of = [&](int r) -> const float* { return d.has_bias ? b_sh[r] : nullptr; };
+    auto res_of = [&](int r) -> const float* { return r_sh ? r_sh[r] : nullptr; };
     const int ldx = (int)plan->xc, ldw = (int)plan->wc, ldy = (int)plan->yc;
     char* tail = plan->tail_bytes ? ws + plan->off_tail : nullptr;
 
@@ -518,7 +519,8 @@ static int forward_xtw(const jg_plan* plan, const float* const* x_sh, const floa
 
     if (ways == 1) {
         g.nprob = 1;
-        g.p[0] = {x_sh[0], w_sh[0], y_sh[0], nullptr, bias_of(0), ldx, ldw, ldy, 0};
+        g.act = act;
+        g.p[0] = {x_sh[0], w_sh[0], y_sh[0], nullptr, bias_of(0), ldx, ldw, ldy, 0, res_of(0), ldy};
         return run_gemm(plan, g, jg::kGemmTN, JG_KERNEL_GEMM, tail, plan->tail_bytes) ? JG_OK : JG_E_HIP;
     }
 
@@ -547,9 +549,13 @@ static int forward_xtw(const jg_plan* plan, const float* const* x_sh, const floa
         // received one; nothing is summed across ranks, so both products carry the bias
         const int64_t half = (int64_t)plan->xc * plan->yc;   // floats in one M/2 x N/2 block of Y_r
         g.nprob = 4;
+        g.act = act;
         for (int r = 0; r < 2; ++r) {
-            g.p[2 * r] = {x_sh[r], w_sh[r], y_sh[r] + r * half, nullptr, bias_of(r), ldx, ldw, ldy, 0};
-            g.p[2 * r + 1] = {x_in[r], w_sh[r], y_sh[r] + (1 - r) * half, nullptr, bias_of(r), ldx, ldw, ldy, 0};
+            const float* res = res_of(r);
+            g.p[2 * r] = {x_sh[r], w_sh[r], y_sh[r] + r * half, nullptr, bias_of(r), ldx, ldw, ldy, 0,
+                          res ? res + r * half : nullptr, ldy};
+            g.p[2 * r + 1] = {x_in[r], w_sh[r], y_sh[r] + (1 - r) * half, nullptr, bias_of(r), ldx, ldw, ldy, 0,
+                              res ? res + (1 - r) * half : nullptr, ldy};
         }
         return run_gemm(plan, g, jg::kGemmTN, JG_KERNEL_GEMM, tail, plan->tail_bytes) ? JG_OK : JG_E_HIP;
     }
@@ -571,8 +577,9 @@ static int forward_xtw(const jg_plan* plan, const float* const* x_sh, const floa
         g.p[r] = {x_send[r], w_sh[r], send_buf(r), nullptr, nullptr, ldx, ldw, ldy, 0};
     if (!run_gemm(plan, g, jg::kGemmTN, JG_KERNEL_GEMM, tail, plan->tail_bytes)) return JG_E_HIP;
     if (d.combine == JG_COMBINE_FUSED) {
+        g.act = act;
         for (int r = 0; r < 4; ++r)
-            g.p[r] = {x_keep[r], w_sh[r], y_sh[r], send_buf(r ^ 2), bias_of(r), ldx, ldw, ldy, ldy};
+            g.p[r] = {x_keep[r], w_sh[r], y_sh[r], send_buf(r ^ 2), bias_of(r), ldx, ldw, ldy, ldy, res_of(r), ldy};
         return run_gemm(plan, g, jg::kGemmTN, JG_KERNEL_GEMM, tail, plan->tail_bytes) ? JG_OK : JG_E_HIP;
     }
     for (int r = 0; r < 4; ++r)
@@ -583,7 +590,8 @@ static int forward_xtw(const jg_plan* plan, const float* const* x_sh, const floa
     cb.nblocks = 4;
     cb.rows = (int)plan->yr;
     cb.cols = (int)plan->yc;
-    for (int r = 0; r < 4; ++r) cb.b[r] = {kept_buf(r), send_buf(r ^ 2), bias_of(r), y_sh[r]};
+    cb.act = act;
+    for (int r = 0; r < 4; ++r) cb.b[r] = {kept_buf(r), send_buf(r ^ 2), bias_of(r), y_sh[r], res_of(r)};
     ScopedTimer t(c, JG_KERNEL_COMBINE);
     return HIP_OK(jg::launch_combine_group(cb, c->stream)) ? JG_OK : JG_E_HIP;
 }
@@ -592,14 +600,26 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
                       const float* const* b_sh, float* const* y_sh, void* workspace,
                       size_t workspace_bytes)
 {
+    return jg_linear_forward_ex(plan, x_sh, w_sh, b_sh, nullptr, JG_ACT_NONE, y_sh, workspace, workspace_bytes);
+}
+
+int jg_linear_forward_ex(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                         const float* const* b_sh, const float* const* r_sh, int activation, float* const* y_sh,
+                         void* workspace, size_t workspace_bytes)
+{
     if (!plan || !plan->ctx) return JG_E_NULL;
     const jg_linear_desc& d = plan->d;
     const int ways = d.ways;
+    if (activation != JG_ACT_NONE && activation != JG_ACT_GELU) return JG_E_DTYPE;
+    const int act = activation == JG_ACT_GELU ? jg::kActGelu : jg::kActNone;
     if (int rc = check_ptr_array(x_sh, ways)) return rc;
     if (int rc = check_ptr_array(w_sh, ways)) return rc;
     if (int rc = check_ptr_array(y_sh, ways)) return rc;
     if (d.has_bias) {
         if (int rc = check_ptr_array(b_sh, ways)) return rc;
+    }
+    if (r_sh) {
+        if (int rc = check_ptr_array(r_sh, ways)) return rc;
     }
     if (plan->ws_bytes > 0) {
         if (!workspace || workspace_bytes < plan->ws_bytes) return JG_E_WORKSPACE;
@@ -609,8 +629,9 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
     if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
     char* ws = static_cast<char*>(workspace);
     auto bias_of = [&](int r) -> const float* { return d.has_bias ? b_sh[r] : nullptr; };
+    auto res_of = [&](int r) -> const float* { return r_sh ? r_sh[r] : nullptr; };
 
-    if (d.op == JG_OP_XTW) return forward_xtw(plan, x_sh, w_sh, b_sh, y_sh, ws);
+    if (d.op == JG_OP_XTW) return forward_xtw(plan, x_sh, w_sh, b_sh, r_sh, act, y_sh, ws);
     char* tail = plan->tail_bytes ? ws + plan->off_tail : nullptr;
 
     jg::GemmGroup g;
@@ -623,7 +644,8 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
 
     if (ways == 1) {
         g.nprob = 1;
-        g.p[0] = {x_sh[0], w_sh[0], y_sh[0], nullptr, bias_of(0), ldk, ldk, ldn, 0};
+        g.act = act;
+        g.p[0] = {x_sh[0], w_sh[0], y_sh[0], nullptr, bias_of(0), ldk, ldk, ldn, 0, res_of(0), ldn};
         return run_gemm(plan, g, jg::kGemmNT, JG_KERNEL_GEMM, tail, plan->tail_bytes) ? JG_OK : JG_E_HIP;
     }
 
@@ -677,8 +699,10 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
 
     // launch 2: the kept products
     if (d.combine == JG_COMBINE_FUSED) {
+        g.act = act;
         for (int r = 0; r < ways; ++r)
-            g.p[r] = {x_sh[r], w_keep[r], y_sh[r], send_buf(recv_from[r]), bias_of(r), ldk, ldk, ldn, ldn};
+            g.p[r] = {x_sh[r], w_keep[r], y_sh[r], send_buf(recv_from[r]), bias_of(r), ldk, ldk, ldn, ldn,
+                      res_of(r), ldn};
         return run_gemm(plan, g, jg::kGemmNT, JG_KERNEL_GEMM, tail, plan->tail_bytes) ? JG_OK : JG_E_HIP;
     }
     for (int r = 0; r < ways; ++r)
@@ -689,8 +713,9 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
     cb.nblocks = ways;
     cb.rows = (int)plan->yr;
     cb.cols = (int)plan->yc;
+    cb.act = act;
     for (int r = 0; r < ways; ++r)
-        cb.b[r] = {kept_buf(r), send_buf(recv_from[r]), bias_of(r), y_sh[r]};
+        cb.b[r] = {kept_buf(r), send_buf(recv_from[r]), bias_of(r), y_sh[r], res_of(r)};
     ScopedTimer t(c, JG_KERNEL_COMBINE);
     return HIP_OK(jg::launch_combine_group(cb, c->stream)) ? JG_OK : JG_E_HIP;
 }
@@ -789,6 +814,25 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
             g.p[r] = {dy_sh[rk(i, cc)], x_sh[rk(i, j)], dw_sh[r], dw_part(r), nullptr, nh, kh, kh, kh};
         }
     return launch(jg::kGemmTN, JG_KERNEL_GEMM_DW) ? JG_OK : JG_E_HIP;
+}
+
+int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh,
+                   const float* const* w1_sh, const float* const* b1_sh, const float* const* w2_sh,
+                   const float* const* b2_sh, float* const* h_sh, float* const* y_sh, void* workspace,
+                   size_t workspace_bytes)
+{
+    if (!first || !second) return JG_E_NULL;
+    const jg_linear_desc &a = first->d, &b = second->d;
+    if (a.op != JG_OP_XWT || b.op != JG_OP_XWT) return JG_E_DTYPE;
+    if (a.ways != b.ways) return JG_E_WAYS;
+    // X [M x C] -> H [M x Hd] -> Y [M x C]: the second layer maps back to the first one's input width
+    if (a.M != b.M || a.N != b.K || b.N != a.K) return JG_E_SHAPE;
+    if (first->ctx != second->ctx) return JG_E_NULL;
+    if (int rc = check_ptr_array(h_sh, a.ways)) return rc;
+    // H_r is written by the first layer in the partition the second one reads its input in
+    int rc = jg_linear_forward_ex(first, x_sh, w1_sh, b1_sh, nullptr, JG_ACT_GELU, h_sh, workspace, workspace_bytes);
+    if (rc != JG_OK) return rc;
+    return jg_linear_forward_ex(second, h_sh, w2_sh, b2_sh, x_sh, JG_ACT_NONE, y_sh, workspace, workspace_bytes);
 }
 
 }  // extern "C"

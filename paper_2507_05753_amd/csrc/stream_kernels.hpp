@@ -12,6 +12,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+
+#include "epilogue.hpp"
 #include <stdint.h>
 
 namespace jg {
@@ -92,12 +94,13 @@ inline hipError_t launch_copy_group(CopyGroup g, hipStream_t stream)
     return hipSuccess;
 }
 
-// ---- separate combine: y = kept + received (+ bias), dense rows x cols each ----
+// ---- separate combine: y = act(kept + received (+ bias)) (+ residual), dense rows x cols each ----
 struct CombineBlock {
     const float* kept;
     const float* recv;
     const float* bias;   // length cols or nullptr
     float* y;
+    const float* residual;   // dense like y, or nullptr
 };
 
 struct CombineGroup {
@@ -107,6 +110,7 @@ struct CombineGroup {
     int vec_ok;
     uint32_t units_per_row;
     uint32_t units;
+    int act;             // kActNone / kActGelu
 };
 
 __global__ __launch_bounds__(COPY_THREADS) void combine_f32(const CombineGroup g)
@@ -120,10 +124,14 @@ __global__ __launch_bounds__(COPY_THREADS) void combine_f32(const CombineGroup g
         const vf4 r = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(B.recv) + i);
         vf4 y = a + r;   // same order as the fused epilogue: (kept + received) + bias
         if (B.bias) y += reinterpret_cast<const vf4*>(B.bias)[c];
+        if (g.act) y = vf4{activate(y.x, g.act), activate(y.y, g.act), activate(y.z, g.act), activate(y.w, g.act)};
+        if (B.residual) y += __builtin_nontemporal_load(reinterpret_cast<const vf4*>(B.residual) + i);
         __builtin_nontemporal_store(y, reinterpret_cast<vf4*>(B.y) + i);
     } else {
         float y = B.kept[i] + B.recv[i];
         if (B.bias) y += B.bias[c];
+        y = activate(y, g.act);
+        if (B.residual) y += B.residual[i];
         B.y[i] = y;
     }
 }
@@ -134,7 +142,8 @@ inline hipError_t launch_combine_group(CombineGroup g, hipStream_t stream)
     int vec = (g.cols & 3) == 0;
     for (int i = 0; i < g.nblocks; ++i) {
         if (((uintptr_t)g.b[i].kept & 15) || ((uintptr_t)g.b[i].recv & 15) ||
-            ((uintptr_t)g.b[i].y & 15) || (g.b[i].bias && ((uintptr_t)g.b[i].bias & 15)))
+            ((uintptr_t)g.b[i].y & 15) || (g.b[i].bias && ((uintptr_t)g.b[i].bias & 15)) ||
+            (g.b[i].residual && ((uintptr_t)g.b[i].residual & 15)))
             vec = 0;
     }
     g.vec_ok = vec;
@@ -150,6 +159,7 @@ inline hipError_t launch_combine_group(CombineGroup g, hipStream_t stream)
             part.b[i].kept = g.b[i].kept + off;
             part.b[i].recv = g.b[i].recv + off;
             part.b[i].y = g.b[i].y + off;
+            if (g.b[i].residual) part.b[i].residual = g.b[i].residual + off;
         }
         part.units = (uint32_t)((int64_t)part.rows * part.units_per_row);
         dim3 grid((part.units + COPY_THREADS - 1) / COPY_THREADS, g.nblocks, 1);

@@ -199,3 +199,12 @@ XTW_CONFIGS = {
     "small": dict(K=200, M=264, N=136, seed=21),
     "token_mixing_1b": dict(K=16200, M=4320, N=8640, seed=22),
 }
+
+# Workloads of the mixing MLP (X and Y are [tokens, channels] = M x C, W1 is Hd x C, W2 is C x Hd).
+# "channel_mixing_1b": the channel-mixing MLP of the paper's 1-billion-parameter model (Sec. 6.2.1:
+# embedding dimension 4320, channel-mixing hidden dimension 4320) over the 16200 tokens of one sample.
+# Streams: X seed, W1 seed + 1, b1 seed + 2, W2 seed + 3, b2 seed + 4.
+MLP_CONFIGS = {
+    "small": dict(M=258, C=264, Hd=136, seed=23),
+    "channel_mixing_1b": dict(M=16200, C=4320, Hd=4320, seed=24),
+}

@@ -52,11 +52,22 @@ class JigsawLinear:
             assert self.bias and b.is_cuda and b.dtype == torch.float32 and b.shape == (self.N,)
             jg.jg_shard(self.plan, jg.JG_T_B, b.data_ptr(), self.N, [t.data_ptr() for t in self.b])
 
-    def forward(self):
-        jg.jg_linear_forward(self.plan, [t.data_ptr() for t in self.x], [t.data_ptr() for t in self.w],
-                             [t.data_ptr() for t in self.b] if self.bias else None,
-                             [t.data_ptr() for t in self.y],
-                             self.ws.data_ptr() if self.ws_bytes else None, self.ws_bytes)
+    def forward(self, residual=None, activation: int = jg.JG_ACT_NONE):
+        """Y_r = act(X W^T + b)_r (+ residual_r); ``residual``: per-rank tensors shaped like the Y shards."""
+        if residual is None and activation == jg.JG_ACT_NONE:
+            jg.jg_linear_forward(self.plan, [t.data_ptr() for t in self.x], [t.data_ptr() for t in self.w],
+                                 [t.data_ptr() for t in self.b] if self.bias else None,
+                                 [t.data_ptr() for t in self.y],
+                                 self.ws.data_ptr() if self.ws_bytes else None, self.ws_bytes)
+            return
+        if residual is not None:
+            assert len(residual) == self.ways and all(r.shape == y.shape and r.is_contiguous()
+                                                      for r, y in zip(residual, self.y))
+        jg.jg_linear_forward_ex(self.plan, [t.data_ptr() for t in self.x], [t.data_ptr() for t in self.w],
+                                [t.data_ptr() for t in self.b] if self.bias else None,
+                                [t.data_ptr() for t in residual] if residual is not None else None, activation,
+                                [t.data_ptr() for t in self.y],
+                                self.ws.data_ptr() if self.ws_bytes else None, self.ws_bytes)
 
     def gather(self, out=None):
         if out is None:
@@ -106,6 +117,50 @@ class JigsawLinear:
         if self._own_ctx and self.ctx:
             jg.jg_free(self.ctx)
             self.ctx = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+
+class JigsawMLP:
+    """One mixing MLP with its skip connection on Jigsaw shards: H = gelu(X W1^T + b1), Y = X + H W2^T + b2.
+
+    X and Y are (M, C), W1 is (Hd, C), W2 is (C, Hd).  Two JigsawLinear holders share one context; the
+    second reads the first one's output shards in place (``jg_mlp_forward``).
+    """
+
+    def __init__(self, M: int, C: int, Hd: int, ways: int, device: int = 0, ctx=None, tail: int = jg.JG_TAIL_SPLIT):
+        self.first = JigsawLinear(M, C, Hd, ways, bias=True, device=device, ctx=ctx, tail=tail)
+        self.second = JigsawLinear(M, Hd, C, ways, bias=True, device=device, ctx=self.first.ctx, tail=tail)
+        self.second.x = self.first.y        # H_r is consumed where it was produced
+        self.M, self.C, self.Hd, self.ways = M, C, Hd, ways
+        self.ctx = self.first.ctx
+        self.ws_bytes = max(self.first.ws_bytes, self.second.ws_bytes)
+        self.ws = self.first.ws if self.first.ws_bytes >= self.second.ws_bytes else self.second.ws
+
+    def shard(self, X=None, W1=None, b1=None, W2=None, b2=None):
+        self.first.shard(X, W1, b1)
+        self.second.shard(None, W2, b2)
+
+    def forward(self):
+        f, s = self.first, self.second
+        jg.jg_mlp_forward(f.plan, s.plan, [t.data_ptr() for t in f.x], [t.data_ptr() for t in f.w],
+                          [t.data_ptr() for t in f.b], [t.data_ptr() for t in s.w], [t.data_ptr() for t in s.b],
+                          [t.data_ptr() for t in f.y], [t.data_ptr() for t in s.y],
+                          self.ws.data_ptr() if self.ws_bytes else None, self.ws_bytes)
+
+    def gather_h(self):
+        return self.first.gather()
+
+    def gather(self):
+        return self.second.gather()
+
+    def close(self):
+        self.second.close()
+        self.first.close()
 
     def __enter__(self):
         return self

@@ -244,3 +244,23 @@ def test_init_without_a_gpu_fails_cleanly():
     with pytest.raises(jg.JigsawError) as e:
         jg.jg_init(0, None)
     assert e.value.status == jg.JG_E_HIP
+
+
+def test_mlp_entry_point_checks_that_the_plans_chain():
+    lib = jg.raw()
+    arr = (ctypes.c_void_p * 2)(256, 512)
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    call = lambda a, b: lib.jg_mlp_forward(a, b, pp, pp, pp, pp, pp, pp, pp, 256, 1 << 20)
+    a = jg.jg_plan_create(None, 64, 32, 48, 2, True)
+    assert call(None, a) == jg.JG_E_NULL
+    for (M, K, N), ways, want in (((64, 48, 30), 2, jg.JG_E_SHAPE), ((62, 48, 32), 2, jg.JG_E_SHAPE),
+                                  ((64, 40, 32), 2, jg.JG_E_SHAPE), ((64, 48, 32), 4, jg.JG_E_WAYS),
+                                  ((64, 48, 32), 2, jg.JG_E_NULL)):      # chains, but no context
+        b = jg.jg_plan_create(None, M, K, N, ways, True)
+        assert call(a, b) == want
+        jg.jg_plan_destroy(b)
+    t = jg.jg_plan_create(None, 48, 64, 32, 2, True, op=jg.JG_OP_XTW)
+    assert call(a, t) == jg.JG_E_DTYPE
+    assert lib.jg_linear_forward_ex(a, pp, pp, pp, None, 7, pp, 256, 1 << 20) == jg.JG_E_NULL   # no context comes first
+    jg.jg_plan_destroy(t)
+    jg.jg_plan_destroy(a)

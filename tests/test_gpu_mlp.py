@@ -1,0 +1,212 @@
+"""GPU parity of the fused epilogue (bias, GELU, residual) and of the mixing MLP against the CPU oracle.
+
+Bars: the linear part as everywhere (1e-6 of the summand magnitude).  Through GELU an error e in the
+pre-activation shows as at most 1.13 |e| (the largest slope of x Phi(x)), and the FP32 erf adds about
+1e-7 of |x| <= S1: H is held to 1.5e-6 * S1.  In Y that error is carried by |W2| (PY = S1 |W2|^T):
+|Y - Y64| <= 1e-6 * SY + 1.5e-6 * PY.  Without an activation, lattice inputs stay bit-exact.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2507_05753_amd import inputs
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-6
+TOL_H = 1.5e-6
+
+
+@pytest.fixture(scope="module")
+def jg():
+    from paper_2507_05753_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ctx(jg):
+    c = jg.jg_init(0, torch.cuda.current_stream().cuda_stream)
+    yield c
+    torch.cuda.synchronize()
+    jg.jg_free(c)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run_ex(jg, ctx, X, W, b, R, act, ways, combine=0, op=0):
+    """shard -> jg_linear_forward_ex -> gather; R is a global residual (shaped like Y) or None."""
+    from paper_2507_05753_amd.layer import JigsawLinear
+    if op == jg.JG_OP_XTW:
+        K, M = X.shape
+        N = W.shape[1]
+    else:
+        M, K = X.shape
+        N = W.shape[0]
+    with JigsawLinear(M, K, N, ways, bias=b is not None, combine=combine, ctx=ctx, op=op) as L:
+        L.ws.fill_(0xFF)
+        L.shard(dev(X), dev(W), dev(b) if b is not None else None)
+        res = None
+        if R is not None:
+            res = [torch.empty_like(y) for y in L.y]
+            jg.jg_shard(L.plan, jg.JG_T_Y, dev(R).data_ptr(), N, [t.data_ptr() for t in res])
+        L.forward(residual=res, activation=act)
+        Y = L.gather()
+        torch.cuda.synchronize()
+        return Y.cpu().numpy()
+
+
+SHAPES = [(100, 100, 100), (130, 72, 258), (258, 200, 136), (300, 1032, 260), (130, 4160, 258)]   # last: split tail
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,K,N", SHAPES)
+def test_gelu_epilogue(jg, ctx, ways, M, K, N):
+    X, W, b = inputs.layer_inputs(51, M, K, N, "R", bias=True)
+    b = (b * 0.5).astype(np.float32)
+    H = run_ex(jg, ctx, X, W, b, None, jg.JG_ACT_GELU, ways)
+    want = oracle.gelu(oracle.linear(X, W, b))
+    S = oracle.magnitude(X, W, b)
+    err = np.abs(H.astype(np.float64) - want)
+    assert np.all(err <= TOL_H * S), f"max err/S = {(err / S).max():.3e}"
+    # the activation was really applied: it differs from the linear output by far more than the bar
+    assert np.abs(want - oracle.linear(X, W, b)).max() > 1e-2
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,K,N", SHAPES)
+def test_residual_epilogue_is_bit_exact_on_lattice_inputs(jg, ctx, ways, M, K, N):
+    X, W, b = inputs.layer_inputs(52, M, K, N, "L", bias=True)
+    R = inputs.matrix(53, M, N, "L")
+    Y = run_ex(jg, ctx, X, W, b, R, jg.JG_ACT_NONE, ways)
+    want = oracle.linear(X, W, b) + R.astype(np.float64)
+    assert np.array_equal(Y.astype(np.float64), want)
+
+
+@pytest.mark.parametrize("ways", [2, 4])
+def test_separate_combine_and_transposed_layer_take_the_same_epilogue(jg, ctx, ways):
+    M, K, N = 258, 200, 136
+    X, W, b = inputs.layer_inputs(54, M, K, N, "R", bias=True)
+    R = inputs.matrix(55, M, N, "R")
+    fused = run_ex(jg, ctx, X, W, b, R, jg.JG_ACT_GELU, ways)
+    sep = run_ex(jg, ctx, X, W, b, R, jg.JG_ACT_GELU, ways, combine=jg.JG_COMBINE_SEPARATE)
+    want = oracle.gelu(oracle.linear(X, W, b)) + R.astype(np.float64)
+    S = oracle.magnitude(X, W, b) + np.abs(R)
+    for got in (fused, sep):
+        assert np.all(np.abs(got.astype(np.float64) - want) <= TOL_H * S)
+    # transposed layer: X [K x M], W [K x N]
+    Xt = inputs.matrix(56, 200, 264, "R")
+    Wt = inputs.matrix(57, 200, 136, "R", inputs.W_SCALE_EXP)
+    bt = inputs.matrix(58, 1, 136, "R")[0]
+    Rt = inputs.matrix(59, 264, 136, "R")
+    got = run_ex(jg, ctx, Xt, Wt, bt, Rt, jg.JG_ACT_GELU, ways, op=jg.JG_OP_XTW)
+    want = oracle.gelu(oracle.linear_xtw(Xt, Wt, bt)) + Rt.astype(np.float64)
+    S = oracle.magnitude_xtw(Xt, Wt, bt) + np.abs(Rt)
+    assert np.all(np.abs(got.astype(np.float64) - want) <= TOL_H * S)
+
+
+def mlp_operands(seed, M, C, Hd, mode="R"):
+    X = inputs.matrix(seed, M, C, mode)
+    W1 = inputs.matrix(seed + 1, Hd, C, mode, inputs.W_SCALE_EXP)
+    b1 = inputs.matrix(seed + 2, 1, Hd, mode)[0]
+    W2 = inputs.matrix(seed + 3, C, Hd, mode, inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(seed + 4, 1, C, mode)[0]
+    return X, W1, b1, W2, b2
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,C,Hd", [(100, 100, 100), (130, 72, 258), (258, 264, 136), (300, 520, 1032)])
+def test_mlp_forward(jg, ctx, ways, M, C, Hd):
+    from paper_2507_05753_amd.layer import JigsawMLP
+    X, W1, b1, W2, b2 = mlp_operands(60, M, C, Hd)
+    with JigsawMLP(M, C, Hd, ways, ctx=ctx) as L:
+        Xd = dev(X)
+        L.shard(Xd, dev(W1), dev(b1), dev(W2), dev(b2))
+        L.forward()
+        H, Y = L.gather_h().cpu().numpy(), L.gather().cpu().numpy()
+        L.forward()                                      # X was not overwritten: the same again
+        assert np.array_equal(Y, L.gather().cpu().numpy())
+        assert torch.equal(Xd.cpu(), torch.from_numpy(X))
+    r = oracle.mlp(X, W1, b1, W2, b2)
+    eh = np.abs(H.astype(np.float64) - r["H"])
+    assert np.all(eh <= TOL_H * r["S1"]), f"H: max err/S1 = {(eh / r['S1']).max():.3e}"
+    ey = np.abs(Y.astype(np.float64) - r["Y"])
+    bound = TOL * r["SY"] + TOL_H * r["PY"]
+    assert np.all(ey <= bound), f"Y: max err/bound = {(ey / bound).max():.3e}"
+    # the second layer on its own, at the usual bar: from the H the GPU produced
+    want2 = oracle.linear(H, W2, b2) + X.astype(np.float64)
+    S2 = oracle.magnitude(H, W2, b2) + np.abs(X)
+    assert np.all(np.abs(Y.astype(np.float64) - want2) <= TOL * S2)
+
+
+def test_mlp_plans_must_chain(jg, ctx):
+    a = jg.jg_plan_create(ctx, 64, 32, 48, 2, True)
+    good = jg.jg_plan_create(ctx, 64, 48, 32, 2, True)
+    ptr = [256, 512]
+    for bad_args, status in ((dict(M=64, K=48, N=30), jg.JG_E_SHAPE), (dict(M=62, K=48, N=32), jg.JG_E_SHAPE),
+                             (dict(M=64, K=40, N=32), jg.JG_E_SHAPE)):
+        b = jg.jg_plan_create(ctx, bad_args["M"], bad_args["K"], bad_args["N"], 2, True)
+        with pytest.raises(jg.JigsawError) as e:
+            jg.jg_mlp_forward(a, b, ptr, ptr, ptr, ptr, ptr, ptr, ptr, None, 0)
+        assert e.value.status == status
+        jg.jg_plan_destroy(b)
+    b = jg.jg_plan_create(ctx, 64, 48, 32, 4, True)
+    with pytest.raises(jg.JigsawError) as e:
+        jg.jg_mlp_forward(a, b, ptr, ptr, ptr, ptr, ptr, ptr, ptr, None, 0)
+    assert e.value.status == jg.JG_E_WAYS
+    with pytest.raises(jg.JigsawError) as e:
+        jg.jg_linear_forward_ex(good, ptr, ptr, ptr, None, 7, ptr, None, 0)
+    assert e.value.status == jg.JG_E_DTYPE
+    for p in (a, good, b):
+        jg.jg_plan_destroy(p)
+
+
+# --------------------------------------------------------------------------------------------
+# full size: the channel-mixing MLP of the paper's 1-billion-parameter model (Sec. 6.2.1: embedding
+# dimension 4320, channel-mixing hidden dimension 4320) over 16200 tokens
+# --------------------------------------------------------------------------------------------
+def note(capsys, msg):
+    with capsys.disabled():
+        print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
+
+
+@pytest.mark.timeout(600)
+def test_channel_mixing_size(jg, capsys):
+    from paper_2507_05753_amd.layer import JigsawMLP
+    cfg = inputs.MLP_CONFIGS["channel_mixing_1b"]
+    M, C, Hd, seed = cfg["M"], cfg["C"], cfg["Hd"], cfg["seed"]
+    Xd = inputs.matrix_torch(seed, M, C, "R", device="cuda")
+    W1 = inputs.matrix(seed + 1, Hd, C, "R", inputs.W_SCALE_EXP)
+    b1 = inputs.matrix(seed + 2, 1, Hd, "R")[0]
+    W2 = inputs.matrix(seed + 3, C, Hd, "R", inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(seed + 4, 1, C, "R")[0]
+    k = inputs.keys(6000, np.arange(96, dtype=np.uint64))
+    rows = np.unique(np.concatenate([(k % np.uint64(M)).astype(np.int64), [0, M // 2 - 1, M // 2, M - 1]]))
+    Xs = inputs.matrix_rows(seed, C, rows, "R")
+    assert np.array_equal(Xd[torch.from_numpy(rows).cuda()].cpu().numpy(), Xs)
+    r = oracle.mlp(Xs, W1, b1, W2, b2)          # whole rows of H and Y for the sampled tokens
+    note(capsys, f"channel mixing: oracle rows ready ({rows.size} tokens)")
+    W1d, b1d, W2d, b2d = dev(W1), dev(b1), dev(W2), dev(b2)
+    for ways in (1, 2, 4):
+        with JigsawMLP(M, C, Hd, ways) as L:
+            L.ws.fill_(0xFF)
+            L.shard(Xd, W1d, b1d, W2d, b2d)
+            L.forward()
+            H, Y = L.gather_h(), L.gather()
+            torch.cuda.synchronize()
+            assert torch.isfinite(H).all() and torch.isfinite(Y).all()
+            idx = torch.from_numpy(rows).cuda()
+            H32 = H[idx].cpu().numpy()
+            Hs, Ys = H32.astype(np.float64), Y[idx].cpu().numpy().astype(np.float64)
+            del H, Y
+        torch.cuda.empty_cache()
+        eh = np.abs(Hs - r["H"]) / r["S1"]
+        ey = np.abs(Ys - r["Y"]) / (TOL * r["SY"] + TOL_H * r["PY"])
+        assert eh.max() <= TOL_H and ey.max() <= 1.0, (ways, eh.max(), ey.max())
+        e2 = np.abs(Ys - (oracle.linear(H32, W2, b2) + Xs)) / (oracle.magnitude(H32, W2, b2) + np.abs(Xs))
+        assert e2.max() <= TOL, (ways, e2.max())      # the second layer alone, from the GPU's own H
+        note(capsys, f"channel mixing ways={ways}: H max err/S1 {eh.max():.2e}, layer 2 max err/S {e2.max():.2e}, Y max err/bound {ey.max():.2e} "
+                     f"({rows.size} x {C} entries each)")
