@@ -20,9 +20,11 @@
 //   wavefront : 64 x 64 sub-tile = 2 x 2 MFMA blocks of 32 x 32 (v_mfma_f32_32x32x2_f32)
 //   K loop    : slabs of 32, two slab buffers in LDS used alternately
 //
-// gemm_f32_stream<A_KS, B_KS> (operand rows 16-byte aligned, contiguous extents in whole
+// gemm_f32_stream<A_KS, B_KS, RUNS> (operand rows 16-byte aligned, contiguous extents in whole
 // 16-byte chunks): slabs go global -> LDS without passing through registers
-// (buffer_load_dwordx4 ... lds), one slab ahead of the math.  A wave-level load fills 1 KiB
+// (buffer_load_dwordx4 ... lds), requested two slabs ahead of the math, one transfer after every
+// second MFMA of a slab's last k-group (a burst of transfers, or any vector ALU instruction
+// between MFMAs, holds up the matrix pipe measurably).  A wave-level load fills 1 KiB
 // of LDS, lane l writing 16-byte slot l; rows are not padded, instead the lane chooses WHICH
 // 16-byte chunk of global memory it fetches so that the later LDS reads are conflict-free:
 //   KC operand slab: 128 rows x 32 k (128-B rows), chunk = slot ^ ((row >> 1) & 7); the MFMA
@@ -34,7 +36,8 @@
 // the operand (past K, or past the last row / column) are fetched from outside the buffer
 // descriptor and arrive as zeros, or are clamped to valid rows whose results are discarded.
 // The received partial product (the addend) is loaded straight into the accumulators while
-// the first slab is in flight, so the epilogue only stores.
+// the first slab is in flight; the epilogue adds the bias, applies the activation, adds the
+// residual and stores.
 //
 // gemm_f32_guarded<A_KS, B_KS> (anything else): register loads with per-element bounds
 // checks written to the same LDS positions.
@@ -46,11 +49,12 @@
 //
 // Tail: tiles are equal, so a launch whose tile count is not a multiple of the number of
 // workgroups the chip holds (2 per CU) ends with a partial round in which part of the chip
-// idles - 10 % of the time for 2312 long tiles on 512 slots.  The launcher therefore runs only
-// whole rounds one tile per workgroup; the K loops of the remaining tiles are cut into equal
-// runs of slabs, one run per extra workgroup (a run covers the end of one tile and the start of
-// the next).  Each run writes its raw accumulators to a scratch tile, and a second small kernel
-// (`gemm_f32_join`) adds a tile's runs in ascending k order, then the addend and the bias, and
+// idles - 10 % of the time for 2312 long tiles on 512 slots.  Where an estimate says it pays, the
+// launcher runs only whole rounds one tile per workgroup (RUNS = false) and cuts the K loops of
+// the remaining tiles into equal runs of slabs, one run per workgroup of a second launch
+// (RUNS = true; a run covers the end of one tile and the start of the next).  Each run writes
+// its raw accumulators to a scratch tile, and a third small kernel (`gemm_f32_join`) adds a
+// tile's runs in ascending k order, then the addend and the bias, applies the epilogue and
 // stores C: no atomics, no flags, the same result on every run.
 #pragma once
 
