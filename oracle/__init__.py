@@ -274,6 +274,60 @@ def jigsaw_mlp(ways: int, X, W1, b1, W2, b2, residual: bool = True):
 
 
 # ----------------------------------------------------------------------------
+# patch encoder / decoder (Sec. 5 "Encoding and decoding layers"): a convolution whose kernel
+# equals its stride is a linear layer over non-overlapping patches
+# ----------------------------------------------------------------------------
+def patchify(field: np.ndarray, p: int) -> np.ndarray:
+    """Patch matrix of a [C, H, W] field: row t = py * (W / p) + px is the patch at (py, px), column
+    f = c * p * p + dy * p + dx holds field[c, py * p + dy, px * p + dx].  Plain loops over patches."""
+    C, H, W = field.shape
+    if p < 1 or H % p or W % p:
+        raise ValueError("H and W must be multiples of the patch size")
+    hp, wp = H // p, W // p
+    out = np.empty((hp * wp, C * p * p), dtype=field.dtype)
+    for py in range(hp):
+        for px in range(wp):
+            for c in range(C):
+                blk = field[c, py * p:(py + 1) * p, px * p:(px + 1) * p]
+                out[py * wp + px, c * p * p:(c + 1) * p * p] = blk.reshape(-1)
+    return out
+
+
+def unpatchify(patches: np.ndarray, C: int, H: int, W: int, p: int) -> np.ndarray:
+    """Inverse of :func:`patchify` (the decoder's rearrangement of token rows back into a field)."""
+    hp, wp = H // p, W // p
+    assert patches.shape == (hp * wp, C * p * p)
+    field = np.empty((C, H, W), dtype=patches.dtype)
+    for py in range(hp):
+        for px in range(wp):
+            for c in range(C):
+                field[c, py * p:(py + 1) * p, px * p:(px + 1) * p] = \
+                    patches[py * wp + px, c * p * p:(c + 1) * p * p].reshape(p, p)
+    return field
+
+
+def patch_conv(field: np.ndarray, kernel: np.ndarray, bias=None) -> np.ndarray:
+    """The encoder by its definition as a strided convolution, in double:
+    out[(py, px), n] = b[n] + sum_{c, dy, dx} field[c, py p + dy, px p + dx] * kernel[n, c, dy, dx].
+    Pure-Python loops: tiny shapes only."""
+    C, H, W = field.shape
+    N, C2, p, p2 = kernel.shape
+    assert C2 == C and p2 == p and H % p == 0 and W % p == 0
+    hp, wp = H // p, W // p
+    out = np.zeros((hp * wp, N))
+    for py in range(hp):
+        for px in range(wp):
+            for n in range(N):
+                acc = float(bias[n]) if bias is not None else 0.0
+                for c in range(C):
+                    for dy in range(p):
+                        for dx in range(p):
+                            acc += float(field[c, py * p + dy, px * p + dx]) * float(kernel[n, c, dy, dx])
+                out[py * wp + px, n] = acc
+    return out
+
+
+# ----------------------------------------------------------------------------
 # layout definitions (pure indexing; bit-exact)
 # ----------------------------------------------------------------------------
 def _check_ways(ways, M, K, N):
