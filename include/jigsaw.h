@@ -186,6 +186,26 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out);
  * Errors: JG_E_NULL, JG_E_SHAPE (ld), JG_E_ALIGN, JG_E_DTYPE (which), JG_E_HIP. */
 int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, float* const* shards);
 
+/* build (data, encoder).  The patch encoder is a convolution whose kernel equals its stride, computed
+ * as a linear layer over non-overlapping patches (Sec. 5 "Encoding and decoding layers").  This call
+ * writes the X shards of that layer straight from the field, each rank reading its own part of it
+ * (Sec. 5 "Data loading"), so the patch matrix is never stored whole.
+ *   field: device, C x H x W dense row-major.  p: patch size; must divide H and W.
+ *   Patch matrix: row t = py * (W / p) + px, column f = c * p * p + dy * p + dx, value
+ *   field[c, py * p + dy, px * p + dx].  The plan (JG_OP_XWT) must have M = (H / p) * (W / p) and
+ *   K = C * p * p; a weight row is the convolution kernel of one output channel, flattened [c][dy][dx].
+ * x_shards as in jg_shard(JG_T_X).  Pure data movement: bit-exact.
+ * Errors: JG_E_NULL, JG_E_DTYPE (op), JG_E_ALIGN, JG_E_SHAPE (sizes do not match the plan), JG_E_HIP. */
+int jg_shard_patches(const jg_plan* plan, const float* field, int64_t C, int64_t H, int64_t W, int64_t p,
+                     float* const* x_shards);
+
+/* query (data, decoder).  The inverse rearrangement for the decoder: the rows of Y (one per patch,
+ * N = C * p * p values each, M = (H / p) * (W / p)) are written back as a C x H x W field from the
+ * per-rank Y shards.  Bit-exact.
+ * Errors: as jg_shard_patches. */
+int jg_gather_patches(const jg_plan* plan, const float* const* y_shards, float* field, int64_t C, int64_t H,
+                      int64_t W, int64_t p);
+
 /* run.  One forward pass of the layer over all `ways` virtual ranks:
  *   (ways = 4, JG_WEIGHTS_COPY) copy each rank's incoming weight block;
  *   launch 1: every rank's product that is handed to a peer, stored into the

@@ -45,6 +45,7 @@ JG_T_X, JG_T_W, JG_T_B, JG_T_Y = 0, 1, 2, 3
  JG_KERNEL_GATHER, JG_KERNEL_GEMM_DX, JG_KERNEL_GEMM_DW, JG_KERNEL_JOIN, JG_KERNEL_COUNT) = range(9)
 
 EXPORTS = ("jg_init", "jg_free", "jg_plan_create", "jg_plan_destroy", "jg_plan_query", "jg_shard",
+           "jg_shard_patches", "jg_gather_patches",
            "jg_linear_forward", "jg_linear_forward_ex", "jg_mlp_forward", "jg_linear_backward", "jg_gather", "jg_gather_as", "jg_profile", "jg_profile_read", "jg_strerror",
            "jg_last_hip_error")
 
@@ -79,6 +80,10 @@ _lib.jg_plan_destroy.argtypes = [_vp]
 _lib.jg_plan_destroy.restype = None
 _lib.jg_plan_query.argtypes = [_vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]
 _lib.jg_shard.argtypes = [_vp, ctypes.c_int, _vp, ctypes.c_int64, _vpp]
+_lib.jg_shard_patches.argtypes = [_vp, _vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, _vpp]
+_lib.jg_gather_patches.argtypes = [_vp, _vpp, _vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
+_lib.jg_shard_patches.restype = ctypes.c_int
+_lib.jg_gather_patches.restype = ctypes.c_int
 _lib.jg_linear_forward.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
 _lib.jg_linear_forward_ex.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, ctypes.c_int, _vpp, _vp, ctypes.c_size_t]
 _lib.jg_mlp_forward.argtypes = [_vp, _vp, _vpp, _vpp, _vpp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
@@ -145,6 +150,14 @@ def jg_plan_query(plan, what: int, rank: int = 0) -> int:
 
 def jg_shard(plan, which: int, global_ptr: int, ld: int, shard_ptrs) -> None:
     _raise(_lib.jg_shard(plan, which, global_ptr, ld, _ptr_array(shard_ptrs)), "jg_shard")
+
+
+def jg_shard_patches(plan, field_ptr: int, C: int, H: int, W: int, p: int, x_ptrs) -> None:
+    _raise(_lib.jg_shard_patches(plan, field_ptr, C, H, W, p, _ptr_array(x_ptrs)), "jg_shard_patches")
+
+
+def jg_gather_patches(plan, y_ptrs, field_ptr: int, C: int, H: int, W: int, p: int) -> None:
+    _raise(_lib.jg_gather_patches(plan, _ptr_array(y_ptrs), field_ptr, C, H, W, p), "jg_gather_patches")
 
 
 def jg_linear_forward(plan, x_ptrs, w_ptrs, b_ptrs, y_ptrs, workspace_ptr, workspace_bytes: int) -> None:

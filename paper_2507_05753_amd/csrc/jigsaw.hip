@@ -12,6 +12,7 @@
 
 #include "gemm_f32.hpp"
 #include "stream_kernels.hpp"
+#include "patch_kernels.hpp"
 
 namespace {
 
@@ -470,6 +471,55 @@ int jg_gather_as(const jg_plan* plan, int which, const float* const* shards, flo
     }
     ScopedTimer t(c, JG_KERNEL_GATHER);
     return HIP_OK(jg::launch_copy_group(g, c->stream)) ? JG_OK : JG_E_HIP;
+}
+
+// Shared by jg_shard_patches / jg_gather_patches: `which` is the tensor whose partition the blocks follow.
+static int patch_move(const jg_plan* plan, int which, float* field, int64_t C, int64_t H, int64_t W, int64_t p,
+                      float* const* blocks, bool to_field)
+{
+    if (!plan || !field) return JG_E_NULL;
+    const jg_linear_desc& d = plan->d;
+    if (d.op != JG_OP_XWT) return JG_E_DTYPE;
+    if (int rc = check_ptr_array(blocks, d.ways)) return rc;
+    if (!aligned(field, 4)) return JG_E_ALIGN;
+    if (C <= 0 || H <= 0 || W <= 0 || p <= 0 || C > kMaxDim || H > kMaxDim || W > kMaxDim || p > 4096) return JG_E_SHAPE;
+    if (H % p || W % p) return JG_E_SHAPE;
+    Partition pt;
+    (void)partition_of(plan, which, &pt);
+    // tokens = patches, features = channels x patch elements
+    if ((H / p) * (W / p) != d.M || C * p * p != pt.width) return JG_E_SHAPE;
+    if (pt.rows * pt.cols >= jg::kMaxUnitsPerLaunch) return JG_E_SHAPE;
+    jg_ctx* c = plan->ctx;
+    if (!c) return JG_E_NULL;
+    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    jg::PatchGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.nblocks = d.ways;
+    g.rows = (int)pt.rows;
+    g.cols = (int)pt.cols;
+    g.field = field;
+    g.H = (int)H; g.W = (int)W; g.p = (int)p; g.wp = (int)(W / p);
+    for (int r = 0; r < d.ways; ++r) {
+        int64_t rb, cb;
+        block_coords(d.ways, r, &rb, &cb);
+        g.block[r] = blocks[r];
+        g.row0[r] = (int)(rb * pt.rows);
+        g.col0[r] = (int)(cb * pt.cols);
+    }
+    ScopedTimer t(c, to_field ? JG_KERNEL_GATHER : JG_KERNEL_SHARD);
+    return HIP_OK(jg::launch_patch_group(g, to_field, c->stream)) ? JG_OK : JG_E_HIP;
+}
+
+int jg_shard_patches(const jg_plan* plan, const float* field, int64_t C, int64_t H, int64_t W, int64_t p,
+                     float* const* x_shards)
+{
+    return patch_move(plan, JG_T_X, const_cast<float*>(field), C, H, W, p, x_shards, false);
+}
+
+int jg_gather_patches(const jg_plan* plan, const float* const* y_shards, float* field, int64_t C, int64_t H,
+                      int64_t W, int64_t p)
+{
+    return patch_move(plan, JG_T_Y, field, C, H, W, p, const_cast<float* const*>(y_shards), true);
 }
 
 int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, int64_t ld)

@@ -208,3 +208,11 @@ MLP_CONFIGS = {
     "small": dict(M=258, C=264, Hd=136, seed=23),
     "channel_mixing_1b": dict(M=16200, C=4320, Hd=4320, seed=24),
 }
+
+# Workload of the patch encoder (a [C, H, W] field -> patches -> linear).  "encoder_1b": the variables
+# of Sec. 6 (4 surface + 5 x 13 pressure-level + 3 constant fields = 72) on the 0.25 degree grid cropped
+# to 720 x 1440, 8 x 8 patches (16200 tokens of 4608 features) into the 1B model's embedding of 4320.
+# The field's element (c, y, x) is element (c * H + y, x) of a (C H) x W matrix of stream `seed`.
+ENCODER_CONFIGS = {
+    "encoder_1b": dict(C=72, H=720, W=1440, p=8, N=4320, seed=25),
+}

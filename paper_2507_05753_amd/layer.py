@@ -52,6 +52,19 @@ class JigsawLinear:
             assert self.bias and b.is_cuda and b.dtype == torch.float32 and b.shape == (self.N,)
             jg.jg_shard(self.plan, jg.JG_T_B, b.data_ptr(), self.N, [t.data_ptr() for t in self.b])
 
+    def shard_patches(self, field, p: int):
+        """X shards straight from a (C, H, W) field: the patch encoder's input (jg_shard_patches)."""
+        assert field.is_cuda and field.dtype == torch.float32 and field.dim() == 3 and field.is_contiguous()
+        C, H, W = field.shape
+        jg.jg_shard_patches(self.plan, field.data_ptr(), C, H, W, p, [t.data_ptr() for t in self.x])
+
+    def gather_patches(self, C: int, H: int, W: int, p: int, out=None):
+        """(C, H, W) field from the Y shards: the patch decoder's output (jg_gather_patches)."""
+        if out is None:
+            out = torch.empty((C, H, W), dtype=torch.float32, device=self.dev)
+        jg.jg_gather_patches(self.plan, [t.data_ptr() for t in self.y], out.data_ptr(), C, H, W, p)
+        return out
+
     def forward(self, residual=None, activation: int = jg.JG_ACT_NONE):
         """Y_r = act(X W^T + b)_r (+ residual_r); ``residual``: per-rank tensors shaped like the Y shards."""
         if residual is None and activation == jg.JG_ACT_NONE:

@@ -264,3 +264,27 @@ def test_mlp_entry_point_checks_that_the_plans_chain():
     assert lib.jg_linear_forward_ex(a, pp, pp, pp, None, 7, pp, 256, 1 << 20) == jg.JG_E_NULL   # no context comes first
     jg.jg_plan_destroy(t)
     jg.jg_plan_destroy(a)
+
+
+def test_patch_calls_check_sizes_against_the_plan():
+    lib = jg.raw()
+    arr = (ctypes.c_void_p * 2)(256, 512)
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    # 2 channels, 8 x 16 field, 4 x 4 patches: 8 patches of 32 features
+    p = jg.jg_plan_create(None, 8, 32, 6, 2)
+    call = lambda C, H, W, ps: lib.jg_shard_patches(p, 256, C, H, W, ps, pp)
+    assert call(2, 8, 16, 4) == jg.JG_E_NULL          # sizes fit; the plan has no context
+    assert call(2, 8, 16, 3) == jg.JG_E_SHAPE         # patch size does not divide the field
+    assert call(2, 8, 8, 4) == jg.JG_E_SHAPE          # 4 patches, the plan has 8 rows
+    assert call(1, 8, 16, 4) == jg.JG_E_SHAPE         # 16 features, the plan has 32
+    assert call(2, 8, 16, 0) == jg.JG_E_SHAPE
+    assert lib.jg_shard_patches(p, None, 2, 8, 16, 4, pp) == jg.JG_E_NULL
+    assert lib.jg_shard_patches(p, 258, 2, 8, 16, 4, pp) == jg.JG_E_ALIGN
+    # decoder side: the features are the plan's N
+    q = jg.jg_plan_create(None, 8, 6, 32, 2)
+    assert lib.jg_gather_patches(q, pp, 256, 2, 8, 16, 4) == jg.JG_E_NULL
+    assert lib.jg_gather_patches(p, pp, 256, 2, 8, 16, 4) == jg.JG_E_SHAPE
+    t = jg.jg_plan_create(None, 32, 8, 6, 2, op=jg.JG_OP_XTW)
+    assert lib.jg_shard_patches(t, 256, 2, 8, 16, 4, pp) == jg.JG_E_DTYPE
+    for h in (p, q, t):
+        jg.jg_plan_destroy(h)
