@@ -31,10 +31,11 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--ways", type=int, default=4, choices=[1, 2, 4])
-    ap.add_argument("--op", choices=["forward", "backward", "xtw", "mlp"], default="forward",
+    ap.add_argument("--op", choices=["forward", "backward", "xtw", "mlp", "encoder"], default="forward",
                     help="forward: Y = X W^T (the headline); backward: dX = dY W and dW = dY^T X; "
                          "xtw: the transposed layer Y = X^T W at the token-mixing size; mlp: one mixing MLP "
-                         "(GELU between two layers, residual) at the channel-mixing size (both ignore --config)")
+                         "(GELU between two layers, residual) at the channel-mixing size; encoder: patch rearrangement of a "
+                         "field + linear layer at the 1B model's encoder size (these ignore --config)")
     ap.add_argument("--combine", choices=["fused", "separate"], default="fused")
     ap.add_argument("--weights", choices=["copy", "direct"], default="copy")
     ap.add_argument("--tail", choices=["split", "whole"], default="split",
@@ -224,6 +225,72 @@ def measure_xtw(cfg, ways, args):
     return out
 
 
+def measure_encoder(cfg, ways, args):
+    """One step = jg_shard_patches (field -> X shards) + jg_linear_forward; field and weights resident in HBM."""
+    import torch
+    from paper_2507_05753_amd import binding as jg
+    from paper_2507_05753_amd import inputs
+    from paper_2507_05753_amd.layer import JigsawLinear
+    C, H, W, p, N, seed = cfg["C"], cfg["H"], cfg["W"], cfg["p"], cfg["N"], cfg["seed"]
+    M, K = (H // p) * (W // p), C * p * p
+    dev = torch.device("cuda", 0)
+    field = inputs.matrix_torch(seed, C * H, W, "R", 0, device=dev).reshape(C, H, W)
+    Wt = inputs.matrix_torch(seed + inputs.W_STREAM, N, K, "R", inputs.W_SCALE_EXP, device=dev)
+    with JigsawLinear(M, K, N, ways, tail=tail_of(args)) as L:
+        L.shard(None, Wt)
+        del Wt
+
+        class Step:            # what time_forward drives
+            ctx = L.ctx
+
+            @staticmethod
+            def forward():
+                L.shard_patches(field, p)
+                L.forward()
+
+        for k in (jg.JG_KERNEL_SHARD,):
+            jg.jg_profile_read(L.ctx, k)
+        sec, gemm_ms, gemm_n, copy_ms, comb_ms = time_forward(Step, jg, args.steps, args.warmup)
+        sh_ms, sh_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_SHARD)
+        flops = L.query(jg.JG_Q_FLOPS_TOTAL)
+        launches = L.query(jg.JG_Q_GEMM_LAUNCHES)
+        avg = gemm_ms / max(gemm_n, 1)
+        out = dict(ms_per_step=sec * 1e3, items_per_s=M * K / sec, tflops=flops / sec / 1e12,
+                   gemm_avg_launch_ms=avg, gemm_launches_timed=gemm_n,
+                   gemm_tflops=(flops / launches) / (avg * 1e-3) / 1e12 if gemm_n else None,
+                   other_kernels_ms_per_step=copy_ms + comb_ms + sh_ms / args.steps,
+                   patch_shard_gbps=8.0 * M * K / (sh_ms / max(sh_n, 1) * 1e-3) / 1e9 if sh_n else None,
+                   M=M, K=K)
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline_encoder(cfg, seconds):
+    """Oracle: plain-loop patch rearrangement of a band of the field, then the forward oracle on those rows."""
+    import oracle
+    from paper_2507_05753_amd import inputs
+    C, H, W, p, N, seed = cfg["C"], cfg["H"], cfg["W"], cfg["p"], cfg["N"], cfg["seed"]
+    K, wp = C * p * p, W // p
+    cores = min(oracle.host_threads(), 16)
+    Wt = inputs.matrix(seed + inputs.W_STREAM, N, K, "R", inputs.W_SCALE_EXP)
+
+    def run(bands):            # bands of p field rows = wp patches each
+        import numpy as np
+        ids = [c * H + y for c in range(C) for y in range(bands * p)]
+        band = inputs.matrix_rows(seed, W, ids, "R").reshape(C, bands * p, W)
+        t0 = time.perf_counter()
+        P = oracle.patchify(band, p)
+        oracle.linear_rows(P, Wt, None, 0, P.shape[0], nthreads=cores)
+        return time.perf_counter() - t0, P.shape[0]
+
+    dt, rows = run(1)
+    bands = int(max(1, min(H // p, seconds / max(dt, 1e-9))))
+    dt, rows = run(bands)
+    return dict(value=rows * K / dt, unit="items/s", cores=cores, kind="oracle",
+                sample=f"{bands} band(s) of {p} field rows = {rows} patches x {K} features against all of W "
+                       f"({N} x {K}), {dt:.1f} s, plain-loop rearrangement + fp64 triple loop")
+
+
 def measure_mlp(cfg, ways, args):
     """One step = one jg_mlp_forward: H = gelu(X W1^T + b1), Y = X + H W2^T + b2, shards resident in HBM."""
     import torch
@@ -393,6 +460,34 @@ def main():
         }
         if args.cpu_seconds > 0:
             line["cpu_baseline"] = cpu_baseline_xtw(xc, args.cpu_seconds)
+        print(json.dumps(line), flush=True)
+        return
+
+    if args.op == "encoder":
+        ec = inputs.ENCODER_CONFIGS["encoder_1b"]
+        r = measure_encoder(ec, args.ways, args)
+        line = {
+            "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
+            "value": r["items_per_s"], "unit": "items/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"patch encoder of the 1B model: field {ec['C']} x {ec['H']} x {ec['W']}, "
+                                   f"{ec['p']} x {ec['p']} patches -> {r['M']} x {r['K']} . W^T ({ec['N']} x {r['K']}), "
+                                   f"{args.ways}-way Jigsaw, fp32",
+                       "n_items": r["M"] * r["K"], "ways": args.ways, "M": r["M"], "K": r["K"], "N": ec["N"],
+                       "seed": ec["seed"], "x_values": "R", "op": "encoder", "tail": args.tail},
+            "tflops": r["tflops"],
+            "roofline": {"bound": "mfma", "kernel": "jg::gemm_f32_stream<false, false, false>",
+                         "achieved": r["gemm_tflops"], "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": r["gemm_tflops"] / FP32_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None,
+                         "avg_launch_ms": r["gemm_avg_launch_ms"], "launches": r["gemm_launches_timed"],
+                         "traffic": None},
+            "other_kernels_ms_per_step": r["other_kernels_ms_per_step"],
+            "streaming": {"patch_shard_gbps": r["patch_shard_gbps"],
+                          "patch_shard_frac": r["patch_shard_gbps"] / HBM_PEAK_GBPS if r["patch_shard_gbps"] else None},
+        }
+        if args.cpu_seconds > 0:
+            line["cpu_baseline"] = cpu_baseline_encoder(ec, args.cpu_seconds)
         print(json.dumps(line), flush=True)
         return
 

@@ -37,7 +37,8 @@ def field_of(seed, C, H, W, mode="R"):
 
 
 # (C, H, W, p): 16-byte path (p = 4, 8), element path (p = 2, 3, 1, and W not a multiple of 4)
-GEOMETRIES = [(2, 8, 16, 4), (6, 16, 24, 8), (4, 12, 18, 3), (2, 6, 8, 2), (8, 4, 6, 1), (3, 8, 16, 8), (2, 16, 12, 4)]
+GEOMETRIES = [(2, 8, 16, 4), (6, 16, 24, 8), (4, 12, 18, 3), (2, 6, 8, 2), (8, 4, 6, 1), (3, 8, 16, 8), (2, 16, 12, 4),
+              (2, 32, 48, 16), (4, 24, 40, 8), (2, 24, 24, 12)]   # tiled kernel: p = 4, 8, 16 with whole channels per block
 
 
 @pytest.mark.parametrize("ways", [1, 2, 4])
