@@ -59,6 +59,7 @@ def _load():
         lib.oracle_linear_xtw.argtypes = [f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int, ctypes.c_int]
         lib.oracle_jigsaw_xtw.argtypes = [ctypes.c_int, f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int]
         lib.oracle_gelu.argtypes = [f64p, i64, f64p]
+        lib.oracle_layernorm.argtypes = [f32p, f32p, f32p, i64, i64, i64, ctypes.c_double, f64p, f64p, ctypes.c_int]
         lib.oracle_mlp.argtypes = [f32p, f32p, f32p, f32p, f32p, i64, i64, i64, ctypes.c_int,
                                    f64p, f64p, f64p, f64p, f64p, ctypes.c_int]
         for fn in (lib.oracle_linear, lib.oracle_linear_rows, lib.oracle_magnitude,
@@ -271,6 +272,49 @@ def jigsaw_mlp(ways: int, X, W1, b1, W2, b2, residual: bool = True):
     H = gelu(jigsaw(ways, X, W1, b1)).astype(np.float32)
     Y = jigsaw(ways, H, W2, b2)
     return Y + np.asarray(X, dtype=np.float64) if residual else Y
+
+
+# ----------------------------------------------------------------------------
+# layer norm (Sec. 3; Sec. 5 "Layer norms") and the pre-norm channel-mixing block
+# ----------------------------------------------------------------------------
+LN_EPS = 1e-5      # the default of the library routine the paper says it uses
+
+
+def ln_groups(ways: int) -> int:
+    """Channel blocks that are normalised on their own: the channels are split in two for 2- and 4-way."""
+    if ways not in (1, 2, 4):
+        raise RuntimeError(f"ways must be 1, 2 or 4, not {ways}")
+    return 1 if ways == 1 else 2
+
+
+def layernorm(X, gamma=None, beta=None, groups: int = 1, eps: float = LN_EPS, nthreads: int | None = None,
+              magnitude: bool = False):
+    """Per token (row) and channel block: (x - mean) / sqrt(var + eps) * gamma + beta, in double.
+
+    With magnitude=True also returns (|x| + |mean|) / sqrt(var + eps) * |gamma| + |beta|."""
+    X, xp = _f32(X)
+    gamma, gp = _opt_f32(gamma)
+    beta, bp = _opt_f32(beta)
+    M, C = X.shape
+    assert gamma is None or gamma.shape == (C,)
+    assert beta is None or beta.shape == (C,)
+    Y, yp = _f64_out((M, C))
+    S, sp = _f64_out((M, C)) if magnitude else (None, None)
+    _check(_load().oracle_layernorm(xp, gp, bp, M, C, groups, float(eps), yp, sp, nthreads or host_threads()),
+           "layernorm")
+    return (Y, S) if magnitude else Y
+
+
+def mixing_block(ways: int, X, gamma, beta, W1, b1, W2, b2, eps: float = LN_EPS):
+    """Channel-mixing half of a mixing block (Sec. 3: layer norm before the MLP, skip connection around it):
+    Xn = layernorm(X), H = gelu(Xn W1^T + b1), Y = X + H W2^T + b2, with Xn handed on in FP32 as the
+    method stores it.  Returns a dict like mlp() plus Xn (double, before rounding)."""
+    Xn = layernorm(X, gamma, beta, ln_groups(ways), eps)
+    out = mlp(Xn.astype(np.float32), W1, b1, W2, b2, residual=False)
+    out["Y"] = out["Y"] + np.asarray(X, dtype=np.float64)
+    out["SY"] = out["SY"] + np.abs(np.asarray(X, dtype=np.float64))
+    out["Xn"] = Xn
+    return out
 
 
 # ----------------------------------------------------------------------------

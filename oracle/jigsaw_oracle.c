@@ -55,6 +55,17 @@
  *                         H = gelu(X W1^T + b1),   Y = X + H W2^T + b2,
  *                       row by row with H kept in double; also returns the magnitudes the
  *                       tolerances of the two outputs are relative to.
+ *  oracle_layernorm   : the layer norm applied before each mixing MLP (Sec. 3; Sec. 5 "Layer
+ *                       norms": over the channels of a token, PyTorch's own routine usable
+ *                       as it is with 2-way parallelism, where every rank holds half of the
+ *                       channels of every token — so each rank normalises over the channels
+ *                       it holds).  For `groups` equal, contiguous channel blocks, each token
+ *                       (row) and block on its own:
+ *                         mu = mean_c x,  var = mean_c (x - mu)^2  (biased, two passes),
+ *                         y[c] = (x[c] - mu) / sqrt(var + eps) * gamma[c] + beta[c]
+ *                       in double; groups = 1 is the unpartitioned layer, 2 the 2- and 4-way
+ *                       ones (4-way also splits the tokens, which changes nothing per token).
+ *                       Also returns the magnitude (|x| + |mu|) / sqrt(var + eps) * |gamma| + |beta|.
  *
  * Pins (see tests/test_oracle_pins.py): closed forms for identity /
  * permutation / all-ones / single-nonzero operands, exact integer brute force
@@ -71,6 +82,12 @@
  * the MLP against the pinned forward oracle applied twice, closed forms (zero first
  * layer, identity weights), and brute force in exact rationals where gelu is not
  * involved.
+ *
+ * Pins of the layer norm (tests/test_oracle_layernorm_pins.py): rows whose result is known
+ * in closed form (constant rows, +-1 rows, an arithmetic progression), the moments of the
+ * output, invariance under a shift and (up to eps) a scaling of the input, a library
+ * routine in double, independence of the channel blocks, and planted mistakes (unbiased
+ * variance, eps outside the root, statistics over the whole row) that the pins must catch.
  *
  * Layout: every matrix is dense row-major; X is M x K, W is N x K, Y is M x N
  * (transposed layer: X is T x C, W is T x D, Y is C x D; MLP: X and Y are M x C,
@@ -699,4 +716,49 @@ int oracle_mlp(const float* X, const float* W1, const float* b1, const float* W2
     if (!X || !W1 || !W2 || !H || !Y || !S1 || !SY || !PY || M < 0 || C < 0 || Hd < 0) return ORACLE_E_ARG;
     mlp_env e = {X, W1, b1, W2, b2, C, Hd, residual, H, Y, S1, SY, PY};
     return for_rows(0, M, nthreads, mlp_row, &e);
+}
+
+/* ------------------------------------------------------------------ */
+/* layer norm over the channels of a token, per channel block           */
+/* ------------------------------------------------------------------ */
+typedef struct {
+    const float *X, *gamma, *beta;
+    int64_t C, groups;
+    double eps;
+    double *Y, *S;
+} ln_env;
+
+static void ln_row(int64_t i, void* p)
+{
+    const ln_env* e = (const ln_env*)p;
+    const int64_t Cg = e->C / e->groups;
+    for (int64_t g = 0; g < e->groups; ++g) {
+        const float* x = e->X + i * e->C + g * Cg;
+        double mu = 0.0, var = 0.0;
+        for (int64_t c = 0; c < Cg; ++c) mu += (double)x[c];
+        mu /= (double)Cg;
+        for (int64_t c = 0; c < Cg; ++c) {
+            const double d = (double)x[c] - mu;
+            var += d * d;
+        }
+        var /= (double)Cg;
+        const double rstd = 1.0 / sqrt(var + e->eps);
+        for (int64_t c = 0; c < Cg; ++c) {
+            const int64_t col = g * Cg + c;
+            const double ga = e->gamma ? (double)e->gamma[col] : 1.0;
+            const double be = e->beta ? (double)e->beta[col] : 0.0;
+            e->Y[i * e->C + col] = ((double)x[c] - mu) * rstd * ga + be;
+            if (e->S) e->S[i * e->C + col] = (fabs((double)x[c]) + fabs(mu)) * rstd * fabs(ga) + fabs(be);
+        }
+    }
+}
+
+int oracle_layernorm(const float* X, const float* gamma, const float* beta, int64_t M, int64_t C,
+                     int64_t groups, double eps, double* Y, double* S, int nthreads)
+{
+    if (!X || !Y || M < 0 || C < 0 || groups < 1 || !(eps >= 0.0)) return ORACLE_E_ARG;
+    if (C % groups) return ORACLE_E_ARG;
+    if (C == 0) return ORACLE_OK;
+    ln_env e = {X, gamma, beta, C, groups, eps, Y, S};
+    return for_rows(0, M, nthreads, ln_row, &e);
 }

@@ -1,0 +1,197 @@
+"""Pins for the layer-norm oracle and the pre-norm channel-mixing block built from it (no GPU).
+
+The paper (Sec. 3; Sec. 5 "Layer norms") names the layer norm of the library it uses, over the channels
+of a token; with the channels split over ranks each rank normalises over the channels it holds.  The
+oracle is pinned by rows whose normalised form is known in closed form, by the moments of its output,
+by its invariances, by the library routine in double, by the independence of channel blocks and tokens,
+and by planted mistakes that these pins must tell apart from the right formula.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2507_05753_amd import inputs
+
+EPS = oracle.LN_EPS
+
+
+def data(seed, M, C, mode="R", shift=0.0):
+    X = inputs.matrix(seed, M, C, mode) + np.float32(shift)
+    gamma = inputs.matrix(seed + 1, 1, C, mode)[0] + np.float32(1.5)
+    beta = inputs.matrix(seed + 2, 1, C, mode)[0]
+    return X.astype(np.float32), gamma.astype(np.float32), beta.astype(np.float32)
+
+
+def test_default_eps_is_the_library_default():
+    assert EPS == torch.nn.LayerNorm(4).eps == 1e-5
+
+
+def test_constant_rows_map_to_beta():
+    # x - mean = 0 exactly, whatever the variance term is
+    C = 12
+    X = np.full((3, C), 2.75, dtype=np.float32)
+    _, gamma, beta = data(1, 3, C)
+    assert np.array_equal(oracle.layernorm(X, gamma, beta), np.tile(beta.astype(np.float64), (3, 1)))
+    assert np.array_equal(oracle.layernorm(X), np.zeros((3, C)))
+
+
+def test_plus_minus_one_rows():
+    # mean 0, variance 1: y = x / sqrt(1 + eps) * gamma + beta
+    C = 16
+    X = np.tile(np.array([1.0, -1.0], dtype=np.float32), (2, C // 2))
+    _, gamma, beta = data(2, 2, C)
+    want = X.astype(np.float64) / math.sqrt(1.0 + EPS) * gamma + beta
+    got = oracle.layernorm(X, gamma, beta)
+    assert np.allclose(got, want, rtol=0, atol=4 * np.finfo(np.float64).eps * (np.abs(want).max() + 1))
+    # eps = 0: exactly x * gamma + beta up to the last bit of the products
+    got = oracle.layernorm(X, gamma, beta, eps=0.0)
+    assert np.allclose(got, X.astype(np.float64) * gamma + beta, rtol=0, atol=1e-15)
+
+
+def test_arithmetic_progression():
+    # x = 0, 1, ..., C-1: mean (C-1)/2, biased variance (C^2 - 1)/12
+    C = 9
+    X = np.arange(C, dtype=np.float32)[None, :]
+    want = (np.arange(C) - (C - 1) / 2) / math.sqrt((C * C - 1) / 12 + EPS)
+    assert np.allclose(oracle.layernorm(X)[0], want, rtol=0, atol=1e-15)
+    # an unbiased variance (divisor C - 1) would give another number
+    wrong = (np.arange(C) - (C - 1) / 2) / math.sqrt((C * C - 1) / 12 * C / (C - 1) + EPS)
+    assert np.abs(wrong - want).max() > 1e-3
+
+
+def test_eps_sits_inside_the_root():
+    # tiny variance: eps dominates; y = d / sqrt(var + eps), not d / (sqrt(var) + eps)
+    X = np.array([[1.0, 1.0 + 2.0 ** -10]], dtype=np.float32)
+    d = 2.0 ** -11
+    want = np.array([-d, d]) / math.sqrt(d * d + EPS)
+    assert np.allclose(oracle.layernorm(X)[0], want, rtol=1e-14, atol=0)
+    outside = np.array([-d, d]) / (math.sqrt(d * d) + EPS)
+    assert np.abs(outside - want).max() > 0.1
+
+
+@pytest.mark.parametrize("M,C", [(4, 8), (7, 50), (3, 4320)])
+def test_moments_of_the_output(M, C):
+    X, _, _ = data(3, M, C, shift=0.75)
+    Y = oracle.layernorm(X)
+    assert np.all(np.abs(Y.mean(axis=1)) <= 1e-13)
+    var = X.astype(np.float64).var(axis=1)
+    assert np.allclose((Y * Y).mean(axis=1), var / (var + EPS), rtol=1e-12, atol=0)
+
+
+def test_shift_and_scale_invariance():
+    M, C = 5, 40
+    X, gamma, beta = data(4, M, C, "L")
+    base = oracle.layernorm(X, gamma, beta)
+    shifted = oracle.layernorm(X + np.float32(8.0), gamma, beta)      # lattice values: the shift is exact
+    assert np.allclose(shifted, base, rtol=0, atol=1e-13)
+    # scaling by 4 is exact in FP32; with eps scaled by 16 the result is the same
+    scaled = oracle.layernorm(X * np.float32(4.0), gamma, beta, eps=16 * EPS)
+    assert np.allclose(scaled, base, rtol=0, atol=1e-13)
+    # and with the same eps it is not (eps matters)
+    assert np.abs(oracle.layernorm(X * np.float32(4.0), gamma, beta) - base).max() > 1e-9
+
+
+@pytest.mark.parametrize("M,C", [(1, 2), (6, 10), (33, 130), (4, 4320)])
+@pytest.mark.parametrize("affine", [False, True])
+def test_library_routine_in_double(M, C, affine):
+    X, gamma, beta = data(5, M, C, shift=0.3)
+    g = torch.from_numpy(gamma).double() if affine else None
+    b = torch.from_numpy(beta).double() if affine else None
+    want = torch.nn.functional.layer_norm(torch.from_numpy(X).double(), (C,), g, b, EPS).numpy()
+    got, S = oracle.layernorm(X, gamma if affine else None, beta if affine else None, magnitude=True)
+    assert np.all(np.abs(got - want) <= 64 * np.finfo(np.float64).eps * S)
+
+
+@pytest.mark.parametrize("groups", [1, 2])
+def test_channel_blocks_and_tokens_are_independent(groups):
+    M, C = 6, 24
+    X, gamma, beta = data(6, M, C)
+    Y = oracle.layernorm(X, gamma, beta, groups)
+    Cg = C // groups
+    for g in range(groups):
+        sl = slice(g * Cg, (g + 1) * Cg)
+        assert np.array_equal(Y[:, sl], oracle.layernorm(X[:, sl], gamma[sl], beta[sl]))
+    # changing one token changes only that row; changing one block changes only that block
+    X2 = X.copy()
+    X2[2, 1] += np.float32(3.0)
+    Y2 = oracle.layernorm(X2, gamma, beta, groups)
+    changed = np.argwhere(Y2 != Y)
+    assert set(changed[:, 0]) == {2}
+    assert changed[:, 1].max() < Cg
+    if groups == 2:
+        assert not np.array_equal(Y, oracle.layernorm(X, gamma, beta, 1))     # statistics over the whole row differ
+
+
+def test_magnitude_bounds_the_output():
+    X, gamma, beta = data(7, 9, 30, shift=-2.0)
+    Y, S = oracle.layernorm(X, gamma, beta, 2, magnitude=True)
+    assert np.all(np.abs(Y) <= S * (1 + 1e-15))
+    Xd = X.astype(np.float64)
+    for g in range(2):
+        sl = slice(g * 15, (g + 1) * 15)
+        mu = Xd[:, sl].mean(axis=1, keepdims=True)
+        rstd = 1 / np.sqrt(Xd[:, sl].var(axis=1, keepdims=True) + EPS)
+        want = (np.abs(Xd[:, sl]) + np.abs(mu)) * rstd * np.abs(gamma[sl]) + np.abs(beta[sl])
+        assert np.allclose(S[:, sl], want, rtol=1e-13, atol=0)
+
+
+def test_argument_checks():
+    X, gamma, beta = data(8, 3, 9)
+    with pytest.raises(RuntimeError):
+        oracle.layernorm(X, gamma, beta, 2)          # 9 channels do not split in two
+    with pytest.raises(RuntimeError):
+        oracle.layernorm(X, gamma, beta, 0)
+    with pytest.raises(RuntimeError):
+        oracle.layernorm(X, gamma, beta, eps=-1.0)
+    assert oracle.layernorm(np.zeros((0, 8), np.float32)).shape == (0, 8)
+    assert oracle.ln_groups(1) == 1 and oracle.ln_groups(2) == 2 and oracle.ln_groups(4) == 2
+    with pytest.raises(RuntimeError):
+        oracle.ln_groups(3)
+
+
+# ---------------------------------------------------------------------------------------------
+# the pre-norm channel-mixing block: Y = X + MLP(layernorm(X))
+# ---------------------------------------------------------------------------------------------
+def block_operands(seed, M, C, Hd, mode="R"):
+    X, W1, b1 = inputs.layer_inputs(seed, M, C, Hd, mode)
+    W2 = inputs.matrix(seed + 50, C, Hd, mode, inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(seed + 51, 1, C, mode)[0]
+    _, gamma, beta = data(seed + 52, 1, C, mode)
+    return X, gamma, beta, W1, b1, W2, b2
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+def test_block_is_the_pinned_pieces_in_sequence(ways):
+    M, C, Hd = 6, 8, 10
+    X, gamma, beta, W1, b1, W2, b2 = block_operands(9, M, C, Hd)
+    out = oracle.mixing_block(ways, X, gamma, beta, W1, b1, W2, b2)
+    Xn = oracle.layernorm(X, gamma, beta, oracle.ln_groups(ways))
+    assert np.array_equal(out["Xn"], Xn)
+    H = oracle.gelu(oracle.linear(Xn.astype(np.float32), W1, b1))
+    assert np.array_equal(out["H"], H)
+    # second layer from H in double, by a library product
+    want = X.astype(np.float64) + H @ W2.astype(np.float64).T + b2
+    assert np.allclose(out["Y"], want, rtol=0, atol=1e-12 * np.abs(out["SY"]).max())
+
+
+def test_block_with_zero_second_layer_is_the_identity_plus_bias():
+    M, C, Hd = 4, 6, 8
+    X, gamma, beta, W1, b1, W2, b2 = block_operands(10, M, C, Hd)
+    out = oracle.mixing_block(2, X, gamma, beta, W1, b1, np.zeros_like(W2), b2)
+    assert np.array_equal(out["Y"], X.astype(np.float64) + b2)
+
+
+def test_block_sees_the_norm():
+    # constant rows: layernorm gives beta for every token, so Y - X is the same row for all tokens
+    M, C, Hd = 5, 6, 8
+    X, gamma, beta, W1, b1, W2, b2 = block_operands(11, M, C, Hd)
+    X = np.tile(np.arange(M, dtype=np.float32)[:, None], (1, C))
+    out = oracle.mixing_block(1, X, gamma, beta, W1, b1, W2, b2)
+    D = out["Y"] - X
+    assert np.allclose(D, np.tile(D[0], (M, 1)), rtol=0, atol=1e-13)
+    # without the norm the rows would differ
+    plain = oracle.mlp(X, W1, b1, W2, b2)["Y"] - X
+    assert np.abs(plain - plain[0]).max() > 1e-3
