@@ -31,10 +31,11 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--ways", type=int, default=4, choices=[1, 2, 4])
-    ap.add_argument("--op", choices=["forward", "backward", "xtw", "mlp", "encoder"], default="forward",
+    ap.add_argument("--op", choices=["forward", "backward", "xtw", "mlp", "mixing", "encoder"], default="forward",
                     help="forward: Y = X W^T (the headline); backward: dX = dY W and dW = dY^T X; "
                          "xtw: the transposed layer Y = X^T W at the token-mixing size; mlp: one mixing MLP "
-                         "(GELU between two layers, residual) at the channel-mixing size; encoder: patch rearrangement of a "
+                         "(GELU between two layers, residual) at the channel-mixing size; mixing: the same behind a layer norm "
+                         "(the channel-mixing half of a mixing block); encoder: patch rearrangement of a "
                          "field + linear layer at the 1B model's encoder size (these ignore --config)")
     ap.add_argument("--combine", choices=["fused", "separate"], default="fused")
     ap.add_argument("--weights", choices=["copy", "direct"], default="copy")
@@ -68,13 +69,14 @@ def make_inputs(cfg, dev):
     return X, W
 
 
-def time_forward(L, jg, steps, warmup):
-    """(seconds per step by wall clock, GEMM ms total, GEMM launches, weight-copy and combine ms per step)."""
+def time_forward(L, jg, steps, warmup, norm=None):
+    """(seconds per step by wall clock, GEMM ms total, GEMM launches, weight-copy and combine ms per step);
+    `norm`: a dict that receives the layer-norm kernel's total ms and launch count."""
     import torch
     for _ in range(warmup):
         L.forward()
     torch.cuda.synchronize()
-    for k in (jg.JG_KERNEL_GEMM, jg.JG_KERNEL_WEIGHT_COPY, jg.JG_KERNEL_COMBINE, jg.JG_KERNEL_JOIN):
+    for k in (jg.JG_KERNEL_GEMM, jg.JG_KERNEL_WEIGHT_COPY, jg.JG_KERNEL_COMBINE, jg.JG_KERNEL_JOIN, jg.JG_KERNEL_NORM):
         jg.jg_profile_read(L.ctx, k)
     jg.jg_profile(L.ctx, True)
     torch.cuda.synchronize()
@@ -88,6 +90,8 @@ def time_forward(L, jg, steps, warmup):
     wc_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_WEIGHT_COPY)
     cb_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_COMBINE)
     join_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_JOIN)   # tail join of split launches, counted with the hand-off copy
+    if norm is not None:
+        norm["ms"], norm["launches"] = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_NORM)
     return (t1 - t0) / steps, gemm_ms, gemm_n, (wc_ms + join_ms) / steps, cb_ms / steps
 
 
@@ -315,6 +319,65 @@ def measure_mlp(cfg, ways, args):
     return out
 
 
+def measure_mixing(cfg, ways, args):
+    """One step = one jg_mixing_forward: Xn = layernorm(X), H = gelu(Xn W1^T + b1), Y = X + H W2^T + b2."""
+    import torch
+    from paper_2507_05753_amd import binding as jg
+    from paper_2507_05753_amd import inputs
+    from paper_2507_05753_amd.layer import JigsawMixing
+    M, C, Hd, seed = cfg["M"], cfg["C"], cfg["Hd"], cfg["seed"]
+    dev = torch.device("cuda", 0)
+    gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device=dev)
+    with JigsawMixing(M, C, Hd, ways, tail=tail_of(args)) as L:
+        L.shard(gen(seed, M, C), (gen(seed + 5, 1, C)[0] + 1.5).contiguous(), gen(seed + 6, 1, C)[0].contiguous(),
+                gen(seed + 1, Hd, C, inputs.W_SCALE_EXP), gen(seed + 2, 1, Hd)[0].contiguous(),
+                gen(seed + 3, C, Hd, inputs.W_SCALE_EXP), gen(seed + 4, 1, C)[0].contiguous())
+        norm = {}
+        sec, gemm_ms, gemm_n, copy_ms, comb_ms = time_forward(L, jg, args.steps, args.warmup, norm)
+        flops = L.first.query(jg.JG_Q_FLOPS_TOTAL) + L.second.query(jg.JG_Q_FLOPS_TOTAL)
+        launches = L.first.query(jg.JG_Q_GEMM_LAUNCHES) + L.second.query(jg.JG_Q_GEMM_LAUNCHES)
+        avg = gemm_ms / max(gemm_n, 1)
+        norm_avg = norm["ms"] / max(norm["launches"], 1)
+        out = dict(ms_per_step=sec * 1e3, items_per_s=M * C / sec, tflops=flops / sec / 1e12,
+                   gemm_avg_launch_ms=avg, gemm_launches_timed=gemm_n,
+                   gemm_tflops=(flops / launches) / (avg * 1e-3) / 1e12 if gemm_n else None,
+                   other_kernels_ms_per_step=copy_ms + comb_ms, workspace_bytes=L.ws_bytes,
+                   norm_avg_launch_ms=norm_avg, norm_launches_timed=norm["launches"],
+                   norm_gbps=8.0 * M * C / (norm_avg * 1e-3) / 1e9 if norm["launches"] else None)
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline_mixing(cfg, seconds):
+    """The mixing-block oracle (layer norm + MLP + skip) timed on a bounded sample of tokens (rows of X)."""
+    import oracle
+    from paper_2507_05753_amd import inputs
+    M, C, Hd, seed = cfg["M"], cfg["C"], cfg["Hd"], cfg["seed"]
+    cores = min(oracle.host_threads(), 16)
+    W1 = inputs.matrix(seed + 1, Hd, C, "R", inputs.W_SCALE_EXP)
+    b1 = inputs.matrix(seed + 2, 1, Hd, "R")[0]
+    W2 = inputs.matrix(seed + 3, C, Hd, "R", inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(seed + 4, 1, C, "R")[0]
+    gamma = inputs.matrix(seed + 5, 1, C, "R")[0] + 1.5
+    beta = inputs.matrix(seed + 6, 1, C, "R")[0]
+
+    def run(rows):
+        X = inputs.matrix(seed, M, C, "R", row_begin=0, row_end=rows)
+        t0 = time.perf_counter()
+        Xn = oracle.layernorm(X, gamma, beta, 1, nthreads=cores)
+        oracle.mlp(Xn.astype("float32"), W1, b1, W2, b2, residual=False, nthreads=cores)["Y"] + X
+        return time.perf_counter() - t0
+
+    probe = min(M, 2 * cores)
+    rate = probe / max(run(probe), 1e-9)
+    rows = int(min(M, max(probe, rate * seconds)))
+    rows = min(M, max(cores, rows // cores * cores))
+    dt = run(rows)
+    return dict(value=rows * C / dt, unit="items/s", cores=cores, kind="oracle",
+                sample=f"tokens 0..{rows - 1} of X ({rows} x {C}) through the norm and both layers ({Hd} hidden), "
+                       f"{dt:.1f} s, fp64 loops")
+
+
 def cpu_baseline_mlp(cfg, seconds):
     """The MLP oracle timed on a bounded sample of tokens (rows of X)."""
     import oracle
@@ -488,6 +551,38 @@ def main():
         }
         if args.cpu_seconds > 0:
             line["cpu_baseline"] = cpu_baseline_encoder(ec, args.cpu_seconds)
+        print(json.dumps(line), flush=True)
+        return
+
+    if args.op == "mixing":
+        mc = inputs.MLP_CONFIGS["channel_mixing_1b"]
+        r = measure_mixing(mc, args.ways, args)
+        M, C, Hd = mc["M"], mc["C"], mc["Hd"]
+        line = {
+            "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
+            "value": r["items_per_s"], "unit": "items/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"channel-mixing half of a mixing block of the 1B model: Xn = layernorm(X), "
+                                   f"H = gelu(Xn W1^T + b1), Y = X + H W2^T + b2, X {M} x {C}, hidden {Hd}, "
+                                   f"{args.ways}-way Jigsaw, fp32",
+                       "n_items": M * C, "ways": args.ways, "M": M, "C": C, "Hd": Hd, "seed": mc["seed"],
+                       "x_values": "R", "op": "mixing", "tail": args.tail},
+            "tflops": r["tflops"],
+            "roofline": {"bound": "mfma", "kernel": "jg::gemm_f32_stream<false, false, false>",
+                         "achieved": r["gemm_tflops"], "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": r["gemm_tflops"] / FP32_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None,
+                         "avg_launch_ms": r["gemm_avg_launch_ms"], "launches": r["gemm_launches_timed"],
+                         "traffic": None},
+            "layernorm": {"bound": "hbm", "kernel": "jg::layernorm_rows_f32", "achieved": r["norm_gbps"],
+                          "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                          "frac": r["norm_gbps"] / HBM_PEAK_GBPS if r["norm_gbps"] else None,
+                          "avg_launch_ms": r["norm_avg_launch_ms"], "launches": r["norm_launches_timed"],
+                          "bytes_per_element": 8},
+            "other_kernels_ms_per_step": r["other_kernels_ms_per_step"],
+        }
+        if args.cpu_seconds > 0:
+            line["cpu_baseline"] = cpu_baseline_mixing(mc, args.cpu_seconds)
         print(json.dumps(line), flush=True)
         return
 

@@ -141,7 +141,8 @@ typedef enum jg_kernel {         /* kernel classes for jg_profile_read */
     JG_KERNEL_GEMM_DX = 5,       /* backward dX = dY W products                          */
     JG_KERNEL_GEMM_DW = 6,       /* backward dW = dY^T X products                        */
     JG_KERNEL_JOIN = 7,          /* adds the runs of split tail tiles (JG_TAIL_SPLIT)    */
-    JG_KERNEL_COUNT = 8
+    JG_KERNEL_NORM = 8,          /* layer norm over a rank's channels                    */
+    JG_KERNEL_COUNT = 9
 } jg_kernel;
 
 /* init.  Creates a context bound to HIP device `device` and to `hip_stream`
@@ -258,6 +259,34 @@ int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* con
                    const float* const* w1_sh, const float* const* b1_sh, const float* const* w2_sh,
                    const float* const* b2_sh, float* const* h_sh, float* const* y_sh, void* workspace,
                    size_t workspace_bytes);
+
+/* run (layer norm).  The layer norm a mixing block applies before each MLP (Sec. 3), on the shards of
+ * X.  Sec. 5 "Layer norms": the norm runs over the channels of a token and, with the channels split
+ * over ranks, the library routine is applied as it is — every rank normalises over the channels it
+ * holds.  Per row of X_r (xr x xc, the plan's JG_T_X partition; channels = columns of X, for both ops):
+ *     mu = mean_c x[c],   var = mean_c (x[c] - mu)^2   (biased),
+ *     out[c] = (x[c] - mu) / sqrt(var + eps) * gamma[c0 + c] + beta[c0 + c],
+ * c0 = first global channel of the rank's block.  gamma, beta: device vectors over ALL channels of X
+ * (length = JG_T_X partition width; each rank reads its own slice; read only), either may be NULL
+ * (scale 1, offset 0).  eps >= 0; the library's default is 1e-5.  out_sh: `ways` device buffers shaped
+ * like X_r; out_sh[r] may be x_sh[r] (in place), other overlaps are not allowed.  Sums and the
+ * normalisation are evaluated in double and rounded once.  Needs no workspace; asynchronous on the
+ * context's stream.
+ * Errors: JG_E_NULL, JG_E_DTYPE (eps negative or NaN), JG_E_ALIGN, JG_E_HIP. */
+int jg_layernorm_forward(const jg_plan* plan, const float* const* x_sh, const float* gamma, const float* beta,
+                         double eps, float* const* out_sh);
+
+/* run (mixing block).  The channel-mixing half of a mixing block (Sec. 3: layer norm before the MLP,
+ * skip connection around it) on Jigsaw shards:
+ *     Xn = layernorm(X),   H = gelu(Xn W1^T + b1),   Y = X + H W2^T + b2.
+ * Plans, weights, h_sh, y_sh and workspace as in jg_mlp_forward; gamma, beta, eps as in
+ * jg_layernorm_forward; xn_sh: `ways` device buffers shaped like X_r that receive Xn (kept: a backward
+ * pass would need it); they must not overlap x_sh, which the skip connection still reads.
+ * Errors: those of jg_mlp_forward and jg_layernorm_forward. */
+int jg_mixing_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* gamma,
+                      const float* beta, double eps, const float* const* w1_sh, const float* const* b1_sh,
+                      const float* const* w2_sh, const float* const* b2_sh, float* const* xn_sh,
+                      float* const* h_sh, float* const* y_sh, void* workspace, size_t workspace_bytes);
 
 /* run (backward).  Gradients of the same layer for an incoming gradient dY (partitioned like Y):
  *     dX = dY W      (M x K, partitioned like X)       dW = dY^T X    (N x K, partitioned like W)

@@ -42,11 +42,13 @@ JG_T_X, JG_T_W, JG_T_B, JG_T_Y = 0, 1, 2, 3
  JG_Q_BACKWARD_WORKSPACE_BYTES, JG_Q_BACKWARD_FLOPS_TOTAL, JG_Q_BACKWARD_GEMM_LAUNCHES,
  JG_Q_TAIL_SCRATCH_BYTES, JG_Q_BACKWARD_TAIL_SCRATCH_BYTES) = range(19)
 (JG_KERNEL_GEMM, JG_KERNEL_WEIGHT_COPY, JG_KERNEL_COMBINE, JG_KERNEL_SHARD,
- JG_KERNEL_GATHER, JG_KERNEL_GEMM_DX, JG_KERNEL_GEMM_DW, JG_KERNEL_JOIN, JG_KERNEL_COUNT) = range(9)
+ JG_KERNEL_GATHER, JG_KERNEL_GEMM_DX, JG_KERNEL_GEMM_DW, JG_KERNEL_JOIN, JG_KERNEL_NORM,
+ JG_KERNEL_COUNT) = range(10)
 
 EXPORTS = ("jg_init", "jg_free", "jg_plan_create", "jg_plan_destroy", "jg_plan_query", "jg_shard",
            "jg_shard_patches", "jg_gather_patches",
-           "jg_linear_forward", "jg_linear_forward_ex", "jg_mlp_forward", "jg_linear_backward", "jg_gather", "jg_gather_as", "jg_profile", "jg_profile_read", "jg_strerror",
+           "jg_linear_forward", "jg_linear_forward_ex", "jg_mlp_forward", "jg_layernorm_forward",
+           "jg_mixing_forward", "jg_linear_backward", "jg_gather", "jg_gather_as", "jg_profile", "jg_profile_read", "jg_strerror",
            "jg_last_hip_error")
 
 
@@ -87,6 +89,9 @@ _lib.jg_gather_patches.restype = ctypes.c_int
 _lib.jg_linear_forward.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
 _lib.jg_linear_forward_ex.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, ctypes.c_int, _vpp, _vp, ctypes.c_size_t]
 _lib.jg_mlp_forward.argtypes = [_vp, _vp, _vpp, _vpp, _vpp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
+_lib.jg_layernorm_forward.argtypes = [_vp, _vpp, _vp, _vp, ctypes.c_double, _vpp]
+_lib.jg_mixing_forward.argtypes = [_vp, _vp, _vpp, _vp, _vp, ctypes.c_double, _vpp, _vpp, _vpp, _vpp, _vpp, _vpp, _vpp,
+                                   _vp, ctypes.c_size_t]
 _lib.jg_linear_backward.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
 _lib.jg_gather.argtypes = [_vp, _vpp, _vp, ctypes.c_int64]
 _lib.jg_gather_as.argtypes = [_vp, ctypes.c_int, _vpp, _vp, ctypes.c_int64]
@@ -94,7 +99,7 @@ _lib.jg_profile.argtypes = [_vp, ctypes.c_int]
 _lib.jg_profile_read.argtypes = [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                  ctypes.POINTER(ctypes.c_int64)]
 for _n in ("jg_init", "jg_plan_create", "jg_plan_query", "jg_shard", "jg_linear_forward", "jg_linear_forward_ex",
-           "jg_mlp_forward", "jg_linear_backward",
+           "jg_mlp_forward", "jg_layernorm_forward", "jg_mixing_forward", "jg_linear_backward",
            "jg_gather", "jg_gather_as", "jg_profile", "jg_profile_read"):
     getattr(_lib, _n).restype = ctypes.c_int
 
@@ -178,6 +183,19 @@ def jg_mlp_forward(first, second, x_ptrs, w1_ptrs, b1_ptrs, w2_ptrs, b2_ptrs, h_
     _raise(_lib.jg_mlp_forward(first, second, _ptr_array(x_ptrs), _ptr_array(w1_ptrs), _ptr_array(b1_ptrs),
                                _ptr_array(w2_ptrs), _ptr_array(b2_ptrs), _ptr_array(h_ptrs), _ptr_array(y_ptrs),
                                workspace_ptr or None, workspace_bytes), "jg_mlp_forward")
+
+
+def jg_layernorm_forward(plan, x_ptrs, gamma_ptr, beta_ptr, eps: float, out_ptrs) -> None:
+    _raise(_lib.jg_layernorm_forward(plan, _ptr_array(x_ptrs), gamma_ptr or None, beta_ptr or None, float(eps),
+                                     _ptr_array(out_ptrs)), "jg_layernorm_forward")
+
+
+def jg_mixing_forward(first, second, x_ptrs, gamma_ptr, beta_ptr, eps: float, w1_ptrs, b1_ptrs, w2_ptrs, b2_ptrs,
+                      xn_ptrs, h_ptrs, y_ptrs, workspace_ptr, workspace_bytes: int) -> None:
+    _raise(_lib.jg_mixing_forward(first, second, _ptr_array(x_ptrs), gamma_ptr or None, beta_ptr or None, float(eps),
+                                  _ptr_array(w1_ptrs), _ptr_array(b1_ptrs), _ptr_array(w2_ptrs), _ptr_array(b2_ptrs),
+                                  _ptr_array(xn_ptrs), _ptr_array(h_ptrs), _ptr_array(y_ptrs),
+                                  workspace_ptr or None, workspace_bytes), "jg_mixing_forward")
 
 
 def jg_linear_backward(plan, x_ptrs, w_ptrs, dy_ptrs, dx_ptrs, dw_ptrs, workspace_ptr, workspace_bytes: int) -> None:

@@ -13,6 +13,7 @@
 #include "gemm_f32.hpp"
 #include "stream_kernels.hpp"
 #include "patch_kernels.hpp"
+#include "norm_kernels.hpp"
 
 namespace {
 
@@ -866,19 +867,67 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
     return launch(jg::kGemmTN, JG_KERNEL_GEMM_DW) ? JG_OK : JG_E_HIP;
 }
 
-int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh,
-                   const float* const* w1_sh, const float* const* b1_sh, const float* const* w2_sh,
-                   const float* const* b2_sh, float* const* h_sh, float* const* y_sh, void* workspace,
-                   size_t workspace_bytes)
+int jg_layernorm_forward(const jg_plan* plan, const float* const* x_sh, const float* gamma, const float* beta,
+                         double eps, float* const* out_sh)
+{
+    if (!plan || !plan->ctx) return JG_E_NULL;
+    const jg_linear_desc& d = plan->d;
+    if (int rc = check_ptr_array(x_sh, d.ways)) return rc;
+    if (int rc = check_ptr_array(out_sh, d.ways)) return rc;
+    if (!(eps >= 0.0)) return JG_E_DTYPE;
+    if (!aligned(gamma, 4) || !aligned(beta, 4)) return JG_E_ALIGN;
+    for (int r = 0; r < d.ways; ++r)
+        if (!aligned(x_sh[r], 4) || !aligned(out_sh[r], 4)) return JG_E_ALIGN;
+    jg_ctx* c = plan->ctx;
+    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    jg::NormGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.nblocks = d.ways;
+    g.rows = (int)plan->xr;
+    g.cols = (int)plan->xc;
+    g.eps = eps;
+    for (int r = 0; r < d.ways; ++r) {
+        int64_t rb, cb;
+        block_coords(d.ways, r, &rb, &cb);     // the channels are the columns of X: block cb of them
+        g.b[r] = {x_sh[r], out_sh[r], gamma ? gamma + cb * plan->xc : nullptr, beta ? beta + cb * plan->xc : nullptr};
+    }
+    ScopedTimer t(c, JG_KERNEL_NORM);
+    return HIP_OK(jg::launch_norm_group(g, c->stream)) ? JG_OK : JG_E_HIP;
+}
+
+// X [M x C] -> H [M x Hd] -> Y [M x C]: the second layer maps back to the first one's input width
+static int check_mlp_chain(const jg_plan* first, const jg_plan* second)
 {
     if (!first || !second) return JG_E_NULL;
     const jg_linear_desc &a = first->d, &b = second->d;
     if (a.op != JG_OP_XWT || b.op != JG_OP_XWT) return JG_E_DTYPE;
     if (a.ways != b.ways) return JG_E_WAYS;
-    // X [M x C] -> H [M x Hd] -> Y [M x C]: the second layer maps back to the first one's input width
     if (a.M != b.M || a.N != b.K || b.N != a.K) return JG_E_SHAPE;
     if (first->ctx != second->ctx) return JG_E_NULL;
-    if (int rc = check_ptr_array(h_sh, a.ways)) return rc;
+    return JG_OK;
+}
+
+int jg_mixing_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* gamma,
+                      const float* beta, double eps, const float* const* w1_sh, const float* const* b1_sh,
+                      const float* const* w2_sh, const float* const* b2_sh, float* const* xn_sh,
+                      float* const* h_sh, float* const* y_sh, void* workspace, size_t workspace_bytes)
+{
+    if (int rc = check_mlp_chain(first, second)) return rc;
+    if (int rc = check_ptr_array(h_sh, first->d.ways)) return rc;
+    int rc = jg_layernorm_forward(first, x_sh, gamma, beta, eps, xn_sh);
+    if (rc != JG_OK) return rc;
+    rc = jg_linear_forward_ex(first, xn_sh, w1_sh, b1_sh, nullptr, JG_ACT_GELU, h_sh, workspace, workspace_bytes);
+    if (rc != JG_OK) return rc;
+    return jg_linear_forward_ex(second, h_sh, w2_sh, b2_sh, x_sh, JG_ACT_NONE, y_sh, workspace, workspace_bytes);
+}
+
+int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh,
+                   const float* const* w1_sh, const float* const* b1_sh, const float* const* w2_sh,
+                   const float* const* b2_sh, float* const* h_sh, float* const* y_sh, void* workspace,
+                   size_t workspace_bytes)
+{
+    if (int rc = check_mlp_chain(first, second)) return rc;
+    if (int rc = check_ptr_array(h_sh, first->d.ways)) return rc;
     // H_r is written by the first layer in the partition the second one reads its input in
     int rc = jg_linear_forward_ex(first, x_sh, w1_sh, b1_sh, nullptr, JG_ACT_GELU, h_sh, workspace, workspace_bytes);
     if (rc != JG_OK) return rc;

@@ -1,0 +1,177 @@
+// Layer norm over the channels a rank holds of each token (Sec. 3: a layer norm before each mixing
+// MLP; Sec. 5 "Layer norms": the library routine applied to the rank's own channels):
+//     mu = mean_c x,  var = mean_c (x - mu)^2,  y[c] = (x[c] - mu) / sqrt(var + eps) * gamma[c] + beta[c]
+// per row of a rank's activation block.
+//
+// HBM-bound: every element is read once and written once.  One wavefront owns one row and keeps it
+// in registers (NV 16-byte vectors per lane) between the reduction and the normalisation, so the row
+// is not read a second time; the two reductions (sum, then sum of squared deviations) and the
+// normalisation run in double, which this chip does at half the FP32 rate — far below the time the
+// memory traffic takes — and leaves the result within one FP32 rounding of the exact value.  Rows that do not fit
+// the register budget, or whose length or alignment rules out 128-bit accesses, take a plain
+// kernel (one workgroup per row, three passes, the second and third served by the caches).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "stream_kernels.hpp"
+
+namespace jg {
+
+struct NormBlock {
+    const float* x;      // rows x cols, dense
+    float* y;            // rows x cols, dense; may be x itself
+    const float* gamma;  // the block's cols scale factors, or nullptr (1)
+    const float* beta;   // the block's cols offsets, or nullptr (0)
+};
+
+struct NormGroup {
+    NormBlock b[kMaxBlocks];
+    int nblocks;
+    int rows, cols;      // common shape
+    double eps;
+};
+
+constexpr int NORM_THREADS = 256;
+constexpr int NORM_ROWS_PER_WG = NORM_THREADS / 64;
+constexpr int kNormMaxVectorsPerLane = 32;     // register-resident rows: up to 64 * 32 * 4 = 8192 columns
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// grid: x = row / NORM_ROWS_PER_WG, y = block.  cols is a multiple of 4, cols / 4 <= 64 * NV.
+template <int NV>
+__global__ __launch_bounds__(NORM_THREADS) void layernorm_rows_f32(const NormGroup g)
+{
+    const NormBlock& B = g.b[blockIdx.y];
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * NORM_ROWS_PER_WG + (threadIdx.x >> 6);
+    if (row >= g.rows) return;       // whole wavefronts leave; no barrier below
+    const int nvec = g.cols >> 2;
+    const vf4* x = reinterpret_cast<const vf4*>(B.x + (int64_t)row * g.cols);
+    vf4 v[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = i * 64 + lane;
+        v[i] = c < nvec ? x[c] : vf4{0.f, 0.f, 0.f, 0.f};
+    }
+    double s = 0.0;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) s += ((double)v[i].x + (double)v[i].y) + ((double)v[i].z + (double)v[i].w);
+    const double mu = wave_sum(s) / (double)g.cols;
+    // The row stays in registers as FP32; each pass widens it again (keeping the widened copies would
+    // triple the register count and halve the number of rows in flight).
+#pragma unroll
+    for (int i = 0; i < NV; ++i) asm volatile("" : "+v"(v[i]));
+    double q = 0.0;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        if (i * 64 + lane < nvec) {
+            const double dx = (double)v[i].x - mu, dy = (double)v[i].y - mu;
+            const double dz = (double)v[i].z - mu, dw = (double)v[i].w - mu;
+            q += (dx * dx + dy * dy) + (dz * dz + dw * dw);
+        }
+    }
+    const double rstd = 1.0 / sqrt(wave_sum(q) / (double)g.cols + g.eps);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) asm volatile("" : "+v"(v[i]));
+    vf4* y = reinterpret_cast<vf4*>(B.y + (int64_t)row * g.cols);
+    const vf4* gamma = reinterpret_cast<const vf4*>(B.gamma);
+    const vf4* beta = reinterpret_cast<const vf4*>(B.beta);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = i * 64 + lane;
+        if (c < nvec) {
+            const vf4 ga = gamma ? gamma[c] : vf4{1.f, 1.f, 1.f, 1.f};
+            const vf4 be = beta ? beta[c] : vf4{0.f, 0.f, 0.f, 0.f};
+            vf4 o;
+            o.x = (float)(((double)v[i].x - mu) * rstd * (double)ga.x + (double)be.x);
+            o.y = (float)(((double)v[i].y - mu) * rstd * (double)ga.y + (double)be.y);
+            o.z = (float)(((double)v[i].z - mu) * rstd * (double)ga.z + (double)be.z);
+            o.w = (float)(((double)v[i].w - mu) * rstd * (double)ga.w + (double)be.w);
+            y[c] = o;
+        }
+    }
+}
+
+// Any row length and alignment.  grid: x = row, y = block.
+__global__ __launch_bounds__(NORM_THREADS) void layernorm_generic_f32(const NormGroup g)
+{
+    __shared__ double part[NORM_THREADS / 64];
+    const NormBlock& B = g.b[blockIdx.y];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* x = B.x + (int64_t)blockIdx.x * g.cols;
+    float* y = B.y + (int64_t)blockIdx.x * g.cols;
+
+    auto block_sum = [&](double v) {
+        v = wave_sum(v);
+        __syncthreads();             // the previous sum has been read by every wavefront
+        if (lane == 0) part[wave] = v;
+        __syncthreads();
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < NORM_THREADS / 64; ++w) t += part[w];
+        return t;
+    };
+
+    double s = 0.0;
+    for (int c = tid; c < g.cols; c += NORM_THREADS) s += (double)x[c];
+    const double mu = block_sum(s) / (double)g.cols;
+    double q = 0.0;
+    for (int c = tid; c < g.cols; c += NORM_THREADS) {
+        const double d = (double)x[c] - mu;
+        q += d * d;
+    }
+    const double rstd = 1.0 / sqrt(block_sum(q) / (double)g.cols + g.eps);
+    // every element is read for the last time by the thread that overwrites it: y may be x
+    for (int c = tid; c < g.cols; c += NORM_THREADS) {
+        const double ga = B.gamma ? (double)B.gamma[c] : 1.0;
+        const double be = B.beta ? (double)B.beta[c] : 0.0;
+        y[c] = (float)(((double)x[c] - mu) * rstd * ga + be);
+    }
+}
+
+template <int NV>
+inline void launch_norm_rows(const NormGroup& g, hipStream_t stream)
+{
+    dim3 grid((g.rows + NORM_ROWS_PER_WG - 1) / NORM_ROWS_PER_WG, g.nblocks, 1);
+    hipLaunchKernelGGL((layernorm_rows_f32<NV>), grid, dim3(NORM_THREADS), 0, stream, g);
+}
+
+// True when the register-resident kernel can take the group.
+inline bool norm_rows_fit(const NormGroup& g)
+{
+    if ((g.cols & 3) || g.cols / 4 > 64 * kNormMaxVectorsPerLane) return false;
+    for (int i = 0; i < g.nblocks; ++i) {
+        const NormBlock& b = g.b[i];
+        if (((uintptr_t)b.x & 15) || ((uintptr_t)b.y & 15) || ((uintptr_t)b.gamma & 15) || ((uintptr_t)b.beta & 15))
+            return false;
+    }
+    return true;
+}
+
+inline hipError_t launch_norm_group(const NormGroup& g, hipStream_t stream)
+{
+    if (g.rows <= 0 || g.cols <= 0 || g.nblocks <= 0) return hipSuccess;
+    if (norm_rows_fit(g)) {
+        const int need = (g.cols / 4 + 63) / 64;      // vectors per lane
+        if (need <= 1) launch_norm_rows<1>(g, stream);
+        else if (need <= 2) launch_norm_rows<2>(g, stream);
+        else if (need <= 4) launch_norm_rows<4>(g, stream);
+        else if (need <= 6) launch_norm_rows<6>(g, stream);
+        else if (need <= 9) launch_norm_rows<9>(g, stream);
+        else if (need <= 12) launch_norm_rows<12>(g, stream);
+        else if (need <= 17) launch_norm_rows<17>(g, stream);
+        else if (need <= 24) launch_norm_rows<24>(g, stream);
+        else launch_norm_rows<32>(g, stream);
+    } else {
+        hipLaunchKernelGGL(layernorm_generic_f32, dim3(g.rows, g.nblocks, 1), dim3(NORM_THREADS), 0, stream, g);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace jg

@@ -82,6 +82,20 @@ class JigsawLinear:
                                 [t.data_ptr() for t in self.y],
                                 self.ws.data_ptr() if self.ws_bytes else None, self.ws_bytes)
 
+    def layernorm(self, gamma=None, beta=None, eps: float = 1e-5, out=None):
+        """Layer norm of the X shards over each rank's channels (jg_layernorm_forward); ``gamma`` / ``beta``
+        are device vectors over all channels of X.  Writes ``out`` (per-rank tensors shaped like the X
+        shards; default: in place) and returns it."""
+        C = self.x_shape[1]
+        for v in (gamma, beta):
+            assert v is None or (v.is_cuda and v.dtype == torch.float32 and v.shape == (C,) and v.is_contiguous())
+        out = self.x if out is None else out
+        assert len(out) == self.ways and all(o.shape == x.shape and o.is_contiguous() for o, x in zip(out, self.x))
+        jg.jg_layernorm_forward(self.plan, [t.data_ptr() for t in self.x],
+                                gamma.data_ptr() if gamma is not None else None,
+                                beta.data_ptr() if beta is not None else None, eps, [t.data_ptr() for t in out])
+        return out
+
     def gather(self, out=None):
         if out is None:
             out = torch.empty((self.M, self.N), dtype=torch.float32, device=self.dev)
@@ -180,3 +194,34 @@ class JigsawMLP:
 
     def __exit__(self, *exc):
         self.close()
+
+
+class JigsawMixing(JigsawMLP):
+    """Channel-mixing half of a mixing block: Xn = layernorm(X), H = gelu(Xn W1^T + b1), Y = X + H W2^T + b2
+    (``jg_mixing_forward``).  ``gamma`` / ``beta``: device vectors of length C."""
+
+    def __init__(self, M: int, C: int, Hd: int, ways: int, device: int = 0, ctx=None, tail: int = jg.JG_TAIL_SPLIT,
+                 eps: float = 1e-5):
+        super().__init__(M, C, Hd, ways, device=device, ctx=ctx, tail=tail)
+        self.eps = eps
+        self.xn = [torch.empty_like(t) for t in self.first.x]
+        self.gamma = self.beta = None
+
+    def shard(self, X=None, gamma=None, beta=None, W1=None, b1=None, W2=None, b2=None):
+        super().shard(X, W1, b1, W2, b2)
+        for v in (gamma, beta):
+            assert v is None or (v.is_cuda and v.dtype == torch.float32 and v.shape == (self.C,) and v.is_contiguous())
+        self.gamma, self.beta = gamma, beta
+
+    def forward(self):
+        f, s = self.first, self.second
+        p = lambda ts: [t.data_ptr() for t in ts]
+        jg.jg_mixing_forward(f.plan, s.plan, p(f.x), self.gamma.data_ptr() if self.gamma is not None else None,
+                             self.beta.data_ptr() if self.beta is not None else None, self.eps, p(f.w), p(f.b),
+                             p(s.w), p(s.b), p(self.xn), p(f.y), p(s.y),
+                             self.ws.data_ptr() if self.ws_bytes else None, self.ws_bytes)
+
+    def gather_xn(self):
+        out = torch.empty((self.M, self.C), dtype=torch.float32, device=self.first.dev)
+        jg.jg_gather_as(self.first.plan, jg.JG_T_X, [t.data_ptr() for t in self.xn], out.data_ptr(), out.stride(0))
+        return out

@@ -266,6 +266,23 @@ def test_mlp_entry_point_checks_that_the_plans_chain():
     jg.jg_plan_destroy(a)
 
 
+def test_mixing_and_layernorm_entry_points_check_their_arguments():
+    lib = jg.raw()
+    arr = (ctypes.c_void_p * 2)(256, 512)
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    mix = lambda a, b: lib.jg_mixing_forward(a, b, pp, None, None, 1e-5, pp, pp, pp, pp, pp, pp, pp, 256, 1 << 20)
+    a = jg.jg_plan_create(None, 64, 32, 48, 2, True)
+    assert mix(None, a) == jg.JG_E_NULL
+    for (M, K, N), ways, want in (((64, 48, 30), 2, jg.JG_E_SHAPE), ((64, 48, 32), 4, jg.JG_E_WAYS),
+                                  ((64, 48, 32), 2, jg.JG_E_NULL)):      # chains, but no context
+        b = jg.jg_plan_create(None, M, K, N, ways, True)
+        assert mix(a, b) == want
+        jg.jg_plan_destroy(b)
+    assert lib.jg_layernorm_forward(None, pp, None, None, 1e-5, pp) == jg.JG_E_NULL
+    assert lib.jg_layernorm_forward(a, pp, None, None, 1e-5, pp) == jg.JG_E_NULL     # a plan without a context
+    jg.jg_plan_destroy(a)
+
+
 def test_patch_calls_check_sizes_against_the_plan():
     lib = jg.raw()
     arr = (ctypes.c_void_p * 2)(256, 512)

@@ -1,0 +1,250 @@
+"""GPU parity of the layer norm over a rank's channels and of the pre-norm channel-mixing block.
+
+Bar for the norm: the kernel evaluates sums and the normalisation in double and rounds once, so
+|out - out64| <= half an FP32 unit in the last place of out64 plus 1e-12 of the magnitude
+S = (|x| + |mu|) / sqrt(var + eps) * |gamma| + |beta| (for the different order of the double sums) — far inside
+the 1e-6 * S asked of floating-point results, which is asserted too.  Rows whose result is known in closed
+form must come out exactly.  The block: as for the MLP, with one FP32 rounding of Xn more in front of it.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2507_05753_amd import inputs
+
+pytestmark = pytest.mark.gpu
+HALF_ULP = 2.0 ** -24
+TOL = 1e-6
+TOL_H = 1.5e-6 + 2.0 ** -23
+
+
+@pytest.fixture(scope="module")
+def jg():
+    from paper_2507_05753_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ctx(jg):
+    c = jg.jg_init(0, torch.cuda.current_stream().cuda_stream)
+    yield c
+    torch.cuda.synchronize()
+    jg.jg_free(c)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def affine(seed, C, mode="R"):
+    gamma = (inputs.matrix(seed, 1, C, mode)[0] + np.float32(1.5)).astype(np.float32)
+    beta = inputs.matrix(seed + 1, 1, C, mode)[0].astype(np.float32)
+    return gamma, beta
+
+
+def run_norm(jg, ctx, X, gamma, beta, ways, eps=oracle.LN_EPS, op=0, in_place=False):
+    """shard X -> jg_layernorm_forward -> gather like X.  X is (rows = tokens, cols = channels)."""
+    from paper_2507_05753_amd.layer import JigsawLinear
+    T, C = X.shape
+    M, K = (C, T) if op == jg.JG_OP_XTW else (T, C)
+    with JigsawLinear(M, K, 8, ways, ctx=ctx, op=op) as L:
+        Xd = dev(X)
+        L.shard(Xd)
+        before = [t.clone() for t in L.x]
+        out = None if in_place else [torch.full_like(t, float("nan")) for t in L.x]
+        res = L.layernorm(dev(gamma) if gamma is not None else None, dev(beta) if beta is not None else None,
+                          eps, out)
+        full = torch.empty((T, C), dtype=torch.float32, device="cuda")
+        jg.jg_gather_as(L.plan, jg.JG_T_X, [t.data_ptr() for t in res], full.data_ptr(), C)
+        torch.cuda.synchronize()
+        if not in_place:
+            assert all(torch.equal(a, b) for a, b in zip(before, L.x))       # the input is left alone
+        return full.cpu().numpy()
+
+
+def check(got, X, gamma, beta, ways, eps=oracle.LN_EPS):
+    want, S = oracle.layernorm(X, gamma, beta, oracle.ln_groups(ways), eps, magnitude=True)
+    err = np.abs(got.astype(np.float64) - want)
+    bound = HALF_ULP * np.abs(want) * (1 + 1e-6) + 1e-12 * S + 1e-45
+    assert np.all(err <= bound), f"max err/bound = {(err / bound).max():.3f}"
+    assert np.all(err <= TOL * S)
+
+
+# (tokens, channels): register-resident rows of several widths, a ragged last vector chunk, row counts
+# that do not fill a workgroup, widths that are no multiple of 4 (4-way: of 8) and one past the register
+# budget (plain kernel)
+SHAPES = [(4, 8), (2, 2), (37, 256), (130, 520), (33, 1032), (18, 4320), (6, 8640), (50, 100), (21, 250),
+          (6, 16392), (4, 33000)]
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("T,C", SHAPES)
+def test_layernorm_matches_oracle(jg, ctx, ways, T, C):
+    if ways == 4 and T % 2:
+        T += 1
+    X = (inputs.matrix(71, T, C, "R") + np.float32(0.4)).astype(np.float32)
+    gamma, beta = affine(72, C)
+    check(run_norm(jg, ctx, X, gamma, beta, ways), X, gamma, beta, ways)
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("use_gamma,use_beta", [(False, False), (True, False), (False, True)])
+def test_optional_scale_and_offset(jg, ctx, ways, use_gamma, use_beta):
+    T, C = 10, 520
+    X = inputs.matrix(73, T, C, "R")
+    gamma, beta = affine(74, C)
+    gamma, beta = (gamma if use_gamma else None), (beta if use_beta else None)
+    check(run_norm(jg, ctx, X, gamma, beta, ways), X, gamma, beta, ways)
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("T,C", [(12, 264), (6, 250), (4, 16392)])
+def test_in_place_and_eps(jg, ctx, ways, T, C):
+    X = inputs.matrix(75, T, C, "R")
+    gamma, beta = affine(76, C)
+    out = run_norm(jg, ctx, X, gamma, beta, ways, in_place=True)
+    assert np.array_equal(out, run_norm(jg, ctx, X, gamma, beta, ways))
+    for eps in (0.0, 1e-3, 0.5):
+        check(run_norm(jg, ctx, X, gamma, beta, ways, eps=eps), X, gamma, beta, ways, eps)
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+def test_transposed_layer_plans_norm_the_same_axis(jg, ctx, ways):
+    # X of the transposed layer is [tokens, channels] as well: rows are tokens
+    T, C = 20, 264
+    X = inputs.matrix(77, T, C, "R")
+    gamma, beta = affine(78, C)
+    got = run_norm(jg, ctx, X, gamma, beta, ways, op=jg.JG_OP_XTW)
+    check(got, X, gamma, beta, ways)
+    assert np.array_equal(got, run_norm(jg, ctx, X, gamma, beta, ways))
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("C", [264, 252, 250])
+def test_closed_forms_are_exact(jg, ctx, ways, C):
+    T = 8
+    if (C // oracle.ln_groups(ways)) % 2:
+        pytest.skip("a channel block of odd width has no +-1 row of mean zero")
+    gamma, beta = affine(79, C, "L")
+    # constant rows: x - mean is exactly zero, the result is beta
+    X = np.tile(np.arange(1, T + 1, dtype=np.float32)[:, None] * np.float32(0.25), (1, C))
+    assert np.array_equal(run_norm(jg, ctx, X, gamma, beta, ways), np.tile(beta, (T, 1)))
+    # +-1 in every channel block, eps = 0: mean 0, variance 1, result x * gamma + beta (exact on the lattice)
+    X = np.tile(np.array([1.0, -1.0], dtype=np.float32), (T, C // 2))
+    want = X.astype(np.float64) * gamma + beta
+    assert np.array_equal(run_norm(jg, ctx, X, gamma, beta, ways, eps=0.0).astype(np.float64), want)
+
+
+def test_large_offset_rows_keep_their_accuracy(jg, ctx):
+    # mean 1000 times the spread: a single-precision mean or a one-pass variance would lose the result
+    T, C = 16, 4320
+    X = (inputs.matrix(80, T, C, "R") + np.float32(1000.0)).astype(np.float32)
+    gamma, beta = affine(81, C)
+    for ways in (1, 2):
+        check(run_norm(jg, ctx, X, gamma, beta, ways), X, gamma, beta, ways)
+
+
+def test_argument_checks(jg, ctx):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    with JigsawLinear(8, 8, 8, 2, ctx=ctx) as L:
+        ptrs = [t.data_ptr() for t in L.x]
+        for eps in (-1.0, float("nan")):
+            with pytest.raises(jg.JigsawError) as e:
+                jg.jg_layernorm_forward(L.plan, ptrs, None, None, eps, ptrs)
+            assert e.value.status == jg.JG_E_DTYPE
+        with pytest.raises(jg.JigsawError) as e:
+            jg.jg_layernorm_forward(L.plan, [ptrs[0], 0], None, None, 1e-5, ptrs)
+        assert e.value.status == jg.JG_E_NULL
+        with pytest.raises(jg.JigsawError) as e:
+            jg.jg_layernorm_forward(L.plan, ptrs, L.x[0].data_ptr() + 2, None, 1e-5, ptrs)
+        assert e.value.status == jg.JG_E_ALIGN
+
+
+# ---------------------------------------------------------------------------------------------
+# the channel-mixing half of a mixing block
+# ---------------------------------------------------------------------------------------------
+def block_operands(seed, M, C, Hd):
+    X = (inputs.matrix(seed, M, C, "R") + np.float32(0.25)).astype(np.float32)
+    W1 = inputs.matrix(seed + 1, Hd, C, "R", inputs.W_SCALE_EXP)
+    b1 = inputs.matrix(seed + 2, 1, Hd, "R")[0]
+    W2 = inputs.matrix(seed + 3, C, Hd, "R", inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(seed + 4, 1, C, "R")[0]
+    gamma, beta = affine(seed + 5, C)
+    return X, gamma, beta, W1, b1, W2, b2
+
+
+def check_block(r, Xn, H, Y):
+    want = r["Xn"]
+    assert np.all(np.abs(Xn.astype(np.float64) - want) <= HALF_ULP * np.abs(want) * (1 + 1e-6) + 1e-10)
+    eh = np.abs(H.astype(np.float64) - r["H"])
+    assert np.all(eh <= TOL_H * r["S1"]), f"H: max err/S1 = {(eh / r['S1']).max():.3e}"
+    ey = np.abs(Y.astype(np.float64) - r["Y"])
+    bound = TOL * r["SY"] + TOL_H * r["PY"]
+    assert np.all(ey <= bound), f"Y: max err/bound = {(ey / bound).max():.3e}"
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,C,Hd", [(100, 100, 100), (130, 72, 258), (258, 264, 136), (300, 520, 1032)])
+def test_mixing_forward(jg, ctx, ways, M, C, Hd):
+    from paper_2507_05753_amd.layer import JigsawMixing
+    X, gamma, beta, W1, b1, W2, b2 = block_operands(90, M, C, Hd)
+    with JigsawMixing(M, C, Hd, ways, ctx=ctx) as L:
+        Xd = dev(X)
+        L.shard(Xd, dev(gamma), dev(beta), dev(W1), dev(b1), dev(W2), dev(b2))
+        L.forward()
+        Xn, H, Y = L.gather_xn().cpu().numpy(), L.gather_h().cpu().numpy(), L.gather().cpu().numpy()
+        L.forward()                                   # the input shards were not overwritten: the same again
+        assert np.array_equal(Y, L.gather().cpu().numpy())
+    check_block(oracle.mixing_block(ways, X, gamma, beta, W1, b1, W2, b2), Xn, H, Y)
+    # the norm matters: the plain MLP of the same operands is far away
+    assert np.abs(Y - oracle.mlp(X, W1, b1, W2, b2)["Y"]).max() > 1e-2
+
+
+def note(capsys, msg):
+    with capsys.disabled():
+        print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
+
+
+@pytest.mark.timeout(600)
+def test_channel_mixing_size(jg, capsys):
+    """The channel-mixing block of the paper's 1-billion-parameter model (Sec. 6.2.1) at full size: the norm
+    on every element of sampled rows and on all rows through its moments, the block on sampled rows."""
+    from paper_2507_05753_amd.layer import JigsawMixing
+    cfg = inputs.MLP_CONFIGS["channel_mixing_1b"]
+    M, C, Hd, seed = cfg["M"], cfg["C"], cfg["Hd"], cfg["seed"]
+    Xd = inputs.matrix_torch(seed, M, C, "R", device="cuda") + 0.25
+    W1d = inputs.matrix_torch(seed + 1, Hd, C, "R", inputs.W_SCALE_EXP, device="cuda")
+    W2d = inputs.matrix_torch(seed + 3, C, Hd, "R", inputs.W_SCALE_EXP, device="cuda")
+    b1 = inputs.matrix(seed + 2, 1, Hd, "R")[0]
+    b2 = inputs.matrix(seed + 4, 1, C, "R")[0]
+    gamma, beta = affine(seed + 5, C)
+    W1, W2 = W1d.cpu().numpy(), W2d.cpu().numpy()
+    k = inputs.keys(7000, np.arange(24, dtype=np.uint64))
+    rows = np.unique(np.concatenate([(k % np.uint64(M)).astype(np.int64), [0, M // 2 - 1, M // 2, M - 1]]))
+    Xs = Xd[torch.from_numpy(rows).cuda()].cpu().numpy()
+    note(capsys, f"channel mixing: {rows.size} sampled rows")
+    for ways in (1, 2, 4):
+        with JigsawMixing(M, C, Hd, ways) as L:
+            L.shard(Xd, dev(gamma), dev(beta), W1d, dev(b1), W2d, dev(b2))
+            L.forward()
+            Xn, H, Y = L.gather_xn(), L.gather_h(), L.gather()
+            torch.cuda.synchronize()
+            assert torch.isfinite(Y).all()
+            # all rows: with gamma = 1, beta = 0 each channel block of each token has mean 0 and
+            # second moment var / (var + eps)
+            jg.jg_layernorm_forward(L.first.plan, [t.data_ptr() for t in L.first.x], None, None, L.eps,
+                                    [t.data_ptr() for t in L.xn])
+            Z = L.gather_xn().double()
+            g = oracle.ln_groups(ways)
+            Zg = Z.view(M, g, C // g)
+            var = Xd.double().view(M, g, C // g).var(dim=2, unbiased=False)
+            assert Zg.mean(dim=2).abs().max().item() <= 1e-7
+            assert ((Zg * Zg).mean(dim=2) - var / (var + L.eps)).abs().max().item() <= 1e-6
+            idx = torch.from_numpy(rows).cuda()
+            Xn, H, Y = Xn[idx].cpu().numpy(), H[idx].cpu().numpy(), Y[idx].cpu().numpy()
+        r = oracle.mixing_block(ways, Xs, gamma, beta, W1, b1, W2, b2)
+        check_block(r, Xn, H, Y)
+        note(capsys, f"channel mixing ways={ways}: ok")
