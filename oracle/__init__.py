@@ -59,6 +59,7 @@ def _load():
         lib.oracle_linear_xtw.argtypes = [f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int, ctypes.c_int]
         lib.oracle_jigsaw_xtw.argtypes = [ctypes.c_int, f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int]
         lib.oracle_gelu.argtypes = [f64p, i64, f64p]
+        lib.oracle_round_bf16.argtypes = [f32p, i64, f32p]
         lib.oracle_layernorm.argtypes = [f32p, f32p, f32p, i64, i64, i64, ctypes.c_double, f64p, f64p, ctypes.c_int]
         lib.oracle_mlp.argtypes = [f32p, f32p, f32p, f32p, f32p, i64, i64, i64, ctypes.c_int,
                                    f64p, f64p, f64p, f64p, f64p, ctypes.c_int]
@@ -272,6 +273,41 @@ def jigsaw_mlp(ways: int, X, W1, b1, W2, b2, residual: bool = True):
     H = gelu(jigsaw(ways, X, W1, b1)).astype(np.float32)
     Y = jigsaw(ways, H, W2, b2)
     return Y + np.asarray(X, dtype=np.float64) if residual else Y
+
+
+# ----------------------------------------------------------------------------
+# reduced precision (Sec. 6.1: matrix units that round FP32 operands to a short mantissa, FP32 sums)
+# ----------------------------------------------------------------------------
+def round_bf16(a) -> np.ndarray:
+    """FP32 values rounded to bfloat16 (nearest, ties to even), returned as FP32."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    out = np.empty_like(a)
+    _check(_load().oracle_round_bf16(a.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), a.size,
+                                     out.ctypes.data_as(ctypes.POINTER(ctypes.c_float))), "round_bf16")
+    return out
+
+
+def split_bf16(a):
+    """x = hi + lo + (a remainder below 2^-17 |x|): hi = round_bf16(x), lo = round_bf16(x - hi)."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    hi = round_bf16(a)
+    lo = round_bf16(a - hi)          # the difference is exact in FP32 (pinned)
+    return hi, lo
+
+
+def linear_reduced(X, W, b=None, terms: int = 1, nthreads: int | None = None, absolute: bool = False) -> np.ndarray:
+    """The layer Y = X W^T + b with operands rounded to bfloat16, in double.
+
+    terms = 1: round(X) round(W)^T.  terms = 3: split operands, Xhi Whi^T + Xhi Wlo^T + Xlo Whi^T (the
+    lo * lo product is dropped).  absolute=True: the same sums of absolute values (the magnitude)."""
+    f = magnitude if absolute else linear
+    if terms == 1:
+        return f(round_bf16(X), round_bf16(W), b, nthreads)
+    if terms != 3:
+        raise RuntimeError(f"terms must be 1 or 3, not {terms}")
+    Xh, Xl = split_bf16(X)
+    Wh, Wl = split_bf16(W)
+    return f(Xh, Wh, b, nthreads) + f(Xh, Wl, None, nthreads) + f(Xl, Wh, None, nthreads)
 
 
 # ----------------------------------------------------------------------------

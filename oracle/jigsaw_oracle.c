@@ -66,6 +66,13 @@
  *                       in double; groups = 1 is the unpartitioned layer, 2 the 2- and 4-way
  *                       ones (4-way also splits the tokens, which changes nothing per token).
  *                       Also returns the magnitude (|x| + |mu|) / sqrt(var + eps) * |gamma| + |beta|.
+ *  oracle_round_bf16  : the reduced-precision mode (Sec. 6.1: the paper trains in a mixed precision
+ *                       whose matrix units round the FP32 operands to a short mantissa and accumulate
+ *                       in FP32).  The short format here is bfloat16 = the upper 16 bits of an FP32
+ *                       number; rounding is to nearest, ties to even, done on the bit pattern.  The
+ *                       reduced-precision layer is the same definition (oracle_linear) applied to
+ *                       rounded operands; with split operands (x = hi + lo, hi = round(x),
+ *                       lo = round(x - hi)) it is the sum of the three products hi*hi, hi*lo, lo*hi.
  *
  * Pins (see tests/test_oracle_pins.py): closed forms for identity /
  * permutation / all-ones / single-nonzero operands, exact integer brute force
@@ -82,6 +89,10 @@
  * the MLP against the pinned forward oracle applied twice, closed forms (zero first
  * layer, identity weights), and brute force in exact rationals where gelu is not
  * involved.
+ *
+ * Pins of the bfloat16 rounding (tests/test_oracle_bf16_pins.py): tabulated ties and neighbours,
+ * the library's own conversion, idempotence, monotonicity, the half-ulp bound, exactness of the
+ * split's remainder, lattice values left unchanged.
  *
  * Pins of the layer norm (tests/test_oracle_layernorm_pins.py): rows whose result is known
  * in closed form (constant rows, +-1 rows, an arithmetic progression), the moments of the
@@ -761,4 +772,26 @@ int oracle_layernorm(const float* X, const float* gamma, const float* beta, int6
     if (C == 0) return ORACLE_OK;
     ln_env e = {X, gamma, beta, C, groups, eps, Y, S};
     return for_rows(0, M, nthreads, ln_row, &e);
+}
+
+/* ------------------------------------------------------------------ */
+/* bfloat16 rounding: nearest, ties to even, on the bit pattern         */
+/* ------------------------------------------------------------------ */
+int oracle_round_bf16(const float* in, int64_t n, float* out)
+{
+    if (!in || !out || n < 0) return ORACLE_E_ARG;
+    for (int64_t i = 0; i < n; ++i) {
+        uint32_t u;
+        memcpy(&u, &in[i], 4);
+        if ((u & 0x7F800000u) == 0x7F800000u) {
+            if (u & 0x007FFFFFu) u |= 0x00400000u;      /* NaN stays NaN when its payload is cut */
+            u &= 0xFFFF0000u;
+        } else {
+            const uint32_t keep_odd = (u >> 16) & 1u;    /* ties go to the even 16-bit pattern */
+            u += 0x7FFFu + keep_odd;
+            u &= 0xFFFF0000u;
+        }
+        memcpy(&out[i], &u, 4);
+    }
+    return ORACLE_OK;
 }
