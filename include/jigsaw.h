@@ -76,7 +76,14 @@ typedef enum jg_status {
 
 enum { JG_OP_XWT = 0,                                    /* Y = X W^T (Sec. 4)          */
        JG_OP_XTW = 1 };                                  /* Y = X^T W (Sec. 5), forward only */
-enum { JG_F32 = 0 };                                     /* the paper's uniform single precision (Sec. 6.1) */
+enum { JG_F32 = 0,       /* the paper's uniform single precision (Sec. 6.1)                          */
+       JG_BF16 = 1,      /* reduced precision (Sec. 6.1 trains in a mixed precision whose matrix units
+                            round FP32 operands to a short mantissa and sum in FP32; this chip has no such
+                            FP32-input mode): X and W are rounded to bfloat16 (nearest, ties to even) when
+                            they are sharded, products are exact, sums FP32, Y and b stay FP32           */
+       JG_BF16X3 = 2 };  /* the same with split operands x = hi + lo (both bfloat16): the product is
+                            hi hi + hi lo + lo hi, 16 mantissa bits per operand at three times the
+                            matrix work of JG_BF16                                                       */
 enum { JG_COMBINE_FUSED = 0, JG_COMBINE_SEPARATE = 1 };  /* where the "+" of Eq. (2)/(4) runs */
 enum { JG_WEIGHTS_COPY = 0, JG_WEIGHTS_DIRECT = 1 };     /* 4-way weight-block hand-off */
 enum { JG_TAIL_SPLIT = 0, JG_TAIL_WHOLE = 1 };           /* last partial round of a GEMM launch */
@@ -88,7 +95,12 @@ typedef struct jg_linear_desc {
                             M x K, W is N x K.  JG_OP_XTW: X is K x M, W is K x N.      */
     int32_t ways;        /* 1, 2 or 4                                                   */
     int32_t op;          /* JG_OP_XWT or JG_OP_XTW                                      */
-    int32_t dtype;       /* JG_F32                                                      */
+    int32_t dtype;       /* JG_F32, or JG_BF16 / JG_BF16X3: JG_OP_XWT forward only, and every
+                            rank's share of K (K, or K / 2 for 2 and 4 ways) must be a
+                            multiple of 8; the X and W shards are then bfloat16 arrays of
+                            JG_Q_X_SHARD_BYTES / JG_Q_W_SHARD_BYTES bytes, 16-byte aligned,
+                            written by jg_shard: xr x xc values per shard, JG_BF16X3 every
+                            row as [hi(0..xc) | lo(0..xc)]                                */
     int32_t has_bias;    /* 0 / 1: b_r (the slice of b matching Y_r's columns) is added
                             once, by the rank that owns the output block                */
     int32_t combine;     /* JG_COMBINE_FUSED: the kept-product GEMM starts its accumulators
@@ -129,7 +141,9 @@ typedef enum jg_query {
     JG_Q_BACKWARD_FLOPS_TOTAL = 15,     /* 4 M K N: twice the forward (Sec. 6.3 work model)      */
     JG_Q_BACKWARD_GEMM_LAUNCHES = 16,   /* GEMM kernel launches per backward (rank ignored)      */
     JG_Q_TAIL_SCRATCH_BYTES = 17,       /* part of JG_Q_WORKSPACE_BYTES that JG_TAIL_SPLIT adds   */
-    JG_Q_BACKWARD_TAIL_SCRATCH_BYTES = 18 /* the same for JG_Q_BACKWARD_WORKSPACE_BYTES           */
+    JG_Q_BACKWARD_TAIL_SCRATCH_BYTES = 18, /* the same for JG_Q_BACKWARD_WORKSPACE_BYTES          */
+    JG_Q_X_SHARD_BYTES = 19,            /* bytes of the rank's X shard in the plan's dtype        */
+    JG_Q_W_SHARD_BYTES = 20             /* ... and of its W shard                                 */
 } jg_query;
 
 typedef enum jg_kernel {         /* kernel classes for jg_profile_read */
@@ -184,6 +198,10 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out);
  * (r/2, r%2)) and b as above.
  * `global` is a device pointer; `shards` is a host array of `ways` device pointers,
  * each with room for the rank's shard.  Pure data movement: bit-exact.
+ * Reduced-precision plans (JG_BF16, JG_BF16X3): `global` is FP32 all the same; X and W shards are
+ * written as bfloat16 (see jg_linear_desc.dtype; the pointers in `shards` are then those buffers,
+ * 16-byte aligned), each value rounded on its bit pattern — bit-exact against that definition; b and
+ * Y stay FP32.
  * Errors: JG_E_NULL, JG_E_SHAPE (ld), JG_E_ALIGN, JG_E_DTYPE (which), JG_E_HIP. */
 int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, float* const* shards);
 

@@ -30,7 +30,7 @@ JG_OK = 0
 JG_E_NULL, JG_E_SHAPE, JG_E_WAYS, JG_E_DTYPE = -1, -2, -3, -4
 JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP, JG_E_ARCH = -5, -6, -7, -8
 JG_OP_XWT, JG_OP_XTW = 0, 1
-JG_F32 = 0
+JG_F32, JG_BF16, JG_BF16X3 = 0, 1, 2
 JG_COMBINE_FUSED, JG_COMBINE_SEPARATE = 0, 1
 JG_WEIGHTS_COPY, JG_WEIGHTS_DIRECT = 0, 1
 JG_TAIL_SPLIT, JG_TAIL_WHOLE = 0, 1
@@ -40,7 +40,7 @@ JG_T_X, JG_T_W, JG_T_B, JG_T_Y = 0, 1, 2, 3
  JG_Q_EXCHANGE_BYTES_RANK, JG_Q_X_ROWS, JG_Q_X_COLS, JG_Q_W_ROWS, JG_Q_W_COLS,
  JG_Q_Y_ROWS, JG_Q_Y_COLS, JG_Q_B_LEN, JG_Q_RESIDENT_BYTES_RANK, JG_Q_GEMM_LAUNCHES,
  JG_Q_BACKWARD_WORKSPACE_BYTES, JG_Q_BACKWARD_FLOPS_TOTAL, JG_Q_BACKWARD_GEMM_LAUNCHES,
- JG_Q_TAIL_SCRATCH_BYTES, JG_Q_BACKWARD_TAIL_SCRATCH_BYTES) = range(19)
+ JG_Q_TAIL_SCRATCH_BYTES, JG_Q_BACKWARD_TAIL_SCRATCH_BYTES, JG_Q_X_SHARD_BYTES, JG_Q_W_SHARD_BYTES) = range(21)
 (JG_KERNEL_GEMM, JG_KERNEL_WEIGHT_COPY, JG_KERNEL_COMBINE, JG_KERNEL_SHARD,
  JG_KERNEL_GATHER, JG_KERNEL_GEMM_DX, JG_KERNEL_GEMM_DW, JG_KERNEL_JOIN, JG_KERNEL_NORM,
  JG_KERNEL_COUNT) = range(10)

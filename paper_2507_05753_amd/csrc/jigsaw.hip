@@ -14,6 +14,8 @@
 #include "stream_kernels.hpp"
 #include "patch_kernels.hpp"
 #include "norm_kernels.hpp"
+#include "gemm_bf16.hpp"
+#include "cvt_kernels.hpp"
 
 namespace {
 
@@ -56,6 +58,9 @@ struct jg_plan {
     jg_linear_desc d;
     // per-rank shard shapes
     int64_t xr, xc, wr, wc, yr, yc;
+    // 4-byte units in one row of an X or W shard: xc for FP32, xc / 2 for bfloat16, xc for the
+    // split mode's [hi | lo] rows
+    int64_t xcp;
     // workspace layout (byte offsets); sizes are per rank
     size_t part_bytes;     // one rank's partial product  (yr x yc floats, padded)
     size_t wblk_bytes;     // one rank's received weight block (4-way, copy mode)
@@ -225,7 +230,10 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     if (!desc) return JG_E_NULL;
     const jg_linear_desc& d = *desc;
     if (d.ways != 1 && d.ways != 2 && d.ways != 4) return JG_E_WAYS;
-    if ((d.op != JG_OP_XWT && d.op != JG_OP_XTW) || d.dtype != JG_F32) return JG_E_DTYPE;
+    if (d.op != JG_OP_XWT && d.op != JG_OP_XTW) return JG_E_DTYPE;
+    if (d.dtype != JG_F32 && d.dtype != JG_BF16 && d.dtype != JG_BF16X3) return JG_E_DTYPE;
+    const bool reduced = d.dtype != JG_F32;
+    if (reduced && d.op != JG_OP_XWT) return JG_E_DTYPE;
     if (d.combine != JG_COMBINE_FUSED && d.combine != JG_COMBINE_SEPARATE) return JG_E_DTYPE;
     if (d.weights != JG_WEIGHTS_COPY && d.weights != JG_WEIGHTS_DIRECT) return JG_E_DTYPE;
     if (d.has_bias != 0 && d.has_bias != 1) return JG_E_DTYPE;
@@ -236,6 +244,8 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     const bool xtw = d.op == JG_OP_XTW;
     if (d.ways >= 2 && ((xtw ? d.M & 1 : d.K & 1) || (d.N & 1))) return JG_E_SHAPE;
     if (d.ways == 4 && ((d.M & 1) || (d.K & 1))) return JG_E_SHAPE;
+    // bfloat16 shards move in 16-byte chunks of 8 elements: a rank's share of K must be whole chunks
+    if (reduced && ((d.K / (d.ways >= 2 ? 2 : 1)) & 7)) return JG_E_SHAPE;
     {   // every product of the plan (forward M x N, backward M x K and N x K, up to four
         // problems a launch) must have a tile count that fits the 32-bit block index
         const int64_t tm = (d.M + jg::BM - 1) / jg::BM, tn = (d.N + jg::BM - 1) / jg::BM,
@@ -268,6 +278,7 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
             break;
         }
     }
+    p->xcp = d.dtype == JG_BF16 ? p->xc / 2 : p->xc;
     p->part_bytes = p->wblk_bytes = 0;
     p->off_send = p->off_kept = p->off_wrecv = 0;
     size_t off = 0;
@@ -286,7 +297,7 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
         }
     }
     if (operand_blocks) {
-        const size_t elems = xtw ? (size_t)p->xr * (size_t)p->xc : (size_t)p->wr * (size_t)p->wc;
+        const size_t elems = xtw ? (size_t)p->xr * (size_t)p->xc : (size_t)p->wr * (size_t)p->xcp;
         p->wblk_bytes = round_up(elems * sizeof(float), kWsAlign);
         p->off_wrecv = off;
         off += p->wblk_bytes * d.ways;
@@ -305,7 +316,7 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     // scratch for the split tail: the largest need over the launches of each pass
     p->slots = ctx ? ctx->slots : kDefaultSlots;
     p->tail_bytes = p->bw_tail_bytes = 0;
-    if (d.tail == JG_TAIL_SPLIT) {
+    if (d.tail == JG_TAIL_SPLIT && !reduced) {      // the bfloat16 kernel runs whole tiles only
         auto need = [&](int nprob, int64_t m, int64_t n, int64_t k) {
             const int64_t tiles = nprob * ((m + jg::BM - 1) / jg::BM) * ((n + jg::BN - 1) / jg::BN);
             return jg::tail_scratch_bytes(tiles, (int)k, p->slots);
@@ -334,11 +345,14 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     if (!plan || !out) return JG_E_NULL;
     const jg_linear_desc& d = plan->d;
     const bool per_rank = what == JG_Q_FLOPS_RANK || what == JG_Q_EXCHANGE_BYTES_RANK ||
-                          (what >= JG_Q_X_ROWS && what <= JG_Q_RESIDENT_BYTES_RANK);
+                          (what >= JG_Q_X_ROWS && what <= JG_Q_RESIDENT_BYTES_RANK) ||
+                          what == JG_Q_X_SHARD_BYTES || what == JG_Q_W_SHARD_BYTES;
     if (per_rank && (rank < 0 || rank >= d.ways)) return JG_E_WAYS;
     const int64_t M = d.M, K = d.K, N = d.N;
     const bool xtw = d.op == JG_OP_XTW;
-    if (xtw && (what == JG_Q_BACKWARD_WORKSPACE_BYTES || what == JG_Q_BACKWARD_FLOPS_TOTAL ||
+    const bool reduced = d.dtype != JG_F32;
+    const int64_t eb = d.dtype == JG_BF16 ? 2 : 4;     // bytes per element of an X or W shard (split mode: hi + lo)
+    if ((xtw || reduced) && (what == JG_Q_BACKWARD_WORKSPACE_BYTES || what == JG_Q_BACKWARD_FLOPS_TOTAL ||
                 what == JG_Q_BACKWARD_GEMM_LAUNCHES || what == JG_Q_BACKWARD_TAIL_SCRATCH_BYTES))
         return JG_E_DTYPE;   // no backward for this op
     switch (what) {
@@ -346,7 +360,7 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     case JG_Q_FLOPS_TOTAL: *out = 2 * M * K * N; break;
     case JG_Q_FLOPS_RANK: *out = 2 * M * K * N / d.ways; break;
     case JG_Q_HBM_BYTES_ALGO:
-        *out = 4 * (M * K + N * K + M * N) + ((xtw ? d.ways == 4 : d.ways >= 2) ? 8 * M * N : 0);
+        *out = eb * (M * K + N * K) + 4 * M * N + ((xtw ? d.ways == 4 : d.ways >= 2) ? 8 * M * N : 0);
         break;
     case JG_Q_EXCHANGE_BYTES_RANK:
         if (xtw) {
@@ -360,7 +374,7 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
         // 2-way: one M x N/2 partial.  4-way: one M/2 x N/2 partial and one N/2 x K/2 weight block.
         *out = d.ways == 1 ? 0
              : d.ways == 2 ? 4 * M * (N / 2)
-                           : 4 * ((M / 2) * (N / 2) + (N / 2) * (K / 2));
+                           : 4 * (M / 2) * (N / 2) + eb * (N / 2) * (K / 2);
         break;
     case JG_Q_X_ROWS: *out = plan->xr; break;
     case JG_Q_X_COLS: *out = plan->xc; break;
@@ -370,7 +384,7 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     case JG_Q_Y_COLS: *out = plan->yc; break;
     case JG_Q_B_LEN: *out = plan->yc; break;
     case JG_Q_RESIDENT_BYTES_RANK:
-        *out = 4 * (plan->xr * plan->xc + plan->wr * plan->wc + plan->yr * plan->yc);
+        *out = eb * (plan->xr * plan->xc + plan->wr * plan->wc) + 4 * plan->yr * plan->yc;
         break;
     case JG_Q_GEMM_LAUNCHES: *out = (d.ways == 1 || (xtw && d.ways == 2)) ? 1 : 2; break;
     case JG_Q_BACKWARD_WORKSPACE_BYTES: *out = (int64_t)plan->bw_ws_bytes; break;
@@ -378,6 +392,8 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     case JG_Q_BACKWARD_GEMM_LAUNCHES: *out = d.ways == 1 ? 2 : d.ways == 2 ? 3 : 4; break;
     case JG_Q_TAIL_SCRATCH_BYTES: *out = (int64_t)plan->tail_bytes; break;
     case JG_Q_BACKWARD_TAIL_SCRATCH_BYTES: *out = (int64_t)plan->bw_tail_bytes; break;
+    case JG_Q_X_SHARD_BYTES: *out = 4 * plan->xr * plan->xcp; break;
+    case JG_Q_W_SHARD_BYTES: *out = 4 * plan->wr * plan->xcp; break;
     default: return JG_E_DTYPE;
     }
     return JG_OK;
@@ -418,6 +434,27 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
     if (!c) return JG_E_NULL;
     if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
 
+    if (d.dtype != JG_F32 && (which == JG_T_X || which == JG_T_W)) {
+        // reduced precision: the shard is written in the format the matrix cores read
+        Partition pt;
+        (void)partition_of(plan, which, &pt);
+        if (ld < pt.width) return JG_E_SHAPE;
+        jg::CvtGroup cv;
+        std::memset(&cv, 0, sizeof(cv));
+        cv.nblocks = d.ways;
+        cv.rows = (int)pt.rows;
+        cv.cols = (int)pt.cols;
+        cv.planes = d.dtype == JG_BF16X3 ? 2 : 1;
+        for (int r = 0; r < d.ways; ++r) {
+            if (!aligned(shards[r], 16)) return JG_E_ALIGN;
+            int64_t rb, cb;
+            block_coords(d.ways, r, &rb, &cb);
+            cv.b[r] = {global + rb * pt.rows * ld + cb * pt.cols, reinterpret_cast<uint16_t*>(shards[r]), ld};
+        }
+        ScopedTimer t(c, JG_KERNEL_SHARD);
+        return HIP_OK(jg::launch_cvt_group(cv, c->stream)) ? JG_OK : JG_E_HIP;
+    }
+
     jg::CopyGroup g;
     std::memset(&g, 0, sizeof(g));
     g.nblocks = d.ways;
@@ -454,6 +491,7 @@ int jg_gather_as(const jg_plan* plan, int which, const float* const* shards, flo
     if (!aligned(global, 4)) return JG_E_ALIGN;
     Partition pt;
     if (int rc = partition_of(plan, which, &pt)) return rc;
+    if (d.dtype != JG_F32 && which != JG_T_Y) return JG_E_DTYPE;   // bfloat16 shards are not converted back
     if (ld < pt.width) return JG_E_SHAPE;
     jg_ctx* c = plan->ctx;
     if (!c) return JG_E_NULL;
@@ -480,7 +518,7 @@ static int patch_move(const jg_plan* plan, int which, float* field, int64_t C, i
 {
     if (!plan || !field) return JG_E_NULL;
     const jg_linear_desc& d = plan->d;
-    if (d.op != JG_OP_XWT) return JG_E_DTYPE;
+    if (d.op != JG_OP_XWT || (d.dtype != JG_F32 && which == JG_T_X)) return JG_E_DTYPE;
     if (int rc = check_ptr_array(blocks, d.ways)) return rc;
     if (!aligned(field, 4)) return JG_E_ALIGN;
     if (C <= 0 || H <= 0 || W <= 0 || p <= 0 || C > kMaxDim || H > kMaxDim || W > kMaxDim || p > 4096) return JG_E_SHAPE;
@@ -535,6 +573,10 @@ static bool run_gemm(const jg_plan* plan, jg::GemmGroup& g, int layout, int kern
 {
     jg_ctx* c = plan->ctx;
     bool join = false;
+    if (plan->d.dtype != JG_F32) {
+        ScopedTimer t(c, kernel_class);
+        return HIP_OK(jg::launch_gemm_bf16_group(g, plan->d.dtype == JG_BF16X3 ? 3 : 1, c->stream));
+    }
     {
         ScopedTimer t(c, kernel_class);
         if (!HIP_OK(jg::launch_gemm_group(g, layout, c->stream, reinterpret_cast<float*>(scratch), scratch_bytes,
@@ -690,7 +732,7 @@ int jg_linear_forward_ex(const jg_plan* plan, const float* const* x_sh, const fl
     g.M = (int)plan->yr;
     g.N = (int)plan->yc;
     g.K = (int)plan->xc;
-    const int ldk = (int)plan->xc;   // leading dimension of every X / W shard
+    const int ldk = (int)plan->xcp;  // leading dimension of every X / W shard, in 4-byte units
     const int ldn = (int)plan->yc;   // leading dimension of every Y shard / partial
 
     if (ways == 1) {
@@ -711,7 +753,7 @@ int jg_linear_forward_ex(const jg_plan* plan, const float* const* x_sh, const fl
     if (ways == 2) {
         // Sec. 4.1: W_r = [W_{r,0}; W_{r,1}] by rows; rank r keeps X_r W_{r,r}^T and ships
         // X_r W_{r,1-r}^T to the other rank.
-        const int64_t half = plan->yc * plan->xc;   // floats in one N/2 x K/2 block
+        const int64_t half = plan->yc * plan->xcp;  // 4-byte units in one N/2 x K/2 block
         for (int r = 0; r < 2; ++r) {
             w_keep[r] = w_sh[r] + r * half;
             w_send[r] = w_sh[r] + (1 - r) * half;
@@ -724,10 +766,10 @@ int jg_linear_forward_ex(const jg_plan* plan, const float* const* x_sh, const fl
             std::memset(&cg, 0, sizeof(cg));
             cg.nblocks = 4;
             cg.rows = (int)plan->wr;
-            cg.cols = (int)plan->wc;
+            cg.cols = (int)plan->xcp;
             for (int r = 0; r < 4; ++r) {
                 float* dst = reinterpret_cast<float*>(ws + plan->off_wrecv + r * plan->wblk_bytes);
-                cg.b[r] = {w_sh[kWeightFrom4[r]], dst, plan->wc, plan->wc};
+                cg.b[r] = {w_sh[kWeightFrom4[r]], dst, plan->xcp, plan->xcp};
                 w_in[r] = dst;
             }
             ScopedTimer t(c, JG_KERNEL_WEIGHT_COPY);
@@ -777,7 +819,7 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
 {
     if (!plan || !plan->ctx) return JG_E_NULL;
     const jg_linear_desc& d = plan->d;
-    if (d.op != JG_OP_XWT) return JG_E_DTYPE;
+    if (d.op != JG_OP_XWT || d.dtype != JG_F32) return JG_E_DTYPE;
     const int ways = d.ways;
     if (int rc = check_ptr_array(x_sh, ways)) return rc;
     if (int rc = check_ptr_array(w_sh, ways)) return rc;
@@ -874,7 +916,7 @@ int jg_layernorm_forward(const jg_plan* plan, const float* const* x_sh, const fl
     const jg_linear_desc& d = plan->d;
     if (int rc = check_ptr_array(x_sh, d.ways)) return rc;
     if (int rc = check_ptr_array(out_sh, d.ways)) return rc;
-    if (!(eps >= 0.0)) return JG_E_DTYPE;
+    if (d.dtype != JG_F32 || !(eps >= 0.0)) return JG_E_DTYPE;
     if (!aligned(gamma, 4) || !aligned(beta, 4)) return JG_E_ALIGN;
     for (int r = 0; r < d.ways; ++r)
         if (!aligned(x_sh[r], 4) || !aligned(out_sh[r], 4)) return JG_E_ALIGN;
@@ -901,6 +943,7 @@ static int check_mlp_chain(const jg_plan* first, const jg_plan* second)
     if (!first || !second) return JG_E_NULL;
     const jg_linear_desc &a = first->d, &b = second->d;
     if (a.op != JG_OP_XWT || b.op != JG_OP_XWT) return JG_E_DTYPE;
+    if (a.dtype != JG_F32 || b.dtype != JG_F32) return JG_E_DTYPE;   // H leaves the first layer in FP32
     if (a.ways != b.ways) return JG_E_WAYS;
     if (a.M != b.M || a.N != b.K || b.N != a.K) return JG_E_SHAPE;
     if (first->ctx != second->ctx) return JG_E_NULL;

@@ -14,12 +14,14 @@ class JigsawLinear:
     """Plan + per-rank shard tensors (X_r, W_r, b_r, Y_r) + workspace on one GPU.
 
     ``op = JG_OP_XWT``: Y = X W^T with X (M, K) and W (N, K).  ``op = JG_OP_XTW``: the transposed
-    layer Y = X^T W with X (K, M) and W (K, N), forward only.
+    layer Y = X^T W with X (K, M) and W (K, N), forward only.  ``dtype = JG_BF16 / JG_BF16X3``: the X and W
+    shards are bfloat16 tensors (split mode: every row is [hi | lo]) written by ``shard`` from FP32 inputs.
     """
 
     def __init__(self, M: int, K: int, N: int, ways: int, bias: bool = False,
                  combine: int = jg.JG_COMBINE_FUSED, weights: int = jg.JG_WEIGHTS_COPY,
-                 device: int = 0, ctx=None, op: int = jg.JG_OP_XWT, tail: int = jg.JG_TAIL_SPLIT):
+                 device: int = 0, ctx=None, op: int = jg.JG_OP_XWT, tail: int = jg.JG_TAIL_SPLIT,
+                 dtype: int = jg.JG_F32):
         if not torch.cuda.is_available():
             raise RuntimeError("JigsawLinear needs a GPU: the HIP library has no CPU fallback")
         self.M, self.K, self.N, self.ways, self.bias, self.op = M, K, N, ways, bias, op
@@ -29,11 +31,20 @@ class JigsawLinear:
         self._own_ctx = ctx is None
         self.stream = torch.cuda.current_stream(self.dev)
         self.ctx = ctx if ctx is not None else jg.jg_init(device, self.stream.cuda_stream)
-        self.plan = jg.jg_plan_create(self.ctx, M, K, N, ways, bias, combine, weights, op, tail=tail)
+        self.dtype = dtype
+        self.plan = jg.jg_plan_create(self.ctx, M, K, N, ways, bias, combine, weights, op, dtype=dtype, tail=tail)
         q = lambda what, r=0: jg.jg_plan_query(self.plan, what, r)
         f32 = dict(dtype=torch.float32, device=self.dev)
-        self.x = [torch.empty((q(jg.JG_Q_X_ROWS, r), q(jg.JG_Q_X_COLS, r)), **f32) for r in range(ways)]
-        self.w = [torch.empty((q(jg.JG_Q_W_ROWS, r), q(jg.JG_Q_W_COLS, r)), **f32) for r in range(ways)]
+        if dtype == jg.JG_F32:
+            self.x = [torch.empty((q(jg.JG_Q_X_ROWS, r), q(jg.JG_Q_X_COLS, r)), **f32) for r in range(ways)]
+            self.w = [torch.empty((q(jg.JG_Q_W_ROWS, r), q(jg.JG_Q_W_COLS, r)), **f32) for r in range(ways)]
+        else:
+            planes = 2 if dtype == jg.JG_BF16X3 else 1
+            b16 = dict(dtype=torch.bfloat16, device=self.dev)
+            self.x = [torch.empty((q(jg.JG_Q_X_ROWS, r), planes * q(jg.JG_Q_X_COLS, r)), **b16) for r in range(ways)]
+            self.w = [torch.empty((q(jg.JG_Q_W_ROWS, r), planes * q(jg.JG_Q_W_COLS, r)), **b16) for r in range(ways)]
+            assert all(t.numel() * 2 == q(jg.JG_Q_X_SHARD_BYTES, r) for r, t in enumerate(self.x))
+            assert all(t.numel() * 2 == q(jg.JG_Q_W_SHARD_BYTES, r) for r, t in enumerate(self.w))
         self.y = [torch.empty((q(jg.JG_Q_Y_ROWS, r), q(jg.JG_Q_Y_COLS, r)), **f32) for r in range(ways)]
         self.b = [torch.empty((q(jg.JG_Q_B_LEN, r),), **f32) for r in range(ways)] if bias else None
         self.ws_bytes = q(jg.JG_Q_WORKSPACE_BYTES)

@@ -55,7 +55,14 @@ def test_plan_validation():
     assert status_of(M=7) == jg.JG_OK                 # ... but any M
     assert status_of(M=7, ways=4) == jg.JG_E_SHAPE    # 4-way needs even M too
     assert status_of(M=7, K=7, N=7, ways=1) == jg.JG_OK
-    assert status_of(dtype=1) == jg.JG_E_DTYPE
+    assert status_of(dtype=3) == jg.JG_E_DTYPE
+    # reduced precision: forward of X W^T only, and every rank's share of K in whole 8-element chunks
+    for dt in (jg.JG_BF16, jg.JG_BF16X3):
+        assert status_of(dtype=dt) == jg.JG_E_SHAPE                 # K / 2 = 4
+        assert status_of(dtype=dt, K=16) == jg.JG_OK
+        assert status_of(dtype=dt, K=8, ways=1) == jg.JG_OK
+        assert status_of(dtype=dt, K=24, ways=4) == jg.JG_E_SHAPE   # K / 2 = 12
+        assert status_of(dtype=dt, K=16, op=jg.JG_OP_XTW) == jg.JG_E_DTYPE
     assert status_of(op=2) == jg.JG_E_DTYPE
     # the transposed layer splits M and N (2-way), and K as well (4-way)
     assert status_of(op=jg.JG_OP_XTW) == jg.JG_OK
@@ -281,6 +288,35 @@ def test_mixing_and_layernorm_entry_points_check_their_arguments():
     assert lib.jg_layernorm_forward(None, pp, None, None, 1e-5, pp) == jg.JG_E_NULL
     assert lib.jg_layernorm_forward(a, pp, None, None, 1e-5, pp) == jg.JG_E_NULL     # a plan without a context
     jg.jg_plan_destroy(a)
+
+
+def test_reduced_precision_plans_account_for_their_shards():
+    M, K, N = 64, 48, 32
+    for ways in (1, 2, 4):
+        f = jg.jg_plan_create(None, M, K, N, ways)
+        h = jg.jg_plan_create(None, M, K, N, ways, dtype=jg.JG_BF16)
+        s = jg.jg_plan_create(None, M, K, N, ways, dtype=jg.JG_BF16X3)
+        q = jg.jg_plan_query
+        for r in range(ways):
+            xe = q(f, jg.JG_Q_X_ROWS, r) * q(f, jg.JG_Q_X_COLS, r)
+            we = q(f, jg.JG_Q_W_ROWS, r) * q(f, jg.JG_Q_W_COLS, r)
+            assert q(f, jg.JG_Q_X_SHARD_BYTES, r) == 4 * xe and q(f, jg.JG_Q_W_SHARD_BYTES, r) == 4 * we
+            assert q(h, jg.JG_Q_X_SHARD_BYTES, r) == 2 * xe and q(h, jg.JG_Q_W_SHARD_BYTES, r) == 2 * we
+            assert q(s, jg.JG_Q_X_SHARD_BYTES, r) == 4 * xe and q(s, jg.JG_Q_W_SHARD_BYTES, r) == 4 * we
+            assert q(h, jg.JG_Q_X_COLS, r) == q(f, jg.JG_Q_X_COLS, r)          # logical sizes do not change
+        assert q(h, jg.JG_Q_FLOPS_TOTAL) == q(f, jg.JG_Q_FLOPS_TOTAL) == 2 * M * K * N
+        extra = 8 * M * N if ways >= 2 else 0
+        assert q(f, jg.JG_Q_HBM_BYTES_ALGO) == 4 * (M * K + N * K + M * N) + extra
+        assert q(h, jg.JG_Q_HBM_BYTES_ALGO) == 2 * (M * K + N * K) + 4 * M * N + extra
+        assert q(s, jg.JG_Q_HBM_BYTES_ALGO) == 4 * (M * K + N * K + M * N) + extra
+        assert q(h, jg.JG_Q_TAIL_SCRATCH_BYTES) == 0
+        with pytest.raises(jg.JigsawError) as e:
+            q(h, jg.JG_Q_BACKWARD_WORKSPACE_BYTES)
+        assert e.value.status == jg.JG_E_DTYPE
+        if ways == 4:   # the received weight block is bfloat16 too
+            assert q(h, jg.JG_Q_WORKSPACE_BYTES) < q(f, jg.JG_Q_WORKSPACE_BYTES)
+        for p in (f, h, s):
+            jg.jg_plan_destroy(p)
 
 
 def test_patch_calls_check_sizes_against_the_plan():

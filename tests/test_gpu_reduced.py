@@ -1,0 +1,247 @@
+"""GPU parity of the reduced-precision modes (JG_BF16, JG_BF16X3) of the X W^T layer against the CPU oracle.
+
+The mode's definition (operands rounded to bfloat16 on their bit pattern, products exact, sums FP32) is
+what the oracle evaluates in double on the same rounded operands, so the bars are those of the FP32 layer:
+the shards bit for bit, |Y_gpu - Y64| <= 1e-6 * S with S the magnitude of the rounded operands' products,
+and bit-exact results on lattice inputs (which the rounding leaves unchanged).  The split mode is also held
+to its distance from the full-precision layer.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2507_05753_amd import inputs
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def jg():
+    from paper_2507_05753_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ctx(jg):
+    c = jg.jg_init(0, torch.cuda.current_stream().cuda_stream)
+    yield c
+    torch.cuda.synchronize()
+    jg.jg_free(c)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def as_f32(t):
+    """A bfloat16 device tensor as the FP32 values it stands for (exact)."""
+    return t.float().cpu().numpy()
+
+
+def terms_of(jg, dtype):
+    return 3 if dtype == jg.JG_BF16X3 else 1
+
+
+def run_layer(jg, ctx, X, W, b, ways, dtype, combine=0, weights=0, residual=None, act=0):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    M, K = X.shape
+    N = W.shape[0]
+    with JigsawLinear(M, K, N, ways, bias=b is not None, combine=combine, weights=weights, ctx=ctx, dtype=dtype) as L:
+        if L.ws_bytes:
+            L.ws.fill_(0xFF)
+        for y in L.y:
+            y.fill_(float("nan"))
+        L.shard(dev(X), dev(W), dev(b) if b is not None else None)
+        res = None
+        if residual is not None:
+            res = [torch.empty_like(y) for y in L.y]
+            jg.jg_shard(L.plan, jg.JG_T_Y, dev(residual).data_ptr(), N, [t.data_ptr() for t in res])
+        L.forward(residual=res, activation=act)
+        Y = L.gather()
+        torch.cuda.synchronize()
+        return Y.cpu().numpy(), [as_f32(t) for t in L.x], [as_f32(t) for t in L.w]
+
+
+# (M, K, N): K shares in whole 8-element chunks; ragged last slabs (K % 64 != 0), ragged tile edges,
+# several tiles in M and in N, K long enough for many slabs
+SHAPES = [(2, 16, 2), (100, 80, 100), (130, 144, 258), (258, 1040, 136), (520, 272, 600), (300, 4112, 260)]
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+@pytest.mark.parametrize("M,K,N", SHAPES)
+def test_shards_hold_the_rounded_operands(jg, ctx, ways, dtype_name, M, K, N):
+    dtype = getattr(jg, dtype_name)
+    X, W, b = inputs.layer_inputs(401, M, K, N, "R", bias=True)
+    X = (X * np.float32(3.0)).astype(np.float32)
+    _, xs, ws = run_layer(jg, ctx, X, W, b, ways, dtype)
+    for got, src in ((xs, oracle.shard_x(X, ways)), (ws, oracle.shard_w(W, ways))):
+        for g, blk in zip(got, src):
+            if dtype == jg.JG_BF16:
+                assert np.array_equal(g, oracle.round_bf16(blk))
+            else:
+                hi, lo = oracle.split_bf16(blk)
+                cols = blk.shape[1]
+                assert np.array_equal(g[:, :cols], hi) and np.array_equal(g[:, cols:], lo)
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+@pytest.mark.parametrize("bias", [False, True])
+@pytest.mark.parametrize("M,K,N", SHAPES)
+def test_forward_matches_oracle_within_tolerance(jg, ctx, ways, dtype_name, bias, M, K, N):
+    dtype = getattr(jg, dtype_name)
+    X, W, b = inputs.layer_inputs(402, M, K, N, "R", bias=bias)
+    Y, _, _ = run_layer(jg, ctx, X, W, b, ways, dtype)
+    t = terms_of(jg, dtype)
+    want = oracle.linear_reduced(X, W, b, t)
+    S = oracle.linear_reduced(X, W, b, t, absolute=True)
+    err = np.abs(Y.astype(np.float64) - want)
+    assert np.all(err <= TOL * S), f"max err/S = {(err / S).max():.3e}"
+    # the mode is what it says: far from (JG_BF16) or close to (JG_BF16X3) the full-precision layer
+    full = np.abs(Y.astype(np.float64) - oracle.linear(X, W, b)) / oracle.magnitude(X, W, b)
+    if dtype == jg.JG_BF16X3:
+        assert full.max() <= 2.0 ** -15
+    elif K >= 80:
+        assert full.max() > 1e-5
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+@pytest.mark.parametrize("M,K,N", SHAPES)
+def test_lattice_inputs_are_bit_exact(jg, ctx, ways, dtype_name, M, K, N):
+    dtype = getattr(jg, dtype_name)
+    X, W, b = inputs.layer_inputs(403, M, K, N, "L", bias=True)
+    Y, _, _ = run_layer(jg, ctx, X, W, b, ways, dtype)
+    want = oracle.linear(X, W, b)
+    assert np.array_equal(want.astype(np.float32).astype(np.float64), want)
+    assert np.array_equal(Y.astype(np.float64), want)
+
+
+@pytest.mark.parametrize("ways", [2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+@pytest.mark.parametrize("combine,weights", [(1, 0), (0, 1), (1, 1)])
+def test_option_variants(jg, ctx, ways, dtype_name, combine, weights):
+    dtype = getattr(jg, dtype_name)
+    M, K, N = 258, 272, 136
+    X, W, b = inputs.layer_inputs(404, M, K, N, "L", bias=True)
+    base, _, _ = run_layer(jg, ctx, X, W, b, ways, dtype)
+    other, _, _ = run_layer(jg, ctx, X, W, b, ways, dtype, combine=combine, weights=weights)
+    assert np.array_equal(base, other)
+    X, W, b = inputs.layer_inputs(405, M, K, N, "R", bias=True)
+    got, _, _ = run_layer(jg, ctx, X, W, b, ways, dtype, combine=combine, weights=weights)
+    t = terms_of(jg, dtype)
+    S = oracle.linear_reduced(X, W, b, t, absolute=True)
+    assert np.all(np.abs(got.astype(np.float64) - oracle.linear_reduced(X, W, b, t)) <= TOL * S)
+
+
+@pytest.mark.parametrize("ways", [1, 4])
+def test_epilogue_rides_along(jg, ctx, ways):
+    M, K, N = 300, 272, 260
+    X, W, b = inputs.layer_inputs(406, M, K, N, "R", bias=True)
+    R = inputs.matrix(407, M, N, "R")
+    Y, _, _ = run_layer(jg, ctx, X, W, b, ways, jg.JG_BF16, residual=R, act=jg.JG_ACT_GELU)
+    want = oracle.gelu(oracle.linear_reduced(X, W, b, 1)) + R.astype(np.float64)
+    S = oracle.linear_reduced(X, W, b, 1, absolute=True) + np.abs(R)
+    assert np.all(np.abs(Y.astype(np.float64) - want) <= 1.5e-6 * S)
+
+
+@pytest.mark.parametrize("K", [1024, 4096])
+def test_same_sign_operands(jg, ctx, K):
+    # All-positive data: the running FP32 sum is the magnitude itself.  The 256 accumulators of a wavefront
+    # fill its register file, so this kernel has no second accumulation level: K / 16 roundings of the
+    # running sum walk to about sqrt(K / 16) * 2^-24 * S.  Inside 1e-6 * S up to K of about 2000; beyond, the
+    # bar for such data is that walk with a factor 2 (zero-mean data stays far inside 1e-6 * S at any K).
+    M, N = 136, 264
+    X = np.abs(inputs.matrix(408, M, K, "R"))
+    W = np.abs(inputs.matrix(409, N, K, "R"))
+    bar = max(TOL, 2.0 * np.sqrt(K / 16) * 2.0 ** -24)
+    for dtype in (jg.JG_BF16, jg.JG_BF16X3):
+        Y, _, _ = run_layer(jg, ctx, X, W, None, 1, dtype)
+        t = terms_of(jg, dtype)
+        S = oracle.linear_reduced(X, W, None, t, absolute=True)
+        err = np.abs(Y.astype(np.float64) - oracle.linear_reduced(X, W, None, t))
+        assert np.all(err <= bar * S), f"dtype={dtype}: {(err / S).max():.3e}"
+
+
+def test_calls_that_need_fp32_shards_are_refused(jg, ctx):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    with JigsawLinear(16, 32, 16, 2, ctx=ctx, dtype=jg.JG_BF16) as L:
+        ptrs = [t.data_ptr() for t in L.y]
+        for call in (lambda: jg.jg_linear_backward(L.plan, ptrs, ptrs, ptrs, ptrs, ptrs, None, 0),
+                     lambda: jg.jg_layernorm_forward(L.plan, ptrs, None, None, 1e-5, ptrs),
+                     lambda: jg.jg_gather_as(L.plan, jg.JG_T_X, ptrs, ptrs[0], 64),
+                     lambda: jg.jg_shard_patches(L.plan, ptrs[0], 2, 8, 8, 4, ptrs)):
+            with pytest.raises(jg.JigsawError) as e:
+                call()
+            assert e.value.status == jg.JG_E_DTYPE
+        with pytest.raises(jg.JigsawError) as e:          # bfloat16 shards move in 16-byte pieces
+            jg.jg_shard(L.plan, jg.JG_T_X, L.y[0].data_ptr(), 32, [ptrs[0] + 4, ptrs[1]])
+        assert e.value.status == jg.JG_E_ALIGN
+
+
+# --------------------------------------------------------------------------------------------
+# full size: config 3 (n = 1e8 items)
+# --------------------------------------------------------------------------------------------
+def note(capsys, msg):
+    with capsys.disabled():
+        print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
+
+
+def pm1(seed, n, cols):
+    bits = inputs.keys(seed, np.arange(n * cols, dtype=np.uint64)) >> np.uint64(63)
+    return np.where(bits.reshape(n, cols) == 1, 1.0, -1.0)
+
+
+@pytest.mark.timeout(900)
+def test_config3_full_size(jg, capsys):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    cfg = inputs.CONFIGS[3]
+    M, K, N, seed = cfg["M"], cfg["K"], cfg["N"], cfg["seed"]
+    Xd = inputs.matrix_torch(seed, M, K, "R", 0, device="cuda")
+    Wd = inputs.matrix_torch(seed + inputs.W_STREAM, N, K, "R", inputs.W_SCALE_EXP, device="cuda")
+    X, W = Xd.cpu().numpy(), Wd.cpu().numpy()
+    k = inputs.keys(8000, np.arange(400, dtype=np.uint64))
+    I = np.unique(np.concatenate([(k[:200] % np.uint64(M)).astype(np.int64), [0, M // 2 - 1, M // 2, M - 1]]))
+    J = np.unique(np.concatenate([(k[200:] % np.uint64(N)).astype(np.int64), [0, N // 2 - 1, N // 2, N - 1]]))
+    V = pm1(8001, N, 2)
+    for dtype, t in ((jg.JG_BF16, 1), (jg.JG_BF16X3, 3)):
+        # references from the rounded operands: sampled entries one by one, and Y v = X (W^T v) in double
+        if t == 1:
+            planes = [(oracle.round_bf16(X), oracle.round_bf16(W))]
+        else:
+            Xh, Xl = oracle.split_bf16(X)
+            Wh, Wl = oracle.split_bf16(W)
+            planes = [(Xh, Wh), (Xh, Wl), (Xl, Wh)]
+        want = np.zeros((I.size, J.size))
+        mag = np.zeros((I.size, J.size))
+        fre = np.zeros((M, 2))
+        frb = np.zeros((M, 2))
+        for A, B in planes:
+            want += oracle.linear(A[I], B[J])
+            mag += oracle.magnitude(A[I], B[J])
+            A64, B64 = A.astype(np.float64), B.astype(np.float64)
+            fre += A64 @ (B64.T @ V)
+            frb += np.abs(A64) @ (np.abs(B64).T @ np.abs(V))
+            del A64, B64
+        del planes
+        note(capsys, f"reduced precision, terms={t}: references ready")
+        for ways in (1, 4):
+            with JigsawLinear(M, K, N, ways, dtype=dtype) as L:
+                if L.ws_bytes:
+                    L.ws.fill_(0xFF)
+                L.shard(Xd, Wd)
+                L.forward()
+                Y = L.gather()
+                torch.cuda.synchronize()
+                Y = Y.cpu().numpy()
+            assert np.isfinite(Y).all()
+            err = np.abs(Y.astype(np.float64) @ V - fre)
+            assert np.all(err <= TOL * frb), f"ways={ways}: Freivalds worst {(err / frb).max():.3e}"
+            e = np.abs(Y[np.ix_(I, J)] - want) / mag
+            assert e.max() <= TOL, (ways, e.max())
+            note(capsys, f"terms={t} ways={ways}: Freivalds {(err / frb).max():.2e}, {e.size} entries max err/S {e.max():.2e}")
