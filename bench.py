@@ -21,6 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X dense FP32 matrix peak
+BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense BF16 matrix peak
 HBM_PEAK_GBPS = 8000.0
 
 
@@ -37,6 +38,10 @@ def parse():
                          "(GELU between two layers, residual) at the channel-mixing size; mixing: the same behind a layer norm "
                          "(the channel-mixing half of a mixing block); encoder: patch rearrangement of a "
                          "field + linear layer at the 1B model's encoder size (these ignore --config)")
+    ap.add_argument("--dtype", choices=["f32", "bf16", "bf16x3"], default="f32",
+                    help="forward only: f32 (the headline), or a reduced-precision mode: operands rounded to bfloat16 "
+                         "when they are sharded (bf16), or split in two bfloat16 parts and multiplied in three "
+                         "passes (bf16x3)")
     ap.add_argument("--combine", choices=["fused", "separate"], default="fused")
     ap.add_argument("--weights", choices=["copy", "direct"], default="copy")
     ap.add_argument("--tail", choices=["split", "whole"], default="split",
@@ -103,7 +108,8 @@ def measure(cfg, ways, args, X, W, streaming=False):
     combine = jg.JG_COMBINE_FUSED if args.combine == "fused" else jg.JG_COMBINE_SEPARATE
     weights = jg.JG_WEIGHTS_COPY if args.weights == "copy" else jg.JG_WEIGHTS_DIRECT
     out = {}
-    with JigsawLinear(M, K, N, ways, combine=combine, weights=weights, tail=tail_of(args)) as L:
+    dtype = {"f32": jg.JG_F32, "bf16": jg.JG_BF16, "bf16x3": jg.JG_BF16X3}[args.dtype]
+    with JigsawLinear(M, K, N, ways, combine=combine, weights=weights, tail=tail_of(args), dtype=dtype) as L:
         L.shard(X, W)
         sec, gemm_ms, gemm_n, wcopy_ms, comb_ms = time_forward(L, jg, args.steps, args.warmup)
         other_ms = wcopy_ms + comb_ms
@@ -133,7 +139,8 @@ def measure(cfg, ways, args, X, W, streaming=False):
             jg.jg_profile(L.ctx, False)
             sh_ms, sh_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_SHARD)
             ga_ms, ga_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_GATHER)
-            stream["shard_x_gbps"] = 8.0 * M * K / (sh_ms / sh_n * 1e-3) / 1e9
+            shard_bytes = {"f32": 8.0, "bf16": 6.0, "bf16x3": 8.0}[args.dtype]   # read FP32, write the shard format
+            stream["shard_x_gbps"] = shard_bytes * M * K / (sh_ms / sh_n * 1e-3) / 1e9
             stream["gather_y_gbps"] = 8.0 * M * N / (ga_ms / ga_n * 1e-3) / 1e9
             stream["shard_x_frac"] = stream["shard_x_gbps"] / HBM_PEAK_GBPS
             stream["gather_y_frac"] = stream["gather_y_gbps"] / HBM_PEAK_GBPS
@@ -143,7 +150,7 @@ def measure(cfg, ways, args, X, W, streaming=False):
         # One rank's share at its real shape: its two block products, alone on the GPU
         # (what one GPU of an n-GPU node would run per layer, exchange excluded).
         Mr, Kr, Nr = (M, K // 2, N // 2) if ways == 2 else (M // 2, K // 2, N // 2)
-        with JigsawLinear(Mr, Kr, Nr, 1) as R:
+        with JigsawLinear(Mr, Kr, Nr, 1, dtype=dtype) as R:
             R.shard(X[:Mr, :Kr], W[:Nr, :Kr])
             for _ in range(2 * args.warmup):
                 R.forward()
@@ -453,8 +460,9 @@ def cpu_baseline_backward(cfg, seconds):
                        f"{dt:.1f} s, fp64 loops")
 
 
-def cpu_baseline(cfg, seconds):
-    """The oracle as it stands, timed on a bounded sample of rows of the same workload."""
+def cpu_baseline(cfg, seconds, reduced_terms=0):
+    """The oracle as it stands, timed on a bounded sample of rows of the same workload (reduced_terms = 1 or 3:
+    the reduced-precision layer, operands rounded or split first)."""
     import numpy as np
     import oracle
     from paper_2507_05753_amd import inputs
@@ -469,14 +477,20 @@ def cpu_baseline(cfg, seconds):
     rows = int(min(M, max(probe, rate * seconds)))
     rows = max(cores, rows // cores * cores)
     rows = min(rows, M)
+    if reduced_terms == 3:
+        rows = max(cores, rows // 3 // cores * cores)
     Xs = inputs.matrix(seed, M, K, cfg["x_mode"], row_begin=0, row_end=rows)
     t0 = time.perf_counter()
-    Y = oracle.linear_rows(Xs, W, None, 0, rows, nthreads=cores)
+    if reduced_terms:
+        Y = oracle.linear_reduced(Xs, W, None, reduced_terms, nthreads=cores)
+    else:
+        Y = oracle.linear_rows(Xs, W, None, 0, rows, nthreads=cores)
     dt = time.perf_counter() - t0
     assert np.isfinite(Y).all()
+    how = {0: "fp64 triple loop", 1: "bfloat16 rounding + fp64 triple loop",
+           3: "bfloat16 split + three fp64 triple loops"}[reduced_terms]
     return dict(value=rows * K / dt, unit="items/s", cores=cores, kind="oracle",
-                sample=f"rows 0..{rows - 1} of X ({rows} x {K}) against all of W ({N} x {K}), "
-                       f"{dt:.1f} s, fp64 triple loop")
+                sample=f"rows 0..{rows - 1} of X ({rows} x {K}) against all of W ({N} x {K}), {dt:.1f} s, {how}")
 
 
 # HBM-side bytes per GEMM launch, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by
@@ -499,6 +513,9 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     from paper_2507_05753_amd import inputs
+    if args.dtype != "f32" and args.op != "forward":
+        print("bench.py: --dtype bf16 / bf16x3 goes with --op forward only", file=sys.stderr)
+        sys.exit(2)
 
     if args.op == "xtw":
         xc = inputs.XTW_CONFIGS["token_mixing_1b"]
@@ -653,8 +670,14 @@ def main():
     del X, W
     torch.cuda.empty_cache()
 
-    workload = f"config {args.config}: Y = X W^T, M={M} K={K} N={N}, {args.ways}-way Jigsaw, fp32"
-    achieved = head["gemm_tflops"]
+    reduced = args.dtype != "f32"
+    terms = 3 if args.dtype == "bf16x3" else 1
+    workload = (f"config {args.config}: Y = X W^T, M={M} K={K} N={N}, {args.ways}-way Jigsaw, "
+                + {"f32": "fp32", "bf16": "operands rounded to bfloat16, fp32 sums",
+                   "bf16x3": "operands split into two bfloat16 parts, three products, fp32 sums"}[args.dtype])
+    # the matrix cores' work: the split mode multiplies three times per product of the layer
+    achieved = head["gemm_tflops"] * terms if head["gemm_tflops"] else None
+    peak = BF16_MFMA_PEAK_TFLOPS if reduced else FP32_MFMA_PEAK_TFLOPS
     line = {
         "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
         "value": head["items_per_s"],
@@ -666,20 +689,20 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "bf16" if reduced else "f32",
         "data": "synthetic",
         "config": {"workload": workload, "n_items": M * K, "ways": args.ways, "M": M, "K": K, "N": N,
                    "seed": cfg["seed"], "x_values": cfg["x_mode"], "combine": args.combine,
-                   "weights": args.weights, "tail": args.tail},
+                   "weights": args.weights, "tail": args.tail, "mode": args.dtype},
         "tflops": head["tflops"],
         "hbm_algo_gbps": head["hbm_algo_gbps"],
         "hbm_algo_frac_of_8TBps": head["hbm_algo_frac"],
         "roofline": {
-            "bound": "mfma", "kernel": "jg::gemm_f32_stream<false, false, false>",
-            "achieved": achieved, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": achieved / FP32_MFMA_PEAK_TFLOPS if achieved else None,
+            "bound": "mfma", "kernel": "jg::gemm_bf16_nt" if reduced else "jg::gemm_f32_stream<false, false, false>",
+            "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+            "frac": achieved / peak if achieved else None,
             "avg_launch_ms": head["gemm_avg_launch_ms"], "launches": head["gemm_launches_timed"],
-            "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((f"config{args.config}", args.ways)),
+            "traffic": None if reduced else MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((f"config{args.config}", args.ways)),
             "traffic_unit": "bytes per launch",
         },
         "other_kernels_ms_per_step": head["other_kernels_ms_per_step"],
@@ -693,8 +716,10 @@ def main():
         line["streaming"]["combine_frac"] = head["combine_gbps"] / HBM_PEAK_GBPS
     if by_ways:
         line["by_ways"] = by_ways
+    if reduced:
+        line["roofline"]["matrix_passes"] = terms
     if args.cpu_seconds > 0:
-        line["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds)
+        line["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds, terms if reduced else 0)
     print(json.dumps(line), flush=True)
 
 

@@ -38,12 +38,13 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int HB_BM = 256;
 constexpr int HB_BN = 256;
-constexpr int HB_BK = 64;                                 // bfloat16 elements per slab row = 128 bytes
+constexpr int HB_BK = 32;                                 // bfloat16 elements per slab row = 64 bytes
 constexpr int HB_THREADS = 256;
-constexpr int HB_OPERAND_BYTES = HB_BM * HB_BK * 2;       // one slab of one operand = 32 KiB (BM == BN)
+constexpr int HB_OPERAND_BYTES = HB_BM * HB_BK * 2;       // one slab of one operand = 16 KiB (BM == BN)
 constexpr int HB_STAGE_BYTES = 2 * HB_OPERAND_BYTES;      // A and B
+constexpr int HB_STAGES = 4;                              // slab buffers in LDS: 128 KiB
 constexpr int HB_BAND_ROWS = 4;                           // row-tiles per band of the tile order
-constexpr int HB_TRANSFERS = HB_OPERAND_BYTES / (HB_THREADS * 16);   // 8 per lane, operand and slab
+constexpr int HB_TRANSFERS = HB_OPERAND_BYTES / (HB_THREADS * 16);   // 4 per lane, operand and slab
 
 struct HbGroup {
     GemmProblem p[kMaxGroup];   // A, B point at bfloat16 data; lda, ldb count 4-byte units (bfloat16 pairs)
@@ -70,10 +71,25 @@ __device__ __forceinline__ TileCoord hb_decode_tile(const HbGroup& g, int lid)
     return c;
 }
 
-// One operand's slabs, global -> LDS.  Transfer t of a lane covers row 32 t + 8 wave + lane / 8
-// of the tile (eight lanes per 128-byte row).
+typedef int hb_int4 __attribute__((ext_vector_type(4)));
+
+// One 16-byte-per-lane transfer global -> LDS: lane l's data lands at lds_base + 16 l.  Written as
+// an instruction rather than through the compiler's builtin: for the builtin the compiler makes every
+// later LDS read wait until ALL transfers in flight have landed, which would undo the prefetch
+// distance; here the kernel's own vmcnt waits say which slab must have arrived.  M0 carries the LDS
+// address (the compiler keeps nothing in M0 across statements).
+__device__ __forceinline__ void hb_transfer(const hb_int4& rsrc, unsigned lds_base, int voffset, int soffset)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset)
+                 : "memory");
+}
+
+// One operand's slabs, global -> LDS.  Transfer t of a lane covers row 64 t + 16 wave + lane / 4
+// of the tile (four lanes per 64-byte slab row).
 struct HbLoader {
-    __amdgpu_buffer_rsrc_t rsrc;
+    hb_int4 rsrc;               // raw buffer descriptor over the tile's valid rows, in scalar registers
     int voff[HB_TRANSFERS];     // byte offset of the lane's chunk in slab 0, or kOutOfBuffer for rows past the operand
     int chunk_k;                // first k (within a slab) of the chunk this lane fetches
     // row_bytes: the bytes of a row that exist (all planes)
@@ -81,116 +97,80 @@ struct HbLoader {
                                          int lane)
     {
         const int valid = min(HB_BM, extent - origin);
-        const int r = wave * 8 + (lane >> 3);
-        const int chunk = (lane & 7) ^ ((r >> 1) & 7);
+        const int r = wave * 16 + (lane >> 2);
+        const int chunk = (lane & 3) ^ ((r >> 2) & 3);
         chunk_k = chunk * 8;
 #pragma unroll
         for (int t = 0; t < HB_TRANSFERS; ++t) {
-            const int row = t * 32 + r;
+            const int row = t * 64 + r;
             voff[t] = row < valid ? row * ld * 4 + chunk * 16 : kOutOfBuffer;
         }
         // The descriptor spans the tile's valid rows.  A slab's column offset travels in the scalar
         // offset: the kernel only issues transfers whose chunk exists, so nothing depends on whether
         // the hardware counts that offset in its range check.
-        const int64_t bytes = (int64_t)(valid - 1) * ld * 4 + row_bytes;
-        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base + (int64_t)origin * ld), 0, (int)bytes,
-                                                 kBufferRsrcFlags);
+        const uintptr_t first = reinterpret_cast<uintptr_t>(base + (int64_t)origin * ld);
+        rsrc.x = __builtin_amdgcn_readfirstlane((int)(uint32_t)first);
+        rsrc.y = __builtin_amdgcn_readfirstlane((int)((first >> 32) & 0xffff));      // stride 0: raw buffer
+        rsrc.z = __builtin_amdgcn_readfirstlane((int)((int64_t)(valid - 1) * ld * 4 + row_bytes));
+        rsrc.w = kBufferRsrcFlags;
     }
-    // transfer t of the slab whose first column (in bytes, plane offset included) is col_bytes; every chunk
-    // of the slab lies below K
-    __device__ __forceinline__ void issue(int t, int col_bytes, char* operand_slab, int wave) const
-    {
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(operand_slab + t * 4096 + wave * 1024), 16, voff[t],
-                                                 col_bytes, 0, 0);
-    }
-    // the same for a slab of which only the first `cols` columns exist
-    __device__ __forceinline__ void issue_ragged(int t, int col_bytes, int cols, char* operand_slab, int wave) const
+    // transfer t of the slab whose first column (in bytes, plane offset included) is col_bytes; of a ragged
+    // slab (cols < HB_BK columns exist) the chunks at or past `cols` are fetched from outside the buffer
+    __device__ __forceinline__ void issue(int t, int col_bytes, int cols, unsigned operand_slab, int wave) const
     {
         const int vo = chunk_k < cols ? voff[t] : kOutOfBuffer;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(operand_slab + t * 4096 + wave * 1024), 16, vo,
-                                                 col_bytes, 0, 0);
+        hb_transfer(rsrc, operand_slab + t * 4096 + wave * 1024, vo, col_bytes);
     }
 };
 
-// acc = addend tile (the partial product received from the peer), or zero.
-// m0, n0: the tile's origin; row_off, col_off: the lane's first row and its column inside the tile.
-__device__ __forceinline__ void hb_init_acc(const GemmProblem& P, int M, int N, int m0, int n0, int row_off, int col_off,
-                                            bool interior, floatx16 (&acc)[4][4])
-{
-    const int row_base = m0 + row_off, col_base = n0 + col_off;
-    const float* __restrict__ addend = P.addend;
-    if (!addend) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-        return;
-    }
-    const int ldadd = P.ldadd;
-    if (interior && ldadd <= kMaxDirectLd / 2) {
-        // lane position in one vector offset, the row of each access in a scalar offset
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<float*>(addend + (int64_t)m0 * ldadd + n0), 0, ((HB_BM - 1) * ldadd + HB_BN) * 4, kBufferRsrcFlags);
-        const int lane_off = (row_off * ldadd + col_off) * 4;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    acc[i][j][v] = __builtin_bit_cast(
-                        float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, lane_off + j * 128,
-                                                                    (i * 32 + 8 * (v >> 2) + (v & 3)) * ldadd * 4, 0));
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int col = col_base + j * 32;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = row_base + i * 32 + 8 * (v >> 2) + (v & 3);
-                    acc[i][j][v] = (row < M && col < N) ? addend[(int64_t)row * ldadd + col] : 0.f;
-                }
-            }
-    }
-}
-
-// C = act(acc + bias) + residual.
+// C = act(acc + addend + bias) + residual for the wave's 128 x 128 part of the tile at (m0, n0).
+// row_off, col_off: the lane's first row and its column inside the tile.  The addend is the partial
+// product received from the peer (Eqs. (2), (4)): (kept + received) + bias, the order of the separate
+// combine kernel.
 __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N, int m0, int n0, int row_off, int col_off,
                                               bool interior, const floatx16 (&acc)[4][4], int act)
 {
     const int row_base = m0 + row_off, col_base = n0 + col_off;
     const float* __restrict__ bias = P.bias;
     const float* __restrict__ residual = P.residual;
+    const float* __restrict__ addend = P.addend;
     float* __restrict__ C = P.C;
-    const int ldc = P.ldc, ldres = P.ldres;
-    if (interior && ldc <= kMaxDirectLd / 2 && (!residual || ldres <= kMaxDirectLd / 2)) {
+    const int ldc = P.ldc, ldres = P.ldres, ldadd = P.ldadd;
+    constexpr int kMaxLd = kMaxDirectLd / 2;      // keeps 256 rows * ld * 4 B below 2^31
+    if (interior && ldc <= kMaxLd && (!residual || ldres <= kMaxLd) && (!addend || ldadd <= kMaxLd)) {
+        // lane position in one vector offset, the row of each access in a scalar offset: no address arithmetic
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             C + (int64_t)m0 * ldc + n0, 0, ((HB_BM - 1) * ldc + HB_BN) * 4, kBufferRsrcFlags);
         const __amdgpu_buffer_rsrc_t res_rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<float*>(residual ? residual + (int64_t)m0 * ldres + n0 : C), 0,
             residual ? ((HB_BM - 1) * ldres + HB_BN) * 4 : 0, kBufferRsrcFlags);
+        const __amdgpu_buffer_rsrc_t add_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(addend ? addend + (int64_t)m0 * ldadd + n0 : C), 0,
+            addend ? ((HB_BM - 1) * ldadd + HB_BN) * 4 : 0, kBufferRsrcFlags);
         const int lane_off = (row_off * ldc + col_off) * 4;
         const int res_off = (row_off * ldres + col_off) * 4;
+        const int add_off = (row_off * ldadd + col_off) * 4;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float bj = bias ? bias[col_base + j * 32] : 0.f;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                float res[16];
-                if (residual) {
+                float add[16], res[16];
 #pragma unroll
-                    for (int v = 0; v < 16; ++v)
+                for (int v = 0; v < 16; ++v) {
+                    const int row = i * 32 + 8 * (v >> 2) + (v & 3);
+                    if (addend)
+                        add[v] = __builtin_bit_cast(
+                            float, __builtin_amdgcn_raw_buffer_load_b32(add_rsrc, add_off + j * 128, row * ldadd * 4, 0));
+                    if (residual)
                         res[v] = __builtin_bit_cast(
-                            float, __builtin_amdgcn_raw_buffer_load_b32(res_rsrc, res_off + j * 128,
-                                                                        (i * 32 + 8 * (v >> 2) + (v & 3)) * ldres * 4, 0));
+                            float, __builtin_amdgcn_raw_buffer_load_b32(res_rsrc, res_off + j * 128, row * ldres * 4, 0));
                 }
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    float y = activate(acc[i][j][v] + bj, act);
+                    float y = acc[i][j][v];
+                    if (addend) y += add[v];
+                    y = activate(y + bj, act);
                     if (residual) y += res[v];
                     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rsrc, lane_off + j * 128,
                                                           (i * 32 + 8 * (v >> 2) + (v & 3)) * ldc * 4, 0);
@@ -209,7 +189,9 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
                 for (int v = 0; v < 16; ++v) {
                     const int row = row_base + i * 32 + 8 * (v >> 2) + (v & 3);
                     if (row < M) {
-                        float y = activate(acc[i][j][v] + bj, act);
+                        float y = acc[i][j][v];
+                        if (addend) y += addend[(int64_t)row * ldadd + col];
+                        y = activate(y + bj, act);
                         if (residual) y += residual[(int64_t)row * ldres + col];
                         C[(int64_t)row * ldc + col] = y;
                     }
@@ -221,9 +203,11 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
 // grid: kNumXcd * per_xcd workgroups; consecutive ids land on different XCDs, so the id is folded
 // into a per-XCD contiguous range of tiles, walked column-major inside bands of 4 row-tiles: the 32
 // tiles an XCD has in flight form a 4 x 8 block that shares 4 A panels and 8 B panels in its L2.
+// PARTS (measurement only; anything but 3 gives wrong results): bit 0 = issue the slab transfers, bit 1 = multiply.
+template <int PARTS = 3>
 __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
 {
-    __shared__ __align__(1024) char slab[2 * HB_STAGE_BYTES];
+    __shared__ __align__(1024) char slab[HB_STAGES * HB_STAGE_BYTES];
 
     const int lid = (blockIdx.x % kNumXcd) * g.per_xcd + blockIdx.x / kNumXcd;
     if (lid >= g.total) return;
@@ -236,6 +220,7 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
     const int lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1;
     const int lr = lane & 31, lk = lane >> 5;
+    const unsigned slab_lds = (unsigned)reinterpret_cast<uintptr_t>((lds_void*)slab);   // LDS address of the buffers
 
     HbLoader load_a, load_b;
     const int row_bytes = (g.terms == 3 ? 2 : 1) * K * 2;
@@ -248,61 +233,113 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
     const int nkt = (K + HB_BK - 1) / HB_BK;
     const int total_slabs = nkt * g.terms;
     const int last_cols = K - (nkt - 1) * HB_BK;            // columns of a pass's last slab
-    auto request = [&](int it, char* stage) __attribute__((always_inline)) {
-        const int pass = it / nkt, kt = it - pass * nkt;
-        const int a_col = (kt * HB_BK + ((g.terms == 3 && pass == 1) ? K : 0)) * 2;
-        const int b_col = (kt * HB_BK + ((g.terms == 3 && pass == 0) ? K : 0)) * 2;
-        if (kt == nkt - 1 && last_cols < HB_BK) {
+    // The slab to request next, walked without divisions.  Past the end it stays on the last slab: the
+    // surplus requests re-read that slab into buffers nobody reads again, so that the number of
+    // transfers in flight is the same in every iteration and one wait count fits all.
+    int req_kt = 0, req_pass = 0;
+    struct SlabRef { int a_col, b_col, cols; };
+    auto next_request = [&]() __attribute__((always_inline)) {
+        SlabRef r;
+        r.a_col = (req_kt * HB_BK + ((g.terms == 3 && req_pass == 1) ? K : 0)) * 2;
+        r.b_col = (req_kt * HB_BK + ((g.terms == 3 && req_pass == 0) ? K : 0)) * 2;
+        r.cols = req_kt == nkt - 1 ? last_cols : HB_BK;
+        if (req_kt + 1 < nkt) {
+            ++req_kt;
+        } else if (req_pass + 1 < g.terms) {
+            req_kt = 0;
+            ++req_pass;
+        }
+        return r;
+    };
+    auto request_all = [&](int buf) __attribute__((always_inline)) {
+        const unsigned stage = slab_lds + buf * HB_STAGE_BYTES;
+        const SlabRef r = next_request();
 #pragma unroll
-            for (int t = 0; t < HB_TRANSFERS; ++t) {
-                load_a.issue_ragged(t, a_col, last_cols, stage, wave);
-                load_b.issue_ragged(t, b_col, last_cols, stage + HB_OPERAND_BYTES, wave);
-            }
-        } else {
-#pragma unroll
-            for (int t = 0; t < HB_TRANSFERS; ++t) {
-                load_a.issue(t, a_col, stage, wave);
-                load_b.issue(t, b_col, stage + HB_OPERAND_BYTES, wave);
-            }
+        for (int t = 0; t < HB_TRANSFERS; ++t) {
+            load_a.issue(t, r.a_col, r.cols, stage, wave);
+            load_b.issue(t, r.b_col, r.cols, stage + HB_OPERAND_BYTES, wave);
         }
     };
-
-    request(0, slab);
+#pragma unroll
+    for (int p = 0; p < HB_STAGES - 1; ++p) request_all(p);
 
     const bool interior = tc.m0 + HB_BM <= M && tc.n0 + HB_BN <= N;
     const int row_off = wm * 128 + 4 * lk;      // the lane's first row and its column inside the tile
     const int col_off = wn * 128 + lr;
     floatx16 acc[4][4];
-    hb_init_acc(P, M, N, tc.m0, tc.n0, row_off, col_off, interior, acc);
-
-    // fragment k-step s (16 k) of block b: row 32 b + lr, chunks 2 s + lk
-    int frag_off[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) frag_off[s] = lr * 128 + (((2 * s + lk) ^ ((lr >> 1) & 7)) << 4);
-    const int a_frag = wm * 4 * 4096;                          // the wave's four row blocks of A
-    const int b_frag = HB_OPERAND_BYTES + wn * 4 * 4096;       // ... and four column blocks of B
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+    // fragment k-step s (16 k) of block b: row 32 b + lr (64-byte rows), chunks 2 s + lk
+    int frag_off[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) frag_off[s] = lr * 64 + (((2 * s + lk) ^ ((lr >> 2) & 3)) << 4);
+    const int a_frag = wm * 4 * 2048;                          // the wave's four row blocks of A
+    const int b_frag = HB_OPERAND_BYTES + wn * 4 * 2048;       // ... and four column blocks of B
+    auto read_frags = [&](const char* stage, int s, bf16x8 (&fa)[4], bf16x8 (&fb)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            fa[b] = *reinterpret_cast<const bf16x8*>(stage + a_frag + b * 2048 + frag_off[s]);
+            fb[b] = *reinterpret_cast<const bf16x8*>(stage + b_frag + b * 2048 + frag_off[s]);
+        }
+    };
+
+    bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];      // operands of a slab's first / second k-step
+    // transfers complete in order: slab 0 has landed once at most those of the later requests are in flight
+    JG_WAIT_VMCNT(2 * HB_TRANSFERS * (HB_STAGES - 2));
+    __syncthreads();
+    read_frags(slab, 0, fa0, fb0);
+
+    int cur_buf = 0;
     for (int it = 0; it < total_slabs; ++it) {
-        char* cur = slab + (it & 1) * HB_STAGE_BYTES;
-        char* nxt = slab + ((it + 1) & 1) * HB_STAGE_BYTES;
-        __builtin_amdgcn_s_waitcnt(0);     // this lane's transfers of slab `it` have landed
-        __syncthreads();                   // everyone's have, and everyone is done reading the other buffer
-        if (it + 1 < total_slabs) request(it + 1, nxt);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            bf16x8 fa[4], fb[4];
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                fa[b] = *reinterpret_cast<const bf16x8*>(cur + a_frag + b * 4096 + frag_off[s]);
-                fb[b] = *reinterpret_cast<const bf16x8*>(cur + b_frag + b * 4096 + frag_off[s]);
-            }
+        const int nxt_buf = cur_buf + 1 == HB_STAGES ? 0 : cur_buf + 1;
+        const int req_buf = cur_buf == 0 ? HB_STAGES - 1 : cur_buf - 1;       // = (it + HB_STAGES - 1) % HB_STAGES
+        const char* cur = slab + cur_buf * HB_STAGE_BYTES;
+        const char* nxt = slab + nxt_buf * HB_STAGE_BYTES;
+        read_frags(cur, 1, fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+        // first k-step, with the transfers of slab it + HB_STAGES - 1 between the MFMAs.  Their buffer
+        // held slab it - 1, which every wavefront had finished reading before the last barrier.
+        {
+            const unsigned stage = slab_lds + req_buf * HB_STAGE_BYTES;
+            const SlabRef r = next_request();
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < 4; ++j) {
+                    if (PARTS & 2)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
+                    const int idx = i * 4 + j;
+                    if ((PARTS & 1) && (idx & 1) == 0) {
+                        const int t = (idx >> 1) & 3;
+                        if (idx < 8) load_a.issue(t, r.a_col, r.cols, stage, wave);
+                        else load_b.issue(t, r.b_col, r.cols, stage + HB_OPERAND_BYTES, wave);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
         }
+        // Slab it + 1 has landed once at most the transfers of the two later slabs are in flight; this
+        // wavefront's reads of slab `it` are complete, so after the barrier slab it + 1 may be read by
+        // all and slab it's buffer may be refilled.
+        if (PARTS & 1) JG_WAIT_VMCNT(2 * HB_TRANSFERS * (HB_STAGES - 2));
+        __builtin_amdgcn_s_waitcnt(0xC07F);    // lgkmcnt(0) only
+        __syncthreads();
+        read_frags(nxt, 0, fa0, fb0);          // (after the last slab: a surplus copy, read but not used)
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (PARTS & 2)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        cur_buf = nxt_buf;
     }
+    JG_WAIT_VMCNT(0);       // the surplus transfers have landed before the buffers are given up
     hb_store_tile(P, M, N, tc.m0, tc.n0, row_off, col_off, interior, acc, g.act);
 }
 
@@ -314,9 +351,8 @@ inline bool hb_operand_ok(const float* p, int ld, int K)
 
 // One grouped launch.  Preconditions (checked by the C-ABI layer when the plan is made): every
 // operand passes hb_operand_ok; 1 <= nprob <= 4; M, N, K >= 1.
-inline hipError_t launch_gemm_bf16_group(const GemmGroup& src, int terms, hipStream_t stream)
+inline hipError_t make_bf16_group(const GemmGroup& src, int terms, HbGroup& g)
 {
-    HbGroup g;
     for (int i = 0; i < kMaxGroup; ++i) g.p[i] = src.p[i];
     g.nprob = src.nprob;
     g.M = src.M;
@@ -333,7 +369,15 @@ inline hipError_t launch_gemm_bf16_group(const GemmGroup& src, int terms, hipStr
             return hipErrorInvalidValue;
     g.total = (int)total;
     g.per_xcd = (g.total + kNumXcd - 1) / kNumXcd;
-    hipLaunchKernelGGL(gemm_bf16_nt, dim3((unsigned)(kNumXcd * g.per_xcd)), dim3(HB_THREADS), 0, stream, g);
+    return hipSuccess;
+}
+
+inline hipError_t launch_gemm_bf16_group(const GemmGroup& src, int terms, hipStream_t stream)
+{
+    HbGroup g;
+    const hipError_t e = make_bf16_group(src, terms, g);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(gemm_bf16_nt<3>, dim3((unsigned)(kNumXcd * g.per_xcd)), dim3(HB_THREADS), 0, stream, g);
     return hipGetLastError();
 }
 
