@@ -52,9 +52,16 @@ struct HbGroup {
     int nprob;
     int M, N, K;                // K counts bfloat16 elements of one plane
     int terms;                  // 1, or 3 for split operands
-    int tiles_m, tiles_n, total, per_xcd;
+    int tiles_m, tiles_n, total;
+    int whole;                  // tiles [0, whole) get a workgroup each; per_xcd = ceil(whole / 8)
+    int per_xcd;
+    // split tail (parts = 0: none): each of the tiles [whole, total) is cut into `parts` runs of slabs, one
+    // workgroup per run, which leaves its raw sums in scratch tile (tile - whole) * parts + part
+    int parts;
+    float* scratch;             // 256 x 256 floats per run
     int act;
 };
+constexpr int HB_TILE_FLOATS = HB_BM * HB_BN;
 
 __device__ __forceinline__ TileCoord hb_decode_tile(const HbGroup& g, int lid)
 {
@@ -202,11 +209,25 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
 {
     __shared__ __align__(1024) char slab[HB_STAGES * HB_STAGE_BYTES];
 
-    const int lid = (blockIdx.x % kNumXcd) * g.per_xcd + blockIdx.x / kNumXcd;
-    if (lid >= g.total) return;
+    const int M = g.M, N = g.N, K = g.K;
+    const int nkt = (K + HB_BK - 1) / HB_BK;
+    const int tile_slabs = nkt * g.terms;
+    // The first 8 * per_xcd workgroups take whole tiles; the rest are the runs of the split tail, in
+    // launch order (so they spread over the XCDs and start last).
+    int lid, s_begin = 0, s_end = tile_slabs, run = -1;
+    if ((int)blockIdx.x < kNumXcd * g.per_xcd) {
+        lid = (blockIdx.x % kNumXcd) * g.per_xcd + blockIdx.x / kNumXcd;
+        if (lid >= g.whole) return;
+    } else {
+        run = blockIdx.x - kNumXcd * g.per_xcd;
+        const int t = run / g.parts, part = run - t * g.parts;
+        lid = g.whole + t;
+        if (lid >= g.total) return;
+        s_begin = (int)((int64_t)tile_slabs * part / g.parts);
+        s_end = (int)((int64_t)tile_slabs * (part + 1) / g.parts);
+    }
     const TileCoord tc = hb_decode_tile(g, lid);
     const GemmProblem& P = g.p[tc.prob];
-    const int M = g.M, N = g.N, K = g.K;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -223,24 +244,24 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
     // The slab sequence: `terms` passes over K.  With split operands the two small cross terms go
     // first (A hi with B lo, then A lo with B hi) and hi with hi last: added to an already large sum,
     // the small products would lose their low bits at every step.
-    const int nkt = (K + HB_BK - 1) / HB_BK;
-    const int total_slabs = nkt * g.terms;
+    const int total_slabs = s_end - s_begin;                // slabs this workgroup multiplies
     const int last_cols = K - (nkt - 1) * HB_BK;            // columns of a pass's last slab
     // The slab to request next, walked without divisions.  Past the end it stays on the last slab: the
     // surplus requests re-read that slab into buffers nobody reads again, so that the number of
     // transfers in flight is the same in every iteration and one wait count fits all.
-    int req_kt = 0, req_pass = 0;
+    int req_pass = s_begin / nkt, req_kt = s_begin - req_pass * nkt, req_left = total_slabs;
     struct SlabRef { int a_col, b_col, cols; };
     auto next_request = [&]() __attribute__((always_inline)) {
         SlabRef r;
         r.a_col = (req_kt * HB_BK + ((g.terms == 3 && req_pass == 1) ? K : 0)) * 2;
         r.b_col = (req_kt * HB_BK + ((g.terms == 3 && req_pass == 0) ? K : 0)) * 2;
         r.cols = req_kt == nkt - 1 ? last_cols : HB_BK;
-        if (req_kt + 1 < nkt) {
-            ++req_kt;
-        } else if (req_pass + 1 < g.terms) {
-            req_kt = 0;
-            ++req_pass;
+        if (req_left > 1) {
+            --req_left;
+            if (++req_kt == nkt) {
+                req_kt = 0;
+                ++req_pass;
+            }
         }
         return r;
     };
@@ -332,9 +353,59 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
     }
     JG_WAIT_VMCNT(0);       // the surplus transfers have landed ...
     __syncthreads();        // ... and nobody reads a slab any more: the buffers become the waves' staging blocks
-    if (!(PARTS & 8) || acc[0][0][0] == 12345.f)
-        hb_store_tile(P, M, N, tc.m0, tc.n0, wm, wn, lr, lk, interior, acc, g.act,
-                      reinterpret_cast<float*>(slab + wave * (32 * HB_SHUFFLE_LD * 4)));
+    float* shuffle = reinterpret_cast<float*>(slab + wave * (32 * HB_SHUFFLE_LD * 4));
+    if ((PARTS & 8) && acc[0][0][0] != 12345.f) return;
+    if (run < 0) {
+        hb_store_tile(P, M, N, tc.m0, tc.n0, wm, wn, lr, lk, interior, acc, g.act, shuffle);
+    } else {                // a run of a split tile: raw sums into its scratch tile
+        GemmProblem raw = {};
+        raw.C = g.scratch + (int64_t)run * HB_TILE_FLOATS;
+        raw.ldc = HB_BN;
+        hb_store_tile(raw, HB_BM, HB_BN, 0, 0, wm, wn, lr, lk, true, acc, kActNone, shuffle);
+    }
+}
+
+// Second kernel of a launch with a split tail: adds a tile's runs in ascending k order, then what the
+// epilogue adds, and stores C.  grid: kHbJoinSlices workgroups per tail tile, each with a band of its rows.
+constexpr int kHbJoinSlices = 32;
+__global__ __launch_bounds__(HB_THREADS) void gemm_bf16_join(const HbGroup g)
+{
+    const int t = blockIdx.x / kHbJoinSlices, slice = blockIdx.x % kHbJoinSlices;
+    constexpr int kSliceFloats = HB_TILE_FLOATS / kHbJoinSlices;
+    const TileCoord tc = hb_decode_tile(g, g.whole + t);
+    const GemmProblem& P = g.p[tc.prob];
+    const float* runs = g.scratch + (int64_t)t * g.parts * HB_TILE_FLOATS;
+    const bool interior = tc.m0 + HB_BM <= g.M && tc.n0 + HB_BN <= g.N;
+    const bool vec_ok = (((uintptr_t)P.C | (uintptr_t)P.addend | (uintptr_t)P.residual | (uintptr_t)P.bias) & 15) == 0 &&
+                        ((P.ldc | (P.addend ? P.ldadd : 0) | (P.residual ? P.ldres : 0)) & 3) == 0;
+    if (interior && vec_ok) {
+        for (int u = slice * (kSliceFloats / 4) + threadIdx.x; u < (slice + 1) * (kSliceFloats / 4); u += HB_THREADS) {
+            const int r = u / (HB_BN / 4), c = (u - r * (HB_BN / 4)) * 4;
+            vf4 y = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(runs) + u);
+            for (int p = 1; p < g.parts; ++p)
+                y += __builtin_nontemporal_load(reinterpret_cast<const vf4*>(runs + (int64_t)p * HB_TILE_FLOATS) + u);
+            const int64_t row = tc.m0 + r;
+            const int col = tc.n0 + c;
+            if (P.addend) y += __builtin_nontemporal_load(reinterpret_cast<const vf4*>(P.addend + row * P.ldadd + col));
+            if (P.bias) y += *reinterpret_cast<const vf4*>(P.bias + col);
+            if (g.act) y = vf4{activate(y.x, g.act), activate(y.y, g.act), activate(y.z, g.act), activate(y.w, g.act)};
+            if (P.residual) y += *reinterpret_cast<const vf4*>(P.residual + row * P.ldres + col);
+            *reinterpret_cast<vf4*>(P.C + row * P.ldc + col) = y;
+        }
+    } else {
+        for (int u = slice * kSliceFloats + threadIdx.x; u < (slice + 1) * kSliceFloats; u += HB_THREADS) {
+            const int r = u / HB_BN, c = u - r * HB_BN;
+            const int64_t row = tc.m0 + r;
+            const int col = tc.n0 + c;
+            if (row >= g.M || col >= g.N) continue;
+            float y = runs[u];
+            for (int p = 1; p < g.parts; ++p) y += runs[(int64_t)p * HB_TILE_FLOATS + u];
+            if (P.addend) y += P.addend[row * P.ldadd + col];
+            y = activate(y + (P.bias ? P.bias[col] : 0.f), g.act);
+            if (P.residual) y += P.residual[row * P.ldres + col];
+            P.C[row * P.ldc + col] = y;
+        }
+    }
 }
 
 // Can this operand take the 16-byte transfers?  (rows 16-byte aligned, K in whole chunks)
@@ -345,7 +416,14 @@ inline bool hb_operand_ok(const float* p, int ld, int K)
 
 // One grouped launch.  Preconditions (checked by the C-ABI layer when the plan is made): every
 // operand passes hb_operand_ok; 1 <= nprob <= 4; M, N, K >= 1.
-inline hipError_t make_bf16_group(const GemmGroup& src, int terms, HbGroup& g)
+// `cus` workgroups run at a time.  When the tiles do not fill whole rounds of them, the tiles of the last
+// partial round are cut into runs of slabs so that every CU gets one (at least kHbMinRunSlabs slabs each);
+// scratch holds a 256 x 256 tile of floats per run, or is null / too small: then every tile stays whole.
+constexpr int kHbMinRunSlabs = 16;
+constexpr int kHbJoinCostSlabs = 40;    // the join kernel takes about as long as 40 slabs of the main loop
+inline size_t bf16_tail_scratch_bytes(int cus) { return (size_t)cus * HB_TILE_FLOATS * sizeof(float); }
+
+inline hipError_t make_bf16_group(const GemmGroup& src, int terms, int cus, float* scratch, size_t scratch_bytes, HbGroup& g)
 {
     for (int i = 0; i < kMaxGroup; ++i) g.p[i] = src.p[i];
     g.nprob = src.nprob;
@@ -362,16 +440,43 @@ inline hipError_t make_bf16_group(const GemmGroup& src, int terms, HbGroup& g)
         if (!hb_operand_ok(g.p[i].A, g.p[i].lda, g.K) || !hb_operand_ok(g.p[i].B, g.p[i].ldb, g.K))
             return hipErrorInvalidValue;
     g.total = (int)total;
-    g.per_xcd = (g.total + kNumXcd - 1) / kNumXcd;
+    g.whole = g.total;
+    g.parts = 0;
+    g.scratch = nullptr;
+    const int tile_slabs = (g.K + HB_BK - 1) / HB_BK * terms;
+    const int tail = cus > 0 ? g.total % cus : 0;
+    if (scratch && tail > 0 && 2 * tail <= cus) {
+        int parts = cus / tail;
+        if (parts > tile_slabs / kHbMinRunSlabs) parts = tile_slabs / kHbMinRunSlabs;
+        // worth it when the shortened last round saves at least twice what the join costs
+        const bool pays = parts >= 2 && tile_slabs - tile_slabs / parts >= 2 * kHbJoinCostSlabs;
+        if (pays && (size_t)tail * parts * HB_TILE_FLOATS * sizeof(float) <= scratch_bytes) {
+            g.whole = g.total - tail;       // a multiple of cus, hence of the number of XCDs
+            g.parts = parts;
+            g.scratch = scratch;
+        }
+    }
+    g.per_xcd = (g.whole + kNumXcd - 1) / kNumXcd;
     return hipSuccess;
 }
 
-inline hipError_t launch_gemm_bf16_group(const GemmGroup& src, int terms, hipStream_t stream)
+inline unsigned bf16_grid(const HbGroup& g) { return (unsigned)(kNumXcd * g.per_xcd + (g.total - g.whole) * g.parts); }
+
+// cus: compute units of the device (one workgroup each).  *needs_join: launch_gemm_bf16_join must follow.
+inline hipError_t launch_gemm_bf16_group(const GemmGroup& src, int terms, int cus, float* scratch, size_t scratch_bytes,
+                                         hipStream_t stream, HbGroup& g, bool* needs_join)
 {
-    HbGroup g;
-    const hipError_t e = make_bf16_group(src, terms, g);
+    *needs_join = false;
+    const hipError_t e = make_bf16_group(src, terms, cus, scratch, scratch_bytes, g);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(gemm_bf16_nt<3>, dim3((unsigned)(kNumXcd * g.per_xcd)), dim3(HB_THREADS), 0, stream, g);
+    hipLaunchKernelGGL(gemm_bf16_nt<3>, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);
+    *needs_join = g.parts > 0;
+    return hipGetLastError();
+}
+
+inline hipError_t launch_gemm_bf16_join(const HbGroup& g, hipStream_t stream)
+{
+    hipLaunchKernelGGL(gemm_bf16_join, dim3((unsigned)(g.total - g.whole) * kHbJoinSlices), dim3(HB_THREADS), 0, stream, g);
     return hipGetLastError();
 }
 

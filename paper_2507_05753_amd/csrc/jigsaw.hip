@@ -316,7 +316,10 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     // scratch for the split tail: the largest need over the launches of each pass
     p->slots = ctx ? ctx->slots : kDefaultSlots;
     p->tail_bytes = p->bw_tail_bytes = 0;
-    if (d.tail == JG_TAIL_SPLIT && !reduced) {      // the bfloat16 kernel runs whole tiles only
+    if (d.tail == JG_TAIL_SPLIT && reduced) {
+        // one 256 x 256 scratch tile per CU, when the launches of the pass can end in a partial round worth splitting
+        p->tail_bytes = jg::bf16_tail_scratch_bytes(p->slots / 2);
+    } else if (d.tail == JG_TAIL_SPLIT) {
         auto need = [&](int nprob, int64_t m, int64_t n, int64_t k) {
             const int64_t tiles = nprob * ((m + jg::BM - 1) / jg::BM) * ((n + jg::BN - 1) / jg::BN);
             return jg::tail_scratch_bytes(tiles, (int)k, p->slots);
@@ -574,8 +577,18 @@ static bool run_gemm(const jg_plan* plan, jg::GemmGroup& g, int layout, int kern
     jg_ctx* c = plan->ctx;
     bool join = false;
     if (plan->d.dtype != JG_F32) {
-        ScopedTimer t(c, kernel_class);
-        return HIP_OK(jg::launch_gemm_bf16_group(g, plan->d.dtype == JG_BF16X3 ? 3 : 1, c->stream));
+        jg::HbGroup hb;
+        {
+            ScopedTimer t(c, kernel_class);
+            if (!HIP_OK(jg::launch_gemm_bf16_group(g, plan->d.dtype == JG_BF16X3 ? 3 : 1, plan->slots / 2,
+                                                   reinterpret_cast<float*>(scratch), scratch_bytes, c->stream, hb, &join)))
+                return false;
+        }
+        if (join) {
+            ScopedTimer t(c, JG_KERNEL_JOIN);
+            if (!HIP_OK(jg::launch_gemm_bf16_join(hb, c->stream))) return false;
+        }
+        return true;
     }
     {
         ScopedTimer t(c, kernel_class);

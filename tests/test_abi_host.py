@@ -309,12 +309,18 @@ def test_reduced_precision_plans_account_for_their_shards():
         assert q(f, jg.JG_Q_HBM_BYTES_ALGO) == 4 * (M * K + N * K + M * N) + extra
         assert q(h, jg.JG_Q_HBM_BYTES_ALGO) == 2 * (M * K + N * K) + 4 * M * N + extra
         assert q(s, jg.JG_Q_HBM_BYTES_ALGO) == 4 * (M * K + N * K + M * N) + extra
-        assert q(h, jg.JG_Q_TAIL_SCRATCH_BYTES) == 0
+        # split tail of the bfloat16 kernel: one 256 x 256 scratch tile of floats per CU (256 CUs without a context)
+        assert q(h, jg.JG_Q_TAIL_SCRATCH_BYTES) == q(s, jg.JG_Q_TAIL_SCRATCH_BYTES) == 256 * 256 * 256 * 4
+        w = jg.jg_plan_create(None, M, K, N, ways, dtype=jg.JG_BF16, tail=jg.JG_TAIL_WHOLE)
+        assert q(w, jg.JG_Q_TAIL_SCRATCH_BYTES) == 0
+        assert q(w, jg.JG_Q_WORKSPACE_BYTES) == q(h, jg.JG_Q_WORKSPACE_BYTES) - q(h, jg.JG_Q_TAIL_SCRATCH_BYTES)
+        jg.jg_plan_destroy(w)
         with pytest.raises(jg.JigsawError) as e:
             q(h, jg.JG_Q_BACKWARD_WORKSPACE_BYTES)
         assert e.value.status == jg.JG_E_DTYPE
         if ways == 4:   # the received weight block is bfloat16 too
-            assert q(h, jg.JG_Q_WORKSPACE_BYTES) < q(f, jg.JG_Q_WORKSPACE_BYTES)
+            assert (q(h, jg.JG_Q_WORKSPACE_BYTES) - q(h, jg.JG_Q_TAIL_SCRATCH_BYTES)
+                    < q(f, jg.JG_Q_WORKSPACE_BYTES) - q(f, jg.JG_Q_TAIL_SCRATCH_BYTES))
         for p in (f, h, s):
             jg.jg_plan_destroy(p)
 

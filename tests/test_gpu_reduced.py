@@ -150,6 +150,41 @@ def test_epilogue_rides_along(jg, ctx, ways):
     assert np.all(np.abs(Y.astype(np.float64) - want) <= 1.5e-6 * S)
 
 
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+def test_split_tail_and_whole_tiles_agree(jg, ctx, dtype_name):
+    """Tiles of a last partial round are cut into runs of slabs that a second kernel adds in ascending k order:
+    another order of the FP32 additions (inside the tolerance), the same numbers on lattice inputs, and the same
+    bits from run to run."""
+    from paper_2507_05753_amd.layer import JigsawLinear
+    dtype = getattr(jg, dtype_name)
+    M, K, N = 300, 8208, 260          # 4 tiles of 257 (771 with split operands) slabs: cut into 16 runs each
+    t = terms_of(jg, dtype)
+    for mode in ("L", "R"):
+        X, W, b = inputs.layer_inputs(410, M, K, N, mode, bias=True)
+        R = inputs.matrix(411, M, N, mode)
+        want = oracle.gelu(oracle.linear_reduced(X, W, b, t)) + R if mode == "R" else oracle.linear(X, W, b) + R
+        S = oracle.linear_reduced(X, W, b, t, absolute=True) + np.abs(R)
+        got = {}
+        for tail in (jg.JG_TAIL_SPLIT, jg.JG_TAIL_WHOLE):
+            for ways in (1, 4):
+                with JigsawLinear(M, K, N, ways, bias=True, ctx=ctx, dtype=dtype, tail=tail) as L:
+                    assert (L.query(jg.JG_Q_TAIL_SCRATCH_BYTES) > 0) == (tail == jg.JG_TAIL_SPLIT)
+                    L.ws.fill_(0xFF)
+                    L.shard(dev(X), dev(W), dev(b))
+                    res = [torch.empty_like(y) for y in L.y]
+                    jg.jg_shard(L.plan, jg.JG_T_Y, dev(R).data_ptr(), N, [r.data_ptr() for r in res])
+                    act = jg.JG_ACT_GELU if mode == "R" else jg.JG_ACT_NONE
+                    L.forward(residual=res, activation=act)
+                    Y = L.gather().cpu().numpy()
+                    L.forward(residual=res, activation=act)
+                    assert np.array_equal(Y, L.gather().cpu().numpy())          # deterministic
+                got[(tail, ways)] = Y
+                if mode == "L":
+                    assert np.array_equal(Y.astype(np.float64), want)
+                else:
+                    assert np.all(np.abs(Y.astype(np.float64) - want) <= 1.5e-6 * S)
+
+
 @pytest.mark.parametrize("K", [1024, 4096])
 def test_same_sign_operands(jg, ctx, K):
     # All-positive data: the running FP32 sum is the magnitude itself.  The 256 accumulators of a wavefront
