@@ -499,6 +499,8 @@ def cpu_baseline(cfg, seconds, reduced_terms=0):
 # from inside this script, so the figure is quoted, keyed by workload, and is null for the others.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
     ("config3", 4): 3.46e9,   # reads 3.05 GB (FETCH_SIZE / 0.5065) + writes 0.406 GB (WRITE_SIZE / 1.0018)
+    # jg::gemm_bf16_nt, whole tiles (profiles/gemm_bf16_nt_forward_config3_kernel_trace.md): reads 1.70 GB, writes 0.46 GB
+    ("config3", 1, "bf16"): 2.16e9,
 }
 
 
@@ -702,7 +704,8 @@ def main():
             "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
             "frac": achieved / peak if achieved else None,
             "avg_launch_ms": head["gemm_avg_launch_ms"], "launches": head["gemm_launches_timed"],
-            "traffic": None if reduced else MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((f"config{args.config}", args.ways)),
+            "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(
+                (f"config{args.config}", args.ways, args.dtype) if reduced else (f"config{args.config}", args.ways)),
             "traffic_unit": "bytes per launch",
         },
         "other_kernels_ms_per_step": head["other_kernels_ms_per_step"],
