@@ -152,11 +152,14 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
     const int ldc = P.ldc, ldres = P.ldres, ldadd = P.ldadd;
     const bool vec_ok = (((uintptr_t)C | (uintptr_t)addend | (uintptr_t)residual | (uintptr_t)bias) & 15) == 0 &&
                         ((ldc | (addend ? ldadd : 0) | (residual ? ldres : 0)) & 3) == 0;
-    if (interior && vec_ok) {
+    // edge tiles take the same way when N is a multiple of 4 (a lane's four columns are then all inside or all
+    // outside), with each row and column group checked
+    if (vec_ok && (interior || (N & 3) == 0)) {
         const int lane = lk * 32 + lr;
         const int rrow = lane >> 5, rcol = (lane & 31) * 4;          // read-back position: row 2 p + rrow, 4 columns
         const int col = n0 + wn * 128 + rcol;
-        const vf4 b4 = bias ? *reinterpret_cast<const vf4*>(bias + col) : vf4{0.f, 0.f, 0.f, 0.f};
+        const bool col_in = col < N;
+        const vf4 b4 = (bias && col_in) ? *reinterpret_cast<const vf4*>(bias + col) : vf4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -168,6 +171,7 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
 #pragma unroll
             for (int p = 0; p < 16; ++p) {
                 const int64_t row = row0 + 2 * p;
+                if (!interior && (!col_in || row >= M)) continue;
                 vf4 y = *reinterpret_cast<const vf4*>(shuffle + (2 * p + rrow) * HB_SHUFFLE_LD + rcol);
                 if (addend) y += __builtin_nontemporal_load(reinterpret_cast<const vf4*>(addend + row * ldadd + col));
                 y += b4;
