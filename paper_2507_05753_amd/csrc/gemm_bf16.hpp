@@ -16,12 +16,18 @@
 //   wavefront : 128 x 128 sub-tile = 4 x 4 MFMA blocks of 32 x 32 (256 accumulator registers);
 //               per 16 k it reads 8 fragments of 16 bytes for 16 MFMAs, the smallest LDS traffic
 //               per MFMA a wavefront's registers allow
-//   K loop    : slabs of 64 (128-byte rows: whole cache lines), two slab buffers of 64 KiB in LDS
-//               used alternately; slab kt + 1 travels global -> LDS (buffer_load_dwordx4 ... lds)
-//               while slab kt is multiplied, one transfer after every fourth MFMA
-// LDS layout as in the FP32 kernel's K-contiguous operands: rows are not padded; the lane that
-// fills 16-byte slot s of row r fetches chunk s ^ ((r >> 1) & 7) of that row, which makes the
-// 128-bit fragment reads (32 rows x 2 chunks per instruction) conflict-free.
+//   K loop    : slabs of 32 (64-byte rows), four slab buffers of 32 KiB in LDS used in turn; slab
+//               it + 3 travels global -> LDS (buffer_load_dwordx4 ... lds) while slab `it` is
+//               multiplied, one transfer after every second MFMA of the slab's first 16 k; the
+//               workgroup's one barrier per slab sits between its two halves, and behind it the
+//               first operands of the next slab are already being read
+//   epilogue  : each 32 x 128 block of a wave's accumulators goes through the wave's piece of LDS
+//               (free by then) and leaves as 16-byte stores
+//   tail      : the tiles of a last partial round of workgroups can be cut into runs of slabs
+//               (gemm_bf16_join adds them in k order); see make_bf16_group
+// LDS layout: rows are not padded; the lane that fills 16-byte slot s of row r fetches chunk
+// s ^ ((r >> 2) & 3) of that row's four, which makes the 128-bit fragment reads (32 rows x 2
+// chunks per instruction) conflict-free.
 // Transfers that would start at or past column K (ragged last slab) or past the operand's last row
 // get an offset outside the buffer descriptor and arrive as zeros: nothing outside the operands is
 // ever read.
