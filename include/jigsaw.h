@@ -99,8 +99,9 @@ typedef struct jg_linear_desc {
                             rank's share of K (K, or K / 2 for 2 and 4 ways) must be a
                             multiple of 8; the X and W shards are then bfloat16 arrays of
                             JG_Q_X_SHARD_BYTES / JG_Q_W_SHARD_BYTES bytes, 16-byte aligned,
-                            written by jg_shard: xr x xc values per shard, JG_BF16X3 every
-                            row as [hi(0..xc) | lo(0..xc)]                                */
+                            written by jg_shard: xr rows per shard, each row xc values padded
+                            to a multiple of 64 (whole 128-byte lines; the padding is never
+                            read), JG_BF16X3 every row as [hi(0..xc) pad | lo(0..xc) pad]  */
     int32_t has_bias;    /* 0 / 1: b_r (the slice of b matching Y_r's columns) is added
                             once, by the rank that owns the output block                */
     int32_t combine;     /* JG_COMBINE_FUSED: the kept-product GEMM starts its accumulators

@@ -16,7 +16,7 @@ namespace jg {
 
 struct CvtBlock {
     const float* src;     // rows x cols, leading dimension ld_src (floats)
-    uint16_t* dst;        // rows x (planes * cols) bfloat16, dense
+    uint16_t* dst;        // rows of planes * plane bfloat16: [hi(0..cols) pad | lo(0..cols) pad]
     int64_t ld_src;
 };
 
@@ -25,6 +25,7 @@ struct CvtGroup {
     int nblocks;
     int rows, cols;       // common shape; cols is a multiple of 8
     int planes;           // 1: hi only; 2: [hi | lo] in every row
+    int plane;            // elements from one plane of a row to the next (>= cols; the padding is not written)
     uint32_t units_per_row, units;   // units of 8 elements
 };
 
@@ -61,13 +62,13 @@ __global__ __launch_bounds__(COPY_THREADS) void cvt_bf16(const CvtGroup g)
     uint32_t hi[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) hi[k] = bf16_bits(x[k]);
-    uint16_t* dst = B.dst + (int64_t)row * g.cols * g.planes + c;
+    uint16_t* dst = B.dst + (int64_t)row * g.plane * g.planes + c;
     *reinterpret_cast<vu4*>(dst) = vu4{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16)};
     if (g.planes == 2) {
         uint32_t lo[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) lo[k] = bf16_bits(x[k] - bf16_value(hi[k]));
-        *reinterpret_cast<vu4*>(dst + g.cols) =
+        *reinterpret_cast<vu4*>(dst + g.plane) =
             vu4{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16)};
     }
 }
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(COPY_THREADS) void cvt_bf16(const CvtGroup g)
 inline hipError_t launch_cvt_group(CvtGroup g, hipStream_t stream)
 {
     if (g.rows <= 0 || g.cols <= 0 || g.nblocks <= 0) return hipSuccess;
-    if (g.cols & 7) return hipErrorInvalidValue;
+    if ((g.cols & 7) || (g.plane & 7) || g.plane < g.cols) return hipErrorInvalidValue;
     bool vec = true;
     for (int i = 0; i < g.nblocks; ++i) {
         if ((uintptr_t)g.b[i].dst & 15) return hipErrorInvalidValue;
@@ -90,7 +91,7 @@ inline hipError_t launch_cvt_group(CvtGroup g, hipStream_t stream)
         part.rows = (int)((total_rows - r0 < max_rows) ? total_rows - r0 : max_rows);
         for (int i = 0; i < g.nblocks; ++i) {
             part.b[i].src = g.b[i].src + r0 * g.b[i].ld_src;
-            part.b[i].dst = g.b[i].dst + r0 * g.cols * g.planes;
+            part.b[i].dst = g.b[i].dst + r0 * g.plane * g.planes;
         }
         part.units = (uint32_t)((int64_t)part.rows * part.units_per_row);
         dim3 grid((part.units + COPY_THREADS - 1) / COPY_THREADS, g.nblocks, 1);

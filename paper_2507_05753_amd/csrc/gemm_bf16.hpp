@@ -8,8 +8,9 @@
 //   terms = 3 : operands split x = hi + lo (both bfloat16) and the product taken as
 //               hi hi + hi lo + lo hi — three passes over K at the same rate, 16 mantissa bits.
 // Both operands are K-contiguous (A is M x K, B is N x K, the "X W^T" form); a split operand stores
-// its lo plane behind its hi plane in every row ([hi(0..K) | lo(0..K)]), so the three terms are three
-// K loops over two column windows of the same rows.
+// its lo plane behind its hi plane in every row ([hi(0..K) pad | lo(0..K) pad]), so the three terms are
+// three K loops over two column windows of the same rows.  The shard step pads every plane to a multiple
+// of 64 elements: rows then start on 128-byte lines and no 64-byte slab row straddles two of them.
 //
 // Work decomposition
 //   workgroup : 256 threads = 4 wavefronts (2 x 2), one 256 x 256 tile of C, one workgroup per CU
@@ -58,6 +59,7 @@ struct HbGroup {
     int nprob;
     int M, N, K;                // K counts bfloat16 elements of one plane
     int terms;                  // 1, or 3 for split operands
+    int plane;                  // split operands: elements from the hi plane of a row to its lo plane (>= K)
     int tiles_m, tiles_n, total;
     int whole;                  // tiles [0, whole) get a workgroup each; per_xcd = ceil(whole / 8)
     int per_xcd;
@@ -247,7 +249,7 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
     const unsigned slab_lds = (unsigned)reinterpret_cast<uintptr_t>((lds_void*)slab);   // LDS address of the buffers
 
     HbLoader load_a, load_b;
-    const int row_bytes = (g.terms == 3 ? 2 : 1) * K * 2;
+    const int row_bytes = ((g.terms == 3 ? g.plane : 0) + K) * 2;
     load_a.init(P.A, P.lda, M, tc.m0, row_bytes, wave, lane);
     load_b.init(P.B, P.ldb, N, tc.n0, row_bytes, wave, lane);
 
@@ -263,8 +265,8 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
     struct SlabRef { int a_col, b_col, cols; };
     auto next_request = [&]() __attribute__((always_inline)) {
         SlabRef r;
-        r.a_col = (req_kt * HB_BK + ((g.terms == 3 && req_pass == 1) ? K : 0)) * 2;
-        r.b_col = (req_kt * HB_BK + ((g.terms == 3 && req_pass == 0) ? K : 0)) * 2;
+        r.a_col = (req_kt * HB_BK + ((g.terms == 3 && req_pass == 1) ? g.plane : 0)) * 2;
+        r.b_col = (req_kt * HB_BK + ((g.terms == 3 && req_pass == 0) ? g.plane : 0)) * 2;
         r.cols = req_kt == nkt - 1 ? last_cols : HB_BK;
         if (req_left > 1) {
             --req_left;
@@ -433,7 +435,9 @@ constexpr int kHbMinRunSlabs = 16;
 constexpr int kHbJoinCostSlabs = 40;    // the join kernel takes about as long as 40 slabs of the main loop
 inline size_t bf16_tail_scratch_bytes(int cus) { return (size_t)cus * HB_TILE_FLOATS * sizeof(float); }
 
-inline hipError_t make_bf16_group(const GemmGroup& src, int terms, int cus, float* scratch, size_t scratch_bytes, HbGroup& g)
+// plane: with split operands, the distance in elements from a row's hi plane to its lo plane (>= K, a multiple of 8)
+inline hipError_t make_bf16_group(const GemmGroup& src, int terms, int plane, int cus, float* scratch, size_t scratch_bytes,
+                                  HbGroup& g)
 {
     for (int i = 0; i < kMaxGroup; ++i) g.p[i] = src.p[i];
     g.nprob = src.nprob;
@@ -441,7 +445,9 @@ inline hipError_t make_bf16_group(const GemmGroup& src, int terms, int cus, floa
     g.N = src.N;
     g.K = src.K;
     g.terms = terms;
+    g.plane = plane;
     g.act = src.act;
+    if (terms == 3 && (plane < src.K || (plane & 7))) return hipErrorInvalidValue;
     g.tiles_m = (g.M + HB_BM - 1) / HB_BM;
     g.tiles_n = (g.N + HB_BN - 1) / HB_BN;
     const int64_t total = (int64_t)g.nprob * g.tiles_m * g.tiles_n;
@@ -473,11 +479,11 @@ inline hipError_t make_bf16_group(const GemmGroup& src, int terms, int cus, floa
 inline unsigned bf16_grid(const HbGroup& g) { return (unsigned)(kNumXcd * g.per_xcd + (g.total - g.whole) * g.parts); }
 
 // cus: compute units of the device (one workgroup each).  *needs_join: launch_gemm_bf16_join must follow.
-inline hipError_t launch_gemm_bf16_group(const GemmGroup& src, int terms, int cus, float* scratch, size_t scratch_bytes,
-                                         hipStream_t stream, HbGroup& g, bool* needs_join)
+inline hipError_t launch_gemm_bf16_group(const GemmGroup& src, int terms, int plane, int cus, float* scratch,
+                                         size_t scratch_bytes, hipStream_t stream, HbGroup& g, bool* needs_join)
 {
     *needs_join = false;
-    const hipError_t e = make_bf16_group(src, terms, cus, scratch, scratch_bytes, g);
+    const hipError_t e = make_bf16_group(src, terms, plane, cus, scratch, scratch_bytes, g);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(gemm_bf16_nt<3>, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);
     *needs_join = g.parts > 0;

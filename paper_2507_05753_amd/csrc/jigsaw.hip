@@ -61,6 +61,7 @@ struct jg_plan {
     // 4-byte units in one row of an X or W shard: xc for FP32, xc / 2 for bfloat16, xc for the
     // split mode's [hi | lo] rows
     int64_t xcp;
+    int64_t plane;   // reduced precision: bfloat16 elements per plane of a shard row = xc rounded up to 64
     // workspace layout (byte offsets); sizes are per rank
     size_t part_bytes;     // one rank's partial product  (yr x yc floats, padded)
     size_t wblk_bytes;     // one rank's received weight block (4-way, copy mode)
@@ -278,7 +279,9 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
             break;
         }
     }
-    p->xcp = d.dtype == JG_BF16 ? p->xc / 2 : p->xc;
+    // bfloat16 shard rows are padded to whole 128-byte lines per plane
+    p->plane = reduced ? (p->xc + 63) / 64 * 64 : p->xc;
+    p->xcp = d.dtype == JG_BF16 ? p->plane / 2 : d.dtype == JG_BF16X3 ? p->plane : p->xc;
     p->part_bytes = p->wblk_bytes = 0;
     p->off_send = p->off_kept = p->off_wrecv = 0;
     size_t off = 0;
@@ -448,6 +451,7 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
         cv.rows = (int)pt.rows;
         cv.cols = (int)pt.cols;
         cv.planes = d.dtype == JG_BF16X3 ? 2 : 1;
+        cv.plane = (int)plan->plane;
         for (int r = 0; r < d.ways; ++r) {
             if (!aligned(shards[r], 16)) return JG_E_ALIGN;
             int64_t rb, cb;
@@ -580,7 +584,7 @@ static bool run_gemm(const jg_plan* plan, jg::GemmGroup& g, int layout, int kern
         jg::HbGroup hb;
         {
             ScopedTimer t(c, kernel_class);
-            if (!HIP_OK(jg::launch_gemm_bf16_group(g, plan->d.dtype == JG_BF16X3 ? 3 : 1, plan->slots / 2,
+            if (!HIP_OK(jg::launch_gemm_bf16_group(g, plan->d.dtype == JG_BF16X3 ? 3 : 1, (int)plan->plane, plan->slots / 2,
                                                    reinterpret_cast<float*>(scratch), scratch_bytes, c->stream, hb, &join)))
                 return false;
         }

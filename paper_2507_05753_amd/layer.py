@@ -39,12 +39,13 @@ class JigsawLinear:
             self.x = [torch.empty((q(jg.JG_Q_X_ROWS, r), q(jg.JG_Q_X_COLS, r)), **f32) for r in range(ways)]
             self.w = [torch.empty((q(jg.JG_Q_W_ROWS, r), q(jg.JG_Q_W_COLS, r)), **f32) for r in range(ways)]
         else:
-            planes = 2 if dtype == jg.JG_BF16X3 else 1
+            # rows are padded by the library (whole 128-byte lines per plane): the row length comes from the byte count
             b16 = dict(dtype=torch.bfloat16, device=self.dev)
-            self.x = [torch.empty((q(jg.JG_Q_X_ROWS, r), planes * q(jg.JG_Q_X_COLS, r)), **b16) for r in range(ways)]
-            self.w = [torch.empty((q(jg.JG_Q_W_ROWS, r), planes * q(jg.JG_Q_W_COLS, r)), **b16) for r in range(ways)]
-            assert all(t.numel() * 2 == q(jg.JG_Q_X_SHARD_BYTES, r) for r, t in enumerate(self.x))
-            assert all(t.numel() * 2 == q(jg.JG_Q_W_SHARD_BYTES, r) for r, t in enumerate(self.w))
+            rowlen = lambda nbytes, rows: nbytes // (2 * rows)
+            self.x = [torch.empty((q(jg.JG_Q_X_ROWS, r), rowlen(q(jg.JG_Q_X_SHARD_BYTES, r), q(jg.JG_Q_X_ROWS, r))), **b16)
+                      for r in range(ways)]
+            self.w = [torch.empty((q(jg.JG_Q_W_ROWS, r), rowlen(q(jg.JG_Q_W_SHARD_BYTES, r), q(jg.JG_Q_W_ROWS, r))), **b16)
+                      for r in range(ways)]
         self.y = [torch.empty((q(jg.JG_Q_Y_ROWS, r), q(jg.JG_Q_Y_COLS, r)), **f32) for r in range(ways)]
         self.b = [torch.empty((q(jg.JG_Q_B_LEN, r),), **f32) for r in range(ways)] if bias else None
         self.ws_bytes = q(jg.JG_Q_WORKSPACE_BYTES)

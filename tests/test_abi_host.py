@@ -291,7 +291,7 @@ def test_mixing_and_layernorm_entry_points_check_their_arguments():
 
 
 def test_reduced_precision_plans_account_for_their_shards():
-    M, K, N = 64, 48, 32
+    M, K, N = 64, 272, 32        # K / 2 = 136: padded to 192 per plane
     for ways in (1, 2, 4):
         f = jg.jg_plan_create(None, M, K, N, ways)
         h = jg.jg_plan_create(None, M, K, N, ways, dtype=jg.JG_BF16)
@@ -301,8 +301,11 @@ def test_reduced_precision_plans_account_for_their_shards():
             xe = q(f, jg.JG_Q_X_ROWS, r) * q(f, jg.JG_Q_X_COLS, r)
             we = q(f, jg.JG_Q_W_ROWS, r) * q(f, jg.JG_Q_W_COLS, r)
             assert q(f, jg.JG_Q_X_SHARD_BYTES, r) == 4 * xe and q(f, jg.JG_Q_W_SHARD_BYTES, r) == 4 * we
-            assert q(h, jg.JG_Q_X_SHARD_BYTES, r) == 2 * xe and q(h, jg.JG_Q_W_SHARD_BYTES, r) == 2 * we
-            assert q(s, jg.JG_Q_X_SHARD_BYTES, r) == 4 * xe and q(s, jg.JG_Q_W_SHARD_BYTES, r) == 4 * we
+            # bfloat16 shard rows are padded to whole 128-byte lines (64 values) per plane
+            xrows, wrows = q(f, jg.JG_Q_X_ROWS, r), q(f, jg.JG_Q_W_ROWS, r)
+            plane = (q(f, jg.JG_Q_X_COLS, r) + 63) // 64 * 64
+            assert q(h, jg.JG_Q_X_SHARD_BYTES, r) == 2 * xrows * plane and q(h, jg.JG_Q_W_SHARD_BYTES, r) == 2 * wrows * plane
+            assert q(s, jg.JG_Q_X_SHARD_BYTES, r) == 4 * xrows * plane and q(s, jg.JG_Q_W_SHARD_BYTES, r) == 4 * wrows * plane
             assert q(h, jg.JG_Q_X_COLS, r) == q(f, jg.JG_Q_X_COLS, r)          # logical sizes do not change
         assert q(h, jg.JG_Q_FLOPS_TOTAL) == q(f, jg.JG_Q_FLOPS_TOTAL) == 2 * M * K * N
         extra = 8 * M * N if ways >= 2 else 0

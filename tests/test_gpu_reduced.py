@@ -81,12 +81,15 @@ def test_shards_hold_the_rounded_operands(jg, ctx, ways, dtype_name, M, K, N):
     _, xs, ws = run_layer(jg, ctx, X, W, b, ways, dtype)
     for got, src in ((xs, oracle.shard_x(X, ways)), (ws, oracle.shard_w(W, ways))):
         for g, blk in zip(got, src):
+            cols = blk.shape[1]
+            plane = (cols + 63) // 64 * 64          # every plane of a shard row is padded to whole 128-byte lines
             if dtype == jg.JG_BF16:
-                assert np.array_equal(g, oracle.round_bf16(blk))
+                assert g.shape[1] == plane
+                assert np.array_equal(g[:, :cols], oracle.round_bf16(blk))
             else:
+                assert g.shape[1] == 2 * plane
                 hi, lo = oracle.split_bf16(blk)
-                cols = blk.shape[1]
-                assert np.array_equal(g[:, :cols], hi) and np.array_equal(g[:, cols:], lo)
+                assert np.array_equal(g[:, :cols], hi) and np.array_equal(g[:, plane:plane + cols], lo)
 
 
 @pytest.mark.parametrize("ways", [1, 2, 4])
