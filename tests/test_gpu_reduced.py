@@ -92,6 +92,29 @@ def test_shards_hold_the_rounded_operands(jg, ctx, ways, dtype_name, M, K, N):
                 assert np.array_equal(g[:, :cols], hi) and np.array_equal(g[:, plane:plane + cols], lo)
 
 
+@pytest.mark.parametrize("ways", [1, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+def test_shard_from_a_strided_unaligned_global_tensor(jg, ctx, ways, dtype_name):
+    """The global FP32 tensors may have any leading dimension and 4-byte alignment (element-wise reads then)."""
+    from paper_2507_05753_amd.layer import JigsawLinear
+    dtype = getattr(jg, dtype_name)
+    M, K, N = 66, 80, 36
+    X, W, _ = inputs.layer_inputs(412, M, K, N, "R")
+    Xbig = torch.full((M, K + 3), float("nan"), device="cuda")
+    Xbig[:, :K] = dev(X)
+    Wflat = torch.full((N * K + 1,), float("nan"), device="cuda")       # W starts 4 bytes into an aligned buffer
+    Wview = Wflat[1:].view(N, K)
+    Wview.copy_(dev(W))
+    with JigsawLinear(M, K, N, ways, ctx=ctx, dtype=dtype) as L:
+        jg.jg_shard(L.plan, jg.JG_T_X, Xbig.data_ptr(), K + 3, [t.data_ptr() for t in L.x])
+        jg.jg_shard(L.plan, jg.JG_T_W, Wview.data_ptr(), K, [t.data_ptr() for t in L.w])
+        L.forward()
+        Y = L.gather().cpu().numpy()
+    t = terms_of(jg, dtype)
+    S = oracle.linear_reduced(X, W, None, t, absolute=True)
+    assert np.all(np.abs(Y.astype(np.float64) - oracle.linear_reduced(X, W, None, t)) <= TOL * S)
+
+
 @pytest.mark.parametrize("ways", [1, 2, 4])
 @pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
 @pytest.mark.parametrize("bias", [False, True])
