@@ -215,7 +215,8 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
 // grid: kNumXcd * per_xcd workgroups; consecutive ids land on different XCDs, so the id is folded
 // into a per-XCD contiguous range of tiles, walked column-major inside bands of 4 row-tiles: the 32
 // tiles an XCD has in flight form a 4 x 8 block that shares 4 A panels and 8 B panels in its L2.
-// PARTS (measurement only; anything but 3 gives wrong results): bit 0 = issue the slab transfers, bit 1 = multiply.
+// PARTS (measurement builds only; the library instantiates 3, anything else gives wrong results): bit 0 = issue the
+// slab transfers, bit 1 = multiply, bit 3 = skip the epilogue.  It is how the kernel's parts were timed one by one.
 template <int PARTS = 3>
 __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
 {
