@@ -176,7 +176,10 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
                 for (int v = 0; v < 16; ++v)
                     shuffle[(8 * (v >> 2) + 4 * lk + (v & 3)) * HB_SHUFFLE_LD + jb * 32 + lr] = acc[i][jb][v];
             const int64_t row0 = m0 + wm * 128 + i * 32 + rrow;
-#pragma unroll
+            // Not unrolled: the body holds every variant of the epilogue (the activation alone is hundreds of
+            // instructions); 64 copies of it made each step jump across more code than the instruction cache
+            // holds, and a step took 830 cycles instead of a few dozen.
+#pragma unroll 1
             for (int p = 0; p < 16; ++p) {
                 const int64_t row = row0 + 2 * p;
                 if (!interior && (!col_in || row >= M)) continue;
