@@ -6,7 +6,9 @@
 // bfloat16 mode runs at 16 times the FP32 rate.  Two variants of the X W^T layer of Sec. 4 use it:
 //   terms = 1 : operands rounded to bfloat16 once, when they are sharded;
 //   terms = 3 : operands split x = hi + lo (both bfloat16) and the product taken as
-//               hi hi + hi lo + lo hi — three passes over K at the same rate, 16 mantissa bits.
+//               hi hi + hi lo + lo hi — three times the matrix work, 16 mantissa bits.  The library
+//               runs it as one pass over K (gemm_bf16x3_nt below); gemm_bf16_nt can also run it as
+//               three passes.
 // Both operands are K-contiguous (A is M x K, B is N x K, the "X W^T" form); a split operand stores
 // its lo plane behind its hi plane in every row ([hi(0..K) pad | lo(0..K) pad]), so the three terms are
 // three K loops over two column windows of the same rows.  The shard step pads every plane to a multiple
@@ -381,6 +383,155 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
     }
 }
 
+// Split operands in one pass over K (terms = 3, the library's form of that mode).  A slab is the
+// same 32 k of all four planes (A hi, A lo, B hi, B lo: 64 KiB) and gives three products per block
+// - hi lo, lo hi, hi hi, the small ones first within every 16 k - so four operand slabs feed what three
+// separate passes fetch six for.  The transfers are what bounds the one-plane loop (L2 delivers about
+// 12 TB/s to LDS), so this form is faster by about that third.  Two slab buffers: the transfers of slab
+// it + 2 are issued behind slab it's mid-slab barrier, into the buffer of the slab just used up, and have
+// a whole slab's time (96 MFMAs per wave) to land.
+// Against three passes with the small terms first, the small products here are added to a sum that
+// has already grown, as in any single pass; the rounding walk on same-sign data is that of 3 K / 16
+// steps (see the tolerance notes of the tests).
+__global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
+{
+    constexpr int STAGE = 4 * HB_OPERAND_BYTES;              // 64 KiB
+    __shared__ __align__(1024) char slab[2 * STAGE];
+
+    const int M = g.M, N = g.N, K = g.K;
+    const int nkt = (K + HB_BK - 1) / HB_BK;
+    int lid, s_begin = 0, s_end = nkt, run = -1;
+    if ((int)blockIdx.x < kNumXcd * g.per_xcd) {
+        lid = (blockIdx.x % kNumXcd) * g.per_xcd + blockIdx.x / kNumXcd;
+        if (lid >= g.whole) return;
+    } else {
+        run = blockIdx.x - kNumXcd * g.per_xcd;
+        const int t = run / g.parts, part = run - t * g.parts;
+        lid = g.whole + t;
+        if (lid >= g.total) return;
+        s_begin = (int)((int64_t)nkt * part / g.parts);
+        s_end = (int)((int64_t)nkt * (part + 1) / g.parts);
+    }
+    const TileCoord tc = hb_decode_tile(g, lid);
+    const GemmProblem& P = g.p[tc.prob];
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lr = lane & 31, lk = lane >> 5;
+    const unsigned slab_lds = (unsigned)reinterpret_cast<uintptr_t>((lds_void*)slab);
+
+    HbLoader load_a, load_b;
+    const int row_bytes = (g.plane + K) * 2;
+    load_a.init(P.A, P.lda, M, tc.m0, row_bytes, wave, lane);
+    load_b.init(P.B, P.ldb, N, tc.n0, row_bytes, wave, lane);
+    const int plane_bytes = g.plane * 2;
+    const int total_slabs = s_end - s_begin;
+    const int last_cols = K - (nkt - 1) * HB_BK;
+    // the slab to request next; past the end it stays on the last one (surplus requests into a buffer
+    // nobody reads again keep the loop uniform)
+    int req_kt = s_begin, req_left = total_slabs;
+    // transfer q (0 .. 15) of the next slab: planes A hi, A lo, B hi, B lo, four transfers each
+    auto issue = [&](int q, int kt, unsigned stage) __attribute__((always_inline)) {
+        const int cols = kt == nkt - 1 ? last_cols : HB_BK;
+        const int col = kt * HB_BK * 2 + ((q & 4) ? plane_bytes : 0);
+        if (q < 8) load_a.issue(q & 3, col, cols, stage + (q >> 2) * HB_OPERAND_BYTES, wave);
+        else load_b.issue(q & 3, col, cols, stage + (q >> 2) * HB_OPERAND_BYTES, wave);
+    };
+    auto advance = [&]() __attribute__((always_inline)) {
+        if (req_left > 1) {
+            --req_left;
+            ++req_kt;
+        }
+    };
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) issue(q, req_kt, slab_lds + b * STAGE);
+        advance();
+    }
+
+    const bool interior = tc.m0 + HB_BM <= M && tc.n0 + HB_BN <= N;
+    floatx16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    int frag_off[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) frag_off[s] = lr * 64 + (((2 * s + lk) ^ ((lr >> 2) & 3)) << 4);
+    const int a_frag = wm * 4 * 2048;
+    const int b_frag = 2 * HB_OPERAND_BYTES + wn * 4 * 2048;
+    struct Frags { bf16x8 ah[4], al[4], bh[4], bl[4]; };
+    auto read_frags = [&](const char* stage, int s, Frags& f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            f.ah[b] = *reinterpret_cast<const bf16x8*>(stage + a_frag + b * 2048 + frag_off[s]);
+            f.al[b] = *reinterpret_cast<const bf16x8*>(stage + a_frag + HB_OPERAND_BYTES + b * 2048 + frag_off[s]);
+            f.bh[b] = *reinterpret_cast<const bf16x8*>(stage + b_frag + b * 2048 + frag_off[s]);
+            f.bl[b] = *reinterpret_cast<const bf16x8*>(stage + b_frag + HB_OPERAND_BYTES + b * 2048 + frag_off[s]);
+        }
+    };
+
+    Frags f0, f1;                       // operands of a slab's first / second 16 k
+    JG_WAIT_VMCNT(16);                  // slab 0 has landed (the 16 transfers of the second request may be in flight)
+    __syncthreads();
+    read_frags(slab, 0, f0);
+
+    for (int it = 0; it < total_slabs; ++it) {
+        char* cur = slab + (it & 1) * STAGE;
+        const char* nxt = slab + ((it + 1) & 1) * STAGE;
+        read_frags(cur, 1, f1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.ah[i], f0.bl[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.al[i], f0.bh[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.ah[i], f0.bh[j], acc[i][j], 0, 0, 0);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+        // Slab it + 1 was requested a slab ago and nothing has been requested since; this wavefront's reads
+        // of slab `it` are complete.  Behind the barrier slab it + 1 may be read and slab it's buffer refilled.
+        JG_WAIT_VMCNT(0);
+        __builtin_amdgcn_s_waitcnt(0xC07F);    // lgkmcnt(0) only
+        __syncthreads();
+        read_frags(nxt, 0, f0);                // (after the last slab: a surplus copy, read but not used)
+        __builtin_amdgcn_sched_barrier(0);
+        {
+            const unsigned stage = slab_lds + (it & 1) * STAGE;
+            const int kt = req_kt;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.ah[i], f1.bl[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.al[i], f1.bh[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.ah[i], f1.bh[j], acc[i][j], 0, 0, 0);
+                    issue(i * 4 + j, kt, stage);        // slab it + 2, one transfer after every third MFMA
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            advance();
+        }
+    }
+    JG_WAIT_VMCNT(0);       // the surplus transfers have landed ...
+    __syncthreads();        // ... and nobody reads a slab any more: the buffers become the waves' staging blocks
+    float* shuffle = reinterpret_cast<float*>(slab + wave * (32 * HB_SHUFFLE_LD * 4));
+    if (run < 0) {
+        hb_store_tile(P, M, N, tc.m0, tc.n0, wm, wn, lr, lk, interior, acc, g.act, shuffle);
+    } else {
+        GemmProblem raw = {};
+        raw.C = g.scratch + (int64_t)run * HB_TILE_FLOATS;
+        raw.ldc = HB_BN;
+        hb_store_tile(raw, HB_BM, HB_BN, 0, 0, wm, wn, lr, lk, true, acc, kActNone, shuffle);
+    }
+}
+
 // Second kernel of a launch with a split tail: adds a tile's runs in ascending k order, then what the
 // epilogue adds, and stores C.  grid: kHbJoinSlices workgroups per tail tile, each with a band of its rows.
 constexpr int kHbJoinSlices = 32;
@@ -463,6 +614,7 @@ inline hipError_t make_bf16_group(const GemmGroup& src, int terms, int plane, in
     g.whole = g.total;
     g.parts = 0;
     g.scratch = nullptr;
+    // in slabs of the one-plane loop; the one-pass split-operand kernel cuts a tile's K / 32 slabs, each three of these
     const int tile_slabs = (g.K + HB_BK - 1) / HB_BK * terms;
     const int tail = cus > 0 ? g.total % cus : 0;
     if (scratch && tail > 0 && 2 * tail <= cus) {
@@ -489,7 +641,8 @@ inline hipError_t launch_gemm_bf16_group(const GemmGroup& src, int terms, int pl
     *needs_join = false;
     const hipError_t e = make_bf16_group(src, terms, plane, cus, scratch, scratch_bytes, g);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(gemm_bf16_nt<3>, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);
+    if (terms == 3) hipLaunchKernelGGL(gemm_bf16x3_nt, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);
+    else hipLaunchKernelGGL(gemm_bf16_nt<3>, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);
     *needs_join = g.parts > 0;
     return hipGetLastError();
 }
