@@ -700,7 +700,7 @@ def main():
         "hbm_algo_gbps": head["hbm_algo_gbps"],
         "hbm_algo_frac_of_8TBps": head["hbm_algo_frac"],
         "roofline": {
-            "bound": "mfma", "kernel": "jg::gemm_bf16_nt" if reduced else "jg::gemm_f32_stream<false, false, false>",
+            "bound": "mfma", "kernel": ("jg::gemm_bf16x3_nt" if terms == 3 else "jg::gemm_bf16_nt") if reduced else "jg::gemm_f32_stream<false, false, false>",
             "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
             "frac": achieved / peak if achieved else None,
             "avg_launch_ms": head["gemm_avg_launch_ms"], "launches": head["gemm_launches_timed"],

@@ -245,8 +245,8 @@ int jg_gather_patches(const jg_plan* plan, const float* const* y_shards, float* 
  * when that is 0); its contents on entry are irrelevant and are overwritten.
  * JG_F32 plans: FP32 storage, FP32 matrix-core multiply-accumulate.  JG_BF16 / JG_BF16X3 plans
  * (JG_OP_XWT only): x_sh and w_sh point at the bfloat16 shards jg_shard wrote, the block products
- * run on the bfloat16 matrix cores with FP32 sums (JG_BF16X3: three products per block, the small
- * cross terms first), the partial products, b and Y stay FP32; the same launches, options and
+ * run on the bfloat16 matrix cores with FP32 sums (JG_BF16X3: three products per block for each 16 k,
+ * the small cross terms first), the partial products, b and Y stay FP32; the same launches, options and
  * epilogue as above; JG_TAIL_SPLIT adds one 256 x 256 scratch tile of floats per compute unit.
  * Errors: JG_E_NULL, JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
 int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
