@@ -6,15 +6,14 @@
 // bfloat16 mode runs at 16 times the FP32 rate.  Two variants of the X W^T layer of Sec. 4 use it:
 //   terms = 1 : operands rounded to bfloat16 once, when they are sharded;
 //   terms = 3 : operands split x = hi + lo (both bfloat16) and the product taken as
-//               hi hi + hi lo + lo hi — three times the matrix work, 16 mantissa bits.  The library
-//               runs it as one pass over K (gemm_bf16x3_nt below); gemm_bf16_nt can also run it as
-//               three passes.
+//               hi hi + hi lo + lo hi — three times the matrix work, 16 mantissa bits, in one pass
+//               over K (gemm_bf16x3_nt).
 // Both operands are K-contiguous (A is M x K, B is N x K, the "X W^T" form); a split operand stores
-// its lo plane behind its hi plane in every row ([hi(0..K) pad | lo(0..K) pad]), so the three terms are
-// three K loops over two column windows of the same rows.  The shard step pads every plane to a multiple
+// its lo plane behind its hi plane in every row ([hi(0..K) pad | lo(0..K) pad]), so the terms read two
+// column windows of the same rows.  The shard step pads every plane to a multiple
 // of 64 elements: rows then start on 128-byte lines and no 64-byte slab row straddles two of them.
 //
-// Work decomposition
+// Work decomposition (gemm_bf16_nt, terms = 1; what differs with split operands is said at gemm_bf16x3_nt)
 //   workgroup : 256 threads = 4 wavefronts (2 x 2), one 256 x 256 tile of C, one workgroup per CU
 //   wavefront : 128 x 128 sub-tile = 4 x 4 MFMA blocks of 32 x 32 (256 accumulator registers);
 //               per 16 k it reads 8 fragments of 16 bytes for 16 MFMAs, the smallest LDS traffic
@@ -48,13 +47,14 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int HB_BM = 256;
 constexpr int HB_BN = 256;
-constexpr int HB_BK = 32;                                 // bfloat16 elements per slab row = 64 bytes
+constexpr int HB_BK = 32;                                 // split operands: bfloat16 elements per slab row = 64 bytes
+constexpr int HB_WIDE_BK = 64;                            // one plane: 128 bytes, a whole cache line per row
 constexpr int HB_THREADS = 256;
-constexpr int HB_OPERAND_BYTES = HB_BM * HB_BK * 2;       // one slab of one operand = 16 KiB (BM == BN)
-constexpr int HB_STAGE_BYTES = 2 * HB_OPERAND_BYTES;      // A and B
-constexpr int HB_STAGES = 4;                              // slab buffers in LDS: 128 KiB
+constexpr int HB_OPERAND_BYTES = HB_BM * HB_BK * 2;       // one 32 k slab of one plane = 16 KiB (BM == BN)
 constexpr int HB_BAND_ROWS = 4;                           // row-tiles per band of the tile order
-constexpr int HB_TRANSFERS = HB_OPERAND_BYTES / (HB_THREADS * 16);   // 4 per lane, operand and slab
+#ifndef HB_PREFETCH_SLABS
+#define HB_PREFETCH_SLABS 2                               // L2 prefetch distance ahead of the transfers, in slabs
+#endif
 
 struct HbGroup {
     GemmProblem p[kMaxGroup];   // A, B point at bfloat16 data; lda, ldb count 4-byte units (bfloat16 pairs)
@@ -104,23 +104,46 @@ __device__ __forceinline__ void hb_transfer(const hb_int4& rsrc, unsigned lds_ba
                  : "memory");
 }
 
-// One operand's slabs, global -> LDS.  Transfer t of a lane covers row 64 t + 16 wave + lane / 4
-// of the tile (four lanes per 64-byte slab row).
+// Asks L2 for the lines that hold the first four bytes at each lane's offset (lanes whose offset lies outside
+// the buffer ask for nothing).  The four bytes go to a 256-byte piece of LDS that nobody reads: the point is that
+// the lines are on their way from HBM to L2 some slabs before the transfers that need them.
+__device__ __forceinline__ void hb_prefetch(const hb_int4& rsrc, unsigned lds_dump, int voffset, int soffset)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_dump), "v"(voffset), "s"(rsrc), "s"(soffset)
+                 : "memory");
+}
+
+// One operand's slabs, global -> LDS, ROW bytes (64 or 128) of every tile row per slab.  ROW / 16 lanes share
+// a row, so a wavefront's transfer covers 1024 / ROW rows and the workgroup's four 4096 / ROW; transfer t of a
+// lane covers row (4096 / ROW) t + (1024 / ROW) wave + lane / (ROW / 16) of the tile.  With 128-byte rows every
+// request is a whole cache line, which L2 serves at 1.6 times the rate of half lines (measured: 25 against
+// 15 TB/s into LDS over all CUs).
+// LDS rows are not padded; the lane that fills 16-byte slot s of row r fetches chunk s ^ swizzle(r) of that
+// row, with swizzle(r) = (r >> 2) & 3 for 64-byte rows and (r >> 1) & 7 for 128-byte rows: the 128-bit fragment
+// reads (32 rows, two chunks per instruction) then touch every bank group once per 16 lanes.
+template <int ROW>
 struct HbLoader {
+    static constexpr int kLanesPerRow = ROW / 16;
+    static constexpr int kRowsPerWave = 64 / kLanesPerRow;
+    static constexpr int kRowsPerTransfer = 4 * kRowsPerWave;
+    static constexpr int kTransfers = HB_BM / kRowsPerTransfer;     // per lane, operand and slab: 4 or 8
+    __device__ static __forceinline__ int swizzle(int row) { return ROW == 64 ? (row >> 2) & 3 : (row >> 1) & 7; }
     hb_int4 rsrc;               // raw buffer descriptor over the tile's valid rows, in scalar registers
-    int voff[HB_TRANSFERS];     // byte offset of the lane's chunk in slab 0, or kOutOfBuffer for rows past the operand
+    int voff[kTransfers];       // byte offset of the lane's chunk in slab 0, or kOutOfBuffer for rows past the operand
     int chunk_k;                // first k (within a slab) of the chunk this lane fetches
     // row_bytes: the bytes of a row that exist (all planes)
     __device__ __forceinline__ void init(const float* base, int ld, int extent, int origin, int row_bytes, int wave,
                                          int lane)
     {
         const int valid = min(HB_BM, extent - origin);
-        const int r = wave * 16 + (lane >> 2);
-        const int chunk = (lane & 3) ^ ((r >> 2) & 3);
+        const int r = wave * kRowsPerWave + lane / kLanesPerRow;
+        const int chunk = (lane % kLanesPerRow) ^ swizzle(r);       // (rows of later transfers: same swizzle)
         chunk_k = chunk * 8;
 #pragma unroll
-        for (int t = 0; t < HB_TRANSFERS; ++t) {
-            const int row = t * 64 + r;
+        for (int t = 0; t < kTransfers; ++t) {
+            const int row = t * kRowsPerTransfer + r;
             voff[t] = row < valid ? row * ld * 4 + chunk * 16 : kOutOfBuffer;
         }
         // The descriptor spans the tile's valid rows.  A slab's column offset travels in the scalar
@@ -133,7 +156,7 @@ struct HbLoader {
         rsrc.w = kBufferRsrcFlags;
     }
     // transfer t of the slab whose first column (in bytes, plane offset included) is col_bytes; of a ragged
-    // slab (cols < HB_BK columns exist) the chunks at or past `cols` are fetched from outside the buffer
+    // slab (cols < ROW / 2 columns exist) the chunks at or past `cols` are fetched from outside the buffer
     __device__ __forceinline__ void issue(int t, int col_bytes, int cols, unsigned operand_slab, int wave) const
     {
         const int vo = chunk_k < cols ? voff[t] : kOutOfBuffer;
@@ -225,14 +248,19 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
 template <int PARTS = 3>
 __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
 {
-    __shared__ __align__(1024) char slab[HB_STAGES * HB_STAGE_BYTES];
+    constexpr int UNIT = HB_BM * HB_WIDE_BK * 2;            // one operand's slab: 256 rows of 128 bytes = 32 KiB
+    constexpr int STAGE = 2 * UNIT;                          // A and B
+    typedef HbLoader<HB_WIDE_BK * 2> Loader;
+    constexpr int T = Loader::kTransfers;                    // 8 per lane and operand
+    constexpr int PF = HB_PREFETCH_SLABS;
+    __shared__ __align__(1024) char slab[2 * STAGE];
+    __shared__ __align__(256) char dump[HB_THREADS * 4];    // where the prefetches' four bytes per lane end up
 
     const int M = g.M, N = g.N, K = g.K;
-    const int nkt = (K + HB_BK - 1) / HB_BK;
-    const int tile_slabs = nkt * g.terms;
+    const int nkt = (K + HB_WIDE_BK - 1) / HB_WIDE_BK;
     // The first 8 * per_xcd workgroups take whole tiles; the rest are the runs of the split tail, in
     // launch order (so they spread over the XCDs and start last).
-    int lid, s_begin = 0, s_end = tile_slabs, run = -1;
+    int lid, s_begin = 0, s_end = nkt, run = -1;
     if ((int)blockIdx.x < kNumXcd * g.per_xcd) {
         lid = (blockIdx.x % kNumXcd) * g.per_xcd + blockIdx.x / kNumXcd;
         if (lid >= g.whole) return;
@@ -241,8 +269,10 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
         const int t = run / g.parts, part = run - t * g.parts;
         lid = g.whole + t;
         if (lid >= g.total) return;
-        s_begin = (int)((int64_t)tile_slabs * part / g.parts);
-        s_end = (int)((int64_t)tile_slabs * (part + 1) / g.parts);
+        // (a 64-bit division runs on the vector unit; the results are pinned back to scalar registers because
+        // the transfers take the slab's column offset from one)
+        s_begin = __builtin_amdgcn_readfirstlane((int)((int64_t)nkt * part / g.parts));
+        s_end = __builtin_amdgcn_readfirstlane((int)((int64_t)nkt * (part + 1) / g.parts));
     }
     const TileCoord tc = hb_decode_tile(g, lid);
     const GemmProblem& P = g.p[tc.prob];
@@ -254,46 +284,63 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
     const int lr = lane & 31, lk = lane >> 5;
     const unsigned slab_lds = (unsigned)reinterpret_cast<uintptr_t>((lds_void*)slab);   // LDS address of the buffers
 
-    HbLoader load_a, load_b;
-    const int row_bytes = ((g.terms == 3 ? g.plane : 0) + K) * 2;
+    Loader load_a, load_b;
+    const int row_bytes = K * 2;
     load_a.init(P.A, P.lda, M, tc.m0, row_bytes, wave, lane);
     load_b.init(P.B, P.ldb, N, tc.n0, row_bytes, wave, lane);
 
-    // The slab sequence: `terms` passes over K.  With split operands the two small cross terms go
-    // first (A hi with B lo, then A lo with B hi) and hi with hi last: added to an already large sum,
-    // the small products would lose their low bits at every step.
     const int total_slabs = s_end - s_begin;                // slabs this workgroup multiplies
-    const int last_cols = K - (nkt - 1) * HB_BK;            // columns of a pass's last slab
-    // The slab to request next, walked without divisions.  Past the end it stays on the last slab: the
-    // surplus requests re-read that slab into buffers nobody reads again, so that the number of
-    // transfers in flight is the same in every iteration and one wait count fits all.
-    int req_pass = s_begin / nkt, req_kt = s_begin - req_pass * nkt, req_left = total_slabs;
-    struct SlabRef { int a_col, b_col, cols; };
-    auto next_request = [&]() __attribute__((always_inline)) {
-        SlabRef r;
-        r.a_col = (req_kt * HB_BK + ((g.terms == 3 && req_pass == 1) ? g.plane : 0)) * 2;
-        r.b_col = (req_kt * HB_BK + ((g.terms == 3 && req_pass == 0) ? g.plane : 0)) * 2;
-        r.cols = req_kt == nkt - 1 ? last_cols : HB_BK;
+    const int last_cols = K - (nkt - 1) * HB_WIDE_BK;       // columns of the last slab
+    // The slab to request next.  Past the end it stays on the last slab: the surplus requests re-read
+    // that slab into buffers nobody reads again, so that every iteration is the same.
+    int req_kt = s_begin, req_left = total_slabs;
+    // transfer q (0 .. 2 T - 1) of slab kt: A's T transfers, then B's
+    auto issue = [&](int q, int kt, unsigned stage) __attribute__((always_inline)) {
+        const int cols = kt == nkt - 1 ? last_cols : HB_WIDE_BK;
+        const int col = kt * HB_WIDE_BK * 2;
+        if (q < T) load_a.issue(q, col, cols, stage, wave);
+        else load_b.issue(q - T, col, cols, stage + UNIT, wave);
+    };
+    auto advance = [&]() __attribute__((always_inline)) {
         if (req_left > 1) {
             --req_left;
-            if (++req_kt == nkt) {
-                req_kt = 0;
-                ++req_pass;
-            }
-        }
-        return r;
-    };
-    auto request_all = [&](int buf) __attribute__((always_inline)) {
-        const unsigned stage = slab_lds + buf * HB_STAGE_BYTES;
-        const SlabRef r = next_request();
-#pragma unroll
-        for (int t = 0; t < HB_TRANSFERS; ++t) {
-            load_a.issue(t, r.a_col, r.cols, stage, wave);
-            load_b.issue(t, r.b_col, r.cols, stage + HB_OPERAND_BYTES, wave);
+            ++req_kt;
         }
     };
 #pragma unroll
-    for (int p = 0; p < HB_STAGES - 1; ++p) request_all(p);
+    for (int b = 0; b < 2; ++b) {
+#pragma unroll
+        for (int q = 0; q < 2 * T; ++q) issue(q, req_kt, slab_lds + b * STAGE);
+        advance();
+    }
+    // L2 prefetch, PF slabs ahead of the transfers.  The 32 tiles an XCD has in flight are a block of 4 row tiles x
+    // 8 column tiles that walk K together: the 8 workgroups of a row share an A panel, the 4 of a column a B panel,
+    // so each asks for its share of a slab's lines only (32 of the 256 A rows, 64 of the 256 B rows; a quarter of
+    // that per wavefront).  Where the block is incomplete (edges, a partial round) some lines are not asked for and
+    // arrive when the transfers need them, as they would without this.
+    // A wavefront's loads complete in order, so a prefetch must be back before the transfers issued after it can
+    // count as landed: it is issued right behind a slab's transfers and has two slab times until the next
+    // slab's transfers are waited for.
+    int pf_a = kOutOfBuffer, pf_b = kOutOfBuffer;
+    {
+        const int row_a = ((tc.n0 / HB_BN) & 7) * 32 + wave * 8 + lane;
+        const int row_b = ((tc.m0 / HB_BM) & 3) * 64 + wave * 16 + lane;
+        if (lane < 8 && row_a < min(HB_BM, M - tc.m0)) pf_a = row_a * P.lda * 4;
+        if (lane < 16 && row_b < min(HB_BN, N - tc.n0)) pf_b = row_b * P.ldb * 4;
+    }
+    const unsigned dump_lds = (unsigned)reinterpret_cast<uintptr_t>((lds_void*)dump) + wave * 256;
+    int pf_kt = s_begin + 2;
+    auto prefetch = [&]() __attribute__((always_inline)) {
+        const bool live = pf_kt < nkt;
+        const int col = pf_kt * HB_WIDE_BK * 2;
+        hb_prefetch(load_a.rsrc, dump_lds, live ? pf_a : kOutOfBuffer, col);
+        hb_prefetch(load_b.rsrc, dump_lds, live ? pf_b : kOutOfBuffer, col);
+        ++pf_kt;
+    };
+    if (PARTS & 1) {
+#pragma unroll
+        for (int d = 0; d < PF; ++d) prefetch();
+    }
 
     const bool interior = tc.m0 + HB_BM <= M && tc.n0 + HB_BN <= N;
     floatx16 acc[4][4];
@@ -304,70 +351,71 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // fragment k-step s (16 k) of block b: row 32 b + lr (64-byte rows), chunks 2 s + lk
-    int frag_off[2];
+    // fragment k-step s (16 k, four per slab) of block b: row 32 b + lr (128-byte rows), chunks 2 s + lk
+    int frag_off[4];
 #pragma unroll
-    for (int s = 0; s < 2; ++s) frag_off[s] = lr * 64 + (((2 * s + lk) ^ ((lr >> 2) & 3)) << 4);
-    const int a_frag = wm * 4 * 2048;                          // the wave's four row blocks of A
-    const int b_frag = HB_OPERAND_BYTES + wn * 4 * 2048;       // ... and four column blocks of B
-    auto read_frags = [&](const char* stage, int s, bf16x8 (&fa)[4], bf16x8 (&fb)[4]) __attribute__((always_inline)) {
+    for (int s = 0; s < 4; ++s) frag_off[s] = lr * 128 + (((2 * s + lk) ^ Loader::swizzle(lr)) << 4);
+    const int a_frag = wm * 4 * 4096;                          // the wave's four row blocks of A
+    const int b_frag = UNIT + wn * 4 * 4096;                   // ... and four column blocks of B
+    struct Half { bf16x8 a[2][4], b[2][4]; };                  // the operands of two k-steps
+    auto read_half = [&](const char* stage, int h, Half& f) __attribute__((always_inline)) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            fa[b] = *reinterpret_cast<const bf16x8*>(stage + a_frag + b * 2048 + frag_off[s]);
-            fb[b] = *reinterpret_cast<const bf16x8*>(stage + b_frag + b * 2048 + frag_off[s]);
-        }
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                f.a[s][b] = *reinterpret_cast<const bf16x8*>(stage + a_frag + b * 4096 + frag_off[2 * h + s]);
+                f.b[s][b] = *reinterpret_cast<const bf16x8*>(stage + b_frag + b * 4096 + frag_off[2 * h + s]);
+            }
     };
 
-    bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];      // operands of a slab's first / second k-step
-    // transfers complete in order: slab 0 has landed once at most those of the later requests are in flight
-    JG_WAIT_VMCNT(2 * HB_TRANSFERS * (HB_STAGES - 2));
+    Half f0, f1;                        // a slab's first / second 32 k
+    // transfers complete in order: slab 0 has landed once at most those of the second request are in flight
+    JG_WAIT_VMCNT(2 * T + 2 * PF);
     __syncthreads();
-    read_frags(slab, 0, fa0, fb0);
+    read_half(slab, 0, f0);
 
-    int cur_buf = 0;
     for (int it = 0; it < total_slabs; ++it) {
-        const int nxt_buf = cur_buf + 1 == HB_STAGES ? 0 : cur_buf + 1;
-        const int req_buf = cur_buf == 0 ? HB_STAGES - 1 : cur_buf - 1;       // = (it + HB_STAGES - 1) % HB_STAGES
-        const char* cur = slab + cur_buf * HB_STAGE_BYTES;
-        const char* nxt = slab + nxt_buf * HB_STAGE_BYTES;
-        read_frags(cur, 1, fa1, fb1);
+        const char* cur = slab + (it & 1) * STAGE;
+        const char* nxt = slab + ((it + 1) & 1) * STAGE;
+        read_half(cur, 1, f1);
         __builtin_amdgcn_sched_barrier(0);
-        // first k-step, with the transfers of slab it + HB_STAGES - 1 between the MFMAs.  Their buffer
-        // held slab it - 1, which every wavefront had finished reading before the last barrier.
-        {
-            const unsigned stage = slab_lds + req_buf * HB_STAGE_BYTES;
-            const SlabRef r = next_request();
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < 4; ++j)
                     if (PARTS & 2)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
-                    const int idx = i * 4 + j;
-                    if ((PARTS & 1) && (idx & 1) == 0) {
-                        const int t = (idx >> 1) & 3;
-                        if (idx < 8) load_a.issue(t, r.a_col, r.cols, stage, wave);
-                        else load_b.issue(t, r.b_col, r.cols, stage + HB_OPERAND_BYTES, wave);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-        }
-        // Slab it + 1 has landed once at most the transfers of the two later slabs are in flight; this
-        // wavefront's reads of slab `it` are complete, so after the barrier slab it + 1 may be read by
-        // all and slab it's buffer may be refilled.
-        if (PARTS & 1) JG_WAIT_VMCNT(2 * HB_TRANSFERS * (HB_STAGES - 2));
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.a[s][i], f0.b[s][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        // Slab it + 1 was requested a slab ago and only two prefetches have been issued since; this wavefront's
+        // reads of slab `it` are complete (its second half sits in registers).  Behind the barrier slab it + 1 may
+        // be read by all and slab it's buffer refilled.
+        if (PARTS & 1) JG_WAIT_VMCNT(PF > 0 ? 2 : 0);
         __builtin_amdgcn_s_waitcnt(0xC07F);    // lgkmcnt(0) only
         __syncthreads();
-        read_frags(nxt, 0, fa0, fb0);          // (after the last slab: a surplus copy, read but not used)
+        read_half(nxt, 0, f0);                 // (after the last slab: a surplus copy, read but not used)
         __builtin_amdgcn_sched_barrier(0);
+        {
+            const unsigned stage = slab_lds + (it & 1) * STAGE;
+            const int kt = req_kt;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+            for (int s = 0; s < 2; ++s)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (PARTS & 2)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        cur_buf = nxt_buf;
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (PARTS & 2)
+                            acc[i][j] =
+                                __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.a[s][i], f1.b[s][j], acc[i][j], 0, 0, 0);
+                        const int idx = s * 16 + i * 4 + j;
+                        // slab it + 2, one transfer after every second MFMA
+                        if ((PARTS & 1) && (idx & 1) == 0) issue(idx >> 1, kt, stage);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+            if ((PARTS & 1) && PF > 0) prefetch();
+            advance();
+        }
     }
     JG_WAIT_VMCNT(0);       // the surplus transfers have landed ...
     __syncthreads();        // ... and nobody reads a slab any more: the buffers become the waves' staging blocks
@@ -383,20 +431,23 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
     }
 }
 
-// Split operands in one pass over K (terms = 3, the library's form of that mode).  A slab is the
+// Split operands in one pass over K (terms = 3).  A slab is the
 // same 32 k of all four planes (A hi, A lo, B hi, B lo: 64 KiB) and gives three products per block
 // - hi lo, lo hi, hi hi, the small ones first within every 16 k - so four operand slabs feed what three
 // separate passes fetch six for.  The transfers are what bounds the one-plane loop (L2 delivers about
 // 12 TB/s to LDS), so this form is faster by about that third.  Two slab buffers: the transfers of slab
 // it + 2 are issued behind slab it's mid-slab barrier, into the buffer of the slab just used up, and have
 // a whole slab's time (96 MFMAs per wave) to land.
-// Against three passes with the small terms first, the small products here are added to a sum that
-// has already grown, as in any single pass; the rounding walk on same-sign data is that of 3 K / 16
-// steps (see the tolerance notes of the tests).
+// Against three separate passes with the two small cross terms first (which this mode was before: added
+// to an already large sum the small products lose their low bits at every step), the small products here
+// meet a sum that has already grown, as in any single pass; the rounding walk on same-sign data is that of
+// 3 K / 16 steps (see the tolerance notes of the tests).
 __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
 {
     constexpr int STAGE = 4 * HB_OPERAND_BYTES;              // 64 KiB
+    constexpr int PF = HB_PREFETCH_SLABS;
     __shared__ __align__(1024) char slab[2 * STAGE];
+    __shared__ __align__(256) char dump[HB_THREADS * 4];    // where the prefetches' four bytes per lane end up
 
     const int M = g.M, N = g.N, K = g.K;
     const int nkt = (K + HB_BK - 1) / HB_BK;
@@ -409,8 +460,8 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
         const int t = run / g.parts, part = run - t * g.parts;
         lid = g.whole + t;
         if (lid >= g.total) return;
-        s_begin = (int)((int64_t)nkt * part / g.parts);
-        s_end = (int)((int64_t)nkt * (part + 1) / g.parts);
+        s_begin = __builtin_amdgcn_readfirstlane((int)((int64_t)nkt * part / g.parts));
+        s_end = __builtin_amdgcn_readfirstlane((int)((int64_t)nkt * (part + 1) / g.parts));
     }
     const TileCoord tc = hb_decode_tile(g, lid);
     const GemmProblem& P = g.p[tc.prob];
@@ -422,7 +473,7 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
     const int lr = lane & 31, lk = lane >> 5;
     const unsigned slab_lds = (unsigned)reinterpret_cast<uintptr_t>((lds_void*)slab);
 
-    HbLoader load_a, load_b;
+    HbLoader<HB_BK * 2> load_a, load_b;
     const int row_bytes = (g.plane + K) * 2;
     load_a.init(P.A, P.lda, M, tc.m0, row_bytes, wave, lane);
     load_b.init(P.B, P.ldb, N, tc.n0, row_bytes, wave, lane);
@@ -451,6 +502,26 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
         for (int q = 0; q < 16; ++q) issue(q, req_kt, slab_lds + b * STAGE);
         advance();
     }
+    // L2 prefetch as in gemm_bf16_nt: the workgroup's share of the rows, both planes of each (a 64-byte slab row is
+    // half a line, so every second request finds its line on the way already)
+    int pf_a = kOutOfBuffer, pf_b = kOutOfBuffer;
+    {
+        const int row_a = ((tc.n0 / HB_BN) & 7) * 32 + wave * 8 + (lane & 7);
+        const int row_b = ((tc.m0 / HB_BM) & 3) * 64 + wave * 16 + (lane & 15);
+        if (lane < 16 && row_a < min(HB_BM, M - tc.m0)) pf_a = row_a * P.lda * 4 + (lane >> 3) * plane_bytes;
+        if (lane < 32 && row_b < min(HB_BN, N - tc.n0)) pf_b = row_b * P.ldb * 4 + (lane >> 4) * plane_bytes;
+    }
+    const unsigned dump_lds = (unsigned)reinterpret_cast<uintptr_t>((lds_void*)dump) + wave * 256;
+    int pf_kt = s_begin + 2;
+    auto prefetch = [&]() __attribute__((always_inline)) {
+        const bool live = pf_kt < nkt;
+        const int col = pf_kt * HB_BK * 2;
+        hb_prefetch(load_a.rsrc, dump_lds, live ? pf_a : kOutOfBuffer, col);
+        hb_prefetch(load_b.rsrc, dump_lds, live ? pf_b : kOutOfBuffer, col);
+        ++pf_kt;
+    };
+#pragma unroll
+    for (int d = 0; d < PF; ++d) prefetch();
 
     const bool interior = tc.m0 + HB_BM <= M && tc.n0 + HB_BN <= N;
     floatx16 acc[4][4];
@@ -478,7 +549,7 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
     };
 
     Frags f0, f1;                       // operands of a slab's first / second 16 k
-    JG_WAIT_VMCNT(16);                  // slab 0 has landed (the 16 transfers of the second request may be in flight)
+    JG_WAIT_VMCNT(16 + 2 * PF);         // slab 0 has landed (the second request and the prefetches may be in flight)
     __syncthreads();
     read_frags(slab, 0, f0);
 
@@ -496,9 +567,9 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.ah[i], f0.bh[j], acc[i][j], 0, 0, 0);
             }
         __builtin_amdgcn_sched_barrier(0);
-        // Slab it + 1 was requested a slab ago and nothing has been requested since; this wavefront's reads
-        // of slab `it` are complete.  Behind the barrier slab it + 1 may be read and slab it's buffer refilled.
-        JG_WAIT_VMCNT(0);
+        // Slab it + 1 was requested a slab ago and only two prefetches have been issued since; this wavefront's
+        // reads of slab `it` are complete.  Behind the barrier slab it + 1 may be read and slab it's buffer refilled.
+        JG_WAIT_VMCNT(PF > 0 ? 2 : 0);
         __builtin_amdgcn_s_waitcnt(0xC07F);    // lgkmcnt(0) only
         __syncthreads();
         read_frags(nxt, 0, f0);                // (after the last slab: a surplus copy, read but not used)
@@ -516,6 +587,7 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
                     issue(i * 4 + j, kt, stage);        // slab it + 2, one transfer after every third MFMA
                     __builtin_amdgcn_sched_barrier(0);
                 }
+            if (PF > 0) prefetch();
             advance();
         }
     }
