@@ -53,7 +53,7 @@ constexpr int HB_THREADS = 256;
 constexpr int HB_OPERAND_BYTES = HB_BM * HB_BK * 2;       // one 32 k slab of one plane = 16 KiB (BM == BN)
 constexpr int HB_BAND_ROWS = 4;                           // row-tiles per band of the tile order
 #ifndef HB_PREFETCH_SLABS
-#define HB_PREFETCH_SLABS 2                               // L2 prefetch distance ahead of the transfers, in slabs
+#define HB_PREFETCH_SLABS 1                               // L2 prefetch distance ahead of the transfers, in slabs
 #endif
 
 struct HbGroup {
@@ -193,6 +193,22 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
         const int col = n0 + wn * 128 + rcol;
         const bool col_in = col < N;
         const vf4 b4 = (bias && col_in) ? *reinterpret_cast<const vf4*>(bias + col) : vf4{0.f, 0.f, 0.f, 0.f};
+        // The addend of a 32 x 128 block is requested as a whole (16 loads per lane in flight) while the block
+        // before it is being stored, and added to the block in LDS before the read-back loop: fetched inside that
+        // loop, one load per step, each step waited out a trip to memory (measured: the launches with an addend
+        // took 1.56 times as long as those without).
+        vf4 ad[16];
+        auto request_addend = [&](int i) __attribute__((always_inline)) {
+            const int64_t row0 = m0 + wm * 128 + i * 32 + rrow;
+#pragma unroll
+            for (int p = 0; p < 16; ++p) {
+                const int64_t row = row0 + 2 * p;
+                ad[p] = (interior || (col_in && row < M))
+                            ? __builtin_nontemporal_load(reinterpret_cast<const vf4*>(addend + row * ldadd + col))
+                            : vf4{0.f, 0.f, 0.f, 0.f};
+            }
+        };
+        if (addend) request_addend(0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -200,20 +216,39 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
                     shuffle[(8 * (v >> 2) + 4 * lk + (v & 3)) * HB_SHUFFLE_LD + jb * 32 + lr] = acc[i][jb][v];
+            if (addend) {
+#pragma unroll
+                for (int p = 0; p < 16; ++p) {
+                    vf4* at = reinterpret_cast<vf4*>(shuffle + (2 * p + rrow) * HB_SHUFFLE_LD + rcol);
+                    *at = *at + ad[p];
+                }
+                if (i < 3) request_addend(i + 1);
+            }
             const int64_t row0 = m0 + wm * 128 + i * 32 + rrow;
-            // Not unrolled: the body holds every variant of the epilogue (the activation alone is hundreds of
-            // instructions); 64 copies of it made each step jump across more code than the instruction cache
-            // holds, and a step took 830 cycles instead of a few dozen.
+            // Rolled up, four steps at a time: the body holds every variant of the epilogue (the activation alone
+            // is hundreds of instructions); 64 copies of it made each step jump across more code than the
+            // instruction cache holds, and a step took 830 cycles instead of a few dozen.  Four steps share their
+            // waits (LDS, and memory for the residual).
 #pragma unroll 1
-            for (int p = 0; p < 16; ++p) {
-                const int64_t row = row0 + 2 * p;
-                if (!interior && (!col_in || row >= M)) continue;
-                vf4 y = *reinterpret_cast<const vf4*>(shuffle + (2 * p + rrow) * HB_SHUFFLE_LD + rcol);
-                if (addend) y += __builtin_nontemporal_load(reinterpret_cast<const vf4*>(addend + row * ldadd + col));
-                y += b4;
-                if (act) y = vf4{activate(y.x, act), activate(y.y, act), activate(y.z, act), activate(y.w, act)};
-                if (residual) y += *reinterpret_cast<const vf4*>(residual + row * ldres + col);
-                *reinterpret_cast<vf4*>(C + row * ldc + col) = y;
+            for (int p0 = 0; p0 < 16; p0 += 4) {
+                vf4 y[4], res[4];
+                bool in[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int64_t row = row0 + 2 * (p0 + q);
+                    in[q] = interior || (col_in && row < M);
+                    y[q] = *reinterpret_cast<const vf4*>(shuffle + (2 * (p0 + q) + rrow) * HB_SHUFFLE_LD + rcol);
+                    res[q] = (residual && in[q]) ? *reinterpret_cast<const vf4*>(residual + row * ldres + col)
+                                                 : vf4{0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int64_t row = row0 + 2 * (p0 + q);
+                    vf4 o = y[q] + b4;
+                    if (act) o = vf4{activate(o.x, act), activate(o.y, act), activate(o.z, act), activate(o.w, act)};
+                    if (residual) o += res[q];
+                    if (in[q]) *reinterpret_cast<vf4*>(C + row * ldc + col) = o;
+                }
             }
         }
     } else {
