@@ -18,18 +18,18 @@
 //   wavefront : 128 x 128 sub-tile = 4 x 4 MFMA blocks of 32 x 32 (256 accumulator registers);
 //               per 16 k it reads 8 fragments of 16 bytes for 16 MFMAs, the smallest LDS traffic
 //               per MFMA a wavefront's registers allow
-//   K loop    : slabs of 32 (64-byte rows), four slab buffers of 32 KiB in LDS used in turn; slab
-//               it + 3 travels global -> LDS (buffer_load_dwordx4 ... lds) while slab `it` is
-//               multiplied, one transfer after every second MFMA of the slab's first 16 k; the
-//               workgroup's one barrier per slab sits between its two halves, and behind it the
-//               first operands of the next slab are already being read
+//   K loop    : slabs of 64 (128-byte rows: every request is a whole cache line), two slab buffers of
+//               64 KiB in LDS.  A slab's second half is in registers before the workgroup's one barrier
+//               per slab, which sits between the halves; behind it the buffer is refilled with slab
+//               it + 2 (buffer_load_dwordx4 ... lds, one transfer after every second MFMA) and the
+//               first operands of slab it + 1 are read.  One slab ahead of the transfers a few lanes
+//               ask L2 for the lines of the slab after, so that first touches of HBM are not waited
+//               for with a whole slab of LDS standing empty
 //   epilogue  : each 32 x 128 block of a wave's accumulators goes through the wave's piece of LDS
 //               (free by then) and leaves as 16-byte stores
 //   tail      : the tiles of a last partial round of workgroups can be cut into runs of slabs
 //               (gemm_bf16_join adds them in k order); see make_bf16_group
-// LDS layout: rows are not padded; the lane that fills 16-byte slot s of row r fetches chunk
-// s ^ ((r >> 2) & 3) of that row's four, which makes the 128-bit fragment reads (32 rows x 2
-// chunks per instruction) conflict-free.
+// LDS layout: see HbLoader.
 // Transfers that would start at or past column K (ragged last slab) or past the operand's last row
 // get an offset outside the buffer descriptor and arrive as zeros: nothing outside the operands is
 // ever read.
