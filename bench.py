@@ -499,8 +499,8 @@ def cpu_baseline(cfg, seconds, reduced_terms=0):
 # from inside this script, so the figure is quoted, keyed by workload, and is null for the others.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
     ("config3", 4): 3.46e9,   # reads 3.05 GB (FETCH_SIZE / 0.5065) + writes 0.406 GB (WRITE_SIZE / 1.0018)
-    # jg::gemm_bf16_nt, whole tiles (profiles/gemm_bf16_nt_forward_config3_kernel_trace.md): reads 1.70 GB, writes 0.46 GB
-    ("config3", 1, "bf16"): 2.16e9,
+    # jg::gemm_bf16_nt, whole tiles (profiles/gemm_bf16_nt_forward_config3_kernel_trace.md): reads 1.51 GB, writes 0.46 GB
+    ("config3", 1, "bf16"): 1.98e9,
 }
 
 
