@@ -477,6 +477,8 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
 // to an already large sum the small products lose their low bits at every step), the small products here
 // meet a sum that has already grown, as in any single pass; the rounding walk on same-sign data is that of
 // 3 K / 16 steps (see the tolerance notes of the tests).
+// PARTS: as for gemm_bf16_nt (measurement builds only).
+template <int PARTS = 3>
 __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
 {
     constexpr int STAGE = 4 * HB_OPERAND_BYTES;              // 64 KiB
@@ -597,14 +599,16 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.ah[i], f0.bl[j], acc[i][j], 0, 0, 0);
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.al[i], f0.bh[j], acc[i][j], 0, 0, 0);
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.ah[i], f0.bh[j], acc[i][j], 0, 0, 0);
+                if (PARTS & 2) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.ah[i], f0.bl[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.al[i], f0.bh[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.ah[i], f0.bh[j], acc[i][j], 0, 0, 0);
+                }
             }
         __builtin_amdgcn_sched_barrier(0);
         // Slab it + 1 was requested a slab ago and only two prefetches have been issued since; this wavefront's
         // reads of slab `it` are complete.  Behind the barrier slab it + 1 may be read and slab it's buffer refilled.
-        JG_WAIT_VMCNT(PF > 0 ? 2 : 0);
+        if (PARTS & 1) JG_WAIT_VMCNT(PF > 0 ? 2 : 0);
         __builtin_amdgcn_s_waitcnt(0xC07F);    // lgkmcnt(0) only
         __syncthreads();
         read_frags(nxt, 0, f0);                // (after the last slab: a surplus copy, read but not used)
@@ -616,19 +620,22 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.ah[i], f1.bl[j], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.al[i], f1.bh[j], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.ah[i], f1.bh[j], acc[i][j], 0, 0, 0);
-                    issue(i * 4 + j, kt, stage);        // slab it + 2, one transfer after every third MFMA
+                    if (PARTS & 2) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.ah[i], f1.bl[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.al[i], f1.bh[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.ah[i], f1.bh[j], acc[i][j], 0, 0, 0);
+                    }
+                    if (PARTS & 1) issue(i * 4 + j, kt, stage);        // slab it + 2, one transfer after every third MFMA
                     __builtin_amdgcn_sched_barrier(0);
                 }
-            if (PF > 0) prefetch();
+            if ((PARTS & 1) && PF > 0) prefetch();
             advance();
         }
     }
     JG_WAIT_VMCNT(0);       // the surplus transfers have landed ...
     __syncthreads();        // ... and nobody reads a slab any more: the buffers become the waves' staging blocks
     float* shuffle = reinterpret_cast<float*>(slab + wave * (32 * HB_SHUFFLE_LD * 4));
+    if ((PARTS & 8) && acc[0][0][0] != 12345.f) return;
     if (run < 0) {
         hb_store_tile(P, M, N, tc.m0, tc.n0, wm, wn, lr, lk, interior, acc, g.act, shuffle);
     } else {
@@ -748,7 +755,7 @@ inline hipError_t launch_gemm_bf16_group(const GemmGroup& src, int terms, int pl
     *needs_join = false;
     const hipError_t e = make_bf16_group(src, terms, plane, cus, scratch, scratch_bytes, g);
     if (e != hipSuccess) return e;
-    if (terms == 3) hipLaunchKernelGGL(gemm_bf16x3_nt, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);
+    if (terms == 3) hipLaunchKernelGGL(gemm_bf16x3_nt<3>, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);
     else hipLaunchKernelGGL(gemm_bf16_nt<3>, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);
     *needs_join = g.parts > 0;
     return hipGetLastError();
