@@ -310,6 +310,24 @@ def linear_reduced(X, W, b=None, terms: int = 1, nthreads: int | None = None, ab
     return f(Xh, Wh, b, nthreads) + f(Xh, Wl, None, nthreads) + f(Xl, Wh, None, nthreads)
 
 
+def mlp_reduced(X, W1, b1, W2, b2, terms: int = 1, residual: bool = True, nthreads: int | None = None):
+    """One mixing MLP in the mixed precision of Sec. 6.1: both matrix products take their operands rounded to
+    bfloat16 (split in two for terms = 3) and sum exactly; bias, GELU and the skip connection are not rounded; H
+    is stored in FP32 between the layers, as the method stores every activation, and is rounded like any other
+    operand when the second product reads it.  Returns H, Y (double) and the magnitudes S1 (pre-activation) and
+    SY (the second layer's own sums, from the stored H)."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    S1 = linear_reduced(X, W1, b1, terms, nthreads, absolute=True)
+    H = gelu(linear_reduced(X, W1, b1, terms, nthreads))
+    H32 = H.astype(np.float32)
+    Y = linear_reduced(H32, W2, b2, terms, nthreads)
+    SY = linear_reduced(H32, W2, b2, terms, nthreads, absolute=True)
+    if residual:
+        Y = Y + X.astype(np.float64)
+        SY = SY + np.abs(X.astype(np.float64))
+    return dict(H=H, Y=Y, S1=S1, SY=SY)
+
+
 # ----------------------------------------------------------------------------
 # layer norm (Sec. 3; Sec. 5 "Layer norms") and the pre-norm channel-mixing block
 # ----------------------------------------------------------------------------
@@ -347,6 +365,17 @@ def mixing_block(ways: int, X, gamma, beta, W1, b1, W2, b2, eps: float = LN_EPS)
     method stores it.  Returns a dict like mlp() plus Xn (double, before rounding)."""
     Xn = layernorm(X, gamma, beta, ln_groups(ways), eps)
     out = mlp(Xn.astype(np.float32), W1, b1, W2, b2, residual=False)
+    out["Y"] = out["Y"] + np.asarray(X, dtype=np.float64)
+    out["SY"] = out["SY"] + np.abs(np.asarray(X, dtype=np.float64))
+    out["Xn"] = Xn
+    return out
+
+
+def mixing_block_reduced(ways: int, X, gamma, beta, W1, b1, W2, b2, terms: int = 1, eps: float = LN_EPS):
+    """mixing_block with the MLP's two products in mixed precision (mlp_reduced); the layer norm, its FP32
+    output Xn and the skip connection stay in full precision."""
+    Xn = layernorm(X, gamma, beta, ln_groups(ways), eps)
+    out = mlp_reduced(Xn.astype(np.float32), W1, b1, W2, b2, terms, residual=False)
     out["Y"] = out["Y"] + np.asarray(X, dtype=np.float64)
     out["SY"] = out["SY"] + np.abs(np.asarray(X, dtype=np.float64))
     out["Xn"] = Xn

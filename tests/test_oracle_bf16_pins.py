@@ -114,3 +114,80 @@ def test_split_products_by_hand():
     got = oracle.linear_reduced(np.array([[x]]), np.array([[w]]), None, 3)[0, 0]
     assert abs(got - want) <= 1e-16
     assert abs(got - float(x) * float(w)) <= 2.0 ** -15 * abs(float(x) * float(w))
+
+
+# ---------------------------------------------------------------------------------------------
+# the mixing MLP and the channel-mixing block in mixed precision
+# ---------------------------------------------------------------------------------------------
+def small_int_mlp(seed, M, C, Hd):
+    """Operands for which every step of the MLP is exact: X in {0, 1, 2}, W1 in {0, 1}, b1 = 10 (so that the
+    pre-activation is an integer in [10, 10 + 2 C], where gelu(x) = x Phi(x) rounds to x in double), W2 in
+    {-1, 0, 1}, b2 small integers."""
+    rng = np.random.default_rng(seed)
+    X = rng.integers(0, 3, (M, C)).astype(np.float32)
+    W1 = rng.integers(0, 2, (Hd, C)).astype(np.float32)
+    b1 = np.full(Hd, 10.0, dtype=np.float32)
+    W2 = rng.integers(-1, 2, (C, Hd)).astype(np.float32)
+    b2 = rng.integers(-3, 4, C).astype(np.float32)
+    return X, W1, b1, W2, b2
+
+
+@pytest.mark.parametrize("terms", [1, 3])
+def test_mixed_mlp_in_closed_form(terms):
+    M, C, Hd = 5, 8, 6
+    X, W1, b1, W2, b2 = small_int_mlp(320, M, C, Hd)
+    Xi, W1i, W2i = X.astype(np.int64), W1.astype(np.int64), W2.astype(np.int64)
+    H = Xi @ W1i.T + 10                       # integers up to 26: exact in bfloat16, and gelu leaves them alone
+    Y = Xi + H @ W2i.T + b2.astype(np.int64)
+    r = oracle.mlp_reduced(X, W1, b1, W2, b2, terms)
+    assert np.array_equal(r["H"], H.astype(np.float64))
+    assert np.array_equal(r["Y"], Y.astype(np.float64))
+    assert np.array_equal(oracle.mlp_reduced(X, W1, b1, W2, b2, terms, residual=False)["Y"], (Y - Xi).astype(np.float64))
+    # a transposed W2 or a dropped bias would give another matrix
+    assert not np.array_equal(Y, Xi + H @ W2i[:, ::-1].T + b2.astype(np.int64))
+    # magnitudes: sums of absolute values
+    assert np.array_equal(r["S1"], (Xi @ W1i.T + 10).astype(np.float64))
+    assert np.array_equal(r["SY"], (np.abs(Xi) + H @ np.abs(W2i).T + np.abs(b2.astype(np.int64))).astype(np.float64))
+
+
+@pytest.mark.parametrize("terms", [1, 3])
+def test_mixed_mlp_is_the_pinned_pieces_in_sequence(terms):
+    M, C, Hd = 6, 16, 24
+    X, W1, b1 = inputs.layer_inputs(321, M, C, Hd, "R")
+    W2 = inputs.matrix(322, C, Hd, "R", inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(323, 1, C, "R")[0]
+    r = oracle.mlp_reduced(X, W1, b1, W2, b2, terms)
+    H = oracle.gelu(oracle.linear_reduced(X, W1, b1, terms))
+    assert np.array_equal(r["H"], H)
+    Y = X.astype(np.float64) + oracle.linear_reduced(H.astype(np.float32), W2, b2, terms)
+    assert np.array_equal(r["Y"], Y)
+    # H is rounded again where the second product reads it: with the unrounded H the result differs, by no more
+    # than the rounding allows (2^-8 of |H| |W2| for one term, 2^-16 for the split)
+    full = oracle.mlp(X, W1, b1, W2, b2)
+    assert not np.array_equal(r["Y"], full["Y"])
+    loose = (2.0 ** -7 if terms == 1 else 2.0 ** -14) * (full["SY"] + full["PY"])
+    assert np.all(np.abs(r["Y"] - full["Y"]) <= loose)
+    if terms == 3:      # and the split is far closer to full precision than the single rounding
+        one = oracle.mlp_reduced(X, W1, b1, W2, b2, 1)
+        assert np.abs(r["Y"] - full["Y"]).max() < 0.02 * np.abs(one["Y"] - full["Y"]).max()
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+def test_mixed_block_norms_first_and_skips_in_full_precision(ways):
+    M, C, Hd = 6, 16, 24
+    X, W1, b1 = inputs.layer_inputs(324, M, C, Hd, "R")
+    X = (X + np.float32(0.3)).astype(np.float32)
+    W2 = inputs.matrix(325, C, Hd, "R", inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(326, 1, C, "R")[0]
+    gamma = (inputs.matrix(327, 1, C, "R")[0] + np.float32(1.5)).astype(np.float32)
+    beta = inputs.matrix(328, 1, C, "R")[0]
+    r = oracle.mixing_block_reduced(ways, X, gamma, beta, W1, b1, W2, b2, 1)
+    Xn = oracle.layernorm(X, gamma, beta, oracle.ln_groups(ways))
+    assert np.array_equal(r["Xn"], Xn)
+    inner = oracle.mlp_reduced(Xn.astype(np.float32), W1, b1, W2, b2, 1, residual=False)
+    assert np.array_equal(r["H"], inner["H"])
+    assert np.array_equal(r["Y"], inner["Y"] + X.astype(np.float64))          # X itself, not its rounding
+    assert not np.array_equal(r["Y"], inner["Y"] + oracle.round_bf16(X).astype(np.float64))
+    # zero second layer: the block is the identity plus b2
+    z = oracle.mixing_block_reduced(ways, X, gamma, beta, W1, b1, np.zeros_like(W2), b2, 1)
+    assert np.array_equal(z["Y"], X.astype(np.float64) + b2)
