@@ -61,6 +61,31 @@ def tail_of(args):
     return jg.JG_TAIL_SPLIT if args.tail == "split" else jg.JG_TAIL_WHOLE
 
 
+def dtype_of(args, jg):
+    return {"f32": jg.JG_F32, "bf16": jg.JG_BF16, "bf16x3": jg.JG_BF16X3}[args.dtype]
+
+
+def gemm_roofline(args, r):
+    """The roofline object of the MLP / mixing lines: the GEMM kernel of the chosen precision against its peak."""
+    terms = 3 if args.dtype == "bf16x3" else 1
+    reduced = args.dtype != "f32"
+    peak = BF16_MFMA_PEAK_TFLOPS if reduced else FP32_MFMA_PEAK_TFLOPS
+    achieved = r["gemm_tflops"] * terms if r["gemm_tflops"] else None      # matrix-core work: three products per block
+    kernel = {"f32": "jg::gemm_f32_stream<false, false, false>", "bf16": "jg::gemm_bf16_nt",
+              "bf16x3": "jg::gemm_bf16x3_nt"}[args.dtype]
+    out = {"bound": "mfma", "kernel": kernel, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+           "frac": achieved / peak if achieved else None, "avg_launch_ms": r["gemm_avg_launch_ms"],
+           "launches": r["gemm_launches_timed"], "traffic": None}
+    if reduced:
+        out["matrix_passes"] = terms
+    return out
+
+
+def precision_words(args):
+    return {"f32": "fp32", "bf16": "mixed precision: bfloat16 products, fp32 sums and activations",
+            "bf16x3": "mixed precision: split bfloat16 operands (three products), fp32 sums and activations"}[args.dtype]
+
+
 def make_inputs(cfg, dev):
     """Global X [M,K] and W [N,K] on the device (seeded, synthetic)."""
     import torch
@@ -81,7 +106,8 @@ def time_forward(L, jg, steps, warmup, norm=None):
     for _ in range(warmup):
         L.forward()
     torch.cuda.synchronize()
-    for k in (jg.JG_KERNEL_GEMM, jg.JG_KERNEL_WEIGHT_COPY, jg.JG_KERNEL_COMBINE, jg.JG_KERNEL_JOIN, jg.JG_KERNEL_NORM):
+    for k in (jg.JG_KERNEL_GEMM, jg.JG_KERNEL_WEIGHT_COPY, jg.JG_KERNEL_COMBINE, jg.JG_KERNEL_JOIN, jg.JG_KERNEL_NORM,
+              jg.JG_KERNEL_SHARD):
         jg.jg_profile_read(L.ctx, k)
     jg.jg_profile(L.ctx, True)
     torch.cuda.synchronize()
@@ -95,9 +121,11 @@ def time_forward(L, jg, steps, warmup, norm=None):
     wc_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_WEIGHT_COPY)
     cb_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_COMBINE)
     join_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_JOIN)   # tail join of split launches, counted with the hand-off copy
+    cvt_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_SHARD)   # a mixed-precision chain rounds its activations per layer
     if norm is not None:
         norm["ms"], norm["launches"] = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_NORM)
-    return (t1 - t0) / steps, gemm_ms, gemm_n, (wc_ms + join_ms) / steps, cb_ms / steps
+        norm["cvt_ms_per_step"] = cvt_ms / steps
+    return (t1 - t0) / steps, gemm_ms, gemm_n, (wc_ms + join_ms + cvt_ms) / steps, cb_ms / steps
 
 
 def measure(cfg, ways, args, X, W, streaming=False):
@@ -311,7 +339,7 @@ def measure_mlp(cfg, ways, args):
     M, C, Hd, seed = cfg["M"], cfg["C"], cfg["Hd"], cfg["seed"]
     dev = torch.device("cuda", 0)
     gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device=dev)
-    with JigsawMLP(M, C, Hd, ways, tail=tail_of(args)) as L:
+    with JigsawMLP(M, C, Hd, ways, tail=tail_of(args), dtype=dtype_of(args, jg)) as L:
         L.shard(gen(seed, M, C), gen(seed + 1, Hd, C, inputs.W_SCALE_EXP), gen(seed + 2, 1, Hd)[0].contiguous(),
                 gen(seed + 3, C, Hd, inputs.W_SCALE_EXP), gen(seed + 4, 1, C)[0].contiguous())
         sec, gemm_ms, gemm_n, copy_ms, comb_ms = time_forward(L, jg, args.steps, args.warmup)
@@ -335,7 +363,7 @@ def measure_mixing(cfg, ways, args):
     M, C, Hd, seed = cfg["M"], cfg["C"], cfg["Hd"], cfg["seed"]
     dev = torch.device("cuda", 0)
     gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device=dev)
-    with JigsawMixing(M, C, Hd, ways, tail=tail_of(args)) as L:
+    with JigsawMixing(M, C, Hd, ways, tail=tail_of(args), dtype=dtype_of(args, jg)) as L:
         L.shard(gen(seed, M, C), (gen(seed + 5, 1, C)[0] + 1.5).contiguous(), gen(seed + 6, 1, C)[0].contiguous(),
                 gen(seed + 1, Hd, C, inputs.W_SCALE_EXP), gen(seed + 2, 1, Hd)[0].contiguous(),
                 gen(seed + 3, C, Hd, inputs.W_SCALE_EXP), gen(seed + 4, 1, C)[0].contiguous())
@@ -355,7 +383,11 @@ def measure_mixing(cfg, ways, args):
     return out
 
 
-def cpu_baseline_mixing(cfg, seconds):
+def reduced_terms(args):
+    return {"f32": 0, "bf16": 1, "bf16x3": 3}[args.dtype]
+
+
+def cpu_baseline_mixing(cfg, seconds, terms=0):
     """The mixing-block oracle (layer norm + MLP + skip) timed on a bounded sample of tokens (rows of X)."""
     import oracle
     from paper_2507_05753_amd import inputs
@@ -371,8 +403,11 @@ def cpu_baseline_mixing(cfg, seconds):
     def run(rows):
         X = inputs.matrix(seed, M, C, "R", row_begin=0, row_end=rows)
         t0 = time.perf_counter()
-        Xn = oracle.layernorm(X, gamma, beta, 1, nthreads=cores)
-        oracle.mlp(Xn.astype("float32"), W1, b1, W2, b2, residual=False, nthreads=cores)["Y"] + X
+        if terms:
+            oracle.mixing_block_reduced(1, X, gamma, beta, W1, b1, W2, b2, terms)
+        else:
+            Xn = oracle.layernorm(X, gamma, beta, 1, nthreads=cores)
+            oracle.mlp(Xn.astype("float32"), W1, b1, W2, b2, residual=False, nthreads=cores)["Y"] + X
         return time.perf_counter() - t0
 
     probe = min(M, 2 * cores)
@@ -382,10 +417,10 @@ def cpu_baseline_mixing(cfg, seconds):
     dt = run(rows)
     return dict(value=rows * C / dt, unit="items/s", cores=cores, kind="oracle",
                 sample=f"tokens 0..{rows - 1} of X ({rows} x {C}) through the norm and both layers ({Hd} hidden), "
-                       f"{dt:.1f} s, fp64 loops")
+                       f"{dt:.1f} s, " + ("fp64 loops" if not terms else f"bfloat16 rounding / split + fp64 loops, {terms} per layer"))
 
 
-def cpu_baseline_mlp(cfg, seconds):
+def cpu_baseline_mlp(cfg, seconds, terms=0):
     """The MLP oracle timed on a bounded sample of tokens (rows of X)."""
     import oracle
     from paper_2507_05753_amd import inputs
@@ -399,7 +434,10 @@ def cpu_baseline_mlp(cfg, seconds):
     def run(rows):
         X = inputs.matrix(seed, M, C, "R", row_begin=0, row_end=rows)
         t0 = time.perf_counter()
-        oracle.mlp(X, W1, b1, W2, b2, nthreads=cores)
+        if terms:
+            oracle.mlp_reduced(X, W1, b1, W2, b2, terms, nthreads=cores)
+        else:
+            oracle.mlp(X, W1, b1, W2, b2, nthreads=cores)
         return time.perf_counter() - t0
 
     probe = min(M, 2 * cores)
@@ -408,7 +446,8 @@ def cpu_baseline_mlp(cfg, seconds):
     rows = min(M, max(cores, rows // cores * cores))
     dt = run(rows)
     return dict(value=rows * C / dt, unit="items/s", cores=cores, kind="oracle",
-                sample=f"tokens 0..{rows - 1} of X ({rows} x {C}) through both layers ({Hd} hidden), {dt:.1f} s, fp64 loops")
+                sample=f"tokens 0..{rows - 1} of X ({rows} x {C}) through both layers ({Hd} hidden), {dt:.1f} s, "
+                       + ("fp64 loops" if not terms else f"bfloat16 rounding / split + fp64 loops, {terms} per layer"))
 
 
 def cpu_baseline_xtw(cfg, seconds):
@@ -515,8 +554,8 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     from paper_2507_05753_amd import inputs
-    if args.dtype != "f32" and args.op != "forward":
-        print("bench.py: --dtype bf16 / bf16x3 goes with --op forward only", file=sys.stderr)
+    if args.dtype != "f32" and args.op not in ("forward", "mlp", "mixing"):
+        print("bench.py: --dtype bf16 / bf16x3 goes with --op forward, mlp or mixing only", file=sys.stderr)
         sys.exit(2)
 
     if args.op == "xtw":
@@ -581,18 +620,14 @@ def main():
             "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
             "value": r["items_per_s"], "unit": "items/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
-            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
             "config": {"workload": f"channel-mixing half of a mixing block of the 1B model: Xn = layernorm(X), "
                                    f"H = gelu(Xn W1^T + b1), Y = X + H W2^T + b2, X {M} x {C}, hidden {Hd}, "
-                                   f"{args.ways}-way Jigsaw, fp32",
+                                   f"{args.ways}-way Jigsaw, {precision_words(args)}",
                        "n_items": M * C, "ways": args.ways, "M": M, "C": C, "Hd": Hd, "seed": mc["seed"],
-                       "x_values": "R", "op": "mixing", "tail": args.tail},
+                       "x_values": "R", "op": "mixing", "tail": args.tail, "mode": args.dtype},
             "tflops": r["tflops"],
-            "roofline": {"bound": "mfma", "kernel": "jg::gemm_f32_stream<false, false, false>",
-                         "achieved": r["gemm_tflops"], "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": r["gemm_tflops"] / FP32_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None,
-                         "avg_launch_ms": r["gemm_avg_launch_ms"], "launches": r["gemm_launches_timed"],
-                         "traffic": None},
+            "roofline": gemm_roofline(args, r),
             "layernorm": {"bound": "hbm", "kernel": "jg::layernorm_rows_f32", "achieved": r["norm_gbps"],
                           "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                           "frac": r["norm_gbps"] / HBM_PEAK_GBPS if r["norm_gbps"] else None,
@@ -601,7 +636,7 @@ def main():
             "other_kernels_ms_per_step": r["other_kernels_ms_per_step"],
         }
         if args.cpu_seconds > 0:
-            line["cpu_baseline"] = cpu_baseline_mixing(mc, args.cpu_seconds)
+            line["cpu_baseline"] = cpu_baseline_mixing(mc, args.cpu_seconds, reduced_terms(args))
         print(json.dumps(line), flush=True)
         return
 
@@ -613,21 +648,17 @@ def main():
             "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
             "value": r["items_per_s"], "unit": "items/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
-            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
             "config": {"workload": f"channel-mixing MLP of the 1B model: H = gelu(X W1^T + b1), Y = X + H W2^T + b2, "
-                                   f"X {M} x {C}, hidden {Hd}, {args.ways}-way Jigsaw, fp32",
+                                   f"X {M} x {C}, hidden {Hd}, {args.ways}-way Jigsaw, {precision_words(args)}",
                        "n_items": M * C, "ways": args.ways, "M": M, "C": C, "Hd": Hd, "seed": mc["seed"],
-                       "x_values": "R", "op": "mlp", "tail": args.tail},
+                       "x_values": "R", "op": "mlp", "tail": args.tail, "mode": args.dtype},
             "tflops": r["tflops"],
-            "roofline": {"bound": "mfma", "kernel": "jg::gemm_f32_stream<false, false, false>",
-                         "achieved": r["gemm_tflops"], "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": r["gemm_tflops"] / FP32_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None,
-                         "avg_launch_ms": r["gemm_avg_launch_ms"], "launches": r["gemm_launches_timed"],
-                         "traffic": None},
+            "roofline": gemm_roofline(args, r),
             "other_kernels_ms_per_step": r["other_kernels_ms_per_step"],
         }
         if args.cpu_seconds > 0:
-            line["cpu_baseline"] = cpu_baseline_mlp(mc, args.cpu_seconds)
+            line["cpu_baseline"] = cpu_baseline_mlp(mc, args.cpu_seconds, reduced_terms(args))
         print(json.dumps(line), flush=True)
         return
 

@@ -88,7 +88,9 @@ enum { JG_COMBINE_FUSED = 0, JG_COMBINE_SEPARATE = 1 };  /* where the "+" of Eq.
 enum { JG_WEIGHTS_COPY = 0, JG_WEIGHTS_DIRECT = 1 };     /* 4-way weight-block hand-off */
 enum { JG_TAIL_SPLIT = 0, JG_TAIL_WHOLE = 1 };           /* last partial round of a GEMM launch */
 enum { JG_ACT_NONE = 0, JG_ACT_GELU = 1 };               /* epilogue activation of jg_linear_forward_ex */
-enum { JG_T_X = 0, JG_T_W = 1, JG_T_B = 2, JG_T_Y = 3 }; /* tensor selector of jg_shard / jg_gather_as */
+enum { JG_T_X = 0, JG_T_W = 1, JG_T_B = 2, JG_T_Y = 3,   /* tensor selector of jg_shard / jg_gather_as */
+       JG_T_X_F32 = 4 };  /* partitioned like X, stored in FP32 whatever the plan's dtype: the activations a
+                             mixed-precision MLP chain takes, its skip connection, a layer norm's output */
 
 typedef struct jg_linear_desc {
     int64_t M, K, N;     /* global sizes: Y is M x N and K is contracted.  JG_OP_XWT: X is
@@ -144,7 +146,10 @@ typedef enum jg_query {
     JG_Q_TAIL_SCRATCH_BYTES = 17,       /* part of JG_Q_WORKSPACE_BYTES that JG_TAIL_SPLIT adds   */
     JG_Q_BACKWARD_TAIL_SCRATCH_BYTES = 18, /* the same for JG_Q_BACKWARD_WORKSPACE_BYTES          */
     JG_Q_X_SHARD_BYTES = 19,            /* bytes of the rank's X shard in the plan's dtype        */
-    JG_Q_W_SHARD_BYTES = 20             /* ... and of its W shard                                 */
+    JG_Q_W_SHARD_BYTES = 20,            /* ... and of its W shard                                 */
+    JG_Q_CHAIN_WORKSPACE_BYTES = 21     /* workspace the plan needs as a layer of jg_mlp_forward /
+                                           jg_mixing_forward: JG_Q_WORKSPACE_BYTES, plus (reduced
+                                           precision) room for its input in bfloat16 (rank ignored) */
 } jg_query;
 
 typedef enum jg_kernel {         /* kernel classes for jg_profile_read */
@@ -274,10 +279,16 @@ int jg_linear_forward_ex(const jg_plan* plan, const float* const* x_sh, const fl
  * its output partitioned like its input (Sec. 4.1), H_r is consumed where it was produced: no
  * re-sharding between the layers.  h_sh: `ways` device buffers shaped like the first plan's Y_r
  * (H is kept: a backward pass would need it).  The workspace is used by both layers in turn and
- * must satisfy both plans' JG_Q_WORKSPACE_BYTES.  x_sh is read by both layers and must not
+ * must satisfy both plans' JG_Q_CHAIN_WORKSPACE_BYTES.  x_sh is read by both layers and must not
  * overlap h_sh or y_sh.
- * Errors: JG_E_NULL, JG_E_DTYPE (op), JG_E_WAYS, JG_E_SHAPE (plans do not chain), and those of
- * jg_linear_forward_ex. */
+ * Mixed precision (Sec. 6.1: the matrix units round their FP32 operands, everything else stays FP32):
+ * both plans JG_BF16, or both JG_BF16X3.  x_sh, h_sh and y_sh are then still FP32 shards (x_sh as
+ * jg_shard(JG_T_X_F32) writes them), w1_sh / w2_sh the plans' bfloat16 weight shards.  Each layer
+ * rounds its input activations into the workspace as jg_shard rounds X (H is rounded from the FP32
+ * values stored in h_sh), runs its products on the bfloat16 matrix cores and adds bias, GELU and
+ * the skip connection (from the unrounded x_sh) in FP32.
+ * Errors: JG_E_NULL, JG_E_DTYPE (op, or the two plans' dtypes differ), JG_E_WAYS, JG_E_SHAPE (plans do
+ * not chain), and those of jg_linear_forward_ex. */
 int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh,
                    const float* const* w1_sh, const float* const* b1_sh, const float* const* w2_sh,
                    const float* const* b2_sh, float* const* h_sh, float* const* y_sh, void* workspace,
@@ -294,7 +305,7 @@ int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* con
  * (scale 1, offset 0).  eps >= 0; the library's default is 1e-5.  out_sh: `ways` device buffers shaped
  * like X_r; out_sh[r] may be x_sh[r] (in place), other overlaps are not allowed.  Sums and the
  * normalisation are evaluated in double and rounded once.  Needs no workspace; asynchronous on the
- * context's stream.
+ * context's stream.  Input and output are FP32 whatever the plan's dtype (JG_T_X_F32 shards).
  * Errors: JG_E_NULL, JG_E_DTYPE (eps negative or NaN), JG_E_ALIGN, JG_E_HIP. */
 int jg_layernorm_forward(const jg_plan* plan, const float* const* x_sh, const float* gamma, const float* beta,
                          double eps, float* const* out_sh);

@@ -35,12 +35,13 @@ JG_COMBINE_FUSED, JG_COMBINE_SEPARATE = 0, 1
 JG_WEIGHTS_COPY, JG_WEIGHTS_DIRECT = 0, 1
 JG_TAIL_SPLIT, JG_TAIL_WHOLE = 0, 1
 JG_ACT_NONE, JG_ACT_GELU = 0, 1
-JG_T_X, JG_T_W, JG_T_B, JG_T_Y = 0, 1, 2, 3
+JG_T_X, JG_T_W, JG_T_B, JG_T_Y, JG_T_X_F32 = 0, 1, 2, 3, 4
 (JG_Q_WORKSPACE_BYTES, JG_Q_FLOPS_TOTAL, JG_Q_FLOPS_RANK, JG_Q_HBM_BYTES_ALGO,
  JG_Q_EXCHANGE_BYTES_RANK, JG_Q_X_ROWS, JG_Q_X_COLS, JG_Q_W_ROWS, JG_Q_W_COLS,
  JG_Q_Y_ROWS, JG_Q_Y_COLS, JG_Q_B_LEN, JG_Q_RESIDENT_BYTES_RANK, JG_Q_GEMM_LAUNCHES,
  JG_Q_BACKWARD_WORKSPACE_BYTES, JG_Q_BACKWARD_FLOPS_TOTAL, JG_Q_BACKWARD_GEMM_LAUNCHES,
- JG_Q_TAIL_SCRATCH_BYTES, JG_Q_BACKWARD_TAIL_SCRATCH_BYTES, JG_Q_X_SHARD_BYTES, JG_Q_W_SHARD_BYTES) = range(21)
+ JG_Q_TAIL_SCRATCH_BYTES, JG_Q_BACKWARD_TAIL_SCRATCH_BYTES, JG_Q_X_SHARD_BYTES, JG_Q_W_SHARD_BYTES,
+ JG_Q_CHAIN_WORKSPACE_BYTES) = range(22)
 (JG_KERNEL_GEMM, JG_KERNEL_WEIGHT_COPY, JG_KERNEL_COMBINE, JG_KERNEL_SHARD,
  JG_KERNEL_GATHER, JG_KERNEL_GEMM_DX, JG_KERNEL_GEMM_DW, JG_KERNEL_JOIN, JG_KERNEL_NORM,
  JG_KERNEL_COUNT) = range(10)

@@ -74,6 +74,9 @@ struct jg_plan {
     // scratch tiles of the split tail (largest need over the pass's launches), at the end of each workspace
     int slots;
     size_t tail_bytes, off_tail, bw_tail_bytes, bw_off_tail;
+    // reduced precision, as a layer of an MLP chain: the FP32 input activations are converted into ways shards of
+    // chain_shard_bytes each, behind the layer's own workspace
+    size_t chain_shard_bytes, chain_bytes;
 };
 
 namespace {
@@ -340,6 +343,9 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     p->ws_bytes += p->tail_bytes;
     p->bw_off_tail = p->bw_ws_bytes;
     p->bw_ws_bytes += p->bw_tail_bytes;
+    p->ws_bytes = round_up(p->ws_bytes, kWsAlign);
+    p->chain_shard_bytes = reduced ? round_up(4 * (size_t)p->xr * (size_t)p->xcp, kWsAlign) : 0;
+    p->chain_bytes = p->chain_shard_bytes * d.ways;
     *out = p;
     return JG_OK;
 }
@@ -400,6 +406,7 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     case JG_Q_BACKWARD_TAIL_SCRATCH_BYTES: *out = (int64_t)plan->bw_tail_bytes; break;
     case JG_Q_X_SHARD_BYTES: *out = 4 * plan->xr * plan->xcp; break;
     case JG_Q_W_SHARD_BYTES: *out = 4 * plan->wr * plan->xcp; break;
+    case JG_Q_CHAIN_WORKSPACE_BYTES: *out = (int64_t)(plan->ws_bytes + plan->chain_bytes); break;
     default: return JG_E_DTYPE;
     }
     return JG_OK;
@@ -414,7 +421,8 @@ struct Partition {
 static int partition_of(const jg_plan* plan, int which, Partition* out)
 {
     switch (which) {
-    case JG_T_X: *out = {plan->xr, plan->xc, plan->d.op == JG_OP_XTW ? plan->d.M : plan->d.K}; return JG_OK;
+    case JG_T_X:
+    case JG_T_X_F32: *out = {plan->xr, plan->xc, plan->d.op == JG_OP_XTW ? plan->d.M : plan->d.K}; return JG_OK;
     case JG_T_W: *out = {plan->wr, plan->wc, plan->d.op == JG_OP_XTW ? plan->d.N : plan->d.K}; return JG_OK;
     case JG_T_Y: *out = {plan->yr, plan->yc, plan->d.N}; return JG_OK;
     default: return JG_E_DTYPE;
@@ -435,7 +443,8 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
     const jg_linear_desc& d = plan->d;
     if (int rc = check_ptr_array(shards, d.ways)) return rc;
     if (!aligned(global, 4)) return JG_E_ALIGN;
-    if (which != JG_T_X && which != JG_T_W && which != JG_T_B && which != JG_T_Y) return JG_E_DTYPE;
+    if (which != JG_T_X && which != JG_T_W && which != JG_T_B && which != JG_T_Y && which != JG_T_X_F32)
+        return JG_E_DTYPE;
     jg_ctx* c = plan->ctx;
     if (!c) return JG_E_NULL;
     if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
@@ -466,7 +475,7 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
     std::memset(&g, 0, sizeof(g));
     g.nblocks = d.ways;
     // activations and gradients are streamed once; weights and bias are re-read soon
-    g.nontemporal = which == JG_T_X || which == JG_T_Y;
+    g.nontemporal = which == JG_T_X || which == JG_T_Y || which == JG_T_X_F32;
     if (which == JG_T_B) {
         g.rows = 1;
         g.cols = (int)plan->yc;
@@ -498,7 +507,8 @@ int jg_gather_as(const jg_plan* plan, int which, const float* const* shards, flo
     if (!aligned(global, 4)) return JG_E_ALIGN;
     Partition pt;
     if (int rc = partition_of(plan, which, &pt)) return rc;
-    if (d.dtype != JG_F32 && which != JG_T_Y) return JG_E_DTYPE;   // bfloat16 shards are not converted back
+    if (d.dtype != JG_F32 && (which == JG_T_X || which == JG_T_W))
+        return JG_E_DTYPE;   // bfloat16 shards are not converted back
     if (ld < pt.width) return JG_E_SHAPE;
     jg_ctx* c = plan->ctx;
     if (!c) return JG_E_NULL;
@@ -933,7 +943,7 @@ int jg_layernorm_forward(const jg_plan* plan, const float* const* x_sh, const fl
     const jg_linear_desc& d = plan->d;
     if (int rc = check_ptr_array(x_sh, d.ways)) return rc;
     if (int rc = check_ptr_array(out_sh, d.ways)) return rc;
-    if (d.dtype != JG_F32 || !(eps >= 0.0)) return JG_E_DTYPE;
+    if (!(eps >= 0.0)) return JG_E_DTYPE;
     if (!aligned(gamma, 4) || !aligned(beta, 4)) return JG_E_ALIGN;
     for (int r = 0; r < d.ways; ++r)
         if (!aligned(x_sh[r], 4) || !aligned(out_sh[r], 4)) return JG_E_ALIGN;
@@ -960,11 +970,48 @@ static int check_mlp_chain(const jg_plan* first, const jg_plan* second)
     if (!first || !second) return JG_E_NULL;
     const jg_linear_desc &a = first->d, &b = second->d;
     if (a.op != JG_OP_XWT || b.op != JG_OP_XWT) return JG_E_DTYPE;
-    if (a.dtype != JG_F32 || b.dtype != JG_F32) return JG_E_DTYPE;   // H leaves the first layer in FP32
+    if (a.dtype != b.dtype) return JG_E_DTYPE;
     if (a.ways != b.ways) return JG_E_WAYS;
     if (a.M != b.M || a.N != b.K || b.N != a.K) return JG_E_SHAPE;
     if (first->ctx != second->ctx) return JG_E_NULL;
     return JG_OK;
+}
+
+// One layer of an MLP chain.  in_sh: the layer's input activations as FP32 shards (xr x xc, dense).  A
+// reduced-precision plan first writes them in the format its matrix products read (the conversion jg_shard
+// applies to X), into the chain region behind its own workspace.
+static int chain_layer(const jg_plan* plan, const float* const* in_sh, const float* const* w_sh,
+                       const float* const* b_sh, const float* const* r_sh, int activation, float* const* out_sh,
+                       void* workspace, size_t workspace_bytes)
+{
+    const jg_linear_desc& d = plan->d;
+    if (d.dtype == JG_F32)
+        return jg_linear_forward_ex(plan, in_sh, w_sh, b_sh, r_sh, activation, out_sh, workspace, workspace_bytes);
+    if (int rc = check_ptr_array(in_sh, d.ways)) return rc;
+    if (!workspace || workspace_bytes < plan->ws_bytes + plan->chain_bytes) return JG_E_WORKSPACE;
+    if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
+    jg_ctx* c = plan->ctx;
+    if (!c) return JG_E_NULL;
+    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    const float* conv[4] = {nullptr, nullptr, nullptr, nullptr};
+    jg::CvtGroup cv;
+    std::memset(&cv, 0, sizeof(cv));
+    cv.nblocks = d.ways;
+    cv.rows = (int)plan->xr;
+    cv.cols = (int)plan->xc;
+    cv.planes = d.dtype == JG_BF16X3 ? 2 : 1;
+    cv.plane = (int)plan->plane;
+    for (int r = 0; r < d.ways; ++r) {
+        if (!aligned(in_sh[r], 4)) return JG_E_ALIGN;
+        char* dst = static_cast<char*>(workspace) + plan->ws_bytes + r * plan->chain_shard_bytes;
+        cv.b[r] = {in_sh[r], reinterpret_cast<uint16_t*>(dst), plan->xc};
+        conv[r] = reinterpret_cast<const float*>(dst);
+    }
+    {
+        ScopedTimer t(c, JG_KERNEL_SHARD);
+        if (!HIP_OK(jg::launch_cvt_group(cv, c->stream))) return JG_E_HIP;
+    }
+    return jg_linear_forward_ex(plan, conv, w_sh, b_sh, r_sh, activation, out_sh, workspace, workspace_bytes);
 }
 
 int jg_mixing_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* gamma,
@@ -976,9 +1023,9 @@ int jg_mixing_forward(const jg_plan* first, const jg_plan* second, const float* 
     if (int rc = check_ptr_array(h_sh, first->d.ways)) return rc;
     int rc = jg_layernorm_forward(first, x_sh, gamma, beta, eps, xn_sh);
     if (rc != JG_OK) return rc;
-    rc = jg_linear_forward_ex(first, xn_sh, w1_sh, b1_sh, nullptr, JG_ACT_GELU, h_sh, workspace, workspace_bytes);
+    rc = chain_layer(first, xn_sh, w1_sh, b1_sh, nullptr, JG_ACT_GELU, h_sh, workspace, workspace_bytes);
     if (rc != JG_OK) return rc;
-    return jg_linear_forward_ex(second, h_sh, w2_sh, b2_sh, x_sh, JG_ACT_NONE, y_sh, workspace, workspace_bytes);
+    return chain_layer(second, h_sh, w2_sh, b2_sh, x_sh, JG_ACT_NONE, y_sh, workspace, workspace_bytes);
 }
 
 int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh,
@@ -989,9 +1036,9 @@ int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* con
     if (int rc = check_mlp_chain(first, second)) return rc;
     if (int rc = check_ptr_array(h_sh, first->d.ways)) return rc;
     // H_r is written by the first layer in the partition the second one reads its input in
-    int rc = jg_linear_forward_ex(first, x_sh, w1_sh, b1_sh, nullptr, JG_ACT_GELU, h_sh, workspace, workspace_bytes);
+    int rc = chain_layer(first, x_sh, w1_sh, b1_sh, nullptr, JG_ACT_GELU, h_sh, workspace, workspace_bytes);
     if (rc != JG_OK) return rc;
-    return jg_linear_forward_ex(second, h_sh, w2_sh, b2_sh, x_sh, JG_ACT_NONE, y_sh, workspace, workspace_bytes);
+    return chain_layer(second, h_sh, w2_sh, b2_sh, x_sh, JG_ACT_NONE, y_sh, workspace, workspace_bytes);
 }
 
 }  // extern "C"

@@ -168,25 +168,42 @@ class JigsawMLP:
     """One mixing MLP with its skip connection on Jigsaw shards: H = gelu(X W1^T + b1), Y = X + H W2^T + b2.
 
     X and Y are (M, C), W1 is (Hd, C), W2 is (C, Hd).  Two JigsawLinear holders share one context; the
-    second reads the first one's output shards in place (``jg_mlp_forward``).
+    second reads the first one's output shards in place (``jg_mlp_forward``).  ``dtype = JG_BF16 /
+    JG_BF16X3``: mixed precision - the weight shards are bfloat16, X, H and Y stay FP32 and each layer rounds
+    its input into the workspace.
     """
 
-    def __init__(self, M: int, C: int, Hd: int, ways: int, device: int = 0, ctx=None, tail: int = jg.JG_TAIL_SPLIT):
-        self.first = JigsawLinear(M, C, Hd, ways, bias=True, device=device, ctx=ctx, tail=tail)
-        self.second = JigsawLinear(M, Hd, C, ways, bias=True, device=device, ctx=self.first.ctx, tail=tail)
+    def __init__(self, M: int, C: int, Hd: int, ways: int, device: int = 0, ctx=None, tail: int = jg.JG_TAIL_SPLIT,
+                 dtype: int = jg.JG_F32):
+        self.first = JigsawLinear(M, C, Hd, ways, bias=True, device=device, ctx=ctx, tail=tail, dtype=dtype)
+        self.second = JigsawLinear(M, Hd, C, ways, bias=True, device=device, ctx=self.first.ctx, tail=tail, dtype=dtype)
+        self.dtype = dtype
+        if dtype == jg.JG_F32:
+            self.xin = self.first.x
+        else:       # FP32 activations, partitioned like X (the holders' bfloat16 X shards are not used)
+            q = self.first.query
+            self.xin = [torch.empty((q(jg.JG_Q_X_ROWS, r), q(jg.JG_Q_X_COLS, r)), dtype=torch.float32,
+                                    device=self.first.dev) for r in range(ways)]
+            self.first.x = None
         self.second.x = self.first.y        # H_r is consumed where it was produced
         self.M, self.C, self.Hd, self.ways = M, C, Hd, ways
         self.ctx = self.first.ctx
-        self.ws_bytes = max(self.first.ws_bytes, self.second.ws_bytes)
-        self.ws = self.first.ws if self.first.ws_bytes >= self.second.ws_bytes else self.second.ws
+        self.ws_bytes = max(self.first.query(jg.JG_Q_CHAIN_WORKSPACE_BYTES), self.second.query(jg.JG_Q_CHAIN_WORKSPACE_BYTES))
+        self.ws = max((self.first.ws, self.second.ws), key=lambda t: t.numel())
+        if self.ws.numel() < self.ws_bytes:
+            self.first.ws = self.second.ws = None
+            self.ws = torch.empty((self.ws_bytes,), dtype=torch.uint8, device=self.first.dev)
 
     def shard(self, X=None, W1=None, b1=None, W2=None, b2=None):
-        self.first.shard(X, W1, b1)
+        if X is not None:
+            assert X.is_cuda and X.dtype == torch.float32 and X.shape == (self.M, self.C) and X.stride(1) == 1
+            jg.jg_shard(self.first.plan, jg.JG_T_X_F32, X.data_ptr(), X.stride(0), [t.data_ptr() for t in self.xin])
+        self.first.shard(None, W1, b1)
         self.second.shard(None, W2, b2)
 
     def forward(self):
         f, s = self.first, self.second
-        jg.jg_mlp_forward(f.plan, s.plan, [t.data_ptr() for t in f.x], [t.data_ptr() for t in f.w],
+        jg.jg_mlp_forward(f.plan, s.plan, [t.data_ptr() for t in self.xin], [t.data_ptr() for t in f.w],
                           [t.data_ptr() for t in f.b], [t.data_ptr() for t in s.w], [t.data_ptr() for t in s.b],
                           [t.data_ptr() for t in f.y], [t.data_ptr() for t in s.y],
                           self.ws.data_ptr() if self.ws_bytes else None, self.ws_bytes)
@@ -213,10 +230,10 @@ class JigsawMixing(JigsawMLP):
     (``jg_mixing_forward``).  ``gamma`` / ``beta``: device vectors of length C."""
 
     def __init__(self, M: int, C: int, Hd: int, ways: int, device: int = 0, ctx=None, tail: int = jg.JG_TAIL_SPLIT,
-                 eps: float = 1e-5):
-        super().__init__(M, C, Hd, ways, device=device, ctx=ctx, tail=tail)
+                 eps: float = 1e-5, dtype: int = jg.JG_F32):
+        super().__init__(M, C, Hd, ways, device=device, ctx=ctx, tail=tail, dtype=dtype)
         self.eps = eps
-        self.xn = [torch.empty_like(t) for t in self.first.x]
+        self.xn = [torch.empty_like(t) for t in self.xin]
         self.gamma = self.beta = None
 
     def shard(self, X=None, gamma=None, beta=None, W1=None, b1=None, W2=None, b2=None):
@@ -228,12 +245,12 @@ class JigsawMixing(JigsawMLP):
     def forward(self):
         f, s = self.first, self.second
         p = lambda ts: [t.data_ptr() for t in ts]
-        jg.jg_mixing_forward(f.plan, s.plan, p(f.x), self.gamma.data_ptr() if self.gamma is not None else None,
+        jg.jg_mixing_forward(f.plan, s.plan, p(self.xin), self.gamma.data_ptr() if self.gamma is not None else None,
                              self.beta.data_ptr() if self.beta is not None else None, self.eps, p(f.w), p(f.b),
                              p(s.w), p(s.b), p(self.xn), p(f.y), p(s.y),
                              self.ws.data_ptr() if self.ws_bytes else None, self.ws_bytes)
 
     def gather_xn(self):
         out = torch.empty((self.M, self.C), dtype=torch.float32, device=self.first.dev)
-        jg.jg_gather_as(self.first.plan, jg.JG_T_X, [t.data_ptr() for t in self.xn], out.data_ptr(), out.stride(0))
+        jg.jg_gather_as(self.first.plan, jg.JG_T_X_F32, [t.data_ptr() for t in self.xn], out.data_ptr(), out.stride(0))
         return out

@@ -235,8 +235,8 @@ def test_calls_that_need_fp32_shards_are_refused(jg, ctx):
     with JigsawLinear(16, 32, 16, 2, ctx=ctx, dtype=jg.JG_BF16) as L:
         ptrs = [t.data_ptr() for t in L.y]
         for call in (lambda: jg.jg_linear_backward(L.plan, ptrs, ptrs, ptrs, ptrs, ptrs, None, 0),
-                     lambda: jg.jg_layernorm_forward(L.plan, ptrs, None, None, 1e-5, ptrs),
                      lambda: jg.jg_gather_as(L.plan, jg.JG_T_X, ptrs, ptrs[0], 64),
+                     lambda: jg.jg_gather_as(L.plan, jg.JG_T_W, ptrs, ptrs[0], 64),
                      lambda: jg.jg_shard_patches(L.plan, ptrs[0], 2, 8, 8, 4, ptrs)):
             with pytest.raises(jg.JigsawError) as e:
                 call()
@@ -244,6 +244,105 @@ def test_calls_that_need_fp32_shards_are_refused(jg, ctx):
         with pytest.raises(jg.JigsawError) as e:          # bfloat16 shards move in 16-byte pieces
             jg.jg_shard(L.plan, jg.JG_T_X, L.y[0].data_ptr(), 32, [ptrs[0] + 4, ptrs[1]])
         assert e.value.status == jg.JG_E_ALIGN
+
+
+# --------------------------------------------------------------------------------------------
+# the mixing MLP and the channel-mixing block in mixed precision (FP32 activations, bfloat16 products)
+# --------------------------------------------------------------------------------------------
+TOL_H = 1.5e-6 + 2.0 ** -23      # the pre-activation's 1e-6 through GELU (slope <= 1.13), and H's own FP32 rounding
+
+
+def mlp_operands(seed, M, C, Hd):
+    X = (inputs.matrix(seed, M, C, "R") + np.float32(0.25)).astype(np.float32)
+    W1 = inputs.matrix(seed + 1, Hd, C, "R", inputs.W_SCALE_EXP)
+    b1 = inputs.matrix(seed + 2, 1, Hd, "R")[0]
+    W2 = inputs.matrix(seed + 3, C, Hd, "R", inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(seed + 4, 1, C, "R")[0]
+    return X, W1, b1, W2, b2
+
+
+def check_mixed_chain(X, Xin, H, Y, W1, b1, W2, b2, t):
+    """Xin: what the first product read (X, or the layer norm's FP32 output as the GPU stored it)."""
+    S1 = oracle.linear_reduced(Xin, W1, b1, t, absolute=True)
+    eh = np.abs(H.astype(np.float64) - oracle.gelu(oracle.linear_reduced(Xin, W1, b1, t)))
+    assert np.all(eh <= TOL_H * S1), f"H: max err/S1 = {(eh / S1).max():.3e}"
+    # the second layer on its own, from the H the GPU stored (both sides round the same FP32 values to bfloat16);
+    # the skip connection adds X itself, not its rounding
+    want = X.astype(np.float64) + oracle.linear_reduced(H, W2, b2, t)
+    SY = np.abs(X.astype(np.float64)) + oracle.linear_reduced(H, W2, b2, t, absolute=True)
+    ey = np.abs(Y.astype(np.float64) - want)
+    assert np.all(ey <= TOL * SY), f"Y: max err/S = {(ey / SY).max():.3e}"
+    return want
+
+
+# C and Hd: every rank's share in whole 8-element chunks; ragged tiles and slabs
+MLP_SHAPES = [(100, 96, 112), (130, 80, 272), (258, 272, 144), (300, 528, 1040)]
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+@pytest.mark.parametrize("M,C,Hd", MLP_SHAPES)
+def test_mixed_precision_mlp(jg, ctx, ways, dtype_name, M, C, Hd):
+    from paper_2507_05753_amd.layer import JigsawMLP
+    dtype = getattr(jg, dtype_name)
+    t = terms_of(jg, dtype)
+    X, W1, b1, W2, b2 = mlp_operands(430, M, C, Hd)
+    with JigsawMLP(M, C, Hd, ways, ctx=ctx, dtype=dtype) as L:
+        L.ws.fill_(0xFF)
+        L.shard(dev(X), dev(W1), dev(b1), dev(W2), dev(b2))
+        L.forward()
+        H, Y = L.gather_h().cpu().numpy(), L.gather().cpu().numpy()
+        L.forward()                                   # the inputs were not overwritten: the same again
+        assert np.array_equal(Y, L.gather().cpu().numpy())
+    check_mixed_chain(X, X, H, Y, W1, b1, W2, b2, t)
+    # end to end against the oracle's own chain: apart from the few entries of H whose bfloat16 rounding
+    # falls the other way for an error in the last FP32 bits, the two agree far inside one bfloat16 step
+    r = oracle.mlp_reduced(X, W1, b1, W2, b2, t)
+    assert np.all(np.abs(Y - r["Y"]) <= 2.0 ** -9 * r["SY"])
+    assert np.abs(Y - oracle.mlp(X, W1, b1, W2, b2)["Y"]).max() > (1e-4 if t == 1 else 1e-8)   # it IS reduced precision
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+def test_mixed_precision_mixing_block(jg, ctx, ways, dtype_name):
+    from paper_2507_05753_amd.layer import JigsawMixing
+    dtype = getattr(jg, dtype_name)
+    t = terms_of(jg, dtype)
+    M, C, Hd = 258, 272, 400
+    X, W1, b1, W2, b2 = mlp_operands(440, M, C, Hd)
+    gamma = (inputs.matrix(445, 1, C, "R")[0] + np.float32(1.5)).astype(np.float32)
+    beta = inputs.matrix(446, 1, C, "R")[0]
+    with JigsawMixing(M, C, Hd, ways, ctx=ctx, dtype=dtype) as L:
+        L.shard(dev(X), dev(gamma), dev(beta), dev(W1), dev(b1), dev(W2), dev(b2))
+        L.forward()
+        Xn, H, Y = L.gather_xn().cpu().numpy(), L.gather_h().cpu().numpy(), L.gather().cpu().numpy()
+    want = oracle.layernorm(X, gamma, beta, oracle.ln_groups(ways))
+    assert np.all(np.abs(Xn.astype(np.float64) - want) <= 2.0 ** -24 * np.abs(want) * (1 + 1e-6) + 1e-10)
+    check_mixed_chain(X, Xn, H, Y, W1, b1, W2, b2, t)
+    r = oracle.mixing_block_reduced(ways, X, gamma, beta, W1, b1, W2, b2, t)
+    assert np.all(np.abs(Y - r["Y"]) <= 2.0 ** -9 * r["SY"])
+
+
+def test_mixed_precision_chain_arguments(jg, ctx):
+    from paper_2507_05753_amd.layer import JigsawLinear, JigsawMLP
+    with JigsawMLP(64, 32, 48, 2, ctx=ctx, dtype=jg.JG_BF16) as L, \
+            JigsawLinear(64, 48, 32, 2, bias=True, ctx=ctx) as F32, \
+            JigsawLinear(64, 48, 32, 2, bias=True, ctx=ctx, dtype=jg.JG_BF16X3) as X3:
+        f, s = L.first, L.second
+        p = lambda ts: [x.data_ptr() for x in ts]
+        need = max(f.query(jg.JG_Q_CHAIN_WORKSPACE_BYTES), s.query(jg.JG_Q_CHAIN_WORKSPACE_BYTES))
+        assert need == L.ws_bytes and need > max(f.query(jg.JG_Q_WORKSPACE_BYTES), s.query(jg.JG_Q_WORKSPACE_BYTES))
+        args = lambda second, ws_bytes: (f.plan, second.plan, p(L.xin), p(f.w), p(f.b), p(second.w), p(second.b),
+                                         p(f.y), p(s.y), L.ws.data_ptr(), ws_bytes)
+        for other in (F32, X3):                           # both layers in the same precision
+            with pytest.raises(jg.JigsawError) as e:
+                jg.jg_mlp_forward(*args(other, L.ws_bytes))
+            assert e.value.status == jg.JG_E_DTYPE
+        with pytest.raises(jg.JigsawError) as e:          # the layers' own workspace alone is not enough
+            jg.jg_mlp_forward(*args(s, need - 256))
+        assert e.value.status == jg.JG_E_WORKSPACE
+        # an FP32 plan's chain workspace is its workspace
+        assert F32.query(jg.JG_Q_CHAIN_WORKSPACE_BYTES) == F32.query(jg.JG_Q_WORKSPACE_BYTES)
 
 
 # --------------------------------------------------------------------------------------------
