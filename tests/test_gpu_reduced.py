@@ -345,6 +345,37 @@ def test_mixed_precision_chain_arguments(jg, ctx):
         assert F32.query(jg.JG_Q_CHAIN_WORKSPACE_BYTES) == F32.query(jg.JG_Q_WORKSPACE_BYTES)
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+def test_mixed_precision_mlp_at_channel_mixing_size(jg, dtype_name):
+    """The channel-mixing MLP of the paper's 1-billion-parameter model (Sec. 6.2.1) at full size, in the launch
+    configuration bench.py --op mlp --dtype times: sampled rows element by element, every entry finite."""
+    from paper_2507_05753_amd.layer import JigsawMLP
+    dtype = getattr(jg, dtype_name)
+    t = terms_of(jg, dtype)
+    cfg = inputs.MLP_CONFIGS["channel_mixing_1b"]
+    M, C, Hd, seed = cfg["M"], cfg["C"], cfg["Hd"], cfg["seed"]
+    Xd = inputs.matrix_torch(seed, M, C, "R", device="cuda")
+    W1d = inputs.matrix_torch(seed + 1, Hd, C, "R", inputs.W_SCALE_EXP, device="cuda")
+    W2d = inputs.matrix_torch(seed + 3, C, Hd, "R", inputs.W_SCALE_EXP, device="cuda")
+    b1 = inputs.matrix(seed + 2, 1, Hd, "R")[0]
+    b2 = inputs.matrix(seed + 4, 1, C, "R")[0]
+    W1, W2 = W1d.cpu().numpy(), W2d.cpu().numpy()
+    k = inputs.keys(7100, np.arange(20, dtype=np.uint64))
+    rows = np.unique(np.concatenate([(k % np.uint64(M)).astype(np.int64), [0, M // 2 - 1, M // 2, M - 1]]))
+    idx = torch.from_numpy(rows).cuda()
+    Xs = Xd[idx].cpu().numpy()
+    for ways in (1, 4):
+        with JigsawMLP(M, C, Hd, ways, dtype=dtype) as L:
+            L.shard(Xd, W1d, dev(b1), W2d, dev(b2))
+            L.forward()
+            H, Y = L.gather_h(), L.gather()
+            torch.cuda.synchronize()
+            assert torch.isfinite(Y).all() and torch.isfinite(H).all()
+            Hs, Ys = H[idx].cpu().numpy(), Y[idx].cpu().numpy()
+        check_mixed_chain(Xs, Xs, Hs, Ys, W1, b1, W2, b2, t)
+
+
 # --------------------------------------------------------------------------------------------
 # full size: config 3 (n = 1e8 items)
 # --------------------------------------------------------------------------------------------
