@@ -230,6 +230,49 @@ def test_same_sign_operands(jg, ctx, K):
         assert np.all(err <= bar * S), f"dtype={dtype}: {(err / S).max():.3e}"
 
 
+def random_cases(n):
+    """Seeded shapes and options: every rank's share of K in whole 8-element chunks, sizes from one element to a
+    few tiles, K from one chunk to dozens of slabs, small enough for the oracle's full product."""
+    k = inputs.keys(5150, np.arange(8 * n, dtype=np.uint64)).reshape(n, 8)
+    cases = []
+    for row in k:
+        ways = (1, 2, 4)[int(row[0] % np.uint64(3))]
+        half = 2 if ways >= 2 else 1
+        share = 8 * (1 + int(row[1] % np.uint64(160)))              # 8 .. 1280 per rank
+        K = share * half
+        M = 1 + int(row[2] % np.uint64(600))
+        N = 1 + int(row[3] % np.uint64(600))
+        if ways == 4:
+            M += M & 1
+        if ways >= 2:
+            N += N & 1
+        while M * N * K > 1.5e8:
+            M = max(2, M // 2 + (M // 2 & 1))
+        cases.append((ways, M, K, N, int(row[4] & np.uint64(1)), int(row[5] & np.uint64(1)), int(row[6] & np.uint64(1)),
+                      int(row[7] & np.uint64(1))))
+    return cases
+
+
+@pytest.mark.parametrize("ways,M,K,N,x3,bias,act,res", random_cases(36))
+def test_random_shapes_and_options(jg, ctx, ways, M, K, N, x3, bias, act, res):
+    dtype = jg.JG_BF16X3 if x3 else jg.JG_BF16
+    t = 3 if x3 else 1
+    X, W, b = inputs.layer_inputs(5200 + M, M, K, N, "R", bias=True)
+    b = b if bias else None
+    R = inputs.matrix(5300 + N, M, N, "R") if res else None
+    Y, _, _ = run_layer(jg, ctx, X, W, b, ways, dtype, residual=R, act=jg.JG_ACT_GELU if act else jg.JG_ACT_NONE)
+    want = oracle.linear_reduced(X, W, b, t)
+    S = oracle.linear_reduced(X, W, b, t, absolute=True)
+    if act:
+        want = oracle.gelu(want)
+    if res:
+        want = want + R
+        S = S + np.abs(R)
+    err = np.abs(Y.astype(np.float64) - want)
+    bar = (1.5e-6 if act else TOL) * S
+    assert np.all(err <= bar), f"max err/S = {(err / S).max():.3e}"
+
+
 def test_calls_that_need_fp32_shards_are_refused(jg, ctx):
     from paper_2507_05753_amd.layer import JigsawLinear
     with JigsawLinear(16, 32, 16, 2, ctx=ctx, dtype=jg.JG_BF16) as L:
