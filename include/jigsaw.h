@@ -147,7 +147,7 @@ typedef enum jg_query {
     JG_Q_BACKWARD_TAIL_SCRATCH_BYTES = 18, /* the same for JG_Q_BACKWARD_WORKSPACE_BYTES          */
     JG_Q_X_SHARD_BYTES = 19,            /* bytes of the rank's X shard in the plan's dtype        */
     JG_Q_W_SHARD_BYTES = 20,            /* ... and of its W shard                                 */
-    JG_Q_CHAIN_WORKSPACE_BYTES = 21     /* workspace the plan needs as a layer of jg_mlp_forward /
+    JG_Q_CHAIN_WORKSPACE_BYTES = 21     /* the plan's share of the workspace of jg_mlp_forward /
                                            jg_mixing_forward: JG_Q_WORKSPACE_BYTES, plus (reduced
                                            precision) room for its input in bfloat16 (rank ignored) */
 } jg_query;
@@ -278,15 +278,17 @@ int jg_linear_forward_ex(const jg_plan* plan, const float* const* x_sh, const fl
  * N = Hd), `second` one of (M, K = Hd, N = C), same `ways`, same context.  Because a layer leaves
  * its output partitioned like its input (Sec. 4.1), H_r is consumed where it was produced: no
  * re-sharding between the layers.  h_sh: `ways` device buffers shaped like the first plan's Y_r
- * (H is kept: a backward pass would need it).  The workspace is used by both layers in turn and
- * must satisfy both plans' JG_Q_CHAIN_WORKSPACE_BYTES.  x_sh is read by both layers and must not
- * overlap h_sh or y_sh.
+ * (H is kept: a backward pass would need it).  Workspace: FP32 plans use it in turn, it must hold
+ * the larger of the two plans' JG_Q_WORKSPACE_BYTES; reduced-precision plans need the SUM of the two
+ * plans' JG_Q_CHAIN_WORKSPACE_BYTES (the rounded H is written while the first layer still works in
+ * its own part).  x_sh is read by both layers and must not overlap h_sh or y_sh.
  * Mixed precision (Sec. 6.1: the matrix units round their FP32 operands, everything else stays FP32):
  * both plans JG_BF16, or both JG_BF16X3.  x_sh, h_sh and y_sh are then still FP32 shards (x_sh as
  * jg_shard(JG_T_X_F32) writes them), w1_sh / w2_sh the plans' bfloat16 weight shards.  Each layer
- * rounds its input activations into the workspace as jg_shard rounds X (H is rounded from the FP32
- * values stored in h_sh), runs its products on the bfloat16 matrix cores and adds bias, GELU and
- * the skip connection (from the unrounded x_sh) in FP32.
+ * reads its input activations rounded as jg_shard rounds X, from a copy in the workspace (H's copy
+ * holds the roundings of exactly the FP32 values stored in h_sh; with the fused combine the launch
+ * that writes H writes it too), runs its products on the bfloat16 matrix cores and adds bias, GELU
+ * and the skip connection (from the unrounded x_sh) in FP32.
  * Errors: JG_E_NULL, JG_E_DTYPE (op, or the two plans' dtypes differ), JG_E_WAYS, JG_E_SHAPE (plans do
  * not chain), and those of jg_linear_forward_ex. */
 int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh,

@@ -26,7 +26,8 @@
 //               ask L2 for the lines of the slab after, so that first touches of HBM are not waited
 //               for with a whole slab of LDS standing empty
 //   epilogue  : each 32 x 128 block of a wave's accumulators goes through the wave's piece of LDS
-//               (free by then) and leaves as 16-byte stores
+//               (free by then) and leaves as 16-byte stores;
+//               optionally a second copy rounded to bfloat16 for a layer that follows
 //   tail      : the tiles of a last partial round of workgroups can be cut into runs of slabs
 //               (gemm_bf16_join adds them in k order); see make_bf16_group
 // LDS layout: see HbLoader.
@@ -38,6 +39,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
+#include "cvt_kernels.hpp"
 #include "gemm_f32.hpp"
 #include "stream_kernels.hpp"
 
@@ -70,6 +75,16 @@ struct HbGroup {
     int parts;
     float* scratch;             // 256 x 256 floats per run
     int act;
+    // Optional second copy of every finished element of C, rounded to bfloat16 as the shard step rounds (hi plane,
+    // and lo plane behind it when planes16 = 2): the next layer of an MLP chain reads it as its X shard.
+    uint16_t* c16[kMaxGroup];   // per problem, or all null
+    int ld16;                   // bfloat16 elements per row of that copy (all planes)
+    int plane16, planes16;      // elements from the hi plane of a row to its lo plane; 1 or 2 planes
+};
+
+struct HbCopy16 {               // what a caller of launch_gemm_bf16_group passes for that copy
+    uint16_t* dst[kMaxGroup];
+    int ld, plane, planes;
 };
 constexpr int HB_TILE_FLOATS = HB_BM * HB_BN;
 
@@ -164,6 +179,21 @@ struct HbLoader {
     }
 };
 
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>): a loop whose index is a compile-time
+// constant in every copy of the body.  The epilogue's loops over accumulator blocks are written with it: as
+// `#pragma unroll` loops they stay rolled once their body outgrows the compiler's unrolling budget, and an
+// accumulator array indexed at run time lives in scratch memory - through the whole K loop.
+template <int... I, typename F>
+__device__ __forceinline__ void hb_static_for_impl(std::integer_sequence<int, I...>, F&& f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void hb_static_for(F&& f)
+{
+    hb_static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
+}
+
 constexpr int HB_SHUFFLE_LD = 136;     // floats per row of a wave's 32 x 128 staging block: 128 + 8 keeps the two
                                        // half-waves of a write (rows r and r + 4) on different banks
 
@@ -175,8 +205,10 @@ constexpr int HB_SHUFFLE_LD = 136;     // floats per row of a wave's 32 x 128 st
 // Interior tiles therefore pass each 32 x 128 block through the wave's own piece of LDS (free by now) and
 // leave as 16 bytes per lane, two 512-byte row pieces per instruction; addend and residual arrive the same way.
 // wm, wn: the wave's quadrant; lr, lk: lane coordinates; shuffle: 32 x HB_SHUFFLE_LD floats of LDS owned by the wave.
+// c16 (may be null): the bfloat16 copy of the finished elements, ld16 elements per row, lo plane at + lo16 (0: none).
 __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N, int m0, int n0, int wm, int wn, int lr,
-                                              int lk, bool interior, const floatx16 (&acc)[4][4], int act, float* shuffle)
+                                              int lk, bool interior, const floatx16 (&acc)[4][4], int act, float* shuffle,
+                                              uint16_t* __restrict__ c16 = nullptr, int ld16 = 0, int lo16 = 0)
 {
     const float* __restrict__ bias = P.bias;
     const float* __restrict__ residual = P.residual;
@@ -184,7 +216,8 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
     float* __restrict__ C = P.C;
     const int ldc = P.ldc, ldres = P.ldres, ldadd = P.ldadd;
     const bool vec_ok = (((uintptr_t)C | (uintptr_t)addend | (uintptr_t)residual | (uintptr_t)bias) & 15) == 0 &&
-                        ((ldc | (addend ? ldadd : 0) | (residual ? ldres : 0)) & 3) == 0;
+                        ((ldc | (addend ? ldadd : 0) | (residual ? ldres : 0)) & 3) == 0 &&
+                        (!c16 || ((((uintptr_t)c16) & 7) == 0 && ((ld16 | lo16) & 3) == 0));
     // edge tiles take the same way when N is a multiple of 4 (a lane's four columns are then all inside or all
     // outside), with each row and column group checked
     if (vec_ok && (interior || (N & 3) == 0)) {
@@ -209,8 +242,8 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
             }
         };
         if (addend) request_addend(0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        hb_static_for<4>([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value;
 #pragma unroll
             for (int jb = 0; jb < 4; ++jb)
 #pragma unroll
@@ -248,17 +281,26 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
                     if (act) o = vf4{activate(o.x, act), activate(o.y, act), activate(o.z, act), activate(o.w, act)};
                     if (residual) o += res[q];
                     if (in[q]) *reinterpret_cast<vf4*>(C + row * ldc + col) = o;
+                    if (c16 && in[q]) {
+                        typedef uint32_t vu2 __attribute__((ext_vector_type(2)));
+                        const uint32_t h0 = bf16_bits(o.x), h1 = bf16_bits(o.y), h2 = bf16_bits(o.z), h3 = bf16_bits(o.w);
+                        uint16_t* at = c16 + row * ld16 + col;
+                        *reinterpret_cast<vu2*>(at) = vu2{h0 | (h1 << 16), h2 | (h3 << 16)};
+                        if (lo16) {
+                            const uint32_t l0 = bf16_bits(o.x - bf16_value(h0)), l1 = bf16_bits(o.y - bf16_value(h1));
+                            const uint32_t l2 = bf16_bits(o.z - bf16_value(h2)), l3 = bf16_bits(o.w - bf16_value(h3));
+                            *reinterpret_cast<vu2*>(at + lo16) = vu2{l0 | (l1 << 16), l2 | (l3 << 16)};
+                        }
+                    }
                 }
             }
-        }
+        });
     } else {
         const int row_base = m0 + wm * 128 + 4 * lk, col_base = n0 + wn * 128 + lr;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
+        hb_static_for<16>([&](auto ic) __attribute__((always_inline)) {
+                constexpr int i = decltype(ic)::value / 4, j = decltype(ic)::value % 4;
                 const int col = col_base + j * 32;
-                if (col >= N) continue;
+                if (col >= N) return;
                 const float bj = bias ? bias[col] : 0.f;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
@@ -269,9 +311,14 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
                         y = activate(y + bj, act);
                         if (residual) y += residual[(int64_t)row * ldres + col];
                         C[(int64_t)row * ldc + col] = y;
+                        if (c16) {
+                            const uint32_t h = bf16_bits(y);
+                            c16[(int64_t)row * ld16 + col] = (uint16_t)h;
+                            if (lo16) c16[(int64_t)row * ld16 + col + lo16] = (uint16_t)bf16_bits(y - bf16_value(h));
+                        }
                     }
                 }
-            }
+        });
     }
 }
 
@@ -457,7 +504,8 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
     float* shuffle = reinterpret_cast<float*>(slab + wave * (32 * HB_SHUFFLE_LD * 4));
     if ((PARTS & 8) && acc[0][0][0] != 12345.f) return;
     if (run < 0) {
-        hb_store_tile(P, M, N, tc.m0, tc.n0, wm, wn, lr, lk, interior, acc, g.act, shuffle);
+        hb_store_tile(P, M, N, tc.m0, tc.n0, wm, wn, lr, lk, interior, acc, g.act, shuffle, g.c16[tc.prob], g.ld16,
+                      g.planes16 == 2 ? g.plane16 : 0);
     } else {                // a run of a split tile: raw sums into its scratch tile
         GemmProblem raw = {};
         raw.C = g.scratch + (int64_t)run * HB_TILE_FLOATS;
@@ -637,7 +685,8 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
     float* shuffle = reinterpret_cast<float*>(slab + wave * (32 * HB_SHUFFLE_LD * 4));
     if ((PARTS & 8) && acc[0][0][0] != 12345.f) return;
     if (run < 0) {
-        hb_store_tile(P, M, N, tc.m0, tc.n0, wm, wn, lr, lk, interior, acc, g.act, shuffle);
+        hb_store_tile(P, M, N, tc.m0, tc.n0, wm, wn, lr, lk, interior, acc, g.act, shuffle, g.c16[tc.prob], g.ld16,
+                      g.planes16 == 2 ? g.plane16 : 0);
     } else {
         GemmProblem raw = {};
         raw.C = g.scratch + (int64_t)run * HB_TILE_FLOATS;
@@ -657,8 +706,11 @@ __global__ __launch_bounds__(HB_THREADS) void gemm_bf16_join(const HbGroup g)
     const GemmProblem& P = g.p[tc.prob];
     const float* runs = g.scratch + (int64_t)t * g.parts * HB_TILE_FLOATS;
     const bool interior = tc.m0 + HB_BM <= g.M && tc.n0 + HB_BN <= g.N;
+    uint16_t* __restrict__ c16 = g.c16[tc.prob];
+    const int lo16 = g.planes16 == 2 ? g.plane16 : 0;
     const bool vec_ok = (((uintptr_t)P.C | (uintptr_t)P.addend | (uintptr_t)P.residual | (uintptr_t)P.bias) & 15) == 0 &&
-                        ((P.ldc | (P.addend ? P.ldadd : 0) | (P.residual ? P.ldres : 0)) & 3) == 0;
+                        ((P.ldc | (P.addend ? P.ldadd : 0) | (P.residual ? P.ldres : 0)) & 3) == 0 &&
+                        (!c16 || ((((uintptr_t)c16) & 7) == 0 && ((g.ld16 | lo16) & 3) == 0));
     if (interior && vec_ok) {
         for (int u = slice * (kSliceFloats / 4) + threadIdx.x; u < (slice + 1) * (kSliceFloats / 4); u += HB_THREADS) {
             const int r = u / (HB_BN / 4), c = (u - r * (HB_BN / 4)) * 4;
@@ -672,6 +724,17 @@ __global__ __launch_bounds__(HB_THREADS) void gemm_bf16_join(const HbGroup g)
             if (g.act) y = vf4{activate(y.x, g.act), activate(y.y, g.act), activate(y.z, g.act), activate(y.w, g.act)};
             if (P.residual) y += *reinterpret_cast<const vf4*>(P.residual + row * P.ldres + col);
             *reinterpret_cast<vf4*>(P.C + row * P.ldc + col) = y;
+            if (c16) {
+                typedef uint32_t vu2 __attribute__((ext_vector_type(2)));
+                const uint32_t h0 = bf16_bits(y.x), h1 = bf16_bits(y.y), h2 = bf16_bits(y.z), h3 = bf16_bits(y.w);
+                uint16_t* at = c16 + row * g.ld16 + col;
+                *reinterpret_cast<vu2*>(at) = vu2{h0 | (h1 << 16), h2 | (h3 << 16)};
+                if (lo16) {
+                    const uint32_t l0 = bf16_bits(y.x - bf16_value(h0)), l1 = bf16_bits(y.y - bf16_value(h1));
+                    const uint32_t l2 = bf16_bits(y.z - bf16_value(h2)), l3 = bf16_bits(y.w - bf16_value(h3));
+                    *reinterpret_cast<vu2*>(at + lo16) = vu2{l0 | (l1 << 16), l2 | (l3 << 16)};
+                }
+            }
         }
     } else {
         for (int u = slice * kSliceFloats + threadIdx.x; u < (slice + 1) * kSliceFloats; u += HB_THREADS) {
@@ -685,6 +748,11 @@ __global__ __launch_bounds__(HB_THREADS) void gemm_bf16_join(const HbGroup g)
             y = activate(y + (P.bias ? P.bias[col] : 0.f), g.act);
             if (P.residual) y += P.residual[row * P.ldres + col];
             P.C[row * P.ldc + col] = y;
+            if (c16) {
+                const uint32_t h = bf16_bits(y);
+                c16[row * g.ld16 + col] = (uint16_t)h;
+                if (lo16) c16[row * g.ld16 + col + lo16] = (uint16_t)bf16_bits(y - bf16_value(h));
+            }
         }
     }
 }
@@ -706,9 +774,13 @@ inline size_t bf16_tail_scratch_bytes(int cus) { return (size_t)cus * HB_TILE_FL
 
 // plane: with split operands, the distance in elements from a row's hi plane to its lo plane (>= K, a multiple of 8)
 inline hipError_t make_bf16_group(const GemmGroup& src, int terms, int plane, int cus, float* scratch, size_t scratch_bytes,
-                                  HbGroup& g)
+                                  HbGroup& g, const HbCopy16* copy16 = nullptr)
 {
     for (int i = 0; i < kMaxGroup; ++i) g.p[i] = src.p[i];
+    for (int i = 0; i < kMaxGroup; ++i) g.c16[i] = copy16 ? copy16->dst[i] : nullptr;
+    g.ld16 = copy16 ? copy16->ld : 0;
+    g.plane16 = copy16 ? copy16->plane : 0;
+    g.planes16 = copy16 ? copy16->planes : 1;
     g.nprob = src.nprob;
     g.M = src.M;
     g.N = src.N;
@@ -749,11 +821,13 @@ inline hipError_t make_bf16_group(const GemmGroup& src, int terms, int plane, in
 inline unsigned bf16_grid(const HbGroup& g) { return (unsigned)(kNumXcd * g.per_xcd + (g.total - g.whole) * g.parts); }
 
 // cus: compute units of the device (one workgroup each).  *needs_join: launch_gemm_bf16_join must follow.
+// copy16 (may be null): see HbGroup::c16.
 inline hipError_t launch_gemm_bf16_group(const GemmGroup& src, int terms, int plane, int cus, float* scratch,
-                                         size_t scratch_bytes, hipStream_t stream, HbGroup& g, bool* needs_join)
+                                         size_t scratch_bytes, hipStream_t stream, HbGroup& g, bool* needs_join,
+                                         const HbCopy16* copy16 = nullptr)
 {
     *needs_join = false;
-    const hipError_t e = make_bf16_group(src, terms, plane, cus, scratch, scratch_bytes, g);
+    const hipError_t e = make_bf16_group(src, terms, plane, cus, scratch, scratch_bytes, g, copy16);
     if (e != hipSuccess) return e;
     if (terms == 3) hipLaunchKernelGGL(gemm_bf16x3_nt<3>, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);
     else hipLaunchKernelGGL(gemm_bf16_nt<3>, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);

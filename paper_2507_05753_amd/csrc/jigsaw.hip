@@ -585,8 +585,9 @@ int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, in
 
 // One GEMM launch of a pass (timed as `kernel_class`), followed by the join kernel when the
 // launcher split the tail; `scratch` is the pass's tail region of the caller's workspace.
+// copy16 (reduced precision only, may be null): a bfloat16 copy of the launch's output for the next layer.
 static bool run_gemm(const jg_plan* plan, jg::GemmGroup& g, int layout, int kernel_class, char* scratch,
-                     size_t scratch_bytes)
+                     size_t scratch_bytes, const jg::HbCopy16* copy16 = nullptr)
 {
     jg_ctx* c = plan->ctx;
     bool join = false;
@@ -595,7 +596,8 @@ static bool run_gemm(const jg_plan* plan, jg::GemmGroup& g, int layout, int kern
         {
             ScopedTimer t(c, kernel_class);
             if (!HIP_OK(jg::launch_gemm_bf16_group(g, plan->d.dtype == JG_BF16X3 ? 3 : 1, (int)plan->plane, plan->slots / 2,
-                                                   reinterpret_cast<float*>(scratch), scratch_bytes, c->stream, hb, &join)))
+                                                   reinterpret_cast<float*>(scratch), scratch_bytes, c->stream, hb, &join,
+                                                   copy16)))
                 return false;
         }
         if (join) {
@@ -723,9 +725,11 @@ int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float
     return jg_linear_forward_ex(plan, x_sh, w_sh, b_sh, nullptr, JG_ACT_NONE, y_sh, workspace, workspace_bytes);
 }
 
-int jg_linear_forward_ex(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
-                         const float* const* b_sh, const float* const* r_sh, int activation, float* const* y_sh,
-                         void* workspace, size_t workspace_bytes)
+// jg_linear_forward_ex.  copy16 (reduced-precision plans with the fused combine only, may be null): the launch
+// that writes Y also writes it in bfloat16, in the X-shard format of the layer that follows.
+static int forward_impl(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                        const float* const* b_sh, const float* const* r_sh, int activation, float* const* y_sh,
+                        void* workspace, size_t workspace_bytes, const jg::HbCopy16* copy16)
 {
     if (!plan || !plan->ctx) return JG_E_NULL;
     const jg_linear_desc& d = plan->d;
@@ -766,7 +770,7 @@ int jg_linear_forward_ex(const jg_plan* plan, const float* const* x_sh, const fl
         g.nprob = 1;
         g.act = act;
         g.p[0] = {x_sh[0], w_sh[0], y_sh[0], nullptr, bias_of(0), ldk, ldk, ldn, 0, res_of(0), ldn};
-        return run_gemm(plan, g, jg::kGemmNT, JG_KERNEL_GEMM, tail, plan->tail_bytes) ? JG_OK : JG_E_HIP;
+        return run_gemm(plan, g, jg::kGemmNT, JG_KERNEL_GEMM, tail, plan->tail_bytes, copy16) ? JG_OK : JG_E_HIP;
     }
 
     auto send_buf = [&](int r) { return reinterpret_cast<float*>(ws + plan->off_send + r * plan->part_bytes); };
@@ -823,7 +827,7 @@ int jg_linear_forward_ex(const jg_plan* plan, const float* const* x_sh, const fl
         for (int r = 0; r < ways; ++r)
             g.p[r] = {x_sh[r], w_keep[r], y_sh[r], send_buf(recv_from[r]), bias_of(r), ldk, ldk, ldn, ldn,
                       res_of(r), ldn};
-        return run_gemm(plan, g, jg::kGemmNT, JG_KERNEL_GEMM, tail, plan->tail_bytes) ? JG_OK : JG_E_HIP;
+        return run_gemm(plan, g, jg::kGemmNT, JG_KERNEL_GEMM, tail, plan->tail_bytes, copy16) ? JG_OK : JG_E_HIP;
     }
     for (int r = 0; r < ways; ++r)
         g.p[r] = {x_sh[r], w_keep[r], kept_buf(r), nullptr, nullptr, ldk, ldk, ldn, 0};
@@ -838,6 +842,13 @@ int jg_linear_forward_ex(const jg_plan* plan, const float* const* x_sh, const fl
         cb.b[r] = {kept_buf(r), send_buf(recv_from[r]), bias_of(r), y_sh[r], res_of(r)};
     ScopedTimer t(c, JG_KERNEL_COMBINE);
     return HIP_OK(jg::launch_combine_group(cb, c->stream)) ? JG_OK : JG_E_HIP;
+}
+
+int jg_linear_forward_ex(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                         const float* const* b_sh, const float* const* r_sh, int activation, float* const* y_sh,
+                         void* workspace, size_t workspace_bytes)
+{
+    return forward_impl(plan, x_sh, w_sh, b_sh, r_sh, activation, y_sh, workspace, workspace_bytes, nullptr);
 }
 
 int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
@@ -977,23 +988,22 @@ static int check_mlp_chain(const jg_plan* first, const jg_plan* second)
     return JG_OK;
 }
 
-// One layer of an MLP chain.  in_sh: the layer's input activations as FP32 shards (xr x xc, dense).  A
-// reduced-precision plan first writes them in the format its matrix products read (the conversion jg_shard
-// applies to X), into the chain region behind its own workspace.
-static int chain_layer(const jg_plan* plan, const float* const* in_sh, const float* const* w_sh,
-                       const float* const* b_sh, const float* const* r_sh, int activation, float* const* out_sh,
-                       void* workspace, size_t workspace_bytes)
+// The two layers of an MLP chain.  in_sh: the first layer's input activations as FP32 shards (xr x xc, dense).
+// FP32 plans: two calls of the layer, H handed on in place.  Reduced-precision plans: the first layer's input is
+// rounded into the workspace in the format its products read (the conversion jg_shard applies to X); the launch
+// that writes H also writes it rounded, in the second layer's format (fused combine), or H is converted like the
+// input (separate combine).  Workspace: [0, ws1) layer 1, [ws1, ws1 + chain1) its rounded input, then from
+// max(ws1 + chain1, ws2) the rounded H; layer 2 works in [0, ws2).
+static size_t chain_h16_offset(const jg_plan* first, const jg_plan* second)
+{
+    const size_t a = first->ws_bytes + first->chain_bytes;
+    return a > second->ws_bytes ? a : second->ws_bytes;
+}
+
+static int convert_shards(const jg_plan* plan, const float* const* in_sh, char* dst, const float** conv)
 {
     const jg_linear_desc& d = plan->d;
-    if (d.dtype == JG_F32)
-        return jg_linear_forward_ex(plan, in_sh, w_sh, b_sh, r_sh, activation, out_sh, workspace, workspace_bytes);
-    if (int rc = check_ptr_array(in_sh, d.ways)) return rc;
-    if (!workspace || workspace_bytes < plan->ws_bytes + plan->chain_bytes) return JG_E_WORKSPACE;
-    if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
     jg_ctx* c = plan->ctx;
-    if (!c) return JG_E_NULL;
-    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
-    const float* conv[4] = {nullptr, nullptr, nullptr, nullptr};
     jg::CvtGroup cv;
     std::memset(&cv, 0, sizeof(cv));
     cv.nblocks = d.ways;
@@ -1003,15 +1013,53 @@ static int chain_layer(const jg_plan* plan, const float* const* in_sh, const flo
     cv.plane = (int)plan->plane;
     for (int r = 0; r < d.ways; ++r) {
         if (!aligned(in_sh[r], 4)) return JG_E_ALIGN;
-        char* dst = static_cast<char*>(workspace) + plan->ws_bytes + r * plan->chain_shard_bytes;
-        cv.b[r] = {in_sh[r], reinterpret_cast<uint16_t*>(dst), plan->xc};
-        conv[r] = reinterpret_cast<const float*>(dst);
+        cv.b[r] = {in_sh[r], reinterpret_cast<uint16_t*>(dst + r * plan->chain_shard_bytes), plan->xc};
+        conv[r] = reinterpret_cast<const float*>(dst + r * plan->chain_shard_bytes);
     }
-    {
-        ScopedTimer t(c, JG_KERNEL_SHARD);
-        if (!HIP_OK(jg::launch_cvt_group(cv, c->stream))) return JG_E_HIP;
+    ScopedTimer t(c, JG_KERNEL_SHARD);
+    return HIP_OK(jg::launch_cvt_group(cv, c->stream)) ? JG_OK : JG_E_HIP;
+}
+
+static int run_chain(const jg_plan* first, const jg_plan* second, const float* const* in_sh, const float* const* x_sh,
+                     const float* const* w1_sh, const float* const* b1_sh, const float* const* w2_sh,
+                     const float* const* b2_sh, float* const* h_sh, float* const* y_sh, void* workspace,
+                     size_t workspace_bytes)
+{
+    if (first->d.dtype == JG_F32) {
+        // H_r is written by the first layer in the partition the second one reads its input in
+        int rc = forward_impl(first, in_sh, w1_sh, b1_sh, nullptr, JG_ACT_GELU, h_sh, workspace, workspace_bytes, nullptr);
+        if (rc != JG_OK) return rc;
+        return forward_impl(second, h_sh, w2_sh, b2_sh, x_sh, JG_ACT_NONE, y_sh, workspace, workspace_bytes, nullptr);
     }
-    return jg_linear_forward_ex(plan, conv, w_sh, b_sh, r_sh, activation, out_sh, workspace, workspace_bytes);
+    const int ways = first->d.ways;
+    if (int rc = check_ptr_array(in_sh, ways)) return rc;
+    const size_t off_h16 = chain_h16_offset(first, second);
+    if (!workspace || workspace_bytes < off_h16 + second->chain_bytes) return JG_E_WORKSPACE;
+    if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
+    jg_ctx* c = first->ctx;
+    if (!c) return JG_E_NULL;
+    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    char* ws = static_cast<char*>(workspace);
+    const float* x16[4] = {nullptr, nullptr, nullptr, nullptr};
+    const float* h16[4] = {nullptr, nullptr, nullptr, nullptr};
+    if (int rc = convert_shards(first, in_sh, ws + first->ws_bytes, x16)) return rc;
+    const bool fused = first->d.combine == JG_COMBINE_FUSED;
+    jg::HbCopy16 copy;
+    std::memset(&copy, 0, sizeof(copy));
+    copy.planes = second->d.dtype == JG_BF16X3 ? 2 : 1;
+    copy.plane = (int)second->plane;
+    copy.ld = copy.plane * copy.planes;
+    for (int r = 0; r < ways; ++r) {
+        copy.dst[r] = reinterpret_cast<uint16_t*>(ws + off_h16 + r * second->chain_shard_bytes);
+        h16[r] = reinterpret_cast<const float*>(copy.dst[r]);
+    }
+    int rc = forward_impl(first, x16, w1_sh, b1_sh, nullptr, JG_ACT_GELU, h_sh, workspace, workspace_bytes,
+                          fused ? &copy : nullptr);
+    if (rc != JG_OK) return rc;
+    if (!fused) {
+        if (int rc2 = convert_shards(second, h_sh, ws + off_h16, h16)) return rc2;
+    }
+    return forward_impl(second, h16, w2_sh, b2_sh, x_sh, JG_ACT_NONE, y_sh, workspace, workspace_bytes, nullptr);
 }
 
 int jg_mixing_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* gamma,
@@ -1023,9 +1071,7 @@ int jg_mixing_forward(const jg_plan* first, const jg_plan* second, const float* 
     if (int rc = check_ptr_array(h_sh, first->d.ways)) return rc;
     int rc = jg_layernorm_forward(first, x_sh, gamma, beta, eps, xn_sh);
     if (rc != JG_OK) return rc;
-    rc = chain_layer(first, xn_sh, w1_sh, b1_sh, nullptr, JG_ACT_GELU, h_sh, workspace, workspace_bytes);
-    if (rc != JG_OK) return rc;
-    return chain_layer(second, h_sh, w2_sh, b2_sh, x_sh, JG_ACT_NONE, y_sh, workspace, workspace_bytes);
+    return run_chain(first, second, xn_sh, x_sh, w1_sh, b1_sh, w2_sh, b2_sh, h_sh, y_sh, workspace, workspace_bytes);
 }
 
 int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh,
@@ -1035,10 +1081,7 @@ int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* con
 {
     if (int rc = check_mlp_chain(first, second)) return rc;
     if (int rc = check_ptr_array(h_sh, first->d.ways)) return rc;
-    // H_r is written by the first layer in the partition the second one reads its input in
-    int rc = chain_layer(first, x_sh, w1_sh, b1_sh, nullptr, JG_ACT_GELU, h_sh, workspace, workspace_bytes);
-    if (rc != JG_OK) return rc;
-    return chain_layer(second, h_sh, w2_sh, b2_sh, x_sh, JG_ACT_NONE, y_sh, workspace, workspace_bytes);
+    return run_chain(first, second, x_sh, x_sh, w1_sh, b1_sh, w2_sh, b2_sh, h_sh, y_sh, workspace, workspace_bytes);
 }
 
 }  // extern "C"

@@ -188,7 +188,8 @@ class JigsawMLP:
         self.second.x = self.first.y        # H_r is consumed where it was produced
         self.M, self.C, self.Hd, self.ways = M, C, Hd, ways
         self.ctx = self.first.ctx
-        self.ws_bytes = max(self.first.query(jg.JG_Q_CHAIN_WORKSPACE_BYTES), self.second.query(jg.JG_Q_CHAIN_WORKSPACE_BYTES))
+        chain = [L.query(jg.JG_Q_CHAIN_WORKSPACE_BYTES) for L in (self.first, self.second)]
+        self.ws_bytes = max(chain) if dtype == jg.JG_F32 else sum(chain)
         self.ws = max((self.first.ws, self.second.ws), key=lambda t: t.numel())
         if self.ws.numel() < self.ws_bytes:
             self.first.ws = self.second.ws = None
