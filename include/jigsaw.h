@@ -199,6 +199,8 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out);
  *           matching Y_r's columns (4-way: replicated on the two ranks of a column).
  *   which = JG_T_Y: global is M x N, ld >= N (an incoming gradient dY): partitioned like Y,
  *           2-way: column halves of N; 4-way: block (r/2, r%2).
+ *   which = JG_T_X_F32: as JG_T_X, and stored in FP32 also for a reduced-precision plan (dense
+ *           xr x xc shards): the activations jg_mlp_forward / jg_mixing_forward / jg_layernorm_forward take.
  * For a JG_OP_XTW plan the global X is K x M (ld >= M), W is K x N (ld >= N) and Y is
  * M x N; all three are partitioned the same way (2-way: column halves; 4-way: block
  * (r/2, r%2)) and b as above.
@@ -351,10 +353,12 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
  * Errors: JG_E_NULL, JG_E_SHAPE, JG_E_ALIGN, JG_E_HIP. */
 int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, int64_t ld);
 
-/* query (data).  Inverse of jg_shard for a tensor partitioned like X (JG_T_X: e.g. dX), like W
- * (JG_T_W: e.g. dW) or like Y (JG_T_Y): writes the global matrix from the per-rank shards.
- * jg_gather(plan, ...) is jg_gather_as(plan, JG_T_Y, ...).  Bit-exact.
- * Errors: JG_E_NULL, JG_E_DTYPE (which), JG_E_SHAPE (ld), JG_E_ALIGN, JG_E_HIP. */
+/* query (data).  Inverse of jg_shard for a tensor partitioned like X (JG_T_X: e.g. dX; JG_T_X_F32: FP32
+ * shards of any plan, e.g. a layer norm's output), like W (JG_T_W: e.g. dW) or like Y (JG_T_Y): writes
+ * the global matrix from the per-rank shards.  jg_gather(plan, ...) is jg_gather_as(plan, JG_T_Y, ...).
+ * Bit-exact.  The bfloat16 X and W shards of a reduced-precision plan are not converted back.
+ * Errors: JG_E_NULL, JG_E_DTYPE (which; JG_T_X / JG_T_W of a reduced-precision plan), JG_E_SHAPE (ld),
+ * JG_E_ALIGN, JG_E_HIP. */
 int jg_gather_as(const jg_plan* plan, int which, const float* const* shards, float* global, int64_t ld);
 
 /* Per-kernel timing with HIP events on the context's stream.
