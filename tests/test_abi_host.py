@@ -324,8 +324,34 @@ def test_reduced_precision_plans_account_for_their_shards():
         if ways == 4:   # the received weight block is bfloat16 too
             assert (q(h, jg.JG_Q_WORKSPACE_BYTES) - q(h, jg.JG_Q_TAIL_SCRATCH_BYTES)
                     < q(f, jg.JG_Q_WORKSPACE_BYTES) - q(f, jg.JG_Q_TAIL_SCRATCH_BYTES))
+        # as a layer of an MLP chain a reduced-precision plan also holds its input, rounded: ways shards, 256-byte pieces
+        up = lambda n: (n + 255) // 256 * 256
+        assert q(f, jg.JG_Q_CHAIN_WORKSPACE_BYTES) == q(f, jg.JG_Q_WORKSPACE_BYTES)
+        for p in (h, s):
+            assert (q(p, jg.JG_Q_CHAIN_WORKSPACE_BYTES)
+                    == q(p, jg.JG_Q_WORKSPACE_BYTES) + ways * up(q(p, jg.JG_Q_X_SHARD_BYTES, 0)))
         for p in (f, h, s):
             jg.jg_plan_destroy(p)
+
+
+def test_chain_refuses_plans_of_different_precision():
+    lib = jg.raw()
+    arr = (ctypes.c_void_p * 2)(256, 512)
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    call = lambda a, b: lib.jg_mlp_forward(a, b, pp, pp, pp, pp, pp, pp, pp, 256, 1 << 30)
+    kinds = {d: (jg.jg_plan_create(None, 64, 32, 48, 2, True, dtype=d), jg.jg_plan_create(None, 64, 48, 32, 2, True, dtype=d))
+             for d in (jg.JG_F32, jg.JG_BF16, jg.JG_BF16X3)}
+    for d1, (a, _) in kinds.items():
+        for d2, (_, b) in kinds.items():
+            assert call(a, b) == (jg.JG_E_NULL if d1 == d2 else jg.JG_E_DTYPE)      # same precision: chains, but no context
+    for a, b in kinds.values():
+        jg.jg_plan_destroy(a)
+        jg.jg_plan_destroy(b)
+    # the FP32 selector is a valid tensor name for data calls (which then miss the context)
+    a = jg.jg_plan_create(None, 64, 32, 48, 2, True, dtype=jg.JG_BF16)
+    assert lib.jg_shard(a, jg.JG_T_X_F32, 256, 32, pp) == jg.JG_E_NULL
+    assert lib.jg_shard(a, 5, 256, 32, pp) == jg.JG_E_DTYPE
+    jg.jg_plan_destroy(a)
 
 
 def test_patch_calls_check_sizes_against_the_plan():
