@@ -947,9 +947,13 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
     return launch(jg::kGemmTN, JG_KERNEL_GEMM_DW) ? JG_OK : JG_E_HIP;
 }
 
-int jg_layernorm_forward(const jg_plan* plan, const float* const* x_sh, const float* gamma, const float* beta,
-                         double eps, float* const* out_sh)
+// jg_layernorm_forward.  copy16 (may be null): `ways` destinations for a bfloat16 copy of the output in the
+// plan's X-shard format; *copied tells whether the kernel wrote them (it does when the rows fit its
+// register-resident form; otherwise the caller converts the FP32 output).
+static int layernorm_impl(const jg_plan* plan, const float* const* x_sh, const float* gamma, const float* beta,
+                          double eps, float* const* out_sh, uint16_t* const* copy16, bool* copied)
 {
+    if (copied) *copied = false;
     if (!plan || !plan->ctx) return JG_E_NULL;
     const jg_linear_desc& d = plan->d;
     if (int rc = check_ptr_array(x_sh, d.ways)) return rc;
@@ -969,10 +973,23 @@ int jg_layernorm_forward(const jg_plan* plan, const float* const* x_sh, const fl
     for (int r = 0; r < d.ways; ++r) {
         int64_t rb, cb;
         block_coords(d.ways, r, &rb, &cb);     // the channels are the columns of X: block cb of them
-        g.b[r] = {x_sh[r], out_sh[r], gamma ? gamma + cb * plan->xc : nullptr, beta ? beta + cb * plan->xc : nullptr};
+        g.b[r] = {x_sh[r], out_sh[r], gamma ? gamma + cb * plan->xc : nullptr, beta ? beta + cb * plan->xc : nullptr,
+                  nullptr};
+    }
+    if (copy16 && d.dtype != JG_F32 && jg::norm_rows_fit(g)) {
+        g.planes16 = d.dtype == JG_BF16X3 ? 2 : 1;
+        g.plane16 = (int)plan->plane;
+        for (int r = 0; r < d.ways; ++r) g.b[r].y16 = copy16[r];
+        if (copied) *copied = true;
     }
     ScopedTimer t(c, JG_KERNEL_NORM);
     return HIP_OK(jg::launch_norm_group(g, c->stream)) ? JG_OK : JG_E_HIP;
+}
+
+int jg_layernorm_forward(const jg_plan* plan, const float* const* x_sh, const float* gamma, const float* beta,
+                         double eps, float* const* out_sh)
+{
+    return layernorm_impl(plan, x_sh, gamma, beta, eps, out_sh, nullptr, nullptr);
 }
 
 // X [M x C] -> H [M x Hd] -> Y [M x C]: the second layer maps back to the first one's input width
@@ -1020,10 +1037,19 @@ static int convert_shards(const jg_plan* plan, const float* const* in_sh, char* 
     return HIP_OK(jg::launch_cvt_group(cv, c->stream)) ? JG_OK : JG_E_HIP;
 }
 
+// Checks of a reduced-precision chain's workspace (the FP32 chain's are those of its layers).
+static int check_chain_workspace(const jg_plan* first, const jg_plan* second, void* workspace, size_t workspace_bytes)
+{
+    if (first->d.dtype == JG_F32) return JG_OK;
+    if (!workspace || workspace_bytes < chain_h16_offset(first, second) + second->chain_bytes) return JG_E_WORKSPACE;
+    return aligned(workspace, kWsAlign) ? JG_OK : JG_E_ALIGN;
+}
+
+// input_converted: the first layer's rounded input is in place already (the layer norm wrote it).
 static int run_chain(const jg_plan* first, const jg_plan* second, const float* const* in_sh, const float* const* x_sh,
                      const float* const* w1_sh, const float* const* b1_sh, const float* const* w2_sh,
                      const float* const* b2_sh, float* const* h_sh, float* const* y_sh, void* workspace,
-                     size_t workspace_bytes)
+                     size_t workspace_bytes, bool input_converted)
 {
     if (first->d.dtype == JG_F32) {
         // H_r is written by the first layer in the partition the second one reads its input in
@@ -1034,15 +1060,19 @@ static int run_chain(const jg_plan* first, const jg_plan* second, const float* c
     const int ways = first->d.ways;
     if (int rc = check_ptr_array(in_sh, ways)) return rc;
     const size_t off_h16 = chain_h16_offset(first, second);
-    if (!workspace || workspace_bytes < off_h16 + second->chain_bytes) return JG_E_WORKSPACE;
-    if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
+    if (int rc = check_chain_workspace(first, second, workspace, workspace_bytes)) return rc;
     jg_ctx* c = first->ctx;
     if (!c) return JG_E_NULL;
     if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
     char* ws = static_cast<char*>(workspace);
     const float* x16[4] = {nullptr, nullptr, nullptr, nullptr};
     const float* h16[4] = {nullptr, nullptr, nullptr, nullptr};
-    if (int rc = convert_shards(first, in_sh, ws + first->ws_bytes, x16)) return rc;
+    if (input_converted) {
+        for (int r = 0; r < ways; ++r)
+            x16[r] = reinterpret_cast<const float*>(ws + first->ws_bytes + r * first->chain_shard_bytes);
+    } else if (int rc = convert_shards(first, in_sh, ws + first->ws_bytes, x16)) {
+        return rc;
+    }
     const bool fused = first->d.combine == JG_COMBINE_FUSED;
     jg::HbCopy16 copy;
     std::memset(&copy, 0, sizeof(copy));
@@ -1069,9 +1099,19 @@ int jg_mixing_forward(const jg_plan* first, const jg_plan* second, const float* 
 {
     if (int rc = check_mlp_chain(first, second)) return rc;
     if (int rc = check_ptr_array(h_sh, first->d.ways)) return rc;
-    int rc = jg_layernorm_forward(first, x_sh, gamma, beta, eps, xn_sh);
+    if (int rc = check_chain_workspace(first, second, workspace, workspace_bytes)) return rc;
+    // a reduced-precision chain: the norm writes its output a second time, rounded, where the first layer reads it
+    uint16_t* x16[4] = {nullptr, nullptr, nullptr, nullptr};
+    const bool reduced = first->d.dtype != JG_F32;
+    if (reduced)
+        for (int r = 0; r < first->d.ways; ++r)
+            x16[r] = reinterpret_cast<uint16_t*>(static_cast<char*>(workspace) + first->ws_bytes +
+                                                 r * first->chain_shard_bytes);
+    bool copied = false;
+    int rc = layernorm_impl(first, x_sh, gamma, beta, eps, xn_sh, reduced ? x16 : nullptr, &copied);
     if (rc != JG_OK) return rc;
-    return run_chain(first, second, xn_sh, x_sh, w1_sh, b1_sh, w2_sh, b2_sh, h_sh, y_sh, workspace, workspace_bytes);
+    return run_chain(first, second, xn_sh, x_sh, w1_sh, b1_sh, w2_sh, b2_sh, h_sh, y_sh, workspace, workspace_bytes,
+                     copied);
 }
 
 int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh,
@@ -1081,7 +1121,8 @@ int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* con
 {
     if (int rc = check_mlp_chain(first, second)) return rc;
     if (int rc = check_ptr_array(h_sh, first->d.ways)) return rc;
-    return run_chain(first, second, x_sh, x_sh, w1_sh, b1_sh, w2_sh, b2_sh, h_sh, y_sh, workspace, workspace_bytes);
+    return run_chain(first, second, x_sh, x_sh, w1_sh, b1_sh, w2_sh, b2_sh, h_sh, y_sh, workspace, workspace_bytes,
+                     false);
 }
 
 }  // extern "C"

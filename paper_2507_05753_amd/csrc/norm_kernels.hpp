@@ -14,6 +14,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include "cvt_kernels.hpp"
 #include "stream_kernels.hpp"
 
 namespace jg {
@@ -23,6 +24,9 @@ struct NormBlock {
     float* y;            // rows x cols, dense; may be x itself
     const float* gamma;  // the block's cols scale factors, or nullptr (1)
     const float* beta;   // the block's cols offsets, or nullptr (0)
+    uint16_t* y16;       // optional second copy of y rounded to bfloat16 as the shard step rounds (rows of planes16
+                         // planes of plane16 elements: [hi | lo]); nullptr: none.  Taken by the register-resident
+                         // kernel only: see launch_norm_group
 };
 
 struct NormGroup {
@@ -30,6 +34,7 @@ struct NormGroup {
     int nblocks;
     int rows, cols;      // common shape
     double eps;
+    int plane16, planes16;   // layout of the y16 copies
 };
 
 constexpr int NORM_THREADS = 256;
@@ -94,6 +99,17 @@ __global__ __launch_bounds__(NORM_THREADS) void layernorm_rows_f32(const NormGro
             o.z = (float)(((double)v[i].z - mu) * rstd * (double)ga.z + (double)be.z);
             o.w = (float)(((double)v[i].w - mu) * rstd * (double)ga.w + (double)be.w);
             y[c] = o;
+            if (B.y16) {
+                typedef uint32_t vu2 __attribute__((ext_vector_type(2)));
+                const uint32_t h0 = bf16_bits(o.x), h1 = bf16_bits(o.y), h2 = bf16_bits(o.z), h3 = bf16_bits(o.w);
+                uint16_t* at = B.y16 + (int64_t)row * g.plane16 * g.planes16 + 4 * c;
+                *reinterpret_cast<vu2*>(at) = vu2{h0 | (h1 << 16), h2 | (h3 << 16)};
+                if (g.planes16 == 2) {
+                    const uint32_t l0 = bf16_bits(o.x - bf16_value(h0)), l1 = bf16_bits(o.y - bf16_value(h1));
+                    const uint32_t l2 = bf16_bits(o.z - bf16_value(h2)), l3 = bf16_bits(o.w - bf16_value(h3));
+                    *reinterpret_cast<vu2*>(at + g.plane16) = vu2{l0 | (l1 << 16), l2 | (l3 << 16)};
+                }
+            }
         }
     }
 }
@@ -142,6 +158,14 @@ inline void launch_norm_rows(const NormGroup& g, hipStream_t stream)
     hipLaunchKernelGGL((layernorm_rows_f32<NV>), grid, dim3(NORM_THREADS), 0, stream, g);
 }
 
+// True when the group asks for bfloat16 copies.
+inline bool norm_wants_copies(const NormGroup& g)
+{
+    for (int i = 0; i < g.nblocks; ++i)
+        if (g.b[i].y16) return true;
+    return false;
+}
+
 // True when the register-resident kernel can take the group.
 inline bool norm_rows_fit(const NormGroup& g)
 {
@@ -154,9 +178,17 @@ inline bool norm_rows_fit(const NormGroup& g)
     return true;
 }
 
+// A group with bfloat16 copies must fit the register-resident kernel (the caller checks norm_rows_fit and
+// converts separately otherwise); the copies must be 8-byte aligned with plane16 a multiple of 4.
 inline hipError_t launch_norm_group(const NormGroup& g, hipStream_t stream)
 {
     if (g.rows <= 0 || g.cols <= 0 || g.nblocks <= 0) return hipSuccess;
+    if (norm_wants_copies(g)) {
+        if (!norm_rows_fit(g) || (g.plane16 & 3) || g.plane16 < g.cols || (g.planes16 != 1 && g.planes16 != 2))
+            return hipErrorInvalidValue;
+        for (int i = 0; i < g.nblocks; ++i)
+            if ((uintptr_t)g.b[i].y16 & 7) return hipErrorInvalidValue;
+    }
     if (norm_rows_fit(g)) {
         const int need = (g.cols / 4 + 63) / 64;      // vectors per lane
         if (need <= 1) launch_norm_rows<1>(g, stream);
