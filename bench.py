@@ -378,9 +378,14 @@ def measure_mixing(cfg, ways, args):
                    gemm_tflops=(flops / launches) / (avg * 1e-3) / 1e12 if gemm_n else None,
                    other_kernels_ms_per_step=copy_ms + comb_ms, workspace_bytes=L.ws_bytes,
                    norm_avg_launch_ms=norm_avg, norm_launches_timed=norm["launches"],
-                   norm_gbps=8.0 * M * C / (norm_avg * 1e-3) / 1e9 if norm["launches"] else None)
+                   norm_gbps=norm_bytes_per_element(args) * M * C / (norm_avg * 1e-3) / 1e9 if norm["launches"] else None)
     torch.cuda.empty_cache()
     return out
+
+
+def norm_bytes_per_element(args):
+    """The layer norm reads and writes FP32; in a mixed-precision block it also writes the first layer's rounded input."""
+    return {"f32": 8.0, "bf16": 10.0, "bf16x3": 12.0}[args.dtype]
 
 
 def reduced_terms(args):
@@ -632,7 +637,7 @@ def main():
                           "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                           "frac": r["norm_gbps"] / HBM_PEAK_GBPS if r["norm_gbps"] else None,
                           "avg_launch_ms": r["norm_avg_launch_ms"], "launches": r["norm_launches_timed"],
-                          "bytes_per_element": 8},
+                          "bytes_per_element": norm_bytes_per_element(args)},
             "other_kernels_ms_per_step": r["other_kernels_ms_per_step"],
         }
         if args.cpu_seconds > 0:
