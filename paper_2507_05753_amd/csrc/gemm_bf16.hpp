@@ -110,13 +110,13 @@ typedef int hb_int4 __attribute__((ext_vector_type(4)));
 // an instruction rather than through the compiler's builtin: for the builtin the compiler makes every
 // later LDS read wait until ALL transfers in flight have landed, which would undo the prefetch
 // distance; here the kernel's own vmcnt waits say which slab must have arrived.  M0 carries the LDS
-// address (the compiler keeps nothing in M0 across statements).
+// address and is declared clobbered.
 __device__ __forceinline__ void hb_transfer(const hb_int4& rsrc, unsigned lds_base, int voffset, int soffset)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // Asks L2 for the lines that hold the first four bytes at each lane's offset (lanes whose offset lies outside
@@ -127,7 +127,7 @@ __device__ __forceinline__ void hb_prefetch(const hb_int4& rsrc, unsigned lds_du
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
                  :
                  : "s"(lds_dump), "v"(voffset), "s"(rsrc), "s"(soffset)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // One operand's slabs, global -> LDS, ROW bytes (64 or 128) of every tile row per slab.  ROW / 16 lanes share
