@@ -382,6 +382,27 @@ def mixing_block_reduced(ways: int, X, gamma, beta, W1, b1, W2, b2, terms: int =
     return out
 
 
+def token_mixing_block(ways: int, X, gamma, beta, W1, b1, W2, b2, eps: float = LN_EPS):
+    """Token-mixing half of a mixing block (Sec. 3: the MLP applied along the token dimension of the layer-normed
+    input, skip connection around it).  X is [T x C]; every channel's column of T token values goes through
+        y_c = x_c + W2 gelu(W1^T xn_c + b1) + b2,     W1, W2: [T x D], b1: [D], b2: [T],
+    with xn the layer norm of X over each token's channels (as in the channel-mixing half).  In matrix form, with
+    the steps taken in the layouts the layers use: H = gelu(Xn^T W1 + b1) is [C x D] (the transposed layer of Sec. 5),
+    and Y = X + W2 H^T + b2 1^T is [T x C] again - a plain X W^T layer with W2 in the activations' place and H in the
+    weights' place, so nothing is ever transposed.  Xn and H are handed on in FP32 as the method stores them.
+    Returns H, Y, Xn (double) and the magnitudes S1 (pre-activation) and SY (the second layer's own sums plus |X|, |b2|)."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    Xn = layernorm(X, gamma, beta, ln_groups(ways), eps)
+    Xn32 = Xn.astype(np.float32)
+    S1 = linear_xtw(Xn32, W1, b1, absolute=True)
+    H = gelu(linear_xtw(Xn32, W1, b1))
+    H32 = H.astype(np.float32)
+    b2 = np.asarray(b2, dtype=np.float64)
+    Y = X.astype(np.float64) + linear(W2, H32) + b2[:, None]
+    SY = np.abs(X.astype(np.float64)) + magnitude(W2, H32) + np.abs(b2)[:, None]
+    return dict(H=H, Y=Y, Xn=Xn, S1=S1, SY=SY)
+
+
 # ----------------------------------------------------------------------------
 # patch encoder / decoder (Sec. 5 "Encoding and decoding layers"): a convolution whose kernel
 # equals its stride is a linear layer over non-overlapping patches

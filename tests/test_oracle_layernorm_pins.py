@@ -195,3 +195,77 @@ def test_block_sees_the_norm():
     # without the norm the rows would differ
     plain = oracle.mlp(X, W1, b1, W2, b2)["Y"] - X
     assert np.abs(plain - plain[0]).max() > 1e-3
+
+
+# ---------------------------------------------------------------------------------------------
+# the token-mixing half of a mixing block: per channel, y_c = x_c + W2 gelu(W1^T xn_c + b1) + b2
+# ---------------------------------------------------------------------------------------------
+def token_operands(seed, T, C, D, mode="R"):
+    X = (inputs.matrix(seed, T, C, mode) + np.float32(0.25)).astype(np.float32)
+    W1 = inputs.matrix(seed + 60, T, D, mode, inputs.W_SCALE_EXP)
+    b1 = inputs.matrix(seed + 61, 1, D, mode)[0]
+    W2 = inputs.matrix(seed + 62, T, D, mode, inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(seed + 63, 1, T, mode)[0]
+    _, gamma, beta = data(seed + 64, 1, C, mode)
+    return X, gamma, beta, W1, b1, W2, b2
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+def test_token_mixing_channel_by_channel(ways):
+    """The definition, one channel at a time, with library products in double."""
+    T, C, D = 10, 8, 6
+    X, gamma, beta, W1, b1, W2, b2 = token_operands(12, T, C, D)
+    out = oracle.token_mixing_block(ways, X, gamma, beta, W1, b1, W2, b2)
+    Xn = oracle.layernorm(X, gamma, beta, oracle.ln_groups(ways))
+    assert np.array_equal(out["Xn"], Xn)
+    Xn32 = Xn.astype(np.float32).astype(np.float64)
+    W1d, W2d = W1.astype(np.float64), W2.astype(np.float64)
+    for c in range(C):
+        h = oracle.gelu(W1d.T @ Xn32[:, c] + b1)                     # [D]
+        assert np.allclose(out["H"][c], h, rtol=0, atol=1e-13)
+        h32 = out["H"][c].astype(np.float32).astype(np.float64)       # handed on in FP32
+        y = X[:, c].astype(np.float64) + W2d @ h32 + b2
+        assert np.allclose(out["Y"][:, c], y, rtol=0, atol=1e-12 * np.abs(out["SY"][:, c]).max())
+
+
+def test_token_mixing_in_closed_form():
+    """All-integer operands with gamma = 1, beta = 0 replaced by a norm that is known: constant channels.  With every
+    token's channels equal the layer norm gives beta for every entry, so H and Y follow from small integers."""
+    T, C, D = 6, 4, 5
+    X = np.tile(np.arange(1, T + 1, dtype=np.float32)[:, None], (1, C))      # token t holds t + 1 in every channel
+    gamma = np.ones(C, dtype=np.float32)
+    beta = np.full(C, 2.0, dtype=np.float32)                                   # Xn = 2 everywhere, exactly
+    rng = np.random.default_rng(5)
+    W1 = rng.integers(0, 2, (T, D)).astype(np.float32)
+    b1 = np.full(D, 10.0, dtype=np.float32)                                    # pre-activation >= 10: gelu(x) = x in double
+    W2 = rng.integers(-1, 2, (T, D)).astype(np.float32)
+    b2 = rng.integers(-3, 4, T).astype(np.float32)
+    out = oracle.token_mixing_block(1, X, gamma, beta, W1, b1, W2, b2)
+    h = 2 * W1.astype(np.int64).sum(axis=0) + 10                               # the same for every channel
+    assert np.array_equal(out["H"], np.tile(h.astype(np.float64), (C, 1)))
+    y = X.astype(np.int64) + (W2.astype(np.int64) @ h)[:, None] + b2.astype(np.int64)[:, None]
+    assert np.array_equal(out["Y"], y.astype(np.float64))
+    # the bias of the second layer goes with the token (row), not with the channel
+    assert not np.array_equal(y, X.astype(np.int64) + (W2.astype(np.int64) @ h)[:, None] + b2.astype(np.int64)[None, :C].repeat(T, 0)) \
+        or np.all(b2 == b2[0])
+
+
+def test_token_mixing_mixes_tokens_not_channels():
+    T, C, D = 8, 6, 5
+    X, gamma, beta, W1, b1, W2, b2 = token_operands(13, T, C, D)
+    base = oracle.token_mixing_block(1, X, gamma, beta, W1, b1, W2, b2)
+    # changing one weight row (one token's weights) changes every channel; channels do not mix apart from the norm:
+    # with the norm switched to a fixed input (gamma = 0) a change in one channel of X moves only that channel of Y
+    g0 = np.zeros_like(gamma)
+    a = oracle.token_mixing_block(1, X, g0, beta, W1, b1, W2, b2)
+    X2 = X.copy()
+    X2[3, 2] += np.float32(1.0)
+    b = oracle.token_mixing_block(1, X2, g0, beta, W1, b1, W2, b2)
+    changed = np.argwhere(a["Y"] != b["Y"])
+    assert set(changed[:, 1]) == {2} and set(changed[:, 0]) == {3}             # only through the skip connection
+    # with the norm in place the same change reaches all tokens of all channels of that token's norm group
+    c2 = oracle.token_mixing_block(1, X2, gamma, beta, W1, b1, W2, b2)
+    assert len(np.argwhere(c2["Y"] != base["Y"])) > T
+    # zero second layer: identity plus the per-token bias
+    z = oracle.token_mixing_block(2, X, gamma, beta, W1, b1, np.zeros_like(W2), b2)
+    assert np.array_equal(z["Y"], X.astype(np.float64) + b2.astype(np.float64)[:, None])
