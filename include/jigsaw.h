@@ -147,9 +147,12 @@ typedef enum jg_query {
     JG_Q_BACKWARD_TAIL_SCRATCH_BYTES = 18, /* the same for JG_Q_BACKWARD_WORKSPACE_BYTES          */
     JG_Q_X_SHARD_BYTES = 19,            /* bytes of the rank's X shard in the plan's dtype        */
     JG_Q_W_SHARD_BYTES = 20,            /* ... and of its W shard                                 */
-    JG_Q_CHAIN_WORKSPACE_BYTES = 21     /* the plan's share of the workspace of jg_mlp_forward /
+    JG_Q_CHAIN_WORKSPACE_BYTES = 21,    /* the plan's share of the workspace of jg_mlp_forward /
                                            jg_mixing_forward: JG_Q_WORKSPACE_BYTES, plus (reduced
                                            precision) room for its input in bfloat16 (rank ignored) */
+    JG_Q_X_F32_SHARDS_BYTES = 22        /* `ways` FP32 shards shaped like X_r, each rounded up to 256
+                                           bytes: what jg_token_mixing_forward needs for its skip
+                                           connection when b2 is given (rank ignored)               */
 } jg_query;
 
 typedef enum jg_kernel {         /* kernel classes for jg_profile_read */
@@ -325,6 +328,29 @@ int jg_mixing_forward(const jg_plan* first, const jg_plan* second, const float* 
                       const float* beta, double eps, const float* const* w1_sh, const float* const* b1_sh,
                       const float* const* w2_sh, const float* const* b2_sh, float* const* xn_sh,
                       float* const* h_sh, float* const* y_sh, void* workspace, size_t workspace_bytes);
+
+/* run (token-mixing block).  The token-mixing half of a mixing block (Sec. 3: the MLP along the token dimension
+ * of the layer-normed input, skip connection around it; Sec. 5: its first layer is the transposed multiplication)
+ * on Jigsaw shards.  X is T x C (tokens x channels); for every channel c, with xn = layernorm(X) as in
+ * jg_layernorm_forward,
+ *     y_c = x_c + W2 gelu(W1^T xn_c + b1) + b2,      W1, W2: T x D,  b1: D,  b2: T,
+ * evaluated without transposing anything:
+ *     H = gelu(Xn^T W1 + b1)     C x D   `first`:  a JG_OP_XTW plan with K = T, M = C, N = D, with bias;
+ *     Y = X + W2 H^T + b2 1^T    T x C   `second`: a JG_OP_XWT plan with M = T, K = D, N = C, WITHOUT bias, in which
+ *                                        W2 takes the activations' place and H the weights' place.
+ * Same `ways`, same context.  H_r leaves the first layer partitioned as the second one partitions its weights, and
+ * Y_r is partitioned like X_r, so nothing is re-sharded.  x_sh: the first plan's X shards (jg_shard(first, JG_T_X)
+ * of the T x C input); w1_sh: its W shards; b1_sh: its bias shards; w2_sh: jg_shard(second, JG_T_X) of the T x D
+ * matrix W2; b2: device vector of length T (the second layer's bias, one value per token), or NULL; gamma, beta,
+ * eps, xn_sh as in jg_mixing_forward; h_sh: `ways` buffers shaped like the first plan's Y_r; y_sh: like X_r.
+ * Workspace: the larger of the two plans' JG_Q_WORKSPACE_BYTES, plus the first plan's JG_Q_X_F32_SHARDS_BYTES when
+ * b2 is given (the norm writes X + b2 there for the skip connection).
+ * Errors: JG_E_NULL, JG_E_DTYPE (ops, precision, or the second plan has a bias), JG_E_WAYS, JG_E_SHAPE (plans do
+ * not chain), JG_E_WORKSPACE, JG_E_ALIGN, and those of jg_linear_forward_ex and jg_layernorm_forward. */
+int jg_token_mixing_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* gamma,
+                            const float* beta, double eps, const float* const* w1_sh, const float* const* b1_sh,
+                            const float* const* w2_sh, const float* b2, float* const* xn_sh, float* const* h_sh,
+                            float* const* y_sh, void* workspace, size_t workspace_bytes);
 
 /* run (backward).  Gradients of the same layer for an incoming gradient dY (partitioned like Y):
  *     dX = dY W      (M x K, partitioned like X)       dW = dY^T X    (N x K, partitioned like W)

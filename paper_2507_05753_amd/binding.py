@@ -41,7 +41,7 @@ JG_T_X, JG_T_W, JG_T_B, JG_T_Y, JG_T_X_F32 = 0, 1, 2, 3, 4
  JG_Q_Y_ROWS, JG_Q_Y_COLS, JG_Q_B_LEN, JG_Q_RESIDENT_BYTES_RANK, JG_Q_GEMM_LAUNCHES,
  JG_Q_BACKWARD_WORKSPACE_BYTES, JG_Q_BACKWARD_FLOPS_TOTAL, JG_Q_BACKWARD_GEMM_LAUNCHES,
  JG_Q_TAIL_SCRATCH_BYTES, JG_Q_BACKWARD_TAIL_SCRATCH_BYTES, JG_Q_X_SHARD_BYTES, JG_Q_W_SHARD_BYTES,
- JG_Q_CHAIN_WORKSPACE_BYTES) = range(22)
+ JG_Q_CHAIN_WORKSPACE_BYTES, JG_Q_X_F32_SHARDS_BYTES) = range(23)
 (JG_KERNEL_GEMM, JG_KERNEL_WEIGHT_COPY, JG_KERNEL_COMBINE, JG_KERNEL_SHARD,
  JG_KERNEL_GATHER, JG_KERNEL_GEMM_DX, JG_KERNEL_GEMM_DW, JG_KERNEL_JOIN, JG_KERNEL_NORM,
  JG_KERNEL_COUNT) = range(10)
@@ -49,7 +49,8 @@ JG_T_X, JG_T_W, JG_T_B, JG_T_Y, JG_T_X_F32 = 0, 1, 2, 3, 4
 EXPORTS = ("jg_init", "jg_free", "jg_plan_create", "jg_plan_destroy", "jg_plan_query", "jg_shard",
            "jg_shard_patches", "jg_gather_patches",
            "jg_linear_forward", "jg_linear_forward_ex", "jg_mlp_forward", "jg_layernorm_forward",
-           "jg_mixing_forward", "jg_linear_backward", "jg_gather", "jg_gather_as", "jg_profile", "jg_profile_read", "jg_strerror",
+           "jg_mixing_forward", "jg_token_mixing_forward", "jg_linear_backward", "jg_gather", "jg_gather_as", "jg_profile",
+           "jg_profile_read", "jg_strerror",
            "jg_last_hip_error")
 
 
@@ -93,6 +94,8 @@ _lib.jg_mlp_forward.argtypes = [_vp, _vp, _vpp, _vpp, _vpp, _vpp, _vpp, _vpp, _v
 _lib.jg_layernorm_forward.argtypes = [_vp, _vpp, _vp, _vp, ctypes.c_double, _vpp]
 _lib.jg_mixing_forward.argtypes = [_vp, _vp, _vpp, _vp, _vp, ctypes.c_double, _vpp, _vpp, _vpp, _vpp, _vpp, _vpp, _vpp,
                                    _vp, ctypes.c_size_t]
+_lib.jg_token_mixing_forward.argtypes = [_vp, _vp, _vpp, _vp, _vp, ctypes.c_double, _vpp, _vpp, _vpp, _vp, _vpp, _vpp,
+                                         _vpp, _vp, ctypes.c_size_t]
 _lib.jg_linear_backward.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
 _lib.jg_gather.argtypes = [_vp, _vpp, _vp, ctypes.c_int64]
 _lib.jg_gather_as.argtypes = [_vp, ctypes.c_int, _vpp, _vp, ctypes.c_int64]
@@ -100,8 +103,8 @@ _lib.jg_profile.argtypes = [_vp, ctypes.c_int]
 _lib.jg_profile_read.argtypes = [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                  ctypes.POINTER(ctypes.c_int64)]
 for _n in ("jg_init", "jg_plan_create", "jg_plan_query", "jg_shard", "jg_linear_forward", "jg_linear_forward_ex",
-           "jg_mlp_forward", "jg_layernorm_forward", "jg_mixing_forward", "jg_linear_backward",
-           "jg_gather", "jg_gather_as", "jg_profile", "jg_profile_read"):
+           "jg_mlp_forward", "jg_layernorm_forward", "jg_mixing_forward", "jg_token_mixing_forward",
+           "jg_linear_backward", "jg_gather", "jg_gather_as", "jg_profile", "jg_profile_read"):
     getattr(_lib, _n).restype = ctypes.c_int
 
 
@@ -197,6 +200,14 @@ def jg_mixing_forward(first, second, x_ptrs, gamma_ptr, beta_ptr, eps: float, w1
                                   _ptr_array(w1_ptrs), _ptr_array(b1_ptrs), _ptr_array(w2_ptrs), _ptr_array(b2_ptrs),
                                   _ptr_array(xn_ptrs), _ptr_array(h_ptrs), _ptr_array(y_ptrs),
                                   workspace_ptr or None, workspace_bytes), "jg_mixing_forward")
+
+
+def jg_token_mixing_forward(first, second, x_ptrs, gamma_ptr, beta_ptr, eps: float, w1_ptrs, b1_ptrs, w2_ptrs, b2_ptr,
+                            xn_ptrs, h_ptrs, y_ptrs, workspace_ptr, workspace_bytes: int) -> None:
+    _raise(_lib.jg_token_mixing_forward(first, second, _ptr_array(x_ptrs), gamma_ptr or None, beta_ptr or None,
+                                        float(eps), _ptr_array(w1_ptrs), _ptr_array(b1_ptrs), _ptr_array(w2_ptrs),
+                                        b2_ptr or None, _ptr_array(xn_ptrs), _ptr_array(h_ptrs), _ptr_array(y_ptrs),
+                                        workspace_ptr or None, workspace_bytes), "jg_token_mixing_forward")
 
 
 def jg_linear_backward(plan, x_ptrs, w_ptrs, dy_ptrs, dx_ptrs, dw_ptrs, workspace_ptr, workspace_bytes: int) -> None:

@@ -407,6 +407,9 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     case JG_Q_X_SHARD_BYTES: *out = 4 * plan->xr * plan->xcp; break;
     case JG_Q_W_SHARD_BYTES: *out = 4 * plan->wr * plan->xcp; break;
     case JG_Q_CHAIN_WORKSPACE_BYTES: *out = (int64_t)(plan->ws_bytes + plan->chain_bytes); break;
+    case JG_Q_X_F32_SHARDS_BYTES:
+        *out = (int64_t)(round_up(4 * (size_t)plan->xr * (size_t)plan->xc, kWsAlign) * d.ways);
+        break;
     default: return JG_E_DTYPE;
     }
     return JG_OK;
@@ -950,8 +953,11 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
 // jg_layernorm_forward.  copy16 (may be null): `ways` destinations for a bfloat16 copy of the output in the
 // plan's X-shard format; *copied tells whether the kernel wrote them (it does when the rows fit its
 // register-resident form; otherwise the caller converts the FP32 output).
+// xb_sh / row_bias (may be null): `ways` destinations for x + row_bias[token] (FP32, shaped like X_r); row_bias is a
+// device vector over all rows of X.
 static int layernorm_impl(const jg_plan* plan, const float* const* x_sh, const float* gamma, const float* beta,
-                          double eps, float* const* out_sh, uint16_t* const* copy16, bool* copied)
+                          double eps, float* const* out_sh, uint16_t* const* copy16, bool* copied,
+                          float* const* xb_sh = nullptr, const float* row_bias = nullptr)
 {
     if (copied) *copied = false;
     if (!plan || !plan->ctx) return JG_E_NULL;
@@ -974,7 +980,7 @@ static int layernorm_impl(const jg_plan* plan, const float* const* x_sh, const f
         int64_t rb, cb;
         block_coords(d.ways, r, &rb, &cb);     // the channels are the columns of X: block cb of them
         g.b[r] = {x_sh[r], out_sh[r], gamma ? gamma + cb * plan->xc : nullptr, beta ? beta + cb * plan->xc : nullptr,
-                  nullptr};
+                  xb_sh ? xb_sh[r] : nullptr, xb_sh ? row_bias + rb * plan->xr : nullptr, nullptr};
     }
     if (copy16 && d.dtype != JG_F32 && jg::norm_rows_fit(g)) {
         g.planes16 = d.dtype == JG_BF16X3 ? 2 : 1;
@@ -1123,6 +1129,56 @@ int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* con
     if (int rc = check_ptr_array(h_sh, first->d.ways)) return rc;
     return run_chain(first, second, x_sh, x_sh, w1_sh, b1_sh, w2_sh, b2_sh, h_sh, y_sh, workspace, workspace_bytes,
                      false);
+}
+
+// X [T x C] -> H [C x D] (transposed layer) -> Y [T x C] (plain layer, W2 in the activations' place, H in the weights')
+static int check_token_chain(const jg_plan* first, const jg_plan* second)
+{
+    if (!first || !second) return JG_E_NULL;
+    const jg_linear_desc &a = first->d, &b = second->d;
+    if (a.op != JG_OP_XTW || b.op != JG_OP_XWT) return JG_E_DTYPE;
+    if (a.dtype != JG_F32 || b.dtype != JG_F32) return JG_E_DTYPE;
+    if (a.ways != b.ways) return JG_E_WAYS;
+    // first: K = T, M = C, N = D; second: M = T, K = D, N = C
+    if (a.K != b.M || a.M != b.N || a.N != b.K) return JG_E_SHAPE;
+    if (b.has_bias) return JG_E_DTYPE;      // the second layer's bias goes with the token: it is b2, not a column bias
+    if (first->ctx != second->ctx) return JG_E_NULL;
+    return JG_OK;
+}
+
+int jg_token_mixing_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* gamma,
+                            const float* beta, double eps, const float* const* w1_sh, const float* const* b1_sh,
+                            const float* const* w2_sh, const float* b2, float* const* xn_sh, float* const* h_sh,
+                            float* const* y_sh, void* workspace, size_t workspace_bytes)
+{
+    if (int rc = check_token_chain(first, second)) return rc;
+    const int ways = first->d.ways;
+    if (int rc = check_ptr_array(h_sh, ways)) return rc;
+    if (int rc = check_ptr_array(x_sh, ways)) return rc;
+    if (!aligned(b2, 4)) return JG_E_ALIGN;
+    const size_t base = first->ws_bytes > second->ws_bytes ? first->ws_bytes : second->ws_bytes;
+    const size_t shard = round_up(4 * (size_t)first->xr * (size_t)first->xc, kWsAlign);
+    const size_t need = base + (b2 ? shard * ways : 0);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return JG_E_WORKSPACE;
+        if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
+    }
+    // the skip connection carries the second layer's per-token bias: the norm, which reads X anyway, also writes
+    // X + b2[token] for it
+    float* xb[4] = {nullptr, nullptr, nullptr, nullptr};
+    const float* res[4];
+    for (int r = 0; r < ways; ++r) {
+        if (b2) xb[r] = reinterpret_cast<float*>(static_cast<char*>(workspace) + base + r * shard);
+        res[r] = b2 ? xb[r] : x_sh[r];
+    }
+    int rc = layernorm_impl(first, x_sh, gamma, beta, eps, xn_sh, nullptr, nullptr, b2 ? xb : nullptr, b2);
+    if (rc != JG_OK) return rc;
+    // H = gelu(Xn^T W1 + b1): [C x D], partitioned like the first plan's Y - which is how the second plan
+    // partitions its weights
+    rc = forward_impl(first, xn_sh, w1_sh, b1_sh, nullptr, JG_ACT_GELU, h_sh, workspace, workspace_bytes, nullptr);
+    if (rc != JG_OK) return rc;
+    // Y = (X + b2) + W2 H^T: [T x C], partitioned like X
+    return forward_impl(second, w2_sh, h_sh, nullptr, res, JG_ACT_NONE, y_sh, workspace, workspace_bytes, nullptr);
 }
 
 }  // extern "C"

@@ -24,6 +24,9 @@ struct NormBlock {
     float* y;            // rows x cols, dense; may be x itself
     const float* gamma;  // the block's cols scale factors, or nullptr (1)
     const float* beta;   // the block's cols offsets, or nullptr (0)
+    float* xb;           // optional: x + row_bias[row] per row (the input with a per-token offset added, for a skip
+                         // connection that carries the bias of a layer along the token dimension); nullptr: none
+    const float* row_bias;   // rows values, read when xb is set
     uint16_t* y16;       // optional second copy of y rounded to bfloat16 as the shard step rounds (rows of planes16
                          // planes of plane16 elements: [hi | lo]); nullptr: none.  Taken by the register-resident
                          // kernel only: see launch_norm_group
@@ -84,6 +87,15 @@ __global__ __launch_bounds__(NORM_THREADS) void layernorm_rows_f32(const NormGro
     const double rstd = 1.0 / sqrt(wave_sum(q) / (double)g.cols + g.eps);
 #pragma unroll
     for (int i = 0; i < NV; ++i) asm volatile("" : "+v"(v[i]));
+    if (B.xb) {
+        const float rb = B.row_bias[row];
+        vf4* xb = reinterpret_cast<vf4*>(B.xb + (int64_t)row * g.cols);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int c = i * 64 + lane;
+            if (c < nvec) xb[c] = v[i] + rb;
+        }
+    }
     vf4* y = reinterpret_cast<vf4*>(B.y + (int64_t)row * g.cols);
     const vf4* gamma = reinterpret_cast<const vf4*>(B.gamma);
     const vf4* beta = reinterpret_cast<const vf4*>(B.beta);
@@ -144,10 +156,14 @@ __global__ __launch_bounds__(NORM_THREADS) void layernorm_generic_f32(const Norm
     }
     const double rstd = 1.0 / sqrt(block_sum(q) / (double)g.cols + g.eps);
     // every element is read for the last time by the thread that overwrites it: y may be x
+    float* xb = B.xb ? B.xb + (int64_t)blockIdx.x * g.cols : nullptr;
+    const float rb = B.xb ? B.row_bias[blockIdx.x] : 0.f;
     for (int c = tid; c < g.cols; c += NORM_THREADS) {
         const double ga = B.gamma ? (double)B.gamma[c] : 1.0;
         const double be = B.beta ? (double)B.beta[c] : 0.0;
-        y[c] = (float)(((double)x[c] - mu) * rstd * ga + be);
+        const float xv = x[c];
+        if (xb) xb[c] = xv + rb;
+        y[c] = (float)(((double)xv - mu) * rstd * ga + be);
     }
 }
 
@@ -172,7 +188,8 @@ inline bool norm_rows_fit(const NormGroup& g)
     if ((g.cols & 3) || g.cols / 4 > 64 * kNormMaxVectorsPerLane) return false;
     for (int i = 0; i < g.nblocks; ++i) {
         const NormBlock& b = g.b[i];
-        if (((uintptr_t)b.x & 15) || ((uintptr_t)b.y & 15) || ((uintptr_t)b.gamma & 15) || ((uintptr_t)b.beta & 15))
+        if (((uintptr_t)b.x & 15) || ((uintptr_t)b.y & 15) || ((uintptr_t)b.gamma & 15) || ((uintptr_t)b.beta & 15) ||
+            ((uintptr_t)b.xb & 15))
             return false;
     }
     return true;

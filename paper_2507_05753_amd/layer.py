@@ -255,3 +255,60 @@ class JigsawMixing(JigsawMLP):
         out = torch.empty((self.M, self.C), dtype=torch.float32, device=self.first.dev)
         jg.jg_gather_as(self.first.plan, jg.JG_T_X_F32, [t.data_ptr() for t in self.xn], out.data_ptr(), out.stride(0))
         return out
+
+
+class JigsawTokenMixing:
+    """Token-mixing half of a mixing block: Xn = layernorm(X), H = gelu(Xn^T W1 + b1), Y = X + W2 H^T + b2 1^T
+    (``jg_token_mixing_forward``).  X and Y are (T, C), W1 and W2 are (T, D), b1 is (D,), b2 is (T,), gamma and beta
+    are (C,).  The first holder is the transposed layer (X^T W), the second a plain layer in which W2 stands where
+    the activations do and H where the weights do; nothing is transposed in memory."""
+
+    def __init__(self, T: int, C: int, D: int, ways: int, device: int = 0, ctx=None, tail: int = jg.JG_TAIL_SPLIT,
+                 eps: float = 1e-5):
+        self.first = JigsawLinear(C, T, D, ways, bias=True, device=device, ctx=ctx, op=jg.JG_OP_XTW, tail=tail)
+        self.second = JigsawLinear(T, D, C, ways, bias=False, device=device, ctx=self.first.ctx, tail=tail)
+        self.second.w = self.first.y        # H_r is the second layer's weight shard, read where it was produced
+        self.T, self.C, self.D, self.ways, self.eps = T, C, D, ways, eps
+        self.ctx = self.first.ctx
+        self.xn = [torch.empty_like(t) for t in self.first.x]
+        self.gamma = self.beta = self.b2 = None
+        self.ws_bytes = max(self.first.ws_bytes, self.second.ws_bytes) + self.first.query(jg.JG_Q_X_F32_SHARDS_BYTES)
+        self.first.ws = self.second.ws = None
+        self.ws = torch.empty((max(self.ws_bytes, 1),), dtype=torch.uint8, device=self.first.dev)
+
+    def shard(self, X=None, gamma=None, beta=None, W1=None, b1=None, W2=None, b2=None):
+        self.first.shard(X, W1, b1)
+        if W2 is not None:      # W2 takes the place of the second layer's activations
+            assert W2.is_cuda and W2.dtype == torch.float32 and W2.shape == (self.T, self.D) and W2.stride(1) == 1
+            jg.jg_shard(self.second.plan, jg.JG_T_X, W2.data_ptr(), W2.stride(0), [t.data_ptr() for t in self.second.x])
+        for v, n in ((gamma, self.C), (beta, self.C), (b2, self.T)):
+            assert v is None or (v.is_cuda and v.dtype == torch.float32 and v.shape == (n,) and v.is_contiguous())
+        self.gamma, self.beta, self.b2 = gamma, beta, b2
+
+    def forward(self):
+        f, s = self.first, self.second
+        p = lambda ts: [t.data_ptr() for t in ts]
+        opt = lambda v: v.data_ptr() if v is not None else None
+        jg.jg_token_mixing_forward(f.plan, s.plan, p(f.x), opt(self.gamma), opt(self.beta), self.eps, p(f.w), p(f.b),
+                                   p(s.x), opt(self.b2), p(self.xn), p(f.y), p(s.y), self.ws.data_ptr(), self.ws_bytes)
+
+    def gather_xn(self):
+        out = torch.empty((self.T, self.C), dtype=torch.float32, device=self.first.dev)
+        jg.jg_gather_as(self.first.plan, jg.JG_T_X, [t.data_ptr() for t in self.xn], out.data_ptr(), out.stride(0))
+        return out
+
+    def gather_h(self):
+        return self.first.gather()
+
+    def gather(self):
+        return self.second.gather()
+
+    def close(self):
+        self.second.close()
+        self.first.close()
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()

@@ -248,3 +248,90 @@ def test_channel_mixing_size(jg, capsys):
         r = oracle.mixing_block(ways, Xs, gamma, beta, W1, b1, W2, b2)
         check_block(r, Xn, H, Y)
         note(capsys, f"channel mixing ways={ways}: ok")
+
+
+# ---------------------------------------------------------------------------------------------
+# the token-mixing half of a mixing block
+# ---------------------------------------------------------------------------------------------
+def token_operands(seed, T, C, D):
+    X = (inputs.matrix(seed, T, C, "R") + np.float32(0.25)).astype(np.float32)
+    W1 = inputs.matrix(seed + 1, T, D, "R", inputs.W_SCALE_EXP)
+    b1 = inputs.matrix(seed + 2, 1, D, "R")[0]
+    W2 = inputs.matrix(seed + 3, T, D, "R", inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(seed + 4, 1, T, "R")[0]
+    gamma, beta = affine(seed + 5, C)
+    return X, gamma, beta, W1, b1, W2, b2
+
+
+def check_token_block(X, gamma, beta, W1, b1, W2, b2, ways, Xn, H, Y):
+    want = oracle.layernorm(X, gamma, beta, oracle.ln_groups(ways))
+    assert np.all(np.abs(Xn.astype(np.float64) - want) <= HALF_ULP * np.abs(want) * (1 + 1e-6) + 1e-10)
+    # first layer from the Xn the GPU stored, second from the H it stored: each at the bar of one layer
+    S1 = oracle.magnitude_xtw(Xn, W1, b1)
+    eh = np.abs(H.astype(np.float64) - oracle.gelu(oracle.linear_xtw(Xn, W1, b1)))
+    assert np.all(eh <= TOL_H * S1), f"H: max err/S1 = {(eh / S1).max():.3e}"
+    b2d = np.zeros(X.shape[0]) if b2 is None else b2.astype(np.float64)
+    ref = X.astype(np.float64) + oracle.linear(W2, H) + b2d[:, None]
+    SY = np.abs(X.astype(np.float64)) + oracle.magnitude(W2, H) + np.abs(b2d)[:, None]
+    ey = np.abs(Y.astype(np.float64) - ref)
+    assert np.all(ey <= TOL * SY), f"Y: max err/S = {(ey / SY).max():.3e}"
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("T,C,D", [(100, 100, 100), (130, 72, 258), (258, 264, 136), (520, 300, 1032)])
+def test_token_mixing_forward(jg, ctx, ways, T, C, D):
+    from paper_2507_05753_amd.layer import JigsawTokenMixing
+    X, gamma, beta, W1, b1, W2, b2 = token_operands(95, T, C, D)
+    with JigsawTokenMixing(T, C, D, ways, ctx=ctx) as L:
+        L.ws.fill_(0xFF)
+        L.shard(dev(X), dev(gamma), dev(beta), dev(W1), dev(b1), dev(W2), dev(b2))
+        L.forward()
+        Xn, H, Y = L.gather_xn().cpu().numpy(), L.gather_h().cpu().numpy(), L.gather().cpu().numpy()
+        L.forward()                                   # the inputs were not overwritten: the same again
+        assert np.array_equal(Y, L.gather().cpu().numpy())
+    check_token_block(X, gamma, beta, W1, b1, W2, b2, ways, Xn, H, Y)
+    # end to end against the oracle's own chain (loose: H's last FP32 bits differ)
+    r = oracle.token_mixing_block(ways, X, gamma, beta, W1, b1, W2, b2)
+    assert np.all(np.abs(Y - r["Y"]) <= 1e-5 * r["SY"])
+    # the tokens are mixed: a channel-mixing block of the same operand shapes would not even type-check, and a
+    # block without the norm is far away
+    assert np.abs(Y - (X + b2[:, None])).max() > 1e-2
+
+
+@pytest.mark.parametrize("ways", [1, 4])
+def test_token_mixing_without_the_second_bias_and_without_scale(jg, ctx, ways):
+    from paper_2507_05753_amd.layer import JigsawTokenMixing
+    T, C, D = 130, 72, 64
+    X, gamma, beta, W1, b1, W2, b2 = token_operands(96, T, C, D)
+    with JigsawTokenMixing(T, C, D, ways, ctx=ctx) as L:
+        L.shard(dev(X), None, None, dev(W1), dev(b1), dev(W2), None)
+        L.forward()
+        Xn, H, Y = L.gather_xn().cpu().numpy(), L.gather_h().cpu().numpy(), L.gather().cpu().numpy()
+    check_token_block(X, None, None, W1, b1, W2, None, ways, Xn, H, Y)
+
+
+def test_token_mixing_argument_checks(jg, ctx):
+    from paper_2507_05753_amd.layer import JigsawLinear, JigsawTokenMixing
+    with JigsawTokenMixing(64, 32, 48, 2, ctx=ctx) as L, \
+            JigsawLinear(64, 48, 32, 2, bias=True, ctx=ctx) as biased, \
+            JigsawLinear(64, 48, 30, 2, ctx=ctx) as narrow, JigsawLinear(64, 48, 32, 4, ctx=ctx) as four:
+        f, s = L.first, L.second
+        p = lambda ts: [t.data_ptr() for t in ts]
+        b2 = torch.zeros(64, device="cuda")
+        call = lambda first, second, ws_bytes, bias=b2: jg.jg_token_mixing_forward(
+            first.plan, second.plan, p(f.x), None, None, 1e-5, p(f.w), p(f.b), p(s.x), bias.data_ptr() if bias is not None else None,
+            p(L.xn), p(f.y), p(s.y), L.ws.data_ptr(), ws_bytes)
+        for first, second, want in ((s, s, jg.JG_E_DTYPE),            # the first layer must be the transposed one
+                                    (f, f, jg.JG_E_DTYPE),
+                                    (f, biased, jg.JG_E_DTYPE),       # the second layer's bias is b2, per token
+                                    (f, narrow, jg.JG_E_SHAPE), (f, four, jg.JG_E_WAYS)):
+            with pytest.raises(jg.JigsawError) as e:
+                call(first, second, L.ws_bytes)
+            assert e.value.status == want
+        with pytest.raises(jg.JigsawError) as e:                      # with b2 the skip connection needs its copy of X
+            call(f, s, L.ws_bytes - 256)
+        assert e.value.status == jg.JG_E_WORKSPACE
+        L.shard(torch.zeros(64, 32, device="cuda"), None, None, torch.zeros(64, 48, device="cuda"),
+                torch.zeros(48, device="cuda"), torch.zeros(64, 48, device="cuda"), None)
+        call(f, s, L.ws_bytes - 256, None)                            # without b2 it does not
+        torch.cuda.synchronize()
