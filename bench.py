@@ -32,11 +32,13 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--ways", type=int, default=4, choices=[1, 2, 4])
-    ap.add_argument("--op", choices=["forward", "backward", "xtw", "mlp", "mixing", "encoder"], default="forward",
+    ap.add_argument("--op", choices=["forward", "backward", "xtw", "mlp", "mixing", "token_mixing", "encoder"],
+                    default="forward",
                     help="forward: Y = X W^T (the headline); backward: dX = dY W and dW = dY^T X; "
                          "xtw: the transposed layer Y = X^T W at the token-mixing size; mlp: one mixing MLP "
                          "(GELU between two layers, residual) at the channel-mixing size; mixing: the same behind a layer norm "
-                         "(the channel-mixing half of a mixing block); encoder: patch rearrangement of a "
+                         "(the channel-mixing half of a mixing block); token_mixing: the token-mixing half (norm, transposed "
+                         "layer with GELU, the layer back with the skip connection); encoder: patch rearrangement of a "
                          "field + linear layer at the 1B model's encoder size (these ignore --config)")
     ap.add_argument("--dtype", choices=["f32", "bf16", "bf16x3"], default="f32",
                     help="forward only: f32 (the headline), or a reduced-precision mode: operands rounded to bfloat16 "
@@ -383,6 +385,65 @@ def measure_mixing(cfg, ways, args):
     return out
 
 
+def measure_token_mixing(cfg, ways, args):
+    """One step = one jg_token_mixing_forward: Xn = layernorm(X), H = gelu(Xn^T W1 + b1), Y = X + W2 H^T + b2 1^T."""
+    import torch
+    from paper_2507_05753_amd import binding as jg
+    from paper_2507_05753_amd import inputs
+    from paper_2507_05753_amd.layer import JigsawTokenMixing
+    T, C, D, seed = cfg["K"], cfg["M"], cfg["N"], cfg["seed"]
+    dev = torch.device("cuda", 0)
+    gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device=dev)
+    with JigsawTokenMixing(T, C, D, ways, tail=tail_of(args)) as L:
+        L.shard(gen(seed, T, C), (gen(seed + 5, 1, C)[0] + 1.5).contiguous(), gen(seed + 6, 1, C)[0].contiguous(),
+                gen(seed + 1, T, D, inputs.W_SCALE_EXP), gen(seed + 2, 1, D)[0].contiguous(),
+                gen(seed + 3, T, D, inputs.W_SCALE_EXP), gen(seed + 4, 1, T)[0].contiguous())
+        norm = {}
+        sec, gemm_ms, gemm_n, copy_ms, comb_ms = time_forward(L, jg, args.steps, args.warmup, norm)
+        flops = L.first.query(jg.JG_Q_FLOPS_TOTAL) + L.second.query(jg.JG_Q_FLOPS_TOTAL)
+        launches = L.first.query(jg.JG_Q_GEMM_LAUNCHES) + L.second.query(jg.JG_Q_GEMM_LAUNCHES)
+        avg = gemm_ms / max(gemm_n, 1)
+        norm_avg = norm["ms"] / max(norm["launches"], 1)
+        out = dict(ms_per_step=sec * 1e3, items_per_s=T * C / sec, tflops=flops / sec / 1e12,
+                   gemm_avg_launch_ms=avg, gemm_launches_timed=gemm_n,
+                   gemm_tflops=(flops / launches) / (avg * 1e-3) / 1e12 if gemm_n else None,
+                   other_kernels_ms_per_step=copy_ms + comb_ms, workspace_bytes=L.ws_bytes,
+                   norm_avg_launch_ms=norm_avg, norm_launches_timed=norm["launches"],
+                   norm_gbps=12.0 * T * C / (norm_avg * 1e-3) / 1e9 if norm["launches"] else None)
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline_token_mixing(cfg, seconds):
+    """The token-mixing oracle timed on a bounded sample of channels (columns of X; the norm sees only those)."""
+    import oracle
+    from paper_2507_05753_amd import inputs
+    import numpy as np
+    T, C, D, seed = cfg["K"], cfg["M"], cfg["N"], cfg["seed"]
+    cores = min(oracle.host_threads(), 16)
+    W1 = inputs.matrix(seed + 1, T, D, "R", inputs.W_SCALE_EXP)
+    b1 = inputs.matrix(seed + 2, 1, D, "R")[0]
+    W2 = inputs.matrix(seed + 3, T, D, "R", inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(seed + 4, 1, T, "R")[0]
+    X = inputs.matrix(seed, T, C, "R")
+
+    def run(ch):
+        Xs = np.ascontiguousarray(X[:, :ch])
+        gamma = (inputs.matrix(seed + 5, 1, C, "R")[0][:ch] + 1.5).astype("float32")
+        beta = inputs.matrix(seed + 6, 1, C, "R")[0][:ch]
+        t0 = time.perf_counter()
+        oracle.token_mixing_block(1, Xs, gamma, beta, W1, b1, W2, b2)
+        return time.perf_counter() - t0
+
+    probe = min(C, 4)
+    rate = probe / max(run(probe), 1e-9)
+    ch = int(min(C, max(probe, rate * seconds)))
+    dt = run(ch)
+    return dict(value=ch * T / dt, unit="items/s", cores=cores, kind="oracle",
+                sample=f"channels 0..{ch - 1} of X ({T} x {ch}) through the norm and both layers ({D} hidden), {dt:.1f} s, "
+                       f"fp64 loops")
+
+
 def norm_bytes_per_element(args):
     """The layer norm reads and writes FP32; in a mixed-precision block it also writes the first layer's rounded input."""
     return {"f32": 8.0, "bf16": 10.0, "bf16x3": 12.0}[args.dtype]
@@ -586,6 +647,38 @@ def main():
         }
         if args.cpu_seconds > 0:
             line["cpu_baseline"] = cpu_baseline_xtw(xc, args.cpu_seconds)
+        print(json.dumps(line), flush=True)
+        return
+
+    if args.op == "token_mixing":
+        xc = inputs.XTW_CONFIGS["token_mixing_1b"]
+        r = measure_token_mixing(xc, args.ways, args)
+        T, C, D = xc["K"], xc["M"], xc["N"]
+        line = {
+            "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
+            "value": r["items_per_s"], "unit": "items/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"token-mixing half of a mixing block of the 1B model: Xn = layernorm(X), "
+                                   f"H = gelu(Xn^T W1 + b1), Y = X + W2 H^T + b2, X {T} x {C} [tokens, channels], "
+                                   f"hidden {D}, {args.ways}-way Jigsaw, fp32",
+                       "n_items": T * C, "ways": args.ways, "T": T, "C": C, "D": D, "seed": xc["seed"],
+                       "x_values": "R", "op": "token_mixing", "tail": args.tail},
+            "tflops": r["tflops"],
+            "roofline": {"bound": "mfma", "kernel": "jg::gemm_f32_stream (<true, true> and <false, false>)",
+                         "achieved": r["gemm_tflops"], "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": r["gemm_tflops"] / FP32_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None,
+                         "avg_launch_ms": r["gemm_avg_launch_ms"], "launches": r["gemm_launches_timed"],
+                         "traffic": None},
+            "layernorm": {"bound": "hbm", "kernel": "jg::layernorm_rows_f32", "achieved": r["norm_gbps"],
+                          "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                          "frac": r["norm_gbps"] / HBM_PEAK_GBPS if r["norm_gbps"] else None,
+                          "avg_launch_ms": r["norm_avg_launch_ms"], "launches": r["norm_launches_timed"],
+                          "bytes_per_element": 12},
+            "other_kernels_ms_per_step": r["other_kernels_ms_per_step"],
+        }
+        if args.cpu_seconds > 0:
+            line["cpu_baseline"] = cpu_baseline_token_mixing(xc, args.cpu_seconds)
         print(json.dumps(line), flush=True)
         return
 

@@ -335,3 +335,50 @@ def test_token_mixing_argument_checks(jg, ctx):
                 torch.zeros(48, device="cuda"), torch.zeros(64, 48, device="cuda"), None)
         call(f, s, L.ws_bytes - 256, None)                            # without b2 it does not
         torch.cuda.synchronize()
+
+
+@pytest.mark.timeout(600)
+def test_token_mixing_size(jg, capsys):
+    """The token-mixing block of the paper's 1-billion-parameter model at full size (16200 tokens, 4320 channels,
+    8640 hidden), in the launch configuration bench.py --op token_mixing times: sampled channels of H and sampled
+    tokens of Y element by element, everything finite."""
+    from paper_2507_05753_amd.layer import JigsawTokenMixing
+    cfg = inputs.XTW_CONFIGS["token_mixing_1b"]
+    T, C, D, seed = cfg["K"], cfg["M"], cfg["N"], cfg["seed"]
+    Xd = inputs.matrix_torch(seed, T, C, "R", device="cuda") + 0.25
+    W1d = inputs.matrix_torch(seed + 1, T, D, "R", inputs.W_SCALE_EXP, device="cuda")
+    W2d = inputs.matrix_torch(seed + 3, T, D, "R", inputs.W_SCALE_EXP, device="cuda")
+    b1 = inputs.matrix(seed + 2, 1, D, "R")[0]
+    b2 = inputs.matrix(seed + 4, 1, T, "R")[0]
+    gamma, beta = affine(seed + 5, C)
+    W1, W2 = W1d.cpu().numpy(), W2d.cpu().numpy()
+    k = inputs.keys(7200, np.arange(40, dtype=np.uint64))
+    chans = np.unique(np.concatenate([(k[:16] % np.uint64(C)).astype(np.int64), [0, C // 2 - 1, C // 2, C - 1]]))
+    toks = np.unique(np.concatenate([(k[16:] % np.uint64(T)).astype(np.int64), [0, T // 2 - 1, T // 2, T - 1]]))
+    ci, ti = torch.from_numpy(chans).cuda(), torch.from_numpy(toks).cuda()
+    note(capsys, f"token mixing block: {chans.size} sampled channels of H, {toks.size} sampled tokens of Y")
+    for ways in (1, 2, 4):
+        with JigsawTokenMixing(T, C, D, ways) as L:
+            L.shard(Xd, dev(gamma), dev(beta), W1d, dev(b1), W2d, dev(b2))
+            L.forward()
+            Xn, H, Y = L.gather_xn(), L.gather_h(), L.gather()
+            torch.cuda.synchronize()
+            assert torch.isfinite(Y).all() and torch.isfinite(H).all()
+            Xn_t = Xn[ti].cpu().numpy()
+            Xn_c = Xn[:, ci].cpu().numpy()                       # the sampled channels' columns of Xn: T x n
+            H_c = H[ci].cpu().numpy()                            # their rows of H: n x D
+            Hh = H.cpu().numpy()
+            Y_t, X_t = Y[ti].cpu().numpy(), Xd[ti].cpu().numpy()
+        want = oracle.layernorm(X_t, gamma, beta, oracle.ln_groups(ways))      # the norm on the sampled tokens
+        assert np.all(np.abs(Xn_t.astype(np.float64) - want) <= HALF_ULP * np.abs(want) * (1 + 1e-6) + 1e-10)
+        # first layer: rows of H for the sampled channels, from the Xn the GPU stored
+        S1 = oracle.magnitude_xtw(Xn_c, W1, b1)
+        eh = np.abs(H_c.astype(np.float64) - oracle.gelu(oracle.linear_xtw(Xn_c, W1, b1)))
+        assert np.all(eh <= TOL_H * S1), f"ways={ways} H: max err/S1 = {(eh / S1).max():.3e}"
+        # second layer: sampled tokens of Y from the H the GPU stored
+        W2_t = np.ascontiguousarray(W2[toks])
+        ref = X_t.astype(np.float64) + oracle.linear(W2_t, Hh) + b2[toks].astype(np.float64)[:, None]
+        SY = np.abs(X_t.astype(np.float64)) + oracle.magnitude(W2_t, Hh) + np.abs(b2[toks]).astype(np.float64)[:, None]
+        ey = np.abs(Y_t.astype(np.float64) - ref)
+        assert np.all(ey <= TOL * SY), f"ways={ways} Y: max err/S = {(ey / SY).max():.3e}"
+        note(capsys, f"token mixing block ways={ways}: H max err/S1 {(eh / S1).max():.2e}, Y max err/S {(ey / SY).max():.2e}")
