@@ -376,3 +376,30 @@ def test_patch_calls_check_sizes_against_the_plan():
     assert lib.jg_shard_patches(t, 256, 2, 8, 16, 4, pp) == jg.JG_E_DTYPE
     for h in (p, q, t):
         jg.jg_plan_destroy(h)
+
+
+def test_token_mixing_entry_point_checks_that_the_plans_chain():
+    lib = jg.raw()
+    arr = (ctypes.c_void_p * 2)(256, 512)
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    call = lambda a, b: lib.jg_token_mixing_forward(a, b, pp, None, None, 1e-5, pp, pp, pp, None, pp, pp, pp, 256, 1 << 20)
+    T, C, D = 64, 32, 48
+    first = jg.jg_plan_create(None, C, T, D, 2, True, op=jg.JG_OP_XTW)      # K = T tokens, M = C channels, N = D hidden
+    assert call(None, first) == jg.JG_E_NULL
+    for (M, K, N), ways, bias, want in (((T, D, C), 2, False, jg.JG_E_NULL),          # chains, but no context
+                                        ((T, D, C), 2, True, jg.JG_E_DTYPE),          # the second bias goes with the token
+                                        ((T, D, C), 4, False, jg.JG_E_WAYS),
+                                        ((T, D, C + 2), 2, False, jg.JG_E_SHAPE),
+                                        ((T + 2, D, C), 2, False, jg.JG_E_SHAPE),
+                                        ((T, D + 2, C), 2, False, jg.JG_E_SHAPE)):
+        second = jg.jg_plan_create(None, M, K, N, ways, bias)
+        assert call(first, second) == want
+        jg.jg_plan_destroy(second)
+    plain = jg.jg_plan_create(None, T, D, C, 2, False)
+    assert call(plain, plain) == jg.JG_E_DTYPE                                          # the first layer is the transposed one
+    assert call(first, first) == jg.JG_E_DTYPE
+    half = jg.jg_plan_create(None, C, T, D, 2, True, op=jg.JG_OP_XTW)
+    q = jg.jg_plan_query
+    assert q(first, jg.JG_Q_X_F32_SHARDS_BYTES) == 2 * ((4 * q(first, jg.JG_Q_X_ROWS) * q(first, jg.JG_Q_X_COLS) + 255) // 256 * 256)
+    for p in (plain, half, first):
+        jg.jg_plan_destroy(p)
