@@ -312,3 +312,46 @@ class JigsawTokenMixing:
 
     def __exit__(self, *exc):
         self.close()
+
+
+class JigsawMixerBlock:
+    """One mixing block (Sec. 3): the token-mixing half followed by the channel-mixing half, each with its layer norm
+    and skip connection, on Jigsaw shards.  X and Y are (T, C).  The token half leaves its output partitioned like
+    X, which is how the channel half reads its input: the second half works on the first one's output shards in
+    place."""
+
+    def __init__(self, T: int, C: int, Dt: int, Dc: int, ways: int, device: int = 0, ctx=None,
+                 tail: int = jg.JG_TAIL_SPLIT, eps: float = 1e-5):
+        self.token = JigsawTokenMixing(T, C, Dt, ways, device=device, ctx=ctx, tail=tail, eps=eps)
+        self.channel = JigsawMixing(T, C, Dc, ways, device=device, ctx=self.token.ctx, tail=tail, eps=eps)
+        self.channel.xin = self.token.second.y
+        self.channel.first.x = self.token.second.y
+        self.T, self.C, self.ways = T, C, ways
+        self.ctx = self.token.ctx
+
+    def shard(self, X=None, token=None, channel=None):
+        """token: dict(gamma, beta, W1, b1, W2, b2) of the token half; channel: the same names for the channel half."""
+        if X is not None or token:
+            self.token.shard(X, **(token or {}))
+        if channel:
+            self.channel.shard(None, **channel)
+
+    def forward(self):
+        self.token.forward()
+        self.channel.forward()
+
+    def gather_token_output(self):
+        return self.token.gather()
+
+    def gather(self):
+        return self.channel.gather()
+
+    def close(self):
+        self.channel.close()
+        self.token.close()
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()

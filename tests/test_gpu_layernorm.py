@@ -382,3 +382,25 @@ def test_token_mixing_size(jg, capsys):
         ey = np.abs(Y_t.astype(np.float64) - ref)
         assert np.all(ey <= TOL * SY), f"ways={ways} Y: max err/S = {(ey / SY).max():.3e}"
         note(capsys, f"token mixing block ways={ways}: H max err/S1 {(eh / S1).max():.2e}, Y max err/S {(ey / SY).max():.2e}")
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+def test_whole_mixing_block(jg, ctx, ways):
+    """Token-mixing half, then channel-mixing half on its output shards in place (Sec. 3): each half against the
+    oracle applied to what the GPU fed it."""
+    from paper_2507_05753_amd.layer import JigsawMixerBlock
+    T, C, Dt, Dc = 258, 264, 136, 200
+    X, g1, be1, W1, b1, W2, b2 = token_operands(97, T, C, Dt)
+    _, g2, be2, V1, c1, V2, c2 = block_operands(98, T, C, Dc)
+    with JigsawMixerBlock(T, C, Dt, Dc, ways, ctx=ctx) as L:
+        L.shard(dev(X), token=dict(gamma=dev(g1), beta=dev(be1), W1=dev(W1), b1=dev(b1), W2=dev(W2), b2=dev(b2)),
+                channel=dict(gamma=dev(g2), beta=dev(be2), W1=dev(V1), b1=dev(c1), W2=dev(V2), b2=dev(c2)))
+        L.forward()
+        Xn, H, U = L.token.gather_xn().cpu().numpy(), L.token.gather_h().cpu().numpy(), L.gather_token_output().cpu().numpy()
+        Un, G, Y = L.channel.gather_xn().cpu().numpy(), L.channel.gather_h().cpu().numpy(), L.gather().cpu().numpy()
+    check_token_block(X, g1, be1, W1, b1, W2, b2, ways, Xn, H, U)
+    check_block(oracle.mixing_block(ways, U, g2, be2, V1, c1, V2, c2), Un, G, Y)
+    # end to end, loosely: both halves by the oracle
+    r1 = oracle.token_mixing_block(ways, X, g1, be1, W1, b1, W2, b2)
+    r2 = oracle.mixing_block(ways, r1["Y"].astype(np.float32), g2, be2, V1, c1, V2, c2)
+    assert np.all(np.abs(Y - r2["Y"]) <= 1e-4 * (r2["SY"] + r2["PY"]))
