@@ -189,6 +189,18 @@ def backward_magnitude(X, W, dY, nthreads: int | None = None):
     return backward(X, W, dY, nthreads, absolute=True)
 
 
+def bias_backward(dY, absolute: bool = False) -> np.ndarray:
+    """db64 = the gradient of the bias of Y = X W^T + 1 b^T for an incoming gradient dY: its column sums
+    db[j] = sum_i dY[i][j], in double, rows ascending (sums of absolute values if ``absolute``)."""
+    G = np.ascontiguousarray(dY, dtype=np.float32).astype(np.float64)
+    if absolute:
+        G = np.abs(G)
+    out = np.zeros(G.shape[1], dtype=np.float64)
+    for i in range(G.shape[0]):
+        out += G[i]
+    return out
+
+
 def jigsaw_backward(ways: int, X, W, dY, nthreads: int | None = None):
     """(dX64, dW64) obtained block by block with dX partitioned like X and dW like W."""
     X, xp = _f32(X)

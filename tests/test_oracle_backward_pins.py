@@ -123,3 +123,32 @@ def test_freivalds_backward_is_the_projected_gradient():
     SX, SW = oracle.backward_magnitude(X, W, dY)
     assert np.all(np.abs(dXv - dX @ V) <= 1e-13 * bX) and np.all(np.abs(dWv - dW @ V) <= 1e-13 * bW)
     assert np.allclose(bX, SX @ np.abs(V), rtol=1e-12) and np.allclose(bW, SW @ np.abs(V), rtol=1e-12)
+
+
+# ---------------------------------------------------------------------------------------------
+# the bias gradient: db[j] = sum_i dY[i][j]
+# ---------------------------------------------------------------------------------------------
+def test_bias_gradient_is_the_adjoint_of_the_bias_term():
+    """b enters the forward as + 1 b^T, so <dY, f(X, W, b + e) - f(X, W, b)> = <db, e> for any e: tied to the
+    (already pinned) forward oracle, on lattice values where every step is exact."""
+    M, K, N = 7, 6, 5
+    X, W, b = inputs.layer_inputs(71, M, K, N, "L", bias=True)
+    dY = inputs.matrix(72, M, N, "L")
+    e = inputs.matrix(73, 1, N, "L")[0]
+    lhs = (dY.astype(np.float64) * (oracle.linear(X, W, b + e) - oracle.linear(X, W, b))).sum()
+    assert lhs == (oracle.bias_backward(dY) * e.astype(np.float64)).sum()
+
+
+def test_bias_gradient_closed_forms_and_brute_force():
+    assert np.array_equal(oracle.bias_backward(np.ones((9, 4), np.float32)), np.full(4, 9.0))
+    G = np.arange(12, dtype=np.float32).reshape(4, 3)            # columns 0 3 6 9 / 1 4 7 10 / 2 5 8 11
+    assert np.array_equal(oracle.bias_backward(G), np.array([18.0, 22.0, 26.0]))
+    assert np.array_equal(oracle.bias_backward(G.T.copy()), np.array([3.0, 12.0, 21.0, 30.0]))    # not the row sums of G
+    R = inputs.matrix(74, 50, 7, "R")
+    want = [sum(float(R[i, j]) for i in range(50)) for j in range(7)]
+    assert np.allclose(oracle.bias_backward(R), want, rtol=0, atol=1e-13)
+    assert np.array_equal(oracle.bias_backward(R, absolute=True), oracle.bias_backward(np.abs(R)))
+    assert oracle.bias_backward(np.zeros((0, 3), np.float32)).tolist() == [0.0, 0.0, 0.0]
+    # cancellation that FP32 accumulation would lose: 2^24, 1, -2^24 sums to 1
+    C = np.array([[2.0 ** 24], [1.0], [-(2.0 ** 24)]], dtype=np.float32)
+    assert oracle.bias_backward(C)[0] == 1.0
