@@ -165,7 +165,8 @@ typedef enum jg_kernel {         /* kernel classes for jg_profile_read */
     JG_KERNEL_GEMM_DW = 6,       /* backward dW = dY^T X products                        */
     JG_KERNEL_JOIN = 7,          /* adds the runs of split tail tiles (JG_TAIL_SPLIT)    */
     JG_KERNEL_NORM = 8,          /* layer norm over a rank's channels                    */
-    JG_KERNEL_COUNT = 9
+    JG_KERNEL_REDUCE = 9,        /* column sums of dY (bias gradient)                    */
+    JG_KERNEL_COUNT = 10
 } jg_kernel;
 
 /* init.  Creates a context bound to HIP device `device` and to `hip_stream`
@@ -367,12 +368,22 @@ int jg_token_mixing_forward(const jg_plan* first, const jg_plan* second, const f
  * x_sh, w_sh, dy_sh: host arrays of `ways` device pointers to the X, W and dY shards (shapes of
  * X_r, W_r, Y_r); dx_sh, dw_sh: the same for the outputs (shapes of X_r, W_r).  `workspace`:
  * 256-byte-aligned device buffer of at least JG_Q_BACKWARD_WORKSPACE_BYTES bytes (may be NULL when
- * that is 0).  The bias gradient is not computed.  The plan's combine / weights options do not apply.
+ * that is 0).  The bias gradient is jg_bias_backward's.  The plan's combine / weights options do not apply.
  * JG_OP_XWT plans only: a JG_OP_XTW plan returns JG_E_DTYPE.
  * Errors: JG_E_NULL, JG_E_DTYPE (op), JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
 int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
                        const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh,
                        void* workspace, size_t workspace_bytes);
+
+/* run (backward, bias).  The gradient of the bias for an incoming gradient dY (Sec. 4.1: the backward pass; the
+ * bias enters the layer as + 1 b^T, whose adjoint is the column sum):  db[j] = sum_i dY[i][j].
+ * dy_sh: the dY shards (shaped and partitioned like Y_r, as for jg_linear_backward); db_sh: `ways` device buffers
+ * of JG_Q_B_LEN floats, partitioned like the bias (4-way: the slice of a column half is summed over both row
+ * halves and written to both ranks of that column).  Sums are accumulated in double in a fixed order and rounded
+ * once: the same bits on every run.  Any plan (op, dtype): only the Y partition matters.  Needs no workspace;
+ * asynchronous on the context's stream.
+ * Errors: JG_E_NULL, JG_E_ALIGN, JG_E_HIP. */
+int jg_bias_backward(const jg_plan* plan, const float* const* dy_sh, float* const* db_sh);
 
 /* query (data).  Inverse of jg_shard for Y: writes the M x N global result (device,
  * leading dimension ld >= N) from the per-rank Y shards.  Bit-exact.

@@ -14,6 +14,7 @@
 #include "stream_kernels.hpp"
 #include "patch_kernels.hpp"
 #include "norm_kernels.hpp"
+#include "reduce_kernels.hpp"
 #include "gemm_bf16.hpp"
 #include "cvt_kernels.hpp"
 
@@ -990,6 +991,42 @@ static int layernorm_impl(const jg_plan* plan, const float* const* x_sh, const f
     }
     ScopedTimer t(c, JG_KERNEL_NORM);
     return HIP_OK(jg::launch_norm_group(g, c->stream)) ? JG_OK : JG_E_HIP;
+}
+
+int jg_bias_backward(const jg_plan* plan, const float* const* dy_sh, float* const* db_sh)
+{
+    if (!plan || !plan->ctx) return JG_E_NULL;
+    const jg_linear_desc& d = plan->d;
+    if (int rc = check_ptr_array(dy_sh, d.ways)) return rc;
+    if (int rc = check_ptr_array(db_sh, d.ways)) return rc;
+    for (int r = 0; r < d.ways; ++r)
+        if (!aligned(dy_sh[r], 4) || !aligned(db_sh[r], 4)) return JG_E_ALIGN;
+    jg_ctx* c = plan->ctx;
+    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    jg::ColSumGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.rows = (int)plan->yr;
+    g.cols = (int)plan->yc;
+    if (d.ways == 4) {
+        // column half j of dY is held as the two row blocks of ranks j and 2 + j, and both hold its bias slice
+        g.nout = 2;
+        for (int j = 0; j < 2; ++j) {
+            g.o[j].nsrc = g.o[j].ndst = 2;
+            g.o[j].src[0] = dy_sh[j];
+            g.o[j].src[1] = dy_sh[2 + j];
+            g.o[j].dst[0] = db_sh[j];
+            g.o[j].dst[1] = db_sh[2 + j];
+        }
+    } else {
+        g.nout = d.ways;
+        for (int r = 0; r < d.ways; ++r) {
+            g.o[r].nsrc = g.o[r].ndst = 1;
+            g.o[r].src[0] = dy_sh[r];
+            g.o[r].dst[0] = db_sh[r];
+        }
+    }
+    ScopedTimer t(c, JG_KERNEL_REDUCE);
+    return HIP_OK(jg::launch_colsum_group(g, c->stream)) ? JG_OK : JG_E_HIP;
 }
 
 int jg_layernorm_forward(const jg_plan* plan, const float* const* x_sh, const float* gamma, const float* beta,

@@ -121,7 +121,9 @@ class JigsawLinear:
             self.dy = [torch.empty_like(t) for t in self.y]
             self.dx = [torch.empty_like(t) for t in self.x]
             self.dw = [torch.empty_like(t) for t in self.w]
-            self.bw_ws_bytes = self.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES)
+            # (a transposed or reduced-precision plan has no dX / dW pass; its dY shards still serve the bias gradient)
+            has_backward = self.op == jg.JG_OP_XWT and self.dtype == jg.JG_F32
+            self.bw_ws_bytes = self.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES) if has_backward else 0
             self.bw_ws = torch.empty((max(self.bw_ws_bytes, 1),), dtype=torch.uint8, device=self.dev)
 
     def shard_dy(self, dY):
@@ -135,6 +137,15 @@ class JigsawLinear:
                               [t.data_ptr() for t in self.dy], [t.data_ptr() for t in self.dx],
                               [t.data_ptr() for t in self.dw],
                               self.bw_ws.data_ptr() if self.bw_ws_bytes else None, self.bw_ws_bytes)
+
+    def bias_backward(self):
+        """db shards (shaped like the bias shards) = column sums of the dY shards (jg_bias_backward)."""
+        self.alloc_backward()
+        if getattr(self, "db", None) is None:
+            self.db = [torch.empty((self.query(jg.JG_Q_B_LEN, r),), dtype=torch.float32, device=self.dev)
+                       for r in range(self.ways)]
+        jg.jg_bias_backward(self.plan, [t.data_ptr() for t in self.dy], [t.data_ptr() for t in self.db])
+        return self.db
 
     def gather_dx(self):
         out = torch.empty((self.M, self.K), dtype=torch.float32, device=self.dev)

@@ -164,3 +164,68 @@ def test_backward_leaves_its_inputs_alone_and_is_repeatable(jg, ctx):
         torch.cuda.synchronize()
         assert all(torch.equal(p, q) for p, q in zip(before, L.x + L.w + L.dy))
         assert torch.equal(a[0], c[0]) and torch.equal(a[1], c[1])
+
+
+# ---------------------------------------------------------------------------------------------
+# the bias gradient: column sums of dY
+# ---------------------------------------------------------------------------------------------
+def run_bias_backward(jg, ctx, dY, ways, op=None):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    M, N = dY.shape
+    K = 8
+    kw = {} if op is None else dict(op=op)
+    with JigsawLinear(M, K, N, ways, bias=True, ctx=ctx, **kw) as L:
+        L.shard_dy(dev(dY))
+        db = L.bias_backward()
+        for t in db:
+            t.fill_(float("nan"))
+        db = L.bias_backward()
+        first = [t.cpu().numpy().copy() for t in db]
+        L.bias_backward()
+        torch.cuda.synchronize()
+        assert all(np.array_equal(a, t.cpu().numpy()) for a, t in zip(first, L.db))      # the same bits again
+        return first
+
+
+def check_bias(db_shards, dY, ways):
+    want, S = oracle.bias_backward(dY), oracle.bias_backward(dY, absolute=True)
+    N = dY.shape[1]
+    for r, got in enumerate(db_shards):
+        sl = slice(0, N) if ways == 1 else slice((r % 2) * (N // 2), (r % 2 + 1) * (N // 2))
+        err = np.abs(got.astype(np.float64) - want[sl])
+        # accumulated in double and rounded once
+        assert np.all(err <= 2.0 ** -24 * np.abs(want[sl]) * (1 + 1e-6) + 1e-12 * S[sl] + 1e-45), \
+            f"rank {r}: max err/S = {(err / np.maximum(S[sl], 1e-300)).max():.3e}"
+    if ways == 4:      # the slice of a column half is replicated on the two ranks of that column
+        assert np.array_equal(db_shards[0], db_shards[2]) and np.array_equal(db_shards[1], db_shards[3])
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,N", [(2, 2), (100, 100), (130, 258), (258, 136), (2200, 72), (300, 1032), (7001 * 2, 66)])
+def test_bias_gradient_matches_oracle(jg, ctx, ways, M, N):
+    dY = inputs.matrix(47, M, N, "R")
+    check_bias(run_bias_backward(jg, ctx, dY, ways), dY, ways)
+    # same-sign data, where FP32 accumulation over the rows would be outside the bar
+    dP = np.abs(dY) + np.float32(0.5)
+    check_bias(run_bias_backward(jg, ctx, dP, ways), dP, ways)
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+def test_bias_gradient_on_lattice_data_and_transposed_plans(jg, ctx, ways):
+    M, N = 258, 136
+    dY = inputs.matrix(48, M, N, "L")
+    want = oracle.bias_backward(dY)
+    for op in (None, jg.JG_OP_XTW):                 # only the Y partition matters, which both ops share
+        for r, got in enumerate(run_bias_backward(jg, ctx, dY, ways, op)):
+            sl = slice(0, N) if ways == 1 else slice((r % 2) * (N // 2), (r % 2 + 1) * (N // 2))
+            assert np.array_equal(got.astype(np.float64), want[sl])
+
+
+@pytest.mark.timeout(300)
+def test_bias_gradient_at_config_3(jg, ctx):
+    cfg = inputs.CONFIGS[3]
+    M, N = cfg["M"], cfg["N"]
+    dYd = inputs.matrix_torch(4700, M, N, "R", device="cuda")
+    dY = dYd.cpu().numpy()
+    for ways in (1, 4):
+        check_bias(run_bias_backward(jg, ctx, dY, ways), dY, ways)
