@@ -233,6 +233,20 @@ def measure_backward(cfg, ways, args, X, W):
                        tflops=half * args.steps / (dw_ms * 1e-3) / 1e12),
         }
         ws = L.bw_ws_bytes
+        # the bias gradient (column sums of dY), timed on its own: it is not part of jg_linear_backward
+        for _ in range(args.warmup):
+            L.bias_backward()
+        torch.cuda.synchronize()
+        jg.jg_profile_read(L.ctx, jg.JG_KERNEL_REDUCE)
+        jg.jg_profile(L.ctx, True)
+        for _ in range(args.steps):
+            L.bias_backward()
+        jg.jg_profile(L.ctx, False)
+        db_ms, db_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_REDUCE)
+        db_avg = db_ms / max(db_n, 1)
+        kernels["db"] = dict(kernel="jg::colsum_f32<true>", avg_launch_ms=db_avg, launches=db_n,
+                             gbps=4.0 * M * N / (db_avg * 1e-3) / 1e9 if db_n else None,
+                             frac_of_hbm_peak=4.0 * M * N / (db_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS if db_n else None)
     torch.cuda.empty_cache()
     return dict(ms_per_step=sec * 1e3, items_per_s=M * K / sec, tflops=flops / sec / 1e12, kernels=kernels,
                 workspace_bytes=ws)

@@ -403,3 +403,13 @@ def test_token_mixing_entry_point_checks_that_the_plans_chain():
     assert q(first, jg.JG_Q_X_F32_SHARDS_BYTES) == 2 * ((4 * q(first, jg.JG_Q_X_ROWS) * q(first, jg.JG_Q_X_COLS) + 255) // 256 * 256)
     for p in (plain, half, first):
         jg.jg_plan_destroy(p)
+
+
+def test_bias_backward_checks_its_arguments():
+    lib = jg.raw()
+    arr = (ctypes.c_void_p * 2)(256, 512)
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    assert lib.jg_bias_backward(None, pp, pp) == jg.JG_E_NULL
+    a = jg.jg_plan_create(None, 64, 32, 48, 2, True)
+    assert lib.jg_bias_backward(a, pp, pp) == jg.JG_E_NULL          # a plan without a context
+    jg.jg_plan_destroy(a)
