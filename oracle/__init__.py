@@ -371,6 +371,42 @@ def layernorm(X, gamma=None, beta=None, groups: int = 1, eps: float = LN_EPS, nt
     return (Y, S) if magnitude else Y
 
 
+def layernorm_backward(X, gamma, dY, groups: int = 1, eps: float = LN_EPS, magnitude: bool = False):
+    """Gradients of Y = layernorm(X, gamma, beta, groups, eps) for an incoming gradient dY, in double.  Per token and
+    channel block of n channels, with xhat = (x - mean) / sqrt(var + eps) and g = dY * gamma:
+        dX     = (g - mean_c(g) - xhat * mean_c(g * xhat)) / sqrt(var + eps)
+        dgamma = sum over tokens of dY * xhat,     dbeta = sum over tokens of dY
+    (the derivative of the definition: mean and variance depend on every channel of the block).  Returns
+    (dX, dgamma, dbeta); with magnitude=True also the sums of absolute values of the terms of each
+    (SX = (|g| + mean|g| + |xhat| mean|g xhat|) rstd, Sg = sum |dY xhat|, Sb = sum |dY|)."""
+    X = np.ascontiguousarray(X, dtype=np.float32).astype(np.float64)
+    G = np.ascontiguousarray(dY, dtype=np.float32).astype(np.float64)
+    M, C = X.shape
+    if groups < 1 or C % groups:
+        raise RuntimeError(f"{C} channels do not split into {groups} blocks")
+    if not eps >= 0:
+        raise RuntimeError("eps must be >= 0")
+    ga = np.ones(C) if gamma is None else np.ascontiguousarray(gamma, dtype=np.float32).astype(np.float64)
+    n = C // groups
+    dX = np.empty((M, C)); SX = np.empty((M, C))
+    xhat = np.empty((M, C))
+    for b in range(groups):
+        sl = slice(b * n, (b + 1) * n)
+        x = X[:, sl]
+        mu = x.mean(axis=1, keepdims=True)
+        rstd = 1.0 / np.sqrt(((x - mu) ** 2).mean(axis=1, keepdims=True) + eps)
+        xh = (x - mu) * rstd
+        g = G[:, sl] * ga[sl]
+        dX[:, sl] = (g - g.mean(axis=1, keepdims=True) - xh * (g * xh).mean(axis=1, keepdims=True)) * rstd
+        SX[:, sl] = (np.abs(g) + np.abs(g).mean(axis=1, keepdims=True)
+                     + np.abs(xh) * np.abs(g * xh).mean(axis=1, keepdims=True)) * rstd
+        xhat[:, sl] = xh
+    dgamma, dbeta = (G * xhat).sum(axis=0), G.sum(axis=0)
+    if magnitude:
+        return dX, dgamma, dbeta, SX, np.abs(G * xhat).sum(axis=0), np.abs(G).sum(axis=0)
+    return dX, dgamma, dbeta
+
+
 def mixing_block(ways: int, X, gamma, beta, W1, b1, W2, b2, eps: float = LN_EPS):
     """Channel-mixing half of a mixing block (Sec. 3: layer norm before the MLP, skip connection around it):
     Xn = layernorm(X), H = gelu(Xn W1^T + b1), Y = X + H W2^T + b2, with Xn handed on in FP32 as the

@@ -269,3 +269,69 @@ def test_token_mixing_mixes_tokens_not_channels():
     # zero second layer: identity plus the per-token bias
     z = oracle.token_mixing_block(2, X, gamma, beta, W1, b1, np.zeros_like(W2), b2)
     assert np.array_equal(z["Y"], X.astype(np.float64) + b2.astype(np.float64)[:, None])
+
+
+# ---------------------------------------------------------------------------------------------
+# the layer norm's gradients
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("groups", [1, 2])
+def test_layernorm_backward_against_differences_of_the_forward(groups):
+    """<dY, LN(X + h E) - LN(X - h E)> / 2h -> <dX, E>.  X on a lattice and h = 2^-10, so that X +- h E is exact in
+    FP32 (the forward oracle takes FP32 input); the central difference is then accurate to O(h^2)."""
+    M, C = 5, 12
+    X, gamma, beta = data(30, M, C, "L")
+    dY = inputs.matrix(31, M, C, "R")
+    dX, dg, db = oracle.layernorm_backward(X, gamma, dY, groups)
+    h = 2.0 ** -10
+    rng = np.random.default_rng(1)
+    for _ in range(6):
+        E = rng.integers(-1, 2, (M, C)).astype(np.float32)
+        fp = oracle.layernorm((X + np.float32(h) * E).astype(np.float32), gamma, beta, groups)
+        fm = oracle.layernorm((X - np.float32(h) * E).astype(np.float32), gamma, beta, groups)
+        lhs = (dY.astype(np.float64) * (fp - fm)).sum() / (2 * h)
+        rhs = (dX * E).sum()
+        assert abs(lhs - rhs) <= 2e-5 * (np.abs(dX).sum() + 1)
+    # gamma and beta enter linearly: the differences are exact
+    for c in (0, 5, C - 1):
+        e = np.zeros(C, dtype=np.float32)
+        e[c] = 1.0
+        dgc = (dY.astype(np.float64) * (oracle.layernorm(X, gamma + e, beta, groups) - oracle.layernorm(X, gamma, beta, groups))).sum()
+        dbc = (dY.astype(np.float64) * (oracle.layernorm(X, gamma, beta + e, groups) - oracle.layernorm(X, gamma, beta, groups))).sum()
+        assert abs(dgc - dg[c]) <= 1e-12 * (abs(dg[c]) + 1) and abs(dbc - db[c]) <= 1e-12 * (abs(db[c]) + 1)
+
+
+@pytest.mark.parametrize("groups", [1, 2])
+def test_layernorm_backward_against_the_library_in_double(groups):
+    M, C = 7, 10
+    X, gamma, beta = data(32, M, C, shift=0.3)
+    dY = inputs.matrix(33, M, C, "R")
+    n = C // groups
+    Xt = torch.from_numpy(X).double().requires_grad_(True)
+    gt = torch.from_numpy(gamma).double().requires_grad_(True)
+    bt = torch.from_numpy(beta).double().requires_grad_(True)
+    out = torch.cat([torch.nn.functional.layer_norm(Xt[:, b * n:(b + 1) * n], (n,), gt[b * n:(b + 1) * n],
+                                                    bt[b * n:(b + 1) * n], EPS) for b in range(groups)], dim=1)
+    out.backward(torch.from_numpy(dY).double())
+    dX, dg, db, SX, Sg, Sb = oracle.layernorm_backward(X, gamma, dY, groups, magnitude=True)
+    assert np.all(np.abs(dX - Xt.grad.numpy()) <= 1e-12 * SX)
+    assert np.all(np.abs(dg - gt.grad.numpy()) <= 1e-12 * Sg) and np.all(np.abs(db - bt.grad.numpy()) <= 1e-12 * Sb)
+
+
+def test_layernorm_backward_invariants():
+    M, C = 6, 16
+    X, gamma, beta = data(34, M, C, shift=-0.4)
+    dY = inputs.matrix(35, M, C, "R")
+    dX, dg, db = oracle.layernorm_backward(X, gamma, dY, 2)
+    # the output does not change when a constant is added to a block's channels: dX sums to zero per block
+    assert np.all(np.abs(dX[:, :8].sum(axis=1)) <= 1e-12) and np.all(np.abs(dX[:, 8:].sum(axis=1)) <= 1e-12)
+    # a gradient along gamma-scaled constants is annihilated: dY = c / gamma per row gives g = const, xhat-free
+    dZ = (np.ones((M, C)) / gamma.astype(np.float64)).astype(np.float32)
+    dX0, _, _ = oracle.layernorm_backward(X, gamma, dZ, 1)
+    assert np.all(np.abs(dX0) <= 1e-5 * np.abs(dX).max())
+    # dbeta is the column sum, dgamma with gamma = None is that of gamma = 1
+    assert np.allclose(db, oracle.bias_backward(dY), rtol=0, atol=1e-13)
+    a = oracle.layernorm_backward(X, None, dY, 1)
+    b = oracle.layernorm_backward(X, np.ones(C, np.float32), dY, 1)
+    assert all(np.array_equal(u, v) for u, v in zip(a, b))
+    with pytest.raises(RuntimeError):
+        oracle.layernorm_backward(X[:, :9], None, dY[:, :9], 2)
