@@ -150,9 +150,10 @@ typedef enum jg_query {
     JG_Q_CHAIN_WORKSPACE_BYTES = 21,    /* the plan's share of the workspace of jg_mlp_forward /
                                            jg_mixing_forward: JG_Q_WORKSPACE_BYTES, plus (reduced
                                            precision) room for its input in bfloat16 (rank ignored) */
-    JG_Q_X_F32_SHARDS_BYTES = 22        /* `ways` FP32 shards shaped like X_r, each rounded up to 256
+    JG_Q_X_F32_SHARDS_BYTES = 22,       /* `ways` FP32 shards shaped like X_r, each rounded up to 256
                                            bytes: what jg_token_mixing_forward needs for its skip
                                            connection when b2 is given (rank ignored)               */
+    JG_Q_NORM_BACKWARD_WORKSPACE_BYTES = 23   /* device bytes jg_layernorm_backward needs (rank ignored) */
 } jg_query;
 
 typedef enum jg_kernel {         /* kernel classes for jg_profile_read */
@@ -374,6 +375,22 @@ int jg_token_mixing_forward(const jg_plan* first, const jg_plan* second, const f
 int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
                        const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh,
                        void* workspace, size_t workspace_bytes);
+
+/* run (backward, layer norm).  Gradients of jg_layernorm_forward's output for an incoming gradient dY (shaped and
+ * partitioned like X_r), per row of X_r over the channels the rank holds, with xhat = (x - mu) / sqrt(var + eps)
+ * and g = dY * gamma:
+ *     dX = (g - mean(g) - xhat * mean(g * xhat)) / sqrt(var + eps),
+ *     dgamma[c] = sum over tokens of dY * xhat,     dbeta[c] = sum over tokens of dY.
+ * x_sh: the forward's input shards; gamma as in the forward (may be NULL: 1); dy_sh, dx_sh: `ways` device buffers
+ * shaped like X_r (no overlaps: the sums over tokens read x_sh and dy_sh after dx_sh is written); dgamma, dbeta: device vectors over ALL channels of X
+ * (every channel block is summed over the ranks that hold it and written once), either may be NULL.  Evaluated in
+ * double and rounded once; the column sums in a fixed order (the same bits on every run).  workspace: 256-byte
+ * aligned, JG_Q_NORM_BACKWARD_WORKSPACE_BYTES (mean and 1 / sqrt(var + eps) of every row).  Any plan (op, dtype):
+ * only the X partition matters.
+ * Errors: JG_E_NULL, JG_E_DTYPE (eps negative or NaN), JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
+int jg_layernorm_backward(const jg_plan* plan, const float* const* x_sh, const float* gamma, double eps,
+                          const float* const* dy_sh, float* const* dx_sh, float* dgamma, float* dbeta, void* workspace,
+                          size_t workspace_bytes);
 
 /* run (backward, bias).  The gradient of the bias for an incoming gradient dY (Sec. 4.1: the backward pass; the
  * bias enters the layer as + 1 b^T, whose adjoint is the column sum):  db[j] = sum_i dY[i][j].

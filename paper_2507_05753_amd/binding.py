@@ -41,7 +41,7 @@ JG_T_X, JG_T_W, JG_T_B, JG_T_Y, JG_T_X_F32 = 0, 1, 2, 3, 4
  JG_Q_Y_ROWS, JG_Q_Y_COLS, JG_Q_B_LEN, JG_Q_RESIDENT_BYTES_RANK, JG_Q_GEMM_LAUNCHES,
  JG_Q_BACKWARD_WORKSPACE_BYTES, JG_Q_BACKWARD_FLOPS_TOTAL, JG_Q_BACKWARD_GEMM_LAUNCHES,
  JG_Q_TAIL_SCRATCH_BYTES, JG_Q_BACKWARD_TAIL_SCRATCH_BYTES, JG_Q_X_SHARD_BYTES, JG_Q_W_SHARD_BYTES,
- JG_Q_CHAIN_WORKSPACE_BYTES, JG_Q_X_F32_SHARDS_BYTES) = range(23)
+ JG_Q_CHAIN_WORKSPACE_BYTES, JG_Q_X_F32_SHARDS_BYTES, JG_Q_NORM_BACKWARD_WORKSPACE_BYTES) = range(24)
 (JG_KERNEL_GEMM, JG_KERNEL_WEIGHT_COPY, JG_KERNEL_COMBINE, JG_KERNEL_SHARD,
  JG_KERNEL_GATHER, JG_KERNEL_GEMM_DX, JG_KERNEL_GEMM_DW, JG_KERNEL_JOIN, JG_KERNEL_NORM, JG_KERNEL_REDUCE,
  JG_KERNEL_COUNT) = range(11)
@@ -49,7 +49,7 @@ JG_T_X, JG_T_W, JG_T_B, JG_T_Y, JG_T_X_F32 = 0, 1, 2, 3, 4
 EXPORTS = ("jg_init", "jg_free", "jg_plan_create", "jg_plan_destroy", "jg_plan_query", "jg_shard",
            "jg_shard_patches", "jg_gather_patches",
            "jg_linear_forward", "jg_linear_forward_ex", "jg_mlp_forward", "jg_layernorm_forward",
-           "jg_mixing_forward", "jg_token_mixing_forward", "jg_linear_backward", "jg_bias_backward", "jg_gather", "jg_gather_as", "jg_profile",
+           "jg_mixing_forward", "jg_token_mixing_forward", "jg_linear_backward", "jg_bias_backward", "jg_layernorm_backward", "jg_gather", "jg_gather_as", "jg_profile",
            "jg_profile_read", "jg_strerror",
            "jg_last_hip_error")
 
@@ -97,6 +97,8 @@ _lib.jg_mixing_forward.argtypes = [_vp, _vp, _vpp, _vp, _vp, ctypes.c_double, _v
 _lib.jg_token_mixing_forward.argtypes = [_vp, _vp, _vpp, _vp, _vp, ctypes.c_double, _vpp, _vpp, _vpp, _vp, _vpp, _vpp,
                                          _vpp, _vp, ctypes.c_size_t]
 _lib.jg_linear_backward.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
+_lib.jg_layernorm_backward.argtypes = [_vp, _vpp, _vp, ctypes.c_double, _vpp, _vpp, _vp, _vp, _vp, ctypes.c_size_t]
+_lib.jg_layernorm_backward.restype = ctypes.c_int
 _lib.jg_bias_backward.argtypes = [_vp, _vpp, _vpp]
 _lib.jg_bias_backward.restype = ctypes.c_int
 _lib.jg_gather.argtypes = [_vp, _vpp, _vp, ctypes.c_int64]
@@ -216,6 +218,13 @@ def jg_linear_backward(plan, x_ptrs, w_ptrs, dy_ptrs, dx_ptrs, dw_ptrs, workspac
     _raise(_lib.jg_linear_backward(plan, _ptr_array(x_ptrs), _ptr_array(w_ptrs), _ptr_array(dy_ptrs),
                                    _ptr_array(dx_ptrs), _ptr_array(dw_ptrs), workspace_ptr or None,
                                    workspace_bytes), "jg_linear_backward")
+
+
+def jg_layernorm_backward(plan, x_ptrs, gamma_ptr, eps: float, dy_ptrs, dx_ptrs, dgamma_ptr, dbeta_ptr, workspace_ptr,
+                          workspace_bytes: int) -> None:
+    _raise(_lib.jg_layernorm_backward(plan, _ptr_array(x_ptrs), gamma_ptr or None, float(eps), _ptr_array(dy_ptrs),
+                                      _ptr_array(dx_ptrs), dgamma_ptr or None, dbeta_ptr or None,
+                                      workspace_ptr or None, workspace_bytes), "jg_layernorm_backward")
 
 
 def jg_bias_backward(plan, dy_ptrs, db_ptrs) -> None:

@@ -408,6 +408,9 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     case JG_Q_X_SHARD_BYTES: *out = 4 * plan->xr * plan->xcp; break;
     case JG_Q_W_SHARD_BYTES: *out = 4 * plan->wr * plan->xcp; break;
     case JG_Q_CHAIN_WORKSPACE_BYTES: *out = (int64_t)(plan->ws_bytes + plan->chain_bytes); break;
+    case JG_Q_NORM_BACKWARD_WORKSPACE_BYTES:
+        *out = (int64_t)(round_up(16 * (size_t)plan->xr, kWsAlign) * d.ways);
+        break;
     case JG_Q_X_F32_SHARDS_BYTES:
         *out = (int64_t)(round_up(4 * (size_t)plan->xr * (size_t)plan->xc, kWsAlign) * d.ways);
         break;
@@ -991,6 +994,61 @@ static int layernorm_impl(const jg_plan* plan, const float* const* x_sh, const f
     }
     ScopedTimer t(c, JG_KERNEL_NORM);
     return HIP_OK(jg::launch_norm_group(g, c->stream)) ? JG_OK : JG_E_HIP;
+}
+
+int jg_layernorm_backward(const jg_plan* plan, const float* const* x_sh, const float* gamma, double eps,
+                          const float* const* dy_sh, float* const* dx_sh, float* dgamma, float* dbeta, void* workspace,
+                          size_t workspace_bytes)
+{
+    if (!plan || !plan->ctx) return JG_E_NULL;
+    const jg_linear_desc& d = plan->d;
+    if (int rc = check_ptr_array(x_sh, d.ways)) return rc;
+    if (int rc = check_ptr_array(dy_sh, d.ways)) return rc;
+    if (int rc = check_ptr_array(dx_sh, d.ways)) return rc;
+    if (!(eps >= 0.0)) return JG_E_DTYPE;
+    if (!aligned(gamma, 4) || !aligned(dgamma, 4) || !aligned(dbeta, 4)) return JG_E_ALIGN;
+    for (int r = 0; r < d.ways; ++r)
+        if (!aligned(x_sh[r], 4) || !aligned(dy_sh[r], 4) || !aligned(dx_sh[r], 4)) return JG_E_ALIGN;
+    const size_t stats_bytes = round_up(16 * (size_t)plan->xr, kWsAlign);
+    if (!workspace || workspace_bytes < stats_bytes * d.ways) return JG_E_WORKSPACE;
+    if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
+    jg_ctx* c = plan->ctx;
+    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    jg::NormBwdGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.nblocks = d.ways;
+    g.rows = (int)plan->xr;
+    g.cols = (int)plan->xc;
+    g.eps = eps;
+    double* stats[4] = {nullptr, nullptr, nullptr, nullptr};
+    for (int r = 0; r < d.ways; ++r) {
+        int64_t rb, cb;
+        block_coords(d.ways, r, &rb, &cb);
+        stats[r] = reinterpret_cast<double*>(static_cast<char*>(workspace) + r * stats_bytes);
+        g.b[r] = {x_sh[r], dy_sh[r], dx_sh[r], gamma ? gamma + cb * plan->xc : nullptr, stats[r]};
+    }
+    // the channel blocks: one per rank (1-, 2-way), or per column of the 2 x 2 grid, summed over its two row halves
+    jg::NormBwdColsGroup cg;
+    std::memset(&cg, 0, sizeof(cg));
+    cg.rows = (int)plan->xr;
+    cg.cols = (int)plan->xc;
+    if (dgamma || dbeta) {
+        cg.nout = d.ways == 4 ? 2 : d.ways;
+        for (int j = 0; j < cg.nout; ++j) {
+            jg::NormBwdColsOut& o = cg.o[j];
+            o.nsrc = d.ways == 4 ? 2 : 1;
+            for (int b = 0; b < o.nsrc; ++b) {
+                const int r = d.ways == 4 ? 2 * b + j : j;
+                o.x[b] = x_sh[r];
+                o.dy[b] = dy_sh[r];
+                o.stats[b] = stats[r];
+            }
+            o.dgamma = dgamma ? dgamma + (int64_t)j * plan->xc : nullptr;
+            o.dbeta = dbeta ? dbeta + (int64_t)j * plan->xc : nullptr;
+        }
+    }
+    ScopedTimer t(c, JG_KERNEL_NORM);
+    return HIP_OK(jg::launch_norm_bwd(g, cg, c->stream)) ? JG_OK : JG_E_HIP;
 }
 
 int jg_bias_backward(const jg_plan* plan, const float* const* dy_sh, float* const* db_sh)

@@ -167,6 +167,145 @@ __global__ __launch_bounds__(NORM_THREADS) void layernorm_generic_f32(const Norm
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Backward of the norm (Sec. 3's norm in the backward pass of Sec. 4.1).  Per row of a block, with
+// xhat = (x - mu) * rstd and g = dy * gamma:
+//     dx = (g - mean(g) - xhat * mean(g * xhat)) * rstd,
+// and over the rows of all blocks that hold a channel:  dgamma = sum dy * xhat,  dbeta = sum dy.
+// Two kernels: rows (one workgroup per row, four passes over a row that stays in the caches, double
+// arithmetic as in the forward; it also leaves mu and rstd of every row in `stats`), then columns (as the
+// bias gradient's column sums: 32-column strips, double accumulators, a fixed order).
+// ------------------------------------------------------------------------------------------
+struct NormBwdBlock {
+    const float* x;      // rows x cols, dense: the forward's input
+    const float* dy;     // rows x cols, dense: gradient of the forward's output
+    float* dx;           // rows x cols, dense
+    const float* gamma;  // the block's cols scale factors, or nullptr (1)
+    double* stats;       // rows x 2: mu, rstd (written by the row kernel, read by the column kernel)
+};
+
+struct NormBwdGroup {
+    NormBwdBlock b[kMaxBlocks];
+    int nblocks;
+    int rows, cols;
+    double eps;
+};
+
+// grid: x = row, y = block
+__global__ __launch_bounds__(NORM_THREADS) void layernorm_bwd_rows_f32(const NormBwdGroup g)
+{
+    __shared__ double part[NORM_THREADS / 64];
+    const NormBwdBlock& B = g.b[blockIdx.y];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t off = (int64_t)blockIdx.x * g.cols;
+    const float* x = B.x + off;
+    const float* dy = B.dy + off;
+    float* dx = B.dx + off;
+    auto block_sum = [&](double v) {
+        v = wave_sum(v);
+        __syncthreads();
+        if (lane == 0) part[wave] = v;
+        __syncthreads();
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < NORM_THREADS / 64; ++w) t += part[w];
+        return t;
+    };
+    double s = 0.0;
+    for (int c = tid; c < g.cols; c += NORM_THREADS) s += (double)x[c];
+    const double mu = block_sum(s) / (double)g.cols;
+    double q = 0.0;
+    for (int c = tid; c < g.cols; c += NORM_THREADS) {
+        const double d = (double)x[c] - mu;
+        q += d * d;
+    }
+    const double rstd = 1.0 / sqrt(block_sum(q) / (double)g.cols + g.eps);
+    double sg = 0.0, sgx = 0.0;
+    for (int c = tid; c < g.cols; c += NORM_THREADS) {
+        const double gv = (double)dy[c] * (B.gamma ? (double)B.gamma[c] : 1.0);
+        sg += gv;
+        sgx += gv * (((double)x[c] - mu) * rstd);
+    }
+    const double mg = block_sum(sg) / (double)g.cols;
+    const double mgx = block_sum(sgx) / (double)g.cols;
+    for (int c = tid; c < g.cols; c += NORM_THREADS) {
+        const double gv = (double)dy[c] * (B.gamma ? (double)B.gamma[c] : 1.0);
+        const double xh = ((double)x[c] - mu) * rstd;
+        dx[c] = (float)((gv - mg - xh * mgx) * rstd);
+    }
+    if (tid == 0) {
+        B.stats[2 * (int64_t)blockIdx.x] = mu;
+        B.stats[2 * (int64_t)blockIdx.x + 1] = rstd;
+    }
+}
+
+struct NormBwdColsOut {
+    const float* x[2];       // source blocks stacked by rows (4-way: the two row halves that hold the channel block)
+    const float* dy[2];
+    const double* stats[2];
+    float* dgamma;           // cols sums of dy * xhat, or nullptr
+    float* dbeta;            // cols sums of dy, or nullptr
+    int nsrc;
+};
+
+struct NormBwdColsGroup {
+    NormBwdColsOut o[kMaxBlocks];
+    int nout;
+    int rows, cols;
+};
+
+constexpr int NORM_STRIP = 32;
+
+// grid: x = column strip, y = output (channel block).  One column per thread, 8 row lanes.
+__global__ __launch_bounds__(NORM_THREADS) void layernorm_bwd_cols_f32(const NormBwdColsGroup g)
+{
+    constexpr int ROW_LANES = NORM_THREADS / NORM_STRIP;
+    __shared__ double pg[ROW_LANES][NORM_STRIP + 1], pb[ROW_LANES][NORM_STRIP + 1];
+    const NormBwdColsOut& O = g.o[blockIdx.y];
+    const int tid = threadIdx.x, cl = tid % NORM_STRIP, rl = tid / NORM_STRIP;
+    const int col = blockIdx.x * NORM_STRIP + cl;
+    double sg = 0.0, sb = 0.0;
+    if (col < g.cols) {
+        for (int b = 0; b < O.nsrc; ++b) {
+#pragma unroll 4
+            for (int r = rl; r < g.rows; r += ROW_LANES) {
+                const double mu = O.stats[b][2 * (int64_t)r], rstd = O.stats[b][2 * (int64_t)r + 1];
+                const double d = (double)O.dy[b][(int64_t)r * g.cols + col];
+                sg += d * (((double)O.x[b][(int64_t)r * g.cols + col] - mu) * rstd);
+                sb += d;
+            }
+        }
+    }
+    pg[rl][cl] = sg;
+    pb[rl][cl] = sb;
+    __syncthreads();
+    if (tid < NORM_STRIP) {
+        const int c = blockIdx.x * NORM_STRIP + tid;
+        if (c < g.cols) {
+            double tg = 0.0, tb = 0.0;
+#pragma unroll
+            for (int r = 0; r < ROW_LANES; ++r) {
+                tg += pg[r][tid];
+                tb += pb[r][tid];
+            }
+            if (O.dgamma) O.dgamma[c] = (float)tg;
+            if (O.dbeta) O.dbeta[c] = (float)tb;
+        }
+    }
+}
+
+inline hipError_t launch_norm_bwd(const NormBwdGroup& g, const NormBwdColsGroup& cg, hipStream_t stream)
+{
+    if (g.cols <= 0 || g.nblocks <= 0) return hipSuccess;
+    if (g.rows > 0)
+        hipLaunchKernelGGL(layernorm_bwd_rows_f32, dim3(g.rows, g.nblocks, 1), dim3(NORM_THREADS), 0, stream, g);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || cg.nout <= 0) return e;
+    hipLaunchKernelGGL(layernorm_bwd_cols_f32, dim3((cg.cols + NORM_STRIP - 1) / NORM_STRIP, cg.nout, 1),
+                       dim3(NORM_THREADS), 0, stream, cg);
+    return hipGetLastError();
+}
+
 template <int NV>
 inline void launch_norm_rows(const NormGroup& g, hipStream_t stream)
 {

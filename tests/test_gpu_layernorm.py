@@ -404,3 +404,83 @@ def test_whole_mixing_block(jg, ctx, ways):
     r1 = oracle.token_mixing_block(ways, X, g1, be1, W1, b1, W2, b2)
     r2 = oracle.mixing_block(ways, r1["Y"].astype(np.float32), g2, be2, V1, c1, V2, c2)
     assert np.all(np.abs(Y - r2["Y"]) <= 1e-4 * (r2["SY"] + r2["PY"]))
+
+
+# ---------------------------------------------------------------------------------------------
+# the layer norm's gradients
+# ---------------------------------------------------------------------------------------------
+def run_norm_backward(jg, ctx, X, gamma, dY, ways, op=None, want_params=True):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    T, C = X.shape
+    kw = dict(op=jg.JG_OP_XTW) if op == "xtw" else {}
+    M, K = (C, T) if op == "xtw" else (T, C)
+    with JigsawLinear(M, K, 16, ways, ctx=ctx, **kw) as L:
+        L.shard(dev(X))
+        dy = [torch.empty_like(t) for t in L.x]
+        dx = [torch.full_like(t, float("nan")) for t in L.x]
+        jg.jg_shard(L.plan, jg.JG_T_X, dev(dY).data_ptr(), C, [t.data_ptr() for t in dy])
+        dg = torch.full((C,), float("nan"), device="cuda") if want_params else None
+        db = torch.full((C,), float("nan"), device="cuda") if want_params else None
+        need = L.query(jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES)
+        ws = torch.full((need,), 0xFF, dtype=torch.uint8, device="cuda")
+        p = lambda ts: [t.data_ptr() for t in ts]
+        g = dev(gamma) if gamma is not None else None
+        call = lambda: jg.jg_layernorm_backward(L.plan, p(L.x), g.data_ptr() if g is not None else None, 1e-5, p(dy), p(dx),
+                                                dg.data_ptr() if dg is not None else None,
+                                                db.data_ptr() if db is not None else None, ws.data_ptr(), need)
+        call()
+        out = torch.empty((T, C), device="cuda")
+        jg.jg_gather_as(L.plan, jg.JG_T_X, p(dx), out.data_ptr(), C)
+        first = (out.cpu().numpy(), dg.cpu().numpy() if want_params else None, db.cpu().numpy() if want_params else None)
+        call()
+        jg.jg_gather_as(L.plan, jg.JG_T_X, p(dx), out.data_ptr(), C)
+        assert np.array_equal(first[0], out.cpu().numpy())
+        if want_params:
+            assert np.array_equal(first[1], dg.cpu().numpy()) and np.array_equal(first[2], db.cpu().numpy())
+        return first
+
+
+def check_norm_backward(X, gamma, dY, ways, got):
+    dX, dg, db, SX, Sg, Sb = oracle.layernorm_backward(X, gamma, dY, oracle.ln_groups(ways), magnitude=True)
+    # evaluated in double and rounded once; the sums' order differs from the oracle's in the last double bits
+    assert np.all(np.abs(got[0] - dX) <= HALF_ULP * np.abs(dX) * (1 + 1e-6) + 1e-11 * SX + 1e-45)
+    if got[1] is not None:
+        assert np.all(np.abs(got[1] - dg) <= HALF_ULP * np.abs(dg) * (1 + 1e-6) + 1e-11 * Sg + 1e-45)
+        assert np.all(np.abs(got[2] - db) <= HALF_ULP * np.abs(db) * (1 + 1e-6) + 1e-11 * Sb + 1e-45)
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("T,C", [(2, 4), (100, 100), (130, 72), (258, 264), (64, 4320), (2200, 50)])
+def test_layernorm_backward_matches_oracle(jg, ctx, ways, T, C):
+    X = (inputs.matrix(130, T, C, "R") + np.float32(0.25)).astype(np.float32)
+    gamma, _ = affine(131, C)
+    dY = inputs.matrix(132, T, C, "R")
+    check_norm_backward(X, gamma, dY, ways, run_norm_backward(jg, ctx, X, gamma, dY, ways))
+
+
+@pytest.mark.parametrize("ways", [1, 4])
+def test_layernorm_backward_options(jg, ctx, ways):
+    T, C = 130, 72
+    X = (inputs.matrix(133, T, C, "R") - np.float32(0.5)).astype(np.float32)
+    gamma, _ = affine(134, C)
+    dY = inputs.matrix(135, T, C, "R")
+    check_norm_backward(X, None, dY, ways, run_norm_backward(jg, ctx, X, None, dY, ways))                 # gamma = 1
+    check_norm_backward(X, gamma, dY, ways, run_norm_backward(jg, ctx, X, gamma, dY, ways, want_params=False))
+    check_norm_backward(X, gamma, dY, ways, run_norm_backward(jg, ctx, X, gamma, dY, ways, op="xtw"))      # same axis
+
+
+def test_layernorm_backward_argument_checks(jg, ctx):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    with JigsawLinear(16, 8, 8, 2, ctx=ctx) as L:
+        p = [t.data_ptr() for t in L.x]
+        need = L.query(jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES)
+        assert need == 2 * 256
+        ws = torch.empty((need,), dtype=torch.uint8, device="cuda")
+        for args, want in (((p, None, -1.0, p, p, None, None, ws.data_ptr(), need), jg.JG_E_DTYPE),
+                           ((p, None, 1e-5, p, p, None, None, ws.data_ptr(), need - 1), jg.JG_E_WORKSPACE),
+                           ((p, None, 1e-5, p, p, None, None, None, 0), jg.JG_E_WORKSPACE),
+                           ((p, None, 1e-5, p, p, None, None, ws.data_ptr() + 16, need), jg.JG_E_ALIGN),
+                           ((p, L.x[0].data_ptr() + 2, 1e-5, p, p, None, None, ws.data_ptr(), need), jg.JG_E_ALIGN)):
+            with pytest.raises(jg.JigsawError) as e:
+                jg.jg_layernorm_backward(L.plan, *args)
+            assert e.value.status == want
