@@ -239,6 +239,104 @@ __global__ __launch_bounds__(NORM_THREADS) void layernorm_bwd_rows_f32(const Nor
     }
 }
 
+// The same with one wavefront per row and the row of x and of dy in registers (NV 16-byte vectors per lane each),
+// as the forward's register-resident kernel: every element is read once.  cols % 4 == 0, cols / 4 <= 64 * NV,
+// 16-byte aligned operands.  grid: x = row / NORM_ROWS_PER_WG, y = block.
+template <int NV>
+__global__ __launch_bounds__(NORM_THREADS) void layernorm_bwd_rows_reg_f32(const NormBwdGroup g)
+{
+    const NormBwdBlock& B = g.b[blockIdx.y];
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * NORM_ROWS_PER_WG + (threadIdx.x >> 6);
+    if (row >= g.rows) return;
+    const int nvec = g.cols >> 2;
+    const vf4* x = reinterpret_cast<const vf4*>(B.x + (int64_t)row * g.cols);
+    const vf4* dy = reinterpret_cast<const vf4*>(B.dy + (int64_t)row * g.cols);
+    const vf4* gamma = reinterpret_cast<const vf4*>(B.gamma);
+    vf4 v[NV], d[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = i * 64 + lane;
+        v[i] = c < nvec ? x[c] : vf4{0.f, 0.f, 0.f, 0.f};
+        d[i] = c < nvec ? __builtin_nontemporal_load(dy + c) : vf4{0.f, 0.f, 0.f, 0.f};
+    }
+    double s = 0.0;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) s += ((double)v[i].x + (double)v[i].y) + ((double)v[i].z + (double)v[i].w);
+    const double mu = wave_sum(s) / (double)g.cols;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) asm volatile("" : "+v"(v[i]));
+    double q = 0.0;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        if (i * 64 + lane < nvec) {
+            const double dx = (double)v[i].x - mu, dy2 = (double)v[i].y - mu;
+            const double dz = (double)v[i].z - mu, dw = (double)v[i].w - mu;
+            q += (dx * dx + dy2 * dy2) + (dz * dz + dw * dw);
+        }
+    }
+    const double rstd = 1.0 / sqrt(wave_sum(q) / (double)g.cols + g.eps);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) asm volatile("" : "+v"(v[i]), "+v"(d[i]));
+    // g = dy * gamma replaces dy in the registers (rounded to FP32 it would differ from the definition: keep dy,
+    // multiply again below)
+    double sg = 0.0, sgx = 0.0;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = i * 64 + lane;
+        if (c < nvec) {
+            const vf4 ga = gamma ? gamma[c] : vf4{1.f, 1.f, 1.f, 1.f};
+            const double g0 = (double)d[i].x * (double)ga.x, g1 = (double)d[i].y * (double)ga.y;
+            const double g2 = (double)d[i].z * (double)ga.z, g3 = (double)d[i].w * (double)ga.w;
+            sg += (g0 + g1) + (g2 + g3);
+            sgx += (g0 * (((double)v[i].x - mu) * rstd) + g1 * (((double)v[i].y - mu) * rstd)) +
+                   (g2 * (((double)v[i].z - mu) * rstd) + g3 * (((double)v[i].w - mu) * rstd));
+        }
+    }
+    const double mg = wave_sum(sg) / (double)g.cols;
+    const double mgx = wave_sum(sgx) / (double)g.cols;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) asm volatile("" : "+v"(v[i]), "+v"(d[i]));
+    vf4* dxp = reinterpret_cast<vf4*>(B.dx + (int64_t)row * g.cols);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = i * 64 + lane;
+        if (c < nvec) {
+            const vf4 ga = gamma ? gamma[c] : vf4{1.f, 1.f, 1.f, 1.f};
+            vf4 o;
+            o.x = (float)(((double)d[i].x * (double)ga.x - mg - (((double)v[i].x - mu) * rstd) * mgx) * rstd);
+            o.y = (float)(((double)d[i].y * (double)ga.y - mg - (((double)v[i].y - mu) * rstd) * mgx) * rstd);
+            o.z = (float)(((double)d[i].z * (double)ga.z - mg - (((double)v[i].z - mu) * rstd) * mgx) * rstd);
+            o.w = (float)(((double)d[i].w * (double)ga.w - mg - (((double)v[i].w - mu) * rstd) * mgx) * rstd);
+            dxp[c] = o;
+        }
+    }
+    if (lane == 0) {
+        B.stats[2 * (int64_t)row] = mu;
+        B.stats[2 * (int64_t)row + 1] = rstd;
+    }
+}
+
+template <int NV>
+inline void launch_norm_bwd_rows_reg(const NormBwdGroup& g, hipStream_t stream)
+{
+    dim3 grid((g.rows + NORM_ROWS_PER_WG - 1) / NORM_ROWS_PER_WG, g.nblocks, 1);
+    hipLaunchKernelGGL((layernorm_bwd_rows_reg_f32<NV>), grid, dim3(NORM_THREADS), 0, stream, g);
+}
+
+constexpr int kNormBwdMaxVectorsPerLane = 17;      // register-resident rows of x and dy: up to 4352 columns
+
+inline bool norm_bwd_rows_fit(const NormBwdGroup& g)
+{
+    if ((g.cols & 3) || g.cols / 4 > 64 * kNormBwdMaxVectorsPerLane) return false;
+    for (int i = 0; i < g.nblocks; ++i) {
+        const NormBwdBlock& b = g.b[i];
+        if (((uintptr_t)b.x & 15) || ((uintptr_t)b.dy & 15) || ((uintptr_t)b.dx & 15) || ((uintptr_t)b.gamma & 15))
+            return false;
+    }
+    return true;
+}
+
 struct NormBwdColsOut {
     const float* x[2];       // source blocks stacked by rows (4-way: the two row halves that hold the channel block)
     const float* dy[2];
@@ -256,28 +354,48 @@ struct NormBwdColsGroup {
 
 constexpr int NORM_STRIP = 32;
 
-// grid: x = column strip, y = output (channel block).  One column per thread, 8 row lanes.
+// grid: x = column strip, y = output (channel block).  VEC (cols % 4 == 0, 16-byte aligned sources): four columns
+// per thread, 8 lanes across the strip, 32 row lanes; otherwise one column per thread, 8 row lanes.
+template <bool VEC>
 __global__ __launch_bounds__(NORM_THREADS) void layernorm_bwd_cols_f32(const NormBwdColsGroup g)
 {
-    constexpr int ROW_LANES = NORM_THREADS / NORM_STRIP;
+    constexpr int LANES = VEC ? NORM_STRIP / 4 : NORM_STRIP;
+    constexpr int ROW_LANES = NORM_THREADS / LANES;
+    constexpr int W = VEC ? 4 : 1;
     __shared__ double pg[ROW_LANES][NORM_STRIP + 1], pb[ROW_LANES][NORM_STRIP + 1];
     const NormBwdColsOut& O = g.o[blockIdx.y];
-    const int tid = threadIdx.x, cl = tid % NORM_STRIP, rl = tid / NORM_STRIP;
-    const int col = blockIdx.x * NORM_STRIP + cl;
-    double sg = 0.0, sb = 0.0;
+    const int tid = threadIdx.x, cl = tid % LANES, rl = tid / LANES;
+    const int col = blockIdx.x * NORM_STRIP + cl * W;
+    double sg[4] = {0.0, 0.0, 0.0, 0.0}, sb[4] = {0.0, 0.0, 0.0, 0.0};
     if (col < g.cols) {
         for (int b = 0; b < O.nsrc; ++b) {
-#pragma unroll 4
+#pragma unroll 2
             for (int r = rl; r < g.rows; r += ROW_LANES) {
                 const double mu = O.stats[b][2 * (int64_t)r], rstd = O.stats[b][2 * (int64_t)r + 1];
-                const double d = (double)O.dy[b][(int64_t)r * g.cols + col];
-                sg += d * (((double)O.x[b][(int64_t)r * g.cols + col] - mu) * rstd);
-                sb += d;
+                if (VEC) {
+                    const vf4 dv = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(O.dy[b] + (int64_t)r * g.cols + col));
+                    const vf4 xv = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(O.x[b] + (int64_t)r * g.cols + col));
+                    sg[0] += (double)dv.x * (((double)xv.x - mu) * rstd);
+                    sg[1] += (double)dv.y * (((double)xv.y - mu) * rstd);
+                    sg[2] += (double)dv.z * (((double)xv.z - mu) * rstd);
+                    sg[3] += (double)dv.w * (((double)xv.w - mu) * rstd);
+                    sb[0] += (double)dv.x;
+                    sb[1] += (double)dv.y;
+                    sb[2] += (double)dv.z;
+                    sb[3] += (double)dv.w;
+                } else {
+                    const double d = (double)O.dy[b][(int64_t)r * g.cols + col];
+                    sg[0] += d * (((double)O.x[b][(int64_t)r * g.cols + col] - mu) * rstd);
+                    sb[0] += d;
+                }
             }
         }
     }
-    pg[rl][cl] = sg;
-    pb[rl][cl] = sb;
+#pragma unroll
+    for (int q = 0; q < W; ++q) {
+        pg[rl][cl * W + q] = sg[q];
+        pb[rl][cl * W + q] = sb[q];
+    }
     __syncthreads();
     if (tid < NORM_STRIP) {
         const int c = blockIdx.x * NORM_STRIP + tid;
@@ -297,12 +415,25 @@ __global__ __launch_bounds__(NORM_THREADS) void layernorm_bwd_cols_f32(const Nor
 inline hipError_t launch_norm_bwd(const NormBwdGroup& g, const NormBwdColsGroup& cg, hipStream_t stream)
 {
     if (g.cols <= 0 || g.nblocks <= 0) return hipSuccess;
-    if (g.rows > 0)
+    if (g.rows > 0 && norm_bwd_rows_fit(g)) {
+        const int need = (g.cols / 4 + 63) / 64;      // vectors per lane
+        if (need <= 1) launch_norm_bwd_rows_reg<1>(g, stream);
+        else if (need <= 2) launch_norm_bwd_rows_reg<2>(g, stream);
+        else if (need <= 4) launch_norm_bwd_rows_reg<4>(g, stream);
+        else if (need <= 9) launch_norm_bwd_rows_reg<9>(g, stream);
+        else launch_norm_bwd_rows_reg<17>(g, stream);
+    } else if (g.rows > 0) {
         hipLaunchKernelGGL(layernorm_bwd_rows_f32, dim3(g.rows, g.nblocks, 1), dim3(NORM_THREADS), 0, stream, g);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || cg.nout <= 0) return e;
-    hipLaunchKernelGGL(layernorm_bwd_cols_f32, dim3((cg.cols + NORM_STRIP - 1) / NORM_STRIP, cg.nout, 1),
-                       dim3(NORM_THREADS), 0, stream, cg);
+    bool vec = (cg.cols & 3) == 0;
+    for (int i = 0; i < cg.nout; ++i)
+        for (int b = 0; b < cg.o[i].nsrc; ++b)
+            if (((uintptr_t)cg.o[i].x[b] | (uintptr_t)cg.o[i].dy[b]) & 15) vec = false;
+    const dim3 cgrid((cg.cols + NORM_STRIP - 1) / NORM_STRIP, cg.nout, 1);
+    if (vec) hipLaunchKernelGGL(layernorm_bwd_cols_f32<true>, cgrid, dim3(NORM_THREADS), 0, stream, cg);
+    else hipLaunchKernelGGL(layernorm_bwd_cols_f32<false>, cgrid, dim3(NORM_THREADS), 0, stream, cg);
     return hipGetLastError();
 }
 

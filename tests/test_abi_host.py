@@ -413,3 +413,16 @@ def test_bias_backward_checks_its_arguments():
     a = jg.jg_plan_create(None, 64, 32, 48, 2, True)
     assert lib.jg_bias_backward(a, pp, pp) == jg.JG_E_NULL          # a plan without a context
     jg.jg_plan_destroy(a)
+
+
+def test_layernorm_backward_checks_its_arguments():
+    lib = jg.raw()
+    arr = (ctypes.c_void_p * 2)(256, 512)
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    call = lambda plan: lib.jg_layernorm_backward(plan, pp, None, 1e-5, pp, pp, None, None, 256, 1 << 20)
+    assert call(None) == jg.JG_E_NULL
+    a = jg.jg_plan_create(None, 64, 32, 48, 2, True)
+    assert call(a) == jg.JG_E_NULL                                      # a plan without a context
+    # two doubles per row of a rank's block, in 256-byte pieces
+    assert jg.jg_plan_query(a, jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES) == 2 * ((16 * 64 + 255) // 256 * 256)
+    jg.jg_plan_destroy(a)
