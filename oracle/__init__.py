@@ -256,6 +256,32 @@ def gelu(a) -> np.ndarray:
     return out
 
 
+def gelu_grad(a) -> np.ndarray:
+    """d/dx (x Phi(x)) = Phi(x) + x phi(x), element by element, in double (Phi, phi: the standard normal
+    distribution function and density; erf from the library)."""
+    from scipy.special import erf
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return 0.5 * (1.0 + erf(a * 0.70710678118654752440)) + a * np.exp(-0.5 * a * a) * 0.39894228040143267794
+
+
+def mlp_backward(X, W1, b1, W2, dY, nthreads: int | None = None):
+    """Gradients of the mixing MLP Y = X + gelu(X W1^T + b1) W2^T + b2 for an incoming gradient dY, in double, by the
+    chain rule through the layers' own backward passes (Sec. 4.1), with what the method stores between the steps
+    handed on in FP32 (H, dA):
+        A = X W1^T + b1,  H = gelu(A);   dH = dY W2,  dW2 = dY^T H,  db2 = sum_i dY;
+        dA = dH * gelu'(A);              dX = dY + dA W1,  dW1 = dA^T X,  db1 = sum_i dA.
+    Returns a dict with A, dH, dA, dX, dW1, db1, dW2, db2."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    A = linear(X, W1, b1, nthreads)
+    H32 = gelu(A).astype(np.float32)
+    dH, dW2 = backward(H32, W2, dY, nthreads)
+    dA = dH * gelu_grad(A)
+    dA32 = dA.astype(np.float32)
+    dXm, dW1 = backward(X, W1, dA32, nthreads)
+    return dict(A=A, dH=dH, dA=dA, dX=dXm + np.asarray(dY, dtype=np.float64), dW1=dW1, db1=bias_backward(dA32),
+                dW2=dW2, db2=bias_backward(dY))
+
+
 def mlp(X, W1, b1, W2, b2, residual: bool = True, nthreads: int | None = None):
     """One mixing MLP: H = gelu(X W1^T + b1), Y = (X +) H W2^T + b2, in double.
 

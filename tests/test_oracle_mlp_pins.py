@@ -115,3 +115,67 @@ def test_blockwise_mlp_agrees_within_the_rounding_of_h(ways):
     # H is handed on in FP32: half an ulp of each H, carried through |W2|
     bound = 2.0 ** -24 * (np.abs(r["H"]) @ np.abs(W2.astype(np.float64)).T) + 1e-14 * r["SY"]
     assert np.all(np.abs(got - r["Y"]) <= bound)
+
+
+# ---------------------------------------------------------------------------------------------
+# the derivative of GELU and the MLP's backward pass
+# ---------------------------------------------------------------------------------------------
+def test_gelu_grad_tabulated_and_limits():
+    g = oracle.gelu_grad(np.array([0.0, 1.0, -1.0, 2.0, 40.0, -40.0]))
+    # Phi(1) = 0.8413447461, phi(1) = 0.2419707245, Phi(2) = 0.9772498681, phi(2) = 0.0539909665
+    want = [0.5, 0.8413447461 + 0.2419707245, (1 - 0.8413447461) - 0.2419707245, 0.9772498681 + 2 * 0.0539909665, 1.0, 0.0]
+    assert np.allclose(g, want, rtol=0, atol=2e-10)
+    # gelu'(x) + gelu'(-x) = 1 (from gelu(x) - gelu(-x) = x)
+    x = np.linspace(-6, 6, 97)
+    assert np.allclose(oracle.gelu_grad(x) + oracle.gelu_grad(-x), 1.0, rtol=0, atol=1e-15)
+
+
+def test_gelu_grad_is_the_slope_of_the_pinned_gelu():
+    x = np.linspace(-5, 5, 201)
+    h = 1e-5
+    slope = (oracle.gelu(x + h) - oracle.gelu(x - h)) / (2 * h)
+    assert np.allclose(oracle.gelu_grad(x), slope, rtol=0, atol=1e-9)
+    # the tanh approximation's derivative is another function
+    t = lambda v: 0.5 * v * (1 + np.tanh(0.7978845608 * (v + 0.044715 * v ** 3)))
+    assert np.abs((t(x + h) - t(x - h)) / (2 * h) - oracle.gelu_grad(x)).max() > 1e-4
+
+
+def test_mlp_backward_against_the_library_autograd_in_double():
+    import torch
+    M, C, Hd = 6, 8, 10
+    X, W1, b1 = inputs.layer_inputs(340, M, C, Hd, "R", bias=True)
+    W2 = inputs.matrix(341, C, Hd, "R", inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(342, 1, C, "R")[0]
+    dY = inputs.matrix(343, M, C, "R")
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64)).requires_grad_(True)
+    Xt, W1t, b1t, W2t, b2t = t(X), t(W1), t(b1), t(W2), t(b2)
+    A = Xt @ W1t.T + b1t
+    Y = Xt + torch.nn.functional.gelu(A) @ W2t.T + b2t
+    Y.backward(torch.from_numpy(dY).double())
+    r = oracle.mlp_backward(X, W1, b1, W2, dY)
+    # H and dA are handed on in FP32 by the method: agreement to their rounding, carried through one product
+    for name, ref in (("dX", Xt.grad), ("dW1", W1t.grad), ("db1", b1t.grad), ("dW2", W2t.grad), ("db2", b2t.grad)):
+        ref = ref.numpy()
+        assert np.all(np.abs(r[name] - ref) <= 1e-6 * (np.abs(ref) + np.abs(ref).max())), name
+    assert np.allclose(r["A"], A.detach().numpy(), rtol=0, atol=1e-13)
+    # the skip connection's share: without it dX would miss dY
+    through = np.abs(r["dX"] - dY).max()                        # what comes back through the two layers
+    assert through > 1e-5 and np.abs((r["dX"] - dY) - (Xt.grad.numpy() - dY)).max() < 1e-5 * through
+
+
+def test_mlp_backward_is_the_pinned_pieces_in_sequence():
+    M, C, Hd = 5, 6, 8
+    X, W1, b1 = inputs.layer_inputs(344, M, C, Hd, "R", bias=True)
+    W2 = inputs.matrix(345, C, Hd, "R", inputs.W_SCALE_EXP)
+    dY = inputs.matrix(346, M, C, "R")
+    r = oracle.mlp_backward(X, W1, b1, W2, dY)
+    A = oracle.linear(X, W1, b1)
+    H32 = oracle.gelu(A).astype(np.float32)
+    dH, dW2 = oracle.backward(H32, W2, dY)
+    assert np.array_equal(r["dH"], dH) and np.array_equal(r["dW2"], dW2)
+    dA = dH * oracle.gelu_grad(A)
+    assert np.array_equal(r["dA"], dA)
+    dXm, dW1 = oracle.backward(X, W1, dA.astype(np.float32))
+    assert np.array_equal(r["dX"], dXm + dY) and np.array_equal(r["dW1"], dW1)
+    assert np.array_equal(r["db1"], oracle.bias_backward(dA.astype(np.float32)))
+    assert np.array_equal(r["db2"], oracle.bias_backward(dY))
