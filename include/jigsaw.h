@@ -376,6 +376,23 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
                        const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh,
                        void* workspace, size_t workspace_bytes);
 
+/* run (backward, MLP).  Gradients of jg_mlp_forward's MLP  H = gelu(X W1^T + b1),  Y = X + H W2^T + b2  for an
+ * incoming gradient dY (shaped and partitioned like Y_r = like X_r), by the chain rule through the layers' own
+ * backward passes (Sec. 4.1):
+ *     dH = dY W2,   dW2 = dY^T H,   db2 = sum_i dY;      A = X W1^T + b1 (recomputed: the forward keeps H, not A);
+ *     dA = dH * gelu'(A),  gelu'(x) = Phi(x) + x phi(x);  dX = dY + dA W1,   dW1 = dA^T X,   db1 = sum_i dA.
+ * FP32 plans as for jg_mlp_forward.  x_sh, w1_sh, b1_sh, w2_sh: as in the forward; h_sh: the H it stored; dy_sh:
+ * the dY shards.  Outputs (`ways` device buffers each): a_sh, dh_sh, da_sh shaped like H_r (A, dH and dA are kept:
+ * they are what the steps hand on); dx_sh like X_r; dw1_sh, dw2_sh like the plans' W_r; db1_sh, db2_sh like their
+ * bias shards.  No output may overlap an input or another output.  workspace: 256-byte aligned, at least the
+ * largest of the first plan's JG_Q_WORKSPACE_BYTES and the two plans' JG_Q_BACKWARD_WORKSPACE_BYTES.
+ * Errors: those of jg_mlp_forward, jg_linear_backward and jg_bias_backward. */
+int jg_mlp_backward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* const* w1_sh,
+                    const float* const* b1_sh, const float* const* w2_sh, const float* const* h_sh,
+                    const float* const* dy_sh, float* const* a_sh, float* const* dh_sh, float* const* da_sh,
+                    float* const* dx_sh, float* const* dw1_sh, float* const* db1_sh, float* const* dw2_sh,
+                    float* const* db2_sh, void* workspace, size_t workspace_bytes);
+
 /* run (backward, layer norm).  Gradients of jg_layernorm_forward's output for an incoming gradient dY (shaped and
  * partitioned like X_r), per row of X_r over the channels the rank holds, with xhat = (x - mu) / sqrt(var + eps)
  * and g = dY * gamma:

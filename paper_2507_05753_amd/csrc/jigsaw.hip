@@ -15,6 +15,7 @@
 #include "patch_kernels.hpp"
 #include "norm_kernels.hpp"
 #include "reduce_kernels.hpp"
+#include "act_kernels.hpp"
 #include "gemm_bf16.hpp"
 #include "cvt_kernels.hpp"
 
@@ -1224,6 +1225,63 @@ int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* con
     if (int rc = check_ptr_array(h_sh, first->d.ways)) return rc;
     return run_chain(first, second, x_sh, x_sh, w1_sh, b1_sh, w2_sh, b2_sh, h_sh, y_sh, workspace, workspace_bytes,
                      false);
+}
+
+int jg_mlp_backward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* const* w1_sh,
+                    const float* const* b1_sh, const float* const* w2_sh, const float* const* h_sh,
+                    const float* const* dy_sh, float* const* a_sh, float* const* dh_sh, float* const* da_sh,
+                    float* const* dx_sh, float* const* dw1_sh, float* const* db1_sh, float* const* dw2_sh,
+                    float* const* db2_sh, void* workspace, size_t workspace_bytes)
+{
+    if (int rc = check_mlp_chain(first, second)) return rc;
+    if (first->d.dtype != JG_F32) return JG_E_DTYPE;
+    const int ways = first->d.ways;
+    for (float* const* arr : {a_sh, dh_sh, da_sh, db1_sh, db2_sh})
+        if (int rc = check_ptr_array(arr, ways)) return rc;
+    size_t need = first->ws_bytes;
+    if (first->bw_ws_bytes > need) need = first->bw_ws_bytes;
+    if (second->bw_ws_bytes > need) need = second->bw_ws_bytes;
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return JG_E_WORKSPACE;
+        if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
+    }
+    jg_ctx* c = first->ctx;
+    // second layer: dH = dY W2, dW2 = dY^T H, db2 = column sums of dY
+    int rc = jg_linear_backward(second, h_sh, w2_sh, dy_sh, dh_sh, dw2_sh, workspace, workspace_bytes);
+    if (rc != JG_OK) return rc;
+    rc = jg_bias_backward(second, dy_sh, db2_sh);
+    if (rc != JG_OK) return rc;
+    // the pre-activation, which the forward does not keep: A = X W1^T + b1 once more
+    rc = forward_impl(first, x_sh, w1_sh, b1_sh, nullptr, JG_ACT_NONE, a_sh, workspace, workspace_bytes, nullptr);
+    if (rc != JG_OK) return rc;
+    // dA = dH * gelu'(A)
+    {
+        jg::ActBwdGroup ag;
+        std::memset(&ag, 0, sizeof(ag));
+        ag.nblocks = ways;
+        ag.n = (int64_t)first->yr * first->yc;
+        for (int r = 0; r < ways; ++r) {
+            if (!aligned(a_sh[r], 4) || !aligned(dh_sh[r], 4) || !aligned(da_sh[r], 4)) return JG_E_ALIGN;
+            ag.b[r] = {a_sh[r], dh_sh[r], da_sh[r]};
+        }
+        ScopedTimer t(c, JG_KERNEL_COMBINE);
+        if (!HIP_OK(jg::launch_act_bwd_group(ag, c->stream))) return JG_E_HIP;
+    }
+    // first layer: dA W1 (into dx_sh), dW1 = dA^T X, db1 = column sums of dA
+    rc = jg_linear_backward(first, x_sh, w1_sh, da_sh, dx_sh, dw1_sh, workspace, workspace_bytes);
+    if (rc != JG_OK) return rc;
+    rc = jg_bias_backward(first, da_sh, db1_sh);
+    if (rc != JG_OK) return rc;
+    // the skip connection: dX = dY + dA W1 (dY_r and dX_r are both shaped like X_r)
+    jg::CombineGroup cb;
+    std::memset(&cb, 0, sizeof(cb));
+    cb.nblocks = ways;
+    cb.rows = (int)first->xr;
+    cb.cols = (int)first->xc;
+    cb.act = jg::kActNone;
+    for (int r = 0; r < ways; ++r) cb.b[r] = {dx_sh[r], dy_sh[r], nullptr, dx_sh[r], nullptr};
+    ScopedTimer t(c, JG_KERNEL_COMBINE);
+    return HIP_OK(jg::launch_combine_group(cb, c->stream)) ? JG_OK : JG_E_HIP;
 }
 
 // X [T x C] -> H [C x D] (transposed layer) -> Y [T x C] (plain layer, W2 in the activations' place, H in the weights')

@@ -226,6 +226,49 @@ class JigsawMLP:
     def gather(self):
         return self.second.gather()
 
+    # -- backward (FP32 plans) -----------------------------------------------------
+    def backward(self, dY):
+        """Gradients for an incoming gradient dY (M, C), after forward(): jg_mlp_backward.  The shards of A, dH, dA,
+        dX, dW1, db1, dW2, db2 are kept on the holder (``self.grads``)."""
+        f, s = self.first, self.second
+        assert self.dtype == jg.JG_F32 and dY.is_cuda and dY.dtype == torch.float32 and dY.shape == (self.M, self.C)
+        if getattr(self, "grads", None) is None:
+            like = lambda ts: [torch.empty_like(t) for t in ts]
+            self.grads = dict(dy=like(s.y), a=like(f.y), dh=like(f.y), da=like(f.y), dx=like(self.xin), dw1=like(f.w),
+                              db1=like(f.b), dw2=like(s.w), db2=like(s.b))
+            need = max(f.query(jg.JG_Q_WORKSPACE_BYTES), f.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES),
+                       s.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES))
+            self.bw_ws = torch.empty((max(need, 1),), dtype=torch.uint8, device=f.dev)
+            self.bw_ws_bytes = need
+        g = self.grads
+        p = lambda ts: [t.data_ptr() for t in ts]
+        jg.jg_shard(s.plan, jg.JG_T_Y, dY.data_ptr(), dY.stride(0), p(g["dy"]))
+        jg.jg_mlp_backward(f.plan, s.plan, p(self.xin), p(f.w), p(f.b), p(s.w), p(f.y), p(g["dy"]), p(g["a"]), p(g["dh"]),
+                           p(g["da"]), p(g["dx"]), p(g["dw1"]), p(g["db1"]), p(g["dw2"]), p(g["db2"]),
+                           self.bw_ws.data_ptr() if self.bw_ws_bytes else None, self.bw_ws_bytes)
+
+    def gather_grad(self, name: str):
+        """A gradient (or kept intermediate) of backward() as a global matrix: 'a', 'dh', 'da' (M, Hd), 'dx' (M, C),
+        'dw1' (Hd, C), 'dw2' (C, Hd); 'db1', 'db2' as global vectors."""
+        f, s, g = self.first, self.second, self.grads
+        p = lambda ts: [t.data_ptr() for t in ts]
+        dev = f.dev
+        if name in ("a", "dh", "da"):
+            out = torch.empty((self.M, self.Hd), dtype=torch.float32, device=dev)
+            jg.jg_gather_as(f.plan, jg.JG_T_Y, p(g[name]), out.data_ptr(), out.stride(0))
+        elif name == "dx":
+            out = torch.empty((self.M, self.C), dtype=torch.float32, device=dev)
+            jg.jg_gather_as(f.plan, jg.JG_T_X_F32, p(g[name]), out.data_ptr(), out.stride(0))
+        elif name in ("dw1", "dw2"):
+            L = f if name == "dw1" else s
+            out = torch.empty(L.w_shape, dtype=torch.float32, device=dev)
+            jg.jg_gather_as(L.plan, jg.JG_T_W, p(g[name]), out.data_ptr(), out.stride(0))
+        else:       # bias gradients: rank r holds the slice of column half r % 2 (replicated in the 4-way form)
+            L = f if name == "db1" else s
+            parts = g[name][:1] if self.ways == 1 else g[name][:2]
+            out = torch.cat(parts)
+        return out
+
     def close(self):
         self.second.close()
         self.first.close()

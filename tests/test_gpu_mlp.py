@@ -210,3 +210,58 @@ def test_channel_mixing_size(jg, capsys):
         assert e2.max() <= TOL, (ways, e2.max())      # the second layer alone, from the GPU's own H
         note(capsys, f"channel mixing ways={ways}: H max err/S1 {eh.max():.2e}, layer 2 max err/S {e2.max():.2e}, Y max err/bound {ey.max():.2e} "
                      f"({rows.size} x {C} entries each)")
+
+
+# ---------------------------------------------------------------------------------------------
+# backward of the MLP: the chain rule through the layers' backward passes, checked step by step
+# ---------------------------------------------------------------------------------------------
+def check_mlp_backward(L, X, W1, b1, W2, dY, ways):
+    g = {k: L.gather_grad(k).cpu().numpy() for k in ("a", "dh", "da", "dx", "dw1", "dw2", "db1", "db2")}
+    H = L.gather_h().cpu().numpy()
+    f64 = lambda a: a.astype(np.float64)
+    rel = lambda err, S: (err / np.maximum(S, 1e-300)).max()
+    # A recomputed: one forward layer
+    A64, SA = oracle.linear(X, W1, b1), oracle.magnitude(X, W1, b1)
+    assert np.all(np.abs(f64(g["a"]) - A64) <= 1e-6 * SA), f"A: {rel(np.abs(f64(g['a']) - A64), SA):.2e}"
+    # second layer's backward from the H the forward stored
+    dH64, dW264 = oracle.backward(H, W2, dY)
+    SH, SW2 = oracle.backward_magnitude(H, W2, dY)
+    assert np.all(np.abs(f64(g["dh"]) - dH64) <= 1e-6 * SH), f"dH: {rel(np.abs(f64(g['dh']) - dH64), SH):.2e}"
+    assert np.all(np.abs(f64(g["dw2"]) - dW264) <= 1e-6 * SW2), f"dW2: {rel(np.abs(f64(g['dw2']) - dW264), SW2):.2e}"
+    db2 = oracle.bias_backward(dY)
+    assert np.all(np.abs(f64(g["db2"]) - db2) <= 2.0 ** -23 * np.abs(db2) + 1e-12 * oracle.bias_backward(dY, absolute=True))
+    # dA from the A and dH the GPU stored: evaluated in double, rounded once
+    dA64 = f64(g["dh"]) * oracle.gelu_grad(f64(g["a"]))
+    assert np.all(np.abs(f64(g["da"]) - dA64) <= 2.0 ** -23 * np.abs(dA64) + 1e-45), "dA"
+    # first layer's backward from the dA the GPU stored, plus the skip connection
+    dX64, dW164 = oracle.backward(X, W1, g["da"])
+    SX, SW1 = oracle.backward_magnitude(X, W1, g["da"])
+    ex = np.abs(f64(g["dx"]) - (dX64 + f64(dY)))
+    assert np.all(ex <= 1e-6 * (SX + np.abs(dY))), f"dX: {rel(ex, SX + np.abs(dY)):.2e}"
+    assert np.all(np.abs(f64(g["dw1"]) - dW164) <= 1e-6 * SW1), f"dW1: {rel(np.abs(f64(g['dw1']) - dW164), SW1):.2e}"
+    db1 = oracle.bias_backward(g["da"])
+    assert np.all(np.abs(f64(g["db1"]) - db1) <= 2.0 ** -23 * np.abs(db1) + 1e-12 * oracle.bias_backward(g["da"], absolute=True))
+    return g
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,C,Hd", [(100, 100, 100), (130, 72, 258), (258, 264, 136), (300, 520, 1032)])
+def test_mlp_backward(jg, ctx, ways, M, C, Hd):
+    from paper_2507_05753_amd.layer import JigsawMLP
+    X, W1, b1 = inputs.layer_inputs(350, M, C, Hd, "R", bias=True)
+    W2 = inputs.matrix(351, C, Hd, "R", inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(352, 1, C, "R")[0]
+    dY = inputs.matrix(353, M, C, "R")
+    with JigsawMLP(M, C, Hd, ways, ctx=ctx) as L:
+        L.shard(dev(X), dev(W1), dev(b1), dev(W2), dev(b2))
+        L.forward()
+        L.backward(dev(dY))
+        g = check_mlp_backward(L, X, W1, b1, W2, dY, ways)
+        L.backward(dev(dY))                                    # nothing it reads was overwritten: the same again
+        assert np.array_equal(g["dx"], L.gather_grad("dx").cpu().numpy())
+        assert np.array_equal(g["dw1"], L.gather_grad("dw1").cpu().numpy())
+    # end to end against the oracle's own chain (A is recomputed in FP32 here, in double there)
+    r = oracle.mlp_backward(X, W1, b1, W2, dY)
+    for name in ("dx", "dw1", "dw2"):
+        ref = r["dX" if name == "dx" else "dW1" if name == "dw1" else "dW2"]
+        assert np.all(np.abs(g[name] - ref) <= 1e-4 * (np.abs(ref) + np.abs(ref).max())), name
