@@ -445,6 +445,20 @@ def mixing_block(ways: int, X, gamma, beta, W1, b1, W2, b2, eps: float = LN_EPS)
     return out
 
 
+def mixing_block_backward(ways: int, X, gamma, beta, W1, b1, W2, dY, eps: float = LN_EPS):
+    """Gradients of mixing_block (Y = X + MLP(layernorm(X))) for an incoming gradient dY, in double: the MLP's
+    backward on Xn without its skip connection, then the norm's backward, then the block's own skip connection;
+    Xn and dXn handed on in FP32.  Returns the dict of mlp_backward (its dX is replaced by the block's) plus dXn,
+    dgamma, dbeta."""
+    G = np.asarray(dY, dtype=np.float64)
+    Xn32 = layernorm(X, gamma, beta, ln_groups(ways), eps).astype(np.float32)
+    r = mlp_backward(Xn32, W1, b1, W2, dY)
+    dXn = r["dX"] - G                               # the MLP's share: dA W1
+    dXl, dgamma, dbeta = layernorm_backward(X, gamma, dXn.astype(np.float32), ln_groups(ways), eps)
+    r.update(dXn=dXn, dX=G + dXl, dgamma=dgamma, dbeta=dbeta)
+    return r
+
+
 def mixing_block_reduced(ways: int, X, gamma, beta, W1, b1, W2, b2, terms: int = 1, eps: float = LN_EPS):
     """mixing_block with the MLP's two products in mixed precision (mlp_reduced); the layer norm, its FP32
     output Xn and the skip connection stay in full precision."""

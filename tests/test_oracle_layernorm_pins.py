@@ -335,3 +335,31 @@ def test_layernorm_backward_invariants():
     assert all(np.array_equal(u, v) for u, v in zip(a, b))
     with pytest.raises(RuntimeError):
         oracle.layernorm_backward(X[:, :9], None, dY[:, :9], 2)
+
+
+@pytest.mark.parametrize("ways", [1, 2])
+def test_mixing_block_backward_against_the_library_autograd_in_double(ways):
+    M, C, Hd = 6, 8, 10
+    X, gamma, beta, W1, _, W2, b2 = block_operands(40, M, C, Hd)
+    b1 = inputs.matrix(42, 1, Hd, "R")[0]
+    dY = inputs.matrix(41, M, C, "R")
+    groups = oracle.ln_groups(ways)
+    n = C // groups
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64)).requires_grad_(True)
+    Xt, gt, bt, W1t, b1t, W2t, b2t = t(X), t(gamma), t(beta), t(W1), t(b1), t(W2), t(b2)
+    Xn = torch.cat([torch.nn.functional.layer_norm(Xt[:, k * n:(k + 1) * n], (n,), gt[k * n:(k + 1) * n],
+                                                   bt[k * n:(k + 1) * n], EPS) for k in range(groups)], dim=1)
+    Y = Xt + torch.nn.functional.gelu(Xn @ W1t.T + b1t) @ W2t.T + b2t
+    Y.backward(torch.from_numpy(dY).double())
+    r = oracle.mixing_block_backward(ways, X, gamma, beta, W1, b1, W2, dY)
+    for name, ref in (("dX", Xt.grad), ("dgamma", gt.grad), ("dbeta", bt.grad), ("dW1", W1t.grad), ("db1", b1t.grad),
+                      ("dW2", W2t.grad), ("db2", b2t.grad)):
+        ref = ref.numpy()
+        # Xn, H, dA and dXn are handed on in FP32 by the method
+        assert np.all(np.abs(r[name] - ref) <= 2e-6 * (np.abs(ref) + np.abs(ref).max())), name
+    # the pieces in sequence
+    Xn32 = oracle.layernorm(X, gamma, beta, groups).astype(np.float32)
+    m = oracle.mlp_backward(Xn32, W1, b1, W2, dY)
+    assert np.array_equal(r["dXn"], m["dX"] - dY) and np.array_equal(r["dW1"], m["dW1"])
+    dXl, dg, db = oracle.layernorm_backward(X, gamma, r["dXn"].astype(np.float32), groups)
+    assert np.array_equal(r["dX"], dY + dXl) and np.array_equal(r["dgamma"], dg) and np.array_equal(r["dbeta"], db)
