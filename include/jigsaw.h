@@ -393,6 +393,23 @@ int jg_mlp_backward(const jg_plan* first, const jg_plan* second, const float* co
                     float* const* dx_sh, float* const* dw1_sh, float* const* db1_sh, float* const* dw2_sh,
                     float* const* db2_sh, void* workspace, size_t workspace_bytes);
 
+/* run (backward, channel-mixing block).  Gradients of jg_mixing_forward's block  Xn = layernorm(X),
+ * Y = X + MLP(Xn)  (Sec. 3: the block; Sec. 4.1 and Sec. 5 "Layer norms": its parts) for an incoming gradient dY:
+ * jg_mlp_backward's chain on Xn without that function's skip connection (dXn = dA W1), then jg_layernorm_backward's
+ * formulas with the block's skip connection added before the one rounding:  dX = dY + layernorm'(dXn).
+ * FP32 plans.  x_sh, gamma, eps, w1_sh, b1_sh, w2_sh: as in the forward; xn_sh, h_sh: the Xn and H it stored;
+ * dy_sh: the dY shards.  Outputs: a_sh, dh_sh, da_sh, dw1_sh, db1_sh, dw2_sh, db2_sh as in jg_mlp_backward; dxn_sh
+ * and dx_sh shaped like X_r; dgamma, dbeta as in jg_layernorm_backward (either may be NULL).  No output may overlap
+ * an input or another output.  workspace: 256-byte aligned, at least the largest of what jg_mlp_backward and
+ * jg_layernorm_backward ask for on these plans.
+ * Errors: those of jg_mlp_backward and jg_layernorm_backward. */
+int jg_mixing_backward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* gamma,
+                       double eps, const float* const* xn_sh, const float* const* w1_sh, const float* const* b1_sh,
+                       const float* const* w2_sh, const float* const* h_sh, const float* const* dy_sh,
+                       float* const* a_sh, float* const* dh_sh, float* const* da_sh, float* const* dxn_sh,
+                       float* const* dx_sh, float* const* dw1_sh, float* const* db1_sh, float* const* dw2_sh,
+                       float* const* db2_sh, float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes);
+
 /* run (backward, layer norm).  Gradients of jg_layernorm_forward's output for an incoming gradient dY (shaped and
  * partitioned like X_r), per row of X_r over the channels the rank holds, with xhat = (x - mu) / sqrt(var + eps)
  * and g = dY * gamma:

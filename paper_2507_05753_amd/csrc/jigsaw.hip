@@ -997,15 +997,21 @@ static int layernorm_impl(const jg_plan* plan, const float* const* x_sh, const f
     return HIP_OK(jg::launch_norm_group(g, c->stream)) ? JG_OK : JG_E_HIP;
 }
 
-int jg_layernorm_backward(const jg_plan* plan, const float* const* x_sh, const float* gamma, double eps,
-                          const float* const* dy_sh, float* const* dx_sh, float* dgamma, float* dbeta, void* workspace,
-                          size_t workspace_bytes)
+// add_sh (or nullptr): per rank a block shaped like X_r that is added to dX_r before its rounding
+static int layernorm_backward_impl(const jg_plan* plan, const float* const* x_sh, const float* gamma, double eps,
+                                   const float* const* dy_sh, float* const* dx_sh, float* dgamma, float* dbeta,
+                                   void* workspace, size_t workspace_bytes, const float* const* add_sh)
 {
     if (!plan || !plan->ctx) return JG_E_NULL;
     const jg_linear_desc& d = plan->d;
     if (int rc = check_ptr_array(x_sh, d.ways)) return rc;
     if (int rc = check_ptr_array(dy_sh, d.ways)) return rc;
     if (int rc = check_ptr_array(dx_sh, d.ways)) return rc;
+    if (add_sh) {
+        if (int rc = check_ptr_array(add_sh, d.ways)) return rc;
+        for (int r = 0; r < d.ways; ++r)
+            if (!aligned(add_sh[r], 4)) return JG_E_ALIGN;
+    }
     if (!(eps >= 0.0)) return JG_E_DTYPE;
     if (!aligned(gamma, 4) || !aligned(dgamma, 4) || !aligned(dbeta, 4)) return JG_E_ALIGN;
     for (int r = 0; r < d.ways; ++r)
@@ -1026,7 +1032,8 @@ int jg_layernorm_backward(const jg_plan* plan, const float* const* x_sh, const f
         int64_t rb, cb;
         block_coords(d.ways, r, &rb, &cb);
         stats[r] = reinterpret_cast<double*>(static_cast<char*>(workspace) + r * stats_bytes);
-        g.b[r] = {x_sh[r], dy_sh[r], dx_sh[r], gamma ? gamma + cb * plan->xc : nullptr, stats[r]};
+        g.b[r] = {x_sh[r], dy_sh[r], dx_sh[r], gamma ? gamma + cb * plan->xc : nullptr, stats[r],
+                  add_sh ? add_sh[r] : nullptr};
     }
     // the channel blocks: one per rank (1-, 2-way), or per column of the 2 x 2 grid, summed over its two row halves
     jg::NormBwdColsGroup cg;
@@ -1050,6 +1057,14 @@ int jg_layernorm_backward(const jg_plan* plan, const float* const* x_sh, const f
     }
     ScopedTimer t(c, JG_KERNEL_NORM);
     return HIP_OK(jg::launch_norm_bwd(g, cg, c->stream)) ? JG_OK : JG_E_HIP;
+}
+
+int jg_layernorm_backward(const jg_plan* plan, const float* const* x_sh, const float* gamma, double eps,
+                          const float* const* dy_sh, float* const* dx_sh, float* dgamma, float* dbeta, void* workspace,
+                          size_t workspace_bytes)
+{
+    return layernorm_backward_impl(plan, x_sh, gamma, eps, dy_sh, dx_sh, dgamma, dbeta, workspace, workspace_bytes,
+                                   nullptr);
 }
 
 int jg_bias_backward(const jg_plan* plan, const float* const* dy_sh, float* const* db_sh)
@@ -1227,20 +1242,28 @@ int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* con
                      false);
 }
 
-int jg_mlp_backward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* const* w1_sh,
-                    const float* const* b1_sh, const float* const* w2_sh, const float* const* h_sh,
-                    const float* const* dy_sh, float* const* a_sh, float* const* dh_sh, float* const* da_sh,
-                    float* const* dx_sh, float* const* dw1_sh, float* const* db1_sh, float* const* dw2_sh,
-                    float* const* db2_sh, void* workspace, size_t workspace_bytes)
+static size_t mlp_backward_workspace(const jg_plan* first, const jg_plan* second)
+{
+    size_t need = first->ws_bytes;
+    if (first->bw_ws_bytes > need) need = first->bw_ws_bytes;
+    if (second->bw_ws_bytes > need) need = second->bw_ws_bytes;
+    return need;
+}
+
+// with_skip: dX = dY + dA W1 (the MLP with its skip connection); otherwise dx_sh receives dA W1 alone
+static int mlp_backward_impl(const jg_plan* first, const jg_plan* second, const float* const* x_sh,
+                             const float* const* w1_sh, const float* const* b1_sh, const float* const* w2_sh,
+                             const float* const* h_sh, const float* const* dy_sh, float* const* a_sh,
+                             float* const* dh_sh, float* const* da_sh, float* const* dx_sh, float* const* dw1_sh,
+                             float* const* db1_sh, float* const* dw2_sh, float* const* db2_sh, void* workspace,
+                             size_t workspace_bytes, bool with_skip)
 {
     if (int rc = check_mlp_chain(first, second)) return rc;
     if (first->d.dtype != JG_F32) return JG_E_DTYPE;
     const int ways = first->d.ways;
     for (float* const* arr : {a_sh, dh_sh, da_sh, db1_sh, db2_sh})
         if (int rc = check_ptr_array(arr, ways)) return rc;
-    size_t need = first->ws_bytes;
-    if (first->bw_ws_bytes > need) need = first->bw_ws_bytes;
-    if (second->bw_ws_bytes > need) need = second->bw_ws_bytes;
+    const size_t need = mlp_backward_workspace(first, second);
     if (need > 0) {
         if (!workspace || workspace_bytes < need) return JG_E_WORKSPACE;
         if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
@@ -1271,7 +1294,7 @@ int jg_mlp_backward(const jg_plan* first, const jg_plan* second, const float* co
     rc = jg_linear_backward(first, x_sh, w1_sh, da_sh, dx_sh, dw1_sh, workspace, workspace_bytes);
     if (rc != JG_OK) return rc;
     rc = jg_bias_backward(first, da_sh, db1_sh);
-    if (rc != JG_OK) return rc;
+    if (rc != JG_OK || !with_skip) return rc;
     // the skip connection: dX = dY + dA W1 (dY_r and dX_r are both shaped like X_r)
     jg::CombineGroup cb;
     std::memset(&cb, 0, sizeof(cb));
@@ -1282,6 +1305,38 @@ int jg_mlp_backward(const jg_plan* first, const jg_plan* second, const float* co
     for (int r = 0; r < ways; ++r) cb.b[r] = {dx_sh[r], dy_sh[r], nullptr, dx_sh[r], nullptr};
     ScopedTimer t(c, JG_KERNEL_COMBINE);
     return HIP_OK(jg::launch_combine_group(cb, c->stream)) ? JG_OK : JG_E_HIP;
+}
+
+int jg_mlp_backward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* const* w1_sh,
+                    const float* const* b1_sh, const float* const* w2_sh, const float* const* h_sh,
+                    const float* const* dy_sh, float* const* a_sh, float* const* dh_sh, float* const* da_sh,
+                    float* const* dx_sh, float* const* dw1_sh, float* const* db1_sh, float* const* dw2_sh,
+                    float* const* db2_sh, void* workspace, size_t workspace_bytes)
+{
+    return mlp_backward_impl(first, second, x_sh, w1_sh, b1_sh, w2_sh, h_sh, dy_sh, a_sh, dh_sh, da_sh, dx_sh, dw1_sh,
+                             db1_sh, dw2_sh, db2_sh, workspace, workspace_bytes, true);
+}
+
+int jg_mixing_backward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* gamma,
+                       double eps, const float* const* xn_sh, const float* const* w1_sh, const float* const* b1_sh,
+                       const float* const* w2_sh, const float* const* h_sh, const float* const* dy_sh,
+                       float* const* a_sh, float* const* dh_sh, float* const* da_sh, float* const* dxn_sh,
+                       float* const* dx_sh, float* const* dw1_sh, float* const* db1_sh, float* const* dw2_sh,
+                       float* const* db2_sh, float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes)
+{
+    if (int rc = check_mlp_chain(first, second)) return rc;
+    if (int rc = check_ptr_array(dxn_sh, first->d.ways)) return rc;
+    size_t need = mlp_backward_workspace(first, second);
+    const size_t stats = round_up(16 * (size_t)first->xr, kWsAlign) * first->d.ways;
+    if (stats > need) need = stats;
+    if (!workspace || workspace_bytes < need) return JG_E_WORKSPACE;
+    // the MLP on Xn, without a skip connection of its own: dXn = dA W1
+    int rc = mlp_backward_impl(first, second, xn_sh, w1_sh, b1_sh, w2_sh, h_sh, dy_sh, a_sh, dh_sh, da_sh, dxn_sh,
+                               dw1_sh, db1_sh, dw2_sh, db2_sh, workspace, workspace_bytes, false);
+    if (rc != JG_OK) return rc;
+    // the norm's backward, with the block's skip connection added before dX is rounded
+    return layernorm_backward_impl(first, x_sh, gamma, eps, dxn_sh, dx_sh, dgamma, dbeta, workspace, workspace_bytes,
+                                   dy_sh);
 }
 
 // X [T x C] -> H [C x D] (transposed layer) -> Y [T x C] (plain layer, W2 in the activations' place, H in the weights')

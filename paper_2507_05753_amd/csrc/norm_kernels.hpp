@@ -182,6 +182,7 @@ struct NormBwdBlock {
     float* dx;           // rows x cols, dense
     const float* gamma;  // the block's cols scale factors, or nullptr (1)
     double* stats;       // rows x 2: mu, rstd (written by the row kernel, read by the column kernel)
+    const float* add;    // rows x cols, dense, added to dx before its one rounding (a skip connection), or nullptr
 };
 
 struct NormBwdGroup {
@@ -231,7 +232,8 @@ __global__ __launch_bounds__(NORM_THREADS) void layernorm_bwd_rows_f32(const Nor
     for (int c = tid; c < g.cols; c += NORM_THREADS) {
         const double gv = (double)dy[c] * (B.gamma ? (double)B.gamma[c] : 1.0);
         const double xh = ((double)x[c] - mu) * rstd;
-        dx[c] = (float)((gv - mg - xh * mgx) * rstd);
+        const double o = (gv - mg - xh * mgx) * rstd;
+        dx[c] = (float)(B.add ? o + (double)B.add[off + c] : o);
     }
     if (tid == 0) {
         B.stats[2 * (int64_t)blockIdx.x] = mu;
@@ -298,16 +300,22 @@ __global__ __launch_bounds__(NORM_THREADS) void layernorm_bwd_rows_reg_f32(const
 #pragma unroll
     for (int i = 0; i < NV; ++i) asm volatile("" : "+v"(v[i]), "+v"(d[i]));
     vf4* dxp = reinterpret_cast<vf4*>(B.dx + (int64_t)row * g.cols);
+    const vf4* addp = B.add ? reinterpret_cast<const vf4*>(B.add + (int64_t)row * g.cols) : nullptr;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int c = i * 64 + lane;
         if (c < nvec) {
             const vf4 ga = gamma ? gamma[c] : vf4{1.f, 1.f, 1.f, 1.f};
+            const vf4 ad = addp ? addp[c] : vf4{0.f, 0.f, 0.f, 0.f};
             vf4 o;
-            o.x = (float)(((double)d[i].x * (double)ga.x - mg - (((double)v[i].x - mu) * rstd) * mgx) * rstd);
-            o.y = (float)(((double)d[i].y * (double)ga.y - mg - (((double)v[i].y - mu) * rstd) * mgx) * rstd);
-            o.z = (float)(((double)d[i].z * (double)ga.z - mg - (((double)v[i].z - mu) * rstd) * mgx) * rstd);
-            o.w = (float)(((double)d[i].w * (double)ga.w - mg - (((double)v[i].w - mu) * rstd) * mgx) * rstd);
+            o.x = (float)(((double)d[i].x * (double)ga.x - mg - (((double)v[i].x - mu) * rstd) * mgx) * rstd +
+                          (double)ad.x);
+            o.y = (float)(((double)d[i].y * (double)ga.y - mg - (((double)v[i].y - mu) * rstd) * mgx) * rstd +
+                          (double)ad.y);
+            o.z = (float)(((double)d[i].z * (double)ga.z - mg - (((double)v[i].z - mu) * rstd) * mgx) * rstd +
+                          (double)ad.z);
+            o.w = (float)(((double)d[i].w * (double)ga.w - mg - (((double)v[i].w - mu) * rstd) * mgx) * rstd +
+                          (double)ad.w);
             dxp[c] = o;
         }
     }
@@ -331,7 +339,8 @@ inline bool norm_bwd_rows_fit(const NormBwdGroup& g)
     if ((g.cols & 3) || g.cols / 4 > 64 * kNormBwdMaxVectorsPerLane) return false;
     for (int i = 0; i < g.nblocks; ++i) {
         const NormBwdBlock& b = g.b[i];
-        if (((uintptr_t)b.x & 15) || ((uintptr_t)b.dy & 15) || ((uintptr_t)b.dx & 15) || ((uintptr_t)b.gamma & 15))
+        if (((uintptr_t)b.x & 15) || ((uintptr_t)b.dy & 15) || ((uintptr_t)b.dx & 15) || ((uintptr_t)b.gamma & 15) ||
+            ((uintptr_t)b.add & 15))
             return false;
     }
     return true;

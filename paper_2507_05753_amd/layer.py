@@ -256,7 +256,7 @@ class JigsawMLP:
         if name in ("a", "dh", "da"):
             out = torch.empty((self.M, self.Hd), dtype=torch.float32, device=dev)
             jg.jg_gather_as(f.plan, jg.JG_T_Y, p(g[name]), out.data_ptr(), out.stride(0))
-        elif name == "dx":
+        elif name in ("dx", "dxn"):
             out = torch.empty((self.M, self.C), dtype=torch.float32, device=dev)
             jg.jg_gather_as(f.plan, jg.JG_T_X_F32, p(g[name]), out.data_ptr(), out.stride(0))
         elif name in ("dw1", "dw2"):
@@ -309,6 +309,29 @@ class JigsawMixing(JigsawMLP):
         out = torch.empty((self.M, self.C), dtype=torch.float32, device=self.first.dev)
         jg.jg_gather_as(self.first.plan, jg.JG_T_X_F32, [t.data_ptr() for t in self.xn], out.data_ptr(), out.stride(0))
         return out
+
+    def backward(self, dY):
+        """Gradients of the block for an incoming gradient dY (M, C), after forward(): jg_mixing_backward.  Beside
+        the MLP's (JigsawMLP.backward) the holder keeps 'dxn' shards and the global vectors ``dgamma`` / ``dbeta``."""
+        f, s = self.first, self.second
+        assert self.dtype == jg.JG_F32 and dY.is_cuda and dY.dtype == torch.float32 and dY.shape == (self.M, self.C)
+        if getattr(self, "grads", None) is None:
+            like = lambda ts: [torch.empty_like(t) for t in ts]
+            self.grads = dict(dy=like(s.y), a=like(f.y), dh=like(f.y), da=like(f.y), dxn=like(self.xin),
+                              dx=like(self.xin), dw1=like(f.w), db1=like(f.b), dw2=like(s.w), db2=like(s.b))
+            self.dgamma = torch.empty((self.C,), dtype=torch.float32, device=f.dev)
+            self.dbeta = torch.empty((self.C,), dtype=torch.float32, device=f.dev)
+            need = max(f.query(jg.JG_Q_WORKSPACE_BYTES), f.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES),
+                       s.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES), f.query(jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES))
+            self.bw_ws = torch.empty((need,), dtype=torch.uint8, device=f.dev)
+            self.bw_ws_bytes = need
+        g = self.grads
+        p = lambda ts: [t.data_ptr() for t in ts]
+        jg.jg_shard(s.plan, jg.JG_T_Y, dY.data_ptr(), dY.stride(0), p(g["dy"]))
+        jg.jg_mixing_backward(f.plan, s.plan, p(self.xin), self.gamma.data_ptr() if self.gamma is not None else None,
+                              self.eps, p(self.xn), p(f.w), p(f.b), p(s.w), p(f.y), p(g["dy"]), p(g["a"]), p(g["dh"]),
+                              p(g["da"]), p(g["dxn"]), p(g["dx"]), p(g["dw1"]), p(g["db1"]), p(g["dw2"]), p(g["db2"]),
+                              self.dgamma.data_ptr(), self.dbeta.data_ptr(), self.bw_ws.data_ptr(), self.bw_ws_bytes)
 
 
 class JigsawTokenMixing:

@@ -426,3 +426,23 @@ def test_layernorm_backward_checks_its_arguments():
     # two doubles per row of a rank's block, in 256-byte pieces
     assert jg.jg_plan_query(a, jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES) == 2 * ((16 * 64 + 255) // 256 * 256)
     jg.jg_plan_destroy(a)
+
+
+def test_mlp_and_mixing_backward_check_that_the_plans_chain():
+    lib = jg.raw()
+    arr = (ctypes.c_void_p * 2)(256, 512)
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    mlp = lambda a, b: lib.jg_mlp_backward(a, b, *([pp] * 14), 256, 1 << 20)
+    mix = lambda a, b: lib.jg_mixing_backward(a, b, pp, None, 1e-5, *([pp] * 15), None, None, 256, 1 << 20)
+    a = jg.jg_plan_create(None, 64, 32, 48, 2, True)
+    for call in (mlp, mix):
+        assert call(None, a) == jg.JG_E_NULL and call(a, None) == jg.JG_E_NULL
+        for (M, K, N), ways, want in (((64, 48, 30), 2, jg.JG_E_SHAPE), ((62, 48, 32), 2, jg.JG_E_SHAPE),
+                                      ((64, 48, 32), 4, jg.JG_E_WAYS), ((64, 48, 32), 2, jg.JG_E_NULL)):
+            b = jg.jg_plan_create(None, M, K, N, ways, True)
+            assert call(a, b) == want
+            jg.jg_plan_destroy(b)
+        t = jg.jg_plan_create(None, 48, 64, 32, 2, True, op=jg.JG_OP_XTW)
+        assert call(a, t) == jg.JG_E_DTYPE
+        jg.jg_plan_destroy(t)
+    jg.jg_plan_destroy(a)

@@ -215,8 +215,9 @@ def test_channel_mixing_size(jg, capsys):
 # ---------------------------------------------------------------------------------------------
 # backward of the MLP: the chain rule through the layers' backward passes, checked step by step
 # ---------------------------------------------------------------------------------------------
-def check_mlp_backward(L, X, W1, b1, W2, dY, ways):
-    g = {k: L.gather_grad(k).cpu().numpy() for k in ("a", "dh", "da", "dx", "dw1", "dw2", "db1", "db2")}
+def check_mlp_backward(L, X, W1, b1, W2, dY, ways, xkey="dx"):
+    """xkey "dx": the MLP with its skip connection; "dxn": the MLP inside a block, dA W1 alone."""
+    g = {k: L.gather_grad(k).cpu().numpy() for k in ("a", "dh", "da", xkey, "dw1", "dw2", "db1", "db2")}
     H = L.gather_h().cpu().numpy()
     f64 = lambda a: a.astype(np.float64)
     rel = lambda err, S: (err / np.maximum(S, 1e-300)).max()
@@ -236,8 +237,9 @@ def check_mlp_backward(L, X, W1, b1, W2, dY, ways):
     # first layer's backward from the dA the GPU stored, plus the skip connection
     dX64, dW164 = oracle.backward(X, W1, g["da"])
     SX, SW1 = oracle.backward_magnitude(X, W1, g["da"])
-    ex = np.abs(f64(g["dx"]) - (dX64 + f64(dY)))
-    assert np.all(ex <= 1e-6 * (SX + np.abs(dY))), f"dX: {rel(ex, SX + np.abs(dY)):.2e}"
+    skip = f64(dY) if xkey == "dx" else 0.0
+    ex = np.abs(f64(g[xkey]) - (dX64 + skip))
+    assert np.all(ex <= 1e-6 * (SX + np.abs(skip))), f"{xkey}: {rel(ex, SX + np.abs(skip)):.2e}"
     assert np.all(np.abs(f64(g["dw1"]) - dW164) <= 1e-6 * SW1), f"dW1: {rel(np.abs(f64(g['dw1']) - dW164), SW1):.2e}"
     db1 = oracle.bias_backward(g["da"])
     assert np.all(np.abs(f64(g["db1"]) - db1) <= 2.0 ** -23 * np.abs(db1) + 1e-12 * oracle.bias_backward(g["da"], absolute=True))
@@ -265,3 +267,40 @@ def test_mlp_backward(jg, ctx, ways, M, C, Hd):
     for name in ("dx", "dw1", "dw2"):
         ref = r["dX" if name == "dx" else "dW1" if name == "dw1" else "dW2"]
         assert np.all(np.abs(g[name] - ref) <= 1e-4 * (np.abs(ref) + np.abs(ref).max())), name
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,C,Hd", [(100, 100, 100), (130, 72, 258), (258, 264, 136), (300, 520, 1032)])
+def test_mixing_block_backward(jg, ctx, ways, M, C, Hd):
+    from paper_2507_05753_amd.layer import JigsawMixing
+    X, W1, b1 = inputs.layer_inputs(360, M, C, Hd, "R", bias=True)
+    X = (X + np.float32(0.25)).astype(np.float32)
+    W2 = inputs.matrix(361, C, Hd, "R", inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(362, 1, C, "R")[0]
+    dY = inputs.matrix(363, M, C, "R")
+    gamma = (inputs.matrix(364, 1, C, "R")[0] + np.float32(1.5)).astype(np.float32)
+    beta = inputs.matrix(365, 1, C, "R")[0]
+    HALF_ULP = 2.0 ** -24
+    with JigsawMixing(M, C, Hd, ways, ctx=ctx) as L:
+        L.shard(dev(X), dev(gamma), dev(beta), dev(W1), dev(b1), dev(W2), dev(b2))
+        L.forward()
+        L.backward(dev(dY))
+        Xn = L.gather_xn().cpu().numpy()
+        # the MLP's chain on the Xn the forward stored, without a skip connection of its own
+        g = check_mlp_backward(L, Xn, W1, b1, W2, dY, ways, xkey="dxn")
+        # the norm's backward from the dXn the GPU stored, the block's skip connection added before the rounding
+        dXl, dg, db, SX, Sg, Sb = oracle.layernorm_backward(X, gamma, g["dxn"], oracle.ln_groups(ways), magnitude=True)
+        want = dY.astype(np.float64) + dXl
+        dx = L.gather_grad("dx").cpu().numpy()
+        assert np.all(np.abs(dx - want) <= HALF_ULP * np.abs(want) * (1 + 1e-6) + 1e-11 * (SX + np.abs(dY)) + 1e-45)
+        dgam, dbet = L.dgamma.cpu().numpy(), L.dbeta.cpu().numpy()
+        assert np.all(np.abs(dgam - dg) <= HALF_ULP * np.abs(dg) * (1 + 1e-6) + 1e-11 * Sg + 1e-45)
+        assert np.all(np.abs(dbet - db) <= HALF_ULP * np.abs(db) * (1 + 1e-6) + 1e-11 * Sb + 1e-45)
+        L.backward(dev(dY))                                    # nothing it reads was overwritten: the same again
+        assert np.array_equal(dx, L.gather_grad("dx").cpu().numpy())
+        assert np.array_equal(dgam, L.dgamma.cpu().numpy())
+    # end to end against the oracle's own chain (Xn and A in FP32 here differ in the last bits from the oracle's)
+    r = oracle.mixing_block_backward(ways, X, gamma, beta, W1, b1, W2, dY)
+    for got, name in ((dx, "dX"), (g["dw1"], "dW1"), (g["dw2"], "dW2"), (dgam, "dgamma"), (dbet, "dbeta")):
+        ref = r[name]
+        assert np.all(np.abs(got - ref) <= 1e-4 * (np.abs(ref) + np.abs(ref).max())), name
