@@ -247,6 +247,15 @@ def jigsaw_xtw(ways: int, X, W, b=None, nthreads: int | None = None) -> np.ndarr
     return Y
 
 
+def backward_xtw(X, W, dY, nthreads: int | None = None, absolute: bool = False):
+    """(dX64, dW64) of the transposed layer Y = X^T W (X [T x C], W [T x D], dY [C x D]) by the definition:
+    dX[t][c] = sum_d W[t][d] dY[c][d]  and  dW[t][d] = sum_c X[t][c] dY[c][d],  in double - each is a product of
+    the form A B^T, evaluated by the forward layer's routine (magnitudes if ``absolute``)."""
+    G = np.ascontiguousarray(dY, dtype=np.float32)
+    f = magnitude if absolute else linear
+    return f(W, G, None, nthreads), f(X, np.ascontiguousarray(G.T), None, nthreads)
+
+
 def gelu(a) -> np.ndarray:
     """x * Phi(x), element by element, in double."""
     a = np.ascontiguousarray(a, dtype=np.float64)

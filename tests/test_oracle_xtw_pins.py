@@ -155,3 +155,40 @@ def test_argument_checks():
     with pytest.raises(RuntimeError):
         oracle.jigsaw_xtw(3, X, W, b)
     assert oracle.jigsaw_xtw(2, X, W, b).shape == (6, 4)
+
+
+# ---- backward of the transposed layer -------------------------------------------------------------------------
+@pytest.mark.parametrize("T,C,D", [(2, 3, 4), (5, 7, 3), (6, 4, 9)])
+def test_backward_xtw_integer_brute_force(T, C, D):
+    X, W, G = rng_ints(81, (T, C)), rng_ints(82, (T, D)), rng_ints(83, (C, D))
+    dX = [[sum(int(W[t, d]) * int(G[c, d]) for d in range(D)) for c in range(C)] for t in range(T)]
+    dW = [[sum(int(X[t, c]) * int(G[c, d]) for c in range(C)) for d in range(D)] for t in range(T)]
+    got = oracle.backward_xtw(X.astype(np.float32), W.astype(np.float32), G.astype(np.float32))
+    assert np.array_equal(got[0], np.array(dX, dtype=np.float64))
+    assert np.array_equal(got[1], np.array(dW, dtype=np.float64))
+    mag = oracle.backward_xtw(X.astype(np.float32), W.astype(np.float32), G.astype(np.float32), absolute=True)
+    assert np.array_equal(mag[0], np.abs(W).astype(np.float64) @ np.abs(G).T)
+    assert np.array_equal(mag[1], np.abs(X).astype(np.float64) @ np.abs(G))
+
+
+@pytest.mark.parametrize("T,C,D", [(12, 10, 14), (33, 64, 18)])
+def test_backward_xtw_is_the_adjoint_of_the_forward(T, C, D):
+    # <dY, X^T W> = <dX, X> = <dW, W>: both gradients are the adjoints of the same bilinear map (lattice values: exact)
+    X, W, _ = operands(84, T, C, D, "L", bias=False)
+    G = inputs.matrix(85, C, D, "L")
+    dX, dW = oracle.backward_xtw(X, W, G)
+    lhs = np.sum(G.astype(np.float64) * oracle.linear_xtw(X, W))
+    assert lhs == np.sum(dX * X) == np.sum(dW * W)
+    # and the library's autograd in double
+    import torch
+    Xt = torch.from_numpy(X).double().requires_grad_(True)
+    Wt = torch.from_numpy(W).double().requires_grad_(True)
+    (Xt.T @ Wt).backward(torch.from_numpy(G).double())
+    assert np.array_equal(dX, Xt.grad.numpy()) and np.array_equal(dW, Wt.grad.numpy())
+    # a transposed operand or a swapped role does not pass
+    if C != D:
+        with pytest.raises(AssertionError):
+            oracle.backward_xtw(X, W, np.ascontiguousarray(G.T))
+    wrong = oracle.backward_xtw(W[:, :min(C, D)], X[:, :min(C, D)], G[:min(C, D), :min(C, D)])
+    right = oracle.backward_xtw(X[:, :min(C, D)], W[:, :min(C, D)], G[:min(C, D), :min(C, D)])
+    assert not np.array_equal(wrong[0], right[0])
