@@ -370,8 +370,12 @@ int jg_token_mixing_forward(const jg_plan* first, const jg_plan* second, const f
  * X_r, W_r, Y_r); dx_sh, dw_sh: the same for the outputs (shapes of X_r, W_r).  `workspace`:
  * 256-byte-aligned device buffer of at least JG_Q_BACKWARD_WORKSPACE_BYTES bytes (may be NULL when
  * that is 0).  The bias gradient is jg_bias_backward's.  The plan's combine / weights options do not apply.
- * JG_OP_XWT plans only: a JG_OP_XTW plan returns JG_E_DTYPE.
- * Errors: JG_E_NULL, JG_E_DTYPE (op), JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
+ * A JG_OP_XTW plan (Y = X^T W; Sec. 4.1 / 4.2 applied to the token-mixing layer): dX = W dY^T and dW = X dY, with
+ * X_(i,a), W_(i,j), dY_(a,j) the plan's blocks (row half, column half; 2-way: one row range, and dY_r stacks
+ * dY_(0,r) over dY_(1,r)):   dX_(i,a) = sum_j W_(i,j) dY_(a,j)^T,   dW_(i,j) = sum_a X_(i,a) dY_(a,j),
+ * two launches each for ways >= 2 (the first term into a partial in the workspace, the second on top of it).
+ * FP32 plans only: a reduced-precision plan returns JG_E_DTYPE.
+ * Errors: JG_E_NULL, JG_E_DTYPE, JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
 int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
                        const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh,
                        void* workspace, size_t workspace_bytes);

@@ -312,11 +312,12 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     }
     p->ws_bytes = off;
     p->bw_dx_bytes = p->bw_dw_bytes = p->bw_off_dw = p->bw_ws_bytes = 0;
-    if (d.ways >= 2 && !xtw) {
+    if (d.ways >= 2 && !reduced) {
+        // one partial per rank for dX and (wherever dW sums two terms: 4-way, and the 2-way transposed layer) for dW
         p->bw_dx_bytes = round_up((size_t)p->xr * (size_t)p->xc * sizeof(float), kWsAlign);
         p->bw_off_dw = p->bw_dx_bytes * d.ways;
         p->bw_ws_bytes = p->bw_off_dw;
-        if (d.ways == 4) {
+        if (d.ways == 4 || xtw) {
             p->bw_dw_bytes = round_up((size_t)p->wr * (size_t)p->wc * sizeof(float), kWsAlign);
             p->bw_ws_bytes += p->bw_dw_bytes * d.ways;
         }
@@ -334,6 +335,9 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
         };
         if (xtw) {
             p->tail_bytes = need(d.ways == 1 ? 1 : 4, p->xc, p->wc, p->xr);
+            const size_t dx = need(d.ways, p->xr, p->xc, p->wc);
+            const size_t dw = need(d.ways, p->xr, p->wc, p->xc);
+            p->bw_tail_bytes = dx > dw ? dx : dw;
         } else {
             p->tail_bytes = need(d.ways, p->yr, p->yc, p->xc);
             const size_t dx = need(d.ways, p->xr, p->xc, p->yc);
@@ -366,7 +370,7 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     const bool xtw = d.op == JG_OP_XTW;
     const bool reduced = d.dtype != JG_F32;
     const int64_t eb = d.dtype == JG_BF16 ? 2 : 4;     // bytes per element of an X or W shard (split mode: hi + lo)
-    if ((xtw || reduced) && (what == JG_Q_BACKWARD_WORKSPACE_BYTES || what == JG_Q_BACKWARD_FLOPS_TOTAL ||
+    if (reduced && (what == JG_Q_BACKWARD_WORKSPACE_BYTES || what == JG_Q_BACKWARD_FLOPS_TOTAL ||
                 what == JG_Q_BACKWARD_GEMM_LAUNCHES || what == JG_Q_BACKWARD_TAIL_SCRATCH_BYTES))
         return JG_E_DTYPE;   // no backward for this op
     switch (what) {
@@ -403,7 +407,7 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     case JG_Q_GEMM_LAUNCHES: *out = (d.ways == 1 || (xtw && d.ways == 2)) ? 1 : 2; break;
     case JG_Q_BACKWARD_WORKSPACE_BYTES: *out = (int64_t)plan->bw_ws_bytes; break;
     case JG_Q_BACKWARD_FLOPS_TOTAL: *out = 4 * M * K * N; break;
-    case JG_Q_BACKWARD_GEMM_LAUNCHES: *out = d.ways == 1 ? 2 : d.ways == 2 ? 3 : 4; break;
+    case JG_Q_BACKWARD_GEMM_LAUNCHES: *out = d.ways == 1 ? 2 : (d.ways == 2 && !xtw) ? 3 : 4; break;
     case JG_Q_TAIL_SCRATCH_BYTES: *out = (int64_t)plan->tail_bytes; break;
     case JG_Q_BACKWARD_TAIL_SCRATCH_BYTES: *out = (int64_t)plan->bw_tail_bytes; break;
     case JG_Q_X_SHARD_BYTES: *out = 4 * plan->xr * plan->xcp; break;
@@ -859,13 +863,74 @@ int jg_linear_forward_ex(const jg_plan* plan, const float* const* x_sh, const fl
     return forward_impl(plan, x_sh, w_sh, b_sh, r_sh, activation, y_sh, workspace, workspace_bytes, nullptr);
 }
 
+// Backward of the transposed layer Y = X^T W (X [T x C], W [T x D], dY [C x D]); arguments already checked.
+//     dX = W dY^T  (contraction over D: both operands read along their rows, as in the forward of X W^T),
+//     dW = X dY    (contraction over C: dY read along its row stride).
+// Blocks: X_(i,a) = tokens half i, channels half a; W_(i,j); dY_(a,j) (2-way: i is the whole token range and
+// dY_r stacks dY_(0,r) over dY_(1,r)).  dX_(i,a) = sum_j W_(i,j) dY_(a,j)^T,  dW_(i,j) = sum_a X_(i,a) dY_(a,j):
+// two terms each, the first into a partial, the second on top of it.
+static int backward_xtw(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                        const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh, char* ws)
+{
+    const int ways = plan->d.ways;
+    const int tr = (int)plan->xr, ch = (int)plan->xc, dh = (int)plan->wc;     // tokens, channels, columns of a block
+    char* tail = plan->bw_tail_bytes ? ws + plan->bw_off_tail : nullptr;
+    jg::GemmGroup g;
+    std::memset(&g, 0, sizeof(g));
+    auto launch = [&](int layout, int kernel_class) -> bool {
+        return run_gemm(plan, g, layout, kernel_class, tail, plan->bw_tail_bytes);
+    };
+    if (ways == 1) {
+        g.nprob = 1; g.M = tr; g.N = ch; g.K = dh;
+        g.p[0] = {w_sh[0], dy_sh[0], dx_sh[0], nullptr, nullptr, dh, dh, ch, 0};
+        if (!launch(jg::kGemmNT, JG_KERNEL_GEMM_DX)) return JG_E_HIP;
+        g.M = tr; g.N = dh; g.K = ch;
+        g.p[0] = {x_sh[0], dy_sh[0], dw_sh[0], nullptr, nullptr, ch, dh, dh, 0};
+        return launch(jg::kGemmNN, JG_KERNEL_GEMM_DW) ? JG_OK : JG_E_HIP;
+    }
+    auto dx_part = [&](int r) { return reinterpret_cast<float*>(ws + r * plan->bw_dx_bytes); };
+    auto dw_part = [&](int r) { return reinterpret_cast<float*>(ws + plan->bw_off_dw + r * plan->bw_dw_bytes); };
+    // rank and block coordinates: 2-way rank r = (0, r); 4-way rank 2 i + j = (i, j)
+    const int rows = ways == 4 ? 2 : 1;
+    auto rk = [&](int i, int j) { return rows == 2 ? 2 * i + j : j; };
+    // dY_(a,j): on rank (a, j) in the 4-way form; block a of rank j's stacked pair in the 2-way form
+    const int64_t yblock = (int64_t)ch * dh;
+    auto dy_blk = [&](int a, int j) { return rows == 2 ? dy_sh[rk(a, j)] : dy_sh[j] + a * yblock; };
+    g.nprob = ways;
+    for (int pass = 0; pass < 2; ++pass) {      // dX_(i,a): term j = 1 - a, then term j = a
+        g.M = tr; g.N = ch; g.K = dh;
+        for (int i = 0; i < rows; ++i)
+            for (int a = 0; a < 2; ++a) {
+                const int r = rk(i, a), j = pass == 0 ? 1 - a : a;
+                if (pass == 0)
+                    g.p[r] = {w_sh[rk(i, j)], dy_blk(a, j), dx_part(r), nullptr, nullptr, dh, dh, ch, 0};
+                else
+                    g.p[r] = {w_sh[rk(i, j)], dy_blk(a, j), dx_sh[r], dx_part(r), nullptr, dh, dh, ch, ch};
+            }
+        if (!launch(jg::kGemmNT, JG_KERNEL_GEMM_DX)) return JG_E_HIP;
+    }
+    for (int pass = 0; pass < 2; ++pass) {      // dW_(i,j): term a = 1 - j, then term a = j
+        g.M = tr; g.N = dh; g.K = ch;
+        for (int i = 0; i < rows; ++i)
+            for (int j = 0; j < 2; ++j) {
+                const int r = rk(i, j), a = pass == 0 ? 1 - j : j;
+                if (pass == 0)
+                    g.p[r] = {x_sh[rk(i, a)], dy_blk(a, j), dw_part(r), nullptr, nullptr, ch, dh, dh, 0};
+                else
+                    g.p[r] = {x_sh[rk(i, a)], dy_blk(a, j), dw_sh[r], dw_part(r), nullptr, ch, dh, dh, dh};
+            }
+        if (!launch(jg::kGemmNN, JG_KERNEL_GEMM_DW)) return JG_E_HIP;
+    }
+    return JG_OK;
+}
+
 int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
                        const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh,
                        void* workspace, size_t workspace_bytes)
 {
     if (!plan || !plan->ctx) return JG_E_NULL;
     const jg_linear_desc& d = plan->d;
-    if (d.op != JG_OP_XWT || d.dtype != JG_F32) return JG_E_DTYPE;
+    if (d.dtype != JG_F32) return JG_E_DTYPE;
     const int ways = d.ways;
     if (int rc = check_ptr_array(x_sh, ways)) return rc;
     if (int rc = check_ptr_array(w_sh, ways)) return rc;
@@ -879,6 +944,7 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
     jg_ctx* c = plan->ctx;
     if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
     char* ws = static_cast<char*>(workspace);
+    if (d.op == JG_OP_XTW) return backward_xtw(plan, x_sh, w_sh, dy_sh, dx_sh, dw_sh, ws);
 
     // shard shapes: X_r is mr x kh, W_r is (wr) x kh, dY_r is mr x nh
     const int mr = (int)plan->xr, kh = (int)plan->xc, nh = (int)plan->yc;

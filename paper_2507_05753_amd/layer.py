@@ -121,8 +121,8 @@ class JigsawLinear:
             self.dy = [torch.empty_like(t) for t in self.y]
             self.dx = [torch.empty_like(t) for t in self.x]
             self.dw = [torch.empty_like(t) for t in self.w]
-            # (a transposed or reduced-precision plan has no dX / dW pass; its dY shards still serve the bias gradient)
-            has_backward = self.op == jg.JG_OP_XWT and self.dtype == jg.JG_F32
+            # (a reduced-precision plan has no dX / dW pass; its dY shards still serve the bias gradient)
+            has_backward = self.dtype == jg.JG_F32
             self.bw_ws_bytes = self.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES) if has_backward else 0
             self.bw_ws = torch.empty((max(self.bw_ws_bytes, 1),), dtype=torch.uint8, device=self.dev)
 
@@ -148,12 +148,12 @@ class JigsawLinear:
         return self.db
 
     def gather_dx(self):
-        out = torch.empty((self.M, self.K), dtype=torch.float32, device=self.dev)
+        out = torch.empty(self.x_shape, dtype=torch.float32, device=self.dev)
         jg.jg_gather_as(self.plan, jg.JG_T_X, [t.data_ptr() for t in self.dx], out.data_ptr(), out.stride(0))
         return out
 
     def gather_dw(self):
-        out = torch.empty((self.N, self.K), dtype=torch.float32, device=self.dev)
+        out = torch.empty(self.w_shape, dtype=torch.float32, device=self.dev)
         jg.jg_gather_as(self.plan, jg.JG_T_W, [t.data_ptr() for t in self.dw], out.data_ptr(), out.stride(0))
         return out
 

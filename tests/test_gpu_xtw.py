@@ -141,13 +141,52 @@ def test_same_sign_operands_stay_within_tolerance(jg, ctx):
         assert np.all(err <= TOL * S), f"ways={ways}: {(err / S).max():.3e}"
 
 
-def test_backward_is_refused(jg, ctx):
+def run_backward(jg, ctx, X, W, dY, ways):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    K, M = X.shape
+    N = W.shape[1]
+    with JigsawLinear(M, K, N, ways, ctx=ctx, op=jg.JG_OP_XTW) as L:
+        L.shard(dev(X), dev(W))
+        L.shard_dy(dev(dY))
+        L.backward()
+        dX, dW = L.gather_dx().cpu().numpy(), L.gather_dw().cpu().numpy()
+        L.backward()        # the inputs are untouched: the same again
+        assert np.array_equal(dX, L.gather_dx().cpu().numpy()) and np.array_equal(dW, L.gather_dw().cpu().numpy())
+    return dX, dW
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("K,M,N", [(2, 2, 2), (100, 100, 100), (130, 72, 258), (258, 264, 136), (520, 300, 1032),
+                                   (64, 1030, 36)])
+def test_backward_matches_oracle_within_tolerance(jg, ctx, ways, K, M, N):
+    """dX = W dY^T and dW = X dY of the transposed layer: |got - want64| <= 1e-6 * (|W| |dY|^T resp. |X| |dY|)."""
+    X, W, _ = operands(640, K, M, N, "R", bias=False)
+    dY = inputs.matrix(641, M, N, "R")
+    dX, dW = run_backward(jg, ctx, X, W, dY, ways)
+    wX, wW = oracle.backward_xtw(X, W, dY)
+    SX, SW = oracle.backward_xtw(X, W, dY, absolute=True)
+    ex, ew = np.abs(dX - wX), np.abs(dW - wW)
+    assert np.all(ex <= TOL * SX), f"dX: {(ex / np.maximum(SX, 1e-300)).max():.3e}"
+    assert np.all(ew <= TOL * SW), f"dW: {(ew / np.maximum(SW, 1e-300)).max():.3e}"
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+def test_backward_is_bit_exact_on_lattice_inputs(jg, ctx, ways):
+    K, M, N = 132, 200, 72
+    X, W, _ = operands(642, K, M, N, "L", bias=False)
+    dY = inputs.matrix(643, M, N, "L")
+    dX, dW = run_backward(jg, ctx, X, W, dY, ways)
+    wX, wW = oracle.backward_xtw(X, W, dY)
+    assert np.array_equal(dX.astype(np.float64), wX) and np.array_equal(dW.astype(np.float64), wW)
+
+
+def test_backward_checks_its_workspace(jg, ctx):
     from paper_2507_05753_amd.layer import JigsawLinear
     with JigsawLinear(8, 8, 8, 2, ctx=ctx, op=jg.JG_OP_XTW) as L:
         ptrs = [t.data_ptr() for t in L.x]
         with pytest.raises(jg.JigsawError) as e:
             jg.jg_linear_backward(L.plan, ptrs, ptrs, ptrs, ptrs, ptrs, None, 0)
-        assert e.value.status == jg.JG_E_DTYPE
+        assert e.value.status == jg.JG_E_WORKSPACE
 
 
 # --------------------------------------------------------------------------------------------
