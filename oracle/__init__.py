@@ -500,6 +500,30 @@ def token_mixing_block(ways: int, X, gamma, beta, W1, b1, W2, b2, eps: float = L
     return dict(H=H, Y=Y, Xn=Xn, S1=S1, SY=SY)
 
 
+def token_mixing_block_backward(ways: int, X, gamma, beta, W1, b1, W2, dY, eps: float = LN_EPS):
+    """Gradients of token_mixing_block for an incoming gradient dY [T x C], in double, by the chain rule through the
+    steps in the layouts the layers use, with what the method stores between the steps handed on in FP32:
+        Xn = layernorm(X),  A = Xn^T W1 + b1 [C x D],  H = gelu(A);
+        second layer (W2 in the activations' place, H in the weights'):  dW2 = dY H,  dH = dY^T W2,
+        db2[t] = sum_c dY[t][c];   dA = dH * gelu'(A);
+        transposed layer:  dXn = W1 dA^T,  dW1 = Xn dA,  db1 = sum_c dA;
+        dX = dY + layernorm'(dXn),  dgamma, dbeta from the norm.
+    Returns a dict with A, dH, dA, dXn, dX, dW1, db1, dW2, db2, dgamma, dbeta."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    G32 = np.ascontiguousarray(dY, dtype=np.float32)
+    Xn32 = layernorm(X, gamma, beta, ln_groups(ways), eps).astype(np.float32)
+    A = linear_xtw(Xn32, W1, b1)
+    H32 = gelu(A).astype(np.float32)
+    dW2, dH = backward(W2, H32, G32)
+    db2 = bias_backward(np.ascontiguousarray(G32.T))
+    dA = dH * gelu_grad(A)
+    dA32 = dA.astype(np.float32)
+    dXn, dW1 = backward_xtw(Xn32, W1, dA32)
+    dXl, dgamma, dbeta = layernorm_backward(X, gamma, dXn.astype(np.float32), ln_groups(ways), eps)
+    return dict(A=A, dH=dH, dA=dA, dXn=dXn, dX=G32.astype(np.float64) + dXl, dW1=dW1, db1=bias_backward(dA32),
+                dW2=dW2, db2=db2, dgamma=dgamma, dbeta=dbeta)
+
+
 # ----------------------------------------------------------------------------
 # patch encoder / decoder (Sec. 5 "Encoding and decoding layers"): a convolution whose kernel
 # equals its stride is a linear layer over non-overlapping patches

@@ -363,3 +363,32 @@ def test_mixing_block_backward_against_the_library_autograd_in_double(ways):
     assert np.array_equal(r["dXn"], m["dX"] - dY) and np.array_equal(r["dW1"], m["dW1"])
     dXl, dg, db = oracle.layernorm_backward(X, gamma, r["dXn"].astype(np.float32), groups)
     assert np.array_equal(r["dX"], dY + dXl) and np.array_equal(r["dgamma"], dg) and np.array_equal(r["dbeta"], db)
+
+
+@pytest.mark.parametrize("ways", [1, 2])
+def test_token_mixing_block_backward_against_the_library_autograd_in_double(ways):
+    T, C, D = 6, 8, 10
+    X, gamma, beta = data(44, T, C, shift=0.2)
+    W1 = inputs.matrix(45, T, D, "R", inputs.W_SCALE_EXP)
+    W2 = inputs.matrix(46, T, D, "R", inputs.W_SCALE_EXP)
+    b1, b2 = inputs.matrix(47, 1, D, "R")[0], inputs.matrix(48, 1, T, "R")[0]
+    dY = inputs.matrix(49, T, C, "R")
+    groups = oracle.ln_groups(ways)
+    n = C // groups
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64)).requires_grad_(True)
+    Xt, gt, bt, W1t, b1t, W2t, b2t = t(X), t(gamma), t(beta), t(W1), t(b1), t(W2), t(b2)
+    Xn = torch.cat([torch.nn.functional.layer_norm(Xt[:, k * n:(k + 1) * n], (n,), gt[k * n:(k + 1) * n],
+                                                   bt[k * n:(k + 1) * n], EPS) for k in range(groups)], dim=1)
+    Y = Xt + W2t @ torch.nn.functional.gelu(Xn.T @ W1t + b1t).T + b2t[:, None]
+    # the forward this is the gradient of is the pinned one
+    fwd = oracle.token_mixing_block(ways, X, gamma, beta, W1, b1, W2, b2)
+    assert np.all(np.abs(fwd["Y"] - Y.detach().numpy()) <= 1e-6 * fwd["SY"])
+    Y.backward(torch.from_numpy(dY).double())
+    r = oracle.token_mixing_block_backward(ways, X, gamma, beta, W1, b1, W2, dY)
+    for name, ref in (("dX", Xt.grad), ("dgamma", gt.grad), ("dbeta", bt.grad), ("dW1", W1t.grad), ("db1", b1t.grad),
+                      ("dW2", W2t.grad), ("db2", b2t.grad)):
+        ref = ref.numpy()
+        assert r[name].shape == ref.shape, name
+        # Xn, H, dA and dXn are handed on in FP32 by the method
+        assert np.all(np.abs(r[name] - ref) <= 2e-6 * (np.abs(ref) + np.abs(ref).max())), name
+    assert np.array_equal(r["db2"], dY.astype(np.float64).sum(axis=1))      # few terms: the order does not matter here
