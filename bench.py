@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--ways", type=int, default=4, choices=[1, 2, 4])
     ap.add_argument("--op", choices=["forward", "backward", "xtw", "mlp", "mixing", "mixing_backward", "token_mixing",
-                                   "encoder"],
+                                   "token_mixing_backward", "encoder"],
                     default="forward",
                     help="forward: Y = X W^T (the headline); backward: dX = dY W and dW = dY^T X; "
                          "xtw: the transposed layer Y = X^T W at the token-mixing size; mlp: one mixing MLP "
@@ -468,6 +468,41 @@ def reduced_terms(args):
     return {"f32": 0, "bf16": 1, "bf16x3": 3}[args.dtype]
 
 
+def time_block_backward(L, dY, n_items, args, jg):
+    """Times L.backward(dY) of a block holder whose forward has run; per-kernel-class HIP-event times per step."""
+    import torch
+    names = {"dx": jg.JG_KERNEL_GEMM_DX, "dw": jg.JG_KERNEL_GEMM_DW, "a": jg.JG_KERNEL_GEMM, "norm": jg.JG_KERNEL_NORM,
+             "db": jg.JG_KERNEL_REDUCE, "elementwise": jg.JG_KERNEL_COMBINE, "join": jg.JG_KERNEL_JOIN,
+             "weight_copy": jg.JG_KERNEL_WEIGHT_COPY}
+    for _ in range(args.warmup):
+        L.backward(dY)
+    torch.cuda.synchronize()
+    for k in names.values():
+        jg.jg_profile_read(L.ctx, k)
+    jg.jg_profile_read(L.ctx, jg.JG_KERNEL_SHARD)
+    jg.jg_profile(L.ctx, True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        L.backward(dY)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    jg.jg_profile(L.ctx, False)
+    shard_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_SHARD)      # dY is sharded by the wrapper on every call
+    sec -= shard_ms * 1e-3 / args.steps
+    kernels = {}
+    for name, k in names.items():
+        ms, n = jg.jg_profile_read(L.ctx, k)
+        kernels[name] = dict(ms_per_step=ms / args.steps, launches_per_step=n / args.steps)
+    f, s2 = L.first, L.second
+    flops = (f.query(jg.JG_Q_BACKWARD_FLOPS_TOTAL) + s2.query(jg.JG_Q_BACKWARD_FLOPS_TOTAL) +
+             f.query(jg.JG_Q_FLOPS_TOTAL))
+    gemm_ms = sum(kernels[k]["ms_per_step"] for k in ("dx", "dw", "a"))
+    return dict(ms_per_step=sec * 1e3, items_per_s=n_items / sec, tflops=flops / sec / 1e12, kernels=kernels,
+                gemm_tflops=flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None, gemm_ms_per_step=gemm_ms,
+                workspace_bytes=L.bw_ws_bytes)
+
+
 def measure_mixing_backward(cfg, ways, args):
     """One step = one jg_mixing_backward after a forward pass: the gradients of the channel-mixing block."""
     import torch
@@ -477,44 +512,64 @@ def measure_mixing_backward(cfg, ways, args):
     M, C, Hd, seed = cfg["M"], cfg["C"], cfg["Hd"], cfg["seed"]
     dev = torch.device("cuda", 0)
     gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device=dev)
-    names = {"dx": jg.JG_KERNEL_GEMM_DX, "dw": jg.JG_KERNEL_GEMM_DW, "a": jg.JG_KERNEL_GEMM, "norm": jg.JG_KERNEL_NORM,
-             "db": jg.JG_KERNEL_REDUCE, "elementwise": jg.JG_KERNEL_COMBINE, "join": jg.JG_KERNEL_JOIN,
-             "weight_copy": jg.JG_KERNEL_WEIGHT_COPY}
     with JigsawMixing(M, C, Hd, ways, tail=tail_of(args)) as L:
         L.shard(gen(seed, M, C), (gen(seed + 5, 1, C)[0] + 1.5).contiguous(), gen(seed + 6, 1, C)[0].contiguous(),
                 gen(seed + 1, Hd, C, inputs.W_SCALE_EXP), gen(seed + 2, 1, Hd)[0].contiguous(),
                 gen(seed + 3, C, Hd, inputs.W_SCALE_EXP), gen(seed + 4, 1, C)[0].contiguous())
         L.forward()
-        dY = gen(seed + 7, M, C)
-        for _ in range(args.warmup):
-            L.backward(dY)
-        torch.cuda.synchronize()
-        for k in names.values():
-            jg.jg_profile_read(L.ctx, k)
-        jg.jg_profile_read(L.ctx, jg.JG_KERNEL_SHARD)
-        jg.jg_profile(L.ctx, True)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            L.backward(dY)
-        torch.cuda.synchronize()
-        sec = (time.perf_counter() - t0) / args.steps
-        jg.jg_profile(L.ctx, False)
-        shard_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_SHARD)      # dY is sharded by the wrapper on every call
-        sec -= shard_ms * 1e-3 / args.steps
-        kernels = {}
-        for name, k in names.items():
-            ms, n = jg.jg_profile_read(L.ctx, k)
-            kernels[name] = dict(ms_per_step=ms / args.steps, launches_per_step=n / args.steps)
-        f, s2 = L.first, L.second
-        flops = (f.query(jg.JG_Q_BACKWARD_FLOPS_TOTAL) + s2.query(jg.JG_Q_BACKWARD_FLOPS_TOTAL) +
-                 f.query(jg.JG_Q_FLOPS_TOTAL))
-        gemm_ms = sum(kernels[k]["ms_per_step"] for k in ("dx", "dw", "a"))
-        out = dict(ms_per_step=sec * 1e3, items_per_s=M * C / sec, tflops=flops / sec / 1e12, kernels=kernels,
-                   gemm_tflops=flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None, gemm_ms_per_step=gemm_ms,
-                   workspace_bytes=L.bw_ws_bytes)
+        out = time_block_backward(L, gen(seed + 7, M, C), M * C, args, jg)
     torch.cuda.empty_cache()
     return out
+
+
+def measure_token_mixing_backward(cfg, ways, args):
+    """One step = one jg_token_mixing_backward after a forward pass: the gradients of the token-mixing block."""
+    import torch
+    from paper_2507_05753_amd import binding as jg
+    from paper_2507_05753_amd import inputs
+    from paper_2507_05753_amd.layer import JigsawTokenMixing
+    T, C, D, seed = cfg["K"], cfg["M"], cfg["N"], cfg["seed"]
+    dev = torch.device("cuda", 0)
+    gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device=dev)
+    with JigsawTokenMixing(T, C, D, ways, tail=tail_of(args)) as L:
+        L.shard(gen(seed, T, C), (gen(seed + 5, 1, C)[0] + 1.5).contiguous(), gen(seed + 6, 1, C)[0].contiguous(),
+                gen(seed + 1, T, D, inputs.W_SCALE_EXP), gen(seed + 2, 1, D)[0].contiguous(),
+                gen(seed + 3, T, D, inputs.W_SCALE_EXP), gen(seed + 4, 1, T)[0].contiguous())
+        L.forward()
+        out = time_block_backward(L, gen(seed + 7, T, C), T * C, args, jg)
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline_token_mixing_backward(cfg, seconds):
+    """The oracle's backward of the token-mixing block timed on a bounded sample of channels (columns of X and dY;
+    the norm sees only those)."""
+    import oracle
+    from paper_2507_05753_amd import inputs
+    import numpy as np
+    T, C, D, seed = cfg["K"], cfg["M"], cfg["N"], cfg["seed"]
+    W1 = inputs.matrix(seed + 1, T, D, "R", inputs.W_SCALE_EXP)
+    b1 = inputs.matrix(seed + 2, 1, D, "R")[0]
+    W2 = inputs.matrix(seed + 3, T, D, "R", inputs.W_SCALE_EXP)
+    X = inputs.matrix(seed, T, C, "R")
+    dY = inputs.matrix(seed + 7, T, C, "R")
+    gamma = (inputs.matrix(seed + 5, 1, C, "R")[0] + 1.5).astype("float32")
+    beta = inputs.matrix(seed + 6, 1, C, "R")[0]
+
+    def run(ch):
+        Xs, Gs = np.ascontiguousarray(X[:, :ch]), np.ascontiguousarray(dY[:, :ch])
+        t0 = time.perf_counter()
+        oracle.token_mixing_block_backward(1, Xs, gamma[:ch], beta[:ch], W1, b1, W2, Gs)
+        return time.perf_counter() - t0
+
+    # a probe's time holds a fixed part (the weights converted to double): scaling it up underestimates the sample,
+    # so the run stays within the budget plus that fixed part
+    probe = min(C, 16)
+    ch = int(min(C, max(probe, probe * seconds / max(run(probe), 1e-9))))
+    dt = run(ch)
+    return dict(value=ch * T / dt, unit="items/s", cores=oracle.host_threads(), kind="oracle",
+                sample=f"channels 0..{ch - 1} of X and dY ({T} x {ch}) through the block's backward ({D} hidden; the "
+                       f"weight gradients are those channels' share), {dt:.1f} s, fp64")
 
 
 def cpu_baseline_mixing_backward(cfg, seconds):
@@ -535,10 +590,10 @@ def cpu_baseline_mixing_backward(cfg, seconds):
         oracle.mixing_block_backward(1, X, gamma, beta, W1, b1, W2, dY)
         return time.perf_counter() - t0
 
-    # the time is a fixed part (the weights converted to double) plus a part per token: two probes give both
-    t1, t2 = run(min(M, 32)), run(min(M, 128))
-    per_row = max((t2 - t1) / 96.0, 1e-9)
-    rows = int(min(M, max(128, (seconds - max(t1 - 32 * per_row, 0.0)) / per_row)))
+    # a probe's time holds a fixed part (the weights converted to double): scaling it up underestimates the sample,
+    # so the run stays within the budget plus that fixed part
+    probe = min(M, 128)
+    rows = int(min(M, max(probe, probe * seconds / max(run(probe), 1e-9))))
     dt = run(rows)
     return dict(value=rows * C / dt, unit="items/s", cores=oracle.host_threads(), kind="oracle",
                 sample=f"tokens 0..{rows - 1} of X and dY ({rows} x {C}) through the block's backward ({Hd} hidden; "
@@ -853,6 +908,32 @@ def main():
         }
         if args.cpu_seconds > 0:
             line["cpu_baseline"] = cpu_baseline_mixing_backward(mc, args.cpu_seconds)
+        print(json.dumps(line), flush=True)
+        return
+
+    if args.op == "token_mixing_backward":
+        xc = inputs.XTW_CONFIGS["token_mixing_1b"]
+        r = measure_token_mixing_backward(xc, args.ways, args)
+        T, C, D = xc["K"], xc["M"], xc["N"]
+        line = {
+            "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
+            "value": r["items_per_s"], "unit": "items/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"backward of the token-mixing half of a mixing block of the 1B model: gradients of "
+                                   f"Y = X + W2 gelu(layernorm(X)^T W1 + b1)^T + b2 for X, gamma, beta, W1, b1, W2, b2; "
+                                   f"X {T} x {C} [tokens, channels], hidden {D}, {args.ways}-way Jigsaw, fp32",
+                       "n_items": T * C, "ways": args.ways, "T": T, "C": C, "D": D, "seed": xc["seed"],
+                       "x_values": "R", "op": "token_mixing_backward", "tail": args.tail},
+            "tflops": r["tflops"],
+            "roofline": {"bound": "mfma", "kernel": "jg::gemm_f32_stream (dX, dW and recomputed A launches together)",
+                         "achieved": r["gemm_tflops"], "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": r["gemm_tflops"] / FP32_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None,
+                         "ms_per_step": r["gemm_ms_per_step"], "traffic": None},
+            "kernels": r["kernels"],
+        }
+        if args.cpu_seconds > 0:
+            line["cpu_baseline"] = cpu_baseline_token_mixing_backward(xc, args.cpu_seconds)
         print(json.dumps(line), flush=True)
         return
 

@@ -397,6 +397,29 @@ int jg_mlp_backward(const jg_plan* first, const jg_plan* second, const float* co
                     float* const* dx_sh, float* const* dw1_sh, float* const* db1_sh, float* const* dw2_sh,
                     float* const* db2_sh, void* workspace, size_t workspace_bytes);
 
+/* run (backward, token-mixing block).  Gradients of jg_token_mixing_forward's block (Sec. 3; Sec. 5: the transposed
+ * layer) for an incoming gradient dY (T x C, partitioned like X_r), by the chain rule through the steps in the layouts
+ * the forward uses:
+ *     second layer (W2 in the activations' place, H in the weights'):  dW2 = dY H,  dH = dY^T W2   (jg_linear_backward);
+ *     db2[t] = sum_c dY[t][c];      A = Xn^T W1 + b1 (recomputed);      dA = dH * gelu'(A);
+ *     transposed layer:  dXn = W1 dA^T,  dW1 = Xn dA  (jg_linear_backward on the JG_OP_XTW plan),  db1 = sum_c dA;
+ *     dX = dY + layernorm'(dXn),  dgamma, dbeta   (as jg_layernorm_backward, the skip added before the rounding).
+ * Plans as for jg_token_mixing_forward.  x_sh, gamma, eps, w1_sh, b1_sh, w2_sh: as in the forward; xn_sh, h_sh: the
+ * Xn and H it stored; dy_sh: the dY shards.  Outputs (`ways` device buffers each): a_sh, dh_sh, da_sh shaped like
+ * H_r; dxn_sh, dx_sh like X_r; dw1_sh like the first plan's W_r; db1_sh like its bias shards; dw2_sh like the second
+ * plan's X_r; db2: device vector of length T (or NULL); dgamma, dbeta: device vectors of length C (either may be
+ * NULL).  No output may overlap an input or another output.  workspace: 256-byte aligned, at least the largest of
+ * the first plan's JG_Q_WORKSPACE_BYTES, the two plans' JG_Q_BACKWARD_WORKSPACE_BYTES and the first plan's
+ * JG_Q_NORM_BACKWARD_WORKSPACE_BYTES.
+ * Errors: those of jg_token_mixing_forward, jg_linear_backward, jg_bias_backward and jg_layernorm_backward. */
+int jg_token_mixing_backward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* gamma,
+                             double eps, const float* const* xn_sh, const float* const* w1_sh,
+                             const float* const* b1_sh, const float* const* w2_sh, const float* const* h_sh,
+                             const float* const* dy_sh, float* const* a_sh, float* const* dh_sh, float* const* da_sh,
+                             float* const* dxn_sh, float* const* dx_sh, float* const* dw1_sh, float* const* db1_sh,
+                             float* const* dw2_sh, float* db2, float* dgamma, float* dbeta, void* workspace,
+                             size_t workspace_bytes);
+
 /* run (backward, channel-mixing block).  Gradients of jg_mixing_forward's block  Xn = layernorm(X),
  * Y = X + MLP(Xn)  (Sec. 3: the block; Sec. 4.1 and Sec. 5 "Layer norms": its parts) for an incoming gradient dY:
  * jg_mlp_backward's chain on Xn without that function's skip connection (dXn = dA W1), then jg_layernorm_backward's

@@ -49,7 +49,7 @@ JG_T_X, JG_T_W, JG_T_B, JG_T_Y, JG_T_X_F32 = 0, 1, 2, 3, 4
 EXPORTS = ("jg_init", "jg_free", "jg_plan_create", "jg_plan_destroy", "jg_plan_query", "jg_shard",
            "jg_shard_patches", "jg_gather_patches",
            "jg_linear_forward", "jg_linear_forward_ex", "jg_mlp_forward", "jg_layernorm_forward",
-           "jg_mixing_forward", "jg_token_mixing_forward", "jg_linear_backward", "jg_bias_backward", "jg_layernorm_backward", "jg_mlp_backward", "jg_mixing_backward", "jg_gather", "jg_gather_as", "jg_profile",
+           "jg_mixing_forward", "jg_token_mixing_forward", "jg_linear_backward", "jg_bias_backward", "jg_layernorm_backward", "jg_mlp_backward", "jg_mixing_backward", "jg_token_mixing_backward", "jg_gather", "jg_gather_as", "jg_profile",
            "jg_profile_read", "jg_strerror",
            "jg_last_hip_error")
 
@@ -104,6 +104,9 @@ _lib.jg_mlp_backward.restype = ctypes.c_int
 _lib.jg_mixing_backward.argtypes = ([_vp, _vp, _vpp, _vp, ctypes.c_double] + [_vpp] * 15 +
                                     [_vp, _vp, _vp, ctypes.c_size_t])
 _lib.jg_mixing_backward.restype = ctypes.c_int
+_lib.jg_token_mixing_backward.argtypes = ([_vp, _vp, _vpp, _vp, ctypes.c_double] + [_vpp] * 14 +
+                                          [_vp, _vp, _vp, _vp, ctypes.c_size_t])
+_lib.jg_token_mixing_backward.restype = ctypes.c_int
 _lib.jg_bias_backward.argtypes = [_vp, _vpp, _vpp]
 _lib.jg_bias_backward.restype = ctypes.c_int
 _lib.jg_gather.argtypes = [_vp, _vpp, _vp, ctypes.c_int64]
@@ -247,6 +250,16 @@ def jg_mixing_backward(first, second, x_ptrs, gamma_ptr, eps: float, xn_ptrs, w1
     _raise(_lib.jg_mixing_backward(first, second, _ptr_array(x_ptrs), gamma_ptr or None, float(eps), *arrays,
                                    dgamma_ptr or None, dbeta_ptr or None, workspace_ptr or None, workspace_bytes),
            "jg_mixing_backward")
+
+
+def jg_token_mixing_backward(first, second, x_ptrs, gamma_ptr, eps: float, xn_ptrs, w1_ptrs, b1_ptrs, w2_ptrs, h_ptrs,
+                             dy_ptrs, a_ptrs, dh_ptrs, da_ptrs, dxn_ptrs, dx_ptrs, dw1_ptrs, db1_ptrs, dw2_ptrs, db2_ptr,
+                             dgamma_ptr, dbeta_ptr, workspace_ptr, workspace_bytes: int) -> None:
+    arrays = [_ptr_array(v) for v in (xn_ptrs, w1_ptrs, b1_ptrs, w2_ptrs, h_ptrs, dy_ptrs, a_ptrs, dh_ptrs, da_ptrs,
+                                      dxn_ptrs, dx_ptrs, dw1_ptrs, db1_ptrs, dw2_ptrs)]
+    _raise(_lib.jg_token_mixing_backward(first, second, _ptr_array(x_ptrs), gamma_ptr or None, float(eps), *arrays,
+                                         db2_ptr or None, dgamma_ptr or None, dbeta_ptr or None, workspace_ptr or None,
+                                         workspace_bytes), "jg_token_mixing_backward")
 
 
 def jg_bias_backward(plan, dy_ptrs, db_ptrs) -> None:

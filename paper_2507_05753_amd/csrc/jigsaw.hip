@@ -1455,4 +1455,70 @@ int jg_token_mixing_forward(const jg_plan* first, const jg_plan* second, const f
     return forward_impl(second, w2_sh, h_sh, nullptr, res, JG_ACT_NONE, y_sh, workspace, workspace_bytes, nullptr);
 }
 
+int jg_token_mixing_backward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* gamma,
+                             double eps, const float* const* xn_sh, const float* const* w1_sh,
+                             const float* const* b1_sh, const float* const* w2_sh, const float* const* h_sh,
+                             const float* const* dy_sh, float* const* a_sh, float* const* dh_sh, float* const* da_sh,
+                             float* const* dxn_sh, float* const* dx_sh, float* const* dw1_sh, float* const* db1_sh,
+                             float* const* dw2_sh, float* db2, float* dgamma, float* dbeta, void* workspace,
+                             size_t workspace_bytes)
+{
+    if (int rc = check_token_chain(first, second)) return rc;
+    const int ways = first->d.ways;
+    for (float* const* arr : {a_sh, dh_sh, da_sh, dxn_sh, db1_sh})
+        if (int rc = check_ptr_array(arr, ways)) return rc;
+    if (int rc = check_ptr_array(dy_sh, ways)) return rc;
+    if (!aligned(db2, 4)) return JG_E_ALIGN;
+    size_t need = mlp_backward_workspace(first, second);
+    const size_t stats = round_up(16 * (size_t)first->xr, kWsAlign) * ways;
+    if (stats > need) need = stats;
+    if (!workspace || workspace_bytes < need) return JG_E_WORKSPACE;
+    if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
+    jg_ctx* c = first->ctx;
+    // second layer, W2 in the activations' place and H in the weights': its "dX" is dW2 = dY H, its "dW" is dH = dY^T W2
+    int rc = jg_linear_backward(second, w2_sh, h_sh, dy_sh, dw2_sh, dh_sh, workspace, workspace_bytes);
+    if (rc != JG_OK) return rc;
+    if (db2) {
+        // db2[t] = sum over the channels of dY[t][.]: the blocks of a token range side by side
+        jg::RowSumGroup rg;
+        std::memset(&rg, 0, sizeof(rg));
+        rg.rows = (int)first->xr;
+        rg.cols = (int)first->xc;
+        rg.nout = ways == 4 ? 2 : 1;
+        for (int i = 0; i < rg.nout; ++i) {
+            rg.o[i].nsrc = ways == 1 ? 1 : 2;
+            for (int b = 0; b < rg.o[i].nsrc; ++b) {
+                if (!aligned(dy_sh[2 * i + b], 4)) return JG_E_ALIGN;
+                rg.o[i].src[b] = dy_sh[2 * i + b];
+            }
+            rg.o[i].dst = db2 + (int64_t)i * first->xr;
+        }
+        ScopedTimer t(c, JG_KERNEL_REDUCE);
+        if (!HIP_OK(jg::launch_rowsum_group(rg, c->stream))) return JG_E_HIP;
+    }
+    // the pre-activation, which the forward does not keep: A = Xn^T W1 + b1 once more
+    rc = forward_impl(first, xn_sh, w1_sh, b1_sh, nullptr, JG_ACT_NONE, a_sh, workspace, workspace_bytes, nullptr);
+    if (rc != JG_OK) return rc;
+    {   // dA = dH * gelu'(A)
+        jg::ActBwdGroup ag;
+        std::memset(&ag, 0, sizeof(ag));
+        ag.nblocks = ways;
+        ag.n = (int64_t)first->yr * first->yc;
+        for (int r = 0; r < ways; ++r) {
+            if (!aligned(a_sh[r], 4) || !aligned(dh_sh[r], 4) || !aligned(da_sh[r], 4)) return JG_E_ALIGN;
+            ag.b[r] = {a_sh[r], dh_sh[r], da_sh[r]};
+        }
+        ScopedTimer t(c, JG_KERNEL_COMBINE);
+        if (!HIP_OK(jg::launch_act_bwd_group(ag, c->stream))) return JG_E_HIP;
+    }
+    // transposed layer: dXn = W1 dA^T, dW1 = Xn dA, db1 = column sums of dA
+    rc = jg_linear_backward(first, xn_sh, w1_sh, da_sh, dxn_sh, dw1_sh, workspace, workspace_bytes);
+    if (rc != JG_OK) return rc;
+    rc = jg_bias_backward(first, da_sh, db1_sh);
+    if (rc != JG_OK) return rc;
+    // the norm's backward, with the block's skip connection added before dX is rounded
+    return layernorm_backward_impl(first, x_sh, gamma, eps, dxn_sh, dx_sh, dgamma, dbeta, workspace, workspace_bytes,
+                                   dy_sh);
+}
+
 }  // extern "C"

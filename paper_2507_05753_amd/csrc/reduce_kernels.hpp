@@ -12,6 +12,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "norm_kernels.hpp"      // wave_sum
 #include "stream_kernels.hpp"
 
 namespace jg {
@@ -88,6 +89,66 @@ inline hipError_t launch_colsum_group(const ColSumGroup& g, hipStream_t stream)
     dim3 grid((g.cols + COLSUM_STRIP - 1) / COLSUM_STRIP, g.nout, 1);
     if (vec) hipLaunchKernelGGL(colsum_f32<true>, grid, dim3(COLSUM_THREADS), 0, stream, g);
     else hipLaunchKernelGGL(colsum_f32<false>, grid, dim3(COLSUM_THREADS), 0, stream, g);
+    return hipGetLastError();
+}
+
+// Row sums: dst[i] = sum over the columns of all source blocks (side by side) of row i.  This is the gradient of a
+// bias that goes with the row (the token) instead of the column: the second layer of the token-mixing MLP
+// (Sec. 5: the transposed layer and the layer after it) adds b2[t] to every channel of token t.
+// One wavefront per row; each lane walks the row in steps of 64 (vectors of four where the layout allows), double
+// accumulators, the lanes' sums added in a fixed order, rounded once.
+struct RowSumOut {
+    const float* src[2];   // source blocks side by side (the two column halves of a row range); rows x cols, dense
+    float* dst;            // rows sums
+    int nsrc;
+};
+
+struct RowSumGroup {
+    RowSumOut o[kMaxBlocks];
+    int nout;
+    int rows, cols;        // shape of every source block
+};
+
+constexpr int ROWSUM_THREADS = 256;
+constexpr int ROWSUM_ROWS_PER_WG = ROWSUM_THREADS / 64;
+
+// grid: x = group of rows, y = output.  VEC: cols % 4 == 0 and every source 16-byte aligned.
+template <bool VEC>
+__global__ __launch_bounds__(ROWSUM_THREADS) void rowsum_f32(const RowSumGroup g)
+{
+    const RowSumOut& O = g.o[blockIdx.y];
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * ROWSUM_ROWS_PER_WG + (threadIdx.x >> 6);
+    if (row >= g.rows) return;      // (whole wavefronts leave together; nothing below waits on another wavefront)
+    double s = 0.0;
+    for (int b = 0; b < O.nsrc; ++b) {
+        const float* src = O.src[b] + (int64_t)row * g.cols;
+        if (VEC) {
+            const vf4* v = reinterpret_cast<const vf4*>(src);
+            const int nvec = g.cols >> 2;
+#pragma unroll 4
+            for (int c = lane; c < nvec; c += 64) {
+                const vf4 x = __builtin_nontemporal_load(v + c);
+                s += ((double)x.x + (double)x.y) + ((double)x.z + (double)x.w);
+            }
+        } else {
+            for (int c = lane; c < g.cols; c += 64) s += (double)src[c];
+        }
+    }
+    s = wave_sum(s);
+    if (lane == 0) O.dst[row] = (float)s;
+}
+
+inline hipError_t launch_rowsum_group(const RowSumGroup& g, hipStream_t stream)
+{
+    if (g.nout <= 0 || g.rows <= 0) return hipSuccess;      // (cols == 0: the sums are zero and are written)
+    bool vec = (g.cols & 3) == 0;
+    for (int i = 0; i < g.nout; ++i)
+        for (int b = 0; b < g.o[i].nsrc; ++b)
+            if ((uintptr_t)g.o[i].src[b] & 15) vec = false;
+    dim3 grid((g.rows + ROWSUM_ROWS_PER_WG - 1) / ROWSUM_ROWS_PER_WG, g.nout, 1);
+    if (vec) hipLaunchKernelGGL(rowsum_f32<true>, grid, dim3(ROWSUM_THREADS), 0, stream, g);
+    else hipLaunchKernelGGL(rowsum_f32<false>, grid, dim3(ROWSUM_THREADS), 0, stream, g);
     return hipGetLastError();
 }
 

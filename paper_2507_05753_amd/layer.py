@@ -374,6 +374,46 @@ class JigsawTokenMixing:
         jg.jg_gather_as(self.first.plan, jg.JG_T_X, [t.data_ptr() for t in self.xn], out.data_ptr(), out.stride(0))
         return out
 
+    def backward(self, dY):
+        """Gradients of the block for an incoming gradient dY (T, C), after forward(): jg_token_mixing_backward.  The
+        shards of A, dH, dA, dXn, dX, dW1, db1, dW2 are kept on the holder (``self.grads``), ``db2`` (T,), ``dgamma``
+        and ``dbeta`` (C,) as global vectors."""
+        f, s = self.first, self.second
+        assert dY.is_cuda and dY.dtype == torch.float32 and dY.shape == (self.T, self.C)
+        if getattr(self, "grads", None) is None:
+            like = lambda ts: [torch.empty_like(t) for t in ts]
+            self.grads = dict(dy=like(s.y), a=like(f.y), dh=like(f.y), da=like(f.y), dxn=like(f.x), dx=like(f.x),
+                              dw1=like(f.w), db1=like(f.b), dw2=like(s.x))
+            vec = lambda n: torch.empty((n,), dtype=torch.float32, device=f.dev)
+            self.db2, self.dgamma, self.dbeta = vec(self.T), vec(self.C), vec(self.C)
+            need = max(f.query(jg.JG_Q_WORKSPACE_BYTES), f.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES),
+                       s.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES), f.query(jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES))
+            self.bw_ws = torch.empty((need,), dtype=torch.uint8, device=f.dev)
+            self.bw_ws_bytes = need
+        g = self.grads
+        p = lambda ts: [t.data_ptr() for t in ts]
+        jg.jg_shard(s.plan, jg.JG_T_Y, dY.data_ptr(), dY.stride(0), p(g["dy"]))
+        jg.jg_token_mixing_backward(f.plan, s.plan, p(f.x), self.gamma.data_ptr() if self.gamma is not None else None,
+                                    self.eps, p(self.xn), p(f.w), p(f.b), p(s.x), p(f.y), p(g["dy"]), p(g["a"]),
+                                    p(g["dh"]), p(g["da"]), p(g["dxn"]), p(g["dx"]), p(g["dw1"]), p(g["db1"]),
+                                    p(g["dw2"]), self.db2.data_ptr(), self.dgamma.data_ptr(), self.dbeta.data_ptr(),
+                                    self.bw_ws.data_ptr(), self.bw_ws_bytes)
+
+    def gather_grad(self, name: str):
+        """A gradient (or kept intermediate) of backward() as a global matrix: 'a', 'dh', 'da' (C, D), 'dx', 'dxn'
+        (T, C), 'dw1', 'dw2' (T, D); 'db1' as a global vector (D,)."""
+        f, s, g = self.first, self.second, self.grads
+        p = lambda ts: [t.data_ptr() for t in ts]
+        if name == "db1":       # rank r holds the slice of column half r % 2 (replicated in the 4-way form)
+            return torch.cat(g[name][:1] if self.ways == 1 else g[name][:2])
+        plan, which, shape = {"a": (f, jg.JG_T_Y, (self.C, self.D)), "dh": (f, jg.JG_T_Y, (self.C, self.D)),
+                              "da": (f, jg.JG_T_Y, (self.C, self.D)), "dx": (f, jg.JG_T_X, (self.T, self.C)),
+                              "dxn": (f, jg.JG_T_X, (self.T, self.C)), "dw1": (f, jg.JG_T_W, (self.T, self.D)),
+                              "dw2": (s, jg.JG_T_X, (self.T, self.D))}[name]
+        out = torch.empty(shape, dtype=torch.float32, device=f.dev)
+        jg.jg_gather_as(plan.plan, which, p(g[name]), out.data_ptr(), out.stride(0))
+        return out
+
     def gather_h(self):
         return self.first.gather()
 

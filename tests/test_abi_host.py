@@ -449,3 +449,23 @@ def test_mlp_and_mixing_backward_check_that_the_plans_chain():
         assert call(a, t) == jg.JG_E_DTYPE
         jg.jg_plan_destroy(t)
     jg.jg_plan_destroy(a)
+
+
+def test_token_mixing_backward_checks_that_the_plans_chain():
+    lib = jg.raw()
+    arr = (ctypes.c_void_p * 2)(256, 512)
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    call = lambda a, b: lib.jg_token_mixing_backward(a, b, pp, None, 1e-5, *([pp] * 14), None, None, None, 256, 1 << 20)
+    first = jg.jg_plan_create(None, 32, 64, 48, 2, True, op=jg.JG_OP_XTW)        # T = 64, C = 32, D = 48
+    assert call(None, first) == jg.JG_E_NULL
+    for (M, K, N), ways, bias, want in (((64, 48, 32), 2, True, jg.JG_E_DTYPE),   # the second layer carries no bias
+                                        ((64, 48, 30), 2, False, jg.JG_E_SHAPE),
+                                        ((64, 48, 32), 4, False, jg.JG_E_WAYS),
+                                        ((64, 48, 32), 2, False, jg.JG_E_NULL)):  # chains, but no context
+        second = jg.jg_plan_create(None, M, K, N, ways, bias)
+        assert call(first, second) == want
+        jg.jg_plan_destroy(second)
+    plain = jg.jg_plan_create(None, 64, 48, 32, 2, False)
+    assert call(plain, plain) == jg.JG_E_DTYPE                                    # the first layer must be the transposed one
+    jg.jg_plan_destroy(plain)
+    jg.jg_plan_destroy(first)

@@ -484,3 +484,55 @@ def test_layernorm_backward_argument_checks(jg, ctx):
             with pytest.raises(jg.JigsawError) as e:
                 jg.jg_layernorm_backward(L.plan, *args)
             assert e.value.status == want
+
+
+# ---- backward of the token-mixing half -----------------------------------------------------------------------
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("T,C,D", [(100, 100, 100), (130, 72, 258), (264, 136, 72), (520, 300, 1032)])
+def test_token_mixing_backward(jg, ctx, ways, T, C, D):
+    """Every step of jg_token_mixing_backward against the oracle applied to what the GPU stored for the step before
+    (the products within 1e-6 * S, the elementwise steps and the sums within one rounding), then the whole chain
+    loosely against the oracle's own chain."""
+    from paper_2507_05753_amd.layer import JigsawTokenMixing
+    X, gamma, beta, W1, b1, W2, b2 = token_operands(370, T, C, D)
+    dY = inputs.matrix(371, T, C, "R")
+    f64 = lambda a: a.astype(np.float64)
+    within = lambda got, want, S: np.all(np.abs(f64(got) - want) <= 1e-6 * S)
+    once = lambda got, want, S: np.all(np.abs(f64(got) - want) <= HALF_ULP * np.abs(want) * (1 + 1e-6) + 1e-11 * S + 1e-45)
+    with JigsawTokenMixing(T, C, D, ways, ctx=ctx) as L:
+        L.shard(dev(X), dev(gamma), dev(beta), dev(W1), dev(b1), dev(W2), dev(b2))
+        L.forward()
+        L.backward(dev(dY))
+        Xn, H = L.gather_xn().cpu().numpy(), L.gather_h().cpu().numpy()
+        g = {k: L.gather_grad(k).cpu().numpy() for k in ("a", "dh", "da", "dxn", "dx", "dw1", "dw2", "db1")}
+        db2, dgam, dbet = L.db2.cpu().numpy(), L.dgamma.cpu().numpy(), L.dbeta.cpu().numpy()
+        L.backward(dev(dY))                                    # nothing it reads was overwritten: the same again
+        for k in ("dx", "dw1", "dw2"):
+            assert np.array_equal(g[k], L.gather_grad(k).cpu().numpy()), k
+        assert np.array_equal(db2, L.db2.cpu().numpy()) and np.array_equal(dgam, L.dgamma.cpu().numpy())
+    # A recomputed: the transposed layer once more
+    assert within(g["a"], oracle.linear_xtw(Xn, W1, b1), oracle.magnitude_xtw(Xn, W1, b1)), "A"
+    # second layer's backward, W2 in the activations' place and H in the weights'
+    (dW2, dH), (SW2, SH) = oracle.backward(W2, H, dY), oracle.backward_magnitude(W2, H, dY)
+    assert within(g["dw2"], dW2, SW2), "dW2"
+    assert within(g["dh"], dH, SH), "dH"
+    want = oracle.bias_backward(np.ascontiguousarray(dY.T))
+    assert once(db2, want, oracle.bias_backward(np.ascontiguousarray(dY.T), absolute=True)), "db2"
+    # dA from the A and dH the GPU stored: evaluated in double, rounded once
+    dA = f64(g["dh"]) * oracle.gelu_grad(f64(g["a"]))
+    assert np.all(np.abs(f64(g["da"]) - dA) <= 2.0 ** -23 * np.abs(dA) + 1e-45), "dA"
+    # the transposed layer's backward from the dA the GPU stored
+    (dXn, dW1), (SXn, SW1) = oracle.backward_xtw(Xn, W1, g["da"]), oracle.backward_xtw(Xn, W1, g["da"], absolute=True)
+    assert within(g["dxn"], dXn, SXn), "dXn"
+    assert within(g["dw1"], dW1, SW1), "dW1"
+    assert once(g["db1"], oracle.bias_backward(g["da"]), oracle.bias_backward(g["da"], absolute=True)), "db1"
+    # the norm's backward from the dXn the GPU stored, the skip connection added before the rounding
+    dXl, dg, db, SX, Sg, Sb = oracle.layernorm_backward(X, gamma, g["dxn"], oracle.ln_groups(ways), magnitude=True)
+    assert once(g["dx"], f64(dY) + dXl, SX + np.abs(dY)), "dX"
+    assert once(dgam, dg, Sg) and once(dbet, db, Sb)
+    # end to end (Xn, H and A in FP32 here differ in the last bits from the oracle's)
+    r = oracle.token_mixing_block_backward(ways, X, gamma, beta, W1, b1, W2, dY)
+    for got, name in ((g["dx"], "dX"), (g["dw1"], "dW1"), (g["dw2"], "dW2"), (g["db1"], "db1"), (db2, "db2"),
+                      (dgam, "dgamma"), (dbet, "dbeta")):
+        ref = r[name]
+        assert got.shape == ref.shape and np.all(np.abs(got - ref) <= 1e-4 * (np.abs(ref) + np.abs(ref).max())), name
