@@ -536,3 +536,82 @@ def test_token_mixing_backward(jg, ctx, ways, T, C, D):
                       (dgam, "dgamma"), (dbet, "dbeta")):
         ref = r[name]
         assert got.shape == ref.shape and np.all(np.abs(got - ref) <= 1e-4 * (np.abs(ref) + np.abs(ref).max())), name
+
+
+@pytest.mark.timeout(900)
+def test_token_mixing_backward_size(jg, capsys):
+    """The token-mixing block's backward at the 1B model's size, in the launch configuration bench.py --op
+    token_mixing_backward times.  Per sampled channel every step of the MLP's chain (whole rows of A, dH, dA, whole
+    columns of dXn), per sampled token the norm's step (whole rows of dX), each against the oracle applied to what
+    the GPU stored for the step before; sampled entries of dW1 and dW2 (sums over all channels); db1, db2, dgamma and
+    dbeta in full."""
+    from paper_2507_05753_amd.layer import JigsawTokenMixing
+    cfg = inputs.XTW_CONFIGS["token_mixing_1b"]
+    T, C, D, seed = cfg["K"], cfg["M"], cfg["N"], cfg["seed"]
+    gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device="cuda")
+    Xd, dYd = gen(seed, T, C) + 0.25, gen(seed + 7, T, C)
+    W1d, W2d = gen(seed + 1, T, D, inputs.W_SCALE_EXP), gen(seed + 3, T, D, inputs.W_SCALE_EXP)
+    b1d, b2d = gen(seed + 2, 1, D)[0].contiguous(), gen(seed + 4, 1, T)[0].contiguous()
+    gamma, beta = affine(seed + 5, C)
+    W1, b1, W2 = W1d.cpu().numpy(), b1d.cpu().numpy(), W2d.cpu().numpy()
+    X, dY = Xd.cpu().numpy(), dYd.cpu().numpy()
+    k = inputs.keys(7300, np.arange(48, dtype=np.uint64))
+    cs = np.unique(np.concatenate([(k[:12] % np.uint64(C)).astype(np.int64), [0, C // 2 - 1, C // 2, C - 1]]))
+    ts = np.unique(np.concatenate([(k[12:32] % np.uint64(T)).astype(np.int64), [0, T // 2 - 1, T // 2, T - 1]]))
+    ds = np.unique(np.concatenate([(k[32:] % np.uint64(D)).astype(np.int64), [0, D // 2 - 1, D // 2, D - 1]]))
+    ci, ti, di = (torch.from_numpy(v).cuda() for v in (cs, ts, ds))
+    f64 = lambda a: a.astype(np.float64)
+    tr = lambda a: np.ascontiguousarray(a.T)
+    for ways in (1, 4):
+        with JigsawTokenMixing(T, C, D, ways) as L:
+            L.shard(Xd, dev(gamma), dev(beta), W1d, b1d, W2d, b2d)
+            L.forward()
+            L.backward(dYd)
+            torch.cuda.synchronize()
+            Xn, H = L.gather_xn(), L.gather_h()
+            full = {}
+            for name in ("a", "dh", "da", "dxn", "dx", "dw1", "dw2"):
+                t = L.gather_grad(name)
+                assert torch.isfinite(t).all(), name
+                full[name] = t
+            a_c, dh_c, da_c = (full[n][ci].cpu().numpy() for n in ("a", "dh", "da"))      # rows of the C x D matrices
+            dxn_c = full["dxn"][:, ci].cpu().numpy()                                    # columns of dXn: T x n
+            dxn_t, dx_t = full["dxn"][ti].cpu().numpy(), full["dx"][ti].cpu().numpy()
+            Xn_c, Xn_t = Xn[:, ci].cpu().numpy(), Xn[ti].cpu().numpy()
+            da_d, H_d = full["da"][:, di].cpu().numpy(), H[:, di].cpu().numpy()          # columns over all channels
+            dW1_s, dW2_s = full["dw1"][ti][:, di].cpu().numpy(), full["dw2"][ti][:, di].cpu().numpy()
+            dA_full, dXn_full = full["da"].cpu().numpy(), full["dxn"].cpu().numpy()
+            db1 = L.gather_grad("db1").cpu().numpy()
+            db2, dgam, dbet = L.db2.cpu().numpy(), L.dgamma.cpu().numpy(), L.dbeta.cpu().numpy()
+            del full, Xn, H
+        torch.cuda.empty_cache()
+        worst = {}
+
+        def within(name, got, want, S):
+            e = (np.abs(f64(got) - want) / np.maximum(S, 1e-300)).max()
+            worst[name] = e
+            assert e <= 1e-6, (ways, name, e)
+
+        def once(name, got, want, S):
+            assert np.all(np.abs(f64(got) - want) <= HALF_ULP * np.abs(want) * (1 + 1e-6) + 1e-11 * S), (ways, name)
+        # per sampled channel
+        within("A", a_c, oracle.linear_xtw(Xn_c, W1, b1), oracle.magnitude_xtw(Xn_c, W1, b1))
+        dY_c = np.ascontiguousarray(dY[:, cs])
+        within("dH", dh_c, oracle.linear_xtw(dY_c, W2), oracle.magnitude_xtw(dY_c, W2))
+        dA = f64(dh_c) * oracle.gelu_grad(f64(a_c))
+        assert np.all(np.abs(f64(da_c) - dA) <= 2.0 ** -23 * np.abs(dA) + 1e-45), (ways, "dA")
+        within("dXn", dxn_c, oracle.linear(W1, da_c), oracle.magnitude(W1, da_c))
+        # per sampled token: the norm's step with the skip connection
+        dXl, _, _, SX, _, _ = oracle.layernorm_backward(X[ts], gamma, dxn_t, oracle.ln_groups(ways), magnitude=True)
+        once("dX", dx_t, f64(dY[ts]) + dXl, SX + np.abs(dY[ts]))
+        # sampled entries of the weight gradients: sums over all channels of what the GPU stored
+        within("dW1", dW1_s, oracle.linear(Xn_t, tr(da_d)), oracle.magnitude(Xn_t, tr(da_d)))
+        within("dW2", dW2_s, oracle.linear(dY[ts], tr(H_d)), oracle.magnitude(dY[ts], tr(H_d)))
+        # in full
+        once("db1", db1, oracle.bias_backward(dA_full), oracle.bias_backward(dA_full, absolute=True))
+        once("db2", db2, oracle.bias_backward(tr(dY)), oracle.bias_backward(tr(dY), absolute=True))
+        _, dg, db, _, Sg, Sb = oracle.layernorm_backward(X, gamma, dXn_full, oracle.ln_groups(ways), magnitude=True)
+        once("dgamma", dgam, dg, Sg)
+        once("dbeta", dbet, db, Sb)
+        note(capsys, f"token mixing backward ways={ways}: {cs.size} channels, {ts.size} tokens, {ts.size} x {ds.size} weight "
+                     f"entries; max err/S " + ", ".join(f"{n} {e:.2e}" for n, e in worst.items()))

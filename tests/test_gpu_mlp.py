@@ -304,3 +304,79 @@ def test_mixing_block_backward(jg, ctx, ways, M, C, Hd):
     for got, name in ((dx, "dX"), (g["dw1"], "dW1"), (g["dw2"], "dW2"), (dgam, "dgamma"), (dbet, "dbeta")):
         ref = r[name]
         assert np.all(np.abs(got - ref) <= 1e-4 * (np.abs(ref) + np.abs(ref).max())), name
+
+
+@pytest.mark.timeout(900)
+def test_mixing_block_backward_size(jg, capsys):
+    """The channel-mixing block's backward at the 1B model's size, in the launch configuration bench.py --op
+    mixing_backward times.  Per sampled token every step of the chain (whole rows of A, dH, dA, dXn, dX) against the
+    oracle applied to what the GPU stored for the step before; sampled entries of dW1 and dW2 (sums over all tokens),
+    the bias gradients and the norm's parameter gradients in full."""
+    from paper_2507_05753_amd.layer import JigsawMixing
+    cfg = inputs.MLP_CONFIGS["channel_mixing_1b"]
+    M, C, Hd, seed = cfg["M"], cfg["C"], cfg["Hd"], cfg["seed"]
+    gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device="cuda")
+    Xd, dYd = gen(seed, M, C) + 0.25, gen(seed + 7, M, C)
+    W1d, W2d = gen(seed + 1, Hd, C, inputs.W_SCALE_EXP), gen(seed + 3, C, Hd, inputs.W_SCALE_EXP)
+    b1d, b2d = gen(seed + 2, 1, Hd)[0].contiguous(), gen(seed + 4, 1, C)[0].contiguous()
+    gammad, betad = (gen(seed + 5, 1, C)[0] + 1.5).contiguous(), gen(seed + 6, 1, C)[0].contiguous()
+    W1, b1, W2, gamma = W1d.cpu().numpy(), b1d.cpu().numpy(), W2d.cpu().numpy(), gammad.cpu().numpy()
+    X, dY = Xd.cpu().numpy(), dYd.cpu().numpy()
+    k = inputs.keys(6100, np.arange(64, dtype=np.uint64))
+    rows = np.unique(np.concatenate([(k[:24] % np.uint64(M)).astype(np.int64), [0, M // 2 - 1, M // 2, M - 1]]))
+    cs = np.unique(np.concatenate([(k[24:44] % np.uint64(C)).astype(np.int64), [0, C // 2 - 1, C // 2, C - 1]]))
+    hs = np.unique(np.concatenate([(k[44:] % np.uint64(Hd)).astype(np.int64), [0, Hd // 2 - 1, Hd // 2, Hd - 1]]))
+    ri, ci, hi = (torch.from_numpy(v).cuda() for v in (rows, cs, hs))
+    f64 = lambda a: a.astype(np.float64)
+    HALF = 2.0 ** -24
+    T = lambda a: np.ascontiguousarray(a.T)
+    for ways in (1, 4):
+        with JigsawMixing(M, C, Hd, ways) as L:
+            L.shard(Xd, gammad, betad, W1d, b1d, W2d, b2d)
+            L.forward()
+            L.backward(dYd)
+            torch.cuda.synchronize()
+            Xn, H = L.gather_xn(), L.gather_h()
+            full = {}
+            for name in ("a", "dh", "da", "dxn", "dx", "dw1", "dw2"):
+                t = L.gather_grad(name)
+                assert torch.isfinite(t).all(), name
+                full[name] = t
+            g = {n: full[n][ri].cpu().numpy() for n in ("a", "dh", "da", "dxn", "dx")}
+            Xn_r, H_r = Xn[ri].cpu().numpy(), H[ri].cpu().numpy()
+            dA_h, Xn_c = full["da"][:, hi].cpu().numpy(), Xn[:, ci].cpu().numpy()       # columns over all tokens
+            H_h, dY_c = H[:, hi].cpu().numpy(), dY[:, cs]
+            dW1_s = full["dw1"][hi][:, ci].cpu().numpy()
+            dW2_s = full["dw2"][ci][:, hi].cpu().numpy()
+            dA_full, dXn_full = full["da"].cpu().numpy(), full["dxn"].cpu().numpy()
+            db1, db2 = L.gather_grad("db1").cpu().numpy(), L.gather_grad("db2").cpu().numpy()
+            dgam, dbet = L.dgamma.cpu().numpy(), L.dbeta.cpu().numpy()
+            del full, Xn, H
+        torch.cuda.empty_cache()
+        worst = {}
+
+        def within(name, got, want, S, tol=TOL):
+            e = (np.abs(f64(got) - want) / np.maximum(S, 1e-300)).max()
+            worst[name] = e
+            assert e <= tol, (ways, name, e)
+        # per sampled token, step by step
+        within("A", g["a"], oracle.linear(Xn_r, W1, b1), oracle.magnitude(Xn_r, W1, b1))
+        within("dH", g["dh"], oracle.backward(H_r, W2, dY[rows])[0], oracle.backward_magnitude(H_r, W2, dY[rows])[0])
+        dA = f64(g["dh"]) * oracle.gelu_grad(f64(g["a"]))
+        assert np.all(np.abs(f64(g["da"]) - dA) <= 2.0 ** -23 * np.abs(dA) + 1e-45), (ways, "dA")
+        within("dXn", g["dxn"], oracle.backward(Xn_r, W1, g["da"])[0], oracle.backward_magnitude(Xn_r, W1, g["da"])[0])
+        dXl, _, _, SX, _, _ = oracle.layernorm_backward(X[rows], gamma, g["dxn"], oracle.ln_groups(ways), magnitude=True)
+        want = f64(dY[rows]) + dXl
+        assert np.all(np.abs(f64(g["dx"]) - want) <= HALF * np.abs(want) * (1 + 1e-6) + 1e-11 * (SX + np.abs(dY[rows]))), (ways, "dX")
+        # sampled entries of the weight gradients: sums over all tokens of what the GPU stored
+        within("dW1", dW1_s, oracle.linear(T(dA_h), T(Xn_c)), oracle.magnitude(T(dA_h), T(Xn_c)))
+        within("dW2", dW2_s, oracle.linear(T(dY_c), T(H_h)), oracle.magnitude(T(dY_c), T(H_h)))
+        # sums over all tokens, in full
+        for name, got, src in (("db1", db1, dA_full), ("db2", db2, dY)):
+            want, S = oracle.bias_backward(src), oracle.bias_backward(src, absolute=True)
+            assert np.all(np.abs(f64(got) - want) <= HALF * np.abs(want) * (1 + 1e-6) + 1e-11 * S), (ways, name)
+        _, dg, db, _, Sg, Sb = oracle.layernorm_backward(X, gamma, dXn_full, oracle.ln_groups(ways), magnitude=True)
+        assert np.all(np.abs(f64(dgam) - dg) <= HALF * np.abs(dg) * (1 + 1e-6) + 1e-11 * Sg), (ways, "dgamma")
+        assert np.all(np.abs(f64(dbet) - db) <= HALF * np.abs(db) * (1 + 1e-6) + 1e-11 * Sb), (ways, "dbeta")
+        note(capsys, f"mixing block backward ways={ways}: {rows.size} tokens, {cs.size} x {hs.size} weight entries; max err/S "
+                     + ", ".join(f"{n} {e:.2e}" for n, e in worst.items()))
