@@ -310,11 +310,13 @@ class JigsawMixing(JigsawMLP):
         jg.jg_gather_as(self.first.plan, jg.JG_T_X_F32, [t.data_ptr() for t in self.xn], out.data_ptr(), out.stride(0))
         return out
 
-    def backward(self, dY):
+    def backward(self, dY=None, dy_shards=None):
         """Gradients of the block for an incoming gradient dY (M, C), after forward(): jg_mixing_backward.  Beside
-        the MLP's (JigsawMLP.backward) the holder keeps 'dxn' shards and the global vectors ``dgamma`` / ``dbeta``."""
+        the MLP's (JigsawMLP.backward) the holder keeps 'dxn' shards and the global vectors ``dgamma`` / ``dbeta``.
+        ``dy_shards``: the gradient already on shards partitioned like X_r (another block's 'dx'), instead of dY."""
         f, s = self.first, self.second
-        assert self.dtype == jg.JG_F32 and dY.is_cuda and dY.dtype == torch.float32 and dY.shape == (self.M, self.C)
+        assert self.dtype == jg.JG_F32 and (dY is None) != (dy_shards is None)
+        assert dY is None or (dY.is_cuda and dY.dtype == torch.float32 and dY.shape == (self.M, self.C))
         if getattr(self, "grads", None) is None:
             like = lambda ts: [torch.empty_like(t) for t in ts]
             self.grads = dict(dy=like(s.y), a=like(f.y), dh=like(f.y), da=like(f.y), dxn=like(self.xin),
@@ -327,9 +329,11 @@ class JigsawMixing(JigsawMLP):
             self.bw_ws_bytes = need
         g = self.grads
         p = lambda ts: [t.data_ptr() for t in ts]
-        jg.jg_shard(s.plan, jg.JG_T_Y, dY.data_ptr(), dY.stride(0), p(g["dy"]))
+        dy = g["dy"] if dy_shards is None else dy_shards
+        if dy_shards is None:
+            jg.jg_shard(s.plan, jg.JG_T_Y, dY.data_ptr(), dY.stride(0), p(dy))
         jg.jg_mixing_backward(f.plan, s.plan, p(self.xin), self.gamma.data_ptr() if self.gamma is not None else None,
-                              self.eps, p(self.xn), p(f.w), p(f.b), p(s.w), p(f.y), p(g["dy"]), p(g["a"]), p(g["dh"]),
+                              self.eps, p(self.xn), p(f.w), p(f.b), p(s.w), p(f.y), p(dy), p(g["a"]), p(g["dh"]),
                               p(g["da"]), p(g["dxn"]), p(g["dx"]), p(g["dw1"]), p(g["db1"]), p(g["dw2"]), p(g["db2"]),
                               self.dgamma.data_ptr(), self.dbeta.data_ptr(), self.bw_ws.data_ptr(), self.bw_ws_bytes)
 
@@ -374,12 +378,14 @@ class JigsawTokenMixing:
         jg.jg_gather_as(self.first.plan, jg.JG_T_X, [t.data_ptr() for t in self.xn], out.data_ptr(), out.stride(0))
         return out
 
-    def backward(self, dY):
+    def backward(self, dY=None, dy_shards=None):
         """Gradients of the block for an incoming gradient dY (T, C), after forward(): jg_token_mixing_backward.  The
         shards of A, dH, dA, dXn, dX, dW1, db1, dW2 are kept on the holder (``self.grads``), ``db2`` (T,), ``dgamma``
-        and ``dbeta`` (C,) as global vectors."""
+        and ``dbeta`` (C,) as global vectors.  ``dy_shards``: the gradient already on shards partitioned like X_r
+        (another block's 'dx'), instead of dY."""
         f, s = self.first, self.second
-        assert dY.is_cuda and dY.dtype == torch.float32 and dY.shape == (self.T, self.C)
+        assert (dY is None) != (dy_shards is None)
+        assert dY is None or (dY.is_cuda and dY.dtype == torch.float32 and dY.shape == (self.T, self.C))
         if getattr(self, "grads", None) is None:
             like = lambda ts: [torch.empty_like(t) for t in ts]
             self.grads = dict(dy=like(s.y), a=like(f.y), dh=like(f.y), da=like(f.y), dxn=like(f.x), dx=like(f.x),
@@ -392,9 +398,11 @@ class JigsawTokenMixing:
             self.bw_ws_bytes = need
         g = self.grads
         p = lambda ts: [t.data_ptr() for t in ts]
-        jg.jg_shard(s.plan, jg.JG_T_Y, dY.data_ptr(), dY.stride(0), p(g["dy"]))
+        dy = g["dy"] if dy_shards is None else dy_shards
+        if dy_shards is None:
+            jg.jg_shard(s.plan, jg.JG_T_Y, dY.data_ptr(), dY.stride(0), p(dy))
         jg.jg_token_mixing_backward(f.plan, s.plan, p(f.x), self.gamma.data_ptr() if self.gamma is not None else None,
-                                    self.eps, p(self.xn), p(f.w), p(f.b), p(s.x), p(f.y), p(g["dy"]), p(g["a"]),
+                                    self.eps, p(self.xn), p(f.w), p(f.b), p(s.x), p(f.y), p(dy), p(g["a"]),
                                     p(g["dh"]), p(g["da"]), p(g["dxn"]), p(g["dx"]), p(g["dw1"]), p(g["db1"]),
                                     p(g["dw2"]), self.db2.data_ptr(), self.dgamma.data_ptr(), self.dbeta.data_ptr(),
                                     self.bw_ws.data_ptr(), self.bw_ws_bytes)
@@ -456,6 +464,17 @@ class JigsawMixerBlock:
     def forward(self):
         self.token.forward()
         self.channel.forward()
+
+    def backward(self, dY):
+        """Gradients of the whole block for an incoming gradient dY (T, C), after forward(): the channel half's
+        backward, then the token half's on the channel half's dX shards in place (they are partitioned as the token
+        half's dY).  The gradients stay on the two halves (``self.channel`` / ``self.token``: grads, dgamma, dbeta,
+        db2); the block's dX is the token half's."""
+        self.channel.backward(dY)
+        self.token.backward(dy_shards=self.channel.grads["dx"])
+
+    def gather_dx(self):
+        return self.token.gather_grad("dx")
 
     def gather_token_output(self):
         return self.token.gather()

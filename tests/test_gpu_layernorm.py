@@ -615,3 +615,38 @@ def test_token_mixing_backward_size(jg, capsys):
         once("dbeta", dbet, db, Sb)
         note(capsys, f"token mixing backward ways={ways}: {cs.size} channels, {ts.size} tokens, {ts.size} x {ds.size} weight "
                      f"entries; max err/S " + ", ".join(f"{n} {e:.2e}" for n, e in worst.items()))
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+def test_whole_mixing_block_backward(jg, ctx, ways):
+    """Backward of a whole mixing block: the channel half's backward, then the token half's on its dX shards in place.
+    The halves are checked step by step in their own tests; here the hand-over on shards must give the bits of the
+    hand-over through a gathered matrix, and the whole chain must follow the oracle's chain."""
+    from paper_2507_05753_amd.layer import JigsawMixerBlock
+    T, C, Dt, Dc = 258, 264, 136, 200
+    X, g1, be1, W1, b1, W2, b2 = token_operands(380, T, C, Dt)
+    _, g2, be2, V1, c1, V2, c2 = block_operands(381, T, C, Dc)
+    dY = inputs.matrix(382, T, C, "R")
+    with JigsawMixerBlock(T, C, Dt, Dc, ways, ctx=ctx) as L:
+        L.shard(dev(X), token=dict(gamma=dev(g1), beta=dev(be1), W1=dev(W1), b1=dev(b1), W2=dev(W2), b2=dev(b2)),
+                channel=dict(gamma=dev(g2), beta=dev(be2), W1=dev(V1), b1=dev(c1), W2=dev(V2), b2=dev(c2)))
+        L.forward()
+        L.backward(dev(dY))
+        mid = L.channel.gather_grad("dx")
+        got = {k: L.token.gather_grad(k).cpu().numpy() for k in ("dx", "dw1", "dw2", "db1")}
+        got.update(db2=L.token.db2.cpu().numpy(), dgamma=L.token.dgamma.cpu().numpy())
+        chan = {k: L.channel.gather_grad(k).cpu().numpy() for k in ("dw1", "dw2")}
+        assert np.array_equal(got["dx"], L.gather_dx().cpu().numpy())
+        L.token.backward(mid)                                   # the same gradient, sharded from the gathered matrix
+        for k in ("dx", "dw1", "dw2", "db1"):
+            assert np.array_equal(got[k], L.token.gather_grad(k).cpu().numpy()), k
+        assert np.array_equal(got["db2"], L.token.db2.cpu().numpy())
+        mid = mid.cpu().numpy()
+    r1 = oracle.token_mixing_block(ways, X, g1, be1, W1, b1, W2, b2)
+    U = r1["Y"].astype(np.float32)
+    rc = oracle.mixing_block_backward(ways, U, g2, be2, V1, c1, V2, dY)
+    rt = oracle.token_mixing_block_backward(ways, X, g1, be1, W1, b1, W2, rc["dX"].astype(np.float32))
+    loose = lambda a, ref: np.all(np.abs(a - ref) <= 1e-4 * (np.abs(ref) + np.abs(ref).max()))
+    assert loose(mid, rc["dX"]) and loose(chan["dw1"], rc["dW1"]) and loose(chan["dw2"], rc["dW2"])
+    for k, name in (("dx", "dX"), ("dw1", "dW1"), ("dw2", "dW2"), ("db1", "db1"), ("db2", "db2"), ("dgamma", "dgamma")):
+        assert loose(got[k], rt[name]), k
