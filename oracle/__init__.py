@@ -357,6 +357,14 @@ def linear_reduced(X, W, b=None, terms: int = 1, nthreads: int | None = None, ab
     return f(Xh, Wh, b, nthreads) + f(Xh, Wl, None, nthreads) + f(Xl, Wh, None, nthreads)
 
 
+def linear_xtw_reduced(X, W, b=None, terms: int = 1, nthreads: int | None = None, absolute: bool = False) -> np.ndarray:
+    """The transposed layer Y = X^T W + b (X [T x C], W [T x D]) in the reduced-precision modes of linear_reduced:
+    the rounding (or the split) acts element by element, so it is that function on the transposed operands."""
+    Xt = np.ascontiguousarray(np.asarray(X, dtype=np.float32).T)
+    Wt = np.ascontiguousarray(np.asarray(W, dtype=np.float32).T)
+    return linear_reduced(Xt, Wt, b, terms, nthreads, absolute)
+
+
 def mlp_reduced(X, W1, b1, W2, b2, terms: int = 1, residual: bool = True, nthreads: int | None = None):
     """One mixing MLP in the mixed precision of Sec. 6.1: both matrix products take their operands rounded to
     bfloat16 (split in two for terms = 3) and sum exactly; bias, GELU and the skip connection are not rounded; H

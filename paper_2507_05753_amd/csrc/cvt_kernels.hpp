@@ -103,4 +103,86 @@ inline hipError_t launch_cvt_group(CvtGroup g, hipStream_t stream)
     return hipSuccess;
 }
 
+// The same conversion with the block transposed: dst row c holds column c of the source, dst[c][k] = bf16(src[k][c]).
+// This is the shard step of the transposed layer Y = X^T W (Sec. 5) in reduced precision: the bfloat16 matrix
+// kernel reads both operands along the contracted index, which for X^T W is the row index of X and W as stored, so
+// the rounding pass that the mode needs anyway also lays the shard out contraction-major.
+// A workgroup moves a 64 x 64 tile through LDS: FP32 reads along the source rows, 128-byte bfloat16 writes along
+// the destination rows.  rows (the contracted length) is a multiple of 8; cols is arbitrary.
+constexpr int CVT_T_TILE = 64;
+
+// grid: x = tile of source columns, y = tile of source rows, z = block
+template <bool VEC>
+__global__ __launch_bounds__(256) void cvt_bf16_transposed(const CvtGroup g)
+{
+    __shared__ float tile[CVT_T_TILE][CVT_T_TILE + 1];
+    const CvtBlock& B = g.b[blockIdx.z];
+    const int tid = threadIdx.x;
+    const int c0 = blockIdx.x * CVT_T_TILE, k0 = blockIdx.y * CVT_T_TILE;
+    {
+        const int tk = tid >> 4, tc = (tid & 15) * 4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int k = k0 + tk + 16 * i, c = c0 + tc;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            if (k < g.rows) {
+                const float* src = B.src + (int64_t)k * B.ld_src + c;
+                if (VEC && c + 3 < g.cols) {
+                    const vf4 a = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(src));
+                    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (c + q < g.cols) v[q] = src[q];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) tile[tk + 16 * i][tc + q] = v[q];
+        }
+    }
+    __syncthreads();
+    const int c = c0 + (tid >> 2), kk = (tid & 3) * 16;
+    if (c >= g.cols) return;
+    uint16_t* dst = B.dst + (int64_t)c * g.plane * g.planes + k0 + kk;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {       // two chunks of 8 contracted elements; rows % 8 == 0: a chunk is whole or absent
+        if (k0 + kk + 8 * h >= g.rows) break;
+        float x[8];
+        uint32_t hi[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            x[j] = tile[kk + 8 * h + j][tid >> 2];
+            hi[j] = bf16_bits(x[j]);
+        }
+        *reinterpret_cast<vu4*>(dst + 8 * h) =
+            vu4{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16)};
+        if (g.planes == 2) {
+            uint32_t lo[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) lo[j] = bf16_bits(x[j] - bf16_value(hi[j]));
+            *reinterpret_cast<vu4*>(dst + g.plane + 8 * h) =
+                vu4{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16)};
+        }
+    }
+}
+
+// g.rows x g.cols: the shape of every SOURCE block; rows % 8 == 0, g.plane >= rows and a multiple of 8; every dst
+// 16-byte aligned.  The destination has g.cols rows.
+inline hipError_t launch_cvt_transposed_group(const CvtGroup& g, hipStream_t stream)
+{
+    if (g.rows <= 0 || g.cols <= 0 || g.nblocks <= 0) return hipSuccess;
+    if ((g.rows & 7) || (g.plane & 7) || g.plane < g.rows) return hipErrorInvalidValue;
+    bool vec = true;
+    for (int i = 0; i < g.nblocks; ++i) {
+        if ((uintptr_t)g.b[i].dst & 15) return hipErrorInvalidValue;
+        if (((uintptr_t)g.b[i].src & 15) || (g.b[i].ld_src & 3)) vec = false;
+    }
+    const unsigned tk = (unsigned)((g.rows + CVT_T_TILE - 1) / CVT_T_TILE);
+    if (tk > 65535u) return hipErrorInvalidConfiguration;
+    dim3 grid((unsigned)((g.cols + CVT_T_TILE - 1) / CVT_T_TILE), tk, (unsigned)g.nblocks);
+    if (vec) hipLaunchKernelGGL(cvt_bf16_transposed<true>, grid, dim3(256), 0, stream, g);
+    else hipLaunchKernelGGL(cvt_bf16_transposed<false>, grid, dim3(256), 0, stream, g);
+    return hipGetLastError();
+}
+
 }  // namespace jg

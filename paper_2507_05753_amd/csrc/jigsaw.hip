@@ -239,7 +239,6 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     if (d.op != JG_OP_XWT && d.op != JG_OP_XTW) return JG_E_DTYPE;
     if (d.dtype != JG_F32 && d.dtype != JG_BF16 && d.dtype != JG_BF16X3) return JG_E_DTYPE;
     const bool reduced = d.dtype != JG_F32;
-    if (reduced && d.op != JG_OP_XWT) return JG_E_DTYPE;
     if (d.combine != JG_COMBINE_FUSED && d.combine != JG_COMBINE_SEPARATE) return JG_E_DTYPE;
     if (d.weights != JG_WEIGHTS_COPY && d.weights != JG_WEIGHTS_DIRECT) return JG_E_DTYPE;
     if (d.has_bias != 0 && d.has_bias != 1) return JG_E_DTYPE;
@@ -251,7 +250,8 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     if (d.ways >= 2 && ((xtw ? d.M & 1 : d.K & 1) || (d.N & 1))) return JG_E_SHAPE;
     if (d.ways == 4 && ((d.M & 1) || (d.K & 1))) return JG_E_SHAPE;
     // bfloat16 shards move in 16-byte chunks of 8 elements: a rank's share of K must be whole chunks
-    if (reduced && ((d.K / (d.ways >= 2 ? 2 : 1)) & 7)) return JG_E_SHAPE;
+    // (K is the contracted dimension of both ops; X^T W halves it in the 4-way form only)
+    if (reduced && ((d.K / ((xtw ? d.ways == 4 : d.ways >= 2) ? 2 : 1)) & 7)) return JG_E_SHAPE;
     {   // every product of the plan (forward M x N, backward M x K and N x K, up to four
         // problems a launch) must have a tile count that fits the 32-bit block index
         const int64_t tm = (d.M + jg::BM - 1) / jg::BM, tn = (d.N + jg::BM - 1) / jg::BM,
@@ -285,7 +285,8 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
         }
     }
     // bfloat16 shard rows are padded to whole 128-byte lines per plane
-    p->plane = reduced ? (p->xc + 63) / 64 * 64 : p->xc;
+    // (the transposed layer's reduced-precision shards are stored contraction-major: X_r as xc rows of xr elements)
+    p->plane = reduced ? ((xtw ? p->xr : p->xc) + 63) / 64 * 64 : p->xc;
     p->xcp = d.dtype == JG_BF16 ? p->plane / 2 : d.dtype == JG_BF16X3 ? p->plane : p->xc;
     p->part_bytes = p->wblk_bytes = 0;
     p->off_send = p->off_kept = p->off_wrecv = 0;
@@ -305,7 +306,8 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
         }
     }
     if (operand_blocks) {
-        const size_t elems = xtw ? (size_t)p->xr * (size_t)p->xc : (size_t)p->wr * (size_t)p->xcp;
+        const size_t elems = xtw ? (reduced ? (size_t)p->xc * (size_t)p->xcp : (size_t)p->xr * (size_t)p->xc)
+                                 : (size_t)p->wr * (size_t)p->xcp;
         p->wblk_bytes = round_up(elems * sizeof(float), kWsAlign);
         p->off_wrecv = off;
         off += p->wblk_bytes * d.ways;
@@ -350,7 +352,7 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     p->bw_off_tail = p->bw_ws_bytes;
     p->bw_ws_bytes += p->bw_tail_bytes;
     p->ws_bytes = round_up(p->ws_bytes, kWsAlign);
-    p->chain_shard_bytes = reduced ? round_up(4 * (size_t)p->xr * (size_t)p->xcp, kWsAlign) : 0;
+    p->chain_shard_bytes = reduced ? round_up(4 * (size_t)(xtw ? p->xc : p->xr) * (size_t)p->xcp, kWsAlign) : 0;
     p->chain_bytes = p->chain_shard_bytes * d.ways;
     *out = p;
     return JG_OK;
@@ -410,8 +412,8 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     case JG_Q_BACKWARD_GEMM_LAUNCHES: *out = d.ways == 1 ? 2 : (d.ways == 2 && !xtw) ? 3 : 4; break;
     case JG_Q_TAIL_SCRATCH_BYTES: *out = (int64_t)plan->tail_bytes; break;
     case JG_Q_BACKWARD_TAIL_SCRATCH_BYTES: *out = (int64_t)plan->bw_tail_bytes; break;
-    case JG_Q_X_SHARD_BYTES: *out = 4 * plan->xr * plan->xcp; break;
-    case JG_Q_W_SHARD_BYTES: *out = 4 * plan->wr * plan->xcp; break;
+    case JG_Q_X_SHARD_BYTES: *out = 4 * ((xtw && reduced) ? plan->xc : plan->xr) * plan->xcp; break;
+    case JG_Q_W_SHARD_BYTES: *out = 4 * ((xtw && reduced) ? plan->wc : plan->wr) * plan->xcp; break;
     case JG_Q_CHAIN_WORKSPACE_BYTES: *out = (int64_t)(plan->ws_bytes + plan->chain_bytes); break;
     case JG_Q_NORM_BACKWARD_WORKSPACE_BYTES:
         *out = (int64_t)(round_up(16 * (size_t)plan->xr, kWsAlign) * d.ways);
@@ -480,6 +482,8 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
             cv.b[r] = {global + rb * pt.rows * ld + cb * pt.cols, reinterpret_cast<uint16_t*>(shards[r]), ld};
         }
         ScopedTimer t(c, JG_KERNEL_SHARD);
+        if (d.op == JG_OP_XTW)      // contraction-major: the block's columns become the shard's rows
+            return HIP_OK(jg::launch_cvt_transposed_group(cv, c->stream)) ? JG_OK : JG_E_HIP;
         return HIP_OK(jg::launch_cvt_group(cv, c->stream)) ? JG_OK : JG_E_HIP;
     }
 
@@ -642,7 +646,11 @@ static int forward_xtw(const jg_plan* plan, const float* const* x_sh, const floa
     jg_ctx* c = plan->ctx;
     auto bias_of = [&](int r) -> const float* { return d.has_bias ? b_sh[r] : nullptr; };
     auto res_of = [&](int r) -> const float* { return r_sh ? r_sh[r] : nullptr; };
-    const int ldx = (int)plan->xc, ldw = (int)plan->wc, ldy = (int)plan->yc;
+    // reduced precision: the shards are stored contraction-major (channels x tokens), so every product is the
+    // bfloat16 kernel's own form A B^T with both leading dimensions the padded token count
+    const bool reduced = d.dtype != JG_F32;
+    const int ldx = reduced ? (int)plan->xcp : (int)plan->xc, ldw = reduced ? (int)plan->xcp : (int)plan->wc;
+    const int ldy = (int)plan->yc;
     char* tail = plan->tail_bytes ? ws + plan->off_tail : nullptr;
 
     jg::GemmGroup g;
@@ -665,11 +673,11 @@ static int forward_xtw(const jg_plan* plan, const float* const* x_sh, const floa
         std::memset(&cg, 0, sizeof(cg));
         cg.nblocks = ways;
         cg.nontemporal = 0;
-        cg.rows = (int)plan->xr;
-        cg.cols = (int)plan->xc;
+        cg.rows = reduced ? (int)plan->xc : (int)plan->xr;
+        cg.cols = reduced ? (int)plan->xcp : (int)plan->xc;
         for (int r = 0; r < ways; ++r) {
             float* dst = reinterpret_cast<float*>(ws + plan->off_wrecv + r * plan->wblk_bytes);
-            cg.b[r] = {x_sh[r ^ 1], dst, plan->xc, plan->xc};
+            cg.b[r] = {x_sh[r ^ 1], dst, cg.cols, cg.cols};
             x_in[r] = dst;
         }
         ScopedTimer t(c, JG_KERNEL_WEIGHT_COPY);

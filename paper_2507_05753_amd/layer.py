@@ -14,8 +14,8 @@ class JigsawLinear:
     """Plan + per-rank shard tensors (X_r, W_r, b_r, Y_r) + workspace on one GPU.
 
     ``op = JG_OP_XWT``: Y = X W^T with X (M, K) and W (N, K).  ``op = JG_OP_XTW``: the transposed
-    layer Y = X^T W with X (K, M) and W (K, N), forward only.  ``dtype = JG_BF16 / JG_BF16X3``: the X and W
-    shards are bfloat16 tensors (split mode: every row is [hi | lo]) written by ``shard`` from FP32 inputs.
+    layer Y = X^T W with X (K, M) and W (K, N).  ``dtype = JG_BF16 / JG_BF16X3``: the X and W shards are
+    bfloat16 tensors (split mode: every row is [hi | lo]) written by ``shard`` from FP32 inputs; forward only.
     """
 
     def __init__(self, M: int, K: int, N: int, ways: int, bias: bool = False,
@@ -41,10 +41,12 @@ class JigsawLinear:
         else:
             # rows are padded by the library (whole 128-byte lines per plane): the row length comes from the byte count
             b16 = dict(dtype=torch.bfloat16, device=self.dev)
+            # (the transposed layer's shards are stored contraction-major: one row per column of the block)
             rowlen = lambda nbytes, rows: nbytes // (2 * rows)
-            self.x = [torch.empty((q(jg.JG_Q_X_ROWS, r), rowlen(q(jg.JG_Q_X_SHARD_BYTES, r), q(jg.JG_Q_X_ROWS, r))), **b16)
+            xrows, wrows = ((jg.JG_Q_X_COLS, jg.JG_Q_W_COLS) if op == jg.JG_OP_XTW else (jg.JG_Q_X_ROWS, jg.JG_Q_W_ROWS))
+            self.x = [torch.empty((q(xrows, r), rowlen(q(jg.JG_Q_X_SHARD_BYTES, r), q(xrows, r))), **b16)
                       for r in range(ways)]
-            self.w = [torch.empty((q(jg.JG_Q_W_ROWS, r), rowlen(q(jg.JG_Q_W_SHARD_BYTES, r), q(jg.JG_Q_W_ROWS, r))), **b16)
+            self.w = [torch.empty((q(wrows, r), rowlen(q(jg.JG_Q_W_SHARD_BYTES, r), q(wrows, r))), **b16)
                       for r in range(ways)]
         self.y = [torch.empty((q(jg.JG_Q_Y_ROWS, r), q(jg.JG_Q_Y_COLS, r)), **f32) for r in range(ways)]
         self.b = [torch.empty((q(jg.JG_Q_B_LEN, r),), **f32) for r in range(ways)] if bias else None

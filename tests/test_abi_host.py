@@ -56,13 +56,17 @@ def test_plan_validation():
     assert status_of(M=7, ways=4) == jg.JG_E_SHAPE    # 4-way needs even M too
     assert status_of(M=7, K=7, N=7, ways=1) == jg.JG_OK
     assert status_of(dtype=3) == jg.JG_E_DTYPE
-    # reduced precision: forward of X W^T only, and every rank's share of K in whole 8-element chunks
+    # reduced precision: forward only, and every rank's share of K in whole 8-element chunks
     for dt in (jg.JG_BF16, jg.JG_BF16X3):
         assert status_of(dtype=dt) == jg.JG_E_SHAPE                 # K / 2 = 4
         assert status_of(dtype=dt, K=16) == jg.JG_OK
         assert status_of(dtype=dt, K=8, ways=1) == jg.JG_OK
         assert status_of(dtype=dt, K=24, ways=4) == jg.JG_E_SHAPE   # K / 2 = 12
-        assert status_of(dtype=dt, K=16, op=jg.JG_OP_XTW) == jg.JG_E_DTYPE
+        # the transposed layer contracts over K too, and halves it in the 4-way form only
+        assert status_of(dtype=dt, K=8, op=jg.JG_OP_XTW) == jg.JG_OK
+        assert status_of(dtype=dt, K=8, op=jg.JG_OP_XTW, ways=4) == jg.JG_E_SHAPE
+        assert status_of(dtype=dt, K=16, op=jg.JG_OP_XTW, ways=4) == jg.JG_OK
+        assert status_of(dtype=dt, K=12, op=jg.JG_OP_XTW, ways=1) == jg.JG_E_SHAPE
     assert status_of(op=2) == jg.JG_E_DTYPE
     # the transposed layer splits M and N (2-way), and K as well (4-way)
     assert status_of(op=jg.JG_OP_XTW) == jg.JG_OK
@@ -469,3 +473,30 @@ def test_token_mixing_backward_checks_that_the_plans_chain():
     assert call(plain, plain) == jg.JG_E_DTYPE                                    # the first layer must be the transposed one
     jg.jg_plan_destroy(plain)
     jg.jg_plan_destroy(first)
+
+
+def test_reduced_precision_transposed_plans_account_for_their_shards():
+    M, K, N = 36, 272, 20        # X is K x M, W is K x N; the shards are stored contraction-major
+    for ways in (1, 2, 4):
+        f = jg.jg_plan_create(None, M, K, N, ways, op=jg.JG_OP_XTW)
+        h = jg.jg_plan_create(None, M, K, N, ways, op=jg.JG_OP_XTW, dtype=jg.JG_BF16)
+        s = jg.jg_plan_create(None, M, K, N, ways, op=jg.JG_OP_XTW, dtype=jg.JG_BF16X3)
+        q = jg.jg_plan_query
+        for r in range(ways):
+            kr = q(f, jg.JG_Q_X_ROWS, r)                       # the rank's share of the contracted dimension
+            plane = (kr + 63) // 64 * 64
+            xc, wc = q(f, jg.JG_Q_X_COLS, r), q(f, jg.JG_Q_W_COLS, r)
+            assert q(h, jg.JG_Q_X_SHARD_BYTES, r) == 2 * xc * plane and q(h, jg.JG_Q_W_SHARD_BYTES, r) == 2 * wc * plane
+            assert q(s, jg.JG_Q_X_SHARD_BYTES, r) == 4 * xc * plane and q(s, jg.JG_Q_W_SHARD_BYTES, r) == 4 * wc * plane
+            assert (q(h, jg.JG_Q_X_ROWS, r), q(h, jg.JG_Q_X_COLS, r)) == (kr, xc)      # logical sizes do not change
+        assert q(h, jg.JG_Q_FLOPS_TOTAL) == 2 * M * K * N
+        extra = 8 * M * N if ways == 4 else 0
+        assert q(h, jg.JG_Q_HBM_BYTES_ALGO) == 2 * (M * K + N * K) + 4 * M * N + extra
+        if ways >= 2:   # the activation block a rank receives is bfloat16 too
+            assert (q(h, jg.JG_Q_WORKSPACE_BYTES) - q(h, jg.JG_Q_TAIL_SCRATCH_BYTES)
+                    < q(f, jg.JG_Q_WORKSPACE_BYTES) - q(f, jg.JG_Q_TAIL_SCRATCH_BYTES))
+        with pytest.raises(jg.JigsawError) as e:
+            q(h, jg.JG_Q_BACKWARD_WORKSPACE_BYTES)
+        assert e.value.status == jg.JG_E_DTYPE
+        for p in (f, h, s):
+            jg.jg_plan_destroy(p)

@@ -515,3 +515,87 @@ def test_config3_full_size(jg, capsys):
             e = np.abs(Y[np.ix_(I, J)] - want) / mag
             assert e.max() <= TOL, (ways, e.max())
             note(capsys, f"terms={t} ways={ways}: Freivalds {(err / frb).max():.2e}, {e.size} entries max err/S {e.max():.2e}")
+
+
+# ---------------------------------------------------------------------------------------------
+# the transposed layer Y = X^T W in reduced precision: the shard step writes contraction-major bfloat16 shards
+# ---------------------------------------------------------------------------------------------
+# (K = tokens, M = channels, N): a rank's share of K in whole 8-element chunks (the 4-way form halves K)
+XTW_SHAPES = [(16, 2, 2), (80, 100, 100), (144, 130, 258), (1040, 258, 136), (272, 520, 600), (4112, 74, 260)]
+
+
+def run_xtw(jg, ctx, X, W, b, ways, dtype, combine=0, weights=0):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    K, M = X.shape
+    N = W.shape[1]
+    with JigsawLinear(M, K, N, ways, bias=b is not None, combine=combine, weights=weights, ctx=ctx, dtype=dtype,
+                      op=jg.JG_OP_XTW) as L:
+        if L.ws_bytes:
+            L.ws.fill_(0xFF)
+        for t in L.y:
+            t.fill_(float("nan"))
+        L.shard(dev(X), dev(W), dev(b) if b is not None else None)
+        L.forward()
+        Y = L.gather()
+        torch.cuda.synchronize()
+        return Y.cpu().numpy(), [as_f32(t) for t in L.x], [as_f32(t) for t in L.w]
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+@pytest.mark.parametrize("K,M,N", XTW_SHAPES)
+def test_transposed_layer_shards_and_forward(jg, ctx, ways, dtype_name, K, M, N):
+    dtype = getattr(jg, dtype_name)
+    X = (inputs.matrix(430, K, M, "R") * np.float32(3.0)).astype(np.float32)
+    W = inputs.matrix(431, K, N, "R", inputs.W_SCALE_EXP)
+    b = inputs.matrix(432, 1, N, "R")[0]
+    Y, xs, ws = run_xtw(jg, ctx, X, W, b, ways, dtype)
+    # the shards: block (row half, column half) of the FP32 matrix, transposed, rounded (or split) element by element
+    rows, cols = (2 if ways == 4 else 1), (2 if ways >= 2 else 1)
+    for got, src in ((xs, X), (ws, W)):
+        kr, cc = src.shape[0] // rows, src.shape[1] // cols
+        plane = (kr + 63) // 64 * 64
+        for r, g in enumerate(got):
+            i, j = (r // 2, r % 2) if ways == 4 else (0, r)
+            blk = np.ascontiguousarray(src[i * kr:(i + 1) * kr, j * cc:(j + 1) * cc].T)
+            assert g.shape[0] == cc
+            if dtype == jg.JG_BF16:
+                assert g.shape[1] == plane and np.array_equal(g[:, :kr], oracle.round_bf16(blk))
+            else:
+                hi, lo = oracle.split_bf16(blk)
+                assert g.shape[1] == 2 * plane
+                assert np.array_equal(g[:, :kr], hi) and np.array_equal(g[:, plane:plane + kr], lo)
+    t = terms_of(jg, dtype)
+    want = oracle.linear_xtw_reduced(X, W, b, t)
+    S = oracle.linear_xtw_reduced(X, W, b, t, absolute=True)
+    err = np.abs(Y.astype(np.float64) - want)
+    assert np.all(err <= TOL * S), f"max err/S = {(err / S).max():.3e}"
+    full = np.abs(Y.astype(np.float64) - oracle.linear_xtw(X, W, b)) / oracle.magnitude_xtw(X, W, b)
+    if dtype == jg.JG_BF16X3:
+        assert full.max() <= 2.0 ** -15
+    elif K >= 80:
+        assert full.max() > 1e-5
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+def test_transposed_layer_is_bit_exact_on_lattice_inputs(jg, ctx, ways, dtype_name):
+    K, M, N = 528, 264, 136
+    X, W = inputs.matrix(433, K, M, "L"), inputs.matrix(434, K, N, "L")
+    b = inputs.matrix(435, 1, N, "L")[0]
+    Y, _, _ = run_xtw(jg, ctx, X, W, b, ways, getattr(jg, dtype_name))
+    assert np.array_equal(Y.astype(np.float64), oracle.linear_xtw(X, W, b))
+
+
+@pytest.mark.parametrize("ways", [2, 4])
+@pytest.mark.parametrize("combine,weights", [(1, 0), (0, 1), (1, 1)])
+def test_transposed_layer_option_variants(jg, ctx, ways, combine, weights):
+    K, M, N = 272, 130, 258
+    X, W = inputs.matrix(436, K, M, "R"), inputs.matrix(437, K, N, "R", inputs.W_SCALE_EXP)
+    b = inputs.matrix(438, 1, N, "R")[0]
+    base, _, _ = run_xtw(jg, ctx, X, W, b, ways, jg.JG_BF16)
+    Y, _, _ = run_xtw(jg, ctx, X, W, b, ways, jg.JG_BF16, combine, weights)
+    S = oracle.linear_xtw_reduced(X, W, b, 1, absolute=True)
+    assert np.all(np.abs(Y.astype(np.float64) - oracle.linear_xtw_reduced(X, W, b, 1)) <= TOL * S)
+    if combine == 0:
+        assert np.array_equal(Y, base)      # where the activation block is read from does not change the arithmetic

@@ -191,3 +191,28 @@ def test_mixed_block_norms_first_and_skips_in_full_precision(ways):
     # zero second layer: the block is the identity plus b2
     z = oracle.mixing_block_reduced(ways, X, gamma, beta, W1, b1, np.zeros_like(W2), b2, 1)
     assert np.array_equal(z["Y"], X.astype(np.float64) + b2)
+
+
+@pytest.mark.parametrize("terms", [1, 3])
+def test_transposed_layer_in_reduced_precision(terms):
+    """linear_xtw_reduced: the rounding acts on the elements, the product is the transposed layer's."""
+    T, C, D = 24, 6, 10
+    X = inputs.matrix(61, T, C, "R") * np.float32(3.0)
+    W = inputs.matrix(62, T, D, "R", inputs.W_SCALE_EXP)
+    b = inputs.matrix(63, 1, D, "R")[0]
+    got = oracle.linear_xtw_reduced(X, W, b, terms)
+    if terms == 1:
+        want = oracle.linear_xtw(oracle.round_bf16(X), oracle.round_bf16(W), b)     # exact products of rounded operands
+        assert np.array_equal(got, want)
+        assert np.abs(got - oracle.linear_xtw(X, W, b)).max() > 1e-4               # and the rounding is there
+    else:
+        (xh, xl), (wh, wl) = oracle.split_bf16(X), oracle.split_bf16(W)
+        want = (oracle.linear_xtw(xh, wh) + oracle.linear_xtw(xh, wl) + oracle.linear_xtw(xl, wh)) + b.astype(np.float64)
+        S = oracle.linear_xtw_reduced(X, W, b, terms, absolute=True)
+        assert np.all(np.abs(got - want) <= 1e-14 * S)
+        assert np.all(np.abs(got - oracle.linear_xtw(X, W, b)) <= 2.0 ** -15 * oracle.magnitude_xtw(X, W, b))
+    # X^T W, not X W^T or W^T X: shapes tell them apart
+    assert got.shape == (C, D)
+    # lattice values are not changed by the mode
+    XL, WL = inputs.matrix(64, T, C, "L"), inputs.matrix(65, T, D, "L")
+    assert np.array_equal(oracle.linear_xtw_reduced(XL, WL, None, terms), oracle.linear_xtw(XL, WL))
