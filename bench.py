@@ -265,7 +265,8 @@ def measure_xtw(cfg, ways, args):
     W = inputs.matrix_torch(seed + inputs.W_STREAM, K, N, "R", inputs.W_SCALE_EXP, device=dev)
     combine = jg.JG_COMBINE_FUSED if args.combine == "fused" else jg.JG_COMBINE_SEPARATE
     weights = jg.JG_WEIGHTS_COPY if args.weights == "copy" else jg.JG_WEIGHTS_DIRECT
-    with JigsawLinear(M, K, N, ways, combine=combine, weights=weights, op=jg.JG_OP_XTW, tail=tail_of(args)) as L:
+    with JigsawLinear(M, K, N, ways, combine=combine, weights=weights, op=jg.JG_OP_XTW, tail=tail_of(args),
+                      dtype=dtype_of(args, jg)) as L:
         L.shard(X, W)
         del X, W
         sec, gemm_ms, gemm_n, copy_ms, comb_ms = time_forward(L, jg, args.steps, args.warmup)
@@ -663,7 +664,7 @@ def cpu_baseline_mlp(cfg, seconds, terms=0):
                        + ("fp64 loops" if not terms else f"bfloat16 rounding / split + fp64 loops, {terms} per layer"))
 
 
-def cpu_baseline_xtw(cfg, seconds):
+def cpu_baseline_xtw(cfg, seconds, terms=0):
     """The transposed-layer oracle timed on a bounded sample of channels (columns of X = rows of Y)."""
     import numpy as np
     import oracle
@@ -676,7 +677,10 @@ def cpu_baseline_xtw(cfg, seconds):
     def run(ch):
         Xs = np.ascontiguousarray(X[:, :ch])
         t0 = time.perf_counter()
-        oracle.linear_xtw(Xs, W, None, nthreads=cores)
+        if terms:
+            oracle.linear_xtw_reduced(Xs, W, None, terms, nthreads=cores)
+        else:
+            oracle.linear_xtw(Xs, W, None, nthreads=cores)
         return time.perf_counter() - t0
 
     probe = min(M, cores)
@@ -685,7 +689,8 @@ def cpu_baseline_xtw(cfg, seconds):
     ch = min(M, max(cores, ch // cores * cores))
     dt = run(ch)
     return dict(value=ch * K / dt, unit="items/s", cores=cores, kind="oracle",
-                sample=f"channels 0..{ch - 1} of X ({K} x {ch}) against all of W ({K} x {N}), {dt:.1f} s, fp64 loops")
+                sample=f"channels 0..{ch - 1} of X ({K} x {ch}) against all of W ({K} x {N}), {dt:.1f} s, "
+                       + ("fp64 loops" if not terms else f"bfloat16 rounding / split + fp64 loops, {terms} product(s)"))
 
 
 def cpu_baseline_backward(cfg, seconds):
@@ -767,8 +772,8 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     from paper_2507_05753_amd import inputs
-    if args.dtype != "f32" and args.op not in ("forward", "mlp", "mixing"):
-        print("bench.py: --dtype bf16 / bf16x3 goes with --op forward, mlp or mixing only", file=sys.stderr)
+    if args.dtype != "f32" and args.op not in ("forward", "xtw", "mlp", "mixing"):
+        print("bench.py: --dtype bf16 / bf16x3 goes with --op forward, xtw, mlp or mixing only", file=sys.stderr)
         sys.exit(2)
 
     if args.op == "xtw":
@@ -779,21 +784,20 @@ def main():
             "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
             "value": r["items_per_s"], "unit": "items/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
-            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
             "config": {"workload": f"token mixing of the 1B model: Y = X^T W, X {K} x {M} [tokens, channels], "
-                                   f"W {K} x {N}, {args.ways}-way Jigsaw, fp32",
+                                   f"W {K} x {N}, {args.ways}-way Jigsaw, {precision_words(args)}",
                        "n_items": M * K, "ways": args.ways, "M": M, "K": K, "N": N, "seed": xc["seed"],
-                       "x_values": "R", "op": "xtw", "combine": args.combine, "weights": args.weights, "tail": args.tail},
+                       "x_values": "R", "op": "xtw", "combine": args.combine, "weights": args.weights, "tail": args.tail,
+                       "mode": args.dtype},
             "tflops": r["tflops"], "hbm_algo_gbps": r["hbm_algo_gbps"],
-            "roofline": {"bound": "mfma", "kernel": "jg::gemm_f32_stream<true, true, false>", "achieved": r["gemm_tflops"],
-                         "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": r["gemm_tflops"] / FP32_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None,
-                         "avg_launch_ms": r["gemm_avg_launch_ms"], "launches": r["gemm_launches_timed"],
-                         "traffic": None},
+            "roofline": gemm_roofline(args, r),
             "other_kernels_ms_per_step": r["other_kernels_ms_per_step"],
         }
+        if args.dtype == "f32":
+            line["roofline"]["kernel"] = "jg::gemm_f32_stream<true, true, false>"
         if args.cpu_seconds > 0:
-            line["cpu_baseline"] = cpu_baseline_xtw(xc, args.cpu_seconds)
+            line["cpu_baseline"] = cpu_baseline_xtw(xc, args.cpu_seconds, reduced_terms(args))
         print(json.dumps(line), flush=True)
         return
 

@@ -97,13 +97,16 @@ typedef struct jg_linear_desc {
                             M x K, W is N x K.  JG_OP_XTW: X is K x M, W is K x N.      */
     int32_t ways;        /* 1, 2 or 4                                                   */
     int32_t op;          /* JG_OP_XWT or JG_OP_XTW                                      */
-    int32_t dtype;       /* JG_F32, or JG_BF16 / JG_BF16X3: JG_OP_XWT forward only, and every
-                            rank's share of K (K, or K / 2 for 2 and 4 ways) must be a
-                            multiple of 8; the X and W shards are then bfloat16 arrays of
-                            JG_Q_X_SHARD_BYTES / JG_Q_W_SHARD_BYTES bytes, 16-byte aligned,
-                            written by jg_shard: xr rows per shard, each row xc values padded
-                            to a multiple of 64 (whole 128-byte lines; the padding is never
-                            read), JG_BF16X3 every row as [hi(0..xc) pad | lo(0..xc) pad]  */
+    int32_t dtype;       /* JG_F32, or JG_BF16 / JG_BF16X3: forward only.  The X and W shards
+                            are then bfloat16 arrays of JG_Q_X_SHARD_BYTES /
+                            JG_Q_W_SHARD_BYTES bytes, 16-byte aligned, written by jg_shard.
+                            JG_OP_XWT: every rank's share of K (K, or K / 2 for 2 and 4
+                            ways) must be a multiple of 8; xr rows per shard, each row xc
+                            values padded to a multiple of 64 (whole 128-byte lines; the
+                            padding is never read), JG_BF16X3 every row as
+                            [hi(0..xc) pad | lo(0..xc) pad].  JG_OP_XTW: any K; the shards
+                            are stored contraction-major - xc (wc) rows of the rank's xr
+                            tokens, padded likewise, zeros up to the next multiple of 8  */
     int32_t has_bias;    /* 0 / 1: b_r (the slice of b matching Y_r's columns) is added
                             once, by the rank that owns the output block                */
     int32_t combine;     /* JG_COMBINE_FUSED: the kept-product GEMM starts its accumulators
@@ -214,7 +217,8 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out);
  * Reduced-precision plans (JG_BF16, JG_BF16X3): `global` is FP32 all the same; X and W shards are
  * written as bfloat16 (see jg_linear_desc.dtype; the pointers in `shards` are then those buffers,
  * 16-byte aligned), each value rounded on its bit pattern — bit-exact against that definition; b and
- * Y stay FP32.
+ * Y stay FP32.  For a JG_OP_XTW plan the same pass transposes each block (Sec. 5: the transposed layer
+ * contracts over the row index of X and W; the bfloat16 matrix kernel reads along the contracted index).
  * Errors: JG_E_NULL, JG_E_SHAPE (ld), JG_E_ALIGN, JG_E_DTYPE (which), JG_E_HIP. */
 int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, float* const* shards);
 

@@ -108,7 +108,9 @@ inline hipError_t launch_cvt_group(CvtGroup g, hipStream_t stream)
 // kernel reads both operands along the contracted index, which for X^T W is the row index of X and W as stored, so
 // the rounding pass that the mode needs anyway also lays the shard out contraction-major.
 // A workgroup moves a 64 x 64 tile through LDS: FP32 reads along the source rows, 128-byte bfloat16 writes along
-// the destination rows.  rows (the contracted length) is a multiple of 8; cols is arbitrary.
+// the destination rows.  rows (the contracted length) and cols are arbitrary; a destination row is written up to the
+// next multiple of 8 elements, with zeros past `rows`, so that the matrix kernel can contract over whole 16-byte
+// chunks (a zero times a zero adds nothing).
 constexpr int CVT_T_TILE = 64;
 
 // grid: x = tile of source columns, y = tile of source rows, z = block
@@ -145,8 +147,8 @@ __global__ __launch_bounds__(256) void cvt_bf16_transposed(const CvtGroup g)
     if (c >= g.cols) return;
     uint16_t* dst = B.dst + (int64_t)c * g.plane * g.planes + k0 + kk;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {       // two chunks of 8 contracted elements; rows % 8 == 0: a chunk is whole or absent
-        if (k0 + kk + 8 * h >= g.rows) break;
+    for (int h = 0; h < 2; ++h) {       // two chunks of 8 contracted elements (the tile holds zeros past `rows`)
+        if (k0 + kk + 8 * h >= g.rows) break;       // nothing of this chunk is inside: absent
         float x[8];
         uint32_t hi[8];
 #pragma unroll
@@ -166,12 +168,12 @@ __global__ __launch_bounds__(256) void cvt_bf16_transposed(const CvtGroup g)
     }
 }
 
-// g.rows x g.cols: the shape of every SOURCE block; rows % 8 == 0, g.plane >= rows and a multiple of 8; every dst
+// g.rows x g.cols: the shape of every SOURCE block; g.plane >= rows rounded up to 8 and a multiple of 8; every dst
 // 16-byte aligned.  The destination has g.cols rows.
 inline hipError_t launch_cvt_transposed_group(const CvtGroup& g, hipStream_t stream)
 {
     if (g.rows <= 0 || g.cols <= 0 || g.nblocks <= 0) return hipSuccess;
-    if ((g.rows & 7) || (g.plane & 7) || g.plane < g.rows) return hipErrorInvalidValue;
+    if ((g.plane & 7) || g.plane < (g.rows + 7) / 8 * 8) return hipErrorInvalidValue;
     bool vec = true;
     for (int i = 0; i < g.nblocks; ++i) {
         if ((uintptr_t)g.b[i].dst & 15) return hipErrorInvalidValue;

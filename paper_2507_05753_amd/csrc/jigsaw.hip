@@ -250,8 +250,8 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     if (d.ways >= 2 && ((xtw ? d.M & 1 : d.K & 1) || (d.N & 1))) return JG_E_SHAPE;
     if (d.ways == 4 && ((d.M & 1) || (d.K & 1))) return JG_E_SHAPE;
     // bfloat16 shards move in 16-byte chunks of 8 elements: a rank's share of K must be whole chunks
-    // (K is the contracted dimension of both ops; X^T W halves it in the 4-way form only)
-    if (reduced && ((d.K / ((xtw ? d.ways == 4 : d.ways >= 2) ? 2 : 1)) & 7)) return JG_E_SHAPE;
+    // (the transposed layer's shard step pads its contraction-major rows with zeros instead: any K)
+    if (reduced && !xtw && ((d.K / (d.ways >= 2 ? 2 : 1)) & 7)) return JG_E_SHAPE;
     {   // every product of the plan (forward M x N, backward M x K and N x K, up to four
         // problems a launch) must have a tile count that fits the 32-bit block index
         const int64_t tm = (d.M + jg::BM - 1) / jg::BM, tn = (d.N + jg::BM - 1) / jg::BM,
@@ -658,6 +658,7 @@ static int forward_xtw(const jg_plan* plan, const float* const* x_sh, const floa
     g.M = (int)plan->xc;   // channels of one X block = rows of one Y block
     g.N = (int)plan->wc;
     g.K = (int)plan->xr;   // tokens of one block
+    if (reduced) g.K = (g.K + 7) / 8 * 8;      // whole 16-byte chunks: the shard step wrote zeros past the last token
 
     if (ways == 1) {
         g.nprob = 1;

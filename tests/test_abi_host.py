@@ -62,11 +62,11 @@ def test_plan_validation():
         assert status_of(dtype=dt, K=16) == jg.JG_OK
         assert status_of(dtype=dt, K=8, ways=1) == jg.JG_OK
         assert status_of(dtype=dt, K=24, ways=4) == jg.JG_E_SHAPE   # K / 2 = 12
-        # the transposed layer contracts over K too, and halves it in the 4-way form only
+        # the transposed layer's shard step pads the contracted dimension itself: any K that `ways` divides
         assert status_of(dtype=dt, K=8, op=jg.JG_OP_XTW) == jg.JG_OK
-        assert status_of(dtype=dt, K=8, op=jg.JG_OP_XTW, ways=4) == jg.JG_E_SHAPE
-        assert status_of(dtype=dt, K=16, op=jg.JG_OP_XTW, ways=4) == jg.JG_OK
-        assert status_of(dtype=dt, K=12, op=jg.JG_OP_XTW, ways=1) == jg.JG_E_SHAPE
+        assert status_of(dtype=dt, K=12, op=jg.JG_OP_XTW, ways=4) == jg.JG_OK
+        assert status_of(dtype=dt, K=7, op=jg.JG_OP_XTW, ways=1) == jg.JG_OK
+        assert status_of(dtype=dt, K=7, op=jg.JG_OP_XTW, ways=4) == jg.JG_E_SHAPE
     assert status_of(op=2) == jg.JG_E_DTYPE
     # the transposed layer splits M and N (2-way), and K as well (4-way)
     assert status_of(op=jg.JG_OP_XTW) == jg.JG_OK

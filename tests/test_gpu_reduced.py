@@ -520,8 +520,8 @@ def test_config3_full_size(jg, capsys):
 # ---------------------------------------------------------------------------------------------
 # the transposed layer Y = X^T W in reduced precision: the shard step writes contraction-major bfloat16 shards
 # ---------------------------------------------------------------------------------------------
-# (K = tokens, M = channels, N): a rank's share of K in whole 8-element chunks (the 4-way form halves K)
-XTW_SHAPES = [(16, 2, 2), (80, 100, 100), (144, 130, 258), (1040, 258, 136), (272, 520, 600), (4112, 74, 260)]
+# (K = tokens, M = channels, N): any K (the shard step pads a rank's share of it to whole 8-element chunks with zeros)
+XTW_SHAPES = [(16, 2, 2), (30, 6, 4), (80, 100, 100), (142, 130, 258), (1040, 258, 136), (272, 520, 600), (4100, 74, 260)]
 
 
 def run_xtw(jg, ctx, X, W, b, ways, dtype, combine=0, weights=0):
@@ -599,3 +599,39 @@ def test_transposed_layer_option_variants(jg, ctx, ways, combine, weights):
     assert np.all(np.abs(Y.astype(np.float64) - oracle.linear_xtw_reduced(X, W, b, 1)) <= TOL * S)
     if combine == 0:
         assert np.array_equal(Y, base)      # where the activation block is read from does not change the arithmetic
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+def test_transposed_layer_at_token_mixing_size(jg, capsys, dtype_name):
+    """The first token-mixing linear of the 1B model (16200 tokens, 4320 channels, 8640 hidden) in reduced precision,
+    in the launch configuration bench.py --op xtw --dtype ... times: whole rows of Y for sampled channels against the
+    oracle, everything finite.  (The 4-way form halves 16200 tokens to 8100, not a multiple of 8: the zero padding.)"""
+    from paper_2507_05753_amd.layer import JigsawLinear
+    dtype = getattr(jg, dtype_name)
+    t = terms_of(jg, dtype)
+    cfg = inputs.XTW_CONFIGS["token_mixing_1b"]
+    K, M, N, seed = cfg["K"], cfg["M"], cfg["N"], cfg["seed"]
+    Xd = inputs.matrix_torch(seed, K, M, "R", device="cuda")
+    Wd = inputs.matrix_torch(seed + inputs.W_STREAM, K, N, "R", inputs.W_SCALE_EXP, device="cuda")
+    W = Wd.cpu().numpy()
+    k = inputs.keys(5100, np.arange(12, dtype=np.uint64))
+    I = np.unique(np.concatenate([(k % np.uint64(M)).astype(np.int64), [0, M // 2 - 1, M // 2, M - 1]]))
+    Xs = np.ascontiguousarray(Xd[:, torch.from_numpy(I).cuda()].cpu().numpy())        # the sampled channels' columns
+    want = oracle.linear_xtw_reduced(Xs, W, None, t)
+    S = oracle.linear_xtw_reduced(Xs, W, None, t, absolute=True)
+    note(capsys, f"{dtype_name} transposed layer: oracle rows ready ({I.size} channels x {N})")
+    for ways in (1, 2, 4):
+        with JigsawLinear(M, K, N, ways, op=jg.JG_OP_XTW, dtype=dtype) as L:
+            L.ws.fill_(0xFF)
+            L.shard(Xd, Wd)
+            L.forward()
+            Y = L.gather()
+            torch.cuda.synchronize()
+            assert torch.isfinite(Y).all()
+            Ys = Y[torch.from_numpy(I).cuda()].cpu().numpy().astype(np.float64)
+            del Y
+        torch.cuda.empty_cache()
+        e = (np.abs(Ys - want) / S).max()
+        assert e <= TOL, (ways, e)
+        note(capsys, f"{dtype_name} transposed layer ways={ways}: {Ys.size} entries max err/S {e:.2e}")
