@@ -410,7 +410,7 @@ def measure_token_mixing(cfg, ways, args):
     T, C, D, seed = cfg["K"], cfg["M"], cfg["N"], cfg["seed"]
     dev = torch.device("cuda", 0)
     gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device=dev)
-    with JigsawTokenMixing(T, C, D, ways, tail=tail_of(args)) as L:
+    with JigsawTokenMixing(T, C, D, ways, tail=tail_of(args), dtype=dtype_of(args, jg)) as L:
         L.shard(gen(seed, T, C), (gen(seed + 5, 1, C)[0] + 1.5).contiguous(), gen(seed + 6, 1, C)[0].contiguous(),
                 gen(seed + 1, T, D, inputs.W_SCALE_EXP), gen(seed + 2, 1, D)[0].contiguous(),
                 gen(seed + 3, T, D, inputs.W_SCALE_EXP), gen(seed + 4, 1, T)[0].contiguous())
@@ -430,7 +430,7 @@ def measure_token_mixing(cfg, ways, args):
     return out
 
 
-def cpu_baseline_token_mixing(cfg, seconds):
+def cpu_baseline_token_mixing(cfg, seconds, terms=0):
     """The token-mixing oracle timed on a bounded sample of channels (columns of X; the norm sees only those)."""
     import oracle
     from paper_2507_05753_amd import inputs
@@ -448,7 +448,10 @@ def cpu_baseline_token_mixing(cfg, seconds):
         gamma = (inputs.matrix(seed + 5, 1, C, "R")[0][:ch] + 1.5).astype("float32")
         beta = inputs.matrix(seed + 6, 1, C, "R")[0][:ch]
         t0 = time.perf_counter()
-        oracle.token_mixing_block(1, Xs, gamma, beta, W1, b1, W2, b2)
+        if terms:
+            oracle.token_mixing_block_reduced(1, Xs, gamma, beta, W1, b1, W2, b2, terms)
+        else:
+            oracle.token_mixing_block(1, Xs, gamma, beta, W1, b1, W2, b2)
         return time.perf_counter() - t0
 
     probe = min(C, 4)
@@ -772,8 +775,9 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     from paper_2507_05753_amd import inputs
-    if args.dtype != "f32" and args.op not in ("forward", "xtw", "mlp", "mixing"):
-        print("bench.py: --dtype bf16 / bf16x3 goes with --op forward, xtw, mlp or mixing only", file=sys.stderr)
+    if args.dtype != "f32" and args.op not in ("forward", "xtw", "mlp", "mixing", "token_mixing"):
+        print("bench.py: --dtype bf16 / bf16x3 goes with --op forward, xtw, mlp, mixing or token_mixing only",
+              file=sys.stderr)
         sys.exit(2)
 
     if args.op == "xtw":
@@ -809,18 +813,14 @@ def main():
             "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
             "value": r["items_per_s"], "unit": "items/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
-            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
             "config": {"workload": f"token-mixing half of a mixing block of the 1B model: Xn = layernorm(X), "
                                    f"H = gelu(Xn^T W1 + b1), Y = X + W2 H^T + b2, X {T} x {C} [tokens, channels], "
-                                   f"hidden {D}, {args.ways}-way Jigsaw, fp32",
+                                   f"hidden {D}, {args.ways}-way Jigsaw, {precision_words(args)}",
                        "n_items": T * C, "ways": args.ways, "T": T, "C": C, "D": D, "seed": xc["seed"],
-                       "x_values": "R", "op": "token_mixing", "tail": args.tail},
+                       "x_values": "R", "op": "token_mixing", "tail": args.tail, "mode": args.dtype},
             "tflops": r["tflops"],
-            "roofline": {"bound": "mfma", "kernel": "jg::gemm_f32_stream (<true, true> and <false, false>)",
-                         "achieved": r["gemm_tflops"], "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": r["gemm_tflops"] / FP32_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None,
-                         "avg_launch_ms": r["gemm_avg_launch_ms"], "launches": r["gemm_launches_timed"],
-                         "traffic": None},
+            "roofline": gemm_roofline(args, r),
             "layernorm": {"bound": "hbm", "kernel": "jg::layernorm_rows_f32", "achieved": r["norm_gbps"],
                           "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                           "frac": r["norm_gbps"] / HBM_PEAK_GBPS if r["norm_gbps"] else None,
@@ -828,8 +828,10 @@ def main():
                           "bytes_per_element": 12},
             "other_kernels_ms_per_step": r["other_kernels_ms_per_step"],
         }
+        if args.dtype == "f32":
+            line["roofline"]["kernel"] = "jg::gemm_f32_stream (<true, true> and <false, false>)"
         if args.cpu_seconds > 0:
-            line["cpu_baseline"] = cpu_baseline_token_mixing(xc, args.cpu_seconds)
+            line["cpu_baseline"] = cpu_baseline_token_mixing(xc, args.cpu_seconds, reduced_terms(args))
         print(json.dumps(line), flush=True)
         return
 

@@ -351,6 +351,11 @@ int jg_mixing_forward(const jg_plan* first, const jg_plan* second, const float* 
  * eps, xn_sh as in jg_mixing_forward; h_sh: `ways` buffers shaped like the first plan's Y_r; y_sh: like X_r.
  * Workspace: the larger of the two plans' JG_Q_WORKSPACE_BYTES, plus the first plan's JG_Q_X_F32_SHARDS_BYTES when
  * b2 is given (the norm writes X + b2 there for the skip connection).
+ * Mixed precision (Sec. 6.1): both plans JG_BF16, or both JG_BF16X3.  x_sh, xn_sh, h_sh and y_sh are then still FP32
+ * shards (x_sh as jg_shard(first, JG_T_X_F32) writes them); w1_sh and w2_sh are the plans' bfloat16 shards
+ * (jg_shard(first, JG_T_W) and jg_shard(second, JG_T_X)); the chain rounds Xn (contraction-major, as the first
+ * plan's X shards) and H (as the second plan's W shards) into the workspace, which grows by `ways` times the first
+ * plan's JG_Q_X_SHARD_BYTES and `ways` times the second plan's JG_Q_W_SHARD_BYTES, each rounded up to 256 bytes.
  * Errors: JG_E_NULL, JG_E_DTYPE (ops, precision, or the second plan has a bias), JG_E_WAYS, JG_E_SHAPE (plans do
  * not chain), JG_E_WORKSPACE, JG_E_ALIGN, and those of jg_linear_forward_ex and jg_layernorm_forward. */
 int jg_token_mixing_forward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* gamma,

@@ -508,6 +508,22 @@ def token_mixing_block(ways: int, X, gamma, beta, W1, b1, W2, b2, eps: float = L
     return dict(H=H, Y=Y, Xn=Xn, S1=S1, SY=SY)
 
 
+def token_mixing_block_reduced(ways: int, X, gamma, beta, W1, b1, W2, b2, terms: int = 1, eps: float = LN_EPS):
+    """token_mixing_block with its two products in mixed precision (linear_xtw_reduced, linear_reduced): the operands
+    of each product are rounded (or split), the layer norm, Xn, H, the skip connection and both biases stay FP32.
+    Returns H, Y, Xn (double) and the magnitudes S1, SY of the rounded operands' products."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    Xn = layernorm(X, gamma, beta, ln_groups(ways), eps)
+    Xn32 = Xn.astype(np.float32)
+    S1 = linear_xtw_reduced(Xn32, W1, b1, terms, absolute=True)
+    H = gelu(linear_xtw_reduced(Xn32, W1, b1, terms))
+    H32 = H.astype(np.float32)
+    b2 = np.asarray(b2, dtype=np.float64)
+    Y = X.astype(np.float64) + linear_reduced(W2, H32, None, terms) + b2[:, None]
+    SY = np.abs(X.astype(np.float64)) + linear_reduced(W2, H32, None, terms, absolute=True) + np.abs(b2)[:, None]
+    return dict(H=H, Y=Y, Xn=Xn, S1=S1, SY=SY)
+
+
 def token_mixing_block_backward(ways: int, X, gamma, beta, W1, b1, W2, dY, eps: float = LN_EPS):
     """Gradients of token_mixing_block for an incoming gradient dY [T x C], in double, by the chain rule through the
     steps in the layouts the layers use, with what the method stores between the steps handed on in FP32:

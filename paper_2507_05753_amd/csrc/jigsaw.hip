@@ -1420,7 +1420,7 @@ static int check_token_chain(const jg_plan* first, const jg_plan* second)
     if (!first || !second) return JG_E_NULL;
     const jg_linear_desc &a = first->d, &b = second->d;
     if (a.op != JG_OP_XTW || b.op != JG_OP_XWT) return JG_E_DTYPE;
-    if (a.dtype != JG_F32 || b.dtype != JG_F32) return JG_E_DTYPE;
+    if (a.dtype != b.dtype) return JG_E_DTYPE;
     if (a.ways != b.ways) return JG_E_WAYS;
     // first: K = T, M = C, N = D; second: M = T, K = D, N = C
     if (a.K != b.M || a.M != b.N || a.N != b.K) return JG_E_SHAPE;
@@ -1436,32 +1436,81 @@ int jg_token_mixing_forward(const jg_plan* first, const jg_plan* second, const f
 {
     if (int rc = check_token_chain(first, second)) return rc;
     const int ways = first->d.ways;
+    const bool reduced = first->d.dtype != JG_F32;
     if (int rc = check_ptr_array(h_sh, ways)) return rc;
     if (int rc = check_ptr_array(x_sh, ways)) return rc;
+    if (int rc = check_ptr_array(xn_sh, ways)) return rc;
     if (!aligned(b2, 4)) return JG_E_ALIGN;
+    // workspace: [the layers' own, shared] [X + b2, FP32] [mixed precision: Xn rounded, contraction-major] [H rounded]
     const size_t base = first->ws_bytes > second->ws_bytes ? first->ws_bytes : second->ws_bytes;
     const size_t shard = round_up(4 * (size_t)first->xr * (size_t)first->xc, kWsAlign);
-    const size_t need = base + (b2 ? shard * ways : 0);
+    const size_t off_x16 = base + (b2 ? shard * ways : 0);
+    const size_t h16_shard = reduced ? round_up(4 * (size_t)second->wr * (size_t)second->xcp, kWsAlign) : 0;
+    const size_t off_h16 = off_x16 + first->chain_bytes;
+    const size_t need = off_h16 + h16_shard * ways;
     if (need > 0) {
         if (!workspace || workspace_bytes < need) return JG_E_WORKSPACE;
         if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
     }
+    char* ws = static_cast<char*>(workspace);
     // the skip connection carries the second layer's per-token bias: the norm, which reads X anyway, also writes
     // X + b2[token] for it
     float* xb[4] = {nullptr, nullptr, nullptr, nullptr};
     const float* res[4];
     for (int r = 0; r < ways; ++r) {
-        if (b2) xb[r] = reinterpret_cast<float*>(static_cast<char*>(workspace) + base + r * shard);
+        if (b2) xb[r] = reinterpret_cast<float*>(ws + base + r * shard);
         res[r] = b2 ? xb[r] : x_sh[r];
     }
     int rc = layernorm_impl(first, x_sh, gamma, beta, eps, xn_sh, nullptr, nullptr, b2 ? xb : nullptr, b2);
     if (rc != JG_OK) return rc;
+    const float* const* first_in = xn_sh;
+    const float* const* second_w = h_sh;
+    const float* xn16[4];
+    const float* h16[4];
+    jg_ctx* c = first->ctx;
+    if (reduced) {
+        // the first layer reads Xn rounded and contraction-major: the transposing conversion of the shard step
+        jg::CvtGroup cv;
+        std::memset(&cv, 0, sizeof(cv));
+        cv.nblocks = ways;
+        cv.rows = (int)first->xr;
+        cv.cols = (int)first->xc;
+        cv.planes = first->d.dtype == JG_BF16X3 ? 2 : 1;
+        cv.plane = (int)first->plane;
+        for (int r = 0; r < ways; ++r) {
+            char* dst = ws + off_x16 + r * first->chain_shard_bytes;
+            cv.b[r] = {xn_sh[r], reinterpret_cast<uint16_t*>(dst), first->xc};
+            xn16[r] = reinterpret_cast<const float*>(dst);
+        }
+        ScopedTimer t(c, JG_KERNEL_SHARD);
+        if (!HIP_OK(jg::launch_cvt_transposed_group(cv, c->stream))) return JG_E_HIP;
+        first_in = xn16;
+    }
     // H = gelu(Xn^T W1 + b1): [C x D], partitioned like the first plan's Y - which is how the second plan
     // partitions its weights
-    rc = forward_impl(first, xn_sh, w1_sh, b1_sh, nullptr, JG_ACT_GELU, h_sh, workspace, workspace_bytes, nullptr);
+    rc = forward_impl(first, first_in, w1_sh, b1_sh, nullptr, JG_ACT_GELU, h_sh, workspace, workspace_bytes, nullptr);
     if (rc != JG_OK) return rc;
+    if (reduced) {
+        // the second layer reads H rounded, in its weight-shard format (rows of the contracted index already)
+        jg::CvtGroup cv;
+        std::memset(&cv, 0, sizeof(cv));
+        cv.nblocks = ways;
+        cv.rows = (int)second->wr;
+        cv.cols = (int)second->wc;
+        cv.planes = second->d.dtype == JG_BF16X3 ? 2 : 1;
+        cv.plane = (int)second->plane;
+        for (int r = 0; r < ways; ++r) {
+            if (!aligned(h_sh[r], 4)) return JG_E_ALIGN;
+            char* dst = ws + off_h16 + r * h16_shard;
+            cv.b[r] = {h_sh[r], reinterpret_cast<uint16_t*>(dst), second->wc};
+            h16[r] = reinterpret_cast<const float*>(dst);
+        }
+        ScopedTimer t(c, JG_KERNEL_SHARD);
+        if (!HIP_OK(jg::launch_cvt_group(cv, c->stream))) return JG_E_HIP;
+        second_w = h16;
+    }
     // Y = (X + b2) + W2 H^T: [T x C], partitioned like X
-    return forward_impl(second, w2_sh, h_sh, nullptr, res, JG_ACT_NONE, y_sh, workspace, workspace_bytes, nullptr);
+    return forward_impl(second, w2_sh, second_w, nullptr, res, JG_ACT_NONE, y_sh, workspace, workspace_bytes, nullptr);
 }
 
 int jg_token_mixing_backward(const jg_plan* first, const jg_plan* second, const float* const* x_sh, const float* gamma,
@@ -1473,6 +1522,7 @@ int jg_token_mixing_backward(const jg_plan* first, const jg_plan* second, const 
                              size_t workspace_bytes)
 {
     if (int rc = check_token_chain(first, second)) return rc;
+    if (first->d.dtype != JG_F32) return JG_E_DTYPE;
     const int ways = first->d.ways;
     for (float* const* arr : {a_sh, dh_sh, da_sh, dxn_sh, db1_sh})
         if (int rc = check_ptr_array(arr, ways)) return rc;

@@ -347,20 +347,36 @@ class JigsawTokenMixing:
     the activations do and H where the weights do; nothing is transposed in memory."""
 
     def __init__(self, T: int, C: int, D: int, ways: int, device: int = 0, ctx=None, tail: int = jg.JG_TAIL_SPLIT,
-                 eps: float = 1e-5):
-        self.first = JigsawLinear(C, T, D, ways, bias=True, device=device, ctx=ctx, op=jg.JG_OP_XTW, tail=tail)
-        self.second = JigsawLinear(T, D, C, ways, bias=False, device=device, ctx=self.first.ctx, tail=tail)
+                 eps: float = 1e-5, dtype: int = jg.JG_F32):
+        """``dtype = JG_BF16 / JG_BF16X3``: mixed precision - X, Xn, H and Y stay FP32, the two products read
+        bfloat16 roundings (W1 and W2 rounded when sharded, Xn and H by the chain, into the workspace)."""
+        self.first = JigsawLinear(C, T, D, ways, bias=True, device=device, ctx=ctx, op=jg.JG_OP_XTW, tail=tail,
+                                  dtype=dtype)
+        self.second = JigsawLinear(T, D, C, ways, bias=False, device=device, ctx=self.first.ctx, tail=tail, dtype=dtype)
         self.second.w = self.first.y        # H_r is the second layer's weight shard, read where it was produced
-        self.T, self.C, self.D, self.ways, self.eps = T, C, D, ways, eps
+        self.T, self.C, self.D, self.ways, self.eps, self.dtype = T, C, D, ways, eps, dtype
         self.ctx = self.first.ctx
-        self.xn = [torch.empty_like(t) for t in self.first.x]
+        q = self.first.query
+        if dtype == jg.JG_F32:
+            self.xin = self.first.x
+        else:                               # the activations enter in FP32; only the products' operands are rounded
+            self.xin = [torch.empty((q(jg.JG_Q_X_ROWS, r), q(jg.JG_Q_X_COLS, r)), dtype=torch.float32,
+                                    device=self.first.dev) for r in range(ways)]
+            self.first.x = None
+        self.xn = [torch.empty_like(t) for t in self.xin]
         self.gamma = self.beta = self.b2 = None
-        self.ws_bytes = max(self.first.ws_bytes, self.second.ws_bytes) + self.first.query(jg.JG_Q_X_F32_SHARDS_BYTES)
+        up = lambda n: (n + 255) // 256 * 256
+        self.ws_bytes = max(self.first.ws_bytes, self.second.ws_bytes) + q(jg.JG_Q_X_F32_SHARDS_BYTES)
+        if dtype != jg.JG_F32:
+            self.ws_bytes += ways * (up(q(jg.JG_Q_X_SHARD_BYTES)) + up(self.second.query(jg.JG_Q_W_SHARD_BYTES)))
         self.first.ws = self.second.ws = None
         self.ws = torch.empty((max(self.ws_bytes, 1),), dtype=torch.uint8, device=self.first.dev)
 
     def shard(self, X=None, gamma=None, beta=None, W1=None, b1=None, W2=None, b2=None):
-        self.first.shard(X, W1, b1)
+        if X is not None:
+            assert X.is_cuda and X.dtype == torch.float32 and X.shape == (self.T, self.C) and X.stride(1) == 1
+            jg.jg_shard(self.first.plan, jg.JG_T_X_F32, X.data_ptr(), X.stride(0), [t.data_ptr() for t in self.xin])
+        self.first.shard(None, W1, b1)
         if W2 is not None:      # W2 takes the place of the second layer's activations
             assert W2.is_cuda and W2.dtype == torch.float32 and W2.shape == (self.T, self.D) and W2.stride(1) == 1
             jg.jg_shard(self.second.plan, jg.JG_T_X, W2.data_ptr(), W2.stride(0), [t.data_ptr() for t in self.second.x])
@@ -372,12 +388,12 @@ class JigsawTokenMixing:
         f, s = self.first, self.second
         p = lambda ts: [t.data_ptr() for t in ts]
         opt = lambda v: v.data_ptr() if v is not None else None
-        jg.jg_token_mixing_forward(f.plan, s.plan, p(f.x), opt(self.gamma), opt(self.beta), self.eps, p(f.w), p(f.b),
+        jg.jg_token_mixing_forward(f.plan, s.plan, p(self.xin), opt(self.gamma), opt(self.beta), self.eps, p(f.w), p(f.b),
                                    p(s.x), opt(self.b2), p(self.xn), p(f.y), p(s.y), self.ws.data_ptr(), self.ws_bytes)
 
     def gather_xn(self):
         out = torch.empty((self.T, self.C), dtype=torch.float32, device=self.first.dev)
-        jg.jg_gather_as(self.first.plan, jg.JG_T_X, [t.data_ptr() for t in self.xn], out.data_ptr(), out.stride(0))
+        jg.jg_gather_as(self.first.plan, jg.JG_T_X_F32, [t.data_ptr() for t in self.xn], out.data_ptr(), out.stride(0))
         return out
 
     def backward(self, dY=None, dy_shards=None):
@@ -390,8 +406,8 @@ class JigsawTokenMixing:
         assert dY is None or (dY.is_cuda and dY.dtype == torch.float32 and dY.shape == (self.T, self.C))
         if getattr(self, "grads", None) is None:
             like = lambda ts: [torch.empty_like(t) for t in ts]
-            self.grads = dict(dy=like(s.y), a=like(f.y), dh=like(f.y), da=like(f.y), dxn=like(f.x), dx=like(f.x),
-                              dw1=like(f.w), db1=like(f.b), dw2=like(s.x))
+            self.grads = dict(dy=like(s.y), a=like(f.y), dh=like(f.y), da=like(f.y), dxn=like(self.xin),
+                              dx=like(self.xin), dw1=like(f.w), db1=like(f.b), dw2=like(s.x))
             vec = lambda n: torch.empty((n,), dtype=torch.float32, device=f.dev)
             self.db2, self.dgamma, self.dbeta = vec(self.T), vec(self.C), vec(self.C)
             need = max(f.query(jg.JG_Q_WORKSPACE_BYTES), f.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES),
@@ -403,7 +419,7 @@ class JigsawTokenMixing:
         dy = g["dy"] if dy_shards is None else dy_shards
         if dy_shards is None:
             jg.jg_shard(s.plan, jg.JG_T_Y, dY.data_ptr(), dY.stride(0), p(dy))
-        jg.jg_token_mixing_backward(f.plan, s.plan, p(f.x), self.gamma.data_ptr() if self.gamma is not None else None,
+        jg.jg_token_mixing_backward(f.plan, s.plan, p(self.xin), self.gamma.data_ptr() if self.gamma is not None else None,
                                     self.eps, p(self.xn), p(f.w), p(f.b), p(s.x), p(f.y), p(dy), p(g["a"]),
                                     p(g["dh"]), p(g["da"]), p(g["dxn"]), p(g["dx"]), p(g["dw1"]), p(g["db1"]),
                                     p(g["dw2"]), self.db2.data_ptr(), self.dgamma.data_ptr(), self.dbeta.data_ptr(),

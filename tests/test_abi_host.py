@@ -500,3 +500,25 @@ def test_reduced_precision_transposed_plans_account_for_their_shards():
         assert e.value.status == jg.JG_E_DTYPE
         for p in (f, h, s):
             jg.jg_plan_destroy(p)
+
+
+def test_token_mixing_chain_takes_two_plans_of_one_precision():
+    lib = jg.raw()
+    arr = (ctypes.c_void_p * 2)(256, 512)
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    fwd = lambda a, b: lib.jg_token_mixing_forward(a, b, pp, None, None, 1e-5, pp, pp, pp, None, pp, pp, pp, 256, 1 << 20)
+    bwd = lambda a, b: lib.jg_token_mixing_backward(a, b, pp, None, 1e-5, *([pp] * 14), None, None, None, 256, 1 << 20)
+    T, C, D = 64, 32, 48
+    plans = {}
+    for dt in (jg.JG_F32, jg.JG_BF16, jg.JG_BF16X3):
+        plans[dt] = (jg.jg_plan_create(None, C, T, D, 2, True, op=jg.JG_OP_XTW, dtype=dt),
+                     jg.jg_plan_create(None, T, D, C, 2, False, dtype=dt))
+    for dt, (f, s) in plans.items():
+        assert fwd(f, s) == jg.JG_E_NULL                                   # chains; the plans have no context
+        assert bwd(f, s) == (jg.JG_E_NULL if dt == jg.JG_F32 else jg.JG_E_DTYPE)      # the backward is FP32 only
+        for other, (f2, s2) in plans.items():
+            if other != dt:
+                assert fwd(f, s2) == jg.JG_E_DTYPE
+    for f, s in plans.values():
+        jg.jg_plan_destroy(f)
+        jg.jg_plan_destroy(s)

@@ -635,3 +635,42 @@ def test_transposed_layer_at_token_mixing_size(jg, capsys, dtype_name):
         e = (np.abs(Ys - want) / S).max()
         assert e <= TOL, (ways, e)
         note(capsys, f"{dtype_name} transposed layer ways={ways}: {Ys.size} entries max err/S {e:.2e}")
+
+
+# ---------------------------------------------------------------------------------------------
+# the token-mixing half of a mixing block in mixed precision
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+@pytest.mark.parametrize("T,C,D", [(100, 100, 112), (130, 72, 272), (264, 136, 80), (520, 300, 1040)])
+def test_mixed_precision_token_mixing_block(jg, ctx, ways, dtype_name, T, C, D):
+    """Layer by layer against the oracle applied to what the GPU fed the layer (Xn and H are FP32 outputs; the
+    products read their bfloat16 roundings), then loosely against the oracle's own chain."""
+    from paper_2507_05753_amd.layer import JigsawTokenMixing
+    dtype = getattr(jg, dtype_name)
+    t = terms_of(jg, dtype)
+    X = (inputs.matrix(450, T, C, "R") + np.float32(0.25)).astype(np.float32)
+    gamma = (inputs.matrix(451, 1, C, "R")[0] + np.float32(1.5)).astype(np.float32)
+    beta = inputs.matrix(452, 1, C, "R")[0]
+    W1, W2 = inputs.matrix(453, T, D, "R", inputs.W_SCALE_EXP), inputs.matrix(454, T, D, "R", inputs.W_SCALE_EXP)
+    b1, b2 = inputs.matrix(455, 1, D, "R")[0], inputs.matrix(456, 1, T, "R")[0]
+    with JigsawTokenMixing(T, C, D, ways, ctx=ctx, dtype=dtype) as L:
+        L.ws.fill_(0xFF)
+        L.shard(dev(X), dev(gamma), dev(beta), dev(W1), dev(b1), dev(W2), dev(b2))
+        L.forward()
+        Xn, H, Y = L.gather_xn().cpu().numpy(), L.gather_h().cpu().numpy(), L.gather().cpu().numpy()
+        L.forward()                                   # the inputs were not overwritten: the same again
+        assert np.array_equal(Y, L.gather().cpu().numpy())
+    want = oracle.layernorm(X, gamma, beta, oracle.ln_groups(ways))
+    assert np.all(np.abs(Xn.astype(np.float64) - want) <= 2.0 ** -24 * np.abs(want) * (1 + 1e-6) + 1e-10)
+    S1 = oracle.linear_xtw_reduced(Xn, W1, b1, t, absolute=True)
+    eh = np.abs(H.astype(np.float64) - oracle.gelu(oracle.linear_xtw_reduced(Xn, W1, b1, t)))
+    assert np.all(eh <= 1.7e-6 * S1), f"H: {(eh / S1).max():.2e}"
+    wantY = X.astype(np.float64) + oracle.linear_reduced(W2, H, None, t) + b2.astype(np.float64)[:, None]
+    SY = np.abs(X) + oracle.linear_reduced(W2, H, None, t, absolute=True) + np.abs(b2)[:, None]
+    ey = np.abs(Y.astype(np.float64) - wantY)
+    assert np.all(ey <= TOL * SY), f"Y: {(ey / SY).max():.2e}"
+    r = oracle.token_mixing_block_reduced(ways, X, gamma, beta, W1, b1, W2, b2, t)
+    assert np.all(np.abs(Y - r["Y"]) <= 1e-4 * r["SY"])
+    if t == 1:      # and it is the mixed-precision block, not the FP32 one
+        assert np.abs(Y - oracle.token_mixing_block(ways, X, gamma, beta, W1, b1, W2, b2)["Y"]).max() > 1e-5

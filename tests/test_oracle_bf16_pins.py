@@ -216,3 +216,27 @@ def test_transposed_layer_in_reduced_precision(terms):
     # lattice values are not changed by the mode
     XL, WL = inputs.matrix(64, T, C, "L"), inputs.matrix(65, T, D, "L")
     assert np.array_equal(oracle.linear_xtw_reduced(XL, WL, None, terms), oracle.linear_xtw(XL, WL))
+
+
+@pytest.mark.parametrize("terms", [1, 3])
+def test_mixed_token_mixing_block_is_the_pinned_pieces_in_sequence(terms):
+    T, C, D = 16, 6, 10
+    X = (inputs.matrix(71, T, C, "R") + np.float32(0.25)).astype(np.float32)
+    gamma = (inputs.matrix(72, 1, C, "R")[0] + np.float32(1.5)).astype(np.float32)
+    beta = inputs.matrix(73, 1, C, "R")[0]
+    W1, W2 = inputs.matrix(74, T, D, "R", inputs.W_SCALE_EXP), inputs.matrix(75, T, D, "R", inputs.W_SCALE_EXP)
+    b1, b2 = inputs.matrix(76, 1, D, "R")[0], inputs.matrix(77, 1, T, "R")[0]
+    r = oracle.token_mixing_block_reduced(1, X, gamma, beta, W1, b1, W2, b2, terms)
+    Xn32 = oracle.layernorm(X, gamma, beta, 1).astype(np.float32)
+    assert np.array_equal(r["Xn"].astype(np.float32), Xn32)                       # the norm is not rounded to bfloat16
+    H = oracle.gelu(oracle.linear_xtw_reduced(Xn32, W1, b1, terms))
+    assert np.array_equal(r["H"], H)
+    Y = X.astype(np.float64) + oracle.linear_reduced(W2, H.astype(np.float32), None, terms) + b2.astype(np.float64)[:, None]
+    assert np.array_equal(r["Y"], Y)
+    # against the full-precision block: the split mode is close, the one-term mode visibly rounded
+    full = oracle.token_mixing_block(1, X, gamma, beta, W1, b1, W2, b2)
+    d = np.abs(r["Y"] - full["Y"]).max()
+    assert (d < 1e-4) if terms == 3 else (1e-5 < d < 5e-2)
+    # the skip connection and the per-token bias are added in full precision: shifting b2 shifts Y by exactly that
+    r2 = oracle.token_mixing_block_reduced(1, X, gamma, beta, W1, b1, W2, b2 + np.float32(0.5), terms)
+    assert np.all(np.abs((r2["Y"] - r["Y"]) - 0.5) < 1e-12)
