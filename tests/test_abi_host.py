@@ -506,8 +506,9 @@ def test_token_mixing_chain_takes_two_plans_of_one_precision():
     lib = jg.raw()
     arr = (ctypes.c_void_p * 2)(256, 512)
     pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
-    fwd = lambda a, b: lib.jg_token_mixing_forward(a, b, pp, None, None, 1e-5, pp, pp, pp, None, pp, pp, pp, 256, 1 << 20)
-    bwd = lambda a, b: lib.jg_token_mixing_backward(a, b, pp, None, 1e-5, *([pp] * 14), None, None, None, 256, 1 << 20)
+    # (a workspace size that passes the size check: nothing is touched, the plans have no context)
+    fwd = lambda a, b: lib.jg_token_mixing_forward(a, b, pp, None, None, 1e-5, pp, pp, pp, None, pp, pp, pp, 256, 1 << 30)
+    bwd = lambda a, b: lib.jg_token_mixing_backward(a, b, pp, None, 1e-5, *([pp] * 14), None, None, None, 256, 1 << 30)
     T, C, D = 64, 32, 48
     plans = {}
     for dt in (jg.JG_F32, jg.JG_BF16, jg.JG_BF16X3):
