@@ -674,3 +674,32 @@ def test_mixed_precision_token_mixing_block(jg, ctx, ways, dtype_name, T, C, D):
     assert np.all(np.abs(Y - r["Y"]) <= 1e-4 * r["SY"])
     if t == 1:      # and it is the mixed-precision block, not the FP32 one
         assert np.abs(Y - oracle.token_mixing_block(ways, X, gamma, beta, W1, b1, W2, b2)["Y"]).max() > 1e-5
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+def test_mixed_precision_whole_mixing_block(jg, ctx, ways, dtype_name):
+    """Token half, then channel half on its FP32 output shards in place, both in mixed precision: the channel half
+    against the oracle applied to what the token half produced, the whole loosely against the oracle's chain."""
+    from paper_2507_05753_amd.layer import JigsawMixerBlock
+    dtype = getattr(jg, dtype_name)
+    t = terms_of(jg, dtype)
+    T, C, Dt, Dc = 264, 272, 144, 208
+    X = (inputs.matrix(470, T, C, "R") + np.float32(0.25)).astype(np.float32)
+    vec = lambda s, n, shift=0.0: (inputs.matrix(s, 1, n, "R")[0] + np.float32(shift)).astype(np.float32)
+    g1, be1, g2, be2 = vec(471, C, 1.5), vec(472, C), vec(473, C, 1.5), vec(474, C)
+    W1, W2 = inputs.matrix(475, T, Dt, "R", inputs.W_SCALE_EXP), inputs.matrix(476, T, Dt, "R", inputs.W_SCALE_EXP)
+    b1, b2 = vec(477, Dt), vec(478, T)
+    V1, V2 = inputs.matrix(479, Dc, C, "R", inputs.W_SCALE_EXP), inputs.matrix(480, C, Dc, "R", inputs.W_SCALE_EXP)
+    c1, c2 = vec(481, Dc), vec(482, C)
+    with JigsawMixerBlock(T, C, Dt, Dc, ways, ctx=ctx, dtype=dtype) as L:
+        L.shard(dev(X), token=dict(gamma=dev(g1), beta=dev(be1), W1=dev(W1), b1=dev(b1), W2=dev(W2), b2=dev(b2)),
+                channel=dict(gamma=dev(g2), beta=dev(be2), W1=dev(V1), b1=dev(c1), W2=dev(V2), b2=dev(c2)))
+        L.forward()
+        U = L.gather_token_output().cpu().numpy()
+        Un, G, Y = L.channel.gather_xn().cpu().numpy(), L.channel.gather_h().cpu().numpy(), L.gather().cpu().numpy()
+    r1 = oracle.token_mixing_block_reduced(ways, X, g1, be1, W1, b1, W2, b2, t)
+    assert np.all(np.abs(U - r1["Y"]) <= 1e-4 * r1["SY"])
+    want = oracle.layernorm(U, g2, be2, oracle.ln_groups(ways))
+    assert np.all(np.abs(Un.astype(np.float64) - want) <= 2.0 ** -24 * np.abs(want) * (1 + 1e-6) + 1e-10)
+    check_mixed_chain(U, Un, G, Y, V1, c1, V2, c2, t)
