@@ -357,6 +357,19 @@ def linear_reduced(X, W, b=None, terms: int = 1, nthreads: int | None = None, ab
     return f(Xh, Wh, b, nthreads) + f(Xh, Wl, None, nthreads) + f(Xl, Wh, None, nthreads)
 
 
+def backward_reduced(X, W, dY, terms: int = 1, nthreads: int | None = None, absolute: bool = False):
+    """(dX64, dW64) = (dY W, dY^T X) of the layer Y = X W^T in the reduced-precision modes of linear_reduced: every
+    operand of a product (dY, W, X) is rounded to bfloat16 (or split) element by element, the products are exact and
+    summed in double.  Each gradient is a product of the form A B^T, so it is linear_reduced on transposed operands."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    G = np.ascontiguousarray(dY, dtype=np.float32)
+    t = lambda a: np.ascontiguousarray(a.T)
+    dX = linear_reduced(G, t(W), None, terms, nthreads, absolute)          # [M x N] [K x N]^T
+    dW = linear_reduced(t(G), t(X), None, terms, nthreads, absolute)       # [N x M] [K x M]^T
+    return dX, dW
+
+
 def linear_xtw_reduced(X, W, b=None, terms: int = 1, nthreads: int | None = None, absolute: bool = False) -> np.ndarray:
     """The transposed layer Y = X^T W + b (X [T x C], W [T x D]) in the reduced-precision modes of linear_reduced:
     the rounding (or the split) acts element by element, so it is that function on the transposed operands."""

@@ -240,3 +240,34 @@ def test_mixed_token_mixing_block_is_the_pinned_pieces_in_sequence(terms):
     # the skip connection and the per-token bias are added in full precision: shifting b2 shifts Y by exactly that
     r2 = oracle.token_mixing_block_reduced(1, X, gamma, beta, W1, b1, W2, b2 + np.float32(0.5), terms)
     assert np.all(np.abs((r2["Y"] - r["Y"]) - 0.5) < 1e-12)
+
+
+@pytest.mark.parametrize("terms", [1, 3])
+def test_backward_in_reduced_precision(terms):
+    M, K, N = 12, 10, 6
+    X = inputs.matrix(81, M, K, "R") * np.float32(3.0)
+    W = inputs.matrix(82, N, K, "R", inputs.W_SCALE_EXP)
+    G = inputs.matrix(83, M, N, "R")
+    dX, dW = oracle.backward_reduced(X, W, G, terms)
+    assert dX.shape == (M, K) and dW.shape == (N, K)
+    if terms == 1:      # exact products of the rounded operands: the full-precision backward of the rounded matrices
+        wX, wW = oracle.backward(oracle.round_bf16(X), oracle.round_bf16(W), oracle.round_bf16(G))
+        assert np.array_equal(dX, wX) and np.array_equal(dW, wW)
+        fX, _ = oracle.backward(X, W, G)
+        assert np.abs(dX - fX).max() > 1e-5
+    else:               # hi hi + hi lo + lo hi of the split operands
+        (gh, gl), (wh, wl), (xh, xl) = oracle.split_bf16(G), oracle.split_bf16(W), oracle.split_bf16(X)
+        z = np.zeros_like
+        wX = oracle.backward(z(X), wh, gh)[0] + oracle.backward(z(X), wl, gh)[0] + oracle.backward(z(X), wh, gl)[0]
+        wW = oracle.backward(xh, z(W), gh)[1] + oracle.backward(xl, z(W), gh)[1] + oracle.backward(xh, z(W), gl)[1]
+        SX, SW = oracle.backward_reduced(X, W, G, terms, absolute=True)
+        assert np.all(np.abs(dX - wX) <= 1e-14 * SX) and np.all(np.abs(dW - wW) <= 1e-14 * SW)
+        fX, fW = oracle.backward(X, W, G)
+        mX, mW = oracle.backward_magnitude(X, W, G)
+        assert np.all(np.abs(dX - fX) <= 2.0 ** -15 * mX) and np.all(np.abs(dW - fW) <= 2.0 ** -15 * mW)
+    # lattice values are not changed by the mode, and the adjoint identity holds exactly on them
+    XL, WL, GL = inputs.matrix(84, M, K, "L"), inputs.matrix(85, N, K, "L"), inputs.matrix(86, M, N, "L")
+    lX, lW = oracle.backward_reduced(XL, WL, GL, terms)
+    eX, eW = oracle.backward(XL, WL, GL)
+    assert np.array_equal(lX, eX) and np.array_equal(lW, eW)
+    assert np.sum(GL.astype(np.float64) * oracle.linear(XL, WL)) == np.sum(lX * XL) == np.sum(lW * WL)
