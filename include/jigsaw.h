@@ -89,8 +89,10 @@ enum { JG_WEIGHTS_COPY = 0, JG_WEIGHTS_DIRECT = 1 };     /* 4-way weight-block h
 enum { JG_TAIL_SPLIT = 0, JG_TAIL_WHOLE = 1 };           /* last partial round of a GEMM launch */
 enum { JG_ACT_NONE = 0, JG_ACT_GELU = 1 };               /* epilogue activation of jg_linear_forward_ex */
 enum { JG_T_X = 0, JG_T_W = 1, JG_T_B = 2, JG_T_Y = 3,   /* tensor selector of jg_shard / jg_gather_as */
-       JG_T_X_F32 = 4 };  /* partitioned like X, stored in FP32 whatever the plan's dtype: the activations a
+       JG_T_X_F32 = 4,    /* partitioned like X, stored in FP32 whatever the plan's dtype: the activations a
                              mixed-precision MLP chain takes, its skip connection, a layer norm's output */
+       JG_T_W_F32 = 5 };  /* partitioned like W, stored in FP32 whatever the plan's dtype: the master copy of the
+                             weights that a reduced-precision backward reads, and its dW */
 
 typedef struct jg_linear_desc {
     int64_t M, K, N;     /* global sizes: Y is M x N and K is contracted.  JG_OP_XWT: X is
@@ -383,8 +385,13 @@ int jg_token_mixing_forward(const jg_plan* first, const jg_plan* second, const f
  * X_(i,a), W_(i,j), dY_(a,j) the plan's blocks (row half, column half; 2-way: one row range, and dY_r stacks
  * dY_(0,r) over dY_(1,r)):   dX_(i,a) = sum_j W_(i,j) dY_(a,j)^T,   dW_(i,j) = sum_a X_(i,a) dY_(a,j),
  * two launches each for ways >= 2 (the first term into a partial in the workspace, the second on top of it).
- * FP32 plans only: a reduced-precision plan returns JG_E_DTYPE.
- * Errors: JG_E_NULL, JG_E_DTYPE, JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
+ * A reduced-precision JG_OP_XWT plan (Sec. 6.1: mixed precision): x_sh and w_sh are FP32 shards (JG_T_X_F32,
+ * JG_T_W_F32: the copies a mixed-precision training step keeps), dy_sh, dx_sh and dw_sh FP32 as always; every operand
+ * of every block product is rounded to bfloat16 (JG_BF16X3: split) into the workspace, in the layout the bfloat16
+ * kernel reads, and the products run on the bfloat16 matrix cores with FP32 sums:  dX = rnd(dY) rnd(W),
+ * dW = rnd(dY)^T rnd(X), block by block as above.  The rank's share of N must be a multiple of 8 (JG_E_SHAPE).
+ * A reduced-precision JG_OP_XTW plan returns JG_E_DTYPE.
+ * Errors: JG_E_NULL, JG_E_DTYPE, JG_E_SHAPE, JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
 int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
                        const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh,
                        void* workspace, size_t workspace_bytes);

@@ -35,7 +35,7 @@ JG_COMBINE_FUSED, JG_COMBINE_SEPARATE = 0, 1
 JG_WEIGHTS_COPY, JG_WEIGHTS_DIRECT = 0, 1
 JG_TAIL_SPLIT, JG_TAIL_WHOLE = 0, 1
 JG_ACT_NONE, JG_ACT_GELU = 0, 1
-JG_T_X, JG_T_W, JG_T_B, JG_T_Y, JG_T_X_F32 = 0, 1, 2, 3, 4
+JG_T_X, JG_T_W, JG_T_B, JG_T_Y, JG_T_X_F32, JG_T_W_F32 = 0, 1, 2, 3, 4, 5
 (JG_Q_WORKSPACE_BYTES, JG_Q_FLOPS_TOTAL, JG_Q_FLOPS_RANK, JG_Q_HBM_BYTES_ALGO,
  JG_Q_EXCHANGE_BYTES_RANK, JG_Q_X_ROWS, JG_Q_X_COLS, JG_Q_W_ROWS, JG_Q_W_COLS,
  JG_Q_Y_ROWS, JG_Q_Y_COLS, JG_Q_B_LEN, JG_Q_RESIDENT_BYTES_RANK, JG_Q_GEMM_LAUNCHES,

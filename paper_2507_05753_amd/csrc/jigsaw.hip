@@ -73,6 +73,7 @@ struct jg_plan {
     size_t ws_bytes;
     // backward workspace: ways partials of dX blocks, then (4-way) ways partials of dW blocks
     size_t bw_dx_bytes, bw_dw_bytes, bw_off_dw, bw_ws_bytes;
+    size_t bw_off_cvt;   // reduced-precision backward: where the rounded operands start in the backward workspace
     // scratch tiles of the split tail (largest need over the pass's launches), at the end of each workspace
     int slots;
     size_t tail_bytes, off_tail, bw_tail_bytes, bw_off_tail;
@@ -229,6 +230,36 @@ int jg_profile_read(jg_ctx* ctx, int kernel, double* total_ms, int64_t* launches
     return JG_OK;
 }
 
+// Reduced-precision backward of the plain layer: the rounded operands in the backward workspace, from bw_off_cvt on.
+// dY_r twice (rows of the contracted N share for dX, contraction-major over the tokens for dW), every weight block
+// and X_r contraction-major.  Sizes in bytes per shard / block, each rounded up to 256.
+struct BwReduced {
+    int planes, plane_n, plane_m, ld_n, ld_m, wblocks;
+    size_t dy16, dy16t, w16t, x16t, off_dy16, off_dy16t, off_w16t, off_x16t, total;
+};
+
+static BwReduced bw_reduced_layout(const jg_plan* p)
+{
+    BwReduced L;
+    const int ways = p->d.ways;
+    L.planes = p->d.dtype == JG_BF16X3 ? 2 : 1;
+    L.plane_n = (int)((p->yc + 63) / 64 * 64);      // contraction over the rank's share of N (dX)
+    L.plane_m = (int)((p->xr + 63) / 64 * 64);      // contraction over the rank's tokens (dW)
+    L.ld_n = L.planes == 2 ? L.plane_n : L.plane_n / 2;     // row strides in 4-byte units
+    L.ld_m = L.planes == 2 ? L.plane_m : L.plane_m / 2;
+    L.wblocks = ways == 2 ? 2 : 1;                  // weight blocks in a rank's shard
+    L.dy16 = round_up(4 * (size_t)p->yr * L.ld_n, kWsAlign);
+    L.dy16t = round_up(4 * (size_t)p->yc * L.ld_m, kWsAlign);
+    L.w16t = round_up(4 * (size_t)p->xc * L.ld_n, kWsAlign);
+    L.x16t = round_up(4 * (size_t)p->xc * L.ld_m, kWsAlign);
+    L.off_dy16 = p->bw_off_cvt;
+    L.off_dy16t = L.off_dy16 + L.dy16 * ways;
+    L.off_w16t = L.off_dy16t + L.dy16t * ways;
+    L.off_x16t = L.off_w16t + L.w16t * ways * L.wblocks;
+    L.total = L.off_x16t + L.x16t * ways - p->bw_off_cvt;
+    return L;
+}
+
 int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
 {
     if (!out) return JG_E_NULL;
@@ -314,7 +345,7 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     }
     p->ws_bytes = off;
     p->bw_dx_bytes = p->bw_dw_bytes = p->bw_off_dw = p->bw_ws_bytes = 0;
-    if (d.ways >= 2 && !reduced) {
+    if (d.ways >= 2 && !(reduced && xtw)) {
         // one partial per rank for dX and (wherever dW sums two terms: 4-way, and the 2-way transposed layer) for dW
         p->bw_dx_bytes = round_up((size_t)p->xr * (size_t)p->xc * sizeof(float), kWsAlign);
         p->bw_off_dw = p->bw_dx_bytes * d.ways;
@@ -330,6 +361,7 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     if (d.tail == JG_TAIL_SPLIT && reduced) {
         // one 256 x 256 scratch tile per CU, when the launches of the pass can end in a partial round worth splitting
         p->tail_bytes = jg::bf16_tail_scratch_bytes(p->slots / 2);
+        if (!xtw) p->bw_tail_bytes = p->tail_bytes;
     } else if (d.tail == JG_TAIL_SPLIT) {
         auto need = [&](int nprob, int64_t m, int64_t n, int64_t k) {
             const int64_t tiles = nprob * ((m + jg::BM - 1) / jg::BM) * ((n + jg::BN - 1) / jg::BN);
@@ -349,6 +381,8 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     }
     p->off_tail = p->ws_bytes;
     p->ws_bytes += p->tail_bytes;
+    p->bw_off_cvt = p->bw_ws_bytes;
+    if (reduced && !xtw) p->bw_ws_bytes += bw_reduced_layout(p).total;
     p->bw_off_tail = p->bw_ws_bytes;
     p->bw_ws_bytes += p->bw_tail_bytes;
     p->ws_bytes = round_up(p->ws_bytes, kWsAlign);
@@ -372,7 +406,7 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     const bool xtw = d.op == JG_OP_XTW;
     const bool reduced = d.dtype != JG_F32;
     const int64_t eb = d.dtype == JG_BF16 ? 2 : 4;     // bytes per element of an X or W shard (split mode: hi + lo)
-    if (reduced && (what == JG_Q_BACKWARD_WORKSPACE_BYTES || what == JG_Q_BACKWARD_FLOPS_TOTAL ||
+    if (reduced && xtw && (what == JG_Q_BACKWARD_WORKSPACE_BYTES || what == JG_Q_BACKWARD_FLOPS_TOTAL ||
                 what == JG_Q_BACKWARD_GEMM_LAUNCHES || what == JG_Q_BACKWARD_TAIL_SCRATCH_BYTES))
         return JG_E_DTYPE;   // no backward for this op
     switch (what) {
@@ -437,7 +471,8 @@ static int partition_of(const jg_plan* plan, int which, Partition* out)
     switch (which) {
     case JG_T_X:
     case JG_T_X_F32: *out = {plan->xr, plan->xc, plan->d.op == JG_OP_XTW ? plan->d.M : plan->d.K}; return JG_OK;
-    case JG_T_W: *out = {plan->wr, plan->wc, plan->d.op == JG_OP_XTW ? plan->d.N : plan->d.K}; return JG_OK;
+    case JG_T_W:
+    case JG_T_W_F32: *out = {plan->wr, plan->wc, plan->d.op == JG_OP_XTW ? plan->d.N : plan->d.K}; return JG_OK;
     case JG_T_Y: *out = {plan->yr, plan->yc, plan->d.N}; return JG_OK;
     default: return JG_E_DTYPE;
     }
@@ -457,7 +492,8 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
     const jg_linear_desc& d = plan->d;
     if (int rc = check_ptr_array(shards, d.ways)) return rc;
     if (!aligned(global, 4)) return JG_E_ALIGN;
-    if (which != JG_T_X && which != JG_T_W && which != JG_T_B && which != JG_T_Y && which != JG_T_X_F32)
+    if (which != JG_T_X && which != JG_T_W && which != JG_T_B && which != JG_T_Y && which != JG_T_X_F32 &&
+        which != JG_T_W_F32)
         return JG_E_DTYPE;
     jg_ctx* c = plan->ctx;
     if (!c) return JG_E_NULL;
@@ -602,8 +638,9 @@ int jg_gather(const jg_plan* plan, const float* const* y_sh, float* global_y, in
 // One GEMM launch of a pass (timed as `kernel_class`), followed by the join kernel when the
 // launcher split the tail; `scratch` is the pass's tail region of the caller's workspace.
 // copy16 (reduced precision only, may be null): a bfloat16 copy of the launch's output for the next layer.
+// plane (reduced precision; 0 = the plan's forward shards'): elements per plane of the operands' rows
 static bool run_gemm(const jg_plan* plan, jg::GemmGroup& g, int layout, int kernel_class, char* scratch,
-                     size_t scratch_bytes, const jg::HbCopy16* copy16 = nullptr)
+                     size_t scratch_bytes, const jg::HbCopy16* copy16 = nullptr, int plane = 0)
 {
     jg_ctx* c = plan->ctx;
     bool join = false;
@@ -611,7 +648,8 @@ static bool run_gemm(const jg_plan* plan, jg::GemmGroup& g, int layout, int kern
         jg::HbGroup hb;
         {
             ScopedTimer t(c, kernel_class);
-            if (!HIP_OK(jg::launch_gemm_bf16_group(g, plan->d.dtype == JG_BF16X3 ? 3 : 1, (int)plan->plane, plan->slots / 2,
+            if (!HIP_OK(jg::launch_gemm_bf16_group(g, plan->d.dtype == JG_BF16X3 ? 3 : 1,
+                                                   plane ? plane : (int)plan->plane, plan->slots / 2,
                                                    reinterpret_cast<float*>(scratch), scratch_bytes, c->stream, hb, &join,
                                                    copy16)))
                 return false;
@@ -933,13 +971,122 @@ static int backward_xtw(const jg_plan* plan, const float* const* x_sh, const flo
     return JG_OK;
 }
 
+// Backward of the plain layer in reduced precision; arguments already checked.  x_sh, w_sh: FP32 shards.  Every
+// operand of every block product is rounded into the workspace in the layout the bfloat16 kernel reads (both operands
+// along the contracted index): dY_r as it is for dX (contraction over its columns) and contraction-major for dW,
+// the weight blocks and X_r contraction-major.  The block products and their sums are those of the FP32 backward.
+static int backward_reduced(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                            const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh, char* ws)
+{
+    const jg_linear_desc& d = plan->d;
+    const int ways = d.ways;
+    jg_ctx* c = plan->ctx;
+    const int mr = (int)plan->xr, kh = (int)plan->xc, nh = (int)plan->yc;
+    if (nh & 7) return JG_E_SHAPE;      // dY_r is rounded in 16-byte chunks of 8 along its rows
+    const BwReduced L = bw_reduced_layout(plan);
+    const int64_t wblock = (int64_t)nh * kh;
+    auto dy16 = [&](int r) { return reinterpret_cast<const float*>(ws + L.off_dy16 + r * L.dy16); };
+    auto dy16t = [&](int r) { return reinterpret_cast<const float*>(ws + L.off_dy16t + r * L.dy16t); };
+    auto w16t = [&](int r, int b) { return reinterpret_cast<const float*>(ws + L.off_w16t + (r * L.wblocks + b) * L.w16t); };
+    auto x16t = [&](int r) { return reinterpret_cast<const float*>(ws + L.off_x16t + r * L.x16t); };
+    auto u16 = [](const float* p) { return reinterpret_cast<uint16_t*>(const_cast<float*>(p)); };
+    {
+        ScopedTimer t(c, JG_KERNEL_SHARD);
+        jg::CvtGroup cv;
+        std::memset(&cv, 0, sizeof(cv));
+        cv.nblocks = ways;
+        cv.planes = L.planes;
+        // dY_r: rows as they are
+        cv.rows = mr; cv.cols = nh; cv.plane = L.plane_n;
+        for (int r = 0; r < ways; ++r) cv.b[r] = {dy_sh[r], u16(dy16(r)), nh};
+        if (!HIP_OK(jg::launch_cvt_group(cv, c->stream))) return JG_E_HIP;
+        // dY_r and X_r: contraction-major over the tokens
+        cv.plane = L.plane_m;
+        for (int r = 0; r < ways; ++r) cv.b[r] = {dy_sh[r], u16(dy16t(r)), nh};
+        if (!HIP_OK(jg::launch_cvt_transposed_group(cv, c->stream))) return JG_E_HIP;
+        cv.cols = kh;
+        for (int r = 0; r < ways; ++r) cv.b[r] = {x_sh[r], u16(x16t(r)), kh};
+        if (!HIP_OK(jg::launch_cvt_transposed_group(cv, c->stream))) return JG_E_HIP;
+        // the weight blocks (nh x kh each): contraction-major over the rank's share of N
+        cv.rows = nh; cv.cols = kh; cv.plane = L.plane_n;
+        for (int b = 0; b < L.wblocks; ++b) {
+            for (int r = 0; r < ways; ++r) cv.b[r] = {w_sh[r] + b * wblock, u16(w16t(r, b)), kh};
+            if (!HIP_OK(jg::launch_cvt_transposed_group(cv, c->stream))) return JG_E_HIP;
+        }
+    }
+    char* tail = plan->bw_tail_bytes ? ws + plan->bw_off_tail : nullptr;
+    jg::GemmGroup g;
+    std::memset(&g, 0, sizeof(g));
+    auto launch = [&](int kernel_class, int plane) -> bool {
+        return run_gemm(plan, g, jg::kGemmNT, kernel_class, tail, plan->bw_tail_bytes, nullptr, plane);
+    };
+    auto dx_shape = [&]() { g.M = mr; g.N = kh; g.K = nh; };
+    auto dw_shape = [&]() { g.M = nh; g.N = kh; g.K = (mr + 7) / 8 * 8; };      // (zeros past the last token)
+    auto dx_part = [&](int r) { return reinterpret_cast<float*>(ws + r * plan->bw_dx_bytes); };
+    auto dw_part = [&](int r) { return reinterpret_cast<float*>(ws + plan->bw_off_dw + r * plan->bw_dw_bytes); };
+    if (ways == 1) {
+        g.nprob = 1;
+        dx_shape();
+        g.p[0] = {dy16(0), w16t(0, 0), dx_sh[0], nullptr, nullptr, L.ld_n, L.ld_n, kh, 0};
+        if (!launch(JG_KERNEL_GEMM_DX, L.plane_n)) return JG_E_HIP;
+        dw_shape();
+        g.p[0] = {dy16t(0), x16t(0), dw_sh[0], nullptr, nullptr, L.ld_m, L.ld_m, kh, 0};
+        return launch(JG_KERNEL_GEMM_DW, L.plane_m) ? JG_OK : JG_E_HIP;
+    }
+    if (ways == 2) {
+        // dX_r = dY_r W_{r,r} + dY_{1-r} W_{r,1-r};  dW_{r,c} = dY_c^T X_r
+        g.nprob = 2;
+        dx_shape();
+        for (int r = 0; r < 2; ++r)
+            g.p[r] = {dy16(1 - r), w16t(r, 1 - r), dx_part(r), nullptr, nullptr, L.ld_n, L.ld_n, kh, 0};
+        if (!launch(JG_KERNEL_GEMM_DX, L.plane_n)) return JG_E_HIP;
+        for (int r = 0; r < 2; ++r)
+            g.p[r] = {dy16(r), w16t(r, r), dx_sh[r], dx_part(r), nullptr, L.ld_n, L.ld_n, kh, kh};
+        if (!launch(JG_KERNEL_GEMM_DX, L.plane_n)) return JG_E_HIP;
+        g.nprob = 4;
+        dw_shape();
+        for (int r = 0; r < 2; ++r)
+            for (int cc = 0; cc < 2; ++cc)
+                g.p[2 * r + cc] = {dy16t(cc), x16t(r), dw_sh[r] + cc * wblock, nullptr, nullptr, L.ld_m, L.ld_m, kh, 0};
+        return launch(JG_KERNEL_GEMM_DW, L.plane_m) ? JG_OK : JG_E_HIP;
+    }
+    // 4-way: dX_(i,j) = sum_c dY_(i,c) W_(c,j);  dW_(c,j) = sum_i dY_(i,c)^T X_(i,j);  rank 2 row + column
+    auto rk = [](int a, int b) { return 2 * a + b; };
+    g.nprob = 4;
+    for (int pass = 0; pass < 2; ++pass) {
+        dx_shape();
+        for (int i = 0; i < 2; ++i)
+            for (int j = 0; j < 2; ++j) {
+                const int r = rk(i, j), cc = pass == 0 ? 1 - j : j;
+                if (pass == 0)
+                    g.p[r] = {dy16(rk(i, cc)), w16t(rk(cc, j), 0), dx_part(r), nullptr, nullptr, L.ld_n, L.ld_n, kh, 0};
+                else
+                    g.p[r] = {dy16(rk(i, cc)), w16t(rk(cc, j), 0), dx_sh[r], dx_part(r), nullptr, L.ld_n, L.ld_n, kh, kh};
+            }
+        if (!launch(JG_KERNEL_GEMM_DX, L.plane_n)) return JG_E_HIP;
+    }
+    for (int pass = 0; pass < 2; ++pass) {
+        dw_shape();
+        for (int cc = 0; cc < 2; ++cc)
+            for (int j = 0; j < 2; ++j) {
+                const int r = rk(cc, j), i = pass == 0 ? 1 - cc : cc;
+                if (pass == 0)
+                    g.p[r] = {dy16t(rk(i, cc)), x16t(rk(i, j)), dw_part(r), nullptr, nullptr, L.ld_m, L.ld_m, kh, 0};
+                else
+                    g.p[r] = {dy16t(rk(i, cc)), x16t(rk(i, j)), dw_sh[r], dw_part(r), nullptr, L.ld_m, L.ld_m, kh, kh};
+            }
+        if (!launch(JG_KERNEL_GEMM_DW, L.plane_m)) return JG_E_HIP;
+    }
+    return JG_OK;
+}
+
 int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
                        const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh,
                        void* workspace, size_t workspace_bytes)
 {
     if (!plan || !plan->ctx) return JG_E_NULL;
     const jg_linear_desc& d = plan->d;
-    if (d.dtype != JG_F32) return JG_E_DTYPE;
+    if (d.dtype != JG_F32 && d.op != JG_OP_XWT) return JG_E_DTYPE;
     const int ways = d.ways;
     if (int rc = check_ptr_array(x_sh, ways)) return rc;
     if (int rc = check_ptr_array(w_sh, ways)) return rc;
@@ -954,6 +1101,11 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
     if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
     char* ws = static_cast<char*>(workspace);
     if (d.op == JG_OP_XTW) return backward_xtw(plan, x_sh, w_sh, dy_sh, dx_sh, dw_sh, ws);
+    if (d.dtype != JG_F32) {
+        for (int r = 0; r < ways; ++r)
+            if (!aligned(x_sh[r], 4) || !aligned(w_sh[r], 4) || !aligned(dy_sh[r], 4)) return JG_E_ALIGN;
+        return backward_reduced(plan, x_sh, w_sh, dy_sh, dx_sh, dw_sh, ws);
+    }
 
     // shard shapes: X_r is mr x kh, W_r is (wr) x kh, dY_r is mr x nh
     const int mr = (int)plan->xr, kh = (int)plan->xc, nh = (int)plan->yc;

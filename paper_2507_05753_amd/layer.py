@@ -118,13 +118,21 @@ class JigsawLinear:
 
     # -- backward ---------------------------------------------------------------
     def alloc_backward(self):
-        """Shard tensors for dY (like Y), dX (like X), dW (like W) and the backward workspace."""
+        """Shard tensors for dY (like Y), dX (like X), dW (like W) and the backward workspace.  A reduced-precision
+        plan's backward reads FP32 copies of X and W (``x32`` / ``w32``, filled by ``shard``) and writes FP32 dX, dW."""
         if getattr(self, "dy", None) is None:
+            q = self.query
             self.dy = [torch.empty_like(t) for t in self.y]
-            self.dx = [torch.empty_like(t) for t in self.x]
-            self.dw = [torch.empty_like(t) for t in self.w]
-            # (a reduced-precision plan has no dX / dW pass; its dY shards still serve the bias gradient)
-            has_backward = self.dtype == jg.JG_F32
+            if self.dtype == jg.JG_F32:
+                self.x32, self.w32 = self.x, self.w
+            else:
+                f32 = dict(dtype=torch.float32, device=self.dev)
+                self.x32 = [torch.empty((q(jg.JG_Q_X_ROWS, r), q(jg.JG_Q_X_COLS, r)), **f32) for r in range(self.ways)]
+                self.w32 = [torch.empty((q(jg.JG_Q_W_ROWS, r), q(jg.JG_Q_W_COLS, r)), **f32) for r in range(self.ways)]
+            self.dx = [torch.empty_like(t) for t in self.x32]
+            self.dw = [torch.empty_like(t) for t in self.w32]
+            # (a reduced-precision transposed plan has no dX / dW pass; its dY shards still serve the bias gradient)
+            has_backward = self.dtype == jg.JG_F32 or self.op == jg.JG_OP_XWT
             self.bw_ws_bytes = self.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES) if has_backward else 0
             self.bw_ws = torch.empty((max(self.bw_ws_bytes, 1),), dtype=torch.uint8, device=self.dev)
 
@@ -133,9 +141,17 @@ class JigsawLinear:
         self.alloc_backward()
         jg.jg_shard(self.plan, jg.JG_T_Y, dY.data_ptr(), dY.stride(0), [t.data_ptr() for t in self.dy])
 
+    def shard_master(self, X=None, W=None):
+        """FP32 copies of X and W for the backward of a reduced-precision plan (JG_T_X_F32 / JG_T_W_F32 shards)."""
+        self.alloc_backward()
+        if X is not None:
+            jg.jg_shard(self.plan, jg.JG_T_X_F32, X.data_ptr(), X.stride(0), [t.data_ptr() for t in self.x32])
+        if W is not None:
+            jg.jg_shard(self.plan, jg.JG_T_W_F32, W.data_ptr(), W.stride(0), [t.data_ptr() for t in self.w32])
+
     def backward(self):
         self.alloc_backward()
-        jg.jg_linear_backward(self.plan, [t.data_ptr() for t in self.x], [t.data_ptr() for t in self.w],
+        jg.jg_linear_backward(self.plan, [t.data_ptr() for t in self.x32], [t.data_ptr() for t in self.w32],
                               [t.data_ptr() for t in self.dy], [t.data_ptr() for t in self.dx],
                               [t.data_ptr() for t in self.dw],
                               self.bw_ws.data_ptr() if self.bw_ws_bytes else None, self.bw_ws_bytes)
@@ -151,12 +167,12 @@ class JigsawLinear:
 
     def gather_dx(self):
         out = torch.empty(self.x_shape, dtype=torch.float32, device=self.dev)
-        jg.jg_gather_as(self.plan, jg.JG_T_X, [t.data_ptr() for t in self.dx], out.data_ptr(), out.stride(0))
+        jg.jg_gather_as(self.plan, jg.JG_T_X_F32, [t.data_ptr() for t in self.dx], out.data_ptr(), out.stride(0))
         return out
 
     def gather_dw(self):
         out = torch.empty(self.w_shape, dtype=torch.float32, device=self.dev)
-        jg.jg_gather_as(self.plan, jg.JG_T_W, [t.data_ptr() for t in self.dw], out.data_ptr(), out.stride(0))
+        jg.jg_gather_as(self.plan, jg.JG_T_W_F32, [t.data_ptr() for t in self.dw], out.data_ptr(), out.stride(0))
         return out
 
     def query(self, what: int, rank: int = 0) -> int:

@@ -325,9 +325,18 @@ def test_reduced_precision_plans_account_for_their_shards():
         assert q(w, jg.JG_Q_TAIL_SCRATCH_BYTES) == 0
         assert q(w, jg.JG_Q_WORKSPACE_BYTES) == q(h, jg.JG_Q_WORKSPACE_BYTES) - q(h, jg.JG_Q_TAIL_SCRATCH_BYTES)
         jg.jg_plan_destroy(w)
-        with pytest.raises(jg.JigsawError) as e:
-            q(h, jg.JG_Q_BACKWARD_WORKSPACE_BYTES)
-        assert e.value.status == jg.JG_E_DTYPE
+        # backward: the FP32 partials of the FP32 plan, plus every operand rounded into the workspace - dY_r twice
+        # (rows as they are; contraction-major over the tokens), the weight blocks and X_r contraction-major
+        up = lambda n: (n + 255) // 256 * 256
+        mr, kh, nh = q(f, jg.JG_Q_X_ROWS), q(f, jg.JG_Q_X_COLS), q(f, jg.JG_Q_Y_COLS)
+        pn, pm = (nh + 63) // 64 * 64, (mr + 63) // 64 * 64
+        wblocks = 2 if ways == 2 else 1
+        for p, eb in ((h, 2), (s, 4)):
+            partials = q(f, jg.JG_Q_BACKWARD_WORKSPACE_BYTES) - q(f, jg.JG_Q_BACKWARD_TAIL_SCRATCH_BYTES)
+            cvt = ways * (up(eb * mr * pn) + up(eb * nh * pm) + wblocks * up(eb * kh * pn) + up(eb * kh * pm))
+            assert q(p, jg.JG_Q_BACKWARD_WORKSPACE_BYTES) - q(p, jg.JG_Q_BACKWARD_TAIL_SCRATCH_BYTES) == partials + cvt
+            assert q(p, jg.JG_Q_BACKWARD_TAIL_SCRATCH_BYTES) == q(p, jg.JG_Q_TAIL_SCRATCH_BYTES)
+            assert q(p, jg.JG_Q_BACKWARD_FLOPS_TOTAL) == 4 * M * K * N
         if ways == 4:   # the received weight block is bfloat16 too
             assert (q(h, jg.JG_Q_WORKSPACE_BYTES) - q(h, jg.JG_Q_TAIL_SCRATCH_BYTES)
                     < q(f, jg.JG_Q_WORKSPACE_BYTES) - q(f, jg.JG_Q_TAIL_SCRATCH_BYTES))
@@ -357,7 +366,8 @@ def test_chain_refuses_plans_of_different_precision():
     # the FP32 selector is a valid tensor name for data calls (which then miss the context)
     a = jg.jg_plan_create(None, 64, 32, 48, 2, True, dtype=jg.JG_BF16)
     assert lib.jg_shard(a, jg.JG_T_X_F32, 256, 32, pp) == jg.JG_E_NULL
-    assert lib.jg_shard(a, 5, 256, 32, pp) == jg.JG_E_DTYPE
+    assert lib.jg_shard(a, jg.JG_T_W_F32, 256, 32, pp) == jg.JG_E_NULL
+    assert lib.jg_shard(a, 6, 256, 32, pp) == jg.JG_E_DTYPE
     jg.jg_plan_destroy(a)
 
 

@@ -703,3 +703,82 @@ def test_mixed_precision_whole_mixing_block(jg, ctx, ways, dtype_name):
     want = oracle.layernorm(U, g2, be2, oracle.ln_groups(ways))
     assert np.all(np.abs(Un.astype(np.float64) - want) <= 2.0 ** -24 * np.abs(want) * (1 + 1e-6) + 1e-10)
     check_mixed_chain(U, Un, G, Y, V1, c1, V2, c2, t)
+
+
+# ---------------------------------------------------------------------------------------------
+# backward of the plain layer in reduced precision
+# ---------------------------------------------------------------------------------------------
+# (M, K, N) below: a rank's share of N and (the plan's own rule) of K in whole 8-element chunks; M free (ragged tiles,
+# token counts that the conversion pads with zeros)
+
+
+def run_backward_reduced(jg, ctx, X, W, dY, ways, dtype):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    M, K = X.shape
+    N = W.shape[0]
+    with JigsawLinear(M, K, N, ways, ctx=ctx, dtype=dtype) as L:
+        L.shard_master(dev(X), dev(W))
+        L.shard_dy(dev(dY))
+        L.bw_ws.fill_(0xFF)
+        L.backward()
+        dX, dW = L.gather_dx().cpu().numpy(), L.gather_dw().cpu().numpy()
+        L.backward()
+        assert np.array_equal(dX, L.gather_dx().cpu().numpy()) and np.array_equal(dW, L.gather_dw().cpu().numpy())
+    return dX, dW
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+@pytest.mark.parametrize("M,K,N", [(2, 16, 16), (100, 80, 112), (130, 144, 272), (258, 272, 144), (525, 304, 1040),
+                                   (64, 1040, 48)])
+def test_backward_in_reduced_precision(jg, ctx, ways, dtype_name, M, K, N):
+    dtype = getattr(jg, dtype_name)
+    t = terms_of(jg, dtype)
+    if ways == 4 and M % 2:
+        M += 1
+    X, W, _ = inputs.layer_inputs(490, M, K, N, "R")
+    X = (X * np.float32(3.0)).astype(np.float32)
+    dY = inputs.matrix(491, M, N, "R")
+    dX, dW = run_backward_reduced(jg, ctx, X, W, dY, ways, dtype)
+    wX, wW = oracle.backward_reduced(X, W, dY, t)
+    SX, SW = oracle.backward_reduced(X, W, dY, t, absolute=True)
+    ex, ew = np.abs(dX - wX), np.abs(dW - wW)
+    assert np.all(ex <= TOL * SX), f"dX: {(ex / np.maximum(SX, 1e-300)).max():.3e}"
+    assert np.all(ew <= TOL * SW), f"dW: {(ew / np.maximum(SW, 1e-300)).max():.3e}"
+    fX, fW = oracle.backward(X, W, dY)
+    mX, mW = oracle.backward_magnitude(X, W, dY)
+    if dtype == jg.JG_BF16X3:       # close to the full-precision backward
+        assert np.all(np.abs(dX - fX) <= 2.0 ** -15 * mX) and np.all(np.abs(dW - fW) <= 2.0 ** -15 * mW)
+    elif N >= 100:                  # visibly the rounded one
+        assert (np.abs(dX - fX) / mX).max() > 1e-5
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+def test_backward_in_reduced_precision_is_bit_exact_on_lattice_inputs(jg, ctx, ways, dtype_name):
+    M, K, N = 132, 208, 80
+    X, W, _ = inputs.layer_inputs(492, M, K, N, "L")
+    dY = inputs.matrix(493, M, N, "L")
+    dX, dW = run_backward_reduced(jg, ctx, X, W, dY, ways, getattr(jg, dtype_name))
+    wX, wW = oracle.backward(X, W, dY)
+    assert np.array_equal(dX.astype(np.float64), wX) and np.array_equal(dW.astype(np.float64), wW)
+
+
+def test_backward_in_reduced_precision_checks_its_arguments(jg, ctx):
+    from paper_2507_05753_amd.layer import JigsawLinear
+    with JigsawLinear(64, 32, 20, 2, ctx=ctx, dtype=jg.JG_BF16) as L:      # N / 2 = 10: not whole chunks
+        L.alloc_backward()
+        p = lambda ts: [t.data_ptr() for t in ts]
+        with pytest.raises(jg.JigsawError) as e:
+            jg.jg_linear_backward(L.plan, p(L.x32), p(L.w32), p(L.dy), p(L.dx), p(L.dw), L.bw_ws.data_ptr(), L.bw_ws_bytes)
+        assert e.value.status == jg.JG_E_SHAPE
+    with JigsawLinear(64, 32, 32, 2, ctx=ctx, dtype=jg.JG_BF16) as L:
+        L.alloc_backward()
+        with pytest.raises(jg.JigsawError) as e:
+            jg.jg_linear_backward(L.plan, p(L.x32), p(L.w32), p(L.dy), p(L.dx), p(L.dw), L.bw_ws.data_ptr(), L.bw_ws_bytes - 1)
+        assert e.value.status == jg.JG_E_WORKSPACE
+    with JigsawLinear(32, 64, 32, 2, ctx=ctx, dtype=jg.JG_BF16, op=jg.JG_OP_XTW) as L:
+        ptrs = [t.data_ptr() for t in L.y]
+        with pytest.raises(jg.JigsawError) as e:
+            jg.jg_linear_backward(L.plan, ptrs, ptrs, ptrs, ptrs, ptrs, None, 0)
+        assert e.value.status == jg.JG_E_DTYPE
