@@ -206,14 +206,19 @@ def measure_backward(cfg, ways, args, X, W):
     from paper_2507_05753_amd.layer import JigsawLinear
     M, K, N = cfg["M"], cfg["K"], cfg["N"]
     dY = inputs.matrix_torch(cfg["seed"] + 3000, M, N, "R", 0, device=X.device)
-    with JigsawLinear(M, K, N, ways, tail=tail_of(args)) as L:
-        L.shard(X, W)
+    reduced = args.dtype != "f32"
+    terms = 3 if args.dtype == "bf16x3" else 1
+    with JigsawLinear(M, K, N, ways, tail=tail_of(args), dtype=dtype_of(args, jg)) as L:
+        if reduced:
+            L.shard_master(X, W)        # the backward of a reduced-precision plan reads FP32 X and W and rounds them
+        else:
+            L.shard(X, W)
         L.shard_dy(dY)
         del dY
         for _ in range(args.warmup):
             L.backward()
         torch.cuda.synchronize()
-        for k in (jg.JG_KERNEL_GEMM_DX, jg.JG_KERNEL_GEMM_DW):
+        for k in (jg.JG_KERNEL_GEMM_DX, jg.JG_KERNEL_GEMM_DW, jg.JG_KERNEL_SHARD, jg.JG_KERNEL_JOIN):
             jg.jg_profile_read(L.ctx, k)
         jg.jg_profile(L.ctx, True)
         torch.cuda.synchronize()
@@ -225,14 +230,26 @@ def measure_backward(cfg, ways, args, X, W):
         jg.jg_profile(L.ctx, False)
         dx_ms, dx_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_GEMM_DX)
         dw_ms, dw_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_GEMM_DW)
+        cvt_ms, cvt_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_SHARD)
+        join_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_JOIN)
         flops = L.query(jg.JG_Q_BACKWARD_FLOPS_TOTAL)
         half = flops / 2   # dX and dW cost the same
+        names = {"f32": ("jg::gemm_f32_stream<false, true, false>", "jg::gemm_f32_stream<true, true, false>"),
+                 "bf16": ("jg::gemm_bf16_nt", "jg::gemm_bf16_nt"), "bf16x3": ("jg::gemm_bf16x3_nt", "jg::gemm_bf16x3_nt")}[args.dtype]
+        # (tflops: the matrix cores' work - the split mode multiplies three times per product of the layer)
         kernels = {
-            "dx": dict(kernel="jg::gemm_f32_stream<false, true, false>", avg_launch_ms=dx_ms / max(dx_n, 1), launches=dx_n,
-                       tflops=half * args.steps / (dx_ms * 1e-3) / 1e12),
-            "dw": dict(kernel="jg::gemm_f32_stream<true, true, false>", avg_launch_ms=dw_ms / max(dw_n, 1), launches=dw_n,
-                       tflops=half * args.steps / (dw_ms * 1e-3) / 1e12),
+            "dx": dict(kernel=names[0] + (" (dX)" if reduced else ""), avg_launch_ms=dx_ms / max(dx_n, 1), launches=dx_n,
+                       tflops=terms * half * args.steps / (dx_ms * 1e-3) / 1e12),
+            "dw": dict(kernel=names[1] + (" (dW)" if reduced else ""), avg_launch_ms=dw_ms / max(dw_n, 1), launches=dw_n,
+                       tflops=terms * half * args.steps / (dw_ms * 1e-3) / 1e12),
         }
+        if reduced:
+            # the rounding passes: dY twice, X and W once each; 4 B read and 2 B (split mode 4 B) written per element
+            out_b = 4 if terms == 3 else 2
+            cvt_bytes = (4 + out_b) * (2 * M * N + M * K + N * K)
+            kernels["cvt"] = dict(kernel="jg::cvt_bf16 / jg::cvt_bf16_transposed", ms_per_step=cvt_ms / args.steps,
+                                  launches=cvt_n, gbps=cvt_bytes * args.steps / (cvt_ms * 1e-3) / 1e9 if cvt_ms > 0 else None)
+            kernels["join"] = dict(kernel="jg::gemm_bf16_join", ms_per_step=join_ms / args.steps)
         ws = L.bw_ws_bytes
         # the bias gradient (column sums of dY), timed on its own: it is not part of jg_linear_backward
         for _ in range(args.warmup):
@@ -696,7 +713,7 @@ def cpu_baseline_xtw(cfg, seconds, terms=0):
                        + ("fp64 loops" if not terms else f"bfloat16 rounding / split + fp64 loops, {terms} product(s)"))
 
 
-def cpu_baseline_backward(cfg, seconds):
+def cpu_baseline_backward(cfg, seconds, terms=0):
     """The backward oracle timed on a bounded row sample (dX rows and the matching share of dW)."""
     import oracle
     from paper_2507_05753_amd import inputs
@@ -708,7 +725,10 @@ def cpu_baseline_backward(cfg, seconds):
         X = inputs.matrix(seed, M, K, cfg["x_mode"], row_begin=0, row_end=rows)
         dY = inputs.matrix(seed + 3000, M, N, "R", row_begin=0, row_end=rows)
         t0 = time.perf_counter()
-        oracle.backward(X, W, dY, nthreads=cores)
+        if terms:
+            oracle.backward_reduced(X, W, dY, terms, nthreads=cores)
+        else:
+            oracle.backward(X, W, dY, nthreads=cores)
         return time.perf_counter() - t0
 
     probe = min(M, 4 * cores)
@@ -717,7 +737,7 @@ def cpu_baseline_backward(cfg, seconds):
     dt = run(rows)
     return dict(value=rows * K / dt, unit="items/s", cores=cores, kind="oracle",
                 sample=f"dX and dW from rows 0..{rows - 1} of X and dY ({rows} x {K}, {rows} x {N}) and all of W, "
-                       f"{dt:.1f} s, fp64 loops")
+                       f"{dt:.1f} s, " + ("fp64 loops" if not terms else f"bfloat16 rounding / split + fp64 loops, {terms} product(s)"))
 
 
 def cpu_baseline(cfg, seconds, reduced_terms=0):
@@ -775,8 +795,8 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     from paper_2507_05753_amd import inputs
-    if args.dtype != "f32" and args.op not in ("forward", "xtw", "mlp", "mixing", "token_mixing"):
-        print("bench.py: --dtype bf16 / bf16x3 goes with --op forward, xtw, mlp, mixing or token_mixing only",
+    if args.dtype != "f32" and args.op not in ("forward", "backward", "xtw", "mlp", "mixing", "token_mixing"):
+        print("bench.py: --dtype bf16 / bf16x3 goes with --op forward, backward, xtw, mlp, mixing or token_mixing only",
               file=sys.stderr)
         sys.exit(2)
 
@@ -974,25 +994,26 @@ def main():
         bw = measure_backward(cfg, args.ways, args, X, W)
         del X, W
         torch.cuda.empty_cache()
-        dom = max(bw["kernels"].values(), key=lambda k: k["avg_launch_ms"] * k["launches"])
+        dom = max((bw["kernels"][k] for k in ("dx", "dw")), key=lambda k: k["avg_launch_ms"] * k["launches"])
+        peak = FP32_MFMA_PEAK_TFLOPS if args.dtype == "f32" else BF16_MFMA_PEAK_TFLOPS
         line = {
             "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
             "value": bw["items_per_s"], "unit": "items/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": bw["ms_per_step"], "higher_is_better": True,
-            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
             "config": {"workload": f"config {args.config}: dX = dY W and dW = dY^T X, M={M} K={K} N={N}, "
-                                   f"{args.ways}-way Jigsaw backward, fp32",
+                                   f"{args.ways}-way Jigsaw backward, {precision_words(args)}",
                        "n_items": M * K, "ways": args.ways, "M": M, "K": K, "N": N, "seed": cfg["seed"],
-                       "x_values": cfg["x_mode"], "op": "backward"},
+                       "x_values": cfg["x_mode"], "op": "backward", "mode": args.dtype},
             "tflops": bw["tflops"],
             "roofline": {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["tflops"],
-                         "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": dom["tflops"] / FP32_MFMA_PEAK_TFLOPS, "avg_launch_ms": dom["avg_launch_ms"],
+                         "peak": peak, "unit": "TFLOP/s",
+                         "frac": dom["tflops"] / peak, "avg_launch_ms": dom["avg_launch_ms"],
                          "launches": dom["launches"], "traffic": None},
             "kernels": bw["kernels"],
         }
         if args.cpu_seconds > 0:
-            line["cpu_baseline"] = cpu_baseline_backward(cfg, args.cpu_seconds)
+            line["cpu_baseline"] = cpu_baseline_backward(cfg, args.cpu_seconds, reduced_terms(args))
         print(json.dumps(line), flush=True)
         return
 

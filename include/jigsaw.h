@@ -99,7 +99,8 @@ typedef struct jg_linear_desc {
                             M x K, W is N x K.  JG_OP_XTW: X is K x M, W is K x N.      */
     int32_t ways;        /* 1, 2 or 4                                                   */
     int32_t op;          /* JG_OP_XWT or JG_OP_XTW                                      */
-    int32_t dtype;       /* JG_F32, or JG_BF16 / JG_BF16X3: forward only.  The X and W shards
+    int32_t dtype;       /* JG_F32, or JG_BF16 / JG_BF16X3 (forward; backward of JG_OP_XWT, which
+                            reads FP32 shards: see jg_linear_backward).  The X and W shards
                             are then bfloat16 arrays of JG_Q_X_SHARD_BYTES /
                             JG_Q_W_SHARD_BYTES bytes, 16-byte aligned, written by jg_shard.
                             JG_OP_XWT: every rank's share of K (K, or K / 2 for 2 and 4

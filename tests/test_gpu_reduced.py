@@ -782,3 +782,48 @@ def test_backward_in_reduced_precision_checks_its_arguments(jg, ctx):
         with pytest.raises(jg.JigsawError) as e:
             jg.jg_linear_backward(L.plan, ptrs, ptrs, ptrs, ptrs, ptrs, None, 0)
         assert e.value.status == jg.JG_E_DTYPE
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+def test_backward_in_reduced_precision_at_config3(jg, capsys, dtype_name):
+    """Config 3 at full size, in the launch configuration bench.py --op backward --dtype ... times: whole rows of dX
+    for sampled tokens and whole rows of dW for sampled output channels against the oracle, everything finite."""
+    from paper_2507_05753_amd.layer import JigsawLinear
+    dtype = getattr(jg, dtype_name)
+    t = terms_of(jg, dtype)
+    cfg = inputs.CONFIGS[3]
+    M, K, N, seed = cfg["M"], cfg["K"], cfg["N"], cfg["seed"]
+    Xd = inputs.matrix_torch(seed, M, K, cfg["x_mode"], device="cuda")
+    Wd = inputs.matrix_torch(seed + inputs.W_STREAM, N, K, "R", inputs.W_SCALE_EXP, device="cuda")
+    dYd = inputs.matrix_torch(seed + 3000, M, N, "R", device="cuda")
+    k = inputs.keys(5200, np.arange(24, dtype=np.uint64))
+    rows = np.unique(np.concatenate([(k[:12] % np.uint64(M)).astype(np.int64), [0, M // 2 - 1, M // 2, M - 1]]))
+    outs = np.unique(np.concatenate([(k[12:] % np.uint64(N)).astype(np.int64), [0, N // 2 - 1, N // 2, N - 1]]))
+    ri, oi = torch.from_numpy(rows).cuda(), torch.from_numpy(outs).cuda()
+    W = Wd.cpu().numpy()
+    dY_r = dYd[ri].cpu().numpy()
+    # dX rows: rnd(dY[rows]) rnd(W);  dW rows: rnd(dY[:, outs])^T rnd(X) - both are A B^T products of the forward oracle
+    wantX = oracle.linear_reduced(dY_r, np.ascontiguousarray(W.T), None, t)
+    SX = oracle.linear_reduced(dY_r, np.ascontiguousarray(W.T), None, t, absolute=True)
+    dYt = np.ascontiguousarray(dYd[:, oi].cpu().numpy().T)
+    Xt = np.ascontiguousarray(Xd.cpu().numpy().T)
+    wantW = oracle.linear_reduced(dYt, Xt, None, t)
+    SW = oracle.linear_reduced(dYt, Xt, None, t, absolute=True)
+    del Xt
+    note(capsys, f"{dtype_name} backward: oracle rows ready ({rows.size} tokens of dX, {outs.size} rows of dW)")
+    for ways in (1, 4):
+        with JigsawLinear(M, K, N, ways, dtype=dtype) as L:
+            L.shard_master(Xd, Wd)
+            L.shard_dy(dYd)
+            L.bw_ws.fill_(0xFF)
+            L.backward()
+            dX, dW = L.gather_dx(), L.gather_dw()
+            torch.cuda.synchronize()
+            assert torch.isfinite(dX).all() and torch.isfinite(dW).all()
+            dXs, dWs = dX[ri].cpu().numpy().astype(np.float64), dW[oi].cpu().numpy().astype(np.float64)
+            del dX, dW
+        torch.cuda.empty_cache()
+        ex, ew = (np.abs(dXs - wantX) / SX).max(), (np.abs(dWs - wantW) / SW).max()
+        assert ex <= TOL and ew <= TOL, (ways, ex, ew)
+        note(capsys, f"{dtype_name} backward ways={ways}: dX max err/S {ex:.2e} ({dXs.size} entries), dW {ew:.2e} ({dWs.size})")
