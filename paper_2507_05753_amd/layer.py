@@ -15,7 +15,8 @@ class JigsawLinear:
 
     ``op = JG_OP_XWT``: Y = X W^T with X (M, K) and W (N, K).  ``op = JG_OP_XTW``: the transposed
     layer Y = X^T W with X (K, M) and W (K, N).  ``dtype = JG_BF16 / JG_BF16X3``: the X and W shards are
-    bfloat16 tensors (split mode: every row is [hi | lo]) written by ``shard`` from FP32 inputs; forward only.
+    bfloat16 tensors (split mode: every row is [hi | lo]) written by ``shard`` from FP32 inputs; the backward of such a
+    plan (plain layer only) reads FP32 copies (``shard_master``).
     """
 
     def __init__(self, M: int, K: int, N: int, ways: int, bias: bool = False,

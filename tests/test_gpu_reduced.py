@@ -277,8 +277,7 @@ def test_calls_that_need_fp32_shards_are_refused(jg, ctx):
     from paper_2507_05753_amd.layer import JigsawLinear
     with JigsawLinear(16, 32, 16, 2, ctx=ctx, dtype=jg.JG_BF16) as L:
         ptrs = [t.data_ptr() for t in L.y]
-        for call in (lambda: jg.jg_linear_backward(L.plan, ptrs, ptrs, ptrs, ptrs, ptrs, None, 0),
-                     lambda: jg.jg_gather_as(L.plan, jg.JG_T_X, ptrs, ptrs[0], 64),
+        for call in (lambda: jg.jg_gather_as(L.plan, jg.JG_T_X, ptrs, ptrs[0], 64),
                      lambda: jg.jg_gather_as(L.plan, jg.JG_T_W, ptrs, ptrs[0], 64),
                      lambda: jg.jg_shard_patches(L.plan, ptrs[0], 2, 8, 8, 4, ptrs)):
             with pytest.raises(jg.JigsawError) as e:
@@ -287,6 +286,9 @@ def test_calls_that_need_fp32_shards_are_refused(jg, ctx):
         with pytest.raises(jg.JigsawError) as e:          # bfloat16 shards move in 16-byte pieces
             jg.jg_shard(L.plan, jg.JG_T_X, L.y[0].data_ptr(), 32, [ptrs[0] + 4, ptrs[1]])
         assert e.value.status == jg.JG_E_ALIGN
+        with pytest.raises(jg.JigsawError) as e:          # the backward rounds its operands into a workspace
+            jg.jg_linear_backward(L.plan, ptrs, ptrs, ptrs, ptrs, ptrs, None, 0)
+        assert e.value.status == jg.JG_E_WORKSPACE
 
 
 # --------------------------------------------------------------------------------------------
