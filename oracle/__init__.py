@@ -489,6 +489,32 @@ def mixing_block_backward(ways: int, X, gamma, beta, W1, b1, W2, dY, eps: float 
     return r
 
 
+def mlp_backward_reduced(X, W1, b1, W2, dY, terms: int = 1, nthreads: int | None = None):
+    """mlp_backward with every product in mixed precision (linear_reduced, backward_reduced): the operands of each
+    product are rounded (or split) from the FP32 values the method keeps; A, H, dH, dA, the GELU derivative, the
+    bias gradients and the skip connection stay in full precision."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    A = linear_reduced(X, W1, b1, terms, nthreads)
+    H32 = gelu(A).astype(np.float32)
+    dH, dW2 = backward_reduced(H32, W2, dY, terms, nthreads)
+    dA = dH * gelu_grad(A)
+    dA32 = dA.astype(np.float32)
+    dXm, dW1 = backward_reduced(X, W1, dA32, terms, nthreads)
+    return dict(A=A, dH=dH, dA=dA, dX=dXm + np.asarray(dY, dtype=np.float64), dW1=dW1, db1=bias_backward(dA32),
+                dW2=dW2, db2=bias_backward(dY))
+
+
+def mixing_block_backward_reduced(ways: int, X, gamma, beta, W1, b1, W2, dY, terms: int = 1, eps: float = LN_EPS):
+    """mixing_block_backward with the MLP's products in mixed precision (mlp_backward_reduced); the norm in full."""
+    G = np.asarray(dY, dtype=np.float64)
+    Xn32 = layernorm(X, gamma, beta, ln_groups(ways), eps).astype(np.float32)
+    r = mlp_backward_reduced(Xn32, W1, b1, W2, dY, terms)
+    dXn = r["dX"] - G
+    dXl, dgamma, dbeta = layernorm_backward(X, gamma, dXn.astype(np.float32), ln_groups(ways), eps)
+    r.update(dXn=dXn, dX=G + dXl, dgamma=dgamma, dbeta=dbeta)
+    return r
+
+
 def mixing_block_reduced(ways: int, X, gamma, beta, W1, b1, W2, b2, terms: int = 1, eps: float = LN_EPS):
     """mixing_block with the MLP's two products in mixed precision (mlp_reduced); the layer norm, its FP32
     output Xn and the skip connection stay in full precision."""

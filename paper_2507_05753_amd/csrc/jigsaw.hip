@@ -1469,9 +1469,15 @@ int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* con
                      false);
 }
 
+// (reduced precision: the recomputed forward reads X and W1 rounded, behind the first plan's own forward workspace)
+static size_t mlp_backward_w16_bytes(const jg_plan* first)
+{
+    return first->d.dtype == JG_F32 ? 0 : round_up(4 * (size_t)first->wr * (size_t)first->xcp, kWsAlign);
+}
+
 static size_t mlp_backward_workspace(const jg_plan* first, const jg_plan* second)
 {
-    size_t need = first->ws_bytes;
+    size_t need = first->ws_bytes + first->chain_bytes + mlp_backward_w16_bytes(first) * first->d.ways;
     if (first->bw_ws_bytes > need) need = first->bw_ws_bytes;
     if (second->bw_ws_bytes > need) need = second->bw_ws_bytes;
     return need;
@@ -1486,8 +1492,8 @@ static int mlp_backward_impl(const jg_plan* first, const jg_plan* second, const 
                              size_t workspace_bytes, bool with_skip)
 {
     if (int rc = check_mlp_chain(first, second)) return rc;
-    if (first->d.dtype != JG_F32) return JG_E_DTYPE;
     const int ways = first->d.ways;
+    const bool reduced = first->d.dtype != JG_F32;
     for (float* const* arr : {a_sh, dh_sh, da_sh, db1_sh, db2_sh})
         if (int rc = check_ptr_array(arr, ways)) return rc;
     const size_t need = mlp_backward_workspace(first, second);
@@ -1501,8 +1507,39 @@ static int mlp_backward_impl(const jg_plan* first, const jg_plan* second, const 
     if (rc != JG_OK) return rc;
     rc = jg_bias_backward(second, dy_sh, db2_sh);
     if (rc != JG_OK) return rc;
-    // the pre-activation, which the forward does not keep: A = X W1^T + b1 once more
-    rc = forward_impl(first, x_sh, w1_sh, b1_sh, nullptr, JG_ACT_NONE, a_sh, workspace, workspace_bytes, nullptr);
+    // the pre-activation, which the forward does not keep: A = X W1^T + b1 once more (mixed precision: from the
+    // FP32 X and W1 this call is given, rounded as the forward rounds them)
+    const float* const* a_x = x_sh;
+    const float* const* a_w = w1_sh;
+    const float* x16[4];
+    const float* w16[4];
+    if (reduced) {
+        if (int rc1 = check_ptr_array(x_sh, ways)) return rc1;
+        if (int rc1 = check_ptr_array(w1_sh, ways)) return rc1;
+        char* ws = static_cast<char*>(workspace);
+        if (int rc1 = convert_shards(first, x_sh, ws + first->ws_bytes, x16)) return rc1;
+        const size_t wbytes = mlp_backward_w16_bytes(first);
+        jg::CvtGroup cv;
+        std::memset(&cv, 0, sizeof(cv));
+        cv.nblocks = ways;
+        cv.rows = (int)first->wr;
+        cv.cols = (int)first->wc;
+        cv.planes = first->d.dtype == JG_BF16X3 ? 2 : 1;
+        cv.plane = (int)first->plane;
+        for (int r = 0; r < ways; ++r) {
+            if (!aligned(w1_sh[r], 4)) return JG_E_ALIGN;
+            char* dst = ws + first->ws_bytes + first->chain_bytes + r * wbytes;
+            cv.b[r] = {w1_sh[r], reinterpret_cast<uint16_t*>(dst), first->wc};
+            w16[r] = reinterpret_cast<const float*>(dst);
+        }
+        {
+            ScopedTimer t(c, JG_KERNEL_SHARD);
+            if (!HIP_OK(jg::launch_cvt_group(cv, c->stream))) return JG_E_HIP;
+        }
+        a_x = x16;
+        a_w = w16;
+    }
+    rc = forward_impl(first, a_x, a_w, b1_sh, nullptr, JG_ACT_NONE, a_sh, workspace, workspace_bytes, nullptr);
     if (rc != JG_OK) return rc;
     // dA = dH * gelu'(A)
     {

@@ -231,6 +231,10 @@ class JigsawMLP:
             jg.jg_shard(self.first.plan, jg.JG_T_X_F32, X.data_ptr(), X.stride(0), [t.data_ptr() for t in self.xin])
         self.first.shard(None, W1, b1)
         self.second.shard(None, W2, b2)
+        if self.dtype != jg.JG_F32 and getattr(self, "keep_masters", False):
+            # mixed-precision training keeps the FP32 weights: the backward reads them
+            self.first.shard_master(None, W1)
+            self.second.shard_master(None, W2)
 
     def forward(self):
         f, s = self.first, self.second
@@ -245,24 +249,43 @@ class JigsawMLP:
     def gather(self):
         return self.second.gather()
 
-    # -- backward (FP32 plans) -----------------------------------------------------
+    # -- backward --------------------------------------------------------------------
+    def master_weights(self):
+        """(W1 shards, W2 shards) in FP32: the plans' own for FP32 plans, the kept masters in mixed precision
+        (set ``keep_masters = True`` before ``shard``)."""
+        f, s = self.first, self.second
+        if self.dtype == jg.JG_F32:
+            return f.w, s.w
+        assert getattr(f, "w32", None) is not None, "mixed-precision backward: set keep_masters before shard()"
+        return f.w32, s.w32
+
+    def backward_workspace_bytes(self):
+        f, s = self.first, self.second
+        up = lambda n: (n + 255) // 256 * 256
+        recompute = f.query(jg.JG_Q_CHAIN_WORKSPACE_BYTES)
+        if self.dtype != jg.JG_F32:
+            recompute += self.ways * up(f.query(jg.JG_Q_W_SHARD_BYTES))
+        return max(recompute, f.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES), s.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES),
+                   f.query(jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES))
+
     def backward(self, dY):
         """Gradients for an incoming gradient dY (M, C), after forward(): jg_mlp_backward.  The shards of A, dH, dA,
-        dX, dW1, db1, dW2, db2 are kept on the holder (``self.grads``)."""
+        dX, dW1, db1, dW2, db2 are kept on the holder (``self.grads``).  Mixed precision: the same call on the FP32
+        activations and master weights, every product's operands rounded as in the forward."""
         f, s = self.first, self.second
-        assert self.dtype == jg.JG_F32 and dY.is_cuda and dY.dtype == torch.float32 and dY.shape == (self.M, self.C)
+        assert dY.is_cuda and dY.dtype == torch.float32 and dY.shape == (self.M, self.C)
+        w1, w2 = self.master_weights()
         if getattr(self, "grads", None) is None:
             like = lambda ts: [torch.empty_like(t) for t in ts]
-            self.grads = dict(dy=like(s.y), a=like(f.y), dh=like(f.y), da=like(f.y), dx=like(self.xin), dw1=like(f.w),
-                              db1=like(f.b), dw2=like(s.w), db2=like(s.b))
-            need = max(f.query(jg.JG_Q_WORKSPACE_BYTES), f.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES),
-                       s.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES))
+            self.grads = dict(dy=like(s.y), a=like(f.y), dh=like(f.y), da=like(f.y), dx=like(self.xin), dw1=like(w1),
+                              db1=like(f.b), dw2=like(w2), db2=like(s.b))
+            need = self.backward_workspace_bytes()
             self.bw_ws = torch.empty((max(need, 1),), dtype=torch.uint8, device=f.dev)
             self.bw_ws_bytes = need
         g = self.grads
         p = lambda ts: [t.data_ptr() for t in ts]
         jg.jg_shard(s.plan, jg.JG_T_Y, dY.data_ptr(), dY.stride(0), p(g["dy"]))
-        jg.jg_mlp_backward(f.plan, s.plan, p(self.xin), p(f.w), p(f.b), p(s.w), p(f.y), p(g["dy"]), p(g["a"]), p(g["dh"]),
+        jg.jg_mlp_backward(f.plan, s.plan, p(self.xin), p(w1), p(f.b), p(w2), p(f.y), p(g["dy"]), p(g["a"]), p(g["dh"]),
                            p(g["da"]), p(g["dx"]), p(g["dw1"]), p(g["db1"]), p(g["dw2"]), p(g["db2"]),
                            self.bw_ws.data_ptr() if self.bw_ws_bytes else None, self.bw_ws_bytes)
 
@@ -281,7 +304,7 @@ class JigsawMLP:
         elif name in ("dw1", "dw2"):
             L = f if name == "dw1" else s
             out = torch.empty(L.w_shape, dtype=torch.float32, device=dev)
-            jg.jg_gather_as(L.plan, jg.JG_T_W, p(g[name]), out.data_ptr(), out.stride(0))
+            jg.jg_gather_as(L.plan, jg.JG_T_W_F32, p(g[name]), out.data_ptr(), out.stride(0))
         else:       # bias gradients: rank r holds the slice of column half r % 2 (replicated in the 4-way form)
             L = f if name == "db1" else s
             parts = g[name][:1] if self.ways == 1 else g[name][:2]
@@ -334,16 +357,16 @@ class JigsawMixing(JigsawMLP):
         the MLP's (JigsawMLP.backward) the holder keeps 'dxn' shards and the global vectors ``dgamma`` / ``dbeta``.
         ``dy_shards``: the gradient already on shards partitioned like X_r (another block's 'dx'), instead of dY."""
         f, s = self.first, self.second
-        assert self.dtype == jg.JG_F32 and (dY is None) != (dy_shards is None)
+        assert (dY is None) != (dy_shards is None)
         assert dY is None or (dY.is_cuda and dY.dtype == torch.float32 and dY.shape == (self.M, self.C))
+        w1, w2 = self.master_weights()
         if getattr(self, "grads", None) is None:
             like = lambda ts: [torch.empty_like(t) for t in ts]
             self.grads = dict(dy=like(s.y), a=like(f.y), dh=like(f.y), da=like(f.y), dxn=like(self.xin),
-                              dx=like(self.xin), dw1=like(f.w), db1=like(f.b), dw2=like(s.w), db2=like(s.b))
+                              dx=like(self.xin), dw1=like(w1), db1=like(f.b), dw2=like(w2), db2=like(s.b))
             self.dgamma = torch.empty((self.C,), dtype=torch.float32, device=f.dev)
             self.dbeta = torch.empty((self.C,), dtype=torch.float32, device=f.dev)
-            need = max(f.query(jg.JG_Q_WORKSPACE_BYTES), f.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES),
-                       s.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES), f.query(jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES))
+            need = self.backward_workspace_bytes()
             self.bw_ws = torch.empty((need,), dtype=torch.uint8, device=f.dev)
             self.bw_ws_bytes = need
         g = self.grads
@@ -352,7 +375,7 @@ class JigsawMixing(JigsawMLP):
         if dy_shards is None:
             jg.jg_shard(s.plan, jg.JG_T_Y, dY.data_ptr(), dY.stride(0), p(dy))
         jg.jg_mixing_backward(f.plan, s.plan, p(self.xin), self.gamma.data_ptr() if self.gamma is not None else None,
-                              self.eps, p(self.xn), p(f.w), p(f.b), p(s.w), p(f.y), p(dy), p(g["a"]), p(g["dh"]),
+                              self.eps, p(self.xn), p(w1), p(f.b), p(w2), p(f.y), p(dy), p(g["a"]), p(g["dh"]),
                               p(g["da"]), p(g["dxn"]), p(g["dx"]), p(g["dw1"]), p(g["db1"]), p(g["dw2"]), p(g["db2"]),
                               self.dgamma.data_ptr(), self.dbeta.data_ptr(), self.bw_ws.data_ptr(), self.bw_ws_bytes)
 

@@ -215,18 +215,23 @@ def test_channel_mixing_size(jg, capsys):
 # ---------------------------------------------------------------------------------------------
 # backward of the MLP: the chain rule through the layers' backward passes, checked step by step
 # ---------------------------------------------------------------------------------------------
-def check_mlp_backward(L, X, W1, b1, W2, dY, ways, xkey="dx"):
-    """xkey "dx": the MLP with its skip connection; "dxn": the MLP inside a block, dA W1 alone."""
+def check_mlp_backward(L, X, W1, b1, W2, dY, ways, xkey="dx", t=0):
+    """xkey "dx": the MLP with its skip connection; "dxn": the MLP inside a block, dA W1 alone.  t: 0 for FP32 plans,
+    1 / 3 for the mixed-precision modes (every product against the oracle's reduced routine)."""
+    lin = (lambda a, w, b: oracle.linear_reduced(a, w, b, t)) if t else oracle.linear
+    lin_mag = (lambda a, w, b: oracle.linear_reduced(a, w, b, t, absolute=True)) if t else oracle.magnitude
+    bwd = (lambda a, w, g_: oracle.backward_reduced(a, w, g_, t)) if t else oracle.backward
+    bwd_mag = (lambda a, w, g_: oracle.backward_reduced(a, w, g_, t, absolute=True)) if t else oracle.backward_magnitude
     g = {k: L.gather_grad(k).cpu().numpy() for k in ("a", "dh", "da", xkey, "dw1", "dw2", "db1", "db2")}
     H = L.gather_h().cpu().numpy()
     f64 = lambda a: a.astype(np.float64)
     rel = lambda err, S: (err / np.maximum(S, 1e-300)).max()
     # A recomputed: one forward layer
-    A64, SA = oracle.linear(X, W1, b1), oracle.magnitude(X, W1, b1)
+    A64, SA = lin(X, W1, b1), lin_mag(X, W1, b1)
     assert np.all(np.abs(f64(g["a"]) - A64) <= 1e-6 * SA), f"A: {rel(np.abs(f64(g['a']) - A64), SA):.2e}"
     # second layer's backward from the H the forward stored
-    dH64, dW264 = oracle.backward(H, W2, dY)
-    SH, SW2 = oracle.backward_magnitude(H, W2, dY)
+    dH64, dW264 = bwd(H, W2, dY)
+    SH, SW2 = bwd_mag(H, W2, dY)
     assert np.all(np.abs(f64(g["dh"]) - dH64) <= 1e-6 * SH), f"dH: {rel(np.abs(f64(g['dh']) - dH64), SH):.2e}"
     assert np.all(np.abs(f64(g["dw2"]) - dW264) <= 1e-6 * SW2), f"dW2: {rel(np.abs(f64(g['dw2']) - dW264), SW2):.2e}"
     db2 = oracle.bias_backward(dY)
@@ -235,8 +240,8 @@ def check_mlp_backward(L, X, W1, b1, W2, dY, ways, xkey="dx"):
     dA64 = f64(g["dh"]) * oracle.gelu_grad(f64(g["a"]))
     assert np.all(np.abs(f64(g["da"]) - dA64) <= 2.0 ** -23 * np.abs(dA64) + 1e-45), "dA"
     # first layer's backward from the dA the GPU stored, plus the skip connection
-    dX64, dW164 = oracle.backward(X, W1, g["da"])
-    SX, SW1 = oracle.backward_magnitude(X, W1, g["da"])
+    dX64, dW164 = bwd(X, W1, g["da"])
+    SX, SW1 = bwd_mag(X, W1, g["da"])
     skip = f64(dY) if xkey == "dx" else 0.0
     ex = np.abs(f64(g[xkey]) - (dX64 + skip))
     assert np.all(ex <= 1e-6 * (SX + np.abs(skip))), f"{xkey}: {rel(ex, SX + np.abs(skip)):.2e}"
@@ -380,3 +385,49 @@ def test_mixing_block_backward_size(jg, capsys):
         assert np.all(np.abs(f64(dbet) - db) <= HALF * np.abs(db) * (1 + 1e-6) + 1e-11 * Sb), (ways, "dbeta")
         note(capsys, f"mixing block backward ways={ways}: {rows.size} tokens, {cs.size} x {hs.size} weight entries; max err/S "
                      + ", ".join(f"{n} {e:.2e}" for n, e in worst.items()))
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+@pytest.mark.parametrize("M,C,Hd", [(100, 112, 112), (130, 80, 272), (258, 272, 144), (301, 528, 1040)])
+def test_mixing_block_backward_in_mixed_precision(jg, ctx, ways, dtype_name, M, C, Hd):
+    """jg_mixing_backward on reduced plans: every product against the oracle's reduced routine applied to what the GPU
+    stored for the step before; the norm's step in full precision; then loosely against the oracle's own chain."""
+    from paper_2507_05753_amd.layer import JigsawMixing
+    dtype = getattr(jg, dtype_name)
+    t = 3 if dtype == jg.JG_BF16X3 else 1
+    if ways == 4 and M % 2:
+        M += 1
+    X, W1, b1 = inputs.layer_inputs(390, M, C, Hd, "R", bias=True)
+    X = (X + np.float32(0.25)).astype(np.float32)
+    W2 = inputs.matrix(391, C, Hd, "R", inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(392, 1, C, "R")[0]
+    dY = inputs.matrix(393, M, C, "R")
+    gamma = (inputs.matrix(394, 1, C, "R")[0] + np.float32(1.5)).astype(np.float32)
+    beta = inputs.matrix(395, 1, C, "R")[0]
+    HALF_ULP = 2.0 ** -24
+    with JigsawMixing(M, C, Hd, ways, ctx=ctx, dtype=dtype) as L:
+        L.keep_masters = True
+        L.shard(dev(X), dev(gamma), dev(beta), dev(W1), dev(b1), dev(W2), dev(b2))
+        L.forward()
+        L.backward(dev(dY))
+        Xn = L.gather_xn().cpu().numpy()
+        g = check_mlp_backward(L, Xn, W1, b1, W2, dY, ways, xkey="dxn", t=t)
+        dXl, dg, db, SX, Sg, Sb = oracle.layernorm_backward(X, gamma, g["dxn"], oracle.ln_groups(ways), magnitude=True)
+        want = dY.astype(np.float64) + dXl
+        dx = L.gather_grad("dx").cpu().numpy()
+        assert np.all(np.abs(dx - want) <= HALF_ULP * np.abs(want) * (1 + 1e-6) + 1e-11 * (SX + np.abs(dY)) + 1e-45)
+        dgam = L.dgamma.cpu().numpy()
+        assert np.all(np.abs(dgam - dg) <= HALF_ULP * np.abs(dg) * (1 + 1e-6) + 1e-11 * Sg + 1e-45)
+        L.backward(dev(dY))
+        assert np.array_equal(dx, L.gather_grad("dx").cpu().numpy())
+    # (an FP32 value that differs in its last bit between the two chains can round to the other bfloat16 neighbour:
+    # in the one-term mode the chains agree to a few bfloat16 roundings of single terms, not to FP32 accuracy)
+    r = oracle.mixing_block_backward_reduced(ways, X, gamma, beta, W1, b1, W2, dY, t)
+    loose = 2e-3 if t == 1 else 1e-4
+    for got, name in ((dx, "dX"), (g["dw1"], "dW1"), (g["dw2"], "dW2"), (dgam, "dgamma")):
+        ref = r[name]
+        assert np.all(np.abs(got - ref) <= loose * (np.abs(ref) + np.abs(ref).max())), name
+    if t == 1:      # and it is the mixed-precision chain, not the FP32 one
+        full = oracle.mixing_block_backward(ways, X, gamma, beta, W1, b1, W2, dY)
+        assert (np.abs(g["dw2"] - full["dW2"]) / (np.abs(full["dW2"]) + np.abs(full["dW2"]).max())).max() > 1e-5

@@ -271,3 +271,35 @@ def test_backward_in_reduced_precision(terms):
     eX, eW = oracle.backward(XL, WL, GL)
     assert np.array_equal(lX, eX) and np.array_equal(lW, eW)
     assert np.sum(GL.astype(np.float64) * oracle.linear(XL, WL)) == np.sum(lX * XL) == np.sum(lW * WL)
+
+
+@pytest.mark.parametrize("terms", [1, 3])
+def test_mixed_mlp_backward_is_the_pinned_pieces_in_sequence(terms):
+    M, C, Hd = 10, 8, 12
+    X = inputs.matrix(91, M, C, "R")
+    W1, W2 = inputs.matrix(92, Hd, C, "R", inputs.W_SCALE_EXP), inputs.matrix(93, C, Hd, "R", inputs.W_SCALE_EXP)
+    b1 = inputs.matrix(94, 1, Hd, "R")[0]
+    dY = inputs.matrix(95, M, C, "R")
+    r = oracle.mlp_backward_reduced(X, W1, b1, W2, dY, terms)
+    A = oracle.linear_reduced(X, W1, b1, terms)
+    H32 = oracle.gelu(A).astype(np.float32)
+    dH, dW2 = oracle.backward_reduced(H32, W2, dY, terms)
+    dA32 = (dH * oracle.gelu_grad(A)).astype(np.float32)
+    dXm, dW1 = oracle.backward_reduced(X, W1, dA32, terms)
+    assert np.array_equal(r["A"], A) and np.array_equal(r["dH"], dH) and np.array_equal(r["dW2"], dW2)
+    assert np.array_equal(r["dX"], dXm + dY) and np.array_equal(r["dW1"], dW1)
+    assert np.array_equal(r["db1"], oracle.bias_backward(dA32)) and np.array_equal(r["db2"], oracle.bias_backward(dY))
+    # against the full-precision chain: the split mode is close, the one-term mode visibly rounded
+    full = oracle.mlp_backward(X, W1, b1, W2, dY)
+    for name in ("dX", "dW1", "dW2"):
+        ref = full[name] - (dY if name == "dX" else 0.0)        # (without the skip connection, which is not rounded)
+        d = (np.abs(r[name] - full[name]) / (np.abs(ref) + np.abs(ref).max())).max()
+        assert (d < 1e-4) if terms == 3 else (1e-5 < d < 5e-2), (name, d)
+    # and the block: the norm's part is the full-precision one applied to the mixed-precision dXn
+    gamma = (inputs.matrix(96, 1, C, "R")[0] + np.float32(1.5)).astype(np.float32)
+    beta = inputs.matrix(97, 1, C, "R")[0]
+    rb = oracle.mixing_block_backward_reduced(1, X, gamma, beta, W1, b1, W2, dY, terms)
+    Xn32 = oracle.layernorm(X, gamma, beta, 1).astype(np.float32)
+    m = oracle.mlp_backward_reduced(Xn32, W1, b1, W2, dY, terms)
+    dXl, dg, db = oracle.layernorm_backward(X, gamma, (m["dX"] - dY).astype(np.float32), 1)
+    assert np.array_equal(rb["dX"], dY + dXl) and np.array_equal(rb["dgamma"], dg) and np.array_equal(rb["dW1"], m["dW1"])
