@@ -509,9 +509,13 @@ def time_block_backward(L, dY, n_items, args, jg):
     torch.cuda.synchronize()
     sec = (time.perf_counter() - t0) / args.steps
     jg.jg_profile(L.ctx, False)
-    shard_ms, _ = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_SHARD)      # dY is sharded by the wrapper on every call
-    sec -= shard_ms * 1e-3 / args.steps
+    shard_ms, shard_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_SHARD)
     kernels = {}
+    if L.dtype == jg.JG_F32:       # dY is sharded by the wrapper on every call: not part of the step
+        sec -= shard_ms * 1e-3 / args.steps
+    else:                          # mixed precision: the rounding passes are part of the step, and the same class;
+        # the wrapper's copy of dY onto shards is in that class too and stays in: the step is overstated by it
+        kernels["rounding_and_dy_shard"] = dict(ms_per_step=shard_ms / args.steps, launches_per_step=shard_n / args.steps)
     for name, k in names.items():
         ms, n = jg.jg_profile_read(L.ctx, k)
         kernels[name] = dict(ms_per_step=ms / args.steps, launches_per_step=n / args.steps)
@@ -533,7 +537,8 @@ def measure_mixing_backward(cfg, ways, args):
     M, C, Hd, seed = cfg["M"], cfg["C"], cfg["Hd"], cfg["seed"]
     dev = torch.device("cuda", 0)
     gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device=dev)
-    with JigsawMixing(M, C, Hd, ways, tail=tail_of(args)) as L:
+    with JigsawMixing(M, C, Hd, ways, tail=tail_of(args), dtype=dtype_of(args, jg)) as L:
+        L.keep_masters = True
         L.shard(gen(seed, M, C), (gen(seed + 5, 1, C)[0] + 1.5).contiguous(), gen(seed + 6, 1, C)[0].contiguous(),
                 gen(seed + 1, Hd, C, inputs.W_SCALE_EXP), gen(seed + 2, 1, Hd)[0].contiguous(),
                 gen(seed + 3, C, Hd, inputs.W_SCALE_EXP), gen(seed + 4, 1, C)[0].contiguous())
@@ -593,7 +598,7 @@ def cpu_baseline_token_mixing_backward(cfg, seconds):
                        f"weight gradients are those channels' share), {dt:.1f} s, fp64")
 
 
-def cpu_baseline_mixing_backward(cfg, seconds):
+def cpu_baseline_mixing_backward(cfg, seconds, terms=0):
     """The oracle's backward of the mixing block timed on a bounded sample of tokens (rows of X and dY)."""
     import oracle
     from paper_2507_05753_amd import inputs
@@ -608,7 +613,10 @@ def cpu_baseline_mixing_backward(cfg, seconds):
         X = inputs.matrix(seed, M, C, "R", row_begin=0, row_end=rows)
         dY = inputs.matrix(seed + 7, M, C, "R", row_begin=0, row_end=rows)
         t0 = time.perf_counter()
-        oracle.mixing_block_backward(1, X, gamma, beta, W1, b1, W2, dY)
+        if terms:
+            oracle.mixing_block_backward_reduced(1, X, gamma, beta, W1, b1, W2, dY, terms)
+        else:
+            oracle.mixing_block_backward(1, X, gamma, beta, W1, b1, W2, dY)
         return time.perf_counter() - t0
 
     # a probe's time holds a fixed part (the weights converted to double): scaling it up underestimates the sample,
@@ -795,8 +803,10 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     from paper_2507_05753_amd import inputs
-    if args.dtype != "f32" and args.op not in ("forward", "backward", "xtw", "mlp", "mixing", "token_mixing"):
-        print("bench.py: --dtype bf16 / bf16x3 goes with --op forward, backward, xtw, mlp, mixing or token_mixing only",
+    if args.dtype != "f32" and args.op not in ("forward", "backward", "xtw", "mlp", "mixing", "mixing_backward",
+                                               "token_mixing"):
+        print("bench.py: --dtype bf16 / bf16x3 goes with --op forward, backward, xtw, mlp, mixing, mixing_backward or "
+              "token_mixing only",
               file=sys.stderr)
         sys.exit(2)
 
@@ -919,21 +929,26 @@ def main():
             "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
             "value": r["items_per_s"], "unit": "items/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
-            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
             "config": {"workload": f"backward of the channel-mixing half of a mixing block of the 1B model: gradients "
                                    f"of Y = X + gelu(layernorm(X) W1^T + b1) W2^T + b2 for X, gamma, beta, W1, b1, W2, "
-                                   f"b2; X {M} x {C}, hidden {Hd}, {args.ways}-way Jigsaw, fp32",
+                                   f"b2; X {M} x {C}, hidden {Hd}, {args.ways}-way Jigsaw, {precision_words(args)}",
                        "n_items": M * C, "ways": args.ways, "M": M, "C": C, "Hd": Hd, "seed": mc["seed"],
                        "x_values": "R", "op": "mixing_backward", "tail": args.tail},
             "tflops": r["tflops"],
-            "roofline": {"bound": "mfma", "kernel": "jg::gemm_f32_stream (dX, dW and recomputed A launches together)",
-                         "achieved": r["gemm_tflops"], "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": r["gemm_tflops"] / FP32_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None,
+            "roofline": {"bound": "mfma",
+                         "kernel": {"f32": "jg::gemm_f32_stream", "bf16": "jg::gemm_bf16_nt", "bf16x3": "jg::gemm_bf16x3_nt"}[args.dtype]
+                                   + " (dX, dW and recomputed A launches together)",
+                         "achieved": r["gemm_tflops"] * (3 if args.dtype == "bf16x3" else 1) if r["gemm_tflops"] else None,
+                         "peak": FP32_MFMA_PEAK_TFLOPS if args.dtype == "f32" else BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": (r["gemm_tflops"] * (3 if args.dtype == "bf16x3" else 1) /
+                                  (FP32_MFMA_PEAK_TFLOPS if args.dtype == "f32" else BF16_MFMA_PEAK_TFLOPS))
+                                 if r["gemm_tflops"] else None,
                          "ms_per_step": r["gemm_ms_per_step"], "traffic": None},
             "kernels": r["kernels"],
         }
         if args.cpu_seconds > 0:
-            line["cpu_baseline"] = cpu_baseline_mixing_backward(mc, args.cpu_seconds)
+            line["cpu_baseline"] = cpu_baseline_mixing_backward(mc, args.cpu_seconds, reduced_terms(args))
         print(json.dumps(line), flush=True)
         return
 

@@ -402,7 +402,12 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
  * backward passes (Sec. 4.1):
  *     dH = dY W2,   dW2 = dY^T H,   db2 = sum_i dY;      A = X W1^T + b1 (recomputed: the forward keeps H, not A);
  *     dA = dH * gelu'(A),  gelu'(x) = Phi(x) + x phi(x);  dX = dY + dA W1,   dW1 = dA^T X,   db1 = sum_i dA.
- * FP32 plans as for jg_mlp_forward.  x_sh, w1_sh, b1_sh, w2_sh: as in the forward; h_sh: the H it stored; dy_sh:
+ * FP32 plans as for jg_mlp_forward; or two reduced-precision plans (mixed precision, Sec. 6.1): then x_sh, w1_sh and
+ * w2_sh are FP32 shards (JG_T_X_F32, JG_T_W_F32: the activations the forward was given and the master weights), every
+ * product's operands are rounded as in the forward (jg_linear_backward on such plans; A from X and W1 rounded once
+ * more), everything else stays FP32, and the workspace must also hold, behind the first plan's
+ * JG_Q_CHAIN_WORKSPACE_BYTES, `ways` times its JG_Q_W_SHARD_BYTES (each rounded up to 256).
+ * x_sh, w1_sh, b1_sh, w2_sh: as in the forward; h_sh: the H it stored; dy_sh:
  * the dY shards.  Outputs (`ways` device buffers each): a_sh, dh_sh, da_sh shaped like H_r (A, dH and dA are kept:
  * they are what the steps hand on); dx_sh like X_r; dw1_sh, dw2_sh like the plans' W_r; db1_sh, db2_sh like their
  * bias shards.  No output may overlap an input or another output.  workspace: 256-byte aligned, at least the
