@@ -391,7 +391,8 @@ int jg_token_mixing_forward(const jg_plan* first, const jg_plan* second, const f
  * of every block product is rounded to bfloat16 (JG_BF16X3: split) into the workspace, in the layout the bfloat16
  * kernel reads, and the products run on the bfloat16 matrix cores with FP32 sums:  dX = rnd(dY) rnd(W),
  * dW = rnd(dY)^T rnd(X), block by block as above.  The rank's share of N must be a multiple of 8 (JG_E_SHAPE).
- * A reduced-precision JG_OP_XTW plan returns JG_E_DTYPE.
+ * A reduced-precision JG_OP_XTW plan: the same with dX = rnd(W) rnd(dY)^T and dW = rnd(X) rnd(dY); the rank's
+ * shares of M (channels) and of N must be multiples of 8 (JG_E_SHAPE), the token count is free.
  * Errors: JG_E_NULL, JG_E_DTYPE, JG_E_SHAPE, JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
 int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
                        const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh,

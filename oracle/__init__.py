@@ -370,6 +370,18 @@ def backward_reduced(X, W, dY, terms: int = 1, nthreads: int | None = None, abso
     return dX, dW
 
 
+def backward_xtw_reduced(X, W, dY, terms: int = 1, nthreads: int | None = None, absolute: bool = False):
+    """(dX64, dW64) = (W dY^T, X dY) of the transposed layer Y = X^T W in the reduced-precision modes: every operand of
+    a product rounded (or split) element by element, exact products, double sums - linear_reduced on the operands laid
+    out as A B^T."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    G = np.ascontiguousarray(dY, dtype=np.float32)
+    dX = linear_reduced(W, G, None, terms, nthreads, absolute)                                # [T x D] [C x D]^T
+    dW = linear_reduced(X, np.ascontiguousarray(G.T), None, terms, nthreads, absolute)       # [T x C] [D x C]^T
+    return dX, dW
+
+
 def linear_xtw_reduced(X, W, b=None, terms: int = 1, nthreads: int | None = None, absolute: bool = False) -> np.ndarray:
     """The transposed layer Y = X^T W + b (X [T x C], W [T x D]) in the reduced-precision modes of linear_reduced:
     the rounding (or the split) acts element by element, so it is that function on the transposed operands."""

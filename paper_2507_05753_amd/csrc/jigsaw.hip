@@ -260,6 +260,36 @@ static BwReduced bw_reduced_layout(const jg_plan* p)
     return L;
 }
 
+// The same for the transposed layer Y = X^T W (X_r tokens x channels, W_r tokens x columns, dY_r channels x columns):
+// dX = W dY^T contracts over the columns (W_r and dY_r rounded as they are), dW = X dY over the channels (X_r rounded
+// as it is, every channels x columns block of dY_r contraction-major).
+struct BwReducedXtw {
+    int planes, plane_d, plane_c, ld_d, ld_c, yblocks;
+    size_t w16, dy16, x16, dy16t, off_w16, off_dy16, off_x16, off_dy16t, total;
+};
+
+static BwReducedXtw bw_reduced_xtw_layout(const jg_plan* p)
+{
+    BwReducedXtw L;
+    const int ways = p->d.ways;
+    L.planes = p->d.dtype == JG_BF16X3 ? 2 : 1;
+    L.plane_d = (int)((p->wc + 63) / 64 * 64);      // contraction over the rank's share of the columns (dX)
+    L.plane_c = (int)((p->xc + 63) / 64 * 64);      // contraction over the rank's share of the channels (dW)
+    L.ld_d = L.planes == 2 ? L.plane_d : L.plane_d / 2;
+    L.ld_c = L.planes == 2 ? L.plane_c : L.plane_c / 2;
+    L.yblocks = ways == 2 ? 2 : 1;                  // channels x columns blocks stacked in a rank's dY shard
+    L.w16 = round_up(4 * (size_t)p->wr * L.ld_d, kWsAlign);
+    L.dy16 = round_up(4 * (size_t)p->yr * L.ld_d, kWsAlign);
+    L.x16 = round_up(4 * (size_t)p->xr * L.ld_c, kWsAlign);
+    L.dy16t = round_up(4 * (size_t)p->wc * L.ld_c, kWsAlign);       // one block: columns x channels
+    L.off_w16 = p->bw_off_cvt;
+    L.off_dy16 = L.off_w16 + L.w16 * ways;
+    L.off_x16 = L.off_dy16 + L.dy16 * ways;
+    L.off_dy16t = L.off_x16 + L.x16 * ways;
+    L.total = L.off_dy16t + L.dy16t * ways * L.yblocks - p->bw_off_cvt;
+    return L;
+}
+
 int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
 {
     if (!out) return JG_E_NULL;
@@ -345,7 +375,7 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     }
     p->ws_bytes = off;
     p->bw_dx_bytes = p->bw_dw_bytes = p->bw_off_dw = p->bw_ws_bytes = 0;
-    if (d.ways >= 2 && !(reduced && xtw)) {
+    if (d.ways >= 2) {
         // one partial per rank for dX and (wherever dW sums two terms: 4-way, and the 2-way transposed layer) for dW
         p->bw_dx_bytes = round_up((size_t)p->xr * (size_t)p->xc * sizeof(float), kWsAlign);
         p->bw_off_dw = p->bw_dx_bytes * d.ways;
@@ -361,7 +391,7 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     if (d.tail == JG_TAIL_SPLIT && reduced) {
         // one 256 x 256 scratch tile per CU, when the launches of the pass can end in a partial round worth splitting
         p->tail_bytes = jg::bf16_tail_scratch_bytes(p->slots / 2);
-        if (!xtw) p->bw_tail_bytes = p->tail_bytes;
+        p->bw_tail_bytes = p->tail_bytes;
     } else if (d.tail == JG_TAIL_SPLIT) {
         auto need = [&](int nprob, int64_t m, int64_t n, int64_t k) {
             const int64_t tiles = nprob * ((m + jg::BM - 1) / jg::BM) * ((n + jg::BN - 1) / jg::BN);
@@ -382,7 +412,7 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     p->off_tail = p->ws_bytes;
     p->ws_bytes += p->tail_bytes;
     p->bw_off_cvt = p->bw_ws_bytes;
-    if (reduced && !xtw) p->bw_ws_bytes += bw_reduced_layout(p).total;
+    if (reduced) p->bw_ws_bytes += xtw ? bw_reduced_xtw_layout(p).total : bw_reduced_layout(p).total;
     p->bw_off_tail = p->bw_ws_bytes;
     p->bw_ws_bytes += p->bw_tail_bytes;
     p->ws_bytes = round_up(p->ws_bytes, kWsAlign);
@@ -406,9 +436,6 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     const bool xtw = d.op == JG_OP_XTW;
     const bool reduced = d.dtype != JG_F32;
     const int64_t eb = d.dtype == JG_BF16 ? 2 : 4;     // bytes per element of an X or W shard (split mode: hi + lo)
-    if (reduced && xtw && (what == JG_Q_BACKWARD_WORKSPACE_BYTES || what == JG_Q_BACKWARD_FLOPS_TOTAL ||
-                what == JG_Q_BACKWARD_GEMM_LAUNCHES || what == JG_Q_BACKWARD_TAIL_SCRATCH_BYTES))
-        return JG_E_DTYPE;   // no backward for this op
     switch (what) {
     case JG_Q_WORKSPACE_BYTES: *out = (int64_t)plan->ws_bytes; break;
     case JG_Q_FLOPS_TOTAL: *out = 2 * M * K * N; break;
@@ -1080,13 +1107,95 @@ static int backward_reduced(const jg_plan* plan, const float* const* x_sh, const
     return JG_OK;
 }
 
+// Backward of the transposed layer in reduced precision; arguments already checked.  x_sh, w_sh: FP32 shards.
+// Blocks and sums as backward_xtw; what each product reads is rounded into the workspace first.
+static int backward_xtw_reduced(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                                const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh, char* ws)
+{
+    const int ways = plan->d.ways;
+    jg_ctx* c = plan->ctx;
+    const int tr = (int)plan->xr, ch = (int)plan->xc, dh = (int)plan->wc;
+    if ((ch & 7) || (dh & 7)) return JG_E_SHAPE;    // X_r, W_r and dY_r are rounded in 16-byte chunks of 8 along their rows
+    const BwReducedXtw L = bw_reduced_xtw_layout(plan);
+    const int rows = ways == 4 ? 2 : 1;
+    auto rk = [&](int i, int j) { return rows == 2 ? 2 * i + j : j; };
+    auto w16 = [&](int r) { return reinterpret_cast<const float*>(ws + L.off_w16 + r * L.w16); };
+    auto x16 = [&](int r) { return reinterpret_cast<const float*>(ws + L.off_x16 + r * L.x16); };
+    // dY_(a,j): on rank (a, j) in the 4-way form; block a of rank j's stacked pair in the 2-way form
+    auto dy16 = [&](int a, int j) {
+        const char* base = ws + L.off_dy16 + (rows == 2 ? rk(a, j) : j) * L.dy16;
+        return reinterpret_cast<const float*>(base) + (rows == 2 ? 0 : (int64_t)a * ch * L.ld_d);
+    };
+    auto dy16t = [&](int a, int j) {
+        const int r = rows == 2 ? rk(a, j) : j, b = rows == 2 ? 0 : a;
+        return reinterpret_cast<const float*>(ws + L.off_dy16t + (r * L.yblocks + b) * L.dy16t);
+    };
+    auto u16 = [](const float* p) { return reinterpret_cast<uint16_t*>(const_cast<float*>(p)); };
+    {
+        ScopedTimer t(c, JG_KERNEL_SHARD);
+        jg::CvtGroup cv;
+        std::memset(&cv, 0, sizeof(cv));
+        cv.nblocks = ways;
+        cv.planes = L.planes;
+        cv.rows = tr; cv.cols = dh; cv.plane = L.plane_d;                   // W_r as it is
+        for (int r = 0; r < ways; ++r) cv.b[r] = {w_sh[r], u16(w16(r)), dh};
+        if (!HIP_OK(jg::launch_cvt_group(cv, c->stream))) return JG_E_HIP;
+        cv.rows = (int)plan->yr;                                            // dY_r as it is (2-way: both blocks)
+        for (int r = 0; r < ways; ++r)
+            cv.b[r] = {dy_sh[r], reinterpret_cast<uint16_t*>(ws + L.off_dy16 + r * L.dy16), dh};
+        if (!HIP_OK(jg::launch_cvt_group(cv, c->stream))) return JG_E_HIP;
+        cv.rows = tr; cv.cols = ch; cv.plane = L.plane_c;                   // X_r as it is
+        for (int r = 0; r < ways; ++r) cv.b[r] = {x_sh[r], u16(x16(r)), ch};
+        if (!HIP_OK(jg::launch_cvt_group(cv, c->stream))) return JG_E_HIP;
+        cv.rows = ch; cv.cols = dh;                                         // every dY block contraction-major
+        for (int b = 0; b < L.yblocks; ++b) {
+            for (int r = 0; r < ways; ++r)
+                cv.b[r] = {dy_sh[r] + (int64_t)b * ch * dh,
+                           reinterpret_cast<uint16_t*>(ws + L.off_dy16t + (r * L.yblocks + b) * L.dy16t), dh};
+            if (!HIP_OK(jg::launch_cvt_transposed_group(cv, c->stream))) return JG_E_HIP;
+        }
+    }
+    char* tail = plan->bw_tail_bytes ? ws + plan->bw_off_tail : nullptr;
+    jg::GemmGroup g;
+    std::memset(&g, 0, sizeof(g));
+    auto launch = [&](int kernel_class, int plane) -> bool {
+        return run_gemm(plan, g, jg::kGemmNT, kernel_class, tail, plan->bw_tail_bytes, nullptr, plane);
+    };
+    auto dx_part = [&](int r) { return reinterpret_cast<float*>(ws + r * plan->bw_dx_bytes); };
+    auto dw_part = [&](int r) { return reinterpret_cast<float*>(ws + plan->bw_off_dw + r * plan->bw_dw_bytes); };
+    g.nprob = ways;
+    const int passes = ways == 1 ? 1 : 2;
+    for (int pass = 0; pass < passes; ++pass) {     // dX_(i,a) = sum_j W_(i,j) dY_(a,j)^T: term j = 1 - a, then j = a
+        g.M = tr; g.N = ch; g.K = dh;
+        for (int i = 0; i < rows; ++i)
+            for (int a = 0; a < (ways == 1 ? 1 : 2); ++a) {
+                const int r = rk(i, a), j = ways == 1 ? 0 : (pass == 0 ? 1 - a : a);
+                const bool last = pass == passes - 1;
+                g.p[r] = {w16(rk(i, j)), dy16(a, j), last ? dx_sh[r] : dx_part(r), (last && ways > 1) ? dx_part(r) : nullptr,
+                          nullptr, L.ld_d, L.ld_d, ch, (last && ways > 1) ? ch : 0};
+            }
+        if (!launch(JG_KERNEL_GEMM_DX, L.plane_d)) return JG_E_HIP;
+    }
+    for (int pass = 0; pass < passes; ++pass) {     // dW_(i,j) = sum_a X_(i,a) dY_(a,j): term a = 1 - j, then a = j
+        g.M = tr; g.N = dh; g.K = ch;
+        for (int i = 0; i < rows; ++i)
+            for (int j = 0; j < (ways == 1 ? 1 : 2); ++j) {
+                const int r = rk(i, j), a = ways == 1 ? 0 : (pass == 0 ? 1 - j : j);
+                const bool last = pass == passes - 1;
+                g.p[r] = {x16(rk(i, a)), dy16t(a, j), last ? dw_sh[r] : dw_part(r), (last && ways > 1) ? dw_part(r) : nullptr,
+                          nullptr, L.ld_c, L.ld_c, dh, (last && ways > 1) ? dh : 0};
+            }
+        if (!launch(JG_KERNEL_GEMM_DW, L.plane_c)) return JG_E_HIP;
+    }
+    return JG_OK;
+}
+
 int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
                        const float* const* dy_sh, float* const* dx_sh, float* const* dw_sh,
                        void* workspace, size_t workspace_bytes)
 {
     if (!plan || !plan->ctx) return JG_E_NULL;
     const jg_linear_desc& d = plan->d;
-    if (d.dtype != JG_F32 && d.op != JG_OP_XWT) return JG_E_DTYPE;
     const int ways = d.ways;
     if (int rc = check_ptr_array(x_sh, ways)) return rc;
     if (int rc = check_ptr_array(w_sh, ways)) return rc;
@@ -1100,12 +1209,13 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
     jg_ctx* c = plan->ctx;
     if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
     char* ws = static_cast<char*>(workspace);
-    if (d.op == JG_OP_XTW) return backward_xtw(plan, x_sh, w_sh, dy_sh, dx_sh, dw_sh, ws);
     if (d.dtype != JG_F32) {
         for (int r = 0; r < ways; ++r)
             if (!aligned(x_sh[r], 4) || !aligned(w_sh[r], 4) || !aligned(dy_sh[r], 4)) return JG_E_ALIGN;
-        return backward_reduced(plan, x_sh, w_sh, dy_sh, dx_sh, dw_sh, ws);
+        return d.op == JG_OP_XTW ? backward_xtw_reduced(plan, x_sh, w_sh, dy_sh, dx_sh, dw_sh, ws)
+                                 : backward_reduced(plan, x_sh, w_sh, dy_sh, dx_sh, dw_sh, ws);
     }
+    if (d.op == JG_OP_XTW) return backward_xtw(plan, x_sh, w_sh, dy_sh, dx_sh, dw_sh, ws);
 
     // shard shapes: X_r is mr x kh, W_r is (wr) x kh, dY_r is mr x nh
     const int mr = (int)plan->xr, kh = (int)plan->xc, nh = (int)plan->yc;

@@ -16,7 +16,7 @@ class JigsawLinear:
     ``op = JG_OP_XWT``: Y = X W^T with X (M, K) and W (N, K).  ``op = JG_OP_XTW``: the transposed
     layer Y = X^T W with X (K, M) and W (K, N).  ``dtype = JG_BF16 / JG_BF16X3``: the X and W shards are
     bfloat16 tensors (split mode: every row is [hi | lo]) written by ``shard`` from FP32 inputs; the backward of such a
-    plan (plain layer only) reads FP32 copies (``shard_master``).
+    plan reads FP32 copies (``shard_master``).
     """
 
     def __init__(self, M: int, K: int, N: int, ways: int, bias: bool = False,
@@ -132,9 +132,7 @@ class JigsawLinear:
                 self.w32 = [torch.empty((q(jg.JG_Q_W_ROWS, r), q(jg.JG_Q_W_COLS, r)), **f32) for r in range(self.ways)]
             self.dx = [torch.empty_like(t) for t in self.x32]
             self.dw = [torch.empty_like(t) for t in self.w32]
-            # (a reduced-precision transposed plan has no dX / dW pass; its dY shards still serve the bias gradient)
-            has_backward = self.dtype == jg.JG_F32 or self.op == jg.JG_OP_XWT
-            self.bw_ws_bytes = self.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES) if has_backward else 0
+            self.bw_ws_bytes = self.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES)
             self.bw_ws = torch.empty((max(self.bw_ws_bytes, 1),), dtype=torch.uint8, device=self.dev)
 
     def shard_dy(self, dY):

@@ -505,9 +505,16 @@ def test_reduced_precision_transposed_plans_account_for_their_shards():
         if ways >= 2:   # the activation block a rank receives is bfloat16 too
             assert (q(h, jg.JG_Q_WORKSPACE_BYTES) - q(h, jg.JG_Q_TAIL_SCRATCH_BYTES)
                     < q(f, jg.JG_Q_WORKSPACE_BYTES) - q(f, jg.JG_Q_TAIL_SCRATCH_BYTES))
-        with pytest.raises(jg.JigsawError) as e:
-            q(h, jg.JG_Q_BACKWARD_WORKSPACE_BYTES)
-        assert e.value.status == jg.JG_E_DTYPE
+        # backward: the FP32 plan's partials, plus W_r, dY_r and X_r rounded as they are and every block of dY_r
+        # contraction-major
+        up = lambda n: (n + 255) // 256 * 256
+        tr, ch, dh, yr = q(f, jg.JG_Q_X_ROWS), q(f, jg.JG_Q_X_COLS), q(f, jg.JG_Q_W_COLS), q(f, jg.JG_Q_Y_ROWS)
+        pd, pc = (dh + 63) // 64 * 64, (ch + 63) // 64 * 64
+        yblocks = 2 if ways == 2 else 1
+        for p, eb in ((h, 2), (s, 4)):
+            partials = q(f, jg.JG_Q_BACKWARD_WORKSPACE_BYTES) - q(f, jg.JG_Q_BACKWARD_TAIL_SCRATCH_BYTES)
+            cvt = ways * (up(eb * tr * pd) + up(eb * yr * pd) + up(eb * tr * pc) + yblocks * up(eb * dh * pc))
+            assert q(p, jg.JG_Q_BACKWARD_WORKSPACE_BYTES) - q(p, jg.JG_Q_BACKWARD_TAIL_SCRATCH_BYTES) == partials + cvt
         for p in (f, h, s):
             jg.jg_plan_destroy(p)
 

@@ -779,11 +779,11 @@ def test_backward_in_reduced_precision_checks_its_arguments(jg, ctx):
         with pytest.raises(jg.JigsawError) as e:
             jg.jg_linear_backward(L.plan, p(L.x32), p(L.w32), p(L.dy), p(L.dx), p(L.dw), L.bw_ws.data_ptr(), L.bw_ws_bytes - 1)
         assert e.value.status == jg.JG_E_WORKSPACE
-    with JigsawLinear(32, 64, 32, 2, ctx=ctx, dtype=jg.JG_BF16, op=jg.JG_OP_XTW) as L:
-        ptrs = [t.data_ptr() for t in L.y]
+    with JigsawLinear(20, 64, 32, 2, ctx=ctx, dtype=jg.JG_BF16, op=jg.JG_OP_XTW) as L:      # M / 2 = 10 channels
+        L.alloc_backward()
         with pytest.raises(jg.JigsawError) as e:
-            jg.jg_linear_backward(L.plan, ptrs, ptrs, ptrs, ptrs, ptrs, None, 0)
-        assert e.value.status == jg.JG_E_DTYPE
+            jg.jg_linear_backward(L.plan, p(L.x32), p(L.w32), p(L.dy), p(L.dx), p(L.dw), L.bw_ws.data_ptr(), L.bw_ws_bytes)
+        assert e.value.status == jg.JG_E_SHAPE
 
 
 @pytest.mark.timeout(900)
@@ -829,3 +829,38 @@ def test_backward_in_reduced_precision_at_config3(jg, capsys, dtype_name):
         ex, ew = (np.abs(dXs - wantX) / SX).max(), (np.abs(dWs - wantW) / SW).max()
         assert ex <= TOL and ew <= TOL, (ways, ex, ew)
         note(capsys, f"{dtype_name} backward ways={ways}: dX max err/S {ex:.2e} ({dXs.size} entries), dW {ew:.2e} ({dWs.size})")
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+@pytest.mark.parametrize("K,M,N", [(2, 16, 16), (100, 112, 80), (130, 272, 144), (258, 144, 272), (521 * 2, 304, 1040)])
+def test_backward_of_the_transposed_layer_in_reduced_precision(jg, ctx, ways, dtype_name, K, M, N):
+    """dX = rnd(W) rnd(dY)^T and dW = rnd(X) rnd(dY): 1e-6 * S against the oracle (K = tokens, any count; a rank's
+    share of the channels M and of the columns N in whole 8-element chunks)."""
+    from paper_2507_05753_amd.layer import JigsawLinear
+    dtype = getattr(jg, dtype_name)
+    t = terms_of(jg, dtype)
+    X = (inputs.matrix(495, K, M, "R") * np.float32(3.0)).astype(np.float32)
+    W = inputs.matrix(496, K, N, "R", inputs.W_SCALE_EXP)
+    dY = inputs.matrix(497, M, N, "R")
+    with JigsawLinear(M, K, N, ways, ctx=ctx, dtype=dtype, op=jg.JG_OP_XTW) as L:
+        L.shard_master(dev(X), dev(W))
+        L.shard_dy(dev(dY))
+        L.bw_ws.fill_(0xFF)
+        L.backward()
+        dX, dW = L.gather_dx().cpu().numpy(), L.gather_dw().cpu().numpy()
+        L.backward()
+        assert np.array_equal(dX, L.gather_dx().cpu().numpy()) and np.array_equal(dW, L.gather_dw().cpu().numpy())
+    wX, wW = oracle.backward_xtw_reduced(X, W, dY, t)
+    SX, SW = oracle.backward_xtw_reduced(X, W, dY, t, absolute=True)
+    ex, ew = np.abs(dX - wX), np.abs(dW - wW)
+    assert np.all(ex <= TOL * SX), f"dX: {(ex / np.maximum(SX, 1e-300)).max():.3e}"
+    assert np.all(ew <= TOL * SW), f"dW: {(ew / np.maximum(SW, 1e-300)).max():.3e}"
+    XL, WL, GL = inputs.matrix(498, K, M, "L"), inputs.matrix(499, K, N, "L"), inputs.matrix(500, M, N, "L")
+    with JigsawLinear(M, K, N, ways, ctx=ctx, dtype=dtype, op=jg.JG_OP_XTW) as L:
+        L.shard_master(dev(XL), dev(WL))
+        L.shard_dy(dev(GL))
+        L.backward()
+        eX, eW = oracle.backward_xtw(XL, WL, GL)
+        assert np.array_equal(L.gather_dx().cpu().numpy().astype(np.float64), eX)
+        assert np.array_equal(L.gather_dw().cpu().numpy().astype(np.float64), eW)

@@ -303,3 +303,26 @@ def test_mixed_mlp_backward_is_the_pinned_pieces_in_sequence(terms):
     m = oracle.mlp_backward_reduced(Xn32, W1, b1, W2, dY, terms)
     dXl, dg, db = oracle.layernorm_backward(X, gamma, (m["dX"] - dY).astype(np.float32), 1)
     assert np.array_equal(rb["dX"], dY + dXl) and np.array_equal(rb["dgamma"], dg) and np.array_equal(rb["dW1"], m["dW1"])
+
+
+@pytest.mark.parametrize("terms", [1, 3])
+def test_backward_of_the_transposed_layer_in_reduced_precision(terms):
+    T, C, D = 12, 6, 10
+    X = inputs.matrix(101, T, C, "R") * np.float32(3.0)
+    W = inputs.matrix(102, T, D, "R", inputs.W_SCALE_EXP)
+    G = inputs.matrix(103, C, D, "R")
+    dX, dW = oracle.backward_xtw_reduced(X, W, G, terms)
+    assert dX.shape == (T, C) and dW.shape == (T, D)
+    fX, fW = oracle.backward_xtw(X, W, G)
+    if terms == 1:      # the full-precision backward of the rounded matrices, and visibly not of the unrounded ones
+        wX, wW = oracle.backward_xtw(oracle.round_bf16(X), oracle.round_bf16(W), oracle.round_bf16(G))
+        assert np.array_equal(dX, wX) and np.array_equal(dW, wW)
+        assert np.abs(dW - fW).max() > 1e-5
+    else:
+        mX, mW = oracle.backward_xtw(X, W, G, absolute=True)
+        assert np.all(np.abs(dX - fX) <= 2.0 ** -15 * mX) and np.all(np.abs(dW - fW) <= 2.0 ** -15 * mW)
+        assert not np.array_equal(dX, fX)
+    XL, WL, GL = inputs.matrix(104, T, C, "L"), inputs.matrix(105, T, D, "L"), inputs.matrix(106, C, D, "L")
+    lX, lW = oracle.backward_xtw_reduced(XL, WL, GL, terms)
+    eX, eW = oracle.backward_xtw(XL, WL, GL)
+    assert np.array_equal(lX, eX) and np.array_equal(lW, eW)
