@@ -575,6 +575,23 @@ def token_mixing_block_reduced(ways: int, X, gamma, beta, W1, b1, W2, b2, terms:
     return dict(H=H, Y=Y, Xn=Xn, S1=S1, SY=SY)
 
 
+def token_mixing_block_backward_reduced(ways: int, X, gamma, beta, W1, b1, W2, dY, terms: int = 1, eps: float = LN_EPS):
+    """token_mixing_block_backward with every product in mixed precision (linear_xtw_reduced, backward_reduced,
+    backward_xtw_reduced); the norm, the GELU derivative, the bias gradients and the skip connection in full."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    G32 = np.ascontiguousarray(dY, dtype=np.float32)
+    Xn32 = layernorm(X, gamma, beta, ln_groups(ways), eps).astype(np.float32)
+    A = linear_xtw_reduced(Xn32, W1, b1, terms)
+    H32 = gelu(A).astype(np.float32)
+    dW2, dH = backward_reduced(W2, H32, G32, terms)
+    dA = dH * gelu_grad(A)
+    dA32 = dA.astype(np.float32)
+    dXn, dW1 = backward_xtw_reduced(Xn32, W1, dA32, terms)
+    dXl, dgamma, dbeta = layernorm_backward(X, gamma, dXn.astype(np.float32), ln_groups(ways), eps)
+    return dict(A=A, dH=dH, dA=dA, dXn=dXn, dX=G32.astype(np.float64) + dXl, dW1=dW1, db1=bias_backward(dA32),
+                dW2=dW2, db2=bias_backward(np.ascontiguousarray(G32.T)), dgamma=dgamma, dbeta=dbeta)
+
+
 def token_mixing_block_backward(ways: int, X, gamma, beta, W1, b1, W2, dY, eps: float = LN_EPS):
     """Gradients of token_mixing_block for an incoming gradient dY [T x C], in double, by the chain rule through the
     steps in the layouts the layers use, with what the method stores between the steps handed on in FP32:

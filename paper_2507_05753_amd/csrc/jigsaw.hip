@@ -1582,7 +1582,9 @@ int jg_mlp_forward(const jg_plan* first, const jg_plan* second, const float* con
 // (reduced precision: the recomputed forward reads X and W1 rounded, behind the first plan's own forward workspace)
 static size_t mlp_backward_w16_bytes(const jg_plan* first)
 {
-    return first->d.dtype == JG_F32 ? 0 : round_up(4 * (size_t)first->wr * (size_t)first->xcp, kWsAlign);
+    if (first->d.dtype == JG_F32) return 0;
+    const size_t rows = first->d.op == JG_OP_XTW ? first->wc : first->wr;      // (contraction-major shards: wc rows)
+    return round_up(4 * rows * (size_t)first->xcp, kWsAlign);
 }
 
 static size_t mlp_backward_workspace(const jg_plan* first, const jg_plan* second)
@@ -1821,8 +1823,8 @@ int jg_token_mixing_backward(const jg_plan* first, const jg_plan* second, const 
                              size_t workspace_bytes)
 {
     if (int rc = check_token_chain(first, second)) return rc;
-    if (first->d.dtype != JG_F32) return JG_E_DTYPE;
     const int ways = first->d.ways;
+    const bool reduced = first->d.dtype != JG_F32;
     for (float* const* arr : {a_sh, dh_sh, da_sh, dxn_sh, db1_sh})
         if (int rc = check_ptr_array(arr, ways)) return rc;
     if (int rc = check_ptr_array(dy_sh, ways)) return rc;
@@ -1854,8 +1856,43 @@ int jg_token_mixing_backward(const jg_plan* first, const jg_plan* second, const 
         ScopedTimer t(c, JG_KERNEL_REDUCE);
         if (!HIP_OK(jg::launch_rowsum_group(rg, c->stream))) return JG_E_HIP;
     }
-    // the pre-activation, which the forward does not keep: A = Xn^T W1 + b1 once more
-    rc = forward_impl(first, xn_sh, w1_sh, b1_sh, nullptr, JG_ACT_NONE, a_sh, workspace, workspace_bytes, nullptr);
+    // the pre-activation, which the forward does not keep: A = Xn^T W1 + b1 once more (mixed precision: from the FP32
+    // Xn and W1 this call is given, rounded contraction-major as the forward's shard step does)
+    const float* const* a_x = xn_sh;
+    const float* const* a_w = w1_sh;
+    const float* x16[4];
+    const float* w16[4];
+    if (reduced) {
+        if (int rc1 = check_ptr_array(xn_sh, ways)) return rc1;
+        if (int rc1 = check_ptr_array(w1_sh, ways)) return rc1;
+        char* ws = static_cast<char*>(workspace);
+        const size_t wbytes = mlp_backward_w16_bytes(first);
+        jg::CvtGroup cv;
+        std::memset(&cv, 0, sizeof(cv));
+        cv.nblocks = ways;
+        cv.planes = first->d.dtype == JG_BF16X3 ? 2 : 1;
+        cv.plane = (int)first->plane;
+        cv.rows = (int)first->xr;
+        ScopedTimer t(c, JG_KERNEL_SHARD);
+        cv.cols = (int)first->xc;
+        for (int r = 0; r < ways; ++r) {
+            if (!aligned(xn_sh[r], 4) || !aligned(w1_sh[r], 4)) return JG_E_ALIGN;
+            char* dst = ws + first->ws_bytes + r * first->chain_shard_bytes;
+            cv.b[r] = {xn_sh[r], reinterpret_cast<uint16_t*>(dst), first->xc};
+            x16[r] = reinterpret_cast<const float*>(dst);
+        }
+        if (!HIP_OK(jg::launch_cvt_transposed_group(cv, c->stream))) return JG_E_HIP;
+        cv.cols = (int)first->wc;
+        for (int r = 0; r < ways; ++r) {
+            char* dst = ws + first->ws_bytes + first->chain_bytes + r * wbytes;
+            cv.b[r] = {w1_sh[r], reinterpret_cast<uint16_t*>(dst), first->wc};
+            w16[r] = reinterpret_cast<const float*>(dst);
+        }
+        if (!HIP_OK(jg::launch_cvt_transposed_group(cv, c->stream))) return JG_E_HIP;
+        a_x = x16;
+        a_w = w16;
+    }
+    rc = forward_impl(first, a_x, a_w, b1_sh, nullptr, JG_ACT_NONE, a_sh, workspace, workspace_bytes, nullptr);
     if (rc != JG_OK) return rc;
     {   // dA = dH * gelu'(A)
         jg::ActBwdGroup ag;

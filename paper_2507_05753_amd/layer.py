@@ -415,6 +415,10 @@ class JigsawTokenMixing:
             assert X.is_cuda and X.dtype == torch.float32 and X.shape == (self.T, self.C) and X.stride(1) == 1
             jg.jg_shard(self.first.plan, jg.JG_T_X_F32, X.data_ptr(), X.stride(0), [t.data_ptr() for t in self.xin])
         self.first.shard(None, W1, b1)
+        if self.dtype != jg.JG_F32 and getattr(self, "keep_masters", False):
+            # mixed-precision training keeps the FP32 weights: the backward reads them
+            self.first.shard_master(None, W1)
+            self.second.shard_master(W2, None)
         if W2 is not None:      # W2 takes the place of the second layer's activations
             assert W2.is_cuda and W2.dtype == torch.float32 and W2.shape == (self.T, self.D) and W2.stride(1) == 1
             jg.jg_shard(self.second.plan, jg.JG_T_X, W2.data_ptr(), W2.stride(0), [t.data_ptr() for t in self.second.x])
@@ -444,11 +448,16 @@ class JigsawTokenMixing:
         assert dY is None or (dY.is_cuda and dY.dtype == torch.float32 and dY.shape == (self.T, self.C))
         if getattr(self, "grads", None) is None:
             like = lambda ts: [torch.empty_like(t) for t in ts]
+            w1, w2 = self.master_weights()
             self.grads = dict(dy=like(s.y), a=like(f.y), dh=like(f.y), da=like(f.y), dxn=like(self.xin),
-                              dx=like(self.xin), dw1=like(f.w), db1=like(f.b), dw2=like(s.x))
+                              dx=like(self.xin), dw1=like(w1), db1=like(f.b), dw2=like(w2))
             vec = lambda n: torch.empty((n,), dtype=torch.float32, device=f.dev)
             self.db2, self.dgamma, self.dbeta = vec(self.T), vec(self.C), vec(self.C)
-            need = max(f.query(jg.JG_Q_WORKSPACE_BYTES), f.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES),
+            up = lambda n: (n + 255) // 256 * 256
+            recompute = f.query(jg.JG_Q_CHAIN_WORKSPACE_BYTES)
+            if self.dtype != jg.JG_F32:
+                recompute += self.ways * up(f.query(jg.JG_Q_W_SHARD_BYTES))
+            need = max(recompute, f.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES),
                        s.query(jg.JG_Q_BACKWARD_WORKSPACE_BYTES), f.query(jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES))
             self.bw_ws = torch.empty((need,), dtype=torch.uint8, device=f.dev)
             self.bw_ws_bytes = need
@@ -457,11 +466,21 @@ class JigsawTokenMixing:
         dy = g["dy"] if dy_shards is None else dy_shards
         if dy_shards is None:
             jg.jg_shard(s.plan, jg.JG_T_Y, dY.data_ptr(), dY.stride(0), p(dy))
+        w1, w2 = self.master_weights()
         jg.jg_token_mixing_backward(f.plan, s.plan, p(self.xin), self.gamma.data_ptr() if self.gamma is not None else None,
-                                    self.eps, p(self.xn), p(f.w), p(f.b), p(s.x), p(f.y), p(dy), p(g["a"]),
+                                    self.eps, p(self.xn), p(w1), p(f.b), p(w2), p(f.y), p(dy), p(g["a"]),
                                     p(g["dh"]), p(g["da"]), p(g["dxn"]), p(g["dx"]), p(g["dw1"]), p(g["db1"]),
                                     p(g["dw2"]), self.db2.data_ptr(), self.dgamma.data_ptr(), self.dbeta.data_ptr(),
                                     self.bw_ws.data_ptr(), self.bw_ws_bytes)
+
+    def master_weights(self):
+        """(W1 shards, W2 shards) in FP32: the plans' own for FP32 plans, the kept masters in mixed precision
+        (set ``keep_masters = True`` before ``shard``)."""
+        f, s = self.first, self.second
+        if self.dtype == jg.JG_F32:
+            return f.w, s.x
+        assert getattr(f, "w32", None) is not None, "mixed-precision backward: set keep_masters before shard()"
+        return f.w32, s.x32
 
     def gather_grad(self, name: str):
         """A gradient (or kept intermediate) of backward() as a global matrix: 'a', 'dh', 'da' (C, D), 'dx', 'dxn'
@@ -471,9 +490,9 @@ class JigsawTokenMixing:
         if name == "db1":       # rank r holds the slice of column half r % 2 (replicated in the 4-way form)
             return torch.cat(g[name][:1] if self.ways == 1 else g[name][:2])
         plan, which, shape = {"a": (f, jg.JG_T_Y, (self.C, self.D)), "dh": (f, jg.JG_T_Y, (self.C, self.D)),
-                              "da": (f, jg.JG_T_Y, (self.C, self.D)), "dx": (f, jg.JG_T_X, (self.T, self.C)),
-                              "dxn": (f, jg.JG_T_X, (self.T, self.C)), "dw1": (f, jg.JG_T_W, (self.T, self.D)),
-                              "dw2": (s, jg.JG_T_X, (self.T, self.D))}[name]
+                              "da": (f, jg.JG_T_Y, (self.C, self.D)), "dx": (f, jg.JG_T_X_F32, (self.T, self.C)),
+                              "dxn": (f, jg.JG_T_X_F32, (self.T, self.C)), "dw1": (f, jg.JG_T_W_F32, (self.T, self.D)),
+                              "dw2": (s, jg.JG_T_X_F32, (self.T, self.D))}[name]
         out = torch.empty(shape, dtype=torch.float32, device=f.dev)
         jg.jg_gather_as(plan.plan, which, p(g[name]), out.data_ptr(), out.stride(0))
         return out

@@ -533,7 +533,7 @@ def test_token_mixing_chain_takes_two_plans_of_one_precision():
                      jg.jg_plan_create(None, T, D, C, 2, False, dtype=dt))
     for dt, (f, s) in plans.items():
         assert fwd(f, s) == jg.JG_E_NULL                                   # chains; the plans have no context
-        assert bwd(f, s) == (jg.JG_E_NULL if dt == jg.JG_F32 else jg.JG_E_DTYPE)      # the backward is FP32 only
+        assert bwd(f, s) == jg.JG_E_NULL
         for other, (f2, s2) in plans.items():
             if other != dt:
                 assert fwd(f, s2) == jg.JG_E_DTYPE

@@ -650,3 +650,52 @@ def test_whole_mixing_block_backward(jg, ctx, ways):
     assert loose(mid, rc["dX"]) and loose(chan["dw1"], rc["dW1"]) and loose(chan["dw2"], rc["dW2"])
     for k, name in (("dx", "dX"), ("dw1", "dW1"), ("dw2", "dW2"), ("db1", "db1"), ("db2", "db2"), ("dgamma", "dgamma")):
         assert loose(got[k], rt[name]), k
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+@pytest.mark.parametrize("T,C,D", [(100, 112, 112), (130, 80, 272), (264, 144, 80), (521, 304, 1040)])
+def test_token_mixing_backward_in_mixed_precision(jg, ctx, ways, dtype_name, T, C, D):
+    """jg_token_mixing_backward on reduced plans: every product against the oracle's reduced routine applied to what
+    the GPU stored for the step before (1e-6 * S), the FP32 steps within one rounding, the chain loosely."""
+    from paper_2507_05753_amd.layer import JigsawTokenMixing
+    dtype = getattr(jg, dtype_name)
+    t = 3 if dtype == jg.JG_BF16X3 else 1
+    if ways == 4 and T % 2:
+        T += 1
+    X, gamma, beta, W1, b1, W2, b2 = token_operands(510, T, C, D)
+    dY = inputs.matrix(511, T, C, "R")
+    f64 = lambda a: a.astype(np.float64)
+    within = lambda got, want, S: np.all(np.abs(f64(got) - want) <= 1e-6 * S)
+    once = lambda got, want, S: np.all(np.abs(f64(got) - want) <= HALF_ULP * np.abs(want) * (1 + 1e-6) + 1e-11 * S + 1e-45)
+    with JigsawTokenMixing(T, C, D, ways, ctx=ctx, dtype=dtype) as L:
+        L.keep_masters = True
+        L.shard(dev(X), dev(gamma), dev(beta), dev(W1), dev(b1), dev(W2), dev(b2))
+        L.forward()
+        L.backward(dev(dY))
+        Xn, H = L.gather_xn().cpu().numpy(), L.gather_h().cpu().numpy()
+        g = {k: L.gather_grad(k).cpu().numpy() for k in ("a", "dh", "da", "dxn", "dx", "dw1", "dw2", "db1")}
+        db2, dgam = L.db2.cpu().numpy(), L.dgamma.cpu().numpy()
+        L.backward(dev(dY))
+        for k in ("dx", "dw1", "dw2"):
+            assert np.array_equal(g[k], L.gather_grad(k).cpu().numpy()), k
+    assert within(g["a"], oracle.linear_xtw_reduced(Xn, W1, b1, t), oracle.linear_xtw_reduced(Xn, W1, b1, t, absolute=True)), "A"
+    (dW2, dH), (SW2, SH) = oracle.backward_reduced(W2, H, dY, t), oracle.backward_reduced(W2, H, dY, t, absolute=True)
+    assert within(g["dw2"], dW2, SW2), "dW2"
+    assert within(g["dh"], dH, SH), "dH"
+    assert once(db2, oracle.bias_backward(np.ascontiguousarray(dY.T)), oracle.bias_backward(np.ascontiguousarray(dY.T), absolute=True))
+    dA = f64(g["dh"]) * oracle.gelu_grad(f64(g["a"]))
+    assert np.all(np.abs(f64(g["da"]) - dA) <= 2.0 ** -23 * np.abs(dA) + 1e-45), "dA"
+    (dXn, dW1) = oracle.backward_xtw_reduced(Xn, W1, g["da"], t)
+    (SXn, SW1) = oracle.backward_xtw_reduced(Xn, W1, g["da"], t, absolute=True)
+    assert within(g["dxn"], dXn, SXn), "dXn"
+    assert within(g["dw1"], dW1, SW1), "dW1"
+    assert once(g["db1"], oracle.bias_backward(g["da"]), oracle.bias_backward(g["da"], absolute=True)), "db1"
+    dXl, dg, db, SX, Sg, Sb = oracle.layernorm_backward(X, gamma, g["dxn"], oracle.ln_groups(ways), magnitude=True)
+    assert once(g["dx"], f64(dY) + dXl, SX + np.abs(dY)), "dX"
+    assert once(dgam, dg, Sg)
+    r = oracle.token_mixing_block_backward_reduced(ways, X, gamma, beta, W1, b1, W2, dY, t)
+    loose = 2e-3 if t == 1 else 1e-4        # (a last-bit difference in an FP32 intermediate can flip a bfloat16 rounding)
+    for got, name in ((g["dx"], "dX"), (g["dw1"], "dW1"), (g["dw2"], "dW2"), (db2, "db2"), (dgam, "dgamma")):
+        ref = r[name]
+        assert got.shape == ref.shape and np.all(np.abs(got - ref) <= loose * (np.abs(ref) + np.abs(ref).max())), name
