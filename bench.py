@@ -557,7 +557,8 @@ def measure_token_mixing_backward(cfg, ways, args):
     T, C, D, seed = cfg["K"], cfg["M"], cfg["N"], cfg["seed"]
     dev = torch.device("cuda", 0)
     gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device=dev)
-    with JigsawTokenMixing(T, C, D, ways, tail=tail_of(args)) as L:
+    with JigsawTokenMixing(T, C, D, ways, tail=tail_of(args), dtype=dtype_of(args, jg)) as L:
+        L.keep_masters = True
         L.shard(gen(seed, T, C), (gen(seed + 5, 1, C)[0] + 1.5).contiguous(), gen(seed + 6, 1, C)[0].contiguous(),
                 gen(seed + 1, T, D, inputs.W_SCALE_EXP), gen(seed + 2, 1, D)[0].contiguous(),
                 gen(seed + 3, T, D, inputs.W_SCALE_EXP), gen(seed + 4, 1, T)[0].contiguous())
@@ -567,7 +568,7 @@ def measure_token_mixing_backward(cfg, ways, args):
     return out
 
 
-def cpu_baseline_token_mixing_backward(cfg, seconds):
+def cpu_baseline_token_mixing_backward(cfg, seconds, terms=0):
     """The oracle's backward of the token-mixing block timed on a bounded sample of channels (columns of X and dY;
     the norm sees only those)."""
     import oracle
@@ -585,7 +586,10 @@ def cpu_baseline_token_mixing_backward(cfg, seconds):
     def run(ch):
         Xs, Gs = np.ascontiguousarray(X[:, :ch]), np.ascontiguousarray(dY[:, :ch])
         t0 = time.perf_counter()
-        oracle.token_mixing_block_backward(1, Xs, gamma[:ch], beta[:ch], W1, b1, W2, Gs)
+        if terms:
+            oracle.token_mixing_block_backward_reduced(1, Xs, gamma[:ch], beta[:ch], W1, b1, W2, Gs, terms)
+        else:
+            oracle.token_mixing_block_backward(1, Xs, gamma[:ch], beta[:ch], W1, b1, W2, Gs)
         return time.perf_counter() - t0
 
     # a probe's time holds a fixed part (the weights converted to double): scaling it up underestimates the sample,
@@ -804,9 +808,8 @@ def main():
         sys.exit(3)
     from paper_2507_05753_amd import inputs
     if args.dtype != "f32" and args.op not in ("forward", "backward", "xtw", "mlp", "mixing", "mixing_backward",
-                                               "token_mixing"):
-        print("bench.py: --dtype bf16 / bf16x3 goes with --op forward, backward, xtw, mlp, mixing, mixing_backward or "
-              "token_mixing only",
+                                               "token_mixing", "token_mixing_backward"):
+        print("bench.py: --dtype bf16 / bf16x3 does not go with --op encoder",
               file=sys.stderr)
         sys.exit(2)
 
@@ -960,21 +963,26 @@ def main():
             "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
             "value": r["items_per_s"], "unit": "items/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
-            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
             "config": {"workload": f"backward of the token-mixing half of a mixing block of the 1B model: gradients of "
                                    f"Y = X + W2 gelu(layernorm(X)^T W1 + b1)^T + b2 for X, gamma, beta, W1, b1, W2, b2; "
-                                   f"X {T} x {C} [tokens, channels], hidden {D}, {args.ways}-way Jigsaw, fp32",
+                                   f"X {T} x {C} [tokens, channels], hidden {D}, {args.ways}-way Jigsaw, {precision_words(args)}",
                        "n_items": T * C, "ways": args.ways, "T": T, "C": C, "D": D, "seed": xc["seed"],
                        "x_values": "R", "op": "token_mixing_backward", "tail": args.tail},
             "tflops": r["tflops"],
-            "roofline": {"bound": "mfma", "kernel": "jg::gemm_f32_stream (dX, dW and recomputed A launches together)",
-                         "achieved": r["gemm_tflops"], "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": r["gemm_tflops"] / FP32_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None,
+            "roofline": {"bound": "mfma",
+                         "kernel": {"f32": "jg::gemm_f32_stream", "bf16": "jg::gemm_bf16_nt", "bf16x3": "jg::gemm_bf16x3_nt"}[args.dtype]
+                                   + " (dX, dW and recomputed A launches together)",
+                         "achieved": r["gemm_tflops"] * (3 if args.dtype == "bf16x3" else 1) if r["gemm_tflops"] else None,
+                         "peak": FP32_MFMA_PEAK_TFLOPS if args.dtype == "f32" else BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": (r["gemm_tflops"] * (3 if args.dtype == "bf16x3" else 1) /
+                                  (FP32_MFMA_PEAK_TFLOPS if args.dtype == "f32" else BF16_MFMA_PEAK_TFLOPS))
+                                 if r["gemm_tflops"] else None,
                          "ms_per_step": r["gemm_ms_per_step"], "traffic": None},
             "kernels": r["kernels"],
         }
         if args.cpu_seconds > 0:
-            line["cpu_baseline"] = cpu_baseline_token_mixing_backward(xc, args.cpu_seconds)
+            line["cpu_baseline"] = cpu_baseline_token_mixing_backward(xc, args.cpu_seconds, reduced_terms(args))
         print(json.dumps(line), flush=True)
         return
 

@@ -427,7 +427,11 @@ int jg_mlp_backward(const jg_plan* first, const jg_plan* second, const float* co
  *     db2[t] = sum_c dY[t][c];      A = Xn^T W1 + b1 (recomputed);      dA = dH * gelu'(A);
  *     transposed layer:  dXn = W1 dA^T,  dW1 = Xn dA  (jg_linear_backward on the JG_OP_XTW plan),  db1 = sum_c dA;
  *     dX = dY + layernorm'(dXn),  dgamma, dbeta   (as jg_layernorm_backward, the skip added before the rounding).
- * Plans as for jg_token_mixing_forward.  x_sh, gamma, eps, w1_sh, b1_sh, w2_sh: as in the forward; xn_sh, h_sh: the
+ * Plans as for jg_token_mixing_forward; on two reduced-precision plans (mixed precision) w1_sh and w2_sh are FP32
+ * shards (jg_shard(first, JG_T_W_F32) of W1, jg_shard(second, JG_T_X_F32) of W2: the master weights), every product's
+ * operands are rounded as in the forward, everything else stays FP32, and the workspace must also hold, behind the
+ * first plan's JG_Q_CHAIN_WORKSPACE_BYTES, `ways` times its JG_Q_W_SHARD_BYTES (each rounded up to 256).
+ * x_sh, gamma, eps, w1_sh, b1_sh, w2_sh: as in the forward; xn_sh, h_sh: the
  * Xn and H it stored; dy_sh: the dY shards.  Outputs (`ways` device buffers each): a_sh, dh_sh, da_sh shaped like
  * H_r; dxn_sh, dx_sh like X_r; dw1_sh like the first plan's W_r; db1_sh like its bias shards; dw2_sh like the second
  * plan's X_r; db2: device vector of length T (or NULL); dgamma, dbeta: device vectors of length C (either may be

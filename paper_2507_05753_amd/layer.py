@@ -521,10 +521,12 @@ class JigsawMixerBlock:
     place."""
 
     def __init__(self, T: int, C: int, Dt: int, Dc: int, ways: int, device: int = 0, ctx=None,
-                 tail: int = jg.JG_TAIL_SPLIT, eps: float = 1e-5, dtype: int = jg.JG_F32):
-        """``dtype = JG_BF16 / JG_BF16X3``: both halves in mixed precision (FP32 activations between them)."""
+                 tail: int = jg.JG_TAIL_SPLIT, eps: float = 1e-5, dtype: int = jg.JG_F32, keep_masters: bool = False):
+        """``dtype = JG_BF16 / JG_BF16X3``: both halves in mixed precision (FP32 activations between them);
+        ``keep_masters``: also keep the FP32 weights on shards, which the mixed-precision backward reads."""
         self.token = JigsawTokenMixing(T, C, Dt, ways, device=device, ctx=ctx, tail=tail, eps=eps, dtype=dtype)
         self.channel = JigsawMixing(T, C, Dc, ways, device=device, ctx=self.token.ctx, tail=tail, eps=eps, dtype=dtype)
+        self.token.keep_masters = self.channel.keep_masters = keep_masters
         self.channel.xin = self.token.second.y
         if dtype == jg.JG_F32:
             self.channel.first.x = self.token.second.y

@@ -864,3 +864,38 @@ def test_backward_of_the_transposed_layer_in_reduced_precision(jg, ctx, ways, dt
         eX, eW = oracle.backward_xtw(XL, WL, GL)
         assert np.array_equal(L.gather_dx().cpu().numpy().astype(np.float64), eX)
         assert np.array_equal(L.gather_dw().cpu().numpy().astype(np.float64), eW)
+
+
+@pytest.mark.parametrize("ways", [1, 4])
+@pytest.mark.parametrize("dtype_name", ["JG_BF16", "JG_BF16X3"])
+def test_mixed_precision_whole_mixing_block_backward(jg, ctx, ways, dtype_name):
+    """Backward of a whole mixing block in mixed precision: the channel half's, then the token half's on its FP32 dX
+    shards in place; the halves are checked step by step in their own tests, here the chain against the oracle's."""
+    from paper_2507_05753_amd.layer import JigsawMixerBlock
+    dtype = getattr(jg, dtype_name)
+    t = terms_of(jg, dtype)
+    T, C, Dt, Dc = 264, 272, 144, 208
+    X = (inputs.matrix(520, T, C, "R") + np.float32(0.25)).astype(np.float32)
+    vec = lambda s, n, shift=0.0: (inputs.matrix(s, 1, n, "R")[0] + np.float32(shift)).astype(np.float32)
+    g1, be1, g2, be2 = vec(521, C, 1.5), vec(522, C), vec(523, C, 1.5), vec(524, C)
+    W1, W2 = inputs.matrix(525, T, Dt, "R", inputs.W_SCALE_EXP), inputs.matrix(526, T, Dt, "R", inputs.W_SCALE_EXP)
+    b1, b2 = vec(527, Dt), vec(528, T)
+    V1, V2 = inputs.matrix(529, Dc, C, "R", inputs.W_SCALE_EXP), inputs.matrix(530, C, Dc, "R", inputs.W_SCALE_EXP)
+    c1, c2 = vec(531, Dc), vec(532, C)
+    dY = inputs.matrix(533, T, C, "R")
+    with JigsawMixerBlock(T, C, Dt, Dc, ways, ctx=ctx, dtype=dtype, keep_masters=True) as L:
+        L.shard(dev(X), token=dict(gamma=dev(g1), beta=dev(be1), W1=dev(W1), b1=dev(b1), W2=dev(W2), b2=dev(b2)),
+                channel=dict(gamma=dev(g2), beta=dev(be2), W1=dev(V1), b1=dev(c1), W2=dev(V2), b2=dev(c2)))
+        L.forward()
+        L.backward(dev(dY))
+        dX = L.gather_dx().cpu().numpy()
+        dW1, dV2 = L.token.gather_grad("dw1").cpu().numpy(), L.channel.gather_grad("dw2").cpu().numpy()
+        mid = L.channel.gather_grad("dx")
+        L.token.backward(mid)                        # the same gradient, sharded from the gathered matrix: the same bits
+        assert np.array_equal(dX, L.gather_dx().cpu().numpy())
+    U = oracle.token_mixing_block_reduced(ways, X, g1, be1, W1, b1, W2, b2, t)["Y"].astype(np.float32)
+    rc = oracle.mixing_block_backward_reduced(ways, U, g2, be2, V1, c1, V2, dY, t)
+    rt = oracle.token_mixing_block_backward_reduced(ways, X, g1, be1, W1, b1, W2, rc["dX"].astype(np.float32), t)
+    loose = 3e-3 if t == 1 else 1e-4
+    for got, ref, name in ((dX, rt["dX"], "dX"), (dW1, rt["dW1"], "dW1"), (dV2, rc["dW2"], "dV2")):
+        assert np.all(np.abs(got - ref) <= loose * (np.abs(ref) + np.abs(ref).max())), name
