@@ -18,6 +18,8 @@ struct CvtBlock {
     const float* src;     // rows x cols, leading dimension ld_src (floats)
     uint16_t* dst;        // rows of planes * plane bfloat16: [hi(0..cols) pad | lo(0..cols) pad]
     int64_t ld_src;
+    uint16_t* dst_rows;   // cvt_bf16_transposed only, or nullptr: the untransposed rounding as well (rows of
+                          // planes * plane_rows), from the same read of the source
 };
 
 struct CvtGroup {
@@ -26,6 +28,7 @@ struct CvtGroup {
     int rows, cols;       // common shape; cols is a multiple of 8
     int planes;           // 1: hi only; 2: [hi | lo] in every row
     int plane;            // elements from one plane of a row to the next (>= cols; the padding is not written)
+    int plane_rows;       // the same for CvtBlock::dst_rows
     uint32_t units_per_row, units;   // units of 8 elements
 };
 
@@ -140,6 +143,26 @@ __global__ __launch_bounds__(256) void cvt_bf16_transposed(const CvtGroup g)
             }
 #pragma unroll
             for (int q = 0; q < 4; ++q) tile[tk + 16 * i][tc + q] = v[q];
+            if (B.dst_rows && k < g.rows && c < g.cols) {      // the same values, rounded row-major
+                uint32_t hi[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) hi[q] = bf16_bits(v[q]);
+                uint16_t* d = B.dst_rows + (int64_t)k * g.plane_rows * g.planes + c;
+                if (c + 3 < g.cols) {       // (plane_rows and c are multiples of 4: 8-byte aligned)
+                    *reinterpret_cast<uint2*>(d) = uint2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+                    if (g.planes == 2) {
+                        uint32_t lo[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) lo[q] = bf16_bits(v[q] - bf16_value(hi[q]));
+                        *reinterpret_cast<uint2*>(d + g.plane_rows) = uint2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+                    }
+                } else {
+                    for (int q = 0; q < 4 && c + q < g.cols; ++q) {
+                        d[q] = (uint16_t)hi[q];
+                        if (g.planes == 2) d[g.plane_rows + q] = (uint16_t)bf16_bits(v[q] - bf16_value(hi[q]));
+                    }
+                }
+            }
         }
     }
     __syncthreads();
@@ -177,6 +200,8 @@ inline hipError_t launch_cvt_transposed_group(const CvtGroup& g, hipStream_t str
     bool vec = true;
     for (int i = 0; i < g.nblocks; ++i) {
         if ((uintptr_t)g.b[i].dst & 15) return hipErrorInvalidValue;
+        if (g.b[i].dst_rows && (((uintptr_t)g.b[i].dst_rows & 15) || (g.plane_rows & 7) || g.plane_rows < g.cols))
+            return hipErrorInvalidValue;
         if (((uintptr_t)g.b[i].src & 15) || (g.b[i].ld_src & 3)) vec = false;
     }
     const unsigned tk = (unsigned)((g.rows + CVT_T_TILE - 1) / CVT_T_TILE);

@@ -1023,21 +1023,18 @@ static int backward_reduced(const jg_plan* plan, const float* const* x_sh, const
         std::memset(&cv, 0, sizeof(cv));
         cv.nblocks = ways;
         cv.planes = L.planes;
-        // dY_r: rows as they are
-        cv.rows = mr; cv.cols = nh; cv.plane = L.plane_n;
-        for (int r = 0; r < ways; ++r) cv.b[r] = {dy_sh[r], u16(dy16(r)), nh};
-        if (!HIP_OK(jg::launch_cvt_group(cv, c->stream))) return JG_E_HIP;
-        // dY_r and X_r: contraction-major over the tokens
-        cv.plane = L.plane_m;
-        for (int r = 0; r < ways; ++r) cv.b[r] = {dy_sh[r], u16(dy16t(r)), nh};
+        // dY_r: contraction-major over the tokens and, from the same read, rows as they are
+        cv.rows = mr; cv.cols = nh; cv.plane = L.plane_m; cv.plane_rows = L.plane_n;
+        for (int r = 0; r < ways; ++r) cv.b[r] = {dy_sh[r], u16(dy16t(r)), nh, u16(dy16(r))};
         if (!HIP_OK(jg::launch_cvt_transposed_group(cv, c->stream))) return JG_E_HIP;
+        // X_r: contraction-major over the tokens
         cv.cols = kh;
-        for (int r = 0; r < ways; ++r) cv.b[r] = {x_sh[r], u16(x16t(r)), kh};
+        for (int r = 0; r < ways; ++r) cv.b[r] = {x_sh[r], u16(x16t(r)), kh, nullptr};
         if (!HIP_OK(jg::launch_cvt_transposed_group(cv, c->stream))) return JG_E_HIP;
         // the weight blocks (nh x kh each): contraction-major over the rank's share of N
         cv.rows = nh; cv.cols = kh; cv.plane = L.plane_n;
         for (int b = 0; b < L.wblocks; ++b) {
-            for (int r = 0; r < ways; ++r) cv.b[r] = {w_sh[r] + b * wblock, u16(w16t(r, b)), kh};
+            for (int r = 0; r < ways; ++r) cv.b[r] = {w_sh[r] + b * wblock, u16(w16t(r, b)), kh, nullptr};
             if (!HIP_OK(jg::launch_cvt_transposed_group(cv, c->stream))) return JG_E_HIP;
         }
     }
