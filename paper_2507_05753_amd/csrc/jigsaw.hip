@@ -1137,18 +1137,18 @@ static int backward_xtw_reduced(const jg_plan* plan, const float* const* x_sh, c
         cv.rows = tr; cv.cols = dh; cv.plane = L.plane_d;                   // W_r as it is
         for (int r = 0; r < ways; ++r) cv.b[r] = {w_sh[r], u16(w16(r)), dh};
         if (!HIP_OK(jg::launch_cvt_group(cv, c->stream))) return JG_E_HIP;
-        cv.rows = (int)plan->yr;                                            // dY_r as it is (2-way: both blocks)
-        for (int r = 0; r < ways; ++r)
-            cv.b[r] = {dy_sh[r], reinterpret_cast<uint16_t*>(ws + L.off_dy16 + r * L.dy16), dh};
-        if (!HIP_OK(jg::launch_cvt_group(cv, c->stream))) return JG_E_HIP;
         cv.rows = tr; cv.cols = ch; cv.plane = L.plane_c;                   // X_r as it is
         for (int r = 0; r < ways; ++r) cv.b[r] = {x_sh[r], u16(x16(r)), ch};
         if (!HIP_OK(jg::launch_cvt_group(cv, c->stream))) return JG_E_HIP;
-        cv.rows = ch; cv.cols = dh;                                         // every dY block contraction-major
+        // every dY block contraction-major and, from the same read, as it is (2-way: the blocks of dY_r one after
+        // the other, as the rows of its rounded shard)
+        cv.rows = ch; cv.cols = dh; cv.plane_rows = L.plane_d;
         for (int b = 0; b < L.yblocks; ++b) {
             for (int r = 0; r < ways; ++r)
                 cv.b[r] = {dy_sh[r] + (int64_t)b * ch * dh,
-                           reinterpret_cast<uint16_t*>(ws + L.off_dy16t + (r * L.yblocks + b) * L.dy16t), dh};
+                           reinterpret_cast<uint16_t*>(ws + L.off_dy16t + (r * L.yblocks + b) * L.dy16t), dh,
+                           reinterpret_cast<uint16_t*>(ws + L.off_dy16 + r * L.dy16) +
+                               (int64_t)b * ch * L.plane_d * L.planes};
             if (!HIP_OK(jg::launch_cvt_transposed_group(cv, c->stream))) return JG_E_HIP;
         }
     }
