@@ -75,7 +75,7 @@ typedef enum jg_status {
 } jg_status;
 
 enum { JG_OP_XWT = 0,                                    /* Y = X W^T (Sec. 4)          */
-       JG_OP_XTW = 1 };                                  /* Y = X^T W (Sec. 5), forward only */
+       JG_OP_XTW = 1 };                                  /* Y = X^T W (Sec. 5) */
 enum { JG_F32 = 0,       /* the paper's uniform single precision (Sec. 6.1)                          */
        JG_BF16 = 1,      /* reduced precision (Sec. 6.1 trains in a mixed precision whose matrix units
                             round FP32 operands to a short mantissa and sum in FP32; this chip has no such
