@@ -366,6 +366,22 @@ int jg_token_mixing_forward(const jg_plan* first, const jg_plan* second, const f
                             const float* const* w2_sh, const float* b2, float* const* xn_sh, float* const* h_sh,
                             float* const* y_sh, void* workspace, size_t workspace_bytes);
 
+/* run, for callers that cannot allocate.  Code under HIP graph capture, tight serving loops and harnesses that
+ * forbid allocation cannot hand jg_linear_forward a workspace they would first have to allocate.  This is the same
+ * call (same kernels, same launches, same results bit for bit) with the workspace taken from a fixed array of
+ * JG_STATIC_WORKSPACE_BYTES bytes that lives in the library's own device memory: every GPU the library has been
+ * initialised on (jg_init looks the array's address up once per device) holds one copy until the process ends.
+ * The call allocates and frees nothing, on the device or through any library.
+ * Limit: plans whose JG_Q_WORKSPACE_BYTES exceeds JG_STATIC_WORKSPACE_BYTES are refused with JG_E_WORKSPACE (a plan
+ * made with JG_TAIL_WHOLE needs no tail scratch and fits more often); so is a context on a device index of 64 or more.
+ * The array keeps the last call's contents; nothing in it has to start at zero (every partial product and scratch
+ * tile is written before it is read).  All calls on one GPU share the array: two calls that overlap on that GPU -
+ * from different streams, contexts or threads - race; calls on one stream are ordered and safe.
+ * x_sh, w_sh, b_sh, y_sh and the other errors: as jg_linear_forward. */
+#define JG_STATIC_WORKSPACE_BYTES (32u << 20)
+int jg_linear_forward_static(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                             const float* const* b_sh, float* const* y_sh);
+
 /* run (backward).  Gradients of the same layer for an incoming gradient dY (partitioned like Y):
  *     dX = dY W      (M x K, partitioned like X)       dW = dY^T X    (N x K, partitioned like W)
  * the transposed multiplications of Sec. 4.1 (last sentence); Sec. 6.3 counts them as twice the

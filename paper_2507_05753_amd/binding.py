@@ -34,6 +34,7 @@ JG_F32, JG_BF16, JG_BF16X3 = 0, 1, 2
 JG_COMBINE_FUSED, JG_COMBINE_SEPARATE = 0, 1
 JG_WEIGHTS_COPY, JG_WEIGHTS_DIRECT = 0, 1
 JG_TAIL_SPLIT, JG_TAIL_WHOLE = 0, 1
+JG_STATIC_WORKSPACE_BYTES = 32 << 20
 JG_ACT_NONE, JG_ACT_GELU = 0, 1
 JG_T_X, JG_T_W, JG_T_B, JG_T_Y, JG_T_X_F32, JG_T_W_F32 = 0, 1, 2, 3, 4, 5
 (JG_Q_WORKSPACE_BYTES, JG_Q_FLOPS_TOTAL, JG_Q_FLOPS_RANK, JG_Q_HBM_BYTES_ALGO,
@@ -48,7 +49,7 @@ JG_T_X, JG_T_W, JG_T_B, JG_T_Y, JG_T_X_F32, JG_T_W_F32 = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ("jg_init", "jg_free", "jg_plan_create", "jg_plan_destroy", "jg_plan_query", "jg_shard",
            "jg_shard_patches", "jg_gather_patches",
-           "jg_linear_forward", "jg_linear_forward_ex", "jg_mlp_forward", "jg_layernorm_forward",
+           "jg_linear_forward", "jg_linear_forward_ex", "jg_linear_forward_static", "jg_mlp_forward", "jg_layernorm_forward",
            "jg_mixing_forward", "jg_token_mixing_forward", "jg_linear_backward", "jg_bias_backward", "jg_layernorm_backward", "jg_mlp_backward", "jg_mixing_backward", "jg_token_mixing_backward", "jg_gather", "jg_gather_as", "jg_profile",
            "jg_profile_read", "jg_strerror",
            "jg_last_hip_error")
@@ -89,6 +90,8 @@ _lib.jg_gather_patches.argtypes = [_vp, _vpp, _vp, ctypes.c_int64, ctypes.c_int6
 _lib.jg_shard_patches.restype = ctypes.c_int
 _lib.jg_gather_patches.restype = ctypes.c_int
 _lib.jg_linear_forward.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
+_lib.jg_linear_forward_static.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp]
+_lib.jg_linear_forward_static.restype = ctypes.c_int
 _lib.jg_linear_forward_ex.argtypes = [_vp, _vpp, _vpp, _vpp, _vpp, ctypes.c_int, _vpp, _vp, ctypes.c_size_t]
 _lib.jg_mlp_forward.argtypes = [_vp, _vp, _vpp, _vpp, _vpp, _vpp, _vpp, _vpp, _vpp, _vp, ctypes.c_size_t]
 _lib.jg_layernorm_forward.argtypes = [_vp, _vpp, _vp, _vp, ctypes.c_double, _vpp]
@@ -185,6 +188,11 @@ def jg_linear_forward(plan, x_ptrs, w_ptrs, b_ptrs, y_ptrs, workspace_ptr, works
     _raise(_lib.jg_linear_forward(plan, _ptr_array(x_ptrs), _ptr_array(w_ptrs), _ptr_array(b_ptrs),
                                   _ptr_array(y_ptrs), workspace_ptr or None, workspace_bytes),
            "jg_linear_forward")
+
+
+def jg_linear_forward_static(plan, x_ptrs, w_ptrs, b_ptrs, y_ptrs) -> None:
+    _raise(_lib.jg_linear_forward_static(plan, _ptr_array(x_ptrs), _ptr_array(w_ptrs), _ptr_array(b_ptrs),
+                                         _ptr_array(y_ptrs)), "jg_linear_forward_static")
 
 
 def jg_linear_forward_ex(plan, x_ptrs, w_ptrs, b_ptrs, r_ptrs, activation: int, y_ptrs, workspace_ptr,

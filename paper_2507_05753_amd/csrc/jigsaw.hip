@@ -7,6 +7,7 @@
 
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -19,7 +20,18 @@
 #include "gemm_bf16.hpp"
 #include "cvt_kernels.hpp"
 
+// Workspace of jg_linear_forward_static: a fixed array in the code object's own device memory, so that the call
+// needs no allocation by anyone.  Every GPU the library is used on holds its own copy at its own address until
+// the process ends.  In host code the name is only a handle for hipGetSymbolAddress; kernels get the device
+// address kept in g_scratch_ptr[device].
+constexpr size_t kStaticScratchBytes = (size_t)JG_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
 
 // Last failing HIP call of this host thread, for jg_last_hip_error().
 thread_local char g_hip_detail[160] = "no HIP error recorded";
@@ -49,6 +61,7 @@ struct jg_ctx {
     int device;
     int slots;                           // workgroups of the GEMM kernel the device holds at once (2 per CU)
     hipStream_t stream;
+    void* static_ws;                     // device address of this device's static workspace (nullptr: device index too high)
     bool profiling;
     std::vector<hipEvent_t> pool;        // created on first jg_profile(ctx, 1)
     size_t pool_used;
@@ -167,9 +180,21 @@ int jg_init(jg_ctx** out, int device, void* hip_stream)
     if (!HIP_OK(hipGetDeviceProperties(&prop, device))) return JG_E_HIP;
     if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return JG_E_ARCH;
     if (!HIP_OK(hipSetDevice(device))) return JG_E_HIP;
+    void* static_ws = nullptr;
+    if (device < kMaxDevices) {
+        // this device's copy of the static workspace: looked up once, with the device current
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[device]) {
+            void* ptr = nullptr;
+            if (!HIP_OK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)))) return JG_E_HIP;
+            g_scratch_ptr[device] = ptr;
+        }
+        static_ws = g_scratch_ptr[device];
+    }
     jg_ctx* c = new (std::nothrow) jg_ctx();
     if (!c) return JG_E_HIP;
     c->device = device;
+    c->static_ws = static_ws;
     c->slots = 2 * prop.multiProcessorCount;
     c->stream = (hipStream_t)hip_stream;
     c->profiling = false;
@@ -935,6 +960,16 @@ int jg_linear_forward_ex(const jg_plan* plan, const float* const* x_sh, const fl
                          void* workspace, size_t workspace_bytes)
 {
     return forward_impl(plan, x_sh, w_sh, b_sh, r_sh, activation, y_sh, workspace, workspace_bytes, nullptr);
+}
+
+int jg_linear_forward_static(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                             const float* const* b_sh, float* const* y_sh)
+{
+    if (!plan || !plan->ctx) return JG_E_NULL;
+    if (plan->ws_bytes > kStaticScratchBytes) return JG_E_WORKSPACE;    // the layer does not fit the fixed array
+    void* ws = plan->ctx->static_ws;
+    if (!ws && plan->ws_bytes > 0) return JG_E_WORKSPACE;
+    return forward_impl(plan, x_sh, w_sh, b_sh, nullptr, JG_ACT_NONE, y_sh, ws, kStaticScratchBytes, nullptr);
 }
 
 // Backward of the transposed layer Y = X^T W (X [T x C], W [T x D], dY [C x D]); arguments already checked.
