@@ -58,6 +58,8 @@ def _load():
                                                ctypes.c_int]
         lib.oracle_linear_xtw.argtypes = [f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int, ctypes.c_int]
         lib.oracle_jigsaw_xtw.argtypes = [ctypes.c_int, f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int]
+        lib.oracle_linear_xw.argtypes = [f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int, ctypes.c_int]
+        lib.oracle_jigsaw_xw.argtypes = [ctypes.c_int, f32p, f32p, f32p, i64, i64, i64, f64p, ctypes.c_int]
         lib.oracle_gelu.argtypes = [f64p, i64, f64p]
         lib.oracle_round_bf16.argtypes = [f32p, i64, f32p]
         lib.oracle_layernorm.argtypes = [f32p, f32p, f32p, i64, i64, i64, ctypes.c_double, f64p, f64p, ctypes.c_int]
@@ -65,7 +67,8 @@ def _load():
                                    f64p, f64p, f64p, f64p, f64p, ctypes.c_int]
         for fn in (lib.oracle_linear, lib.oracle_linear_rows, lib.oracle_magnitude,
                    lib.oracle_entries, lib.oracle_jigsaw, lib.oracle_backward, lib.oracle_jigsaw_backward,
-                   lib.oracle_linear_xtw, lib.oracle_jigsaw_xtw, lib.oracle_gelu, lib.oracle_mlp):
+                   lib.oracle_linear_xtw, lib.oracle_jigsaw_xtw, lib.oracle_linear_xw, lib.oracle_jigsaw_xw,
+                   lib.oracle_gelu, lib.oracle_mlp):
             fn.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -254,6 +257,47 @@ def backward_xtw(X, W, dY, nthreads: int | None = None, absolute: bool = False):
     G = np.ascontiguousarray(dY, dtype=np.float32)
     f = magnitude if absolute else linear
     return f(W, G, None, nthreads), f(X, np.ascontiguousarray(G.T), None, nthreads)
+
+
+def linear_xw(X, W, b=None, nthreads: int | None = None, absolute: bool = False) -> np.ndarray:
+    """Y64 = X W + b by the definition (X [M x K], W [K x N], Y [M x N]: the permutation of Sec. 5 whose weights are
+    stored along the contracted index), in double; the magnitude |b| + |X| |W| if ``absolute``."""
+    X, xp = _f32(X)
+    W, wp = _f32(W)
+    b, bp = _opt_f32(b)
+    M, K = X.shape
+    K2, N = W.shape
+    assert K == K2 and (b is None or b.shape == (N,))
+    Y, yp = _f64_out((M, N))
+    _check(_load().oracle_linear_xw(xp, wp, bp, M, K, N, yp, int(absolute), nthreads or host_threads()), "linear_xw")
+    return Y
+
+
+def magnitude_xw(X, W, b=None, nthreads: int | None = None) -> np.ndarray:
+    return linear_xw(X, W, b, nthreads, absolute=True)
+
+
+def jigsaw_xw(ways: int, X, W, b=None, nthreads: int | None = None) -> np.ndarray:
+    """Y64 = X W + b obtained block by block (the decomposition is stated in the C source)."""
+    X, xp = _f32(X)
+    W, wp = _f32(W)
+    b, bp = _opt_f32(b)
+    M, K = X.shape
+    N = W.shape[1]
+    assert W.shape[0] == K
+    Y, yp = _f64_out((M, N))
+    _check(_load().oracle_jigsaw_xw(ways, xp, wp, bp, M, K, N, yp, nthreads or host_threads()), "jigsaw_xw")
+    return Y
+
+
+def backward_xw(X, W, dY, nthreads: int | None = None, absolute: bool = False):
+    """(dX64, dW64) of the layer Y = X W (X [M x K], W [K x N], dY [M x N]) by the definition:
+    dX[i][k] = sum_j dY[i][j] W[k][j]  (the form A B^T: the forward layer's routine)  and
+    dW[k][j] = sum_i X[i][k] dY[i][j]  (the form A^T B: the transposed layer's routine), in double
+    (magnitudes if ``absolute``)."""
+    G = np.ascontiguousarray(dY, dtype=np.float32)
+    f = magnitude if absolute else linear
+    return f(G, W, None, nthreads), linear_xtw(X, G, None, nthreads, absolute)
 
 
 def gelu(a) -> np.ndarray:

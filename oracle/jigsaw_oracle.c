@@ -45,6 +45,12 @@
  *                       never duplicated, two block products per rank, one partial
  *                       product handed to one peer) and is stated above the function.
  *
+ *  oracle_linear_xw   : the third permutation Sec. 5 names, Y = X W with the weights stored K x N, by
+ *                       definition; oracle_jigsaw_xw: the same block by block (decomposition stated
+ *                       above the function).  Pins (tests/test_oracle_xw_pins.py): integer brute force,
+ *                       oracle_linear on explicitly transposed weights, closed forms, the block-wise
+ *                       result against the definition, the adjoint identities of its gradients.
+ *
  *  oracle_gelu        : the activation between the two linear layers of a mixing MLP
  *                       (Sec. 3; Sec. 5 "Activation functions": point-wise, no
  *                       synchronisation).  The paper names GELU without a formula; this is
@@ -652,6 +658,95 @@ int oracle_jigsaw_xtw(int ways, const float* X, const float* W, const float* b, 
                 put_block(Y, D, a * Ch, Ch, c * Dh, Dh, kept);
             }
             free(kept); free(recv);
+            if (rc) goto done;
+            rc = ORACLE_E_MEM;
+        }
+    rc = ORACLE_OK;
+done:
+    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j) { free(Xb[i][j]); free(Wb[i][j]); }
+    return rc;
+}
+
+/* ------------------------------------------------------------------ */
+/* the third permutation  Y = X W + b  (weights stored K x N)           */
+/* ------------------------------------------------------------------ */
+typedef struct { const float *X, *W, *b; int64_t K, N; double* Y; int absolute; } xw_env;
+static void xw_row(int64_t i, void* p)
+{
+    const xw_env* e = (const xw_env*)p;
+    double* out = e->Y + i * e->N;
+    for (int64_t j = 0; j < e->N; ++j) {
+        const double bj = e->b ? (double)e->b[j] : 0.0;
+        out[j] = e->absolute ? fabs(bj) : bj;
+    }
+    for (int64_t k = 0; k < e->K; ++k) {
+        const double x = (double)e->X[i * e->K + k];
+        const float* w = e->W + k * e->N;
+        if (e->absolute)
+            for (int64_t j = 0; j < e->N; ++j) out[j] += fabs(x) * fabs((double)w[j]);
+        else
+            for (int64_t j = 0; j < e->N; ++j) out[j] += x * (double)w[j];
+    }
+}
+
+/* Sec. 5 names three permutations of the layer, X W^T, X W and X^T W.  This one by its definition,
+ *     Y[i][j] = b[j] + sum_{k=0}^{K-1} X[i][k] * W[k][j],   X [M x K], W [K x N], Y [M x N],
+ * every product and sum in double, k ascending (absolute != 0: the same sum of absolute values). */
+int oracle_linear_xw(const float* X, const float* W, const float* b, int64_t M, int64_t K, int64_t N,
+                     double* Y, int absolute, int nthreads)
+{
+    if (!X || !W || !Y || M < 0 || K < 0 || N < 0) return ORACLE_E_ARG;
+    xw_env e = {X, W, b, K, N, Y, absolute};
+    return for_rows(0, M, nthreads, xw_row, &e);
+}
+
+/* Block decomposition of Y = X W.  The paper prints no equations for this permutation; it is the form of the
+ * backward product dX = dY W of Sec. 4.1 (activations times weights stored along the contracted index), and
+ * the blocks follow that pass and the rules of Sec. 4: every tensor split on its last dimension (2-way) or
+ * in 2 x 2 blocks with block (i, j) on rank 2 i + j (4-way), nothing duplicated, two block products per rank.
+ * 2-way: X_r = X[:, r-th half of K], W_r = W[:, r-th half of N] (all K rows), Y_r = Y[:, r-th half of N]
+ *     Y_r = X_r W_(r,r) + X_(1-r) W_(1-r,r),   W_(k,c) = rows k-th half of K, columns c-th half of N:
+ * rank r holds both weight blocks of its column half and receives the peer's activation block.
+ * 4-way:  Y_(i,j) = X_(i,j) W_(j,j) + X_(i,1-j) W_(1-j,j):  rank (i, j) multiplies its own activation block
+ * with W_(j,j) (its own block if i = j, else its column neighbour's) and the block X_(i,1-j) of its row
+ * neighbour with W_(1-j,j) (its own if i = 1 - j, else its column neighbour's): one activation block and one
+ * weight block come from peers, both products stay.  Bias: b[j-th half] on the owner of the block. */
+int oracle_jigsaw_xw(int ways, const float* X, const float* W, const float* b, int64_t M, int64_t K,
+                     int64_t N, double* Y, int nthreads)
+{
+    if (!X || !W || !Y || M < 0 || K < 0 || N < 0) return ORACLE_E_ARG;
+    if (ways == 1) return oracle_linear_xw(X, W, b, M, K, N, Y, 0, nthreads);
+    if (ways != 2 && ways != 4) return ORACLE_E_ARG;
+    if ((K % 2) || (N % 2) || (ways == 4 && (M % 2))) return ORACLE_E_ARG;
+    const int rh = ways == 4 ? 2 : 1;                 /* row halves of X and Y */
+    const int64_t Mb = M / rh, Kh = K / 2, Nh = N / 2;
+    int rc = ORACLE_E_MEM;
+    /* Xb[i][k] (Mb x Kh): on rank (i, k);  Wb[k][c] (Kh x Nh): 4-way on rank (k, c), 2-way both on rank c */
+    float *Xb[2][2] = {{0}}, *Wb[2][2] = {{0}};
+    for (int i = 0; i < rh; ++i)
+        for (int k = 0; k < 2; ++k) {
+            Xb[i][k] = take_block(X, K, i * Mb, Mb, k * Kh, Kh);
+            if (!Xb[i][k]) goto done;
+        }
+    for (int k = 0; k < 2; ++k)
+        for (int c = 0; c < 2; ++c) {
+            Wb[k][c] = take_block(W, N, k * Kh, Kh, c * Nh, Nh);
+            if (!Wb[k][c]) goto done;
+        }
+    for (int i = 0; i < rh; ++i)
+        for (int j = 0; j < 2; ++j) {     /* the owner of Y block (i, j): rank (i, j), 2-way rank j */
+            double* acc = new_partial(Mb, Nh);
+            if (!acc) goto done;
+            rc = add_nn(Xb[i][j], Wb[j][j], Mb, Kh, Nh, acc, nthreads);              /* its own activation block */
+            if (!rc) rc = add_nn(Xb[i][1 - j], Wb[1 - j][j], Mb, Kh, Nh, acc, nthreads);   /* the received one */
+            if (!rc) {
+                if (b)
+                    for (int64_t r = 0; r < Mb; ++r)
+                        for (int64_t q = 0; q < Nh; ++q) acc[r * Nh + q] += (double)b[j * Nh + q];
+                put_block(Y, N, i * Mb, Mb, j * Nh, Nh, acc);
+            }
+            free(acc);
             if (rc) goto done;
             rc = ORACLE_E_MEM;
         }
