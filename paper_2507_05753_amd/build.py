@@ -12,7 +12,9 @@ LIB = os.path.join(HERE, "libjigsaw.so")
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
-    # packed FP32 VALU ops are kept off for every kernel of this library
+    # No packed FP32 VALU instructions (v_pk_fma_f32 and friends) in any kernel of this library.  The flag acts
+    # on the gfx950 pass (a float2 multiply-add compiles to two scalar-lane FMAs with it, to one v_pk_fma_f32
+    # without); the x86 host pass does not know the feature and says so in a warning.
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
 

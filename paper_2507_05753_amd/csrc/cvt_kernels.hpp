@@ -18,7 +18,7 @@ struct CvtBlock {
     const float* src;     // rows x cols, leading dimension ld_src (floats)
     uint16_t* dst;        // rows of planes * plane bfloat16: [hi(0..cols) pad | lo(0..cols) pad]
     int64_t ld_src;
-    uint16_t* dst_rows;   // cvt_bf16_transposed only, or nullptr: the untransposed rounding as well (rows of
+    uint16_t* dst_rows = nullptr;   // cvt_bf16_transposed only, or nullptr: the untransposed rounding as well (rows of
                           // planes * plane_rows), from the same read of the source
 };
 

@@ -57,9 +57,7 @@ constexpr int HB_WIDE_BK = 64;                            // one plane: 128 byte
 constexpr int HB_THREADS = 256;
 constexpr int HB_OPERAND_BYTES = HB_BM * HB_BK * 2;       // one 32 k slab of one plane = 16 KiB (BM == BN)
 constexpr int HB_BAND_ROWS = 4;                           // row-tiles per band of the tile order
-#ifndef HB_PREFETCH_SLABS
-#define HB_PREFETCH_SLABS 1                               // L2 prefetch distance ahead of the transfers, in slabs
-#endif
+constexpr int HB_PREFETCH_SLABS = 1;                      // L2 prefetch distance ahead of the transfers, in slabs
 
 struct HbGroup {
     GemmProblem p[kMaxGroup];   // A, B point at bfloat16 data; lda, ldb count 4-byte units (bfloat16 pairs)
@@ -111,6 +109,10 @@ typedef int hb_int4 __attribute__((ext_vector_type(4)));
 // later LDS read wait until ALL transfers in flight have landed, which would undo the prefetch
 // distance; here the kernel's own vmcnt waits say which slab must have arrived.  M0 carries the LDS
 // address and is declared clobbered.
+// (The compiler reserves M0 for itself and warns about seeing it in a clobber list; it does not keep a value in
+// M0 across a volatile statement, and naming it states what the statement does.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void hb_transfer(const hb_int4& rsrc, unsigned lds_base, int voffset, int soffset)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
@@ -129,6 +131,7 @@ __device__ __forceinline__ void hb_prefetch(const hb_int4& rsrc, unsigned lds_du
                  : "s"(lds_dump), "v"(voffset), "s"(rsrc), "s"(soffset)
                  : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // One operand's slabs, global -> LDS, ROW bytes (64 or 128) of every tile row per slab.  ROW / 16 lanes share
 // a row, so a wavefront's transfer covers 1024 / ROW rows and the workgroup's four 4096 / ROW; transfer t of a
@@ -325,9 +328,6 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
 // grid: kNumXcd * per_xcd workgroups; consecutive ids land on different XCDs, so the id is folded
 // into a per-XCD contiguous range of tiles, walked column-major inside bands of 4 row-tiles: the 32
 // tiles an XCD has in flight form a 4 x 8 block that shares 4 A panels and 8 B panels in its L2.
-// PARTS (measurement builds only; the library instantiates 3, anything else gives wrong results): bit 0 = issue the
-// slab transfers, bit 1 = multiply, bit 3 = skip the epilogue.  It is how the kernel's parts were timed one by one.
-template <int PARTS = 3>
 __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
 {
     constexpr int UNIT = HB_BM * HB_WIDE_BK * 2;            // one operand's slab: 256 rows of 128 bytes = 32 KiB
@@ -419,10 +419,8 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
         hb_prefetch(load_b.rsrc, dump_lds, live ? pf_b : kOutOfBuffer, col);
         ++pf_kt;
     };
-    if (PARTS & 1) {
 #pragma unroll
-        for (int d = 0; d < PF; ++d) prefetch();
-    }
+    for (int d = 0; d < PF; ++d) prefetch();
 
     const bool interior = tc.m0 + HB_BM <= M && tc.n0 + HB_BN <= N;
     floatx16 acc[4][4];
@@ -467,13 +465,12 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    if (PARTS & 2)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.a[s][i], f0.b[s][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.a[s][i], f0.b[s][j], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         // Slab it + 1 was requested a slab ago and only two prefetches have been issued since; this wavefront's
         // reads of slab `it` are complete (its second half sits in registers).  Behind the barrier slab it + 1 may
         // be read by all and slab it's buffer refilled.
-        if (PARTS & 1) JG_WAIT_VMCNT(PF > 0 ? 2 : 0);
+        JG_WAIT_VMCNT(PF > 0 ? 2 : 0);
         __builtin_amdgcn_s_waitcnt(0xC07F);    // lgkmcnt(0) only
         __syncthreads();
         read_half(nxt, 0, f0);                 // (after the last slab: a surplus copy, read but not used)
@@ -487,22 +484,19 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        if (PARTS & 2)
-                            acc[i][j] =
-                                __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.a[s][i], f1.b[s][j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.a[s][i], f1.b[s][j], acc[i][j], 0, 0, 0);
                         const int idx = s * 16 + i * 4 + j;
                         // slab it + 2, one transfer after every second MFMA
-                        if ((PARTS & 1) && (idx & 1) == 0) issue(idx >> 1, kt, stage);
+                        if ((idx & 1) == 0) issue(idx >> 1, kt, stage);
                         __builtin_amdgcn_sched_barrier(0);
                     }
-            if ((PARTS & 1) && PF > 0) prefetch();
+            if (PF > 0) prefetch();
             advance();
         }
     }
     JG_WAIT_VMCNT(0);       // the surplus transfers have landed ...
     __syncthreads();        // ... and nobody reads a slab any more: the buffers become the waves' staging blocks
     float* shuffle = reinterpret_cast<float*>(slab + wave * (32 * HB_SHUFFLE_LD * 4));
-    if ((PARTS & 8) && acc[0][0][0] != 12345.f) return;
     if (run < 0) {
         hb_store_tile(P, M, N, tc.m0, tc.n0, wm, wn, lr, lk, interior, acc, g.act, shuffle, g.c16[tc.prob], g.ld16,
                       g.planes16 == 2 ? g.plane16 : 0);
@@ -525,8 +519,6 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
 // to an already large sum the small products lose their low bits at every step), the small products here
 // meet a sum that has already grown, as in any single pass; the rounding walk on same-sign data is that of
 // 3 K / 16 steps (see the tolerance notes of the tests).
-// PARTS: as for gemm_bf16_nt (measurement builds only).
-template <int PARTS = 3>
 __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
 {
     constexpr int STAGE = 4 * HB_OPERAND_BYTES;              // 64 KiB
@@ -647,16 +639,14 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                if (PARTS & 2) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.ah[i], f0.bl[j], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.al[i], f0.bh[j], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.ah[i], f0.bh[j], acc[i][j], 0, 0, 0);
-                }
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.ah[i], f0.bl[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.al[i], f0.bh[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.ah[i], f0.bh[j], acc[i][j], 0, 0, 0);
             }
         __builtin_amdgcn_sched_barrier(0);
         // Slab it + 1 was requested a slab ago and only two prefetches have been issued since; this wavefront's
         // reads of slab `it` are complete.  Behind the barrier slab it + 1 may be read and slab it's buffer refilled.
-        if (PARTS & 1) JG_WAIT_VMCNT(PF > 0 ? 2 : 0);
+        JG_WAIT_VMCNT(PF > 0 ? 2 : 0);
         __builtin_amdgcn_s_waitcnt(0xC07F);    // lgkmcnt(0) only
         __syncthreads();
         read_frags(nxt, 0, f0);                // (after the last slab: a surplus copy, read but not used)
@@ -668,22 +658,19 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    if (PARTS & 2) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.ah[i], f1.bl[j], acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.al[i], f1.bh[j], acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.ah[i], f1.bh[j], acc[i][j], 0, 0, 0);
-                    }
-                    if (PARTS & 1) issue(i * 4 + j, kt, stage);        // slab it + 2, one transfer after every third MFMA
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.ah[i], f1.bl[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.al[i], f1.bh[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.ah[i], f1.bh[j], acc[i][j], 0, 0, 0);
+                    issue(i * 4 + j, kt, stage);        // slab it + 2, one transfer after every third MFMA
                     __builtin_amdgcn_sched_barrier(0);
                 }
-            if ((PARTS & 1) && PF > 0) prefetch();
+            if (PF > 0) prefetch();
             advance();
         }
     }
     JG_WAIT_VMCNT(0);       // the surplus transfers have landed ...
     __syncthreads();        // ... and nobody reads a slab any more: the buffers become the waves' staging blocks
     float* shuffle = reinterpret_cast<float*>(slab + wave * (32 * HB_SHUFFLE_LD * 4));
-    if ((PARTS & 8) && acc[0][0][0] != 12345.f) return;
     if (run < 0) {
         hb_store_tile(P, M, N, tc.m0, tc.n0, wm, wn, lr, lk, interior, acc, g.act, shuffle, g.c16[tc.prob], g.ld16,
                       g.planes16 == 2 ? g.plane16 : 0);
@@ -829,8 +816,8 @@ inline hipError_t launch_gemm_bf16_group(const GemmGroup& src, int terms, int pl
     *needs_join = false;
     const hipError_t e = make_bf16_group(src, terms, plane, cus, scratch, scratch_bytes, g, copy16);
     if (e != hipSuccess) return e;
-    if (terms == 3) hipLaunchKernelGGL(gemm_bf16x3_nt<3>, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);
-    else hipLaunchKernelGGL(gemm_bf16_nt<3>, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);
+    if (terms == 3) hipLaunchKernelGGL(gemm_bf16x3_nt, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);
+    else hipLaunchKernelGGL(gemm_bf16_nt, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);
     *needs_join = g.parts > 0;
     return hipGetLastError();
 }

@@ -85,8 +85,8 @@ struct GemmProblem {
     const float* addend;  // M x N (ldadd) added in the epilogue, or nullptr
     const float* bias;    // length N added in the epilogue, or nullptr
     int lda, ldb, ldc, ldadd;
-    const float* residual;   // M x N (ldres) added after the activation, or nullptr
-    int ldres;
+    const float* residual = nullptr;   // M x N (ldres) added after the activation, or nullptr
+    int ldres = 0;
 };
 
 struct GemmGroup {
