@@ -31,6 +31,15 @@
  *              rank (i, 1-j) (a term of Y block (1-j, j)); it keeps the term of the
  *              block it owns (row half i) and hands the other to rank (1-i, j).
  *
+ * The third permutation Sec. 5 names, Y = X W (+ b) with the weights stored along the contracted index
+ * (X: M x K, W: K x N), selected by op = JG_OP_XW.  It is the form of the backward product dX = dY W of
+ * Sec. 4.1 and takes that pass's blocks: all tensors split on their last dimension (2-way: X_r = X[:, r-th half
+ * of K], W_r = W[:, r-th half of N] with all K rows, Y_r = Y[:, r-th half of N]) or 2 x 2 (4-way), and
+ *     Y_(i,j) = X_(i,j) W_(j,j) + X_(i,1-j) W_(1-j,j)      (W_(k,c): rows k-th half of K, columns c-th half of N),
+ * both products formed by the block's owner, which gets the activation block of its row neighbour and (4-way)
+ * the weight block of its column neighbour.  Its own gradients are the other two permutations (dX = dY W^T,
+ * dW = X^T dY), which jg_linear_backward runs on the same shards.
+ *
  * All n ranks of one layer are "virtual ranks" resident on the one GPU: each has its
  * own shard buffers, and a hand-off to a peer is a store into the peer's buffer.
  *
@@ -75,7 +84,8 @@ typedef enum jg_status {
 } jg_status;
 
 enum { JG_OP_XWT = 0,                                    /* Y = X W^T (Sec. 4)          */
-       JG_OP_XTW = 1 };                                  /* Y = X^T W (Sec. 5) */
+       JG_OP_XTW = 1,                                    /* Y = X^T W (Sec. 5) */
+       JG_OP_XW = 2 };                                   /* Y = X W   (Sec. 5; FP32 only) */
 enum { JG_F32 = 0,       /* the paper's uniform single precision (Sec. 6.1)                          */
        JG_BF16 = 1,      /* reduced precision (Sec. 6.1 trains in a mixed precision whose matrix units
                             round FP32 operands to a short mantissa and sum in FP32; this chip has no such
@@ -96,9 +106,10 @@ enum { JG_T_X = 0, JG_T_W = 1, JG_T_B = 2, JG_T_Y = 3,   /* tensor selector of j
 
 typedef struct jg_linear_desc {
     int64_t M, K, N;     /* global sizes: Y is M x N and K is contracted.  JG_OP_XWT: X is
-                            M x K, W is N x K.  JG_OP_XTW: X is K x M, W is K x N.      */
+                            M x K, W is N x K.  JG_OP_XTW: X is K x M, W is K x N.
+                            JG_OP_XW: X is M x K, W is K x N.                           */
     int32_t ways;        /* 1, 2 or 4                                                   */
-    int32_t op;          /* JG_OP_XWT or JG_OP_XTW                                      */
+    int32_t op;          /* JG_OP_XWT, JG_OP_XTW or JG_OP_XW                            */
     int32_t dtype;       /* JG_F32, or JG_BF16 / JG_BF16X3 (forward; backward of JG_OP_XWT, which
                             reads FP32 shards: see jg_linear_backward).  The X and W shards
                             are then bfloat16 arrays of JG_Q_X_SHARD_BYTES /
@@ -136,9 +147,9 @@ typedef enum jg_query {
     JG_Q_WORKSPACE_BYTES = 0,    /* device bytes jg_linear_forward needs (rank ignored)        */
     JG_Q_FLOPS_TOTAL = 1,        /* 2 M K N: matmul dimensions only (Sec. 6.3 work model)      */
     JG_Q_FLOPS_RANK = 2,         /* one rank's two block products                              */
-    JG_Q_HBM_BYTES_ALGO = 3,     /* 4(MK + NK + MN), plus 8 MN where partial products are handed
-                                    over (each written once and read once): ways >= 2, for
-                                    JG_OP_XTW ways = 4 only                                    */
+    JG_Q_HBM_BYTES_ALGO = 3,     /* 4(MK + NK + MN), plus 8 MN where a block's first product passes
+                                    through a partial (written once and read once): ways >= 2,
+                                    for JG_OP_XTW ways = 4 only                                */
     JG_Q_EXCHANGE_BYTES_RANK = 4,/* bytes a rank hands to its peers per forward                */
     JG_Q_X_ROWS = 5, JG_Q_X_COLS = 6,   /* shape of rank's X shard                             */
     JG_Q_W_ROWS = 7, JG_Q_W_COLS = 8,   /* shape of rank's W shard                             */
@@ -182,11 +193,12 @@ typedef enum jg_kernel {         /* kernel classes for jg_profile_read */
  * Errors: JG_E_NULL (out), JG_E_HIP (bad device), JG_E_ARCH (not gfx950). */
 int jg_init(jg_ctx** out, int device, void* hip_stream);
 
-/* free.  Releases the context (not its plans, not the stream). */
+/* free.  Releases the context (not the stream).  Plans made with it that are still alive are detached: they
+ * keep answering jg_plan_query, their data calls return JG_E_NULL, and jg_plan_destroy still releases them. */
 void jg_free(jg_ctx* ctx);
 
 /* build.  Validates `desc` and fixes the block decomposition of Sec. 4.1 / 4.2 for
- * these sizes.  JG_OP_XWT: 2-way needs even K and N; JG_OP_XTW: 2-way needs even M and N
+ * these sizes.  JG_OP_XWT and JG_OP_XW: 2-way needs even K and N; JG_OP_XTW: 2-way needs even M and N
  * (the dimensions that are split); 4-way needs even M, K and N for both (the paper's
  * loader zero-pads to make partitions equal, Sec. 5 "Data loading": padding is the
  * caller's job).  Size limits: each of M, K, N below 2^31 - 1024, and for each pair
@@ -214,7 +226,7 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out);
  *           xr x xc shards): the activations jg_mlp_forward / jg_mixing_forward / jg_layernorm_forward take.
  * For a JG_OP_XTW plan the global X is K x M (ld >= M), W is K x N (ld >= N) and Y is
  * M x N; all three are partitioned the same way (2-way: column halves; 4-way: block
- * (r/2, r%2)) and b as above.
+ * (r/2, r%2)) and b as above.  For a JG_OP_XW plan X is M x K, W is K x N (ld >= N), partitioned the same way.
  * `global` is a device pointer; `shards` is a host array of `ways` device pointers,
  * each with room for the rank's shard.  Pure data movement: bit-exact.
  * Reduced-precision plans (JG_BF16, JG_BF16X3): `global` is FP32 all the same; X and W shards are
@@ -262,6 +274,10 @@ int jg_gather_patches(const jg_plan* plan, const float* const* y_shards, float* 
  * b_sh: the same for the bias slices, required iff has_bias.  `workspace` is a
  * 256-byte-aligned device buffer of at least JG_Q_WORKSPACE_BYTES bytes (may be NULL
  * when that is 0); its contents on entry are irrelevant and are overwritten.
+ * JG_OP_XW plans: (JG_WEIGHTS_COPY) copy each rank's incoming activation block and, 4-way, weight block;
+ * launch 1: every rank's product of the received activation block, into a partial of its own in the workspace;
+ * launch 2: the product of its own activation block on top of it, plus the bias (or, JG_COMBINE_SEPARATE,
+ * written out and combined).  The weight blocks are read along their row stride.
  * JG_F32 plans: FP32 storage, FP32 matrix-core multiply-accumulate.  JG_BF16 / JG_BF16X3 plans
  * (JG_OP_XWT only): x_sh and w_sh point at the bfloat16 shards jg_shard wrote, the block products
  * run on the bfloat16 matrix cores with FP32 sums (JG_BF16X3: three products per block for each 16 k,
@@ -402,6 +418,8 @@ int jg_linear_forward_static(const jg_plan* plan, const float* const* x_sh, cons
  * X_(i,a), W_(i,j), dY_(a,j) the plan's blocks (row half, column half; 2-way: one row range, and dY_r stacks
  * dY_(0,r) over dY_(1,r)):   dX_(i,a) = sum_j W_(i,j) dY_(a,j)^T,   dW_(i,j) = sum_a X_(i,a) dY_(a,j),
  * two launches each for ways >= 2 (the first term into a partial in the workspace, the second on top of it).
+ * A JG_OP_XW plan (Y = X W): dX = dY W^T and dW = X^T dY, the forward passes of the other two permutations on
+ * (dY, W) and (X, dY) with their launches and workspace (JG_Q_BACKWARD_WORKSPACE_BYTES covers both).
  * A reduced-precision JG_OP_XWT plan (Sec. 6.1: mixed precision): x_sh and w_sh are FP32 shards (JG_T_X_F32,
  * JG_T_W_F32: the copies a mixed-precision training step keeps), dy_sh, dx_sh and dw_sh FP32 as always; every operand
  * of every block product is rounded to bfloat16 (JG_BF16X3: split) into the workspace, in the layout the bfloat16

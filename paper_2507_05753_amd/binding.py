@@ -29,7 +29,7 @@ _lib = ctypes.CDLL(LIB_PATH)
 JG_OK = 0
 JG_E_NULL, JG_E_SHAPE, JG_E_WAYS, JG_E_DTYPE = -1, -2, -3, -4
 JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP, JG_E_ARCH = -5, -6, -7, -8
-JG_OP_XWT, JG_OP_XTW = 0, 1
+JG_OP_XWT, JG_OP_XTW, JG_OP_XW = 0, 1, 2
 JG_F32, JG_BF16, JG_BF16X3 = 0, 1, 2
 JG_COMBINE_FUSED, JG_COMBINE_SEPARATE = 0, 1
 JG_WEIGHTS_COPY, JG_WEIGHTS_DIRECT = 0, 1

@@ -66,6 +66,7 @@ struct jg_ctx {
     std::vector<hipEvent_t> pool;        // created on first jg_profile(ctx, 1)
     size_t pool_used;
     std::vector<TimedLaunch> timed;
+    std::vector<jg_plan*> plans;         // the live plans made with this context: jg_free detaches them
 };
 
 struct jg_plan {
@@ -93,6 +94,12 @@ struct jg_plan {
     // reduced precision, as a layer of an MLP chain: the FP32 input activations are converted into ways shards of
     // chain_shard_bytes each, behind the layer's own workspace
     size_t chain_shard_bytes, chain_bytes;
+    // JG_OP_XW: the activation block a rank receives (copy mode), next to the weight block of off_wrecv
+    size_t xblk_bytes, off_xrecv;
+    // JG_OP_XW: its gradients are the other two permutations, dX = dY W^T (an X W^T layer on dY and W) and
+    // dW = X^T dY (an X^T W layer on X and dY); the plans of those two layers, owned by this plan
+    jg_plan* bw_dx_plan;
+    jg_plan* bw_dw_plan;
 };
 
 namespace {
@@ -208,6 +215,7 @@ void jg_free(jg_ctx* ctx)
     if (!ctx) return;
     (void)hipSetDevice(ctx->device);
     for (hipEvent_t e : ctx->pool) (void)hipEventDestroy(e);
+    for (jg_plan* p : ctx->plans) p->ctx = nullptr;     // surviving plans answer queries only from now on
     delete ctx;
 }
 
@@ -322,9 +330,10 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     if (!desc) return JG_E_NULL;
     const jg_linear_desc& d = *desc;
     if (d.ways != 1 && d.ways != 2 && d.ways != 4) return JG_E_WAYS;
-    if (d.op != JG_OP_XWT && d.op != JG_OP_XTW) return JG_E_DTYPE;
+    if (d.op != JG_OP_XWT && d.op != JG_OP_XTW && d.op != JG_OP_XW) return JG_E_DTYPE;
     if (d.dtype != JG_F32 && d.dtype != JG_BF16 && d.dtype != JG_BF16X3) return JG_E_DTYPE;
     const bool reduced = d.dtype != JG_F32;
+    if (d.op == JG_OP_XW && reduced) return JG_E_DTYPE;     // the X W permutation exists in FP32 only
     if (d.combine != JG_COMBINE_FUSED && d.combine != JG_COMBINE_SEPARATE) return JG_E_DTYPE;
     if (d.weights != JG_WEIGHTS_COPY && d.weights != JG_WEIGHTS_DIRECT) return JG_E_DTYPE;
     if (d.has_bias != 0 && d.has_bias != 1) return JG_E_DTYPE;
@@ -350,7 +359,17 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     if (!p) return JG_E_HIP;
     p->ctx = ctx;
     p->d = d;
-    if (xtw) {
+    p->xblk_bytes = p->off_xrecv = 0;
+    p->bw_dx_plan = p->bw_dw_plan = nullptr;
+    const bool xw = d.op == JG_OP_XW;
+    if (xw) {
+        // X is M x K, W is K x N, Y is M x N; all split on the last dimension (2-way) or 2 x 2; in the 2-way
+        // form a rank holds all K rows of its column half of W
+        const int64_t rows = d.ways == 4 ? 2 : 1, cols = d.ways >= 2 ? 2 : 1;
+        p->xr = d.M / rows; p->xc = d.K / cols;
+        p->wr = d.ways == 4 ? d.K / 2 : d.K; p->wc = d.N / cols;
+        p->yr = d.M / rows; p->yc = d.N / cols;
+    } else if (xtw) {
         // X is K x M, W is K x N, Y is M x N; all split on the last dimension (2-way) or 2 x 2
         const int64_t rows = d.ways == 4 ? 2 : 1, cols = d.ways >= 2 ? 2 : 1;
         p->xr = d.K / rows; p->xc = d.M / cols;
@@ -380,8 +399,15 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     // partial products are handed over wherever the contraction is split across ranks; an operand
     // block comes from a peer in the 4-way X W^T layer (a weight block) and in the 2- and 4-way
     // X^T W layer (an activation block)
+    // (X W: both products of an output block are formed by its owner, the first into a partial of its own; the
+    // activation block comes from the row neighbour, 4-way also a weight block from the column neighbour)
     const bool partials = xtw ? d.ways == 4 : d.ways >= 2;
     const bool operand_blocks = (xtw ? d.ways >= 2 : d.ways == 4) && d.weights == JG_WEIGHTS_COPY;
+    if (xw && d.ways >= 2 && d.weights == JG_WEIGHTS_COPY) {
+        p->xblk_bytes = round_up((size_t)p->xr * (size_t)p->xc * sizeof(float), kWsAlign);
+        p->off_xrecv = off;
+        off += p->xblk_bytes * d.ways;
+    }
     if (partials) {
         p->part_bytes = round_up((size_t)p->yr * (size_t)p->yc * sizeof(float), kWsAlign);
         p->off_send = off;
@@ -392,8 +418,9 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
         }
     }
     if (operand_blocks) {
-        const size_t elems = xtw ? (reduced ? (size_t)p->xc * (size_t)p->xcp : (size_t)p->xr * (size_t)p->xc)
-                                 : (size_t)p->wr * (size_t)p->xcp;
+        const size_t elems = xtw  ? (reduced ? (size_t)p->xc * (size_t)p->xcp : (size_t)p->xr * (size_t)p->xc)
+                             : xw ? (size_t)p->wr * (size_t)p->wc
+                                  : (size_t)p->wr * (size_t)p->xcp;
         p->wblk_bytes = round_up(elems * sizeof(float), kWsAlign);
         p->off_wrecv = off;
         off += p->wblk_bytes * d.ways;
@@ -443,11 +470,42 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     p->ws_bytes = round_up(p->ws_bytes, kWsAlign);
     p->chain_shard_bytes = reduced ? round_up(4 * (size_t)(xtw ? p->xc : p->xr) * (size_t)p->xcp, kWsAlign) : 0;
     p->chain_bytes = p->chain_shard_bytes * d.ways;
+    if (xw) {
+        jg_linear_desc dx = d, dw = d;
+        dx.op = JG_OP_XWT; dx.M = d.M; dx.K = d.N; dx.N = d.K; dx.has_bias = 0; dx.combine = JG_COMBINE_FUSED;
+        dw.op = JG_OP_XTW; dw.K = d.M; dw.M = d.K; dw.N = d.N; dw.has_bias = 0; dw.combine = JG_COMBINE_FUSED;
+        int rc = jg_plan_create(ctx, &dx, &p->bw_dx_plan);
+        if (rc == JG_OK) rc = jg_plan_create(ctx, &dw, &p->bw_dw_plan);
+        if (rc != JG_OK) {
+            jg_plan_destroy(p);
+            return rc;
+        }
+        p->bw_ws_bytes = p->bw_dx_plan->ws_bytes > p->bw_dw_plan->ws_bytes ? p->bw_dx_plan->ws_bytes
+                                                                           : p->bw_dw_plan->ws_bytes;
+        p->bw_tail_bytes = p->bw_dx_plan->tail_bytes > p->bw_dw_plan->tail_bytes ? p->bw_dx_plan->tail_bytes
+                                                                                 : p->bw_dw_plan->tail_bytes;
+    }
+    if (ctx) ctx->plans.push_back(p);
     *out = p;
     return JG_OK;
 }
 
-void jg_plan_destroy(jg_plan* plan) { delete plan; }
+void jg_plan_destroy(jg_plan* plan)
+{
+    if (!plan) return;
+    jg_plan_destroy(plan->bw_dx_plan);
+    jg_plan_destroy(plan->bw_dw_plan);
+    if (plan->ctx) {
+        std::vector<jg_plan*>& live = plan->ctx->plans;
+        for (size_t i = 0; i < live.size(); ++i)
+            if (live[i] == plan) {
+                live[i] = live.back();
+                live.pop_back();
+                break;
+            }
+    }
+    delete plan;
+}
 
 int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
 {
@@ -469,6 +527,14 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
         *out = eb * (M * K + N * K) + 4 * M * N + ((xtw ? d.ways == 4 : d.ways >= 2) ? 8 * M * N : 0);
         break;
     case JG_Q_EXCHANGE_BYTES_RANK:
+        if (d.op == JG_OP_XW) {
+            // 2-way: one M x K/2 activation block.  4-way: one M/2 x K/2 activation block and one K/2 x N/2
+            // weight block.
+            *out = d.ways == 1 ? 0
+                 : d.ways == 2 ? 4 * M * (K / 2)
+                               : 4 * ((M / 2) * (K / 2) + (K / 2) * (N / 2));
+            break;
+        }
         if (xtw) {
             // 2-way: one K x M/2 activation block.  4-way: one M/2 x N/2 partial and one K/2 x M/2
             // activation block.
@@ -499,7 +565,9 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     case JG_Q_TAIL_SCRATCH_BYTES: *out = (int64_t)plan->tail_bytes; break;
     case JG_Q_BACKWARD_TAIL_SCRATCH_BYTES: *out = (int64_t)plan->bw_tail_bytes; break;
     case JG_Q_X_SHARD_BYTES: *out = 4 * ((xtw && reduced) ? plan->xc : plan->xr) * plan->xcp; break;
-    case JG_Q_W_SHARD_BYTES: *out = 4 * ((xtw && reduced) ? plan->wc : plan->wr) * plan->xcp; break;
+    case JG_Q_W_SHARD_BYTES:
+        *out = d.op == JG_OP_XW ? 4 * plan->wr * plan->wc : 4 * ((xtw && reduced) ? plan->wc : plan->wr) * plan->xcp;
+        break;
     case JG_Q_CHAIN_WORKSPACE_BYTES: *out = (int64_t)(plan->ws_bytes + plan->chain_bytes); break;
     case JG_Q_NORM_BACKWARD_WORKSPACE_BYTES:
         *out = (int64_t)(round_up(16 * (size_t)plan->xr, kWsAlign) * d.ways);
@@ -524,7 +592,7 @@ static int partition_of(const jg_plan* plan, int which, Partition* out)
     case JG_T_X:
     case JG_T_X_F32: *out = {plan->xr, plan->xc, plan->d.op == JG_OP_XTW ? plan->d.M : plan->d.K}; return JG_OK;
     case JG_T_W:
-    case JG_T_W_F32: *out = {plan->wr, plan->wc, plan->d.op == JG_OP_XTW ? plan->d.N : plan->d.K}; return JG_OK;
+    case JG_T_W_F32: *out = {plan->wr, plan->wc, plan->d.op == JG_OP_XWT ? plan->d.K : plan->d.N}; return JG_OK;
     case JG_T_Y: *out = {plan->yr, plan->yc, plan->d.N}; return JG_OK;
     default: return JG_E_DTYPE;
     }
@@ -829,6 +897,114 @@ static int forward_xtw(const jg_plan* plan, const float* const* x_sh, const floa
     return HIP_OK(jg::launch_combine_group(cb, c->stream)) ? JG_OK : JG_E_HIP;
 }
 
+// Forward pass of the third permutation Y = X W (+ b), weights stored K x N; arguments already checked.  It is
+// the form of the backward product dX = dY W (Sec. 4.1) and takes that pass's blocks: every output block is
+//     Y_(i,j) = X_(i,j) W_(j,j) + X_(i,1-j) W_(1-j,j),
+// both products formed by the block's owner - the second from the activation block of its row neighbour, and
+// whichever weight block is not its own from its column neighbour (2-way: a rank holds both weight blocks of
+// its column half).  The first product goes to a partial in the workspace, the second is accumulated on top.
+// A = an X block (K-contiguous), B = a W block read along its row stride.
+static int forward_xw(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
+                      const float* const* b_sh, const float* const* r_sh, int act, float* const* y_sh, char* ws)
+{
+    const jg_linear_desc& d = plan->d;
+    const int ways = d.ways;
+    jg_ctx* c = plan->ctx;
+    auto bias_of = [&](int r) -> const float* { return d.has_bias ? b_sh[r] : nullptr; };
+    auto res_of = [&](int r) -> const float* { return r_sh ? r_sh[r] : nullptr; };
+    char* tail = plan->tail_bytes ? ws + plan->off_tail : nullptr;
+    const int ldx = (int)plan->xc, ldw = (int)plan->wc, ldy = (int)plan->yc;
+
+    jg::GemmGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.M = (int)plan->yr;
+    g.N = (int)plan->yc;
+    g.K = (int)plan->xc;
+    if (ways == 1) {
+        g.nprob = 1;
+        g.act = act;
+        g.p[0] = {x_sh[0], w_sh[0], y_sh[0], nullptr, bias_of(0), ldx, ldw, ldy, 0, res_of(0), ldy};
+        return run_gemm(plan, g, jg::kGemmNN, JG_KERNEL_GEMM, tail, plan->tail_bytes) ? JG_OK : JG_E_HIP;
+    }
+    // what a rank gets from its peers: the activation block of its row neighbour (r ^ 1) and, 4-way, the weight
+    // block of its column neighbour (r ^ 2)
+    const float* x_in[4];
+    const float* w_in[4] = {nullptr, nullptr, nullptr, nullptr};
+    if (d.weights == JG_WEIGHTS_COPY) {
+        jg::CopyGroup cg;
+        std::memset(&cg, 0, sizeof(cg));
+        cg.nblocks = ways;
+        cg.nontemporal = 0;
+        cg.rows = (int)plan->xr;
+        cg.cols = (int)plan->xc;
+        for (int r = 0; r < ways; ++r) {
+            float* dst = reinterpret_cast<float*>(ws + plan->off_xrecv + r * plan->xblk_bytes);
+            cg.b[r] = {x_sh[r ^ 1], dst, cg.cols, cg.cols};
+            x_in[r] = dst;
+        }
+        {
+            ScopedTimer t(c, JG_KERNEL_WEIGHT_COPY);
+            if (!HIP_OK(jg::launch_copy_group(cg, c->stream))) return JG_E_HIP;
+        }
+        if (ways == 4) {
+            cg.rows = (int)plan->wr;
+            cg.cols = (int)plan->wc;
+            for (int r = 0; r < 4; ++r) {
+                float* dst = reinterpret_cast<float*>(ws + plan->off_wrecv + r * plan->wblk_bytes);
+                cg.b[r] = {w_sh[r ^ 2], dst, cg.cols, cg.cols};
+                w_in[r] = dst;
+            }
+            ScopedTimer t(c, JG_KERNEL_WEIGHT_COPY);
+            if (!HIP_OK(jg::launch_copy_group(cg, c->stream))) return JG_E_HIP;
+        }
+    } else {
+        for (int r = 0; r < ways; ++r) {
+            x_in[r] = x_sh[r ^ 1];
+            if (ways == 4) w_in[r] = w_sh[r ^ 2];
+        }
+    }
+    // the weight block of the product with the rank's own activation block, and of the one with the received block
+    const float* w_own[4];
+    const float* w_other[4];
+    if (ways == 2) {
+        const int64_t block = (int64_t)plan->xc * plan->wc;     // floats in one K/2 x N/2 block of W_r = [W_(0,r); W_(1,r)]
+        for (int r = 0; r < 2; ++r) {
+            w_own[r] = w_sh[r] + r * block;
+            w_other[r] = w_sh[r] + (1 - r) * block;
+        }
+    } else {
+        for (int r = 0; r < 4; ++r) {
+            const bool diagonal = (r / 2) == (r % 2);           // rank (i, j) holds W_(i,j): W_(j,j) iff i = j
+            w_own[r] = diagonal ? w_sh[r] : w_in[r];
+            w_other[r] = diagonal ? w_in[r] : w_sh[r];
+        }
+    }
+    auto part_buf = [&](int r) { return reinterpret_cast<float*>(ws + plan->off_send + r * plan->part_bytes); };
+    auto kept_buf = [&](int r) { return reinterpret_cast<float*>(ws + plan->off_kept + r * plan->part_bytes); };
+    g.nprob = ways;
+    for (int r = 0; r < ways; ++r)
+        g.p[r] = {x_in[r], w_other[r], part_buf(r), nullptr, nullptr, ldx, ldw, ldy, 0, nullptr, 0};
+    if (!run_gemm(plan, g, jg::kGemmNN, JG_KERNEL_GEMM, tail, plan->tail_bytes)) return JG_E_HIP;
+    if (d.combine == JG_COMBINE_FUSED) {
+        g.act = act;
+        for (int r = 0; r < ways; ++r)
+            g.p[r] = {x_sh[r], w_own[r], y_sh[r], part_buf(r), bias_of(r), ldx, ldw, ldy, ldy, res_of(r), ldy};
+        return run_gemm(plan, g, jg::kGemmNN, JG_KERNEL_GEMM, tail, plan->tail_bytes) ? JG_OK : JG_E_HIP;
+    }
+    for (int r = 0; r < ways; ++r)
+        g.p[r] = {x_sh[r], w_own[r], kept_buf(r), nullptr, nullptr, ldx, ldw, ldy, 0, nullptr, 0};
+    if (!run_gemm(plan, g, jg::kGemmNN, JG_KERNEL_GEMM, tail, plan->tail_bytes)) return JG_E_HIP;
+    jg::CombineGroup cb;
+    std::memset(&cb, 0, sizeof(cb));
+    cb.nblocks = ways;
+    cb.rows = (int)plan->yr;
+    cb.cols = (int)plan->yc;
+    cb.act = act;
+    for (int r = 0; r < ways; ++r) cb.b[r] = {kept_buf(r), part_buf(r), bias_of(r), y_sh[r], res_of(r)};
+    ScopedTimer t(c, JG_KERNEL_COMBINE);
+    return HIP_OK(jg::launch_combine_group(cb, c->stream)) ? JG_OK : JG_E_HIP;
+}
+
 int jg_linear_forward(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
                       const float* const* b_sh, float* const* y_sh, void* workspace,
                       size_t workspace_bytes)
@@ -867,6 +1043,7 @@ static int forward_impl(const jg_plan* plan, const float* const* x_sh, const flo
     auto res_of = [&](int r) -> const float* { return r_sh ? r_sh[r] : nullptr; };
 
     if (d.op == JG_OP_XTW) return forward_xtw(plan, x_sh, w_sh, b_sh, r_sh, act, y_sh, ws);
+    if (d.op == JG_OP_XW) return forward_xw(plan, x_sh, w_sh, b_sh, r_sh, act, y_sh, ws);
     char* tail = plan->tail_bytes ? ws + plan->off_tail : nullptr;
 
     jg::GemmGroup g;
@@ -1241,6 +1418,15 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
     jg_ctx* c = plan->ctx;
     if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
     char* ws = static_cast<char*>(workspace);
+    if (d.op == JG_OP_XW) {
+        // dX = dY W^T is the X W^T layer on (dY, W), dW = X^T dY the X^T W layer on (X, dY): the partitions agree
+        // (every tensor of the three permutations is split the same way), so the shards are used as they are
+        int rc = forward_impl(plan->bw_dx_plan, dy_sh, w_sh, nullptr, nullptr, JG_ACT_NONE, dx_sh, workspace,
+                              workspace_bytes, nullptr);
+        if (rc != JG_OK) return rc;
+        return forward_impl(plan->bw_dw_plan, x_sh, dy_sh, nullptr, nullptr, JG_ACT_NONE, dw_sh, workspace,
+                            workspace_bytes, nullptr);
+    }
     if (d.dtype != JG_F32) {
         for (int r = 0; r < ways; ++r)
             if (!aligned(x_sh[r], 4) || !aligned(w_sh[r], 4) || !aligned(dy_sh[r], 4)) return JG_E_ALIGN;

@@ -13,7 +13,8 @@ from . import binding as jg
 class JigsawLinear:
     """Plan + per-rank shard tensors (X_r, W_r, b_r, Y_r) + workspace on one GPU.
 
-    ``op = JG_OP_XWT``: Y = X W^T with X (M, K) and W (N, K).  ``op = JG_OP_XTW``: the transposed
+    ``op = JG_OP_XWT``: Y = X W^T with X (M, K) and W (N, K).  ``op = JG_OP_XW``: Y = X W with W (K, N).
+    ``op = JG_OP_XTW``: the transposed
     layer Y = X^T W with X (K, M) and W (K, N).  ``dtype = JG_BF16 / JG_BF16X3``: the X and W shards are
     bfloat16 tensors (split mode: every row is [hi | lo]) written by ``shard`` from FP32 inputs; the backward of such a
     plan reads FP32 copies (``shard_master``).
@@ -27,7 +28,7 @@ class JigsawLinear:
             raise RuntimeError("JigsawLinear needs a GPU: the HIP library has no CPU fallback")
         self.M, self.K, self.N, self.ways, self.bias, self.op = M, K, N, ways, bias, op
         self.x_shape = (K, M) if op == jg.JG_OP_XTW else (M, K)
-        self.w_shape = (K, N) if op == jg.JG_OP_XTW else (N, K)
+        self.w_shape = (N, K) if op == jg.JG_OP_XWT else (K, N)
         self.dev = torch.device("cuda", device)
         self._own_ctx = ctx is None
         self.stream = torch.cuda.current_stream(self.dev)

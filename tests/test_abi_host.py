@@ -67,7 +67,14 @@ def test_plan_validation():
         assert status_of(dtype=dt, K=12, op=jg.JG_OP_XTW, ways=4) == jg.JG_OK
         assert status_of(dtype=dt, K=7, op=jg.JG_OP_XTW, ways=1) == jg.JG_OK
         assert status_of(dtype=dt, K=7, op=jg.JG_OP_XTW, ways=4) == jg.JG_E_SHAPE
-    assert status_of(op=2) == jg.JG_E_DTYPE
+    assert status_of(op=3) == jg.JG_E_DTYPE
+    # the X W permutation: FP32 only, split like X W^T (K and N halved, 4-way M as well)
+    assert status_of(op=jg.JG_OP_XW) == jg.JG_OK
+    assert status_of(op=jg.JG_OP_XW, dtype=jg.JG_BF16, K=16) == jg.JG_E_DTYPE
+    assert status_of(op=jg.JG_OP_XW, K=7) == jg.JG_E_SHAPE
+    assert status_of(op=jg.JG_OP_XW, N=7) == jg.JG_E_SHAPE
+    assert status_of(op=jg.JG_OP_XW, M=7) == jg.JG_OK
+    assert status_of(op=jg.JG_OP_XW, M=7, ways=4) == jg.JG_E_SHAPE
     # the transposed layer splits M and N (2-way), and K as well (4-way)
     assert status_of(op=jg.JG_OP_XTW) == jg.JG_OK
     assert status_of(op=jg.JG_OP_XTW, K=7) == jg.JG_OK
@@ -540,3 +547,39 @@ def test_token_mixing_chain_takes_two_plans_of_one_precision():
     for f, s in plans.values():
         jg.jg_plan_destroy(f)
         jg.jg_plan_destroy(s)
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,K,N", [(100, 60, 40), (16200, 4320, 4320), (6, 4, 2)])
+def test_accounting_of_the_xw_permutation(ways, M, K, N):
+    p = jg.jg_plan_create(None, M, K, N, ways, op=jg.JG_OP_XW)
+    q = lambda what, r=0: jg.jg_plan_query(p, what, r)
+    try:
+        assert q(jg.JG_Q_FLOPS_TOTAL) == 2 * M * K * N and q(jg.JG_Q_BACKWARD_FLOPS_TOTAL) == 4 * M * K * N
+        # zero memory redundancy (Sec. 4): the shards tile X [M x K], W [K x N] and Y [M x N] exactly
+        assert sum(q(jg.JG_Q_RESIDENT_BYTES_RANK, r) for r in range(ways)) == 4 * (M * K + K * N + M * N)
+        assert sum(q(jg.JG_Q_X_ROWS, r) * q(jg.JG_Q_X_COLS, r) for r in range(ways)) == M * K
+        assert sum(q(jg.JG_Q_W_ROWS, r) * q(jg.JG_Q_W_COLS, r) for r in range(ways)) == K * N
+        assert sum(q(jg.JG_Q_Y_ROWS, r) * q(jg.JG_Q_Y_COLS, r) for r in range(ways)) == M * N
+        for r in range(ways):
+            assert q(jg.JG_Q_W_SHARD_BYTES, r) == 4 * q(jg.JG_Q_W_ROWS, r) * q(jg.JG_Q_W_COLS, r)
+            assert q(jg.JG_Q_W_COLS, r) == q(jg.JG_Q_Y_COLS, r)         # W is split along N like Y
+            assert q(jg.JG_Q_W_ROWS, r) == (K // 2 if ways == 4 else K)   # 2-way: all K rows of the column half
+        # what a rank gets from its peers: the row neighbour's activation block, 4-way also a weight block
+        want = {1: 0, 2: 4 * M * (K // 2), 4: 4 * ((M // 2) * (K // 2) + (K // 2) * (N // 2))}[ways]
+        assert q(jg.JG_Q_EXCHANGE_BYTES_RANK) == want
+        assert q(jg.JG_Q_GEMM_LAUNCHES) == (1 if ways == 1 else 2)
+        ws, tail = q(jg.JG_Q_WORKSPACE_BYTES), q(jg.JG_Q_TAIL_SCRATCH_BYTES)
+        if ways == 1:
+            assert ws == tail
+        else:
+            assert ws >= tail + 4 * M * N + ways * want      # partials of every block + the copies of the received blocks
+        # the gradients are the other two permutations: their workspaces bound the backward's
+        dx = jg.jg_plan_create(None, M, N, K, ways)
+        dw = jg.jg_plan_create(None, K, M, N, ways, op=jg.JG_OP_XTW)
+        assert q(jg.JG_Q_BACKWARD_WORKSPACE_BYTES) == max(jg.jg_plan_query(dx, jg.JG_Q_WORKSPACE_BYTES),
+                                                         jg.jg_plan_query(dw, jg.JG_Q_WORKSPACE_BYTES))
+        jg.jg_plan_destroy(dx)
+        jg.jg_plan_destroy(dw)
+    finally:
+        jg.jg_plan_destroy(p)
