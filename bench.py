@@ -51,11 +51,10 @@ def parse():
                     help="last partial round of a GEMM launch: cut into runs when that pays (default), or whole tiles")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="target CPU time of the oracle baseline sample (0 disables it)")
-    ap.add_argument("--extras", action="store_true",
-                    help="also time the other values of `ways` (by_ways) and one rank's share alone "
-                         "(one_rank_share); these launch the GEMM kernel at other shapes")
+    ap.add_argument("--extras", action="store_true", help="(accepted for older command lines: the extras are on by default)")
     ap.add_argument("--only-headline", action="store_true",
-                    help="skip the streaming-kernel measurements")
+                    help="the headline configuration only: skip the streaming kernels, the other values of `ways`, one "
+                         "rank's share, the separate combine, the reduced-precision modes and the other configs")
     return ap.parse_args()
 
 
@@ -131,18 +130,23 @@ def time_forward(L, jg, steps, warmup, norm=None):
     return (t1 - t0) / steps, gemm_ms, gemm_n, (wc_ms + join_ms + cvt_ms) / steps, cb_ms / steps
 
 
-def measure(cfg, ways, args, X, W, streaming=False):
+def measure(cfg, ways, args, X, W, streaming=False, steps=None, warmup=None, combine=None, dtype=None, share=False):
+    """One configuration of the forward layer.  steps / warmup / combine / dtype default to the command line's."""
     import torch
     from paper_2507_05753_amd import binding as jg
     from paper_2507_05753_amd.layer import JigsawLinear
     M, K, N = cfg["M"], cfg["K"], cfg["N"]
-    combine = jg.JG_COMBINE_FUSED if args.combine == "fused" else jg.JG_COMBINE_SEPARATE
+    steps = args.steps if steps is None else steps
+    warmup = args.warmup if warmup is None else warmup
+    combine = args.combine if combine is None else combine
+    dtype_name = args.dtype if dtype is None else dtype
+    combine = jg.JG_COMBINE_FUSED if combine == "fused" else jg.JG_COMBINE_SEPARATE
     weights = jg.JG_WEIGHTS_COPY if args.weights == "copy" else jg.JG_WEIGHTS_DIRECT
     out = {}
-    dtype = {"f32": jg.JG_F32, "bf16": jg.JG_BF16, "bf16x3": jg.JG_BF16X3}[args.dtype]
+    dtype = {"f32": jg.JG_F32, "bf16": jg.JG_BF16, "bf16x3": jg.JG_BF16X3}[dtype_name]
     with JigsawLinear(M, K, N, ways, combine=combine, weights=weights, tail=tail_of(args), dtype=dtype) as L:
         L.shard(X, W)
-        sec, gemm_ms, gemm_n, wcopy_ms, comb_ms = time_forward(L, jg, args.steps, args.warmup)
+        sec, gemm_ms, gemm_n, wcopy_ms, comb_ms = time_forward(L, jg, steps, warmup)
         other_ms = wcopy_ms + comb_ms
         flops = L.query(jg.JG_Q_FLOPS_TOTAL)
         launches = L.query(jg.JG_Q_GEMM_LAUNCHES)
@@ -170,28 +174,28 @@ def measure(cfg, ways, args, X, W, streaming=False):
             jg.jg_profile(L.ctx, False)
             sh_ms, sh_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_SHARD)
             ga_ms, ga_n = jg.jg_profile_read(L.ctx, jg.JG_KERNEL_GATHER)
-            shard_bytes = {"f32": 8.0, "bf16": 6.0, "bf16x3": 8.0}[args.dtype]   # read FP32, write the shard format
+            shard_bytes = {"f32": 8.0, "bf16": 6.0, "bf16x3": 8.0}[dtype_name]   # read FP32, write the shard format
             stream["shard_x_gbps"] = shard_bytes * M * K / (sh_ms / sh_n * 1e-3) / 1e9
             stream["gather_y_gbps"] = 8.0 * M * N / (ga_ms / ga_n * 1e-3) / 1e9
             stream["shard_x_frac"] = stream["shard_x_gbps"] / HBM_PEAK_GBPS
             stream["gather_y_frac"] = stream["gather_y_gbps"] / HBM_PEAK_GBPS
             out["streaming"] = stream
             del Yg
-    if args.extras and streaming and ways > 1:
+    if share and ways > 1:
         # One rank's share at its real shape: its two block products, alone on the GPU
         # (what one GPU of an n-GPU node would run per layer, exchange excluded).
         Mr, Kr, Nr = (M, K // 2, N // 2) if ways == 2 else (M // 2, K // 2, N // 2)
         with JigsawLinear(Mr, Kr, Nr, 1, dtype=dtype) as R:
             R.shard(X[:Mr, :Kr], W[:Nr, :Kr])
-            for _ in range(2 * args.warmup):
+            for _ in range(2 * warmup):
                 R.forward()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            for _ in range(args.steps):
+            for _ in range(steps):
                 R.forward()
                 R.forward()
             torch.cuda.synchronize()
-            dt = (time.perf_counter() - t0) / args.steps
+            dt = (time.perf_counter() - t0) / steps
             out["one_rank_share"] = dict(ms=dt * 1e3, tflops=2 * R.query(jg.JG_Q_FLOPS_TOTAL) / dt / 1e12,
                                          shape=f"2 x ([{Mr} x {Kr}] . [{Nr} x {Kr}]^T)")
     torch.cuda.empty_cache()
@@ -790,7 +794,7 @@ def cpu_baseline(cfg, seconds, reduced_terms=0):
 # the factors are in profiles/gemm_f32_stream_forward_config3_ways4_hbm_counters.md.  Counters cannot be read
 # from inside this script, so the figure is quoted, keyed by workload, and is null for the others.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
-    ("config3", 4): 3.46e9,   # reads 3.05 GB (FETCH_SIZE / 0.5065) + writes 0.406 GB (WRITE_SIZE / 1.0018)
+    ("config3", 4): 3.50e9,   # reads 3.09 GB (FETCH_SIZE / 0.5065) + writes 0.406 GB (WRITE_SIZE / 1.0018)
     # jg::gemm_bf16_nt, whole tiles (profiles/gemm_bf16_nt_forward_config3_kernel_trace.md): reads 1.51 GB, writes 0.46 GB
     ("config3", 1, "bf16"): 1.98e9,
 }
@@ -1040,15 +1044,47 @@ def main():
         print(json.dumps(line), flush=True)
         return
 
-    head = measure(cfg, args.ways, args, X, W, streaming=not args.only_headline)
-    by_ways = {}
-    if args.extras:
+    extras = not args.only_headline
+    head = measure(cfg, args.ways, args, X, W, streaming=extras, share=extras)
+    by_ways, modes, configs = {}, {}, {}
+    few = max(3, min(args.steps, 10))
+    pick = lambda r: {k: r[k] for k in ("ms_per_step", "items_per_s", "tflops", "gemm_tflops")}
+    if extras:
+        mine = pick(head)
+        mine["steps"] = args.steps
+        by_ways[str(args.ways)] = mine
         for w in (1, 2, 4):
             if w != args.ways:
-                r = measure(cfg, w, args, X, W)
-                by_ways[str(w)] = {k: r[k] for k in ("ms_per_step", "items_per_s", "tflops", "gemm_tflops")}
+                by_ways[str(w)] = dict(pick(measure(cfg, w, args, X, W, steps=few, warmup=2)), steps=few)
+        if args.combine == "fused" and args.ways > 1:
+            # the separate combine kernel (measurement variant): 12 bytes per output element
+            r = measure(cfg, args.ways, args, X, W, steps=few, warmup=2, combine="separate")
+            if "combine_gbps" in r:
+                head["combine_gbps"] = r["combine_gbps"]
+        if args.dtype == "f32":
+            # the reduced-precision modes of the same layer, for scale (each against the bfloat16 matrix peak)
+            for mode in ("bf16", "bf16x3"):
+                r = measure(cfg, args.ways, args, X, W, steps=few, warmup=2, dtype=mode)
+                t = 3 if mode == "bf16x3" else 1
+                modes[mode] = dict(pick(r), steps=few, matrix_tflops=r["gemm_tflops"] * t if r["gemm_tflops"] else None,
+                                   frac_of_bf16_peak=r["gemm_tflops"] * t / BF16_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None)
     del X, W
     torch.cuda.empty_cache()
+    if extras:
+        # the other configurations of the workload table, same launch options, a few steps each
+        for c in (1, 2, 3, 4, 5):
+            if c == args.config:
+                continue
+            cc = inputs.CONFIGS[c]
+            Xc, Wc = make_inputs(cc, dev)
+            n = {1: 200, 2: 200, 5: 3}.get(c, few)
+            r = measure(cc, args.ways, args, Xc, Wc, steps=n, warmup=2 if c >= 3 else 20)
+            configs[str(c)] = dict(pick(r), steps=n, M=cc["M"], K=cc["K"], N=cc["N"], x_values=cc["x_mode"],
+                                   frac_of_peak=r["gemm_tflops"] * (3 if args.dtype == "bf16x3" else 1) /
+                                   (FP32_MFMA_PEAK_TFLOPS if args.dtype == "f32" else BF16_MFMA_PEAK_TFLOPS)
+                                   if r["gemm_tflops"] else None)
+            del Xc, Wc
+            torch.cuda.empty_cache()
 
     reduced = args.dtype != "f32"
     terms = 3 if args.dtype == "bf16x3" else 1
@@ -1085,6 +1121,8 @@ def main():
             "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(
                 (f"config{args.config}", args.ways, args.dtype) if reduced else (f"config{args.config}", args.ways)),
             "traffic_unit": "bytes per launch",
+            "traffic_source": "quoted from profiles/ (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, scaled by "
+                              "a copy kernel of known size): counters cannot be read from inside the run",
         },
         "other_kernels_ms_per_step": head["other_kernels_ms_per_step"],
     }
@@ -1097,6 +1135,10 @@ def main():
         line["streaming"]["combine_frac"] = head["combine_gbps"] / HBM_PEAK_GBPS
     if by_ways:
         line["by_ways"] = by_ways
+    if modes:
+        line["reduced_precision"] = modes
+    if configs:
+        line["configs"] = configs
     if reduced:
         line["roofline"]["matrix_passes"] = terms
     if args.cpu_seconds > 0:

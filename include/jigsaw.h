@@ -97,6 +97,8 @@ enum { JG_F32 = 0,       /* the paper's uniform single precision (Sec. 6.1)     
 enum { JG_COMBINE_FUSED = 0, JG_COMBINE_SEPARATE = 1 };  /* where the "+" of Eq. (2)/(4) runs */
 enum { JG_WEIGHTS_COPY = 0, JG_WEIGHTS_DIRECT = 1 };     /* 4-way weight-block hand-off */
 enum { JG_TAIL_SPLIT = 0, JG_TAIL_WHOLE = 1 };           /* last partial round of a GEMM launch */
+enum { JG_ACC_LEVELS = 0,   /* reduced precision: long contractions are summed in two levels (chunks of K, one launch each) */
+       JG_ACC_SINGLE = 1 }; /* ... or in one level, for data known to be zero-mean                              */
 enum { JG_ACT_NONE = 0, JG_ACT_GELU = 1 };               /* epilogue activation of jg_linear_forward_ex */
 enum { JG_T_X = 0, JG_T_W = 1, JG_T_B = 2, JG_T_Y = 3,   /* tensor selector of jg_shard / jg_gather_as */
        JG_T_X_F32 = 4,    /* partitioned like X, stored in FP32 whatever the plan's dtype: the activations a
@@ -141,6 +143,15 @@ typedef struct jg_linear_desc {
                             ascending k order (no atomics: results do not vary from run to
                             run).  Needs JG_Q_TAIL_SCRATCH_BYTES more workspace.
                             JG_TAIL_WHOLE: one workgroup per tile throughout.           */
+    int32_t accumulate;  /* Reduced-precision plans only (FP32 plans always sum in two levels inside the
+                            kernel).  The bfloat16 kernels sum in one level: on operands of one sign a
+                            running FP32 sum of K products drifts past 1e-6 of its magnitude from K of
+                            about 1500 (500 with split operands).  JG_ACC_LEVELS (the default): a product
+                            with a longer contraction is cut into chunks of K, one launch each, every launch
+                            after the first adding on top of what the output holds - the second summation
+                            level; results stay within 1e-6 of the magnitude on any data, at the price of
+                            one more pass over the output per chunk.  JG_ACC_SINGLE: one launch whatever K;
+                            for zero-mean data, whose running sums stay small (measured below 1e-7).     */
 } jg_linear_desc;
 
 typedef enum jg_query {

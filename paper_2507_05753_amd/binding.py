@@ -34,6 +34,7 @@ JG_F32, JG_BF16, JG_BF16X3 = 0, 1, 2
 JG_COMBINE_FUSED, JG_COMBINE_SEPARATE = 0, 1
 JG_WEIGHTS_COPY, JG_WEIGHTS_DIRECT = 0, 1
 JG_TAIL_SPLIT, JG_TAIL_WHOLE = 0, 1
+JG_ACC_LEVELS, JG_ACC_SINGLE = 0, 1
 JG_STATIC_WORKSPACE_BYTES = 32 << 20
 JG_ACT_NONE, JG_ACT_GELU = 0, 1
 JG_T_X, JG_T_W, JG_T_B, JG_T_Y, JG_T_X_F32, JG_T_W_F32 = 0, 1, 2, 3, 4, 5
@@ -59,7 +60,7 @@ class jg_linear_desc(ctypes.Structure):
     _fields_ = [("M", ctypes.c_int64), ("K", ctypes.c_int64), ("N", ctypes.c_int64),
                 ("ways", ctypes.c_int32), ("op", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("has_bias", ctypes.c_int32), ("combine", ctypes.c_int32), ("weights", ctypes.c_int32),
-                ("tail", ctypes.c_int32)]
+                ("tail", ctypes.c_int32), ("accumulate", ctypes.c_int32)]
 
 
 class JigsawError(RuntimeError):
@@ -155,8 +156,9 @@ def jg_free(ctx) -> None:
 
 def jg_plan_create(ctx, M: int, K: int, N: int, ways: int, has_bias: bool = False,
                    combine: int = JG_COMBINE_FUSED, weights: int = JG_WEIGHTS_COPY,
-                   op: int = JG_OP_XWT, dtype: int = JG_F32, tail: int = JG_TAIL_SPLIT) -> int:
-    d = jg_linear_desc(M, K, N, ways, op, dtype, int(has_bias), combine, weights, tail)
+                   op: int = JG_OP_XWT, dtype: int = JG_F32, tail: int = JG_TAIL_SPLIT,
+                   accumulate: int = JG_ACC_LEVELS) -> int:
+    d = jg_linear_desc(M, K, N, ways, op, dtype, int(has_bias), combine, weights, tail, accumulate)
     out = ctypes.c_void_p()
     _raise(_lib.jg_plan_create(ctx, ctypes.byref(d), ctypes.byref(out)), "jg_plan_create")
     return out.value

@@ -39,6 +39,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <cmath>
 #include <type_traits>
 #include <utility>
 
@@ -215,8 +216,8 @@ __device__ __forceinline__ void hb_store_tile(const GemmProblem& P, int M, int N
 {
     const float* __restrict__ bias = P.bias;
     const float* __restrict__ residual = P.residual;
-    const float* __restrict__ addend = P.addend;
-    float* __restrict__ C = P.C;
+    const float* addend = P.addend;     // may be C itself: a later chunk of a contraction adds on top of what C holds
+    float* C = P.C;                     // (every element is read and then written by the same lane)
     const int ldc = P.ldc, ldres = P.ldres, ldadd = P.ldadd;
     const bool vec_ok = (((uintptr_t)C | (uintptr_t)addend | (uintptr_t)residual | (uintptr_t)bias) & 15) == 0 &&
                         ((ldc | (addend ? ldadd : 0) | (residual ? ldres : 0)) & 3) == 0 &&
@@ -755,6 +756,21 @@ inline bool hb_operand_ok(const float* p, int ld, int K)
 // `cus` workgroups run at a time.  When the tiles do not fill whole rounds of them, the tiles of the last
 // partial round are cut into runs of slabs so that every CU gets one (at least kHbMinRunSlabs slabs each);
 // scratch holds a 256 x 256 tile of floats per run, or is null / too small: then every tile stays whole.
+// Second summation level of the bfloat16 kernels, taken between launches: the length of the chunks a contraction of
+// K (elements of one plane) is cut into.  A same-sign sum of n accumulate steps (one MFMA = 16 k, three MFMAs per
+// 16 k with split operands) was measured to drift by 4.7e-7 / 7.3e-7 / 9.8e-7 of its magnitude at n = 32 / 64 / 96,
+// about n^0.62; c equal chunks leave that of n / c steps divided by sqrt(c).  The smallest c that stays at the level
+// of 64 steps (7.3e-7, inside the 1e-6 the layer is held to) is taken; chunks are whole 64-element slabs.
+inline int bf16_chunk_k(int K, int terms)
+{
+    const double steps = (double)terms * K / 16.0;
+    const double level = std::pow(64.0, 0.62);
+    int c = 1;
+    while (c < 256 && std::pow(steps / c, 0.62) > level * std::sqrt((double)c)) ++c;
+    const int chunk = ((K + c - 1) / c + 63) / 64 * 64;
+    return chunk < K ? chunk : K;
+}
+
 constexpr int kHbMinRunSlabs = 16;
 constexpr int kHbJoinCostSlabs = 40;    // the join kernel takes about as long as 40 slabs of the main loop
 inline size_t bf16_tail_scratch_bytes(int cus) { return (size_t)cus * HB_TILE_FLOATS * sizeof(float); }

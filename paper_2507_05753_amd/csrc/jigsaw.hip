@@ -338,6 +338,7 @@ int jg_plan_create(jg_ctx* ctx, const jg_linear_desc* desc, jg_plan** out)
     if (d.weights != JG_WEIGHTS_COPY && d.weights != JG_WEIGHTS_DIRECT) return JG_E_DTYPE;
     if (d.has_bias != 0 && d.has_bias != 1) return JG_E_DTYPE;
     if (d.tail != JG_TAIL_SPLIT && d.tail != JG_TAIL_WHOLE) return JG_E_DTYPE;
+    if (d.accumulate != JG_ACC_LEVELS && d.accumulate != JG_ACC_SINGLE) return JG_E_DTYPE;
     if (d.M <= 0 || d.K <= 0 || d.N <= 0) return JG_E_SHAPE;
     if (d.M > kMaxDim || d.K > kMaxDim || d.N > kMaxDim) return JG_E_SHAPE;
     // the dimensions that are halved: X W^T splits K (2-way) and M, K (4-way); X^T W splits M and K, M
@@ -558,7 +559,18 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
     case JG_Q_RESIDENT_BYTES_RANK:
         *out = eb * (plan->xr * plan->xc + plan->wr * plan->wc) + 4 * plan->yr * plan->yc;
         break;
-    case JG_Q_GEMM_LAUNCHES: *out = (d.ways == 1 || (xtw && d.ways == 2)) ? 1 : 2; break;
+    case JG_Q_GEMM_LAUNCHES: {
+        // block-product launches per forward; a reduced-precision product takes one launch per chunk of its contraction
+        int64_t chunks = 1;
+        if (reduced && d.accumulate != JG_ACC_SINGLE) {
+            int kk = (int)(xtw ? plan->xr : plan->xc);
+            if (xtw) kk = (kk + 7) / 8 * 8;
+            const int ck = jg::bf16_chunk_k(kk, d.dtype == JG_BF16X3 ? 3 : 1);
+            chunks = (kk + ck - 1) / ck;
+        }
+        *out = ((d.ways == 1 || (xtw && d.ways == 2)) ? 1 : 2) * chunks;
+        break;
+    }
     case JG_Q_BACKWARD_WORKSPACE_BYTES: *out = (int64_t)plan->bw_ws_bytes; break;
     case JG_Q_BACKWARD_FLOPS_TOTAL: *out = 4 * M * K * N; break;
     case JG_Q_BACKWARD_GEMM_LAUNCHES: *out = d.ways == 1 ? 2 : (d.ways == 2 && !xtw) ? 3 : 4; break;
@@ -765,18 +777,38 @@ static bool run_gemm(const jg_plan* plan, jg::GemmGroup& g, int layout, int kern
     jg_ctx* c = plan->ctx;
     bool join = false;
     if (plan->d.dtype != JG_F32) {
-        jg::HbGroup hb;
-        {
-            ScopedTimer t(c, kernel_class);
-            if (!HIP_OK(jg::launch_gemm_bf16_group(g, plan->d.dtype == JG_BF16X3 ? 3 : 1,
-                                                   plane ? plane : (int)plan->plane, plan->slots / 2,
-                                                   reinterpret_cast<float*>(scratch), scratch_bytes, c->stream, hb, &join,
-                                                   copy16)))
-                return false;
-        }
-        if (join) {
-            ScopedTimer t(c, JG_KERNEL_JOIN);
-            if (!HIP_OK(jg::launch_gemm_bf16_join(hb, c->stream))) return false;
+        // The bfloat16 kernels sum in one level (their accumulators fill the register file).  The second level is
+        // taken here: the contraction is cut into chunks, one launch each; the first writes its sums to C (on top
+        // of the product's addend), every later one adds its own on top of what C holds, and the last applies the
+        // epilogue.  One chunk, and nothing changes, for short contractions and for JG_ACC_SINGLE plans.
+        const int terms = plan->d.dtype == JG_BF16X3 ? 3 : 1;
+        const int K = g.K;
+        const int chunk = plan->d.accumulate == JG_ACC_SINGLE ? K : jg::bf16_chunk_k(K, terms);
+        const jg::GemmGroup whole = g;
+        for (int k0 = 0; k0 < K; k0 += chunk) {
+            const bool first = k0 == 0, last = k0 + chunk >= K;
+            jg::GemmGroup part = whole;
+            part.K = last ? K - k0 : chunk;
+            if (!last) part.act = jg::kActNone;
+            for (int i = 0; i < whole.nprob; ++i) {
+                jg::GemmProblem& q = part.p[i];
+                q.A += k0 / 2;      // operand rows hold bfloat16 pairs per 4-byte unit; a split operand's lo plane
+                q.B += k0 / 2;      // sits at the same distance behind its hi plane in every chunk
+                if (!first) { q.addend = q.C; q.ldadd = q.ldc; }
+                if (!last) { q.bias = nullptr; q.residual = nullptr; q.ldres = 0; }
+            }
+            jg::HbGroup hb;
+            {
+                ScopedTimer t(c, kernel_class);
+                if (!HIP_OK(jg::launch_gemm_bf16_group(part, terms, plane ? plane : (int)plan->plane, plan->slots / 2,
+                                                       reinterpret_cast<float*>(scratch), scratch_bytes, c->stream, hb,
+                                                       &join, last ? copy16 : nullptr)))
+                    return false;
+            }
+            if (join) {
+                ScopedTimer t(c, JG_KERNEL_JOIN);
+                if (!HIP_OK(jg::launch_gemm_bf16_join(hb, c->stream))) return false;
+            }
         }
         return true;
     }

@@ -23,7 +23,7 @@ class JigsawLinear:
     def __init__(self, M: int, K: int, N: int, ways: int, bias: bool = False,
                  combine: int = jg.JG_COMBINE_FUSED, weights: int = jg.JG_WEIGHTS_COPY,
                  device: int = 0, ctx=None, op: int = jg.JG_OP_XWT, tail: int = jg.JG_TAIL_SPLIT,
-                 dtype: int = jg.JG_F32):
+                 dtype: int = jg.JG_F32, accumulate: int = jg.JG_ACC_LEVELS):
         if not torch.cuda.is_available():
             raise RuntimeError("JigsawLinear needs a GPU: the HIP library has no CPU fallback")
         self.M, self.K, self.N, self.ways, self.bias, self.op = M, K, N, ways, bias, op
@@ -34,7 +34,8 @@ class JigsawLinear:
         self.stream = torch.cuda.current_stream(self.dev)
         self.ctx = ctx if ctx is not None else jg.jg_init(device, self.stream.cuda_stream)
         self.dtype = dtype
-        self.plan = jg.jg_plan_create(self.ctx, M, K, N, ways, bias, combine, weights, op, dtype=dtype, tail=tail)
+        self.plan = jg.jg_plan_create(self.ctx, M, K, N, ways, bias, combine, weights, op, dtype=dtype, tail=tail,
+                                      accumulate=accumulate)
         q = lambda what, r=0: jg.jg_plan_query(self.plan, what, r)
         f32 = dict(dtype=torch.float32, device=self.dev)
         if dtype == jg.JG_F32:
@@ -203,9 +204,11 @@ class JigsawMLP:
     """
 
     def __init__(self, M: int, C: int, Hd: int, ways: int, device: int = 0, ctx=None, tail: int = jg.JG_TAIL_SPLIT,
-                 dtype: int = jg.JG_F32):
-        self.first = JigsawLinear(M, C, Hd, ways, bias=True, device=device, ctx=ctx, tail=tail, dtype=dtype)
-        self.second = JigsawLinear(M, Hd, C, ways, bias=True, device=device, ctx=self.first.ctx, tail=tail, dtype=dtype)
+                 dtype: int = jg.JG_F32, accumulate: int = jg.JG_ACC_LEVELS):
+        self.first = JigsawLinear(M, C, Hd, ways, bias=True, device=device, ctx=ctx, tail=tail, dtype=dtype,
+                                  accumulate=accumulate)
+        self.second = JigsawLinear(M, Hd, C, ways, bias=True, device=device, ctx=self.first.ctx, tail=tail, dtype=dtype,
+                                   accumulate=accumulate)
         self.dtype = dtype
         if dtype == jg.JG_F32:
             self.xin = self.first.x
@@ -326,8 +329,8 @@ class JigsawMixing(JigsawMLP):
     (``jg_mixing_forward``).  ``gamma`` / ``beta``: device vectors of length C."""
 
     def __init__(self, M: int, C: int, Hd: int, ways: int, device: int = 0, ctx=None, tail: int = jg.JG_TAIL_SPLIT,
-                 eps: float = 1e-5, dtype: int = jg.JG_F32):
-        super().__init__(M, C, Hd, ways, device=device, ctx=ctx, tail=tail, dtype=dtype)
+                 eps: float = 1e-5, dtype: int = jg.JG_F32, accumulate: int = jg.JG_ACC_LEVELS):
+        super().__init__(M, C, Hd, ways, device=device, ctx=ctx, tail=tail, dtype=dtype, accumulate=accumulate)
         self.eps = eps
         self.xn = [torch.empty_like(t) for t in self.xin]
         self.gamma = self.beta = None
@@ -386,12 +389,13 @@ class JigsawTokenMixing:
     the activations do and H where the weights do; nothing is transposed in memory."""
 
     def __init__(self, T: int, C: int, D: int, ways: int, device: int = 0, ctx=None, tail: int = jg.JG_TAIL_SPLIT,
-                 eps: float = 1e-5, dtype: int = jg.JG_F32):
+                 eps: float = 1e-5, dtype: int = jg.JG_F32, accumulate: int = jg.JG_ACC_LEVELS):
         """``dtype = JG_BF16 / JG_BF16X3``: mixed precision - X, Xn, H and Y stay FP32, the two products read
         bfloat16 roundings (W1 and W2 rounded when sharded, Xn and H by the chain, into the workspace)."""
         self.first = JigsawLinear(C, T, D, ways, bias=True, device=device, ctx=ctx, op=jg.JG_OP_XTW, tail=tail,
-                                  dtype=dtype)
-        self.second = JigsawLinear(T, D, C, ways, bias=False, device=device, ctx=self.first.ctx, tail=tail, dtype=dtype)
+                                  dtype=dtype, accumulate=accumulate)
+        self.second = JigsawLinear(T, D, C, ways, bias=False, device=device, ctx=self.first.ctx, tail=tail, dtype=dtype,
+                                   accumulate=accumulate)
         self.second.w = self.first.y        # H_r is the second layer's weight shard, read where it was produced
         self.T, self.C, self.D, self.ways, self.eps, self.dtype = T, C, D, ways, eps, dtype
         self.ctx = self.first.ctx
@@ -522,11 +526,14 @@ class JigsawMixerBlock:
     place."""
 
     def __init__(self, T: int, C: int, Dt: int, Dc: int, ways: int, device: int = 0, ctx=None,
-                 tail: int = jg.JG_TAIL_SPLIT, eps: float = 1e-5, dtype: int = jg.JG_F32, keep_masters: bool = False):
+                 tail: int = jg.JG_TAIL_SPLIT, eps: float = 1e-5, dtype: int = jg.JG_F32, keep_masters: bool = False,
+                 accumulate: int = jg.JG_ACC_LEVELS):
         """``dtype = JG_BF16 / JG_BF16X3``: both halves in mixed precision (FP32 activations between them);
         ``keep_masters``: also keep the FP32 weights on shards, which the mixed-precision backward reads."""
-        self.token = JigsawTokenMixing(T, C, Dt, ways, device=device, ctx=ctx, tail=tail, eps=eps, dtype=dtype)
-        self.channel = JigsawMixing(T, C, Dc, ways, device=device, ctx=self.token.ctx, tail=tail, eps=eps, dtype=dtype)
+        self.token = JigsawTokenMixing(T, C, Dt, ways, device=device, ctx=ctx, tail=tail, eps=eps, dtype=dtype,
+                                       accumulate=accumulate)
+        self.channel = JigsawMixing(T, C, Dc, ways, device=device, ctx=self.token.ctx, tail=tail, eps=eps, dtype=dtype,
+                                    accumulate=accumulate)
         self.token.keep_masters = self.channel.keep_masters = keep_masters
         self.channel.xin = self.token.second.y
         if dtype == jg.JG_F32:

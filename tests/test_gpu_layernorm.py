@@ -18,7 +18,7 @@ from paper_2507_05753_amd import inputs
 pytestmark = pytest.mark.gpu
 HALF_ULP = 2.0 ** -24
 TOL = 1e-6
-TOL_H = 1.5e-6 + 2.0 ** -23
+TOL_H = 1e-6 + 2.0 ** -23
 
 
 @pytest.fixture(scope="module")
