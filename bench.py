@@ -47,6 +47,8 @@ def parse():
                          "passes (bf16x3)")
     ap.add_argument("--combine", choices=["fused", "separate"], default="fused")
     ap.add_argument("--weights", choices=["copy", "direct"], default="copy")
+    ap.add_argument("--accumulate", choices=["levels", "single"], default="levels",
+                    help="reduced precision: second summation level between launches (default), or one launch per product")
     ap.add_argument("--tail", choices=["split", "whole"], default="split",
                     help="last partial round of a GEMM launch: cut into runs when that pays (default), or whole tiles")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
@@ -61,6 +63,11 @@ def parse():
 def tail_of(args):
     from paper_2507_05753_amd import binding as jg
     return jg.JG_TAIL_SPLIT if args.tail == "split" else jg.JG_TAIL_WHOLE
+
+
+def acc_of(args):
+    from paper_2507_05753_amd import binding as jg
+    return jg.JG_ACC_LEVELS if args.accumulate == "levels" else jg.JG_ACC_SINGLE
 
 
 def dtype_of(args, jg):
@@ -130,7 +137,8 @@ def time_forward(L, jg, steps, warmup, norm=None):
     return (t1 - t0) / steps, gemm_ms, gemm_n, (wc_ms + join_ms + cvt_ms) / steps, cb_ms / steps
 
 
-def measure(cfg, ways, args, X, W, streaming=False, steps=None, warmup=None, combine=None, dtype=None, share=False):
+def measure(cfg, ways, args, X, W, streaming=False, steps=None, warmup=None, combine=None, dtype=None, share=False,
+            accumulate=None):
     """One configuration of the forward layer.  steps / warmup / combine / dtype default to the command line's."""
     import torch
     from paper_2507_05753_amd import binding as jg
@@ -144,7 +152,9 @@ def measure(cfg, ways, args, X, W, streaming=False, steps=None, warmup=None, com
     weights = jg.JG_WEIGHTS_COPY if args.weights == "copy" else jg.JG_WEIGHTS_DIRECT
     out = {}
     dtype = {"f32": jg.JG_F32, "bf16": jg.JG_BF16, "bf16x3": jg.JG_BF16X3}[dtype_name]
-    with JigsawLinear(M, K, N, ways, combine=combine, weights=weights, tail=tail_of(args), dtype=dtype) as L:
+    acc = {"levels": jg.JG_ACC_LEVELS, "single": jg.JG_ACC_SINGLE}[args.accumulate if accumulate is None else accumulate]
+    with JigsawLinear(M, K, N, ways, combine=combine, weights=weights, tail=tail_of(args), dtype=dtype,
+                      accumulate=acc) as L:
         L.shard(X, W)
         sec, gemm_ms, gemm_n, wcopy_ms, comb_ms = time_forward(L, jg, steps, warmup)
         other_ms = wcopy_ms + comb_ms
@@ -155,6 +165,7 @@ def measure(cfg, ways, args, X, W, streaming=False, steps=None, warmup=None, com
         out = dict(
             ms_per_step=sec * 1e3, items_per_s=M * K / sec, tflops=flops / sec / 1e12,
             gemm_avg_launch_ms=avg_launch_ms, gemm_launches_timed=gemm_n,
+            gemm_launches_per_step=launches,
             gemm_tflops=(flops / launches) / (avg_launch_ms * 1e-3) / 1e12 if gemm_n else None,
             other_kernels_ms_per_step=other_ms,
             hbm_algo_gbps=algo_bytes / sec / 1e9, hbm_algo_frac=algo_bytes / sec / 1e9 / HBM_PEAK_GBPS,
@@ -212,7 +223,7 @@ def measure_backward(cfg, ways, args, X, W):
     dY = inputs.matrix_torch(cfg["seed"] + 3000, M, N, "R", 0, device=X.device)
     reduced = args.dtype != "f32"
     terms = 3 if args.dtype == "bf16x3" else 1
-    with JigsawLinear(M, K, N, ways, tail=tail_of(args), dtype=dtype_of(args, jg)) as L:
+    with JigsawLinear(M, K, N, ways, tail=tail_of(args), dtype=dtype_of(args, jg), accumulate=acc_of(args)) as L:
         if reduced:
             L.shard_master(X, W)        # the backward of a reduced-precision plan reads FP32 X and W and rounds them
         else:
@@ -287,7 +298,7 @@ def measure_xtw(cfg, ways, args):
     combine = jg.JG_COMBINE_FUSED if args.combine == "fused" else jg.JG_COMBINE_SEPARATE
     weights = jg.JG_WEIGHTS_COPY if args.weights == "copy" else jg.JG_WEIGHTS_DIRECT
     with JigsawLinear(M, K, N, ways, combine=combine, weights=weights, op=jg.JG_OP_XTW, tail=tail_of(args),
-                      dtype=dtype_of(args, jg)) as L:
+                      dtype=dtype_of(args, jg), accumulate=acc_of(args)) as L:
         L.shard(X, W)
         del X, W
         sec, gemm_ms, gemm_n, copy_ms, comb_ms = time_forward(L, jg, args.steps, args.warmup)
@@ -378,7 +389,7 @@ def measure_mlp(cfg, ways, args):
     M, C, Hd, seed = cfg["M"], cfg["C"], cfg["Hd"], cfg["seed"]
     dev = torch.device("cuda", 0)
     gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device=dev)
-    with JigsawMLP(M, C, Hd, ways, tail=tail_of(args), dtype=dtype_of(args, jg)) as L:
+    with JigsawMLP(M, C, Hd, ways, tail=tail_of(args), dtype=dtype_of(args, jg), accumulate=acc_of(args)) as L:
         L.shard(gen(seed, M, C), gen(seed + 1, Hd, C, inputs.W_SCALE_EXP), gen(seed + 2, 1, Hd)[0].contiguous(),
                 gen(seed + 3, C, Hd, inputs.W_SCALE_EXP), gen(seed + 4, 1, C)[0].contiguous())
         sec, gemm_ms, gemm_n, copy_ms, comb_ms = time_forward(L, jg, args.steps, args.warmup)
@@ -402,7 +413,7 @@ def measure_mixing(cfg, ways, args):
     M, C, Hd, seed = cfg["M"], cfg["C"], cfg["Hd"], cfg["seed"]
     dev = torch.device("cuda", 0)
     gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device=dev)
-    with JigsawMixing(M, C, Hd, ways, tail=tail_of(args), dtype=dtype_of(args, jg)) as L:
+    with JigsawMixing(M, C, Hd, ways, tail=tail_of(args), dtype=dtype_of(args, jg), accumulate=acc_of(args)) as L:
         L.shard(gen(seed, M, C), (gen(seed + 5, 1, C)[0] + 1.5).contiguous(), gen(seed + 6, 1, C)[0].contiguous(),
                 gen(seed + 1, Hd, C, inputs.W_SCALE_EXP), gen(seed + 2, 1, Hd)[0].contiguous(),
                 gen(seed + 3, C, Hd, inputs.W_SCALE_EXP), gen(seed + 4, 1, C)[0].contiguous())
@@ -431,7 +442,7 @@ def measure_token_mixing(cfg, ways, args):
     T, C, D, seed = cfg["K"], cfg["M"], cfg["N"], cfg["seed"]
     dev = torch.device("cuda", 0)
     gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device=dev)
-    with JigsawTokenMixing(T, C, D, ways, tail=tail_of(args), dtype=dtype_of(args, jg)) as L:
+    with JigsawTokenMixing(T, C, D, ways, tail=tail_of(args), dtype=dtype_of(args, jg), accumulate=acc_of(args)) as L:
         L.shard(gen(seed, T, C), (gen(seed + 5, 1, C)[0] + 1.5).contiguous(), gen(seed + 6, 1, C)[0].contiguous(),
                 gen(seed + 1, T, D, inputs.W_SCALE_EXP), gen(seed + 2, 1, D)[0].contiguous(),
                 gen(seed + 3, T, D, inputs.W_SCALE_EXP), gen(seed + 4, 1, T)[0].contiguous())
@@ -541,7 +552,7 @@ def measure_mixing_backward(cfg, ways, args):
     M, C, Hd, seed = cfg["M"], cfg["C"], cfg["Hd"], cfg["seed"]
     dev = torch.device("cuda", 0)
     gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device=dev)
-    with JigsawMixing(M, C, Hd, ways, tail=tail_of(args), dtype=dtype_of(args, jg)) as L:
+    with JigsawMixing(M, C, Hd, ways, tail=tail_of(args), dtype=dtype_of(args, jg), accumulate=acc_of(args)) as L:
         L.keep_masters = True
         L.shard(gen(seed, M, C), (gen(seed + 5, 1, C)[0] + 1.5).contiguous(), gen(seed + 6, 1, C)[0].contiguous(),
                 gen(seed + 1, Hd, C, inputs.W_SCALE_EXP), gen(seed + 2, 1, Hd)[0].contiguous(),
@@ -561,7 +572,7 @@ def measure_token_mixing_backward(cfg, ways, args):
     T, C, D, seed = cfg["K"], cfg["M"], cfg["N"], cfg["seed"]
     dev = torch.device("cuda", 0)
     gen = lambda s, r, c, e=0: inputs.matrix_torch(s, r, c, "R", e, device=dev)
-    with JigsawTokenMixing(T, C, D, ways, tail=tail_of(args), dtype=dtype_of(args, jg)) as L:
+    with JigsawTokenMixing(T, C, D, ways, tail=tail_of(args), dtype=dtype_of(args, jg), accumulate=acc_of(args)) as L:
         L.keep_masters = True
         L.shard(gen(seed, T, C), (gen(seed + 5, 1, C)[0] + 1.5).contiguous(), gen(seed + 6, 1, C)[0].contiguous(),
                 gen(seed + 1, T, D, inputs.W_SCALE_EXP), gen(seed + 2, 1, D)[0].contiguous(),
@@ -1063,11 +1074,15 @@ def main():
                 head["combine_gbps"] = r["combine_gbps"]
         if args.dtype == "f32":
             # the reduced-precision modes of the same layer, for scale (each against the bfloat16 matrix peak)
+            # (levels: the default, a second summation level between launches; single: one launch per product)
             for mode in ("bf16", "bf16x3"):
-                r = measure(cfg, args.ways, args, X, W, steps=few, warmup=2, dtype=mode)
-                t = 3 if mode == "bf16x3" else 1
-                modes[mode] = dict(pick(r), steps=few, matrix_tflops=r["gemm_tflops"] * t if r["gemm_tflops"] else None,
-                                   frac_of_bf16_peak=r["gemm_tflops"] * t / BF16_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None)
+                for acc in ("levels", "single"):
+                    r = measure(cfg, args.ways, args, X, W, steps=few, warmup=2, dtype=mode, accumulate=acc)
+                    t = 3 if mode == "bf16x3" else 1
+                    modes[f"{mode}_{acc}"] = dict(
+                        pick(r), steps=few, gemm_launches_per_step=r["gemm_launches_per_step"],
+                        matrix_tflops=r["gemm_tflops"] * t if r["gemm_tflops"] else None,
+                        frac_of_bf16_peak=r["gemm_tflops"] * t / BF16_MFMA_PEAK_TFLOPS if r["gemm_tflops"] else None)
     del X, W
     torch.cuda.empty_cache()
     if extras:
@@ -1109,7 +1124,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": workload, "n_items": M * K, "ways": args.ways, "M": M, "K": K, "N": N,
                    "seed": cfg["seed"], "x_values": cfg["x_mode"], "combine": args.combine,
-                   "weights": args.weights, "tail": args.tail, "mode": args.dtype},
+                   "weights": args.weights, "tail": args.tail, "mode": args.dtype,
+                   **({"accumulate": args.accumulate} if args.dtype != "f32" else {})},
         "tflops": head["tflops"],
         "hbm_algo_gbps": head["hbm_algo_gbps"],
         "hbm_algo_frac_of_8TBps": head["hbm_algo_frac"],
