@@ -181,7 +181,10 @@ typedef enum jg_query {
     JG_Q_X_F32_SHARDS_BYTES = 22,       /* `ways` FP32 shards shaped like X_r, each rounded up to 256
                                            bytes: what jg_token_mixing_forward needs for its skip
                                            connection when b2 is given (rank ignored)               */
-    JG_Q_NORM_BACKWARD_WORKSPACE_BYTES = 23   /* device bytes jg_layernorm_backward needs (rank ignored) */
+    JG_Q_NORM_BACKWARD_WORKSPACE_BYTES = 23,  /* device bytes jg_layernorm_backward wants (rank ignored): the rows'
+                                                 statistics, which it needs, and the partial column sums that let its
+                                                 dgamma / dbeta kernel use the whole chip                              */
+    JG_Q_BIAS_BACKWARD_WORKSPACE_BYTES = 24   /* device bytes that let jg_bias_backward use the whole chip (rank ignored) */
 } jg_query;
 
 typedef enum jg_kernel {         /* kernel classes for jg_profile_read */
@@ -518,8 +521,9 @@ int jg_mixing_backward(const jg_plan* first, const jg_plan* second, const float*
  * shaped like X_r (no overlaps: the sums over tokens read x_sh and dy_sh after dx_sh is written); dgamma, dbeta: device vectors over ALL channels of X
  * (every channel block is summed over the ranks that hold it and written once), either may be NULL.  Evaluated in
  * double and rounded once; the column sums in a fixed order (the same bits on every run).  workspace: 256-byte
- * aligned, JG_Q_NORM_BACKWARD_WORKSPACE_BYTES (mean and 1 / sqrt(var + eps) of every row).  Any plan (op, dtype):
- * only the X partition matters.
+ * aligned; it must hold mean and 1 / sqrt(var + eps) of every row (`ways` times 16 bytes per row of X_r, each
+ * rank's share rounded up to 256), and with JG_Q_NORM_BACKWARD_WORKSPACE_BYTES the column sums also run in row
+ * ranges on the whole chip (as jg_bias_backward's).  Any plan (op, dtype): only the X partition matters.
  * Errors: JG_E_NULL, JG_E_DTYPE (eps negative or NaN), JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
 int jg_layernorm_backward(const jg_plan* plan, const float* const* x_sh, const float* gamma, double eps,
                           const float* const* dy_sh, float* const* dx_sh, float* dgamma, float* dbeta, void* workspace,
@@ -530,10 +534,15 @@ int jg_layernorm_backward(const jg_plan* plan, const float* const* x_sh, const f
  * dy_sh: the dY shards (shaped and partitioned like Y_r, as for jg_linear_backward); db_sh: `ways` device buffers
  * of JG_Q_B_LEN floats, partitioned like the bias (4-way: the slice of a column half is summed over both row
  * halves and written to both ranks of that column).  Sums are accumulated in double in a fixed order and rounded
- * once: the same bits on every run.  Any plan (op, dtype): only the Y partition matters.  Needs no workspace;
- * asynchronous on the context's stream.
+ * once: the same bits on every run.  Any plan (op, dtype): only the Y partition matters.
+ * workspace (optional; 8-byte aligned device buffer): with JG_Q_BIAS_BACKWARD_WORKSPACE_BYTES bytes the rows are
+ * summed in ranges by several workgroups per column strip (partial sums in double, added in a fixed order by a
+ * second small kernel), which takes the pass from 3 to about 6 TB/s; with NULL, or less room, one workgroup per
+ * strip sums all rows.  The result is within half an FP32 unit of the exact sum either way.  Asynchronous on the
+ * context's stream.
  * Errors: JG_E_NULL, JG_E_ALIGN, JG_E_HIP. */
-int jg_bias_backward(const jg_plan* plan, const float* const* dy_sh, float* const* db_sh);
+int jg_bias_backward(const jg_plan* plan, const float* const* dy_sh, float* const* db_sh, void* workspace,
+                     size_t workspace_bytes);
 
 /* query (data).  Inverse of jg_shard for Y: writes the M x N global result (device,
  * leading dimension ld >= N) from the per-rank Y shards.  Bit-exact.

@@ -43,7 +43,8 @@ JG_T_X, JG_T_W, JG_T_B, JG_T_Y, JG_T_X_F32, JG_T_W_F32 = 0, 1, 2, 3, 4, 5
  JG_Q_Y_ROWS, JG_Q_Y_COLS, JG_Q_B_LEN, JG_Q_RESIDENT_BYTES_RANK, JG_Q_GEMM_LAUNCHES,
  JG_Q_BACKWARD_WORKSPACE_BYTES, JG_Q_BACKWARD_FLOPS_TOTAL, JG_Q_BACKWARD_GEMM_LAUNCHES,
  JG_Q_TAIL_SCRATCH_BYTES, JG_Q_BACKWARD_TAIL_SCRATCH_BYTES, JG_Q_X_SHARD_BYTES, JG_Q_W_SHARD_BYTES,
- JG_Q_CHAIN_WORKSPACE_BYTES, JG_Q_X_F32_SHARDS_BYTES, JG_Q_NORM_BACKWARD_WORKSPACE_BYTES) = range(24)
+ JG_Q_CHAIN_WORKSPACE_BYTES, JG_Q_X_F32_SHARDS_BYTES, JG_Q_NORM_BACKWARD_WORKSPACE_BYTES,
+ JG_Q_BIAS_BACKWARD_WORKSPACE_BYTES) = range(25)
 (JG_KERNEL_GEMM, JG_KERNEL_WEIGHT_COPY, JG_KERNEL_COMBINE, JG_KERNEL_SHARD,
  JG_KERNEL_GATHER, JG_KERNEL_GEMM_DX, JG_KERNEL_GEMM_DW, JG_KERNEL_JOIN, JG_KERNEL_NORM, JG_KERNEL_REDUCE,
  JG_KERNEL_COUNT) = range(11)
@@ -111,7 +112,7 @@ _lib.jg_mixing_backward.restype = ctypes.c_int
 _lib.jg_token_mixing_backward.argtypes = ([_vp, _vp, _vpp, _vp, ctypes.c_double] + [_vpp] * 14 +
                                           [_vp, _vp, _vp, _vp, ctypes.c_size_t])
 _lib.jg_token_mixing_backward.restype = ctypes.c_int
-_lib.jg_bias_backward.argtypes = [_vp, _vpp, _vpp]
+_lib.jg_bias_backward.argtypes = [_vp, _vpp, _vpp, _vp, ctypes.c_size_t]
 _lib.jg_bias_backward.restype = ctypes.c_int
 _lib.jg_gather.argtypes = [_vp, _vpp, _vp, ctypes.c_int64]
 _lib.jg_gather_as.argtypes = [_vp, ctypes.c_int, _vpp, _vp, ctypes.c_int64]
@@ -272,8 +273,9 @@ def jg_token_mixing_backward(first, second, x_ptrs, gamma_ptr, eps: float, xn_pt
                                          workspace_bytes), "jg_token_mixing_backward")
 
 
-def jg_bias_backward(plan, dy_ptrs, db_ptrs) -> None:
-    _raise(_lib.jg_bias_backward(plan, _ptr_array(dy_ptrs), _ptr_array(db_ptrs)), "jg_bias_backward")
+def jg_bias_backward(plan, dy_ptrs, db_ptrs, workspace_ptr=None, workspace_bytes: int = 0) -> None:
+    _raise(_lib.jg_bias_backward(plan, _ptr_array(dy_ptrs), _ptr_array(db_ptrs), workspace_ptr or None, workspace_bytes),
+           "jg_bias_backward")
 
 
 def jg_gather(plan, y_ptrs, global_y_ptr: int, ld: int) -> None:

@@ -582,7 +582,12 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
         break;
     case JG_Q_CHAIN_WORKSPACE_BYTES: *out = (int64_t)(plan->ws_bytes + plan->chain_bytes); break;
     case JG_Q_NORM_BACKWARD_WORKSPACE_BYTES:
-        *out = (int64_t)(round_up(16 * (size_t)plan->xr, kWsAlign) * d.ways);
+        // mean and 1 / sqrt(var + eps) of every row, then the partial column sums of the dgamma / dbeta kernel
+        *out = (int64_t)(round_up(16 * (size_t)plan->xr, kWsAlign) * d.ways +
+                         jg::norm_cols_workspace_bytes((int)plan->xr, (int)plan->xc, d.ways == 4 ? 2 : d.ways));
+        break;
+    case JG_Q_BIAS_BACKWARD_WORKSPACE_BYTES:
+        *out = (int64_t)jg::colsum_workspace_bytes((int)plan->yr, (int)plan->yc, d.ways == 4 ? 2 : d.ways);
         break;
     case JG_Q_X_F32_SHARDS_BYTES:
         *out = (int64_t)(round_up(4 * (size_t)plan->xr * (size_t)plan->xc, kWsAlign) * d.ways);
@@ -1642,8 +1647,11 @@ static int layernorm_backward_impl(const jg_plan* plan, const float* const* x_sh
             o.dbeta = dbeta ? dbeta + (int64_t)j * plan->xc : nullptr;
         }
     }
+    // behind the rows' statistics: room for the column sums' partial results, used when it is there
+    char* part = static_cast<char*>(workspace) + stats_bytes * d.ways;
+    const size_t part_bytes = workspace_bytes - stats_bytes * d.ways;
     ScopedTimer t(c, JG_KERNEL_NORM);
-    return HIP_OK(jg::launch_norm_bwd(g, cg, c->stream)) ? JG_OK : JG_E_HIP;
+    return HIP_OK(jg::launch_norm_bwd(g, cg, c->stream, part, part_bytes)) ? JG_OK : JG_E_HIP;
 }
 
 int jg_layernorm_backward(const jg_plan* plan, const float* const* x_sh, const float* gamma, double eps,
@@ -1654,7 +1662,8 @@ int jg_layernorm_backward(const jg_plan* plan, const float* const* x_sh, const f
                                    nullptr);
 }
 
-int jg_bias_backward(const jg_plan* plan, const float* const* dy_sh, float* const* db_sh)
+int jg_bias_backward(const jg_plan* plan, const float* const* dy_sh, float* const* db_sh, void* workspace,
+                     size_t workspace_bytes)
 {
     if (!plan || !plan->ctx) return JG_E_NULL;
     const jg_linear_desc& d = plan->d;
@@ -1686,8 +1695,9 @@ int jg_bias_backward(const jg_plan* plan, const float* const* dy_sh, float* cons
             g.o[r].dst[0] = db_sh[r];
         }
     }
+    if (workspace && !aligned(workspace, 8)) return JG_E_ALIGN;
     ScopedTimer t(c, JG_KERNEL_REDUCE);
-    return HIP_OK(jg::launch_colsum_group(g, c->stream)) ? JG_OK : JG_E_HIP;
+    return HIP_OK(jg::launch_colsum_group(g, c->stream, workspace, workspace ? workspace_bytes : 0)) ? JG_OK : JG_E_HIP;
 }
 
 int jg_layernorm_forward(const jg_plan* plan, const float* const* x_sh, const float* gamma, const float* beta,
@@ -1867,7 +1877,7 @@ static int mlp_backward_impl(const jg_plan* first, const jg_plan* second, const 
     // second layer: dH = dY W2, dW2 = dY^T H, db2 = column sums of dY
     int rc = jg_linear_backward(second, h_sh, w2_sh, dy_sh, dh_sh, dw2_sh, workspace, workspace_bytes);
     if (rc != JG_OK) return rc;
-    rc = jg_bias_backward(second, dy_sh, db2_sh);
+    rc = jg_bias_backward(second, dy_sh, db2_sh, workspace, workspace_bytes);
     if (rc != JG_OK) return rc;
     // the pre-activation, which the forward does not keep: A = X W1^T + b1 once more (mixed precision: from the
     // FP32 X and W1 this call is given, rounded as the forward rounds them)
@@ -1919,7 +1929,7 @@ static int mlp_backward_impl(const jg_plan* first, const jg_plan* second, const 
     // first layer: dA W1 (into dx_sh), dW1 = dA^T X, db1 = column sums of dA
     rc = jg_linear_backward(first, x_sh, w1_sh, da_sh, dx_sh, dw1_sh, workspace, workspace_bytes);
     if (rc != JG_OK) return rc;
-    rc = jg_bias_backward(first, da_sh, db1_sh);
+    rc = jg_bias_backward(first, da_sh, db1_sh, workspace, workspace_bytes);
     if (rc != JG_OK || !with_skip) return rc;
     // the skip connection: dX = dY + dA W1 (dY_r and dX_r are both shaped like X_r)
     jg::CombineGroup cb;
@@ -2159,7 +2169,7 @@ int jg_token_mixing_backward(const jg_plan* first, const jg_plan* second, const 
     // transposed layer: dXn = W1 dA^T, dW1 = Xn dA, db1 = column sums of dA
     rc = jg_linear_backward(first, xn_sh, w1_sh, da_sh, dxn_sh, dw1_sh, workspace, workspace_bytes);
     if (rc != JG_OK) return rc;
-    rc = jg_bias_backward(first, da_sh, db1_sh);
+    rc = jg_bias_backward(first, da_sh, db1_sh, workspace, workspace_bytes);
     if (rc != JG_OK) return rc;
     // the norm's backward, with the block's skip connection added before dX is rounded
     return layernorm_backward_impl(first, x_sh, gamma, eps, dxn_sh, dx_sh, dgamma, dbeta, workspace, workspace_bytes,

@@ -359,27 +359,34 @@ struct NormBwdColsGroup {
     NormBwdColsOut o[kMaxBlocks];
     int nout;
     int rows, cols;
+    // the rows of every source block are cut into `parts` ranges of part_rows (one workgroup per strip and range, as
+    // in the bias gradient: a strip per workgroup alone leaves half the chip idle); parts > 1: every workgroup leaves
+    // its sums in `partial` (nout x parts x cols pairs of doubles) and layernorm_bwd_cols_join_f32 adds them in order
+    int parts, part_rows;
+    double* partial;
 };
 
-constexpr int NORM_STRIP = 32;
+constexpr int NORM_STRIP = 32;            // columns per workgroup of the column kernel
+constexpr int NORM_COLS_THREADS = 256;
 
-// grid: x = column strip, y = output (channel block).  VEC (cols % 4 == 0, 16-byte aligned sources): four columns
-// per thread, 8 lanes across the strip, 32 row lanes; otherwise one column per thread, 8 row lanes.
+// grid: x = column strip, y = output (channel block), z = row range.  VEC (cols % 4 == 0, 16-byte aligned sources):
+// four columns per thread, 8 lanes across the strip, 32 row lanes; otherwise one column per thread, 8 row lanes.
 template <bool VEC>
-__global__ __launch_bounds__(NORM_THREADS) void layernorm_bwd_cols_f32(const NormBwdColsGroup g)
+__global__ __launch_bounds__(NORM_COLS_THREADS) void layernorm_bwd_cols_f32(const NormBwdColsGroup g)
 {
     constexpr int LANES = VEC ? NORM_STRIP / 4 : NORM_STRIP;
-    constexpr int ROW_LANES = NORM_THREADS / LANES;
+    constexpr int ROW_LANES = NORM_COLS_THREADS / LANES;
     constexpr int W = VEC ? 4 : 1;
     __shared__ double pg[ROW_LANES][NORM_STRIP + 1], pb[ROW_LANES][NORM_STRIP + 1];
     const NormBwdColsOut& O = g.o[blockIdx.y];
     const int tid = threadIdx.x, cl = tid % LANES, rl = tid / LANES;
     const int col = blockIdx.x * NORM_STRIP + cl * W;
     double sg[4] = {0.0, 0.0, 0.0, 0.0}, sb[4] = {0.0, 0.0, 0.0, 0.0};
+    const int r_begin = blockIdx.z * g.part_rows, r_end = min(g.rows, r_begin + g.part_rows);
     if (col < g.cols) {
         for (int b = 0; b < O.nsrc; ++b) {
 #pragma unroll 2
-            for (int r = rl; r < g.rows; r += ROW_LANES) {
+            for (int r = r_begin + rl; r < r_end; r += ROW_LANES) {
                 const double mu = O.stats[b][2 * (int64_t)r], rstd = O.stats[b][2 * (int64_t)r + 1];
                 if (VEC) {
                     const vf4 dv = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(O.dy[b] + (int64_t)r * g.cols + col));
@@ -415,13 +422,52 @@ __global__ __launch_bounds__(NORM_THREADS) void layernorm_bwd_cols_f32(const Nor
                 tg += pg[r][tid];
                 tb += pb[r][tid];
             }
-            if (O.dgamma) O.dgamma[c] = (float)tg;
-            if (O.dbeta) O.dbeta[c] = (float)tb;
+            if (g.parts > 1) {
+                double* p = g.partial + 2 * (((int64_t)blockIdx.y * g.parts + blockIdx.z) * g.cols + c);
+                p[0] = tg;
+                p[1] = tb;
+            } else {
+                if (O.dgamma) O.dgamma[c] = (float)tg;
+                if (O.dbeta) O.dbeta[c] = (float)tb;
+            }
         }
     }
 }
 
-inline hipError_t launch_norm_bwd(const NormBwdGroup& g, const NormBwdColsGroup& cg, hipStream_t stream)
+// Second stage of the column sums: the parts of column c in ascending order, rounded once.
+__global__ __launch_bounds__(NORM_COLS_THREADS) void layernorm_bwd_cols_join_f32(const NormBwdColsGroup g)
+{
+    const NormBwdColsOut& O = g.o[blockIdx.y];
+    const int c = blockIdx.x * NORM_COLS_THREADS + threadIdx.x;
+    if (c >= g.cols) return;
+    const double* p = g.partial + 2 * ((int64_t)blockIdx.y * g.parts * g.cols + c);
+    double tg = 0.0, tb = 0.0;
+    for (int k = 0; k < g.parts; ++k) {
+        tg += p[2 * (int64_t)k * g.cols];
+        tb += p[2 * (int64_t)k * g.cols + 1];
+    }
+    if (O.dgamma) O.dgamma[c] = (float)tg;
+    if (O.dbeta) O.dbeta[c] = (float)tb;
+}
+
+// Row ranges of the column kernel and the bytes of their partial sums (0: one range).
+inline int norm_col_parts(int rows, int cols, int nout)
+{
+    const int64_t strips = (int64_t)((cols + NORM_STRIP - 1) / NORM_STRIP) * nout;
+    int parts = strips > 0 ? (int)((1024 + strips - 1) / strips) : 1;
+    if (parts > rows / 64) parts = rows / 64;
+    if (parts > 64) parts = 64;
+    return parts < 1 ? 1 : parts;
+}
+inline size_t norm_cols_workspace_bytes(int rows, int cols, int nout)
+{
+    const int parts = norm_col_parts(rows, cols, nout);
+    return parts > 1 ? (size_t)nout * parts * cols * 2 * sizeof(double) : 0;
+}
+
+// partial / partial_bytes (may be null): room for the column kernel's partial sums (norm_cols_workspace_bytes)
+inline hipError_t launch_norm_bwd(const NormBwdGroup& g, NormBwdColsGroup cg, hipStream_t stream, void* partial = nullptr,
+                                  size_t partial_bytes = 0)
 {
     if (g.cols <= 0 || g.nblocks <= 0) return hipSuccess;
     if (g.rows > 0 && norm_bwd_rows_fit(g)) {
@@ -440,9 +486,17 @@ inline hipError_t launch_norm_bwd(const NormBwdGroup& g, const NormBwdColsGroup&
     for (int i = 0; i < cg.nout; ++i)
         for (int b = 0; b < cg.o[i].nsrc; ++b)
             if (((uintptr_t)cg.o[i].x[b] | (uintptr_t)cg.o[i].dy[b]) & 15) vec = false;
-    const dim3 cgrid((cg.cols + NORM_STRIP - 1) / NORM_STRIP, cg.nout, 1);
-    if (vec) hipLaunchKernelGGL(layernorm_bwd_cols_f32<true>, cgrid, dim3(NORM_THREADS), 0, stream, cg);
-    else hipLaunchKernelGGL(layernorm_bwd_cols_f32<false>, cgrid, dim3(NORM_THREADS), 0, stream, cg);
+    cg.parts = norm_col_parts(cg.rows, cg.cols, cg.nout);
+    if (!partial || partial_bytes < norm_cols_workspace_bytes(cg.rows, cg.cols, cg.nout)) cg.parts = 1;
+    cg.part_rows = cg.parts > 1 ? ((cg.rows + cg.parts - 1) / cg.parts + 31) / 32 * 32 : cg.rows;
+    if (cg.parts > 1) cg.parts = (cg.rows + cg.part_rows - 1) / cg.part_rows;
+    cg.partial = static_cast<double*>(partial);
+    const dim3 cgrid((cg.cols + NORM_STRIP - 1) / NORM_STRIP, cg.nout, cg.parts);
+    if (vec) hipLaunchKernelGGL(layernorm_bwd_cols_f32<true>, cgrid, dim3(NORM_COLS_THREADS), 0, stream, cg);
+    else hipLaunchKernelGGL(layernorm_bwd_cols_f32<false>, cgrid, dim3(NORM_COLS_THREADS), 0, stream, cg);
+    if (cg.parts > 1)
+        hipLaunchKernelGGL(layernorm_bwd_cols_join_f32, dim3((cg.cols + NORM_COLS_THREADS - 1) / NORM_COLS_THREADS, cg.nout, 1),
+                           dim3(NORM_COLS_THREADS), 0, stream, cg);
     return hipGetLastError();
 }
 

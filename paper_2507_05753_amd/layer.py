@@ -163,7 +163,11 @@ class JigsawLinear:
         if getattr(self, "db", None) is None:
             self.db = [torch.empty((self.query(jg.JG_Q_B_LEN, r),), dtype=torch.float32, device=self.dev)
                        for r in range(self.ways)]
-        jg.jg_bias_backward(self.plan, [t.data_ptr() for t in self.dy], [t.data_ptr() for t in self.db])
+        if getattr(self, "db_ws", None) is None:
+            self.db_ws_bytes = self.query(jg.JG_Q_BIAS_BACKWARD_WORKSPACE_BYTES)
+            self.db_ws = torch.empty((max(self.db_ws_bytes, 8),), dtype=torch.uint8, device=self.dev)
+        jg.jg_bias_backward(self.plan, [t.data_ptr() for t in self.dy], [t.data_ptr() for t in self.db],
+                            self.db_ws.data_ptr() if self.db_ws_bytes else None, self.db_ws_bytes)
         return self.db
 
     def gather_dx(self):

@@ -97,7 +97,7 @@ int main()
                         EXPECT(jg_linear_backward(plan, in, in, in, out, out, nullptr, 0) < 0);
                         EXPECT(jg_shard(plan, JG_T_X, &x, 1, out) < 0);
                         EXPECT(jg_gather(plan, in, &x, 1) < 0);
-                        EXPECT(jg_bias_backward(plan, in, out) < 0);
+                        EXPECT(jg_bias_backward(plan, in, out, nullptr, 0) < 0);
                         EXPECT(jg_layernorm_forward(plan, in, nullptr, nullptr, 1e-5, out) < 0);
                         EXPECT(jg_mlp_forward(plan, plan, in, in, in, in, in, out, out, nullptr, 0) < 0);
                         jg_plan_destroy(plan);

@@ -433,9 +433,9 @@ def test_bias_backward_checks_its_arguments():
     lib = jg.raw()
     arr = (ctypes.c_void_p * 2)(256, 512)
     pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
-    assert lib.jg_bias_backward(None, pp, pp) == jg.JG_E_NULL
+    assert lib.jg_bias_backward(None, pp, pp, None, 0) == jg.JG_E_NULL
     a = jg.jg_plan_create(None, 64, 32, 48, 2, True)
-    assert lib.jg_bias_backward(a, pp, pp) == jg.JG_E_NULL          # a plan without a context
+    assert lib.jg_bias_backward(a, pp, pp, None, 0) == jg.JG_E_NULL          # a plan without a context
     jg.jg_plan_destroy(a)
 
 

@@ -211,6 +211,32 @@ def test_bias_gradient_matches_oracle(jg, ctx, ways, M, N):
 
 
 @pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,N", [(4098, 200), (2 * 2049, 72), (640, 4320), (126, 64)])
+def test_bias_gradient_with_and_without_workspace(jg, ctx, ways, M, N):
+    """With a workspace the rows are summed in ranges by several workgroups per strip (the last range ragged), without
+    one a single workgroup per strip walks all rows: both within half a unit of the exact sum."""
+    from paper_2507_05753_amd.layer import JigsawLinear
+    dY = np.abs(inputs.matrix(49, M, N, "R")) + np.float32(0.25)
+    with JigsawLinear(M, 8, N, ways, bias=True, ctx=ctx) as L:
+        L.shard_dy(dev(dY))
+        need = L.query(jg.JG_Q_BIAS_BACKWARD_WORKSPACE_BYTES)
+        assert (need > 0) == (M // (2 if ways == 4 else 1) >= 128)
+        ws = torch.full((max(need, 8),), 0xFF, dtype=torch.uint8, device="cuda")
+        p = lambda ts: [t.data_ptr() for t in ts]
+        out = {}
+        for name, (ptr, size) in dict(none=(None, 0), full=(ws.data_ptr(), need), short=(ws.data_ptr(), max(need - 8, 0))).items():
+            db = [torch.full((L.query(jg.JG_Q_B_LEN, r),), float("nan"), device="cuda") for r in range(ways)]
+            jg.jg_bias_backward(L.plan, p(L.dy), p(db), ptr, size)
+            out[name] = [t.cpu().numpy() for t in db]
+            check_bias(out[name], dY, ways)
+        assert all(np.array_equal(a, b) for a, b in zip(out["none"], out["short"]))       # too little room: one stage
+        if need:
+            with pytest.raises(jg.JigsawError) as e:
+                jg.jg_bias_backward(L.plan, p(L.dy), p(db), ws.data_ptr() + 4, need)
+            assert e.value.status == jg.JG_E_ALIGN
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
 def test_bias_gradient_on_lattice_data_and_transposed_plans(jg, ctx, ways):
     M, N = 258, 136
     dY = inputs.matrix(48, M, N, "L")

@@ -409,7 +409,7 @@ def test_whole_mixing_block(jg, ctx, ways):
 # ---------------------------------------------------------------------------------------------
 # the layer norm's gradients
 # ---------------------------------------------------------------------------------------------
-def run_norm_backward(jg, ctx, X, gamma, dY, ways, op=None, want_params=True):
+def run_norm_backward(jg, ctx, X, gamma, dY, ways, op=None, want_params=True, minimal_workspace=False):
     from paper_2507_05753_amd.layer import JigsawLinear
     T, C = X.shape
     kw = dict(op=jg.JG_OP_XTW) if op == "xtw" else {}
@@ -422,6 +422,8 @@ def run_norm_backward(jg, ctx, X, gamma, dY, ways, op=None, want_params=True):
         dg = torch.full((C,), float("nan"), device="cuda") if want_params else None
         db = torch.full((C,), float("nan"), device="cuda") if want_params else None
         need = L.query(jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES)
+        if minimal_workspace:       # the rows' statistics only: the column sums then run one workgroup per strip
+            need = ways * ((16 * L.query(jg.JG_Q_X_ROWS) + 255) // 256 * 256)
         ws = torch.full((need,), 0xFF, dtype=torch.uint8, device="cuda")
         p = lambda ts: [t.data_ptr() for t in ts]
         g = dev(gamma) if gamma is not None else None
@@ -456,6 +458,21 @@ def test_layernorm_backward_matches_oracle(jg, ctx, ways, T, C):
     gamma, _ = affine(131, C)
     dY = inputs.matrix(132, T, C, "R")
     check_norm_backward(X, gamma, dY, ways, run_norm_backward(jg, ctx, X, gamma, dY, ways))
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("T,C", [(4098, 200), (2 * 2049, 72), (640, 4320)])
+def test_layernorm_backward_column_sums_in_row_ranges(jg, ctx, ways, T, C):
+    """Enough rows for the column sums to run in several row ranges (the last one ragged), with the whole workspace
+    and with the statistics' share only: both inside the bar of a sum taken in double and rounded once."""
+    X = (inputs.matrix(136, T, C, "R") + np.float32(0.125)).astype(np.float32)
+    gamma, _ = affine(137, C)
+    dY = np.abs(inputs.matrix(138, T, C, "R")) + np.float32(0.25)        # same-sign: FP32 sums would not do
+    full = run_norm_backward(jg, ctx, X, gamma, dY, ways)
+    small = run_norm_backward(jg, ctx, X, gamma, dY, ways, minimal_workspace=True)
+    check_norm_backward(X, gamma, dY, ways, full)
+    check_norm_backward(X, gamma, dY, ways, small)
+    assert np.array_equal(full[0], small[0])                              # dX does not depend on the workspace
 
 
 @pytest.mark.parametrize("ways", [1, 4])
