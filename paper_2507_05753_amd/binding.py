@@ -126,10 +126,18 @@ for _n in ("jg_init", "jg_plan_create", "jg_plan_query", "jg_shard", "jg_linear_
 
 
 def _ptr_array(ptrs):
-    if ptrs is None:
-        return None
+    if ptrs is None or isinstance(ptrs, _vpp):
+        return ptrs
     arr = (ctypes.c_void_p * len(ptrs))(*[int(p) if p else None for p in ptrs])
-    return ctypes.cast(arr, _vpp)
+    out = ctypes.cast(arr, _vpp)
+    out._keep = arr         # the array lives as long as the pointer to it
+    return out
+
+
+def ptr_array(ptrs):
+    """A host array of device pointers, marshalled once: every shard argument accepts the result in place of a
+    sequence, which saves the conversion in a loop that passes the same buffers again and again."""
+    return _ptr_array(ptrs)
 
 
 def _raise(status: int, where: str):

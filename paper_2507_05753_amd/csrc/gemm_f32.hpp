@@ -658,12 +658,14 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_f32_stream(const GemmGro
     }
 }
 
-// Second kernel of a launch whose tail was split: workgroup t adds the runs of tail tile t in
-// ascending k order, then the addend and the bias, applies the activation, adds the residual and
-// stores the tile of C.
+// Second kernel of a launch whose tail was split: kJoinSlices workgroups per tail tile, each with a band of 16
+// of its rows, add the tile's runs in ascending k order, then the addend and the bias, apply the activation, add
+// the residual and store C.  (One workgroup per tile took 40 us on a small problem cut into eight runs per tile:
+// too few loads in flight.)
+constexpr int kJoinSlices = 8;
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_f32_join(const GemmGroup g)
 {
-    const int t = blockIdx.x;
+    const int t = blockIdx.x / kJoinSlices, slice = blockIdx.x % kJoinSlices;
     const int nkt = (g.K + BK - 1) / BK;
     const TileCoord tc = decode_tile(g, g.whole_tiles + t);
     const GemmProblem& P = g.p[tc.prob];
@@ -671,9 +673,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_f32_join(const GemmGroup g)
     const int w_first = run_of(g, it0), w_last = run_of(g, it0 + nkt - 1);
     const float* __restrict__ addend = P.addend;
     const float* __restrict__ bias = P.bias;
+    constexpr int kPieces = BM * BN / 4 / kJoinSlices;      // 4-element pieces of a slice
 #pragma unroll 1
-    for (int u = 0; u < BM * BN / 4 / GEMM_THREADS; ++u) {
-        const int idx = threadIdx.x + GEMM_THREADS * u;   // one 4-element piece of a tile row
+    for (int u = 0; u < kPieces / GEMM_THREADS; ++u) {
+        const int idx = slice * kPieces + threadIdx.x + GEMM_THREADS * u;   // one 4-element piece of a tile row
         const int r = idx / (BN / 4), c = (idx % (BN / 4)) * 4;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int w = w_first; w <= w_last; ++w) {
@@ -777,7 +780,9 @@ inline void launch_gemm_layout(const GemmGroup& g, bool stream_ok, hipStream_t s
 // ------------------------------------------------------------------------------------------
 // Host side
 // ------------------------------------------------------------------------------------------
-constexpr int kMinRunSlabs = 32;   // a run shorter than this is not worth its start-up and its scratch tile
+constexpr int kMinRunSlabs = 32;   // a run shorter than this is not worth its start-up and its scratch tile ...
+constexpr int kMinRunSlabsFewRounds = 8;   // ... unless the launch has few rounds of tiles, where the last one weighs more,
+constexpr int kMinRunSlabsSubRound = 4;    // ... or not even half a round: a small problem, cut up to fill the chip
 constexpr int kRunOverheadSlabs = 6;   // start-up, scratch store and join of a run, in slab times
 
 // How a launch of `total` tiles with `nkt` slabs each is divided on a chip that holds `slots`
@@ -793,7 +798,11 @@ inline TailSplit plan_tail(int64_t total, int nkt, int slots)
     const int64_t rest = total % slots;
     if (rest == 0) return t;
     const int64_t iters = rest * nkt;
-    const int64_t runs = iters / kMinRunSlabs < slots ? iters / kMinRunSlabs : slots;
+    const int min_slabs = 2 * total < slots ? kMinRunSlabsSubRound : total <= 4 * (int64_t)slots ? kMinRunSlabsFewRounds : kMinRunSlabs;
+    // (a problem smaller than the chip gets one run per compute unit at most: a workgroup alone on its unit runs
+    // nearly twice as fast, and half as many scratch tiles pass through the join)
+    const int64_t cap = 2 * total < slots ? slots / 2 : slots;
+    const int64_t runs = iters / min_slabs < cap ? iters / min_slabs : cap;
     if (runs <= rest) return t;                       // no finer than whole tiles: nothing gained
     // Estimated time of the last round either way, in slab times at the two-workgroups-per-CU rate
     // (a workgroup alone on its CU runs about 1.8 times as fast); split only for a saving of at least
@@ -860,7 +869,7 @@ inline hipError_t launch_gemm_group(GemmGroup& g, int layout, hipStream_t stream
 inline hipError_t launch_gemm_join(const GemmGroup& g, hipStream_t stream)
 {
     const int tail_tiles = g.nprob * g.tiles_m * g.tiles_n - g.whole_tiles;
-    hipLaunchKernelGGL(gemm_f32_join, dim3((unsigned)tail_tiles), dim3(GEMM_THREADS), 0, stream, g);
+    hipLaunchKernelGGL(gemm_f32_join, dim3((unsigned)tail_tiles * kJoinSlices), dim3(GEMM_THREADS), 0, stream, g);
     return hipGetLastError();
 }
 

@@ -85,10 +85,14 @@ class JigsawLinear:
     def forward(self, residual=None, activation: int = jg.JG_ACT_NONE):
         """Y_r = act(X W^T + b)_r (+ residual_r); ``residual``: per-rank tensors shaped like the Y shards."""
         if residual is None and activation == jg.JG_ACT_NONE:
-            jg.jg_linear_forward(self.plan, [t.data_ptr() for t in self.x], [t.data_ptr() for t in self.w],
-                                 [t.data_ptr() for t in self.b] if self.bias else None,
-                                 [t.data_ptr() for t in self.y],
-                                 self.ws.data_ptr() if self.ws_bytes else None, self.ws_bytes)
+            key = tuple(t.data_ptr() for t in self.x + self.w + self.y) + (self.ws.data_ptr(),)
+            if getattr(self, "_fwd_key", None) != key:      # the shard buffers' addresses, marshalled once
+                self._fwd_key = key
+                self._fwd_args = (jg.ptr_array([t.data_ptr() for t in self.x]), jg.ptr_array([t.data_ptr() for t in self.w]),
+                                  jg.ptr_array([t.data_ptr() for t in self.b]) if self.bias else None,
+                                  jg.ptr_array([t.data_ptr() for t in self.y]),
+                                  self.ws.data_ptr() if self.ws_bytes else None, self.ws_bytes)
+            jg.jg_linear_forward(self.plan, *self._fwd_args)
             return
         if residual is not None:
             assert len(residual) == self.ways and all(r.shape == y.shape and r.is_contiguous()

@@ -221,9 +221,17 @@ def test_tail_split_accounting():
     p = jg.jg_plan_create(None, 100, 100, 100, 1)
     assert q(p, jg.JG_Q_TAIL_SCRATCH_BYTES) == 0
     jg.jg_plan_destroy(p)
-    # few long tiles: 3 x 3 tiles of 65 slabs -> 585 / 32 = 18 runs
+    # a problem smaller than the chip (less than half a round of tiles): runs of four slabs fill it.
+    # 1000^3, one rank: 8 x 8 tiles of 32 slabs -> one run per compute unit; 4-way: 4 x 16 tiles of 16 slabs -> 256 runs
+    p = jg.jg_plan_create(None, 1000, 1000, 1000, 1)
+    assert q(p, jg.JG_Q_TAIL_SCRATCH_BYTES) == 256 * 2 * tile
+    jg.jg_plan_destroy(p)
+    p = jg.jg_plan_create(None, 1000, 1000, 1000, 4)
+    assert q(p, jg.JG_Q_TAIL_SCRATCH_BYTES) == 256 * 2 * tile
+    jg.jg_plan_destroy(p)
+    # few long tiles: 3 x 3 tiles of 65 slabs -> 585 / 4 = 146 runs
     p = jg.jg_plan_create(None, 300, 2080, 260, 1)
-    assert q(p, jg.JG_Q_TAIL_SCRATCH_BYTES) == 18 * 2 * tile
+    assert q(p, jg.JG_Q_TAIL_SCRATCH_BYTES) == 146 * 2 * tile
     # ... and in the backward pass: dX 3 x 17 tiles of 9 slabs (whole), dW 3 x 17 tiles of 10 slabs (whole)
     assert q(p, jg.JG_Q_BACKWARD_TAIL_SCRATCH_BYTES) == 0
     jg.jg_plan_destroy(p)

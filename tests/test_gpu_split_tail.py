@@ -75,6 +75,30 @@ def test_forward(jg, ctx, ways, M, K, N):
     assert np.array_equal(Yl.astype(np.float64), oracle.linear(Xl, Wl, bl))
 
 
+# Problems smaller than the chip (less than half a round of tiles): every tile's K loop is cut into short runs so
+# that all compute units get work.  1000^3 is the second configuration of the workload table; the others put the
+# run boundaries on a ragged last slab (K = 516 = 16 slabs + 4), on runs that span two tiles, and on edge tiles.
+SMALL = [(1000, 1000, 1000), (384, 516, 256), (130, 1188, 258), (640, 260, 136)]
+
+
+@pytest.mark.parametrize("ways", [1, 2, 4])
+@pytest.mark.parametrize("M,K,N", SMALL)
+def test_small_problems_fill_the_chip(jg, ctx, ways, M, K, N):
+    X, W, b = inputs.layer_inputs(51, M, K, N, "R", bias=True)
+    Y, split = forward(jg, ctx, X, W, b, ways, jg.JG_TAIL_SPLIT)
+    if (M, K, N) == (1000, 1000, 1000):
+        assert split, "64 tiles of 16 or 32 slabs on 256 compute units: meant to be cut into runs"
+    S = oracle.magnitude(X, W, b)
+    err = np.abs(Y.astype(np.float64) - oracle.linear(X, W, b))
+    assert np.all(err <= TOL * S), f"max err/S = {(err / S).max():.3e}"
+    Y2, _ = forward(jg, ctx, X, W, b, ways, jg.JG_TAIL_SPLIT)
+    assert np.array_equal(Y, Y2)                       # the same bits on every run
+    Xl, Wl, bl = inputs.layer_inputs(52, M, K, N, "L", bias=True)
+    Yl, _ = forward(jg, ctx, Xl, Wl, bl, ways, jg.JG_TAIL_SPLIT)
+    Yw, _ = forward(jg, ctx, Xl, Wl, bl, ways, jg.JG_TAIL_WHOLE)
+    assert np.array_equal(Yl, Yw) and np.array_equal(Yl.astype(np.float64), oracle.linear(Xl, Wl, bl))
+
+
 @pytest.mark.parametrize("ways", [1, 2, 4])
 @pytest.mark.parametrize("K,M,N", [(4160, 136, 264), (8200, 520, 264)])
 def test_transposed_layer(jg, ctx, ways, K, M, N):

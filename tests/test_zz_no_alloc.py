@@ -46,7 +46,7 @@ def test_two_calls_in_a_row_the_second_smaller(ways):
 
 def test_split_tail_scratch_in_the_static_array():
     # a long contraction on few tiles: the planner splits the tail and its scratch tiles live in the array too
-    run_both(640, 8192, 512, 2, seed=7, bias=True, tail=jg.JG_TAIL_SPLIT)
+    run_both(640, 2048, 512, 2, seed=7, bias=True, tail=jg.JG_TAIL_SPLIT)
     run_both(258, 1024, 130, 2, seed=8, bias=False, tail=jg.JG_TAIL_SPLIT)
 
 
