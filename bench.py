@@ -814,7 +814,7 @@ def cpu_baseline(cfg, seconds, reduced_terms=0):
 # the factors are in profiles/gemm_f32_stream_forward_config3_ways4_hbm_counters.md.  Counters cannot be read
 # from inside this script, so the figure is quoted, keyed by workload, and is null for the others.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
-    ("config3", 4): 3.50e9,   # reads 3.09 GB (FETCH_SIZE / 0.5065) + writes 0.406 GB (WRITE_SIZE / 1.0018)
+    ("config3", 4): 3.76e9,   # reads 3.35 GB (FETCH_SIZE / 0.5118) + writes 0.405 GB (WRITE_SIZE / 1.0001)
     # jg::gemm_bf16_nt, whole tiles (profiles/gemm_bf16_nt_forward_config3_kernel_trace.md): reads 1.51 GB, writes 0.46 GB
     ("config3", 1, "bf16"): 1.98e9,
 }
