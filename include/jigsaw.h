@@ -402,13 +402,14 @@ int jg_token_mixing_forward(const jg_plan* first, const jg_plan* second, const f
  * JG_STATIC_WORKSPACE_BYTES bytes that lives in the library's own device memory: every GPU the library has been
  * initialised on (jg_init looks the array's address up once per device) holds one copy until the process ends.
  * The call allocates and frees nothing, on the device or through any library.
- * Limit: plans whose JG_Q_WORKSPACE_BYTES exceeds JG_STATIC_WORKSPACE_BYTES are refused with JG_E_WORKSPACE (a plan
- * made with JG_TAIL_WHOLE needs no tail scratch and fits more often); so is a context on a device index of 64 or more.
+ * Limit: plans whose JG_Q_WORKSPACE_BYTES exceeds JG_STATIC_WORKSPACE_BYTES (64 MiB) are refused with
+ * JG_E_WORKSPACE (a plan made with JG_TAIL_WHOLE needs no tail scratch and fits more often; the scratch of a small
+ * problem cut along K is up to 32 MiB); so is a context on a device index of 64 or more.
  * The array keeps the last call's contents; nothing in it has to start at zero (every partial product and scratch
  * tile is written before it is read).  All calls on one GPU share the array: two calls that overlap on that GPU -
  * from different streams, contexts or threads - race; calls on one stream are ordered and safe.
  * x_sh, w_sh, b_sh, y_sh and the other errors: as jg_linear_forward. */
-#define JG_STATIC_WORKSPACE_BYTES (32u << 20)
+#define JG_STATIC_WORKSPACE_BYTES (64u << 20)
 int jg_linear_forward_static(const jg_plan* plan, const float* const* x_sh, const float* const* w_sh,
                              const float* const* b_sh, float* const* y_sh);
 

@@ -35,7 +35,7 @@ JG_COMBINE_FUSED, JG_COMBINE_SEPARATE = 0, 1
 JG_WEIGHTS_COPY, JG_WEIGHTS_DIRECT = 0, 1
 JG_TAIL_SPLIT, JG_TAIL_WHOLE = 0, 1
 JG_ACC_LEVELS, JG_ACC_SINGLE = 0, 1
-JG_STATIC_WORKSPACE_BYTES = 32 << 20
+JG_STATIC_WORKSPACE_BYTES = 64 << 20
 JG_ACT_NONE, JG_ACT_GELU = 0, 1
 JG_T_X, JG_T_W, JG_T_B, JG_T_Y, JG_T_X_F32, JG_T_W_F32 = 0, 1, 2, 3, 4, 5
 (JG_Q_WORKSPACE_BYTES, JG_Q_FLOPS_TOTAL, JG_Q_FLOPS_RANK, JG_Q_HBM_BYTES_ALGO,

@@ -178,3 +178,40 @@ def test_plans_that_outlive_their_context_answer_queries_only():
             jg.jg_shard(p, jg.JG_T_X, t.data_ptr(), 64, ptrs)
         assert e.value.status == jg.JG_E_NULL
         jg.jg_plan_destroy(p)
+
+
+@pytest.mark.parametrize("ways", [1, 4])
+def test_the_forward_can_be_captured_in_a_graph(ways):
+    """Callers under HIP graph capture are whom jg_linear_forward_static is for: it allocates nothing, synchronises
+    nothing and records no memset.  Captured on a side stream and replayed several times, with eager work and
+    synchronisations between the replays; every replay must give the eager run's bits."""
+    M, K, N = 1000, 1000, 1000
+    X, W, b = inputs.layer_inputs(831, M, K, N, "R", bias=True)
+    side = torch.cuda.Stream()
+    ctx = jg.jg_init(0, side.cuda_stream)
+    try:
+        with torch.cuda.stream(side):
+            L = JigsawLinear(M, K, N, ways, bias=True, ctx=ctx)
+            L.shard(dev(X), dev(W), dev(b))
+            L.forward()
+            eager = L.gather().cpu().numpy()
+        side.synchronize()
+        args = ([t.data_ptr() for t in L.x], [t.data_ptr() for t in L.w], [t.data_ptr() for t in L.b],
+                [t.data_ptr() for t in L.y])
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            jg.jg_linear_forward_static(L.plan, *args)
+        for rep in range(4):
+            for y in L.y:
+                y.fill_(float("nan"))
+            scratch = torch.randn(1 << 20, device="cuda").sum()       # eager work of the program between replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(side):
+                got = L.gather().cpu().numpy()
+            assert np.array_equal(got, eager), f"replay {rep} differs from the eager run"
+            assert torch.isfinite(scratch)
+        L.close()
+    finally:
+        jg.jg_free(ctx)
