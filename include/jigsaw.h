@@ -182,8 +182,9 @@ typedef enum jg_query {
                                            bytes: what jg_token_mixing_forward needs for its skip
                                            connection when b2 is given (rank ignored)               */
     JG_Q_NORM_BACKWARD_WORKSPACE_BYTES = 23,  /* device bytes jg_layernorm_backward wants (rank ignored): the rows'
-                                                 statistics, which it needs, and the partial column sums that let its
-                                                 dgamma / dbeta kernel use the whole chip                              */
+                                                 statistics, which it needs, and the partial column sums that let it
+                                                 read x and dy once (or, for rows it cannot take that way, let its
+                                                 dgamma / dbeta kernel use the whole chip)                             */
     JG_Q_BIAS_BACKWARD_WORKSPACE_BYTES = 24   /* device bytes that let jg_bias_backward use the whole chip (rank ignored) */
 } jg_query;
 
@@ -523,8 +524,10 @@ int jg_mixing_backward(const jg_plan* first, const jg_plan* second, const float*
  * (every channel block is summed over the ranks that hold it and written once), either may be NULL.  Evaluated in
  * double and rounded once; the column sums in a fixed order (the same bits on every run).  workspace: 256-byte
  * aligned; it must hold mean and 1 / sqrt(var + eps) of every row (`ways` times 16 bytes per row of X_r, each
- * rank's share rounded up to 256), and with JG_Q_NORM_BACKWARD_WORKSPACE_BYTES the column sums also run in row
- * ranges on the whole chip (as jg_bias_backward's).  Any plan (op, dtype): only the X partition matters.
+ * rank's share rounded up to 256).  With JG_Q_NORM_BACKWARD_WORKSPACE_BYTES one kernel reads x and dy once and
+ * leaves dx and, per band of rows, the column sums, which a second adds in order (rows of up to 6144 columns per
+ * rank, a multiple of 4, 16-byte aligned shards; otherwise, or with less workspace, a rows' kernel and a column
+ * kernel read them twice).  Any plan (op, dtype): only the X partition matters.
  * Errors: JG_E_NULL, JG_E_DTYPE (eps negative or NaN), JG_E_WORKSPACE, JG_E_ALIGN, JG_E_HIP. */
 int jg_layernorm_backward(const jg_plan* plan, const float* const* x_sh, const float* gamma, double eps,
                           const float* const* dy_sh, float* const* dx_sh, float* dgamma, float* dbeta, void* workspace,

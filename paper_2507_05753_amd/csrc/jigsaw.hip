@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 #include <mutex>
@@ -582,9 +583,11 @@ int jg_plan_query(const jg_plan* plan, int what, int rank, int64_t* out)
         break;
     case JG_Q_CHAIN_WORKSPACE_BYTES: *out = (int64_t)(plan->ws_bytes + plan->chain_bytes); break;
     case JG_Q_NORM_BACKWARD_WORKSPACE_BYTES:
-        // mean and 1 / sqrt(var + eps) of every row, then the partial column sums of the dgamma / dbeta kernel
+        // mean and 1 / sqrt(var + eps) of every row (the two-kernel form), then the partial column sums of whichever
+        // form runs
         *out = (int64_t)(round_up(16 * (size_t)plan->xr, kWsAlign) * d.ways +
-                         jg::norm_cols_workspace_bytes((int)plan->xr, (int)plan->xc, d.ways == 4 ? 2 : d.ways));
+                         std::max(jg::norm_cols_workspace_bytes((int)plan->xr, (int)plan->xc, d.ways == 4 ? 2 : d.ways),
+                                  jg::norm_fused_workspace_bytes((int)plan->xr, (int)plan->xc, d.ways)));
         break;
     case JG_Q_BIAS_BACKWARD_WORKSPACE_BYTES:
         *out = (int64_t)jg::colsum_workspace_bytes((int)plan->yr, (int)plan->yc, d.ways == 4 ? 2 : d.ways);
@@ -1642,6 +1645,7 @@ static int layernorm_backward_impl(const jg_plan* plan, const float* const* x_sh
                 o.x[b] = x_sh[r];
                 o.dy[b] = dy_sh[r];
                 o.stats[b] = stats[r];
+                o.src_block[b] = r;
             }
             o.dgamma = dgamma ? dgamma + (int64_t)j * plan->xc : nullptr;
             o.dbeta = dbeta ? dbeta + (int64_t)j * plan->xc : nullptr;

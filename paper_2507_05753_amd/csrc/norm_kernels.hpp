@@ -172,9 +172,11 @@ __global__ __launch_bounds__(NORM_THREADS) void layernorm_generic_f32(const Norm
 // xhat = (x - mu) * rstd and g = dy * gamma:
 //     dx = (g - mean(g) - xhat * mean(g * xhat)) * rstd,
 // and over the rows of all blocks that hold a channel:  dgamma = sum dy * xhat,  dbeta = sum dy.
-// Two kernels: rows (one workgroup per row, four passes over a row that stays in the caches, double
-// arithmetic as in the forward; it also leaves mu and rstd of every row in `stats`), then columns (as the
-// bias gradient's column sums: 32-column strips, double accumulators, a fixed order).
+// Two forms.  One pass (layernorm_bwd_fused_f32 and its join): a workgroup per band of rows keeps the column sums
+// of its band while it produces dx.  Two kernels, for rows that form cannot take or when the caller's workspace has
+// no room for the bands' sums: rows (one wavefront or workgroup per row, double arithmetic as in the forward; it
+// also leaves mu and rstd of every row in `stats`), then columns (as the bias gradient's column sums: 32-column
+// strips, double accumulators, a fixed order).
 // ------------------------------------------------------------------------------------------
 struct NormBwdBlock {
     const float* x;      // rows x cols, dense: the forward's input
@@ -190,6 +192,10 @@ struct NormBwdGroup {
     int nblocks;
     int rows, cols;
     double eps;
+    // the one-pass kernel (layernorm_bwd_fused_f32): rows per workgroup, workgroups per block, and where each leaves
+    // its column sums (nblocks x nbands x cols pairs of doubles: dgamma's, dbeta's), or nullptr (no column sums wanted)
+    int band_rows, nbands;
+    double* partial;
 };
 
 // grid: x = row, y = block
@@ -325,6 +331,178 @@ __global__ __launch_bounds__(NORM_THREADS) void layernorm_bwd_rows_reg_f32(const
     }
 }
 
+// One pass over x and dy that gives dx AND the column sums: a workgroup takes a band of a block's rows, RB rows at a
+// time, every thread the same columns of each (NV 16-byte vectors, T vectors apart), so a thread's column sums stay
+// in its registers (double, rows in ascending order) while the rows' own sums go through LDS.  Every element is read
+// once (12 bytes per element with the store, against 20 of the two-kernel form); the bands' sums are added in a
+// fixed order by layernorm_bwd_fused_join_f32.
+// All four sums over a row are taken in one round, before the statistics exist, about the row's first element p:
+//     S1 = sum (x - p),  S2 = sum (x - p)^2,  Sg = sum g,  Sgx = sum g (x - p)       (g = dy * gamma)
+//     mu = p + S1 / n,  var = S2 / n - (S1 / n)^2,  mean(g) = Sg / n,  mean(g xhat) = rstd (Sgx - (mu - p) Sg) / n
+// in double: p is a sample of the row, so (mu - p)^2 is of the order of var and the subtraction costs a few units
+// of 1e-16, where the definition's two-pass form has as much from its own sums.  One barrier per batch; the next
+// batch's rows are requested before the current one is worked on.
+// cols % 4 == 0, cols / 4 <= T * NV, 16-byte aligned operands.  T threads, grid: x = band, y = block.
+template <int NV, int RB, int T>
+__global__ __launch_bounds__(T) void layernorm_bwd_fused_f32(const NormBwdGroup g)
+{
+    constexpr int NW = T / 64;
+    __shared__ double part[2][NW][4 * RB];
+    // gamma lives in LDS: read from memory inside the loop it would sit behind the next batch's rows in the wave's
+    // in-order memory queue, and every batch would wait out that trip to HBM
+    __shared__ vf4 gsh[NV * T];
+    const NormBwdBlock& B = g.b[blockIdx.y];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nvec = g.cols >> 2;
+    const int r_begin = blockIdx.x * g.band_rows, r_end = min(g.rows, r_begin + g.band_rows);
+    const vf4* gamma = reinterpret_cast<const vf4*>(B.gamma);
+    const double inv_cols = 1.0 / (double)g.cols;
+    const vf4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = i * T + tid;
+        gsh[c] = (gamma && c < nvec) ? gamma[c] : vf4{1.f, 1.f, 1.f, 1.f};      // (read back by the same thread only)
+    }
+    double accg[NV][4], accb[NV][4];
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) accg[i][k] = accb[i][k] = 0.0;
+    auto fetch = [&](int r0, vf4 (&v)[RB][NV], vf4 (&d)[RB][NV], float (&p)[RB]) {
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            const bool row_ok = r0 + j < r_end;
+            const vf4* x = reinterpret_cast<const vf4*>(B.x + (int64_t)(r0 + j) * g.cols);
+            const vf4* dy = reinterpret_cast<const vf4*>(B.dy + (int64_t)(r0 + j) * g.cols);
+            p[j] = row_ok ? B.x[(int64_t)(r0 + j) * g.cols] : 0.f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int c = i * T + tid;
+                const bool ok = row_ok && c < nvec;
+                v[j][i] = ok ? __builtin_nontemporal_load(x + c) : zero;
+                d[j][i] = ok ? __builtin_nontemporal_load(dy + c) : zero;
+            }
+        }
+    };
+    vf4 v[RB][NV], d[RB][NV];
+    float pv[RB];
+    fetch(r_begin, v, d, pv);
+    int parity = 0;
+    for (int r0 = r_begin; r0 < r_end; r0 += RB, parity ^= 1) {
+        // the skip connection's rows of this batch, then the next batch's x and dy: what is needed first is asked first
+        vf4 ad[RB][NV];
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            const vf4* addp = reinterpret_cast<const vf4*>(B.add + (int64_t)(r0 + j) * g.cols);
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int c = i * T + tid;
+                ad[j][i] = (B.add && r0 + j < r_end && c < nvec) ? __builtin_nontemporal_load(addp + c) : zero;
+            }
+        }
+        vf4 vn[RB][NV], dn[RB][NV];
+        float pn[RB];
+        fetch(r0 + RB, vn, dn, pn);        // (past the band's end: nothing is read)
+        double t[4 * RB];
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            const double p = (double)pv[j];
+            double s1 = 0.0, s2 = 0.0, sg = 0.0, sgx = 0.0;
+            int own = tid;      // opaque to the compiler: hoisted out of the loop, gamma would take 4 * NV registers
+            asm volatile("" : "+v"(own));
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int c = i * T + tid;
+                if (c < nvec) {
+                    const vf4 ga = gsh[i * T + own];
+                    const double x0 = (double)v[j][i].x - p, x1 = (double)v[j][i].y - p;
+                    const double x2 = (double)v[j][i].z - p, x3 = (double)v[j][i].w - p;
+                    const double g0 = (double)d[j][i].x * (double)ga.x, g1 = (double)d[j][i].y * (double)ga.y;
+                    const double g2 = (double)d[j][i].z * (double)ga.z, g3 = (double)d[j][i].w * (double)ga.w;
+                    s1 += (x0 + x1) + (x2 + x3);
+                    s2 += (x0 * x0 + x1 * x1) + (x2 * x2 + x3 * x3);
+                    sg += (g0 + g1) + (g2 + g3);
+                    sgx += (g0 * x0 + g1 * x1) + (g2 * x2 + g3 * x3);
+                }
+            }
+            t[4 * j] = wave_sum(s1);
+            t[4 * j + 1] = wave_sum(s2);
+            t[4 * j + 2] = wave_sum(sg);
+            t[4 * j + 3] = wave_sum(sgx);
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int k = 0; k < 4 * RB; ++k) part[parity][wave][k] = t[k];
+        }
+        __syncthreads();    // a place in `part` is written again two batches on, behind the next batch's barrier
+#pragma unroll
+        for (int k = 0; k < 4 * RB; ++k) {
+            double a = part[parity][0][k];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) a += part[parity][w][k];
+            t[k] = a;
+        }
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            if (r0 + j < r_end) {
+                const double p = (double)pv[j];
+                const double m1 = t[4 * j] * inv_cols;                       // mu - p
+                const double var = fmax(t[4 * j + 1] * inv_cols - m1 * m1, 0.0);
+                const double rstd = 1.0 / sqrt(var + g.eps);
+                const double mg = t[4 * j + 2] * inv_cols;
+                const double mgx = rstd * (t[4 * j + 3] - m1 * t[4 * j + 2]) * inv_cols;
+                const double shift = p + m1;                                 // mu
+                vf4* dxp = reinterpret_cast<vf4*>(B.dx + (int64_t)(r0 + j) * g.cols);
+                int own = tid;
+                asm volatile("" : "+v"(own));
+#pragma unroll
+                for (int i = 0; i < NV; ++i) {
+                    const int c = i * T + tid;
+                    if (c < nvec) {
+                        const vf4 ga = gsh[i * T + own];
+                        const float xs[4] = {v[j][i].x, v[j][i].y, v[j][i].z, v[j][i].w};
+                        const float ds[4] = {d[j][i].x, d[j][i].y, d[j][i].z, d[j][i].w};
+                        const float gs[4] = {ga.x, ga.y, ga.z, ga.w};
+                        const float as[4] = {ad[j][i].x, ad[j][i].y, ad[j][i].z, ad[j][i].w};
+                        float o[4];
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            const double xh = ((double)xs[k] - shift) * rstd;
+                            o[k] = (float)(((double)ds[k] * (double)gs[k] - mg - xh * mgx) * rstd + (double)as[k]);
+                            accg[i][k] += (double)ds[k] * xh;
+                            accb[i][k] += (double)ds[k];
+                        }
+                        __builtin_nontemporal_store(vf4{o[0], o[1], o[2], o[3]}, dxp + c);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            pv[j] = pn[j];
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                v[j][i] = vn[j][i];
+                d[j][i] = dn[j][i];
+            }
+        }
+    }
+    if (g.partial) {
+        double* p = g.partial + 2 * ((int64_t)blockIdx.y * g.nbands + blockIdx.x) * g.cols;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int c = i * T + tid;
+            if (c < nvec) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    p[2 * (4 * c + k)] = accg[i][k];
+                    p[2 * (4 * c + k) + 1] = accb[i][k];
+                }
+            }
+        }
+    }
+}
+
 template <int NV>
 inline void launch_norm_bwd_rows_reg(const NormBwdGroup& g, hipStream_t stream)
 {
@@ -353,6 +531,7 @@ struct NormBwdColsOut {
     float* dgamma;           // cols sums of dy * xhat, or nullptr
     float* dbeta;            // cols sums of dy, or nullptr
     int nsrc;
+    int src_block[2];        // the sources' places in the row kernel's group (where the one-pass kernel left their sums)
 };
 
 struct NormBwdColsGroup {
@@ -465,11 +644,108 @@ inline size_t norm_cols_workspace_bytes(int rows, int cols, int nout)
     return parts > 1 ? (size_t)nout * parts * cols * 2 * sizeof(double) : 0;
 }
 
-// partial / partial_bytes (may be null): room for the column kernel's partial sums (norm_cols_workspace_bytes)
+// Second stage of the one-pass kernel: column c of output o is the sum over its source blocks, in order, and over
+// each one's bands, in order - eight interleaved running sums (band k goes to sum k mod 8) added in order at the end.  g.parts = bands
+// per block.  grid: x = strip of 32 columns, y = output.
+__global__ __launch_bounds__(NORM_COLS_THREADS) void layernorm_bwd_fused_join_f32(const NormBwdColsGroup g)
+{
+    constexpr int PL = NORM_COLS_THREADS / NORM_STRIP;
+    __shared__ double pg[PL][NORM_STRIP + 1], pb[PL][NORM_STRIP + 1];
+    const NormBwdColsOut& O = g.o[blockIdx.y];
+    const int cl = threadIdx.x % NORM_STRIP, pl = threadIdx.x / NORM_STRIP;
+    const int c = blockIdx.x * NORM_STRIP + cl;
+    double tg = 0.0, tb = 0.0;
+    if (c < g.cols) {
+        typedef double vd2 __attribute__((ext_vector_type(2)));
+        for (int b = 0; b < O.nsrc; ++b) {
+            const vd2* p = reinterpret_cast<const vd2*>(g.partial) + ((int64_t)O.src_block[b] * g.parts * g.cols + c);
+#pragma unroll 8
+            for (int band = pl; band < g.parts; band += PL) {
+                const vd2 q = __builtin_nontemporal_load(p + (int64_t)band * g.cols);
+                tg += q.x;
+                tb += q.y;
+            }
+        }
+    }
+    pg[pl][cl] = tg;
+    pb[pl][cl] = tb;
+    __syncthreads();
+    if (threadIdx.x < NORM_STRIP && c < g.cols) {
+        double sg = 0.0, sb = 0.0;
+#pragma unroll
+        for (int k = 0; k < PL; ++k) {
+            sg += pg[k][cl];
+            sb += pb[k][cl];
+        }
+        if (O.dgamma) O.dgamma[c] = (float)sg;
+        if (O.dbeta) O.dbeta[c] = (float)sb;
+    }
+}
+
+// The one-pass kernel's shape.  Three vectors per thread: the column sums (24 registers per vector), the rows of two
+// batches and the skip connection's fit a wavefront that shares its SIMD with one other (about 200 registers; rows
+// of two at a time, or four vectors per thread, were slower).  The workgroup is as wide as the row needs then, up to
+// 512 threads, and there are as many workgroups as the chip holds at once: 8 wavefronts per compute unit.
+constexpr int kNormFusedNV = 3;
+constexpr int kNormFusedMaxThreads = 512;          // rows of up to 512 * 3 * 4 = 6144 columns
+constexpr int kNormFusedCus = 256;
+inline int norm_fused_threads(int cols) { return ((cols / 4 + kNormFusedNV - 1) / kNormFusedNV + 63) / 64 * 64; }
+inline int norm_fused_band_rows(int rows, int cols, int nblocks)
+{
+    int wgs = kNormFusedCus * (8 / (norm_fused_threads(cols) / 64));
+    if (wgs > 1024) wgs = 1024;
+    const int bands = (wgs + nblocks - 1) / nblocks;
+    const int per = (rows + bands - 1) / bands;
+    return per < 1 ? 1 : per;
+}
+inline bool norm_fused_fits(int rows, int cols)
+{
+    return rows > 0 && cols > 0 && (cols & 3) == 0 && norm_fused_threads(cols) <= kNormFusedMaxThreads;
+}
+inline size_t norm_fused_workspace_bytes(int rows, int cols, int nblocks)
+{
+    if (!norm_fused_fits(rows, cols) || nblocks <= 0) return 0;
+    const int per = norm_fused_band_rows(rows, cols, nblocks);
+    return (size_t)nblocks * ((rows + per - 1) / per) * cols * 2 * sizeof(double);
+}
+
+template <int T>
+inline void launch_norm_bwd_fused(const NormBwdGroup& g, hipStream_t stream)
+{
+    hipLaunchKernelGGL((layernorm_bwd_fused_f32<kNormFusedNV, 1, T>), dim3(g.nbands, g.nblocks, 1), dim3(T), 0, stream, g);
+}
+
+// partial / partial_bytes (may be null): room for the partial column sums - the one-pass kernel's
+// (norm_fused_workspace_bytes) when the rows fit it, else the column kernel's (norm_cols_workspace_bytes)
 inline hipError_t launch_norm_bwd(const NormBwdGroup& g, NormBwdColsGroup cg, hipStream_t stream, void* partial = nullptr,
                                   size_t partial_bytes = 0)
 {
     if (g.cols <= 0 || g.nblocks <= 0) return hipSuccess;
+    const size_t fused_bytes = norm_fused_workspace_bytes(g.rows, g.cols, g.nblocks);
+    if (cg.nout > 0 && fused_bytes > 0 && norm_bwd_rows_fit(g) && partial && partial_bytes >= fused_bytes) {
+        NormBwdGroup f = g;
+        f.band_rows = norm_fused_band_rows(g.rows, g.cols, g.nblocks);
+        f.nbands = (g.rows + f.band_rows - 1) / f.band_rows;
+        f.partial = static_cast<double*>(partial);
+        switch (norm_fused_threads(g.cols)) {
+        case 64: launch_norm_bwd_fused<64>(f, stream); break;
+        case 128: launch_norm_bwd_fused<128>(f, stream); break;
+        case 192: launch_norm_bwd_fused<192>(f, stream); break;
+        case 256: launch_norm_bwd_fused<256>(f, stream); break;
+        case 320: launch_norm_bwd_fused<320>(f, stream); break;
+        case 384: launch_norm_bwd_fused<384>(f, stream); break;
+        case 448: launch_norm_bwd_fused<448>(f, stream); break;
+        default: launch_norm_bwd_fused<512>(f, stream); break;
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        cg.parts = f.nbands;
+        cg.part_rows = f.band_rows;
+        cg.partial = f.partial;
+        hipLaunchKernelGGL(layernorm_bwd_fused_join_f32, dim3((cg.cols + NORM_STRIP - 1) / NORM_STRIP, cg.nout, 1),
+                           dim3(NORM_COLS_THREADS), 0, stream, cg);
+        return hipGetLastError();
+    }
     if (g.rows > 0 && norm_bwd_rows_fit(g)) {
         const int need = (g.cols / 4 + 63) / 64;      // vectors per lane
         if (need <= 1) launch_norm_bwd_rows_reg<1>(g, stream);

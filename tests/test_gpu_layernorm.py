@@ -463,8 +463,9 @@ def test_layernorm_backward_matches_oracle(jg, ctx, ways, T, C):
 @pytest.mark.parametrize("ways", [1, 2, 4])
 @pytest.mark.parametrize("T,C", [(4098, 200), (2 * 2049, 72), (640, 4320)])
 def test_layernorm_backward_column_sums_in_row_ranges(jg, ctx, ways, T, C):
-    """Enough rows for the column sums to run in several row ranges (the last one ragged), with the whole workspace
-    and with the statistics' share only: both inside the bar of a sum taken in double and rounded once."""
+    """Enough rows for several bands / row ranges (the last one ragged), with the whole workspace (one pass: the rows'
+    kernel keeps the column sums of its band) and with the statistics' share only (two kernels, one workgroup per
+    strip of columns): both inside the bar of a sum taken in double and rounded once."""
     X = (inputs.matrix(136, T, C, "R") + np.float32(0.125)).astype(np.float32)
     gamma, _ = affine(137, C)
     dY = np.abs(inputs.matrix(138, T, C, "R")) + np.float32(0.25)        # same-sign: FP32 sums would not do
@@ -472,7 +473,31 @@ def test_layernorm_backward_column_sums_in_row_ranges(jg, ctx, ways, T, C):
     small = run_norm_backward(jg, ctx, X, gamma, dY, ways, minimal_workspace=True)
     check_norm_backward(X, gamma, dY, ways, full)
     check_norm_backward(X, gamma, dY, ways, small)
-    assert np.array_equal(full[0], small[0])                              # dX does not depend on the workspace
+    # the two forms take the rows' sums in different orders: dX agrees to a unit in the last place at worst
+    assert np.all(np.abs(full[0] - small[0]) <= 2.0 ** -23 * np.abs(small[0]))
+
+
+@pytest.mark.parametrize("ways", [1, 4])
+@pytest.mark.parametrize("T,C", [(70, 6144), (70, 6148), (38, 12288), (2, 64), (6, 772)])
+def test_layernorm_backward_row_widths(jg, ctx, ways, T, C):
+    """The widest rows the one-pass form takes (6144 columns per block), the first width past it, a width of one
+    vector per thread, and fewer rows than workgroups."""
+    X = (inputs.matrix(140, T, C, "R") + np.float32(0.25)).astype(np.float32)
+    gamma, _ = affine(141, C)
+    dY = inputs.matrix(142, T, C, "R")
+    check_norm_backward(X, gamma, dY, ways, run_norm_backward(jg, ctx, X, gamma, dY, ways))
+
+
+@pytest.mark.parametrize("minimal", [False, True])
+def test_layernorm_backward_rows_far_from_zero(jg, ctx, minimal):
+    """Rows whose mean is hundreds of standard deviations from zero: the one-pass form takes its sums about the row's
+    first element, so nothing is lost to the mean."""
+    T, C = 300, 1080
+    X = (inputs.matrix(143, T, C, "R") * np.float32(0.5) + np.float32(300.0)).astype(np.float32)
+    gamma, _ = affine(144, C)
+    dY = inputs.matrix(145, T, C, "R")
+    for ways in (1, 4):
+        check_norm_backward(X, gamma, dY, ways, run_norm_backward(jg, ctx, X, gamma, dY, ways, minimal_workspace=minimal))
 
 
 @pytest.mark.parametrize("ways", [1, 4])
@@ -491,10 +516,11 @@ def test_layernorm_backward_argument_checks(jg, ctx):
     with JigsawLinear(16, 8, 8, 2, ctx=ctx) as L:
         p = [t.data_ptr() for t in L.x]
         need = L.query(jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES)
-        assert need == 2 * 256
+        # the rows' statistics (required), then the column sums of two blocks x sixteen bands of one row x four columns
+        assert need == 2 * 256 + 2 * 16 * 4 * 16
         ws = torch.empty((need,), dtype=torch.uint8, device="cuda")
         for args, want in (((p, None, -1.0, p, p, None, None, ws.data_ptr(), need), jg.JG_E_DTYPE),
-                           ((p, None, 1e-5, p, p, None, None, ws.data_ptr(), need - 1), jg.JG_E_WORKSPACE),
+                           ((p, None, 1e-5, p, p, None, None, ws.data_ptr(), 2 * 256 - 1), jg.JG_E_WORKSPACE),
                            ((p, None, 1e-5, p, p, None, None, None, 0), jg.JG_E_WORKSPACE),
                            ((p, None, 1e-5, p, p, None, None, ws.data_ptr() + 16, need), jg.JG_E_ALIGN),
                            ((p, L.x[0].data_ptr() + 2, 1e-5, p, p, None, None, ws.data_ptr(), need), jg.JG_E_ALIGN)):
