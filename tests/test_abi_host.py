@@ -455,8 +455,9 @@ def test_layernorm_backward_checks_its_arguments():
     assert call(None) == jg.JG_E_NULL
     a = jg.jg_plan_create(None, 64, 32, 48, 2, True)
     assert call(a) == jg.JG_E_NULL                                      # a plan without a context
-    # two doubles per row of a rank's block, in 256-byte pieces
-    assert jg.jg_plan_query(a, jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES) == 2 * ((16 * 64 + 255) // 256 * 256)
+    # two doubles per row of a rank's block, in 256-byte pieces; then the one-pass form's column sums: a rank's
+    # 64 rows x 16 columns go to 64 bands of one row, two doubles per column and band
+    assert jg.jg_plan_query(a, jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES) == 2 * ((16 * 64 + 255) // 256 * 256) + 2 * 64 * 16 * 16
     jg.jg_plan_destroy(a)
 
 
