@@ -248,14 +248,19 @@ __device__ __forceinline__ void init_acc(const GemmProblem& P, int M, int N, int
     const int ldadd = P.ldadd;
     const int row_base = m0 + L.wm * 64 + 4 * L.lk;
     const int col_base = n0 + L.wn * 64 + L.lr;
-    if (m0 + BM <= M && n0 + BN <= N && ldadd <= kMaxDirectLd) {
-        // interior tile: the lane's position goes into one vector offset per column block and the
+    if (m0 + BM <= M && ldadd <= kMaxDirectLd) {
+        // all 128 rows inside: the lane's position goes into one vector offset per column block and the
         // row of each access into a scalar offset, so the 64 loads need no vector ALU work (a
         // workgroup that starts up shares its SIMDs with one that is saturating the matrix pipe,
-        // and every vector ALU instruction there waits for a gap between MFMAs)
+        // and every vector ALU instruction there waits for a gap between MFMAs).  A tile that hangs
+        // over the last column takes the same path: a lane whose column lies past N gets an offset
+        // outside the descriptor, and what it reads is zero.
+        const int ncols = min(BN, N - n0);
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<float*>(addend + (int64_t)m0 * ldadd + n0), 0, ((BM - 1) * ldadd + BN) * 4, kBufferRsrcFlags);
-        const int lane_off = ((L.wm * 64 + 4 * L.lk) * ldadd + L.wn * 64 + L.lr) * 4;
+            const_cast<float*>(addend + (int64_t)m0 * ldadd + n0), 0, ((BM - 1) * ldadd + ncols) * 4, kBufferRsrcFlags);
+        const int lane_col = L.wn * 64 + L.lr;
+        const int lane_off = ((L.wm * 64 + 4 * L.lk) * ldadd + lane_col) * 4;
+        const int off[2] = {lane_col < ncols ? lane_off : kOutOfBuffer, lane_col + 32 < ncols ? lane_off + 128 : kOutOfBuffer};
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -263,7 +268,7 @@ __device__ __forceinline__ void init_acc(const GemmProblem& P, int M, int N, int
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
                     acc[i][j][v] = __builtin_bit_cast(
-                        float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, lane_off + j * 128,
+                        float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, off[j],
                                                                     (i * 32 + 8 * (v >> 2) + (v & 3)) * ldadd * 4, 0));
     } else {
 #pragma unroll
@@ -290,12 +295,20 @@ __device__ __forceinline__ void store_tile(const GemmProblem& P, int M, int N, i
     const int ldc = P.ldc;
     const int row_base = m0 + L.wm * 64 + 4 * L.lk;     // + i * 32 + 8 (v / 4) + v % 4
     const int col_base = n0 + L.wn * 64 + L.lr;         // + j * 32
-    if (m0 + BM <= M && n0 + BN <= N && ldc <= kMaxDirectLd && (!residual || P.ldres <= kMaxDirectLd)) {
-        // interior tile: no bounds checks, and no vector ALU work for addresses (lane position in
-        // one vector offset per column block, the row of each store in a scalar offset)
+    if (m0 + BM <= M && ldc <= kMaxDirectLd && (!residual || P.ldres <= kMaxDirectLd)) {
+        // all 128 rows inside: no per-element bounds checks, and no vector ALU work for addresses (lane
+        // position in one vector offset per column block, the row of each store in a scalar offset).
+        // Columns past N (the tile that hangs over the last column; one in sixteen at N = 2000) are left
+        // to the descriptor: such a lane's offset lies outside it, its stores are dropped and its loads
+        // read zero.  With per-element checks that tile's epilogue took about 85 us of vector ALU work
+        // squeezed between the other workgroup's MFMAs, against a 225 us tile.
+        const int ncols = min(BN, N - n0);
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            C + (int64_t)m0 * ldc + n0, 0, ((BM - 1) * ldc + BN) * 4, kBufferRsrcFlags);
-        const int lane_off = ((L.wm * 64 + 4 * L.lk) * ldc + L.wn * 64 + L.lr) * 4;
+            C + (int64_t)m0 * ldc + n0, 0, ((BM - 1) * ldc + ncols) * 4, kBufferRsrcFlags);
+        const int lane_col = L.wn * 64 + L.lr;
+        const int lane_off = ((L.wm * 64 + 4 * L.lk) * ldc + lane_col) * 4;
+        const bool in[2] = {lane_col < ncols, lane_col + 32 < ncols};
+        const int off[2] = {in[0] ? lane_off : kOutOfBuffer, in[1] ? lane_off + 128 : kOutOfBuffer};
         if (!bias && !act && !residual) {
 #pragma unroll
             for (int j = 0; j < 2; ++j)
@@ -304,19 +317,19 @@ __device__ __forceinline__ void store_tile(const GemmProblem& P, int M, int N, i
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const float value = acc[i][j][v];   // a copy: bit-casting the vector element in place reads element 0
-                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, value), rsrc,
-                                                              lane_off + j * 128,
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, value), rsrc, off[j],
                                                               (i * 32 + 8 * (v >> 2) + (v & 3)) * ldc * 4, 0);
                     }
         } else {
             const int ldres = P.ldres;
             const __amdgpu_buffer_rsrc_t res_rsrc = __builtin_amdgcn_make_buffer_rsrc(
                 const_cast<float*>(residual ? residual + (int64_t)m0 * ldres + n0 : C), 0,
-                residual ? ((BM - 1) * ldres + BN) * 4 : 0, kBufferRsrcFlags);
-            const int res_off = ((L.wm * 64 + 4 * L.lk) * ldres + L.wn * 64 + L.lr) * 4;
+                residual ? ((BM - 1) * ldres + ncols) * 4 : 0, kBufferRsrcFlags);
+            const int res_lane = ((L.wm * 64 + 4 * L.lk) * ldres + lane_col) * 4;
+            const int res_offs[2] = {in[0] ? res_lane : kOutOfBuffer, in[1] ? res_lane + 128 : kOutOfBuffer};
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const float bj = bias ? bias[col_base + j * 32] : 0.f;
+                const float bj = (bias && in[j]) ? bias[col_base + j * 32] : 0.f;
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
                     float res[16];
@@ -325,19 +338,19 @@ __device__ __forceinline__ void store_tile(const GemmProblem& P, int M, int N, i
                         for (int v = 0; v < 16; ++v)
                             res[v] = __builtin_bit_cast(
                                 float, __builtin_amdgcn_raw_buffer_load_b32(
-                                           res_rsrc, res_off + j * 128, (i * 32 + 8 * (v >> 2) + (v & 3)) * ldres * 4, 0));
+                                           res_rsrc, res_offs[j], (i * 32 + 8 * (v >> 2) + (v & 3)) * ldres * 4, 0));
                     }
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         float y = activate(acc[i][j][v] + bj, act);
                         if (residual) y += res[v];
-                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rsrc, lane_off + j * 128,
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rsrc, off[j],
                                                               (i * 32 + 8 * (v >> 2) + (v & 3)) * ldc * 4, 0);
                     }
                 }
             }
         }
-    } else {                              // edge tile: every element checked against M and N
+    } else {                              // rows past M (or a leading dimension too long for 32-bit offsets): every element checked
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
 #pragma unroll

@@ -46,6 +46,15 @@ bool hip_ok(hipError_t e, const char* what)
 }
 #define HIP_OK(call) hip_ok((call), #call)
 
+// Makes `device` the calling thread's current one; a thread that already is on it (every call after a context's
+// first, in the usual program) pays a thread-local read instead of a trip into the runtime's device switch.
+static hipError_t use_device(int device)
+{
+    int cur = -1;
+    if (hipGetDevice(&cur) == hipSuccess && cur == device) return hipSuccess;
+    return hipSetDevice(device);
+}
+
 constexpr int kProfileMaxLaunches = 8192;
 constexpr int64_t kMaxDim = 0x7fffffff - 1024;   // every dimension fits an int with tile slack
 constexpr int kDefaultSlots = 512;               // MI355X: 256 CUs x 2 resident GEMM workgroups (plans made without a context)
@@ -214,7 +223,7 @@ int jg_init(jg_ctx** out, int device, void* hip_stream)
 void jg_free(jg_ctx* ctx)
 {
     if (!ctx) return;
-    (void)hipSetDevice(ctx->device);
+    (void)use_device(ctx->device);
     for (hipEvent_t e : ctx->pool) (void)hipEventDestroy(e);
     for (jg_plan* p : ctx->plans) p->ctx = nullptr;     // surviving plans answer queries only from now on
     delete ctx;
@@ -223,7 +232,7 @@ void jg_free(jg_ctx* ctx)
 int jg_profile(jg_ctx* ctx, int enable)
 {
     if (!ctx) return JG_E_NULL;
-    if (!HIP_OK(hipSetDevice(ctx->device))) return JG_E_HIP;
+    if (!HIP_OK(use_device(ctx->device))) return JG_E_HIP;
     if (enable && ctx->pool.empty()) {
         ctx->pool.reserve(2 * kProfileMaxLaunches);
         ctx->timed.reserve(kProfileMaxLaunches);
@@ -241,7 +250,7 @@ int jg_profile_read(jg_ctx* ctx, int kernel, double* total_ms, int64_t* launches
 {
     if (!ctx || !total_ms || !launches) return JG_E_NULL;
     if (kernel < 0 || kernel >= JG_KERNEL_COUNT) return JG_E_DTYPE;
-    if (!HIP_OK(hipSetDevice(ctx->device))) return JG_E_HIP;
+    if (!HIP_OK(use_device(ctx->device))) return JG_E_HIP;
     if (!HIP_OK(hipStreamSynchronize(ctx->stream))) return JG_E_HIP;
     double sum = 0.0;
     int64_t n = 0;
@@ -637,7 +646,7 @@ int jg_shard(const jg_plan* plan, int which, const float* global, int64_t ld, fl
         return JG_E_DTYPE;
     jg_ctx* c = plan->ctx;
     if (!c) return JG_E_NULL;
-    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    if (!HIP_OK(use_device(c->device))) return JG_E_HIP;
 
     if (d.dtype != JG_F32 && (which == JG_T_X || which == JG_T_W)) {
         // reduced precision: the shard is written in the format the matrix cores read
@@ -704,7 +713,7 @@ int jg_gather_as(const jg_plan* plan, int which, const float* const* shards, flo
     if (ld < pt.width) return JG_E_SHAPE;
     jg_ctx* c = plan->ctx;
     if (!c) return JG_E_NULL;
-    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    if (!HIP_OK(use_device(c->device))) return JG_E_HIP;
 
     jg::CopyGroup g;
     std::memset(&g, 0, sizeof(g));
@@ -739,7 +748,7 @@ static int patch_move(const jg_plan* plan, int which, float* field, int64_t C, i
     if (pt.rows * pt.cols >= jg::kMaxUnitsPerLaunch) return JG_E_SHAPE;
     jg_ctx* c = plan->ctx;
     if (!c) return JG_E_NULL;
-    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    if (!HIP_OK(use_device(c->device))) return JG_E_HIP;
     jg::PatchGroup g;
     std::memset(&g, 0, sizeof(g));
     g.nblocks = d.ways;
@@ -1077,7 +1086,7 @@ static int forward_impl(const jg_plan* plan, const float* const* x_sh, const flo
         if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
     }
     jg_ctx* c = plan->ctx;
-    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    if (!HIP_OK(use_device(c->device))) return JG_E_HIP;
     char* ws = static_cast<char*>(workspace);
     auto bias_of = [&](int r) -> const float* { return d.has_bias ? b_sh[r] : nullptr; };
     auto res_of = [&](int r) -> const float* { return r_sh ? r_sh[r] : nullptr; };
@@ -1456,7 +1465,7 @@ int jg_linear_backward(const jg_plan* plan, const float* const* x_sh, const floa
         if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
     }
     jg_ctx* c = plan->ctx;
-    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    if (!HIP_OK(use_device(c->device))) return JG_E_HIP;
     char* ws = static_cast<char*>(workspace);
     if (d.op == JG_OP_XW) {
         // dX = dY W^T is the X W^T layer on (dY, W), dW = X^T dY the X^T W layer on (X, dY): the partitions agree
@@ -1569,7 +1578,7 @@ static int layernorm_impl(const jg_plan* plan, const float* const* x_sh, const f
     for (int r = 0; r < d.ways; ++r)
         if (!aligned(x_sh[r], 4) || !aligned(out_sh[r], 4)) return JG_E_ALIGN;
     jg_ctx* c = plan->ctx;
-    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    if (!HIP_OK(use_device(c->device))) return JG_E_HIP;
     jg::NormGroup g;
     std::memset(&g, 0, sizeof(g));
     g.nblocks = d.ways;
@@ -1615,7 +1624,7 @@ static int layernorm_backward_impl(const jg_plan* plan, const float* const* x_sh
     if (!workspace || workspace_bytes < stats_bytes * d.ways) return JG_E_WORKSPACE;
     if (!aligned(workspace, kWsAlign)) return JG_E_ALIGN;
     jg_ctx* c = plan->ctx;
-    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    if (!HIP_OK(use_device(c->device))) return JG_E_HIP;
     jg::NormBwdGroup g;
     std::memset(&g, 0, sizeof(g));
     g.nblocks = d.ways;
@@ -1676,7 +1685,7 @@ int jg_bias_backward(const jg_plan* plan, const float* const* dy_sh, float* cons
     for (int r = 0; r < d.ways; ++r)
         if (!aligned(dy_sh[r], 4) || !aligned(db_sh[r], 4)) return JG_E_ALIGN;
     jg_ctx* c = plan->ctx;
-    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    if (!HIP_OK(use_device(c->device))) return JG_E_HIP;
     jg::ColSumGroup g;
     std::memset(&g, 0, sizeof(g));
     g.rows = (int)plan->yr;
@@ -1781,7 +1790,7 @@ static int run_chain(const jg_plan* first, const jg_plan* second, const float* c
     if (int rc = check_chain_workspace(first, second, workspace, workspace_bytes)) return rc;
     jg_ctx* c = first->ctx;
     if (!c) return JG_E_NULL;
-    if (!HIP_OK(hipSetDevice(c->device))) return JG_E_HIP;
+    if (!HIP_OK(use_device(c->device))) return JG_E_HIP;
     char* ws = static_cast<char*>(workspace);
     const float* x16[4] = {nullptr, nullptr, nullptr, nullptr};
     const float* h16[4] = {nullptr, nullptr, nullptr, nullptr};
