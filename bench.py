@@ -29,7 +29,7 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--ways", type=int, default=4, choices=[1, 2, 4])
     ap.add_argument("--op", choices=["forward", "backward", "xtw", "mlp", "mixing", "mixing_backward", "token_mixing",
