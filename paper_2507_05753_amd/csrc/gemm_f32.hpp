@@ -248,28 +248,39 @@ __device__ __forceinline__ void init_acc(const GemmProblem& P, int M, int N, int
     const int ldadd = P.ldadd;
     const int row_base = m0 + L.wm * 64 + 4 * L.lk;
     const int col_base = n0 + L.wn * 64 + L.lr;
-    if (m0 + BM <= M && ldadd <= kMaxDirectLd) {
-        // all 128 rows inside: the lane's position goes into one vector offset per column block and the
-        // row of each access into a scalar offset, so the 64 loads need no vector ALU work (a
-        // workgroup that starts up shares its SIMDs with one that is saturating the matrix pipe,
-        // and every vector ALU instruction there waits for a gap between MFMAs).  A tile that hangs
-        // over the last column takes the same path: a lane whose column lies past N gets an offset
-        // outside the descriptor, and what it reads is zero.
-        const int ncols = min(BN, N - n0);
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<float*>(addend + (int64_t)m0 * ldadd + n0), 0, ((BM - 1) * ldadd + ncols) * 4, kBufferRsrcFlags);
-        const int lane_col = L.wn * 64 + L.lr;
-        const int lane_off = ((L.wm * 64 + 4 * L.lk) * ldadd + lane_col) * 4;
-        const int off[2] = {lane_col < ncols ? lane_off : kOutOfBuffer, lane_col + 32 < ncols ? lane_off + 128 : kOutOfBuffer};
+    if (ldadd <= kMaxDirectLd) {
+        // The lane's position goes into one vector offset per column block and the row of each access into
+        // a scalar offset, so the 64 loads of a tile whose rows are all inside need no vector ALU work (a
+        // workgroup that starts up shares its SIMDs with one that is saturating the matrix pipe, and every
+        // vector ALU instruction there waits for a gap between MFMAs).  A tile that hangs over the last
+        // column takes the same path: the descriptor ends at the last valid column, a lane whose column
+        // lies past N gets an offset outside it, and what it reads is zero.  A tile that hangs over the last
+        // row (ROWS_IN = false) masks each access the same way, by the rows the lane has left: a compare
+        // and a select per access instead of a 64-bit address and a predicated load.
+        auto direct = [&](auto rows_in_c) __attribute__((always_inline)) {
+            constexpr bool ROWS_IN = decltype(rows_in_c)::value;
+            const int nrows = ROWS_IN ? BM : M - m0;
+            const int ncols = min(BN, N - n0);
+            const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<float*>(addend + (int64_t)m0 * ldadd + n0), 0, ((nrows - 1) * ldadd + ncols) * 4, kBufferRsrcFlags);
+            const int lane_col = L.wn * 64 + L.lr;
+            const int lane_row = L.wm * 64 + 4 * L.lk;
+            const int lane_off = (lane_row * ldadd + lane_col) * 4;
+            const int off[2] = {lane_col < ncols ? lane_off : kOutOfBuffer, lane_col + 32 < ncols ? lane_off + 128 : kOutOfBuffer};
+            const int slack = nrows - lane_row;      // rows of the tile at or below the lane's first that are inside
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < 2; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    acc[i][j][v] = __builtin_bit_cast(
-                        float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, off[j],
-                                                                    (i * 32 + 8 * (v >> 2) + (v & 3)) * ldadd * 4, 0));
+                    for (int v = 0; v < 16; ++v) {
+                        const int rel = i * 32 + 8 * (v >> 2) + (v & 3);
+                        const int voff = (ROWS_IN || rel < slack) ? off[j] : kOutOfBuffer;
+                        acc[i][j][v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, voff, rel * ldadd * 4, 0));
+                    }
+        };
+        if (m0 + BM <= M) direct(std::true_type{});
+        else direct(std::false_type{});
     } else {
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -295,20 +306,26 @@ __device__ __forceinline__ void store_tile(const GemmProblem& P, int M, int N, i
     const int ldc = P.ldc;
     const int row_base = m0 + L.wm * 64 + 4 * L.lk;     // + i * 32 + 8 (v / 4) + v % 4
     const int col_base = n0 + L.wn * 64 + L.lr;         // + j * 32
-    if (m0 + BM <= M && ldc <= kMaxDirectLd && (!residual || P.ldres <= kMaxDirectLd)) {
-        // all 128 rows inside: no per-element bounds checks, and no vector ALU work for addresses (lane
-        // position in one vector offset per column block, the row of each store in a scalar offset).
-        // Columns past N (the tile that hangs over the last column; one in sixteen at N = 2000) are left
-        // to the descriptor: such a lane's offset lies outside it, its stores are dropped and its loads
-        // read zero.  With per-element checks that tile's epilogue took about 85 us of vector ALU work
-        // squeezed between the other workgroup's MFMAs, against a 225 us tile.
+    if (ldc <= kMaxDirectLd && (!residual || P.ldres <= kMaxDirectLd)) {
+        // No per-element bounds checks and no 64-bit addresses: lane position in one vector offset per column
+        // block, the row of each store in a scalar offset.  Columns past N (the tile that hangs over the last
+        // column; one in sixteen at N = 2000) are left to the descriptor: such a lane's offset lies outside
+        // it, its stores are dropped and its loads read zero.  With per-element checks that tile's epilogue
+        // took about 85 us of vector ALU work squeezed between the other workgroup's MFMAs, against a 225 us
+        // tile.  Rows past M (ROWS_IN = false: the tile that hangs over the last row) are masked per access
+        // by the rows the lane has left.
+        auto direct = [&](auto rows_in_c) __attribute__((always_inline)) {
+        constexpr bool ROWS_IN = decltype(rows_in_c)::value;
+        const int nrows = ROWS_IN ? BM : M - m0;
         const int ncols = min(BN, N - n0);
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            C + (int64_t)m0 * ldc + n0, 0, ((BM - 1) * ldc + ncols) * 4, kBufferRsrcFlags);
+            C + (int64_t)m0 * ldc + n0, 0, ((nrows - 1) * ldc + ncols) * 4, kBufferRsrcFlags);
         const int lane_col = L.wn * 64 + L.lr;
-        const int lane_off = ((L.wm * 64 + 4 * L.lk) * ldc + lane_col) * 4;
+        const int lane_row = L.wm * 64 + 4 * L.lk;
+        const int lane_off = (lane_row * ldc + lane_col) * 4;
         const bool in[2] = {lane_col < ncols, lane_col + 32 < ncols};
         const int off[2] = {in[0] ? lane_off : kOutOfBuffer, in[1] ? lane_off + 128 : kOutOfBuffer};
+        const int slack = nrows - lane_row;
         if (!bias && !act && !residual) {
 #pragma unroll
             for (int j = 0; j < 2; ++j)
@@ -317,15 +334,16 @@ __device__ __forceinline__ void store_tile(const GemmProblem& P, int M, int N, i
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const float value = acc[i][j][v];   // a copy: bit-casting the vector element in place reads element 0
-                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, value), rsrc, off[j],
-                                                              (i * 32 + 8 * (v >> 2) + (v & 3)) * ldc * 4, 0);
+                        const int rel = i * 32 + 8 * (v >> 2) + (v & 3);
+                        const int voff = (ROWS_IN || rel < slack) ? off[j] : kOutOfBuffer;
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, value), rsrc, voff, rel * ldc * 4, 0);
                     }
         } else {
             const int ldres = P.ldres;
             const __amdgpu_buffer_rsrc_t res_rsrc = __builtin_amdgcn_make_buffer_rsrc(
                 const_cast<float*>(residual ? residual + (int64_t)m0 * ldres + n0 : C), 0,
-                residual ? ((BM - 1) * ldres + ncols) * 4 : 0, kBufferRsrcFlags);
-            const int res_lane = ((L.wm * 64 + 4 * L.lk) * ldres + lane_col) * 4;
+                residual ? ((nrows - 1) * ldres + ncols) * 4 : 0, kBufferRsrcFlags);
+            const int res_lane = (lane_row * ldres + lane_col) * 4;
             const int res_offs[2] = {in[0] ? res_lane : kOutOfBuffer, in[1] ? res_lane + 128 : kOutOfBuffer};
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -335,22 +353,28 @@ __device__ __forceinline__ void store_tile(const GemmProblem& P, int M, int N, i
                     float res[16];
                     if (residual) {
 #pragma unroll
-                        for (int v = 0; v < 16; ++v)
+                        for (int v = 0; v < 16; ++v) {
+                            const int rel = i * 32 + 8 * (v >> 2) + (v & 3);
+                            const int voff = (ROWS_IN || rel < slack) ? res_offs[j] : kOutOfBuffer;
                             res[v] = __builtin_bit_cast(
-                                float, __builtin_amdgcn_raw_buffer_load_b32(
-                                           res_rsrc, res_offs[j], (i * 32 + 8 * (v >> 2) + (v & 3)) * ldres * 4, 0));
+                                float, __builtin_amdgcn_raw_buffer_load_b32(res_rsrc, voff, rel * ldres * 4, 0));
+                        }
                     }
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         float y = activate(acc[i][j][v] + bj, act);
                         if (residual) y += res[v];
-                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rsrc, off[j],
-                                                              (i * 32 + 8 * (v >> 2) + (v & 3)) * ldc * 4, 0);
+                        const int rel = i * 32 + 8 * (v >> 2) + (v & 3);
+                        const int voff = (ROWS_IN || rel < slack) ? off[j] : kOutOfBuffer;
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rsrc, voff, rel * ldc * 4, 0);
                     }
                 }
             }
         }
-    } else {                              // rows past M (or a leading dimension too long for 32-bit offsets): every element checked
+        };
+        if (m0 + BM <= M) direct(std::true_type{});
+        else direct(std::false_type{});
+    } else {                              // a leading dimension too long for 32-bit offsets: every element checked, 64-bit addresses
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
 #pragma unroll
