@@ -32,10 +32,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--ways", type=int, default=4, choices=[1, 2, 4])
-    ap.add_argument("--op", choices=["forward", "backward", "xtw", "mlp", "mixing", "mixing_backward", "token_mixing",
+    ap.add_argument("--op", choices=["forward", "backward", "xw", "xtw", "mlp", "mixing", "mixing_backward", "token_mixing",
                                    "token_mixing_backward", "encoder"],
                     default="forward",
-                    help="forward: Y = X W^T (the headline); backward: dX = dY W and dW = dY^T X; "
+                    help="forward: Y = X W^T (the headline); backward: dX = dY W and dW = dY^T X; xw: the third permutation Y = X W (weights stored along the contracted index) at --config's size; "
                          "xtw: the transposed layer Y = X^T W at the token-mixing size; mlp: one mixing MLP "
                          "(GELU between two layers, residual) at the channel-mixing size; mixing: the same behind a layer norm "
                          "(the channel-mixing half of a mixing block); token_mixing: the token-mixing half (norm, transposed "
@@ -292,6 +292,59 @@ def measure_backward(cfg, ways, args, X, W):
     torch.cuda.empty_cache()
     return dict(ms_per_step=sec * 1e3, items_per_s=M * K / sec, tflops=flops / sec / 1e12, kernels=kernels,
                 workspace_bytes=ws)
+
+
+def measure_xw(cfg, ways, args):
+    """One step = one forward of the permutation Y = X W (W stored [K, N]; all ranks), shards resident in HBM."""
+    import torch
+    from paper_2507_05753_amd import binding as jg
+    from paper_2507_05753_amd import inputs
+    from paper_2507_05753_amd.layer import JigsawLinear
+    M, K, N, seed = cfg["M"], cfg["K"], cfg["N"], cfg["seed"]
+    dev = torch.device("cuda", 0)
+    X = inputs.matrix_torch(seed, M, K, cfg["x_mode"], 0, device=dev)
+    W = inputs.matrix_torch(seed + inputs.W_STREAM, K, N, "R", inputs.W_SCALE_EXP, device=dev)
+    weights = jg.JG_WEIGHTS_COPY if args.weights == "copy" else jg.JG_WEIGHTS_DIRECT
+    with JigsawLinear(M, K, N, ways, weights=weights, op=jg.JG_OP_XW, tail=tail_of(args)) as L:
+        L.shard(X, W)
+        del X, W
+        sec, gemm_ms, gemm_n, copy_ms, comb_ms = time_forward(L, jg, args.steps, args.warmup)
+        flops = L.query(jg.JG_Q_FLOPS_TOTAL)
+        launches = L.query(jg.JG_Q_GEMM_LAUNCHES)
+        avg = gemm_ms / max(gemm_n, 1)
+        out = dict(ms_per_step=sec * 1e3, items_per_s=M * K / sec, tflops=flops / sec / 1e12,
+                   gemm_avg_launch_ms=avg, gemm_launches_timed=gemm_n,
+                   gemm_tflops=(flops / launches) / (avg * 1e-3) / 1e12 if gemm_n else None,
+                   other_kernels_ms_per_step=copy_ms + comb_ms,
+                   hbm_algo_gbps=L.query(jg.JG_Q_HBM_BYTES_ALGO) / sec / 1e9, workspace_bytes=L.ws_bytes)
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline_xw(cfg, seconds):
+    """The oracle of Y = X W timed on a bounded sample of rows of X."""
+    import numpy as np
+    import oracle
+    from paper_2507_05753_amd import inputs
+    M, K, N, seed = cfg["M"], cfg["K"], cfg["N"], cfg["seed"]
+    cores = min(oracle.host_threads(), 16)
+    W = inputs.matrix(seed + inputs.W_STREAM, K, N, "R", inputs.W_SCALE_EXP)
+
+    def run(rows):
+        Xs = inputs.matrix(seed, M, K, cfg["x_mode"], row_begin=0, row_end=rows)
+        t0 = time.perf_counter()
+        Y = oracle.linear_xw(Xs, W, None, nthreads=cores)
+        dt = time.perf_counter() - t0
+        assert np.isfinite(Y).all()
+        return dt
+
+    probe = min(M, 2 * cores)
+    rate = probe / max(run(probe), 1e-9)
+    rows = int(min(M, max(probe, rate * seconds)))
+    rows = min(M, max(cores, rows // cores * cores))
+    dt = run(rows)
+    return dict(value=rows * K / dt, unit="items/s", cores=cores, kind="oracle",
+                sample=f"rows 0..{rows - 1} of X ({rows} x {K}) against all of W ({K} x {N}), {dt:.1f} s, fp64 triple loop")
 
 
 def measure_xtw(cfg, ways, args):
@@ -833,9 +886,32 @@ def main():
     from paper_2507_05753_amd import inputs
     if args.dtype != "f32" and args.op not in ("forward", "backward", "xtw", "mlp", "mixing", "mixing_backward",
                                                "token_mixing", "token_mixing_backward"):
-        print("bench.py: --dtype bf16 / bf16x3 does not go with --op encoder",
+        print("bench.py: --dtype bf16 / bf16x3 does not go with --op encoder or --op xw",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.op == "xw":
+        cfg = inputs.CONFIGS[args.config]
+        r = measure_xw(cfg, args.ways, args)
+        M, K, N = cfg["M"], cfg["K"], cfg["N"]
+        line = {
+            "metric": "hot-path items/s at n=1e8 + achieved HBM GB/s (% of MI355X peak)",
+            "value": r["items_per_s"], "unit": "items/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"config {args.config}: Y = X W, M={M} K={K} N={N}, W stored [K, N], "
+                                   f"{args.ways}-way Jigsaw, fp32",
+                       "n_items": M * K, "ways": args.ways, "M": M, "K": K, "N": N, "seed": cfg["seed"],
+                       "x_values": cfg["x_mode"], "op": "xw", "weights": args.weights, "tail": args.tail, "mode": "f32"},
+            "tflops": r["tflops"], "hbm_algo_gbps": r["hbm_algo_gbps"],
+            "roofline": gemm_roofline(args, r),
+            "other_kernels_ms_per_step": r["other_kernels_ms_per_step"],
+        }
+        line["roofline"]["kernel"] = "jg::gemm_f32_stream<false, true, false>"
+        if args.cpu_seconds > 0:
+            line["cpu_baseline"] = cpu_baseline_xw(cfg, args.cpu_seconds)
+        print(json.dumps(line), flush=True)
+        return
 
     if args.op == "xtw":
         xc = inputs.XTW_CONFIGS["token_mixing_1b"]
