@@ -79,6 +79,10 @@ struct HbGroup {
     uint16_t* c16[kMaxGroup];   // per problem, or all null
     int ld16;                   // bfloat16 elements per row of that copy (all planes)
     int plane16, planes16;      // elements from the hi plane of a row to its lo plane; 1 or 2 planes
+    // Whole tiles taken last to first.  A launch that reads what the launch before it wrote (the received partial
+    // products, or C itself between the chunks of a contraction) alternates with it, so that it starts with the
+    // tiles written last - the ones the memory-side cache still holds.  Same tiles, same sums: only the order differs.
+    int reverse;
 };
 
 struct HbCopy16 {               // what a caller of launch_gemm_bf16_group passes for that copy
@@ -347,6 +351,7 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16_nt(const HbGroup g)
     if ((int)blockIdx.x < kNumXcd * g.per_xcd) {
         lid = (blockIdx.x % kNumXcd) * g.per_xcd + blockIdx.x / kNumXcd;
         if (lid >= g.whole) return;
+        if (g.reverse) lid = g.whole - 1 - lid;
     } else {
         run = blockIdx.x - kNumXcd * g.per_xcd;
         const int t = run / g.parts, part = run - t * g.parts;
@@ -533,6 +538,7 @@ __global__ __launch_bounds__(HB_THREADS, 1) void gemm_bf16x3_nt(const HbGroup g)
     if ((int)blockIdx.x < kNumXcd * g.per_xcd) {
         lid = (blockIdx.x % kNumXcd) * g.per_xcd + blockIdx.x / kNumXcd;
         if (lid >= g.whole) return;
+        if (g.reverse) lid = g.whole - 1 - lid;
     } else {
         run = blockIdx.x - kNumXcd * g.per_xcd;
         const int t = run / g.parts, part = run - t * g.parts;
@@ -777,8 +783,9 @@ inline size_t bf16_tail_scratch_bytes(int cus) { return (size_t)cus * HB_TILE_FL
 
 // plane: with split operands, the distance in elements from a row's hi plane to its lo plane (>= K, a multiple of 8)
 inline hipError_t make_bf16_group(const GemmGroup& src, int terms, int plane, int cus, float* scratch, size_t scratch_bytes,
-                                  HbGroup& g, const HbCopy16* copy16 = nullptr)
+                                  HbGroup& g, const HbCopy16* copy16 = nullptr, bool reverse = false)
 {
+    g.reverse = reverse ? 1 : 0;
     for (int i = 0; i < kMaxGroup; ++i) g.p[i] = src.p[i];
     for (int i = 0; i < kMaxGroup; ++i) g.c16[i] = copy16 ? copy16->dst[i] : nullptr;
     g.ld16 = copy16 ? copy16->ld : 0;
@@ -827,10 +834,10 @@ inline unsigned bf16_grid(const HbGroup& g) { return (unsigned)(kNumXcd * g.per_
 // copy16 (may be null): see HbGroup::c16.
 inline hipError_t launch_gemm_bf16_group(const GemmGroup& src, int terms, int plane, int cus, float* scratch,
                                          size_t scratch_bytes, hipStream_t stream, HbGroup& g, bool* needs_join,
-                                         const HbCopy16* copy16 = nullptr)
+                                         const HbCopy16* copy16 = nullptr, bool reverse = false)
 {
     *needs_join = false;
-    const hipError_t e = make_bf16_group(src, terms, plane, cus, scratch, scratch_bytes, g, copy16);
+    const hipError_t e = make_bf16_group(src, terms, plane, cus, scratch, scratch_bytes, g, copy16, reverse);
     if (e != hipSuccess) return e;
     if (terms == 3) hipLaunchKernelGGL(gemm_bf16x3_nt, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);
     else hipLaunchKernelGGL(gemm_bf16_nt, dim3(bf16_grid(g)), dim3(HB_THREADS), 0, stream, g);

@@ -77,6 +77,7 @@ struct jg_ctx {
     size_t pool_used;
     std::vector<TimedLaunch> timed;
     std::vector<jg_plan*> plans;         // the live plans made with this context: jg_free detaches them
+    bool hb_reverse = false;             // tile order of the last bfloat16 launch (see run_gemm)
 };
 
 struct jg_plan {
@@ -815,11 +816,15 @@ static bool run_gemm(const jg_plan* plan, jg::GemmGroup& g, int layout, int kern
                 if (!last) { q.bias = nullptr; q.residual = nullptr; q.ldres = 0; }
             }
             jg::HbGroup hb;
+            // a launch that adds on top of what the one before it wrote walks the tiles the other way round
+            // (HbGroup::reverse)
+            const bool reverse = part.p[0].addend ? !c->hb_reverse : false;
+            c->hb_reverse = reverse;
             {
                 ScopedTimer t(c, kernel_class);
                 if (!HIP_OK(jg::launch_gemm_bf16_group(part, terms, plane ? plane : (int)plan->plane, plan->slots / 2,
                                                        reinterpret_cast<float*>(scratch), scratch_bytes, c->stream, hb,
-                                                       &join, last ? copy16 : nullptr)))
+                                                       &join, last ? copy16 : nullptr, reverse)))
                     return false;
             }
             if (join) {
