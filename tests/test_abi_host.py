@@ -459,6 +459,14 @@ def test_layernorm_backward_checks_its_arguments():
     # 64 rows x 16 columns go to 64 bands of one row, two doubles per column and band
     assert jg.jg_plan_query(a, jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES) == 2 * ((16 * 64 + 255) // 256 * 256) + 2 * 64 * 16 * 16
     jg.jg_plan_destroy(a)
+    # the 1B model's channel mixing: one band of rows per compute unit and workgroup slot
+    for ways, blocks, rows, cols, bands in ((1, 1, 16200, 4320, 256), (2, 2, 16200, 2160, 256), (4, 4, 8100, 2160, 128)):
+        b = jg.jg_plan_create(None, 16200, 4320, 4320, ways)
+        per = -(-rows // bands)
+        nbands = -(-rows // per)
+        stats = ways * ((16 * rows + 255) // 256 * 256)
+        assert jg.jg_plan_query(b, jg.JG_Q_NORM_BACKWARD_WORKSPACE_BYTES) == stats + blocks * nbands * cols * 16
+        jg.jg_plan_destroy(b)
 
 
 def test_mlp_and_mixing_backward_check_that_the_plans_chain():
