@@ -274,6 +274,56 @@ def test_mlp_backward(jg, ctx, ways, M, C, Hd):
         assert np.all(np.abs(g[name] - ref) <= 1e-4 * (np.abs(ref) + np.abs(ref).max())), name
 
 
+@pytest.mark.parametrize("ways", [1, 4])
+def test_gelu_derivative_over_its_range(jg, ctx, ways):
+    """dA = dH * gelu'(A) with A chosen column by column: X = 0 makes the recomputed pre-activation equal to b1 exactly,
+    and b1 sweeps [-5.8, 5.8] (the kernel's table of Taylor polynomials for erf), every float within 250 units in the
+    last place of the derivative's root near -0.7518 (where Phi(x) and x phi(x) cancel and the bar of one rounding of
+    the exact product is hardest), and the tails up to +-6.3 (the library's erf; further out 1 + erf(x / sqrt 2) has
+    too few bits left for two libraries to agree to a rounding of the product).  Checked against the oracle on the A
+    and dH the GPU stored, to one rounding; an infinite or NaN pre-activation gives NaN, as the definition does."""
+    from paper_2507_05753_amd.layer import JigsawMLP
+    root = np.float32(-0.7517916)
+    near = [root]
+    for _ in range(250):
+        near.append(np.nextafter(near[-1], np.float32(-1)))
+    lo = root
+    for _ in range(249):
+        lo = np.nextafter(lo, np.float32(0))
+        near.append(lo)
+    b1 = np.concatenate([np.linspace(-5.8, 5.8, 1500).astype(np.float32), np.array(near, dtype=np.float32),
+                         np.linspace(-6.3, -5.8, 24).astype(np.float32), np.linspace(5.8, 6.3, 24).astype(np.float32)])
+    Hd = b1.size
+    assert Hd == 2048
+    M, C = 64, 64
+    X = np.zeros((M, C), dtype=np.float32)
+    W1 = inputs.matrix(356, Hd, C, "R", inputs.W_SCALE_EXP)
+    W2 = inputs.matrix(357, C, Hd, "R", inputs.W_SCALE_EXP)
+    b2 = inputs.matrix(358, 1, C, "R")[0]
+    dY = inputs.matrix(359, M, C, "R")
+    f64 = lambda a: a.astype(np.float64)
+    with JigsawMLP(M, C, Hd, ways, ctx=ctx) as L:
+        L.shard(dev(X), dev(W1), dev(b1), dev(W2), dev(b2))
+        L.forward()
+        L.backward(dev(dY))
+        A, dH, dA = (L.gather_grad(k).cpu().numpy() for k in ("a", "dh", "da"))
+        assert np.array_equal(A, np.broadcast_to(b1, (M, Hd)))
+        want = f64(dH) * oracle.gelu_grad(f64(A))
+        assert np.all(np.abs(f64(dA) - want) <= 2.0 ** -23 * np.abs(want) + 1e-45), \
+            float((np.abs(f64(dA) - want) / np.maximum(np.abs(want), 1e-300)).max())
+        assert np.count_nonzero(dA) > 0.99 * dA.size
+        # non-finite pre-activations
+        b1n = b1.copy()
+        b1n[[3, 700, 1501]] = [np.inf, -np.inf, np.nan]
+        L.shard(None, None, dev(b1n), None, None)
+        L.forward()
+        L.backward(dev(dY))
+        dAn = L.gather_grad("da").cpu().numpy()
+        assert np.isnan(dAn[:, [3, 700, 1501]]).all()
+        keep = np.delete(np.arange(Hd), [3, 700, 1501])
+        assert np.array_equal(dAn[:, keep], dA[:, keep])
+
+
 @pytest.mark.parametrize("ways", [1, 2, 4])
 @pytest.mark.parametrize("M,C,Hd", [(100, 100, 100), (130, 72, 258), (258, 264, 136), (300, 520, 1032)])
 def test_mixing_block_backward(jg, ctx, ways, M, C, Hd):
