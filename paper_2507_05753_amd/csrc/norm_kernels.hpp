@@ -44,11 +44,30 @@ constexpr int NORM_THREADS = 256;
 constexpr int NORM_ROWS_PER_WG = NORM_THREADS / 64;
 constexpr int kNormMaxVectorsPerLane = 32;     // register-resident rows: up to 64 * 32 * 4 = 8192 columns
 
+
+// The sum of a value over the 64 lanes of a wavefront, the same in every lane.  It goes through the data-parallel-
+// primitive paths of the vector ALU (six round trips through the LDS crossbar, as shuffles make them, cost the
+// one-pass backward kernel a tenth of its time): within quads, within eights (half mirror), within rows of 16
+// (mirror), then lane 15 of every row into the next row and lane 31 into the upper half; lane 63 ends with the
+// total, which goes out through a scalar register.  A fixed order, so the same bits on every run.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_neighbour(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, ROW_MASK, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, ROW_MASK, 0xF, false);
+    return __hiloint2double(hi, lo);        // lanes outside ROW_MASK, or without a source lane, see +0.0
+}
 __device__ __forceinline__ double wave_sum(double v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    v += dpp_neighbour<0xB1, 0xF>(v);       // quad_perm [1, 0, 3, 2]
+    v += dpp_neighbour<0x4E, 0xF>(v);       // quad_perm [2, 3, 0, 1]
+    v += dpp_neighbour<0x141, 0xF>(v);      // row_half_mirror
+    v += dpp_neighbour<0x140, 0xF>(v);      // row_mirror
+    v += dpp_neighbour<0x142, 0xA>(v);      // row_bcast15 into rows 1 and 3
+    v += dpp_neighbour<0x143, 0xC>(v);      // row_bcast31 into rows 2 and 3
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
+    return __hiloint2double(hi, lo);
 }
 
 // grid: x = row / NORM_ROWS_PER_WG, y = block.  cols is a multiple of 4, cols / 4 <= 64 * NV.
